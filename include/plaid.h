@@ -1,0 +1,156 @@
+/*
+ * plaid.h -- C ABI of the MI355X (gfx950) PLAID search library.
+ *
+ * The library runs the search pipeline of "PLAID: An Efficient Engine for Late Interaction
+ * Retrieval" (Figure 4, Sections 4.1-4.5) for one or more queries on ONE GPU:
+ *
+ *   stage 1  S_cq = C . Q^T (Eq. 2); per query token the nprobe best centroids; candidate
+ *            passages = union of the probed centroids' inverted lists (Section 4.1, no size cap);
+ *   stage 2  centroid interaction (Eq. 3-4) over all candidates using only tokens whose centroid
+ *            passes the pruning test max_i S_cq[c][i] >= t_cs (Eq. 5); keep the best ndocs;
+ *   stage 3  centroid interaction without pruning over those; keep the best max(1, ndocs/4)
+ *            (Figure 4, Section 4.3);
+ *   stage 4  decompress the residuals of those passages through the byte lookup table
+ *            (Section 4.5), exact MaxSim (Eq. 1), best k (Section 4.4).
+ *
+ * Readings where the paper is silent: rankings are by (score descending, id ascending); a passage
+ * with no surviving token in stage 2 scores -infinity and still fills the ndocs slots in pid
+ * order; reconstructed vectors are centroid + bucket weight with no renormalisation; packed
+ * bucket indices are stored most-significant first (dimension order preserved inside a byte).
+ *
+ * Conventions: every function returns PLAID_OK (0) or a negative plaid_status and never throws
+ * or aborts; plaid_last_error() returns a thread-local description of the last failure.
+ * Pointers marked DEVICE are HIP device pointers valid on the index's device; pointers marked
+ * HOST are ordinary host pointers.  The caller owns every buffer it passes; the library owns the
+ * index handle and a per-index workspace that grows on demand and is released by
+ * plaid_index_free.  Searches on one index must not run concurrently.  Kernels are enqueued on
+ * the caller's stream; plaid_search returns without waiting for them unless stated otherwise.
+ */
+#ifndef PLAID_H
+#define PLAID_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PLAID_QLEN 32 /* query tokens per query   */
+#define PLAID_DIM 128 /* embedding dimension      */
+
+typedef enum {
+    PLAID_OK = 0,
+    PLAID_EINVAL = -1,  /* null pointer, size out of range, malformed view */
+    PLAID_ENOMEM = -2,  /* host or device allocation failed                */
+    PLAID_EHIP = -3,    /* a HIP runtime call failed (text in last_error)  */
+    PLAID_EIO = -4,     /* file could not be opened or read                */
+    PLAID_EFORMAT = -5  /* file is not a PLAID index file                  */
+} plaid_status;
+
+typedef struct plaid_index plaid_index; /* opaque */
+
+/* Borrowed description of an index (storage format of Section 3.1: a 4-byte centroid id and a
+ * 16*nbits-byte packed residual per token; inverted lists of unique passage ids, Section 4.1).
+ * All arrays live on the host (on_device = 0) or all on the device (on_device = 1). */
+typedef struct {
+    int32_t dim;                 /* must be PLAID_DIM */
+    int32_t nbits;               /* 1 or 2 bits per residual dimension */
+    int64_t num_centroids;       /* C, 1 <= C < 2^31 */
+    int64_t num_passages;        /* P, 1 <= P < 2^31 */
+    int64_t num_embeddings;      /* N = doc_offsets[P] */
+    const float *centroids;      /* [C][128] row-major fp32 */
+    const int64_t *doc_offsets;  /* [P+1], doc_offsets[0] = 0, non-decreasing; tokens of passage p are
+                                    doc_offsets[p] .. doc_offsets[p+1]-1 */
+    const int32_t *codes;        /* [N], centroid id of each token, in [0, C) */
+    const uint8_t *residuals;    /* [N][16*nbits] packed bucket indices */
+    const float *bucket_weights; /* [2^nbits] */
+    const int64_t *ivf_offsets;  /* [C+1], ivf_offsets[0] = 0 */
+    const int32_t *ivf_pids;     /* [ivf_offsets[C]], ascending unique pids per centroid */
+    int32_t on_device;
+} plaid_index_view;
+
+/* Optional per-stage outputs of plaid_search_debug.  Every pointer is DEVICE, caller-owned, and may be
+ * NULL (that output is skipped).  nq is the number of queries of the call. */
+typedef struct {
+    float *S_cq;          /* [nq][C][32]  Eq. 2 scores, row c = centroid c */
+    int32_t *probed;      /* [nq][32][nprobe]  per query token, best first (Section 4.1) */
+    int32_t *cand;        /* [nq][P]  ascending candidate pids, first n_cand[q] valid */
+    int32_t *n_cand;      /* [nq] */
+    int32_t *sel2_ids;    /* [nq][ndocs]  stage-2 survivors, unspecified order, first n2[q] valid */
+    float *sel2_scores;   /* [nq][ndocs]  their pruned centroid-interaction scores (Eq. 3-5) */
+    int32_t *n2;          /* [nq]  = min(ndocs, n_cand) */
+    int32_t *sel3_ids;    /* [nq][max(1,ndocs/4)]  stage-3 survivors, unspecified order */
+    float *sel3_scores;   /* [nq][max(1,ndocs/4)]  their unpruned centroid-interaction scores (Eq. 3-4) */
+    int32_t *n3;          /* [nq]  = min(max(1,ndocs/4), n2) */
+} plaid_debug_buffers;
+
+/* Read an index file and upload it to `device` (a HIP device ordinal).  File layout, little-endian:
+ * bytes 0-7 "PLAIDIX1"; int32 dim, int32 nbits, int64 C, P, N, ivf_len; zero padding to byte 64; then
+ * centroids, doc_offsets, codes, residuals, bucket_weights, ivf_offsets, ivf_pids in the types of
+ * plaid_index_view, each section starting at a multiple of 64 bytes.  On success *out is a new handle.
+ * Errors: PLAID_EINVAL, PLAID_EIO, PLAID_EFORMAT, PLAID_ENOMEM, PLAID_EHIP. */
+int plaid_index_load(const char *path, int device, plaid_index **out);
+
+/* Build a handle from caller memory.  copy = 1: the arrays (host or device) are copied into
+ * library-owned device memory.  copy = 0: requires on_device = 1; the library keeps the caller's device
+ * pointers and the caller must keep them alive and unchanged until plaid_index_free.  Host-side views are
+ * validated (offsets monotone, codes and pids in range); device-side views are validated for sizes only. */
+int plaid_index_from_view(const plaid_index_view *view, int device, int copy, plaid_index **out);
+
+/* Release the handle, its workspace and any memory the library allocated for it.  NULL is allowed. */
+void plaid_index_free(plaid_index *idx);
+
+/* Search nq queries (Figure 4 pipeline, stages as listed at the top of this file).
+ *   Q           DEVICE  [nq][32][128] fp32 query token embeddings (unit norm expected, not checked)
+ *   nprobe      centroids probed per query token, 1 <= nprobe <= C
+ *   t_cs        pruning threshold of Eq. 5; -INFINITY disables pruning, +INFINITY prunes everything
+ *   ndocs       passages kept by stage 2 (>= 1); stage 3 keeps max(1, ndocs/4)
+ *   k           results per query (>= 1)
+ *   out_ids     DEVICE  [nq][k] passage ids, best first; unused slots -1
+ *   out_scores  DEVICE  [nq][k] MaxSim scores (Eq. 1) of the reconstructed passages; unused slots -INFINITY
+ *   hip_stream  a hipStream_t (NULL = the default stream); the call is asynchronous on it
+ * Errors: PLAID_EINVAL for null pointers or out-of-range sizes, PLAID_ENOMEM when the workspace cannot be
+ * allocated, PLAID_EHIP for launch failures. */
+int plaid_search(plaid_index *idx, const float *Q, int32_t nq, int32_t nprobe, float t_cs, int32_t ndocs,
+                 int32_t k, int32_t *out_ids, float *out_scores, void *hip_stream);
+
+/* plaid_search that also copies the intermediates named in *dbg out of the workspace (same kernels, same
+ * results).  dbg = NULL behaves like plaid_search. */
+int plaid_search_debug(plaid_index *idx, const float *Q, int32_t nq, int32_t nprobe, float t_cs, int32_t ndocs,
+                       int32_t k, int32_t *out_ids, float *out_scores, void *hip_stream,
+                       const plaid_debug_buffers *dbg);
+
+/* Decompress the tokens of n listed passages (Section 4.5: packed byte -> bucket indices through the
+ * 256-entry table, value = centroid + bucket weight, one fp32 addition per element).
+ *   pids         DEVICE [n] passage ids
+ *   out_offsets  DEVICE [n+1] receives the exclusive prefix sum of the passages' token counts (may be NULL)
+ *   out_vectors  DEVICE [total][128] fp32 reconstructed vectors, passages concatenated in list order (may be NULL)
+ *   out_indices  DEVICE [total][128] uint8 unpacked bucket indices (may be NULL)
+ *   capacity     rows available in out_vectors / out_indices; PLAID_EINVAL if total exceeds it
+ * Synchronises the stream once (the total is read back to check the capacity). */
+int plaid_decompress_passages(plaid_index *idx, const int32_t *pids, int32_t n, int64_t *out_offsets,
+                              float *out_vectors, uint8_t *out_indices, int64_t capacity, void *hip_stream);
+
+/* Sizes of a loaded index: any pointer may be NULL. */
+int plaid_index_info(const plaid_index *idx, int64_t *num_centroids, int64_t *num_passages,
+                     int64_t *num_embeddings, int32_t *nbits, int64_t *ivf_len);
+
+/* Per-stage GPU time of the most recent plaid_search on this index when stage timing is on
+ * (plaid_set_stage_timing(idx, 1)): HOST out_ms[PLAID_NUM_STAGES], summed over the call's query chunks.
+ * Turning timing on makes every search synchronise at its end. */
+#define PLAID_NUM_STAGES 8
+/* stage order: 0 S_cq+prune map, 1 top-nprobe, 2 candidate union, 3 stage-2 interaction, 4 select ndocs,
+ * 5 stage-3 interaction+select, 6 stage-4 decompress+MaxSim, 7 top-k */
+int plaid_set_stage_timing(plaid_index *idx, int32_t on);
+int plaid_get_stage_ms(const plaid_index *idx, float *out_ms);
+
+/* Limit on queries processed per internal chunk (0 = library default).  Affects workspace size only. */
+int plaid_set_max_chunk(plaid_index *idx, int32_t max_queries_per_chunk);
+
+/* Thread-local message describing the most recent error on the calling thread ("" if none). */
+const char *plaid_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PLAID_H */

@@ -1,0 +1,152 @@
+// Centroid interaction (Eq. 3-4) and centroid pruning (Eq. 5): the score of a passage is
+// sum_i max_j S_cq[code_j][i] over its tokens j (only tokens whose centroid is kept, when pruning).
+// The rows S_cq[code_j] are never stacked into a matrix: a wave keeps one running maximum per query
+// token (lane i and lane i+32 both serve token i, on alternate passage tokens) and sums the 32 maxima
+// at the end -- in double, so that equal sets of rows give bit-equal scores whatever the order.
+//
+// This file holds the gather formulation (one wave per passage, rows fetched from the L2-resident S);
+// it serves stage 3 and is the general fallback of stage 2.
+#include "plaid_internal.h"
+
+#include <math.h>
+
+__device__ __forceinline__ float sum32_as_double(float m)
+{
+    double d = (double)m;
+#pragma unroll
+    for (int o = 1; o < 32; o <<= 1) d += __shfl_xor(d, o);
+    return (float)d;
+}
+
+// Score of the passage with tokens [t0, t1).  Uniform across the wave; -inf when no token contributes.
+template <bool PRUNE>
+__device__ __forceinline__ float ci_passage(const float *__restrict__ Sq, const uint32_t *__restrict__ kb, int64_t t0,
+                                            int64_t t1, const int32_t *__restrict__ codes, int lane)
+{
+    const int i = lane & 31, h = lane >> 5;
+    float m = -INFINITY;
+    for (int64_t base = t0; base < t1; base += 64) {
+        const int cnt = t1 - base < 64 ? (int)(t1 - base) : 64;
+        const int32_t code = lane < cnt ? codes[base + lane] : 0;
+        if (!PRUNE) {
+            int j = 0;
+            for (; j + 8 <= cnt; j += 8) {  // 4 row pairs in flight
+                const int c0 = __shfl(code, j + h), c1 = __shfl(code, j + 2 + h), c2 = __shfl(code, j + 4 + h),
+                          c3 = __shfl(code, j + 6 + h);
+                const float v0 = Sq[(int64_t)c0 * QLEN + i], v1 = Sq[(int64_t)c1 * QLEN + i],
+                            v2 = Sq[(int64_t)c2 * QLEN + i], v3 = Sq[(int64_t)c3 * QLEN + i];
+                m = fmaxf(fmaxf(m, v0), fmaxf(v1, fmaxf(v2, v3)));
+            }
+            for (; j < cnt; j += 2) {
+                const int jj = j + h < cnt ? j + h : j;
+                const int c = __shfl(code, jj);
+                m = fmaxf(m, Sq[(int64_t)c * QLEN + i]);
+            }
+        } else {
+            bool hit = lane < cnt;
+            if (hit) hit = (kb[code >> 5] >> (code & 31)) & 1u;
+            unsigned long long mask = __ballot(hit);
+            while (mask) {
+                const int j0 = __ffsll((long long)mask) - 1;
+                mask &= mask - 1;
+                int j1 = j0;
+                if (mask) {
+                    j1 = __ffsll((long long)mask) - 1;
+                    mask &= mask - 1;
+                }
+                const int c = __shfl(code, h ? j1 : j0);
+                m = fmaxf(m, Sq[(int64_t)c * QLEN + i]);
+            }
+        }
+    }
+    m = fmaxf(m, __shfl_xor(m, 32));
+    return sum32_as_double(m);
+}
+
+// Stage 3: out_keys[q][j] = key(score of passage of in_keys[q][j]).
+__global__ __launch_bounds__(256) void ci_list_kernel(const float *__restrict__ S, int64_t C,
+                                                      const int64_t *__restrict__ doc_offsets,
+                                                      const int32_t *__restrict__ codes,
+                                                      const uint64_t *__restrict__ in_keys, int64_t in_stride,
+                                                      const int32_t *__restrict__ in_counts,
+                                                      uint64_t *__restrict__ out_keys, int64_t out_stride)
+{
+    const int q = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= in_counts[q]) return;
+    const uint32_t pid = (uint32_t)(in_keys[(int64_t)q * in_stride + j] & 0xFFFFFFFFu);
+    const float sc = ci_passage<false>(S + (int64_t)q * C * QLEN, nullptr, doc_offsets[pid], doc_offsets[pid + 1], codes, lane);
+    if (lane == 0) out_keys[(int64_t)q * out_stride + j] = plaid_make_key(sc, pid);
+}
+
+void plaid_launch_ci_list(hipStream_t st, const float *S, int64_t C, const int64_t *doc_offsets, const int32_t *codes,
+                          int nq, const uint64_t *in_keys, int64_t in_stride, const int32_t *in_counts, int n_upper,
+                          uint64_t *out_keys, int64_t out_stride)
+{
+    hipLaunchKernelGGL(ci_list_kernel, dim3((n_upper + 3) / 4, nq), dim3(256), 0, st, S, C, doc_offsets, codes, in_keys,
+                       in_stride, in_counts, out_keys, out_stride);
+}
+
+// Stage 2, general form: every candidate of the bitmap, pruned rows, keys appended in any order
+// (the selection that follows is order-independent because keys are unique).
+__global__ __launch_bounds__(256) void ci_pruned_gather_kernel(const float *__restrict__ S, int64_t C,
+                                                               const uint32_t *__restrict__ keepbits, int64_t keep_words,
+                                                               const uint32_t *__restrict__ candbits, int64_t cand_words,
+                                                               int64_t P, const int64_t *__restrict__ doc_offsets,
+                                                               const int32_t *__restrict__ codes,
+                                                               uint64_t *__restrict__ keys2, int64_t key_stride,
+                                                               int32_t *__restrict__ n_cand, SelState *state)
+{
+    const int q = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const float *Sq = S + (int64_t)q * C * QLEN;
+    const uint32_t *kb = keepbits + (int64_t)q * keep_words;
+    const uint32_t *cb = candbits + (int64_t)q * cand_words;
+    uint64_t *out = keys2 + (int64_t)q * key_stride;
+    unsigned long long k_or = 0, k_nor = 0;
+    for (int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); w < cand_words; w += (int64_t)gridDim.x * 4) {
+        const uint32_t word = cb[w];
+        if (!word) continue;
+        const int64_t p0 = w * 32;
+        int64_t off = 0;
+        if (lane <= 32 && p0 + lane <= P) off = doc_offsets[p0 + lane];
+        uint64_t mykey = 0;
+        uint32_t rest = word;
+        while (rest) {
+            const int b = __ffs(rest) - 1;
+            rest &= rest - 1;
+            const int64_t t0 = __shfl(off, b), t1 = __shfl(off, b + 1);
+            const float sc = ci_passage<true>(Sq, kb, t0, t1, codes, lane);
+            if (lane == b) mykey = plaid_make_key(sc, (uint32_t)(p0 + b));
+        }
+        int base = 0;
+        if (lane == 0) base = atomicAdd(&n_cand[q], __popc(word));
+        base = __shfl(base, 0);
+        if (lane < 32 && ((word >> lane) & 1u)) {
+            out[base + __popc(word & ((1u << lane) - 1u))] = mykey;
+            k_or |= mykey;
+            k_nor |= ~mykey;
+        }
+    }
+    for (int d = 1; d < 64; d <<= 1) {
+        k_or |= __shfl_xor(k_or, d);
+        k_nor |= __shfl_xor(k_nor, d);
+    }
+    if (lane == 0 && (k_or | k_nor)) {
+        atomicOr(&state[q].key_or, k_or);
+        atomicOr(&state[q].key_nor, k_nor);
+    }
+}
+
+void plaid_launch_ci_pruned(hipStream_t st, const float *S, int64_t C, const uint32_t *keepbits, int64_t keep_words,
+                            const uint32_t *candbits, int64_t cand_words, int64_t P, const int64_t *doc_offsets,
+                            const int32_t *codes, int nq, uint64_t *keys2, int64_t key_stride, int32_t *n_cand,
+                            SelState *state)
+{
+    int64_t gx = (cand_words + 3) / 4;
+    const int64_t cap = nq >= 16 ? 256 : (nq >= 4 ? 1024 : 4096);
+    if (gx > cap) gx = cap;
+    hipLaunchKernelGGL(ci_pruned_gather_kernel, dim3((int)gx, nq), dim3(256), 0, st, S, C, keepbits, keep_words, candbits,
+                       cand_words, P, doc_offsets, codes, keys2, key_stride, n_cand, state);
+}

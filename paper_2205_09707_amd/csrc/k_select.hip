@@ -1,0 +1,449 @@
+// Batched top-m selection on unique 64-bit ranking keys (ascending key = better rank).
+//
+// Every cut of the pipeline (nprobe centroids per token, ndocs after stage 2, ndocs/4 after
+// stage 3, k at the end) is "the m smallest keys of a list".  Lists of up to SEL_SORT_CAP keys are
+// sorted by one workgroup in LDS.  Longer lists go through a two-level most-significant-digit
+// radix selection that starts below the keys' common prefix (the producer accumulates the AND/OR
+// of its keys): level 0 histograms an 11-bit digit over the whole list, level 1 over the keys that
+// fell into the boundary bin; keys in lower bins are selected for sure, the remaining boundary
+// (normally a handful of exact score ties) is resolved by the finishing workgroup, which falls
+// back to an in-block radix selection over global memory if that boundary is still long.
+// Nothing is read back to the host; all counts live in device memory.
+#include "plaid_internal.h"
+
+#define SEL_THREADS 256
+#define FIN_THREADS 1024
+
+__device__ __forceinline__ SelState *state_of(SelState *base, int seg) { return base + seg; }
+
+// ------------------------------------------------------------------ AND/OR of a list (when the producer has not)
+__global__ __launch_bounds__(SEL_THREADS) void sel_andor_kernel(const uint64_t *__restrict__ keys, int64_t key_stride,
+                                                                const int32_t *__restrict__ counts, SelState *state)
+{
+    const int seg = blockIdx.y;
+    const int n = counts[seg];
+    const uint64_t *k = keys + (int64_t)seg * key_stride;
+    unsigned long long o = 0, no = 0;
+    for (int64_t i = (int64_t)blockIdx.x * SEL_THREADS + threadIdx.x; i < n; i += (int64_t)gridDim.x * SEL_THREADS) {
+        const unsigned long long v = k[i];
+        o |= v;
+        no |= ~v;
+    }
+    for (int d = 1; d < 64; d <<= 1) {
+        o |= __shfl_xor(o, d);
+        no |= __shfl_xor(no, d);
+    }
+    if ((threadIdx.x & 63) == 0 && (o | no)) {
+        SelState *s = state_of(state, seg);
+        atomicOr(&s->key_or, o);
+        atomicOr(&s->key_nor, no);
+    }
+}
+
+__device__ __forceinline__ void digit_plan(const SelState *s, int &shift0, int &width0, int &shift1, int &width1)
+{
+    const unsigned long long diff = s->key_or & s->key_nor;  // bits in which the keys differ
+    const int hi = diff ? 63 - __clzll((long long)diff) : -1;
+    width0 = hi + 1 < SEL_RADIX_BITS ? hi + 1 : SEL_RADIX_BITS;
+    shift0 = hi + 1 - width0;
+    width1 = shift0 < SEL_RADIX_BITS ? shift0 : SEL_RADIX_BITS;
+    shift1 = shift0 - width1;
+}
+__device__ __forceinline__ int digit_of(uint64_t key, int shift, int width)
+{
+    return (int)((key >> shift) & ((1u << width) - 1u));
+}
+
+// ------------------------------------------------------------------ level-0 histogram over the whole list
+__global__ __launch_bounds__(SEL_THREADS) void sel_hist0_kernel(const uint64_t *__restrict__ keys, int64_t key_stride,
+                                                                const int32_t *__restrict__ counts, int32_t m,
+                                                                SelState *state, int32_t *__restrict__ hist)
+{
+    __shared__ int32_t lh[SEL_BINS];
+    const int seg = blockIdx.y;
+    SelState *s = state_of(state, seg);
+    const int n = counts[seg];
+    int shift0, width0, shift1, width1;
+    digit_plan(s, shift0, width0, shift1, width1);
+    for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS) lh[b] = 0;
+    __syncthreads();
+    const uint64_t *k = keys + (int64_t)seg * key_stride;
+    for (int64_t i = (int64_t)blockIdx.x * SEL_THREADS + threadIdx.x; i < n; i += (int64_t)gridDim.x * SEL_THREADS)
+        atomicAdd(&lh[digit_of(k[i], shift0, width0)], 1);
+    __syncthreads();
+    int32_t *gh = hist + (int64_t)seg * 2 * SEL_BINS;
+    for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS)
+        if (lh[b]) atomicAdd(&gh[b], lh[b]);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        s->n_in = n;
+        s->m_rem[0] = m < n ? m : n;
+        s->shift[0] = shift0;
+        s->width[0] = width0;
+        s->shift[1] = shift1;
+        s->width[1] = width1;
+    }
+}
+
+// Finds the boundary bin of a histogram: the smallest b with count(bins <= b) >= m_rem.  Every thread of
+// the block returns the same (bstar, before).  bstar = SEL_BINS when the whole list is taken.
+__device__ void find_boundary(const int32_t *__restrict__ gh, int32_t m_rem, int32_t *scan /* [SEL_THREADS] */,
+                              int32_t *res /* [2] */, int &bstar, int &before)
+{
+    constexpr int PER = SEL_BINS / SEL_THREADS;
+    int32_t loc[PER];
+    int32_t sum = 0;
+    for (int j = 0; j < PER; ++j) {
+        loc[j] = gh[threadIdx.x * PER + j];
+        sum += loc[j];
+    }
+    scan[threadIdx.x] = sum;
+    if (threadIdx.x == 0) {
+        res[0] = SEL_BINS;
+        res[1] = 0;
+    }
+    __syncthreads();
+    for (int d = 1; d < SEL_THREADS; d <<= 1) {
+        int32_t v = threadIdx.x >= d ? scan[threadIdx.x - d] : 0;
+        __syncthreads();
+        scan[threadIdx.x] += v;
+        __syncthreads();
+    }
+    const int32_t incl = scan[threadIdx.x], excl = incl - sum;
+    if (m_rem > 0 && excl < m_rem && m_rem <= incl) {
+        int32_t run = excl;
+        for (int j = 0; j < PER; ++j) {
+            if (run + loc[j] >= m_rem) {
+                res[0] = threadIdx.x * PER + j;
+                res[1] = run;
+                break;
+            }
+            run += loc[j];
+        }
+    }
+    if (m_rem <= 0 && threadIdx.x == 0) {
+        res[0] = -1;  // take nothing, keep nothing
+        res[1] = 0;
+    }
+    __syncthreads();
+    bstar = res[0];
+    before = res[1];
+    if (bstar == SEL_BINS) before = scan[SEL_THREADS - 1];
+}
+
+// ------------------------------------------------------------------ level kernel: split a list by its digit
+template <int LEVEL>
+__global__ __launch_bounds__(SEL_THREADS) void sel_level_kernel(const uint64_t *__restrict__ keys, int64_t key_stride,
+                                                                SelState *state, int32_t *__restrict__ hist,
+                                                                uint64_t *__restrict__ sure, int64_t sure_stride,
+                                                                uint64_t *__restrict__ list_out, int64_t list_stride)
+{
+    __shared__ int32_t scan[SEL_THREADS];
+    __shared__ int32_t res[2];
+    __shared__ int32_t lh[LEVEL == 0 ? SEL_BINS : 1];
+    const int seg = blockIdx.y;
+    SelState *s = state_of(state, seg);
+    const int n = LEVEL == 0 ? s->n_in : s->n_list[0];
+    const int32_t m_rem = s->m_rem[LEVEL];
+    const int shift = s->shift[LEVEL], width = s->width[LEVEL];
+    const int shift_n = s->shift[1], width_n = s->width[1];
+    int bstar, before;
+    find_boundary(hist + ((int64_t)seg * 2 + LEVEL) * SEL_BINS, m_rem, scan, res, bstar, before);
+    if (blockIdx.x == 0 && threadIdx.x == 0) s->m_rem[LEVEL + 1] = m_rem - before;
+    if (LEVEL == 0) {
+        for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS) lh[b] = 0;
+        __syncthreads();
+    }
+    const uint64_t *k = keys + (int64_t)seg * key_stride;
+    uint64_t *my_sure = sure + (int64_t)seg * sure_stride;
+    uint64_t *my_out = list_out + (int64_t)seg * list_stride;
+    const int lane = threadIdx.x & 63;
+    const int64_t n_round = ((int64_t)n + 63) & ~63ll;  // whole waves iterate together (ballots below)
+    for (int64_t i = (int64_t)blockIdx.x * SEL_THREADS + threadIdx.x; i < n_round; i += (int64_t)gridDim.x * SEL_THREADS) {
+        uint64_t key = 0;
+        int cls = 2;  // 0 = surely selected, 1 = boundary, 2 = dropped
+        if (i < n) {
+            key = k[i];
+            const int d = digit_of(key, shift, width);
+            cls = d < bstar ? 0 : (d == bstar ? 1 : 2);
+        }
+        const unsigned long long b0 = __ballot(cls == 0), b1 = __ballot(cls == 1);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        int base0 = 0, base1 = 0;
+        if (lane == 0) {
+            if (b0) base0 = atomicAdd(&s->n_sure, __popcll(b0));
+            if (b1) base1 = atomicAdd(&s->n_list[LEVEL], __popcll(b1));
+        }
+        base0 = __shfl(base0, 0);
+        base1 = __shfl(base1, 0);
+        if (cls == 0) my_sure[base0 + __popcll(b0 & below)] = key;
+        if (cls == 1) {
+            my_out[base1 + __popcll(b1 & below)] = key;
+            if (LEVEL == 0) atomicAdd(&lh[digit_of(key, shift_n, width_n)], 1);
+        }
+    }
+    if (LEVEL == 0) {
+        __syncthreads();
+        int32_t *gh = hist + ((int64_t)seg * 2 + 1) * SEL_BINS;
+        for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS)
+            if (lh[b]) atomicAdd(&gh[b], lh[b]);
+    }
+}
+
+// ------------------------------------------------------------------ finishing workgroup
+__device__ void lds_bitonic_sort(uint64_t *s, int n2)
+{
+    for (int k = 2; k <= n2; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = threadIdx.x; i < n2; i += FIN_THREADS) {
+                const int p = i ^ j;
+                if (p > i) {
+                    const uint64_t a = s[i], b = s[p];
+                    const bool up = (i & k) == 0;
+                    if ((a > b) == up) {
+                        s[i] = b;
+                        s[p] = a;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+}
+__device__ __forceinline__ int next_pow2(int n)
+{
+    int p = 1;
+    while (p < n) p <<= 1;
+    return p;
+}
+
+// DIRECT: the list is the input itself (no levels ran).  Otherwise: sure keys + boundary list1.
+template <bool DIRECT>
+__global__ __launch_bounds__(FIN_THREADS) void sel_finish_kernel(const uint64_t *__restrict__ keys, int64_t key_stride,
+                                                                 const int32_t *__restrict__ counts, int32_t m,
+                                                                 SelState *state, const uint64_t *__restrict__ sure,
+                                                                 int64_t sure_stride, const uint64_t *__restrict__ list1,
+                                                                 int64_t list_stride, uint64_t *__restrict__ out,
+                                                                 int64_t out_stride, int32_t *__restrict__ out_counts,
+                                                                 int sorted)
+{
+    __shared__ uint64_t sk[SEL_SORT_CAP];
+    __shared__ int32_t h256[256];
+    __shared__ int32_t sh[4];
+    const int seg = blockIdx.x;
+    const uint64_t *bl;
+    const uint64_t *sr = nullptr;
+    int nb, n_sure, m_rem, top_bit;
+    if (DIRECT) {
+        bl = keys + (int64_t)seg * key_stride;
+        nb = counts[seg];
+        n_sure = 0;
+        m_rem = m < nb ? m : nb;
+        top_bit = 64;
+    } else {
+        SelState *s = state_of(state, seg);
+        bl = list1 + (int64_t)seg * list_stride;
+        sr = sure + (int64_t)seg * sure_stride;
+        nb = s->n_list[1];
+        n_sure = s->n_sure;
+        m_rem = s->m_rem[2];
+        top_bit = s->shift[1];  // boundary keys agree on every bit at or above this position
+    }
+    uint64_t *o = out + (int64_t)seg * out_stride;
+    const int total_out = n_sure + m_rem;
+    if (threadIdx.x == 0) out_counts[seg] = total_out;
+
+    if (n_sure + nb <= SEL_SORT_CAP) {
+        // common case: sort the union; the first total_out keys are the answer, in rank order
+        const int tot = n_sure + nb, n2 = next_pow2(tot > 1 ? tot : 1);
+        for (int i = threadIdx.x; i < n2; i += FIN_THREADS)
+            sk[i] = i < n_sure ? sr[i] : (i < tot ? bl[i - n_sure] : PLAID_KEY_MAX);
+        __syncthreads();
+        lds_bitonic_sort(sk, n2);
+        for (int i = threadIdx.x; i < total_out; i += FIN_THREADS) o[i] = sk[i];
+        return;
+    }
+
+    // long boundary: find the m_rem-th smallest boundary key by 8-bit radix passes over global memory
+    uint64_t prefix = 0, pmask = 0;  // bits decided so far
+    int r = m_rem;
+    int pos = top_bit;
+    while (pos > 0 && r > 0) {
+        const int w = pos < 8 ? pos : 8;
+        pos -= w;
+        for (int b = threadIdx.x; b < 256; b += FIN_THREADS) h256[b] = 0;
+        __syncthreads();
+        for (int i = threadIdx.x; i < nb; i += FIN_THREADS) {
+            const uint64_t key = bl[i];
+            if ((key & pmask) == prefix) atomicAdd(&h256[(int)((key >> pos) & ((1u << w) - 1u))], 1);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int run = 0, b = 0;
+            for (; b < (1 << w); ++b) {
+                if (run + h256[b] >= r) break;
+                run += h256[b];
+            }
+            sh[0] = b;
+            sh[1] = run;
+        }
+        __syncthreads();
+        prefix |= (uint64_t)sh[0] << pos;
+        pmask |= (uint64_t)((1u << w) - 1u) << pos;
+        r -= sh[1];
+        __syncthreads();
+    }
+    // keys are unique, so after all bits are decided `prefix` (restricted to pmask) is the threshold key itself
+    if (threadIdx.x == 0) sh[2] = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < n_sure; i += FIN_THREADS) o[i] = sr[i];
+    if (m_rem > 0)
+        for (int i = threadIdx.x; i < nb; i += FIN_THREADS) {
+            const uint64_t key = bl[i];
+            if ((key & pmask) <= prefix) o[n_sure + atomicAdd(&sh[2], 1)] = key;
+        }
+    __syncthreads();
+    if (sorted && total_out <= SEL_SORT_CAP) {
+        __threadfence_block();
+        const int n2 = next_pow2(total_out > 1 ? total_out : 1);
+        for (int i = threadIdx.x; i < n2; i += FIN_THREADS) sk[i] = i < total_out ? o[i] : PLAID_KEY_MAX;
+        __syncthreads();
+        lds_bitonic_sort(sk, n2);
+        for (int i = threadIdx.x; i < total_out; i += FIN_THREADS) o[i] = sk[i];
+    }
+}
+
+// ------------------------------------------------------------------ global bitonic sort (only for m > SEL_SORT_CAP, sorted)
+__global__ void sel_pad_copy_kernel(const uint64_t *__restrict__ src, int64_t src_stride, const int32_t *__restrict__ counts,
+                                    uint64_t *__restrict__ dst, int64_t n2)
+{
+    const int seg = blockIdx.y;
+    const int n = counts[seg];
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n2; i += (int64_t)gridDim.x * blockDim.x)
+        dst[(int64_t)seg * n2 + i] = i < n ? src[(int64_t)seg * src_stride + i] : PLAID_KEY_MAX;
+}
+__global__ void sel_bitonic_step_kernel(uint64_t *__restrict__ a, int64_t n2, int64_t k, int64_t j)
+{
+    uint64_t *s = a + (int64_t)blockIdx.y * n2;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n2; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t p = i ^ j;
+        if (p > i) {
+            const uint64_t x = s[i], y = s[p];
+            const bool up = (i & k) == 0;
+            if ((x > y) == up) {
+                s[i] = y;
+                s[p] = x;
+            }
+        }
+    }
+}
+__global__ void sel_copy_back_kernel(const uint64_t *__restrict__ src, int64_t n2, const int32_t *__restrict__ counts,
+                                     uint64_t *__restrict__ dst, int64_t dst_stride)
+{
+    const int seg = blockIdx.y;
+    const int n = counts[seg];
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        dst[(int64_t)seg * dst_stride + i] = src[(int64_t)seg * n2 + i];
+}
+
+// ------------------------------------------------------------------ host side
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+static inline int64_t pow2_at_least(int64_t n)
+{
+    int64_t p = 1;
+    while (p < n) p <<= 1;
+    return p;
+}
+
+// Scratch of one selection instance comes in two parts: a small head (state + histograms) that must be
+// zero before the producer of the keys runs, and a body (sure / boundary lists, sort buffer) that needs no
+// initialisation.  The body is only needed for lists longer than SEL_SORT_CAP or more than SEL_SORT_CAP
+// sorted results.
+size_t plaid_select_zero_bytes(int nseg)
+{
+    return align256((size_t)nseg * sizeof(SelState)) + align256((size_t)nseg * 2 * SEL_BINS * sizeof(int32_t));
+}
+size_t plaid_select_body_bytes(int nseg, int64_t n_upper, int32_t m)
+{
+    size_t b = 0;
+    const int64_t mm = m < n_upper ? m : n_upper;
+    if (n_upper > SEL_SORT_CAP) b += align256((size_t)nseg * mm * 8) + 2 * align256((size_t)nseg * n_upper * 8);
+    if (mm > SEL_SORT_CAP) b += align256((size_t)nseg * pow2_at_least(mm) * 8);
+    return b;
+}
+size_t plaid_select_scratch_bytes(int nseg, int64_t n_upper, int32_t m)
+{
+    return plaid_select_zero_bytes(nseg) + plaid_select_body_bytes(nseg, n_upper, m);
+}
+
+SelScratch plaid_select_scratch_carve2(void *zero_base, void *body_base, int nseg, int64_t n_upper, int32_t m)
+{
+    SelScratch sc{};
+    char *z = (char *)zero_base;
+    sc.state = (SelState *)z;
+    sc.hist = (int32_t *)(z + align256((size_t)nseg * sizeof(SelState)));
+    char *p = (char *)body_base;
+    const int64_t mm = m < n_upper ? m : n_upper;
+    if (n_upper > SEL_SORT_CAP) {
+        sc.sure = (uint64_t *)p;
+        sc.sure_stride = mm;
+        p += align256((size_t)nseg * mm * 8);
+        sc.list0 = (uint64_t *)p;
+        p += align256((size_t)nseg * n_upper * 8);
+        sc.list1 = (uint64_t *)p;
+        p += align256((size_t)nseg * n_upper * 8);
+        sc.list_stride = n_upper;
+    }
+    sc.sortbuf = (mm > SEL_SORT_CAP) ? (uint64_t *)p : nullptr;
+    return sc;
+}
+SelScratch plaid_select_scratch_carve(void *base, int nseg, int64_t n_upper, int32_t m)
+{
+    return plaid_select_scratch_carve2(base, (char *)base + plaid_select_zero_bytes(nseg), nseg, n_upper, m);
+}
+
+static int blocks_for(int64_t n, int nseg)
+{
+    int64_t b = (n + SEL_THREADS * 8 - 1) / (SEL_THREADS * 8);
+    const int64_t cap = nseg >= 16 ? 64 : (nseg >= 4 ? 256 : 1024);
+    if (b > cap) b = cap;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+void plaid_launch_select(hipStream_t st, const uint64_t *keys, int64_t key_stride, const int32_t *counts, int nseg,
+                         int64_t n_upper, int32_t m, uint64_t *out, int64_t out_stride, int32_t *out_counts, int sorted,
+                         const SelScratch &sc, int state_ready)
+{
+    // the caller zeroes state + hist (plaid_launch_fill_u32 over the head of the scratch) before the
+    // producer runs; see search.hip
+    if (n_upper <= SEL_SORT_CAP) {
+        hipLaunchKernelGGL(sel_finish_kernel<true>, dim3(nseg), dim3(FIN_THREADS), 0, st, keys, key_stride, counts, m,
+                           sc.state, nullptr, 0, nullptr, 0, out, out_stride, out_counts, sorted);
+    } else {
+        const int gx = blocks_for(n_upper, nseg);
+        if (!state_ready)
+            hipLaunchKernelGGL(sel_andor_kernel, dim3(gx, nseg), dim3(SEL_THREADS), 0, st, keys, key_stride, counts,
+                               sc.state);
+        hipLaunchKernelGGL(sel_hist0_kernel, dim3(gx, nseg), dim3(SEL_THREADS), 0, st, keys, key_stride, counts, m,
+                           sc.state, sc.hist);
+        hipLaunchKernelGGL(sel_level_kernel<0>, dim3(gx, nseg), dim3(SEL_THREADS), 0, st, keys, key_stride, sc.state,
+                           sc.hist, sc.sure, sc.sure_stride, sc.list0, sc.list_stride);
+        const int gx1 = gx > 16 ? 16 : gx;
+        hipLaunchKernelGGL(sel_level_kernel<1>, dim3(gx1, nseg), dim3(SEL_THREADS), 0, st, sc.list0, sc.list_stride,
+                           sc.state, sc.hist, sc.sure, sc.sure_stride, sc.list1, sc.list_stride);
+        hipLaunchKernelGGL(sel_finish_kernel<false>, dim3(nseg), dim3(FIN_THREADS), 0, st, keys, key_stride, counts, m,
+                           sc.state, sc.sure, sc.sure_stride, sc.list1, sc.list_stride, out, out_stride, out_counts,
+                           sorted);
+    }
+    const int64_t mm = m < n_upper ? m : n_upper;
+    if (sorted && mm > SEL_SORT_CAP) {
+        // rare: more than SEL_SORT_CAP results in rank order -> bitonic network in global memory
+        uint64_t *buf = sc.sortbuf;
+        const int64_t n2 = pow2_at_least(mm);
+        const int gx = (int)((n2 + 255) / 256 > 1024 ? 1024 : (n2 + 255) / 256);
+        hipLaunchKernelGGL(sel_pad_copy_kernel, dim3(gx, nseg), dim3(256), 0, st, out, out_stride, out_counts, buf, n2);
+        for (int64_t k = 2; k <= n2; k <<= 1)
+            for (int64_t j = k >> 1; j > 0; j >>= 1)
+                hipLaunchKernelGGL(sel_bitonic_step_kernel, dim3(gx, nseg), dim3(256), 0, st, buf, n2, k, j);
+        hipLaunchKernelGGL(sel_copy_back_kernel, dim3(gx, nseg), dim3(256), 0, st, buf, n2, out_counts, out, out_stride);
+    }
+}

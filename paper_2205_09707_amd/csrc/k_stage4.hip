@@ -1,0 +1,201 @@
+// Stage 4 (Sections 4.4-4.5): residual decompression fused with exact MaxSim (Eq. 1).
+//
+// Decompression follows the lookup-table idea of Section 4.5: a packed byte indexes a 256-entry
+// table held in LDS.  The table stores the bucket WEIGHTS of the byte's dimensions (4 for 2-bit,
+// 8 for 1-bit codes) instead of the bucket indices, so one 16-byte LDS read yields four residual
+// values; a reconstructed value is centroid + weight, one fp32 addition, exactly as stored form
+// defines it.  The reconstructed 32-token x 128 tile never leaves registers: each lane decodes
+// the half row of its own passage token and feeds it as the A operand of v_mfma_f32_32x32x2_f32
+// against the query (B operand, 64 VGPRs), giving a 32 passage-token x 32 query-token block of dot
+// products whose column maxima are the MaxSim terms.  One workgroup scores one passage.
+#include "plaid_internal.h"
+
+#include <math.h>
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// Table entry (byte v, quad s): weights of dimensions 4s .. 4s+3 of the 8/NBITS dimensions packed in v.
+// Bucket indices are stored most-significant first.
+template <int NBITS>
+__device__ __forceinline__ void build_tables(float4 *wlut, uint32_t *ilut, const float *__restrict__ weights, int tid,
+                                             int nthreads)
+{
+    constexpr int QUADS = NBITS == 2 ? 1 : 2;
+    for (int e = tid; e < 256 * QUADS; e += nthreads) {
+        const int v = e / QUADS, s = e % QUADS;
+        uint32_t idx[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int d = 4 * s + t;  // dimension within the byte
+            idx[t] = (v >> (8 - NBITS * (d + 1))) & ((1 << NBITS) - 1);
+        }
+        wlut[e] = make_float4(weights[idx[0]], weights[idx[1]], weights[idx[2]], weights[idx[3]]);
+        if (ilut) ilut[e] = idx[0] | (idx[1] << 8) | (idx[2] << 16) | (idx[3] << 24);
+    }
+}
+// Entry for dimensions 4*quad .. 4*quad+3 of a token whose packed residual starts at r.
+template <int NBITS>
+__device__ __forceinline__ int table_slot(const uint8_t *__restrict__ r, int quad)
+{
+    if (NBITS == 2) return r[quad];
+    return 2 * r[quad >> 1] + (quad & 1);
+}
+
+template <int NBITS>
+__global__ __launch_bounds__(256) void decompress_maxsim_kernel(
+    const float *__restrict__ Q, const float *__restrict__ centroids, const int64_t *__restrict__ doc_offsets,
+    const int32_t *__restrict__ codes, const uint8_t *__restrict__ residuals, const float *__restrict__ weights,
+    const uint64_t *__restrict__ in_keys, int64_t in_stride, const int32_t *__restrict__ in_counts,
+    uint64_t *__restrict__ out_keys, int64_t out_stride)
+{
+    constexpr int RB = 16 * NBITS;
+    __shared__ float4 wlut[256 * (NBITS == 2 ? 1 : 2)];
+    __shared__ float wmax[4][QLEN];
+    const int q = blockIdx.y, j = blockIdx.x;
+    if (j >= in_counts[q]) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r32 = lane & 31, h = lane >> 5;
+    build_tables<NBITS>(wlut, nullptr, weights, threadIdx.x, 256);
+    const float *Qq = Q + (int64_t)q * QLEN * DIM;
+    float4 qf[16];
+#pragma unroll
+    for (int g = 0; g < 16; ++g) qf[g] = *reinterpret_cast<const float4 *>(Qq + r32 * DIM + 8 * g + 4 * h);
+    const uint32_t pid = (uint32_t)(in_keys[(int64_t)q * in_stride + j] & 0xFFFFFFFFu);
+    const int64_t t0 = doc_offsets[pid];
+    const int len = (int)(doc_offsets[pid + 1] - t0);
+    __syncthreads();
+
+    float m = -INFINITY;  // running maximum for query token r32 over this wave's passage tokens
+    for (int tile = wave; tile * 32 < len; tile += 4) {
+        const int row = tile * 32 + r32;  // this lane's passage token
+        const bool valid = row < len;
+        const int64_t tok = t0 + (valid ? row : 0);
+        const float *crow = centroids + (int64_t)codes[tok] * DIM;
+        const uint8_t *rrow = residuals + tok * RB;
+        floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int g = 0; g < 16; ++g) {
+            const int quad = 2 * g + h;  // dimensions 8g+4h .. 8g+4h+3
+            const float4 c = *reinterpret_cast<const float4 *>(crow + 4 * quad);
+            const float4 w = wlut[table_slot<NBITS>(rrow, quad)];
+            const float4 a = make_float4(c.x + w.x, c.y + w.y, c.z + w.z, c.w + w.w);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, qf[g].x, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, qf[g].y, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, qf[g].z, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, qf[g].w, acc, 0, 0, 0);
+        }
+        // acc[v] = (passage token tile*32 + 8*(v/4) + 4h + v%4) . (query token r32)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            if (tile * 32 + 8 * (v >> 2) + 4 * h + (v & 3) < len) m = fmaxf(m, acc[v]);
+    }
+    m = fmaxf(m, __shfl_xor(m, 32));
+    if (h == 0) wmax[wave][r32] = m;
+    __syncthreads();
+    if (wave == 0) {
+        float mm = fmaxf(fmaxf(wmax[0][r32], wmax[1][r32]), fmaxf(wmax[2][r32], wmax[3][r32]));
+        double d = (double)mm;
+#pragma unroll
+        for (int o = 1; o < 32; o <<= 1) d += __shfl_xor(d, o);
+        if (lane == 0) out_keys[(int64_t)q * out_stride + j] = plaid_make_key((float)d, pid);
+    }
+}
+
+void plaid_launch_decompress_maxsim(hipStream_t st, const float *Q, const float *centroids, const int64_t *doc_offsets,
+                                    const int32_t *codes, const uint8_t *residuals, const float *bucket_weights,
+                                    int nbits, int nq, const uint64_t *in_keys, int64_t in_stride,
+                                    const int32_t *in_counts, int n_upper, uint64_t *out_keys, int64_t out_stride)
+{
+    if (nbits == 2)
+        hipLaunchKernelGGL(decompress_maxsim_kernel<2>, dim3(n_upper, nq), dim3(256), 0, st, Q, centroids, doc_offsets,
+                           codes, residuals, bucket_weights, in_keys, in_stride, in_counts, out_keys, out_stride);
+    else
+        hipLaunchKernelGGL(decompress_maxsim_kernel<1>, dim3(n_upper, nq), dim3(256), 0, st, Q, centroids, doc_offsets,
+                           codes, residuals, bucket_weights, in_keys, in_stride, in_counts, out_keys, out_stride);
+}
+
+// ------------------------------------------------------------------ decompression alone (parity of the codec)
+__global__ __launch_bounds__(256) void passage_offsets_kernel(const int64_t *__restrict__ doc_offsets,
+                                                              const int32_t *__restrict__ pids, int n,
+                                                              int64_t *__restrict__ out_offsets)
+{
+    // one workgroup; serial carry across chunks of 256 passages
+    __shared__ int64_t scan[256];
+    __shared__ int64_t carry;
+    if (threadIdx.x == 0) {
+        carry = 0;
+        out_offsets[0] = 0;
+    }
+    __syncthreads();
+    for (int base = 0; base < n; base += 256) {
+        const int e = base + threadIdx.x;
+        int64_t len = 0;
+        if (e < n) len = doc_offsets[pids[e] + 1] - doc_offsets[pids[e]];
+        scan[threadIdx.x] = len;
+        __syncthreads();
+        for (int d = 1; d < 256; d <<= 1) {
+            const int64_t t = threadIdx.x >= d ? scan[threadIdx.x - d] : 0;
+            __syncthreads();
+            scan[threadIdx.x] += t;
+            __syncthreads();
+        }
+        if (e < n) out_offsets[e + 1] = carry + scan[threadIdx.x];
+        __syncthreads();
+        if (threadIdx.x == 255) carry += scan[255];
+        __syncthreads();
+    }
+}
+void plaid_launch_passage_offsets(hipStream_t st, const int64_t *doc_offsets, const int32_t *pids, int n,
+                                  int64_t *out_offsets)
+{
+    hipLaunchKernelGGL(passage_offsets_kernel, dim3(1), dim3(256), 0, st, doc_offsets, pids, n, out_offsets);
+}
+
+// Same table, same lookup and same addition as the fused kernel; thread t handles dimensions 4t .. 4t+3.
+template <int NBITS>
+__global__ __launch_bounds__(256) void decompress_dump_kernel(const float *__restrict__ centroids,
+                                                              const int64_t *__restrict__ doc_offsets,
+                                                              const int32_t *__restrict__ codes,
+                                                              const uint8_t *__restrict__ residuals,
+                                                              const float *__restrict__ weights,
+                                                              const int32_t *__restrict__ pids,
+                                                              const int64_t *__restrict__ out_offsets,
+                                                              float *__restrict__ out_vectors,
+                                                              uint8_t *__restrict__ out_indices)
+{
+    constexpr int RB = 16 * NBITS;
+    __shared__ float4 wlut[256 * (NBITS == 2 ? 1 : 2)];
+    __shared__ uint32_t ilut[256 * (NBITS == 2 ? 1 : 2)];
+    build_tables<NBITS>(wlut, ilut, weights, threadIdx.x, 256);
+    __syncthreads();
+    const int a = blockIdx.x;
+    const int32_t pid = pids[a];
+    const int64_t t0 = doc_offsets[pid];
+    const int len = (int)(doc_offsets[pid + 1] - t0);
+    const int64_t o0 = out_offsets[a];
+    const int quad = threadIdx.x & 31;
+    for (int row = threadIdx.x >> 5; row < len; row += 8) {
+        const int64_t tok = t0 + row;
+        const float *crow = centroids + (int64_t)codes[tok] * DIM;
+        const int slot = table_slot<NBITS>(residuals + tok * RB, quad);
+        const float4 c = *reinterpret_cast<const float4 *>(crow + 4 * quad);
+        const float4 w = wlut[slot];
+        if (out_vectors)
+            *reinterpret_cast<float4 *>(out_vectors + (o0 + row) * DIM + 4 * quad) =
+                make_float4(c.x + w.x, c.y + w.y, c.z + w.z, c.w + w.w);
+        if (out_indices) *reinterpret_cast<uint32_t *>(out_indices + (o0 + row) * DIM + 4 * quad) = ilut[slot];
+    }
+}
+void plaid_launch_decompress_dump(hipStream_t st, const float *centroids, const int64_t *doc_offsets,
+                                  const int32_t *codes, const uint8_t *residuals, const float *bucket_weights,
+                                  int nbits, const int32_t *pids, int n, const int64_t *out_offsets, float *out_vectors,
+                                  uint8_t *out_indices)
+{
+    if (n <= 0) return;
+    if (nbits == 2)
+        hipLaunchKernelGGL(decompress_dump_kernel<2>, dim3(n), dim3(256), 0, st, centroids, doc_offsets, codes, residuals,
+                           bucket_weights, pids, out_offsets, out_vectors, out_indices);
+    else
+        hipLaunchKernelGGL(decompress_dump_kernel<1>, dim3(n), dim3(256), 0, st, centroids, doc_offsets, codes, residuals,
+                           bucket_weights, pids, out_offsets, out_vectors, out_indices);
+}

@@ -1,0 +1,575 @@
+// C ABI of libplaid: index handles, the per-index workspace, and the host side of the search
+// pipeline (Figure 4): it only enqueues kernels on the caller's stream and never reads a result
+// back, so a search costs no host-device round trip.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "plaid_internal.h"
+
+// ------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+extern "C" const char *plaid_last_error(void) { return g_err; }
+
+#define HIP_TRY(expr)                                                                                         \
+    do {                                                                                                      \
+        hipError_t e_ = (expr);                                                                               \
+        if (e_ != hipSuccess) return fail(PLAID_EHIP, "%s: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+// ------------------------------------------------------------------ handle
+#define N_EVENTS (PLAID_NUM_STAGES + 1)
+
+struct plaid_index {
+    int device = 0;
+    int32_t nbits = 0;
+    int64_t C = 0, P = 0, N = 0, ivf_len = 0;
+    const float *centroids = nullptr;
+    const int64_t *doc_offsets = nullptr;
+    const int32_t *codes = nullptr;
+    const uint8_t *residuals = nullptr;
+    const float *weights = nullptr;
+    const int64_t *ivf_offsets = nullptr;
+    const int32_t *ivf_pids = nullptr;
+    std::vector<void *> owned;  // device allocations released by plaid_index_free
+    void *ws = nullptr;         // workspace, grown on demand
+    size_t ws_bytes = 0;
+    int32_t max_chunk = 0;
+    int32_t timing = 0;
+    float stage_ms[PLAID_NUM_STAGES] = {0};
+    hipEvent_t ev[N_EVENTS] = {nullptr};
+};
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(dev) == hipSuccess) ok = true;
+    }
+    ~DeviceGuard()
+    {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+static inline size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static int check_sizes(int32_t dim, int32_t nbits, int64_t C, int64_t P, int64_t N, int64_t ivf_len)
+{
+    if (dim != PLAID_DIM) return fail(PLAID_EINVAL, "dim must be %d (got %d)", PLAID_DIM, dim);
+    if (nbits != 1 && nbits != 2) return fail(PLAID_EINVAL, "nbits must be 1 or 2 (got %d)", nbits);
+    if (C < 1 || C >= (1ll << 31)) return fail(PLAID_EINVAL, "num_centroids out of range (%lld)", (long long)C);
+    if (P < 1 || P >= (1ll << 31)) return fail(PLAID_EINVAL, "num_passages out of range (%lld)", (long long)P);
+    if (N < 0) return fail(PLAID_EINVAL, "num_embeddings negative");
+    if (ivf_len < 0) return fail(PLAID_EINVAL, "inverted-list length negative");
+    return PLAID_OK;
+}
+
+// Host-side structural validation of an index whose arrays are in host memory.
+static int validate_host(const plaid_index_view *v, int64_t ivf_len)
+{
+    const int64_t C = v->num_centroids, P = v->num_passages, N = v->num_embeddings;
+    if (v->doc_offsets[0] != 0) return fail(PLAID_EINVAL, "doc_offsets[0] must be 0");
+    for (int64_t p = 0; p < P; ++p)
+        if (v->doc_offsets[p + 1] < v->doc_offsets[p]) return fail(PLAID_EINVAL, "doc_offsets decreases at passage %lld", (long long)p);
+    if (v->doc_offsets[P] != N) return fail(PLAID_EINVAL, "doc_offsets[P] (%lld) != num_embeddings (%lld)", (long long)v->doc_offsets[P], (long long)N);
+    for (int64_t j = 0; j < N; ++j)
+        if (v->codes[j] < 0 || v->codes[j] >= C) return fail(PLAID_EINVAL, "codes[%lld] = %d out of range", (long long)j, v->codes[j]);
+    if (v->ivf_offsets[0] != 0) return fail(PLAID_EINVAL, "ivf_offsets[0] must be 0");
+    for (int64_t c = 0; c < C; ++c) {
+        const int64_t a = v->ivf_offsets[c], b = v->ivf_offsets[c + 1];
+        if (b < a || b > ivf_len) return fail(PLAID_EINVAL, "ivf_offsets malformed at centroid %lld", (long long)c);
+        for (int64_t e = a; e < b; ++e) {
+            if (v->ivf_pids[e] < 0 || v->ivf_pids[e] >= P) return fail(PLAID_EINVAL, "ivf_pids[%lld] out of range", (long long)e);
+            if (e > a && v->ivf_pids[e] <= v->ivf_pids[e - 1]) return fail(PLAID_EINVAL, "inverted list %lld not ascending/unique", (long long)c);
+        }
+    }
+    return PLAID_OK;
+}
+
+static int dev_alloc_copy(plaid_index *ix, const void *src, size_t bytes, hipMemcpyKind kind, const void **out)
+{
+    void *d = nullptr;
+    const size_t alloc = bytes ? bytes : 256;
+    hipError_t e = hipMalloc(&d, alloc);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PLAID_ENOMEM, "hipMalloc(%zu) failed: %s", alloc, hipGetErrorString(e));
+    }
+    ix->owned.push_back(d);
+    if (bytes) HIP_TRY(hipMemcpy(d, src, bytes, kind));
+    *out = d;
+    return PLAID_OK;
+}
+
+extern "C" void plaid_index_free(plaid_index *idx)
+{
+    if (!idx) return;
+    DeviceGuard g(idx->device);
+    (void)hipDeviceSynchronize();
+    for (void *p : idx->owned) (void)hipFree(p);
+    if (idx->ws) (void)hipFree(idx->ws);
+    for (int i = 0; i < N_EVENTS; ++i)
+        if (idx->ev[i]) (void)hipEventDestroy(idx->ev[i]);
+    delete idx;
+}
+
+extern "C" int plaid_index_from_view(const plaid_index_view *v, int device, int copy, plaid_index **out)
+{
+    if (!v || !out) return fail(PLAID_EINVAL, "null argument");
+    *out = nullptr;
+    if (!v->centroids || !v->doc_offsets || !v->bucket_weights || !v->ivf_offsets)
+        return fail(PLAID_EINVAL, "null array in view");
+    if (v->num_embeddings > 0 && (!v->codes || !v->residuals)) return fail(PLAID_EINVAL, "null codes/residuals");
+    if (!copy && !v->on_device) return fail(PLAID_EINVAL, "copy = 0 requires device arrays");
+    int rc = check_sizes(v->dim, v->nbits, v->num_centroids, v->num_passages, v->num_embeddings, 0);
+    if (rc) return rc;
+    const int64_t C = v->num_centroids, P = v->num_passages, N = v->num_embeddings;
+    int64_t ivf_len = 0;
+    if (!v->on_device) {
+        // host arrays are checked in full before any device is touched
+        ivf_len = v->ivf_offsets[C];
+        if (ivf_len < 0 || (ivf_len > 0 && !v->ivf_pids)) return fail(PLAID_EINVAL, "bad inverted lists");
+        rc = validate_host(v, ivf_len);
+        if (rc) return rc;
+    }
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) {
+        (void)hipGetLastError();
+        return fail(PLAID_EHIP, "no HIP device %d (found %d)", device, ndev);
+    }
+    DeviceGuard g(device);
+    if (!g.ok) return fail(PLAID_EHIP, "hipSetDevice(%d) failed", device);
+    if (v->on_device) {
+        HIP_TRY(hipMemcpy(&ivf_len, v->ivf_offsets + C, sizeof(int64_t), hipMemcpyDeviceToHost));
+        int64_t n_chk = 0;
+        HIP_TRY(hipMemcpy(&n_chk, v->doc_offsets + P, sizeof(int64_t), hipMemcpyDeviceToHost));
+        if (n_chk != N) return fail(PLAID_EINVAL, "doc_offsets[P] (%lld) != num_embeddings (%lld)", (long long)n_chk, (long long)N);
+        if (ivf_len < 0 || (ivf_len > 0 && !v->ivf_pids)) return fail(PLAID_EINVAL, "bad inverted lists");
+    }
+
+    plaid_index *ix = new (std::nothrow) plaid_index();
+    if (!ix) return fail(PLAID_ENOMEM, "host allocation failed");
+    ix->device = device;
+    ix->nbits = v->nbits;
+    ix->C = C;
+    ix->P = P;
+    ix->N = N;
+    ix->ivf_len = ivf_len;
+    if (copy) {
+        const hipMemcpyKind kind = v->on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+        const size_t rb = (size_t)16 * v->nbits;
+        rc = dev_alloc_copy(ix, v->centroids, (size_t)C * PLAID_DIM * 4, kind, (const void **)&ix->centroids);
+        if (!rc) rc = dev_alloc_copy(ix, v->doc_offsets, (size_t)(P + 1) * 8, kind, (const void **)&ix->doc_offsets);
+        if (!rc) rc = dev_alloc_copy(ix, v->codes, (size_t)N * 4, kind, (const void **)&ix->codes);
+        if (!rc) rc = dev_alloc_copy(ix, v->residuals, (size_t)N * rb, kind, (const void **)&ix->residuals);
+        if (!rc) rc = dev_alloc_copy(ix, v->bucket_weights, (size_t)(1 << v->nbits) * 4, kind, (const void **)&ix->weights);
+        if (!rc) rc = dev_alloc_copy(ix, v->ivf_offsets, (size_t)(C + 1) * 8, kind, (const void **)&ix->ivf_offsets);
+        if (!rc) rc = dev_alloc_copy(ix, v->ivf_pids, (size_t)ivf_len * 4, kind, (const void **)&ix->ivf_pids);
+        if (rc) {
+            plaid_index_free(ix);
+            return rc;
+        }
+    } else {
+        ix->centroids = v->centroids;
+        ix->doc_offsets = v->doc_offsets;
+        ix->codes = v->codes;
+        ix->residuals = v->residuals;
+        ix->weights = v->bucket_weights;
+        ix->ivf_offsets = v->ivf_offsets;
+        ix->ivf_pids = v->ivf_pids;
+    }
+    *out = ix;
+    return PLAID_OK;
+}
+
+// ------------------------------------------------------------------ index file
+static const char kMagic[8] = {'P', 'L', 'A', 'I', 'D', 'I', 'X', '1'};
+
+struct FileHeader {
+    char magic[8];
+    int32_t dim, nbits;
+    int64_t C, P, N, ivf_len;
+    char pad[16];
+};
+static_assert(sizeof(FileHeader) == 64, "index file header is 64 bytes");
+
+static int read_section(FILE *f, std::vector<char> &buf, size_t bytes)
+{
+    const size_t padded = (bytes + 63) & ~(size_t)63;
+    buf.resize(padded ? padded : 1);
+    if (padded && fread(buf.data(), 1, padded, f) != padded) return fail(PLAID_EFORMAT, "index file truncated");
+    return PLAID_OK;
+}
+
+extern "C" int plaid_index_load(const char *path, int device, plaid_index **out)
+{
+    if (!path || !out) return fail(PLAID_EINVAL, "null argument");
+    *out = nullptr;
+    FILE *f = fopen(path, "rb");
+    if (!f) return fail(PLAID_EIO, "cannot open %s", path);
+    FileHeader h;
+    if (fread(&h, 1, sizeof(h), f) != sizeof(h) || memcmp(h.magic, kMagic, 8) != 0) {
+        fclose(f);
+        return fail(PLAID_EFORMAT, "%s is not a PLAID index file", path);
+    }
+    int rc = check_sizes(h.dim, h.nbits, h.C, h.P, h.N, h.ivf_len);
+    if (rc) {
+        fclose(f);
+        return rc == PLAID_EINVAL ? fail(PLAID_EFORMAT, "bad header in %s: %s", path, std::string(g_err).c_str()) : rc;
+    }
+    const size_t rb = (size_t)16 * h.nbits;
+    const size_t sizes[7] = {(size_t)h.C * PLAID_DIM * 4, (size_t)(h.P + 1) * 8, (size_t)h.N * 4, (size_t)h.N * rb,
+                             (size_t)(1 << h.nbits) * 4, (size_t)(h.C + 1) * 8, (size_t)h.ivf_len * 4};
+    std::vector<char> sec[7];
+    for (int s = 0; s < 7; ++s) {
+        rc = read_section(f, sec[s], sizes[s]);
+        if (rc) {
+            fclose(f);
+            return rc;
+        }
+    }
+    fclose(f);
+    plaid_index_view v;
+    memset(&v, 0, sizeof(v));
+    v.dim = h.dim;
+    v.nbits = h.nbits;
+    v.num_centroids = h.C;
+    v.num_passages = h.P;
+    v.num_embeddings = h.N;
+    v.centroids = (const float *)sec[0].data();
+    v.doc_offsets = (const int64_t *)sec[1].data();
+    v.codes = (const int32_t *)sec[2].data();
+    v.residuals = (const uint8_t *)sec[3].data();
+    v.bucket_weights = (const float *)sec[4].data();
+    v.ivf_offsets = (const int64_t *)sec[5].data();
+    v.ivf_pids = (const int32_t *)sec[6].data();
+    v.on_device = 0;
+    if (v.ivf_offsets[h.C] != h.ivf_len) return fail(PLAID_EFORMAT, "inverted-list length in header does not match offsets");
+    rc = plaid_index_from_view(&v, device, 1, out);
+    if (rc == PLAID_EINVAL) return fail(PLAID_EFORMAT, "malformed index in %s: %s", path, std::string(g_err).c_str());
+    return rc;
+}
+
+extern "C" int plaid_index_info(const plaid_index *idx, int64_t *num_centroids, int64_t *num_passages,
+                                int64_t *num_embeddings, int32_t *nbits, int64_t *ivf_len)
+{
+    if (!idx) return fail(PLAID_EINVAL, "null index");
+    if (num_centroids) *num_centroids = idx->C;
+    if (num_passages) *num_passages = idx->P;
+    if (num_embeddings) *num_embeddings = idx->N;
+    if (nbits) *nbits = idx->nbits;
+    if (ivf_len) *ivf_len = idx->ivf_len;
+    return PLAID_OK;
+}
+
+extern "C" int plaid_set_stage_timing(plaid_index *idx, int32_t on)
+{
+    if (!idx) return fail(PLAID_EINVAL, "null index");
+    if (on && !idx->ev[0]) {
+        DeviceGuard g(idx->device);
+        for (int i = 0; i < N_EVENTS; ++i) HIP_TRY(hipEventCreate(&idx->ev[i]));
+    }
+    idx->timing = on ? 1 : 0;
+    return PLAID_OK;
+}
+extern "C" int plaid_get_stage_ms(const plaid_index *idx, float *out_ms)
+{
+    if (!idx || !out_ms) return fail(PLAID_EINVAL, "null argument");
+    for (int i = 0; i < PLAID_NUM_STAGES; ++i) out_ms[i] = idx->stage_ms[i];
+    return PLAID_OK;
+}
+extern "C" int plaid_set_max_chunk(plaid_index *idx, int32_t max_queries_per_chunk)
+{
+    if (!idx || max_queries_per_chunk < 0) return fail(PLAID_EINVAL, "bad argument");
+    idx->max_chunk = max_queries_per_chunk;
+    return PLAID_OK;
+}
+
+// ------------------------------------------------------------------ workspace of one query chunk
+struct Workspace {
+    // region that must be zero before each chunk
+    char *zero_base;
+    size_t zero_bytes;
+    uint32_t *candbits;  // [qc][cand_words]
+    int32_t *n_cand;     // [qc]
+    void *sel2_zero, *sel3_zero, *sel4_zero;
+    // everything else
+    double *Qd;          // [qc][128][32]
+    float *S;            // [qc][C][32]
+    uint32_t *keepbits;  // [qc][keep_words]
+    int32_t *probed;     // [qc][32][nprobe]
+    int32_t *uniq;       // [qc][uniq_stride]
+    int32_t *n_uniq;     // [qc]
+    void *probe_scratch;
+    size_t probe_scratch_bytes;
+    uint64_t *keys2;  // [qc][P]
+    uint64_t *sel2;   // [qc][nd]
+    int32_t *n2;      // [qc]
+    uint64_t *keys3;  // [qc][nd]
+    uint64_t *sel3;   // [qc][m3]
+    int32_t *n3;      // [qc]
+    uint64_t *keys4;  // [qc][m3]
+    uint64_t *topk;   // [qc][kk]
+    int32_t *n_out;   // [qc]
+    void *sel2_body, *sel3_body, *sel4_body;
+    int64_t keep_words, cand_words;
+    int uniq_stride;
+    size_t total;
+};
+
+struct Plan {
+    int32_t nprobe, nd, m3, kk;  // effective sizes: nd = min(ndocs, P), m3 = min(max(1, ndocs/4), nd), kk = min(k, m3)
+};
+
+static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl)
+{
+    Workspace w;
+    memset(&w, 0, sizeof(w));
+    const int64_t C = ix->C, P = ix->P;
+    w.keep_words = (C + 31) / 32;
+    w.cand_words = (P + 31) / 32;
+    const int64_t up = (int64_t)QLEN * pl.nprobe;
+    w.uniq_stride = (int)(up < C ? up : C);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char *p = base ? base + off : nullptr;
+        off += a256(bytes);
+        return p;
+    };
+    w.zero_base = take(0);
+    w.candbits = (uint32_t *)take((size_t)qc * w.cand_words * 4);
+    w.n_cand = (int32_t *)take((size_t)qc * 4);
+    w.sel2_zero = take(plaid_select_zero_bytes(qc));
+    w.sel3_zero = take(plaid_select_zero_bytes(qc));
+    w.sel4_zero = take(plaid_select_zero_bytes(qc));
+    w.zero_bytes = off;
+    w.Qd = (double *)take((size_t)qc * QLEN * DIM * 8);
+    w.S = (float *)take((size_t)qc * C * QLEN * 4);
+    w.keepbits = (uint32_t *)take((size_t)qc * w.keep_words * 4);
+    w.probed = (int32_t *)take((size_t)qc * QLEN * pl.nprobe * 4);
+    w.uniq = (int32_t *)take((size_t)qc * w.uniq_stride * 4);
+    w.n_uniq = (int32_t *)take((size_t)qc * 4);
+    w.probe_scratch_bytes = plaid_top_nprobe_scratch_bytes(C, qc, pl.nprobe);
+    w.probe_scratch = take(w.probe_scratch_bytes);
+    w.keys2 = (uint64_t *)take((size_t)qc * P * 8);
+    w.sel2 = (uint64_t *)take((size_t)qc * pl.nd * 8);
+    w.n2 = (int32_t *)take((size_t)qc * 4);
+    w.keys3 = (uint64_t *)take((size_t)qc * pl.nd * 8);
+    w.sel3 = (uint64_t *)take((size_t)qc * pl.m3 * 8);
+    w.n3 = (int32_t *)take((size_t)qc * 4);
+    w.keys4 = (uint64_t *)take((size_t)qc * pl.m3 * 8);
+    w.topk = (uint64_t *)take((size_t)qc * pl.kk * 8);
+    w.n_out = (int32_t *)take((size_t)qc * 4);
+    w.sel2_body = take(plaid_select_body_bytes(qc, P, pl.nd));
+    w.sel3_body = take(plaid_select_body_bytes(qc, pl.nd, pl.m3));
+    w.sel4_body = take(plaid_select_body_bytes(qc, pl.m3, pl.kk));
+    w.total = off;
+    return w;
+}
+
+static int ensure_workspace(plaid_index *ix, size_t bytes)
+{
+    if (ix->ws_bytes >= bytes) return PLAID_OK;
+    if (ix->ws) {
+        HIP_TRY(hipDeviceSynchronize());
+        (void)hipFree(ix->ws);
+        ix->ws = nullptr;
+        ix->ws_bytes = 0;
+    }
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PLAID_ENOMEM, "workspace of %zu bytes: %s", bytes, hipGetErrorString(e));
+    }
+    ix->ws = p;
+    ix->ws_bytes = bytes;
+    return PLAID_OK;
+}
+
+// ------------------------------------------------------------------ search
+static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t nprobe, float t_cs, int32_t ndocs, int32_t k,
+                       int32_t *out_ids, float *out_scores, void *hip_stream, const plaid_debug_buffers *dbg)
+{
+    if (!ix) return fail(PLAID_EINVAL, "null index");
+    if (!Q || !out_ids || !out_scores) return fail(PLAID_EINVAL, "null buffer");
+    if (nq < 1) return fail(PLAID_EINVAL, "nq must be >= 1 (got %d)", nq);
+    if (nprobe < 1 || nprobe > ix->C) return fail(PLAID_EINVAL, "nprobe must be in [1, C] (got %d, C = %lld)", nprobe, (long long)ix->C);
+    if (ndocs < 1) return fail(PLAID_EINVAL, "ndocs must be >= 1 (got %d)", ndocs);
+    if (k < 1) return fail(PLAID_EINVAL, "k must be >= 1 (got %d)", k);
+    if (t_cs != t_cs) return fail(PLAID_EINVAL, "t_cs is NaN");
+    DeviceGuard g(ix->device);
+    if (!g.ok) return fail(PLAID_EHIP, "hipSetDevice(%d) failed", ix->device);
+    hipStream_t st = (hipStream_t)hip_stream;
+
+    const int64_t C = ix->C, P = ix->P;
+    Plan pl;
+    pl.nprobe = nprobe;
+    pl.nd = (int32_t)(ndocs < P ? ndocs : P);
+    int32_t m3 = ndocs / 4 > 1 ? ndocs / 4 : 1;
+    pl.m3 = m3 < pl.nd ? m3 : pl.nd;
+    pl.kk = k < pl.m3 ? k : pl.m3;
+
+    // queries per chunk: bounded by the caller's limit, else by a workspace budget of about 6 GiB
+    const Workspace one = carve(nullptr, ix, 1, pl);
+    int qc = ix->max_chunk > 0 ? ix->max_chunk : 64;
+    if (ix->max_chunk <= 0) {
+        const size_t budget = (size_t)6 << 30;
+        const size_t fit = budget / (one.total ? one.total : 1);
+        if ((size_t)qc > fit) qc = fit < 1 ? 1 : (int)fit;
+    }
+    if (qc > nq) qc = nq;
+    if ((int64_t)qc * QLEN > 32768) qc = 32768 / QLEN;  // grid.y / segment limits of the per-token selections
+    const Workspace wsz = carve(nullptr, ix, qc, pl);
+    int rc = ensure_workspace(ix, wsz.total);
+    if (rc) return rc;
+
+    const bool timing = ix->timing != 0;
+    if (timing)
+        for (int s = 0; s < PLAID_NUM_STAGES; ++s) ix->stage_ms[s] = 0.f;
+
+    for (int32_t q0 = 0; q0 < nq; q0 += qc) {
+        const int n = nq - q0 < qc ? nq - q0 : qc;
+        const Workspace w = carve((char *)ix->ws, ix, n, pl);
+        const float *Qc = Q + (int64_t)q0 * QLEN * DIM;
+        const SelScratch sc2 = plaid_select_scratch_carve2(w.sel2_zero, w.sel2_body, n, P, pl.nd);
+        const SelScratch sc3 = plaid_select_scratch_carve2(w.sel3_zero, w.sel3_body, n, pl.nd, pl.m3);
+        const SelScratch sc4 = plaid_select_scratch_carve2(w.sel4_zero, w.sel4_body, n, pl.m3, pl.kk);
+        int e = 0;
+#define STAMP()                                            \
+    do {                                                   \
+        if (timing) HIP_TRY(hipEventRecord(ix->ev[e++], st)); \
+    } while (0)
+
+        STAMP();
+        // stage 1: S_cq (Eq. 2), pruning map (Eq. 5), probes and candidates (Section 4.1)
+        plaid_launch_fill_u32(st, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), 0u);
+        plaid_launch_scq(st, ix->centroids, C, Qc, w.Qd, n, t_cs, w.S, w.keepbits, w.keep_words);
+        STAMP();
+        plaid_launch_top_nprobe(st, w.S, C, n, nprobe, w.probed, w.uniq, w.uniq_stride, w.n_uniq, w.probe_scratch,
+                                w.probe_scratch_bytes);
+        STAMP();
+        plaid_launch_ivf_union(st, w.uniq, w.n_uniq, w.uniq_stride, ix->ivf_offsets, ix->ivf_pids, n, w.candbits,
+                               w.cand_words);
+        STAMP();
+        // stage 2: centroid interaction with pruning over every candidate (Eq. 3-5), keep ndocs
+        plaid_launch_ci_pruned(st, w.S, C, w.keepbits, w.keep_words, w.candbits, w.cand_words, P, ix->doc_offsets,
+                               ix->codes, n, w.keys2, P, w.n_cand, sc2.state);
+        STAMP();
+        plaid_launch_select(st, w.keys2, P, w.n_cand, n, P, pl.nd, w.sel2, pl.nd, w.n2, 0, sc2, 1);
+        STAMP();
+        // stage 3: centroid interaction without pruning (Eq. 3-4), keep ndocs/4
+        plaid_launch_ci_list(st, w.S, C, ix->doc_offsets, ix->codes, n, w.sel2, pl.nd, w.n2, pl.nd, w.keys3, pl.nd);
+        plaid_launch_select(st, w.keys3, pl.nd, w.n2, n, pl.nd, pl.m3, w.sel3, pl.m3, w.n3, 0, sc3, 0);
+        STAMP();
+        // stage 4: decompression (Section 4.5) + exact MaxSim (Eq. 1), best k
+        plaid_launch_decompress_maxsim(st, Qc, ix->centroids, ix->doc_offsets, ix->codes, ix->residuals, ix->weights,
+                                       ix->nbits, n, w.sel3, pl.m3, w.n3, pl.m3, w.keys4, pl.m3);
+        STAMP();
+        plaid_launch_select(st, w.keys4, pl.m3, w.n3, n, pl.m3, pl.kk, w.topk, pl.kk, w.n_out, 1, sc4, 0);
+        plaid_launch_keys_to_output(st, w.topk, pl.kk, w.n_out, n, k, out_ids + (int64_t)q0 * k,
+                                    out_scores + (int64_t)q0 * k);
+        STAMP();
+#undef STAMP
+        HIP_TRY(hipGetLastError());
+
+        if (dbg) {
+            if (dbg->S_cq)
+                HIP_TRY(hipMemcpyAsync(dbg->S_cq + (int64_t)q0 * C * QLEN, w.S, (size_t)n * C * QLEN * 4,
+                                       hipMemcpyDeviceToDevice, st));
+            if (dbg->probed)
+                HIP_TRY(hipMemcpyAsync(dbg->probed + (int64_t)q0 * QLEN * nprobe, w.probed, (size_t)n * QLEN * nprobe * 4,
+                                       hipMemcpyDeviceToDevice, st));
+            if (dbg->cand || dbg->n_cand)
+                plaid_launch_bitmap_to_list(st, w.candbits, w.cand_words, P, n, dbg->cand ? dbg->cand + (int64_t)q0 * P : nullptr,
+                                            P, dbg->n_cand ? dbg->n_cand + q0 : nullptr);
+            if (dbg->sel2_ids || dbg->sel2_scores || dbg->n2)
+                plaid_launch_keys_to_pairs(st, w.sel2, pl.nd, w.n2, n, ndocs,
+                                           dbg->sel2_ids ? dbg->sel2_ids + (int64_t)q0 * ndocs : nullptr,
+                                           dbg->sel2_scores ? dbg->sel2_scores + (int64_t)q0 * ndocs : nullptr,
+                                           dbg->n2 ? dbg->n2 + q0 : nullptr);
+            if (dbg->sel3_ids || dbg->sel3_scores || dbg->n3)
+                plaid_launch_keys_to_pairs(st, w.sel3, pl.m3, w.n3, n, m3,
+                                           dbg->sel3_ids ? dbg->sel3_ids + (int64_t)q0 * m3 : nullptr,
+                                           dbg->sel3_scores ? dbg->sel3_scores + (int64_t)q0 * m3 : nullptr,
+                                           dbg->n3 ? dbg->n3 + q0 : nullptr);
+            HIP_TRY(hipGetLastError());
+        }
+        if (timing) {
+            HIP_TRY(hipEventSynchronize(ix->ev[e - 1]));
+            for (int s = 0; s + 1 < e && s < PLAID_NUM_STAGES; ++s) {
+                float ms = 0.f;
+                HIP_TRY(hipEventElapsedTime(&ms, ix->ev[s], ix->ev[s + 1]));
+                ix->stage_ms[s] += ms;
+            }
+        }
+    }
+    return PLAID_OK;
+}
+
+extern "C" int plaid_search(plaid_index *idx, const float *Q, int32_t nq, int32_t nprobe, float t_cs, int32_t ndocs,
+                            int32_t k, int32_t *out_ids, float *out_scores, void *hip_stream)
+{
+    return search_impl(idx, Q, nq, nprobe, t_cs, ndocs, k, out_ids, out_scores, hip_stream, nullptr);
+}
+
+extern "C" int plaid_search_debug(plaid_index *idx, const float *Q, int32_t nq, int32_t nprobe, float t_cs, int32_t ndocs,
+                                  int32_t k, int32_t *out_ids, float *out_scores, void *hip_stream,
+                                  const plaid_debug_buffers *dbg)
+{
+    return search_impl(idx, Q, nq, nprobe, t_cs, ndocs, k, out_ids, out_scores, hip_stream, dbg);
+}
+
+// ------------------------------------------------------------------ decompression alone
+extern "C" int plaid_decompress_passages(plaid_index *ix, const int32_t *pids, int32_t n, int64_t *out_offsets,
+                                         float *out_vectors, uint8_t *out_indices, int64_t capacity, void *hip_stream)
+{
+    if (!ix) return fail(PLAID_EINVAL, "null index");
+    if (n < 0 || (n > 0 && !pids)) return fail(PLAID_EINVAL, "bad passage list");
+    if (capacity < 0) return fail(PLAID_EINVAL, "negative capacity");
+    DeviceGuard g(ix->device);
+    if (!g.ok) return fail(PLAID_EHIP, "hipSetDevice(%d) failed", ix->device);
+    hipStream_t st = (hipStream_t)hip_stream;
+    // the passage ids come from the caller: check them on the host before any kernel dereferences them
+    std::vector<int32_t> hp((size_t)(n > 0 ? n : 1));
+    if (n > 0) {
+        HIP_TRY(hipMemcpyAsync(hp.data(), pids, (size_t)n * 4, hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        for (int32_t a = 0; a < n; ++a)
+            if (hp[a] < 0 || hp[a] >= ix->P) return fail(PLAID_EINVAL, "pids[%d] = %d out of range", a, hp[a]);
+    }
+    int64_t *offs = out_offsets;
+    const size_t need = a256((size_t)(n + 1) * 8);
+    if (!offs) {
+        int rc = ensure_workspace(ix, need);
+        if (rc) return rc;
+        offs = (int64_t *)ix->ws;
+    }
+    plaid_launch_passage_offsets(st, ix->doc_offsets, pids, n, offs);
+    int64_t total = 0;
+    HIP_TRY(hipMemcpyAsync(&total, offs + n, 8, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (total > capacity && (out_vectors || out_indices))
+        return fail(PLAID_EINVAL, "passages hold %lld tokens, capacity is %lld", (long long)total, (long long)capacity);
+    if (out_vectors || out_indices)
+        plaid_launch_decompress_dump(st, ix->centroids, ix->doc_offsets, ix->codes, ix->residuals, ix->weights, ix->nbits,
+                                     pids, n, offs, out_vectors, out_indices);
+    HIP_TRY(hipGetLastError());
+    return PLAID_OK;
+}

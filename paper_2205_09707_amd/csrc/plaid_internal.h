@@ -1,0 +1,132 @@
+// Internal declarations shared by the HIP translation units of libplaid (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "plaid.h"
+
+#define QLEN PLAID_QLEN
+#define DIM PLAID_DIM
+
+// ---------------------------------------------------------------------------------------------
+// Ranking keys.  Every top-n of the pipeline ranks by (score descending, id ascending).  A 64-bit
+// key whose ASCENDING order is that ranking: high word = bitwise complement of the usual
+// order-preserving map of the fp32 score, low word = id.  Keys are unique because ids are.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ __forceinline__ uint32_t plaid_score_to_ord(float s)
+{
+    s += 0.0f;  // -0 -> +0 so that the two zeros tie
+    union { float f; uint32_t u; } c;
+    c.f = s;
+    uint32_t u = c.u;
+    u ^= (u >> 31) ? 0xFFFFFFFFu : 0x80000000u;  // larger score -> larger u
+    return ~u;                                   // larger score -> smaller key
+}
+__host__ __device__ __forceinline__ float plaid_ord_to_score(uint32_t k)
+{
+    uint32_t u = ~k;
+    u ^= (u >> 31) ? 0x80000000u : 0xFFFFFFFFu;
+    union { float f; uint32_t u; } c;
+    c.u = u;
+    return c.f;
+}
+__host__ __device__ __forceinline__ uint64_t plaid_make_key(float score, uint32_t id)
+{
+    return ((uint64_t)plaid_score_to_ord(score) << 32) | id;
+}
+#define PLAID_KEY_MAX 0xFFFFFFFFFFFFFFFFull
+
+// ---------------------------------------------------------------------------------------------
+// Selection (k_select.hip): first m keys in ascending order out of per-segment lists.
+// ---------------------------------------------------------------------------------------------
+#define SEL_RADIX_BITS 11
+#define SEL_BINS (1 << SEL_RADIX_BITS)
+#define SEL_SORT_CAP 8192  // keys one block can sort in LDS
+
+// Per-segment state of a multi-level selection (device memory, 64 bytes, zeroed before each use).
+struct SelState {
+    unsigned long long key_or;   // OR over the input keys   (accumulated by the producer or by sel_andor_kernel)
+    unsigned long long key_nor;  // OR over their complements (AND of the keys = ~key_nor)
+    int32_t n_in;       // number of input keys
+    int32_t m_rem[3];   // keys still to take before level 0 / level 1 / the finishing step
+    int32_t n_sure;     // keys already known to be selected
+    int32_t n_list[2];  // sizes of the boundary lists after level 0 and level 1
+    int32_t shift[2];   // bit position of the digit examined at level 0 / level 1
+    int32_t width[2];   // its width in bits
+    int32_t pad;
+};
+static_assert(sizeof(SelState) == 64, "SelState is a 64-byte record");
+
+struct SelScratch {         // all device pointers, per segment strides in elements
+    SelState *state;        // [nseg]                 } zeroed together before each use:
+    int32_t *hist;          // [nseg][2][SEL_BINS]    } plaid_select_zero_bytes(nseg) bytes from `state`
+    uint64_t *sure;         // [nseg][sure_stride]
+    uint64_t *list0;        // [nseg][list_stride]   boundary list after level 0
+    uint64_t *list1;        // [nseg][list_stride]   boundary list after level 1
+    uint64_t *sortbuf;      // [nseg][pow2(m)] only when more than SEL_SORT_CAP sorted results are requested
+    int64_t sure_stride, list_stride;
+};
+
+// keys: [nseg][key_stride]; counts[seg] valid entries (device).  n_upper / m: host upper bounds.
+// out: [nseg][out_stride] receives min(m, count) keys (ascending if sorted != 0, else unspecified
+// order), out_counts[seg] their number.  When state_ready != 0 the producer has already filled
+// SelState::key_and / key_or / n_in for every segment.
+void plaid_launch_select(hipStream_t st, const uint64_t *keys, int64_t key_stride, const int32_t *counts, int nseg,
+                         int64_t n_upper, int32_t m, uint64_t *out, int64_t out_stride, int32_t *out_counts,
+                         int sorted, const SelScratch &sc, int state_ready);
+size_t plaid_select_scratch_bytes(int nseg, int64_t n_upper, int32_t m);
+size_t plaid_select_zero_bytes(int nseg);
+size_t plaid_select_body_bytes(int nseg, int64_t n_upper, int32_t m);
+SelScratch plaid_select_scratch_carve(void *base, int nseg, int64_t n_upper, int32_t m);
+SelScratch plaid_select_scratch_carve2(void *zero_base, void *body_base, int nseg, int64_t n_upper, int32_t m);
+
+// ---------------------------------------------------------------------------------------------
+// Stage kernels
+// ---------------------------------------------------------------------------------------------
+// Eq. 2 + Eq. 5: S[q][c][i] and the keep bitmap (bit c of keepbits[q] = max_i S[q][c][i] >= t_cs).
+void plaid_launch_scq(hipStream_t st, const float *centroids, int64_t C, const float *Q, double *Qd, int nq, float t_cs, float *S,
+                      uint32_t *keepbits, int64_t keep_words);
+
+// Section 4.1: per query token the nprobe best centroids (rank order) + the ascending unique union.
+void plaid_launch_top_nprobe(hipStream_t st, const float *S, int64_t C, int nq, int nprobe, int32_t *probed,
+                             int32_t *uniq, int uniq_stride, int32_t *n_uniq, void *scratch, size_t scratch_bytes);
+size_t plaid_top_nprobe_scratch_bytes(int64_t C, int nq, int nprobe);
+
+// Section 4.1: candidate bitmap = union of the inverted lists of the unique probed centroids.
+void plaid_launch_ivf_union(hipStream_t st, const int32_t *uniq, const int32_t *n_uniq, int uniq_stride,
+                            const int64_t *ivf_offsets, const int32_t *ivf_pids, int nq, uint32_t *candbits,
+                            int64_t cand_words);
+
+// Eq. 3-5 over every candidate (stage 2): appends one key per candidate to keys2[q] and counts them.
+void plaid_launch_ci_pruned(hipStream_t st, const float *S, int64_t C, const uint32_t *keepbits, int64_t keep_words,
+                            const uint32_t *candbits, int64_t cand_words, int64_t P, const int64_t *doc_offsets,
+                            const int32_t *codes, int nq, uint64_t *keys2, int64_t key_stride, int32_t *n_cand,
+                            SelState *state);
+
+// Eq. 3-4 over a key list (stage 3): out_keys[q][j] is the key of the passage of in_keys[q][j].
+void plaid_launch_ci_list(hipStream_t st, const float *S, int64_t C, const int64_t *doc_offsets, const int32_t *codes,
+                          int nq, const uint64_t *in_keys, int64_t in_stride, const int32_t *in_counts, int n_upper,
+                          uint64_t *out_keys, int64_t out_stride);
+
+// Section 4.5 + Eq. 1 over a key list (stage 4).
+void plaid_launch_decompress_maxsim(hipStream_t st, const float *Q, const float *centroids, const int64_t *doc_offsets,
+                                    const int32_t *codes, const uint8_t *residuals, const float *bucket_weights,
+                                    int nbits, int nq, const uint64_t *in_keys, int64_t in_stride,
+                                    const int32_t *in_counts, int n_upper, uint64_t *out_keys, int64_t out_stride);
+
+// Section 4.5 alone: reconstructed vectors / bucket indices of listed passages.
+void plaid_launch_decompress_dump(hipStream_t st, const float *centroids, const int64_t *doc_offsets,
+                                  const int32_t *codes, const uint8_t *residuals, const float *bucket_weights,
+                                  int nbits, const int32_t *pids, int n, const int64_t *out_offsets, float *out_vectors,
+                                  uint8_t *out_indices);
+void plaid_launch_passage_offsets(hipStream_t st, const int64_t *doc_offsets, const int32_t *pids, int n,
+                                  int64_t *out_offsets);
+
+// Small utilities
+void plaid_launch_fill_u32(hipStream_t st, uint32_t *p, int64_t n, uint32_t v);
+void plaid_launch_keys_to_output(hipStream_t st, const uint64_t *keys, int64_t key_stride, const int32_t *counts, int nq,
+                                 int32_t k, int32_t *out_ids, float *out_scores);
+void plaid_launch_keys_to_pairs(hipStream_t st, const uint64_t *keys, int64_t key_stride, const int32_t *counts, int nq,
+                                int32_t cap, int32_t *out_ids, float *out_scores, int32_t *out_counts);
+void plaid_launch_bitmap_to_list(hipStream_t st, const uint32_t *bits, int64_t words, int64_t nbits_valid, int nq,
+                                 int32_t *out, int64_t out_stride, int32_t *out_counts);

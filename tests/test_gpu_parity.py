@@ -1,0 +1,188 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Runs only on a machine with an MI355X (`-m gpu`).  Sizes: the tiny configuration with all its
+queries stage by stage, random small indexes sweeping the degenerate cases, and the codec alone.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from synth import get_config, make_workload, tiny_config
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pl():
+    import paper_2205_09707_amd as pl_
+    pl_.load_library()   # fails loudly when libplaid.so has not been built
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return pl_
+
+
+def _check_workload(pl, w, params_list, want=None, queries=None, copy=False):
+    ix = pu.oracle_index(w)
+    gidx = pl.plaid_index_from_view(pu.device_arrays(w), w.cfg.nbits, device=0, copy=copy)
+    Qdev = w.queries.to("cuda:0")
+    Qh = w.queries.numpy()
+    nq = Qh.shape[0]
+    identical = 0
+    total = 0
+    try:
+        for params in params_list:
+            print(f"[parity] {w.cfg.name} {w.noise} params={params}", flush=True)
+            out = pu.run_gpu_debug(pl, gidx, Qdev, params, want=want)
+            for q in (range(nq) if queries is None else queries):
+                same = pu.compare_query(ix, Qh[q], params, pu.slice_query(out, q), ctx=f"{w.cfg.name}/{w.noise} {params} q{q}")
+                identical += bool(same)
+                total += 1
+    finally:
+        pl.plaid_index_free(gidx)
+    return identical, total
+
+
+@pytest.mark.parametrize("noise", ["literal", "calibrated"])
+def test_cfg1_all_stages(pl, noise):
+    cfg = get_config("cfg1")
+    w = make_workload(cfg, device="cpu", noise=noise)
+    same, total = _check_workload(pl, w, [(cfg.nprobe, cfg.t_cs, cfg.ndocs, cfg.k)])
+    print(f"cfg1/{noise}: {same}/{total} queries with id lists identical to the oracle's")
+    assert same >= total - 1   # near-ties inside 1e-4 at the final cut are the only allowed difference
+
+
+def test_cfg1_other_operating_points(pl):
+    """Table 2's other two triples, and a threshold low enough that many centroids survive."""
+    cfg = get_config("cfg1")
+    w = make_workload(cfg, device="cpu", noise="calibrated")
+    _check_workload(pl, w, [(2, 0.45, 1024, 100), (4, 0.4, 4096, 1000), (3, 0.2, 300, 40), (1, -np.inf, 64, 16)])
+
+
+def test_pipeline_equals_exhaustive_when_nothing_is_filtered(pl):
+    """nprobe = C, t_cs = -inf, ndocs >= 4P: every passage reaches stage 4, so the library's result must be the
+    exhaustive MaxSim ranking (ndocs = 4P because stage 3 keeps ndocs/4)."""
+    w = make_workload(tiny_config(C=48, P=150, lo=1, hi=70, nbits=2, nq=5, seed=11), noise="calibrated")
+    ix = pu.oracle_index(w)
+    gidx = pl.plaid_index_from_view(pu.device_arrays(w), 2, device=0, copy=True)
+    try:
+        k = 20
+        ids, sc = pl.plaid_search(gidx, w.queries.to("cuda:0"), 48, -np.inf, 4 * 150, k)
+        ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+        allp = np.arange(150, dtype=np.int32)
+        for q in range(5):
+            Q = w.queries[q].numpy()
+            e_ids, e_sc = orc.exhaustive(ix, Q, k)
+            s_all = orc.maxsim(ix, Q, allp)
+            same = pu.assert_final_matches(ids[q], sc[q], allp, s_all, k, ctx=f"exhaustive q{q}")
+            if same:
+                assert np.array_equal(ids[q], e_ids)
+            assert np.max(np.abs(sc[q] - e_sc)) <= 2 * pu.TOL
+    finally:
+        pl.plaid_index_free(gidx)
+
+
+SWEEP = [
+    # C, P, lo, hi, nbits, seed, noise
+    (16, 50, 1, 9, 2, 1, "calibrated"),
+    (16, 50, 1, 9, 1, 2, "literal"),
+    (5, 7, 1, 3, 2, 3, "calibrated"),
+    (33, 200, 1, 130, 2, 4, "calibrated"),     # passages longer than two waves of tokens
+    (70, 321, 0, 40, 1, 5, "calibrated"),      # empty passages, ragged sizes
+    (1, 9, 1, 5, 2, 6, "literal"),             # a single centroid
+    (300, 1, 5, 5, 2, 7, "calibrated"),        # a single passage
+]
+
+
+@pytest.mark.parametrize("C,P,lo,hi,nbits,seed,noise", SWEEP)
+def test_small_index_sweep(pl, C, P, lo, hi, nbits, seed, noise):
+    w = make_workload(tiny_config(C=C, P=P, lo=lo, hi=hi, nbits=nbits, nq=4, seed=seed), noise=noise)
+    S = orc.scq(w.centroids.numpy(), w.queries[0].numpy())
+    qs = np.quantile(S.max(axis=1), [0.3, 0.9]).tolist()
+    params = []
+    for nprobe in sorted({1, min(2, C), min(9, C), C}):
+        for t_cs in (-np.inf, qs[0], qs[1], np.inf):
+            for ndocs, k in ((1, 1), (4, 3), (17, 5), (4 * P + 3, P + 2)):
+                params.append((nprobe, float(t_cs), ndocs, k))
+    # a deterministic subset keeps the run short while every value of every parameter appears
+    params = params[:: 3] + params[-2:]
+    _check_workload(pl, w, params)
+
+
+def test_codec_bit_exact(pl):
+    """Unpacked bucket indices and reconstructed vectors (Section 4.5) are bit-identical to the oracle's."""
+    for nbits, seed in ((2, 21), (1, 22)):
+        w = make_workload(tiny_config(C=64, P=300, lo=0, hi=50, nbits=nbits, nq=1, seed=seed), noise="calibrated")
+        ix = pu.oracle_index(w)
+        gidx = pl.plaid_index_from_view(pu.device_arrays(w), nbits, device=0, copy=False)
+        try:
+            rng = np.random.default_rng(seed)
+            pids = np.concatenate([rng.permutation(300)[:120], [0, 299, 299]]).astype(np.int32)
+            lens = (w.doc_offsets[1:] - w.doc_offsets[:-1]).numpy()
+            total = int(lens[pids].sum())
+            offs, vec, ind = pl.plaid_decompress_passages(gidx, torch.from_numpy(pids).to("cuda:0"), total)
+            offs, vec, ind = offs.cpu().numpy(), vec.cpu().numpy(), ind.cpu().numpy()
+            assert offs[-1] == total
+            do = w.doc_offsets.numpy()
+            for a, p in enumerate(pids):
+                D, idx = orc.decompress(ix, int(do[p]), int(do[p + 1]))
+                assert np.array_equal(ind[offs[a]:offs[a + 1]], idx), f"bucket indices of passage {p}"
+                assert np.array_equal(pu.bits(vec[offs[a]:offs[a + 1]]), pu.bits(D)), f"vectors of passage {p}"
+            with pytest.raises(pl.PlaidError):
+                pl.plaid_decompress_passages(gidx, torch.from_numpy(pids).to("cuda:0"), total - 1)
+        finally:
+            pl.plaid_index_free(gidx)
+
+
+def test_argument_errors(pl):
+    w = make_workload(tiny_config(C=8, P=10, lo=1, hi=4, nbits=2, nq=2, seed=9), noise="literal")
+    gidx = pl.plaid_index_from_view(pu.device_arrays(w), 2, device=0, copy=True)
+    Q = w.queries.to("cuda:0")
+    try:
+        for bad in ((0, 0.5, 4, 2), (9, 0.5, 4, 2), (1, 0.5, 0, 2), (1, 0.5, 4, 0), (1, float("nan"), 4, 2)):
+            with pytest.raises(pl.PlaidError) as e:
+                pl.plaid_search(gidx, Q, *bad)
+            assert e.value.status == pl.plaid.PLAID_EINVAL
+        # the handle still works after rejected calls
+        ids, sc = pl.plaid_search(gidx, Q, 1, 0.5, 4, 2)
+        torch.cuda.synchronize()
+        assert ids.shape == (2, 2)
+    finally:
+        pl.plaid_index_free(gidx)
+
+
+def test_index_file_round_trip(pl, tmp_path):
+    from synth import save_index_file
+    w = make_workload(tiny_config(C=32, P=80, lo=1, hi=20, nbits=2, nq=3, seed=13), noise="calibrated")
+    path = str(tmp_path / "tiny.plaid")
+    save_index_file(path, w.numpy(), 2)
+    a = pl.plaid_index_load(path, 0)
+    b = pl.plaid_index_from_view(pu.device_arrays(w), 2, device=0, copy=False)
+    try:
+        Q = w.queries.to("cuda:0")
+        ia, sa = pl.plaid_search(a, Q, 2, 0.3, 16, 4)
+        ib, sb = pl.plaid_search(b, Q, 2, 0.3, 16, 4)
+        torch.cuda.synchronize()
+        assert torch.equal(ia, ib) and torch.equal(sa, sb)
+        assert pl.plaid_index_info(a) == pl.plaid_index_info(b)
+    finally:
+        pl.plaid_index_free(a)
+        pl.plaid_index_free(b)
+
+
+def test_repeatable(pl):
+    """The same call twice gives bit-identical outputs (no order-dependent arithmetic anywhere)."""
+    cfg = get_config("cfg1")
+    w = make_workload(cfg, device="cpu", noise="calibrated")
+    gidx = pl.plaid_index_from_view(pu.device_arrays(w), 2, device=0, copy=False)
+    try:
+        Q = w.queries.to("cuda:0")
+        a = pl.plaid_search(gidx, Q, 2, 0.45, 1024, 100)
+        b = pl.plaid_search(gidx, Q, 2, 0.45, 1024, 100)
+        one = [pl.plaid_search(gidx, Q[q:q + 1], 2, 0.45, 1024, 100) for q in range(Q.shape[0])]
+        torch.cuda.synchronize()
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+        assert torch.equal(a[0], torch.cat([o[0] for o in one])) and torch.equal(a[1], torch.cat([o[1] for o in one]))
+    finally:
+        pl.plaid_index_free(gidx)

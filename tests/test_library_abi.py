@@ -1,0 +1,126 @@
+"""CPU-side checks of libplaid.so: it loads, exports every function include/plaid.h declares, and its
+host-side validation rejects malformed input before any device is touched.  No compute calls."""
+import ctypes as ct
+import os
+import re
+import struct
+
+import numpy as np
+import pytest
+
+import paper_2205_09707_amd as pl
+from paper_2205_09707_amd import plaid
+from synth import make_workload, save_index_file, tiny_config
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "plaid.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(plaid.LIB_PATH):
+        from paper_2205_09707_amd import build
+        build.build()
+    return pl.load_library()
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(plaid_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert "plaid_search" in names and "plaid_index_load" in names and len(names) >= 10
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in plaid.h but not exported by libplaid.so"
+    assert sorted(plaid.EXPORTS) == names, "the Python binding must carry the same names as the header"
+
+
+def _view(w, **over):
+    a = w.numpy()
+    v = plaid.plaid_index_view()
+    v.dim, v.nbits = 128, w.cfg.nbits
+    v.num_centroids, v.num_passages, v.num_embeddings = a["centroids"].shape[0], a["doc_offsets"].shape[0] - 1, a["codes"].shape[0]
+    for n in ("centroids", "doc_offsets", "codes", "residuals", "bucket_weights", "ivf_offsets", "ivf_pids"):
+        setattr(v, n, a[n].ctypes.data)
+    v.on_device = 0
+    for k, val in over.items():
+        setattr(v, k, val)
+    return v, a
+
+
+def test_from_view_rejects_malformed_host_views(lib):
+    w = make_workload(tiny_config(C=8, P=10, lo=1, hi=4, nbits=2, nq=1, seed=1), noise="literal")
+    h = ct.c_void_p()
+
+    def call(v, copy=1):
+        return lib.plaid_index_from_view(ct.byref(v), 0, copy, ct.byref(h))
+
+    assert lib.plaid_index_from_view(None, 0, 1, ct.byref(h)) == plaid.PLAID_EINVAL
+    v, keep = _view(w, dim=64)
+    assert call(v) == plaid.PLAID_EINVAL and "dim" in pl.plaid_last_error()
+    v, keep = _view(w, nbits=3)
+    assert call(v) == plaid.PLAID_EINVAL
+    v, keep = _view(w, centroids=None)
+    assert call(v) == plaid.PLAID_EINVAL
+    v, keep = _view(w)
+    assert call(v, copy=0) == plaid.PLAID_EINVAL            # host arrays cannot be adopted
+    v, keep = _view(w, num_embeddings=keep["codes"].shape[0] + 1)
+    assert call(v) == plaid.PLAID_EINVAL                    # doc_offsets[P] != N
+    v, keep = _view(w)
+    keep["codes"][3] = 8                                    # centroid id out of range
+    assert call(v) == plaid.PLAID_EINVAL and "codes[3]" in pl.plaid_last_error()
+    v, keep = _view(w)
+    keep["doc_offsets"][4] = keep["doc_offsets"][5] + 1     # offsets decrease
+    assert call(v) == plaid.PLAID_EINVAL
+    v, keep = _view(w)
+    lst = [c for c in range(8) if keep["ivf_offsets"][c + 1] - keep["ivf_offsets"][c] >= 2][0]
+    e = keep["ivf_offsets"][lst]
+    keep["ivf_pids"][e + 1] = keep["ivf_pids"][e]           # list no longer strictly ascending
+    assert call(v) == plaid.PLAID_EINVAL
+    assert h.value is None
+
+
+def test_index_load_errors(lib, tmp_path):
+    h = ct.c_void_p()
+    assert lib.plaid_index_load(None, 0, ct.byref(h)) == plaid.PLAID_EINVAL
+    assert lib.plaid_index_load(os.fsencode(str(tmp_path / "missing")), 0, ct.byref(h)) == plaid.PLAID_EIO
+    bad = tmp_path / "bad"
+    bad.write_bytes(b"NOTANIDX" + b"\0" * 100)
+    assert lib.plaid_index_load(os.fsencode(str(bad)), 0, ct.byref(h)) == plaid.PLAID_EFORMAT
+    w = make_workload(tiny_config(C=8, P=10, lo=1, hi=4, nbits=2, nq=1, seed=1), noise="literal")
+    good = tmp_path / "good"
+    save_index_file(str(good), w.numpy(), 2)
+    data = good.read_bytes()
+    assert len(data) % 64 == 0 and data[:8] == b"PLAIDIX1"
+    dim, nbits, C, P, N, L = struct.unpack("<iiqqqq", data[8:48])
+    assert (dim, nbits, C, P, N) == (128, 2, 8, 10, w.N) and L == w.ivf_pids.numel()
+    trunc = tmp_path / "trunc"
+    trunc.write_bytes(data[: len(data) - 64])
+    assert lib.plaid_index_load(os.fsencode(str(trunc)), 0, ct.byref(h)) == plaid.PLAID_EFORMAT
+    hdr = bytearray(data)
+    hdr[12:16] = struct.pack("<i", 5)                       # nbits = 5
+    (tmp_path / "hdr").write_bytes(bytes(hdr))
+    assert lib.plaid_index_load(os.fsencode(str(tmp_path / "hdr")), 0, ct.byref(h)) == plaid.PLAID_EFORMAT
+
+
+def test_null_handles(lib):
+    lib.plaid_index_free(None)                              # allowed
+    buf = (ct.c_float * 8)()
+    assert lib.plaid_get_stage_ms(None, buf) == plaid.PLAID_EINVAL
+    assert lib.plaid_set_stage_timing(None, 1) == plaid.PLAID_EINVAL
+    assert lib.plaid_set_max_chunk(None, 4) == plaid.PLAID_EINVAL
+    assert lib.plaid_index_info(None, None, None, None, None, None) == plaid.PLAID_EINVAL
+    assert lib.plaid_search(None, None, 1, 1, ct.c_float(0.5), 4, 2, None, None, None) == plaid.PLAID_EINVAL
+    assert lib.plaid_decompress_passages(None, None, 0, None, None, None, 0, None) == plaid.PLAID_EINVAL
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    class Fake:
+        device = torch.device("cuda", 0)
+        handle = ct.c_void_p(1)
+    with pytest.raises(ValueError):
+        pl.plaid_search(Fake(), torch.zeros(1, 32, 128), 1, 0.5, 4, 2)

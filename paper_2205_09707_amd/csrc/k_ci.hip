@@ -4,8 +4,8 @@
 // token (lane i and lane i+32 both serve token i, on alternate passage tokens) and sums the 32 maxima
 // at the end -- in double, so that equal sets of rows give bit-equal scores whatever the order.
 //
-// This file holds the gather formulation (one wave per passage, rows fetched from the L2-resident S);
-// it serves stage 3 and is the general fallback of stage 2.
+// This file holds the gather formulation for a list of passages (one wave per passage, rows fetched
+// from the L2-resident S): stage 3.
 #include "plaid_internal.h"
 
 #include <math.h>
@@ -86,67 +86,4 @@ void plaid_launch_ci_list(hipStream_t st, const float *S, int64_t C, const int64
 {
     hipLaunchKernelGGL(ci_list_kernel, dim3((n_upper + 3) / 4, nq), dim3(256), 0, st, S, C, doc_offsets, codes, in_keys,
                        in_stride, in_counts, out_keys, out_stride);
-}
-
-// Stage 2, general form: every candidate of the bitmap, pruned rows, keys appended in any order
-// (the selection that follows is order-independent because keys are unique).
-__global__ __launch_bounds__(256) void ci_pruned_gather_kernel(const float *__restrict__ S, int64_t C,
-                                                               const uint32_t *__restrict__ keepbits, int64_t keep_words,
-                                                               const uint32_t *__restrict__ candbits, int64_t cand_words,
-                                                               int64_t P, const int64_t *__restrict__ doc_offsets,
-                                                               const int32_t *__restrict__ codes,
-                                                               uint64_t *__restrict__ keys2, int64_t key_stride,
-                                                               int32_t *__restrict__ n_cand, SelState *state)
-{
-    const int q = blockIdx.y;
-    const int lane = threadIdx.x & 63;
-    const float *Sq = S + (int64_t)q * C * QLEN;
-    const uint32_t *kb = keepbits + (int64_t)q * keep_words;
-    const uint32_t *cb = candbits + (int64_t)q * cand_words;
-    uint64_t *out = keys2 + (int64_t)q * key_stride;
-    unsigned long long k_or = 0, k_nor = 0;
-    for (int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); w < cand_words; w += (int64_t)gridDim.x * 4) {
-        const uint32_t word = cb[w];
-        if (!word) continue;
-        const int64_t p0 = w * 32;
-        int64_t off = 0;
-        if (lane <= 32 && p0 + lane <= P) off = doc_offsets[p0 + lane];
-        uint64_t mykey = 0;
-        uint32_t rest = word;
-        while (rest) {
-            const int b = __ffs(rest) - 1;
-            rest &= rest - 1;
-            const int64_t t0 = __shfl(off, b), t1 = __shfl(off, b + 1);
-            const float sc = ci_passage<true>(Sq, kb, t0, t1, codes, lane);
-            if (lane == b) mykey = plaid_make_key(sc, (uint32_t)(p0 + b));
-        }
-        int base = 0;
-        if (lane == 0) base = atomicAdd(&n_cand[q], __popc(word));
-        base = __shfl(base, 0);
-        if (lane < 32 && ((word >> lane) & 1u)) {
-            out[base + __popc(word & ((1u << lane) - 1u))] = mykey;
-            k_or |= mykey;
-            k_nor |= ~mykey;
-        }
-    }
-    for (int d = 1; d < 64; d <<= 1) {
-        k_or |= __shfl_xor(k_or, d);
-        k_nor |= __shfl_xor(k_nor, d);
-    }
-    if (lane == 0 && (k_or | k_nor)) {
-        atomicOr(&state[q].key_or, k_or);
-        atomicOr(&state[q].key_nor, k_nor);
-    }
-}
-
-void plaid_launch_ci_pruned(hipStream_t st, const float *S, int64_t C, const uint32_t *keepbits, int64_t keep_words,
-                            const uint32_t *candbits, int64_t cand_words, int64_t P, const int64_t *doc_offsets,
-                            const int32_t *codes, int nq, uint64_t *keys2, int64_t key_stride, int32_t *n_cand,
-                            SelState *state)
-{
-    int64_t gx = (cand_words + 3) / 4;
-    const int64_t cap = nq >= 16 ? 256 : (nq >= 4 ? 1024 : 4096);
-    if (gx > cap) gx = cap;
-    hipLaunchKernelGGL(ci_pruned_gather_kernel, dim3((int)gx, nq), dim3(256), 0, st, S, C, keepbits, keep_words, candbits,
-                       cand_words, P, doc_offsets, codes, keys2, key_stride, n_cand, state);
 }

@@ -447,3 +447,286 @@ void plaid_launch_select(hipStream_t st, const uint64_t *keys, int64_t key_strid
         hipLaunchKernelGGL(sel_copy_back_kernel, dim3(gx, nseg), dim3(256), 0, st, buf, n2, out_counts, out, out_stride);
     }
 }
+
+// =================================================================================================
+// Stage-2 selection: the ndocs best candidates out of up to P keys plus the empty-bag candidates.
+//
+// The producer has already counted the keys into SEL_BINS score bins (bin 0 = best), so the cut is
+// found without another pass: keys in bins before the boundary bin are selected for sure, the
+// boundary bin (normally a few hundred keys) is sorted by the finishing workgroup.  Exact score
+// ties are common (passages with the same surviving centroids score identically), so a boundary
+// bin can be long: then one digit pass over its keys -- starting at the highest bit in which they
+// differ, which skips the tied score bits and lands in the passage id -- cuts it down first.
+// Candidates with an empty bag (-infinity) are appended last, in passage-id order, straight from
+// their bitmap.
+// =================================================================================================
+__global__ __launch_bounds__(SEL_THREADS) void sel2_filter_kernel(const uint64_t *__restrict__ keys, int64_t key_stride,
+                                                                  const int32_t *__restrict__ n_ne, int32_t m,
+                                                                  const S2Meta *__restrict__ meta,
+                                                                  const int32_t *__restrict__ hist, Sel2State *state,
+                                                                  uint64_t *__restrict__ out, int64_t out_stride,
+                                                                  uint64_t *__restrict__ blist, int64_t blist_stride)
+{
+    __shared__ int32_t scan[SEL_THREADS];
+    __shared__ int32_t res[2];
+    const int seg = blockIdx.y;
+    const int n = n_ne[seg];
+    if ((int64_t)blockIdx.x * SEL_THREADS >= (((int64_t)n + 63) & ~63ll) && blockIdx.x != 0) return;
+    Sel2State *s = state + seg;
+    const S2Meta mt = meta[seg];
+    const int32_t m_eff = m < n ? m : n;
+    int bstar, before;
+    find_boundary(hist + (int64_t)seg * SEL_BINS, m_eff, scan, res, bstar, before);
+    if (blockIdx.x == 0 && threadIdx.x == 0) s->m_rem = m_eff - before;
+    const uint64_t *k = keys + (int64_t)seg * key_stride;
+    uint64_t *my_out = out + (int64_t)seg * out_stride;
+    uint64_t *my_bl = blist + (int64_t)seg * blist_stride;
+    const int lane = threadIdx.x & 63;
+    const int64_t n_round = ((int64_t)n + 63) & ~63ll;
+    unsigned long long o = 0, no = 0;
+    for (int64_t i = (int64_t)blockIdx.x * SEL_THREADS + threadIdx.x; i < n_round; i += (int64_t)gridDim.x * SEL_THREADS) {
+        uint64_t key = 0;
+        int cls = 2;  // 0 = surely selected, 1 = boundary, 2 = dropped
+        if (i < n) {
+            key = k[i];
+            const int d = plaid_s2_bin(plaid_ord_to_score((uint32_t)(key >> 32)), mt.bin_hi, mt.bin_scale);
+            cls = d < bstar ? 0 : (d == bstar ? 1 : 2);
+        }
+        const unsigned long long b0 = __ballot(cls == 0), b1 = __ballot(cls == 1);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        int base0 = 0, base1 = 0;
+        if (lane == 0) {
+            if (b0) base0 = atomicAdd(&s->n_sure, __popcll(b0));
+            if (b1) base1 = atomicAdd(&s->n_b, __popcll(b1));
+        }
+        base0 = __shfl(base0, 0);
+        base1 = __shfl(base1, 0);
+        if (cls == 0) my_out[base0 + __popcll(b0 & below)] = key;
+        if (cls == 1) {
+            my_bl[base1 + __popcll(b1 & below)] = key;
+            o |= key;
+            no |= ~key;
+        }
+    }
+    for (int d = 1; d < 64; d <<= 1) {
+        o |= __shfl_xor(o, d);
+        no |= __shfl_xor(no, d);
+    }
+    if (lane == 0 && (o | no)) {
+        atomicOr(&s->b_or, o);
+        atomicOr(&s->b_nor, no);
+    }
+}
+
+__device__ __forceinline__ void sel2_digit_plan(const Sel2State *s, int &shift, int &width)
+{
+    const unsigned long long diff = s->b_or & s->b_nor;
+    const int hi = diff ? 63 - __clzll((long long)diff) : -1;
+    width = hi + 1 < SEL_RADIX_BITS ? hi + 1 : SEL_RADIX_BITS;
+    shift = hi + 1 - width;
+}
+
+// Digit histogram of an over-long boundary list (no-op otherwise).
+__global__ __launch_bounds__(SEL_THREADS) void sel2_digit_hist_kernel(const uint64_t *__restrict__ blist,
+                                                                      int64_t blist_stride, Sel2State *state,
+                                                                      int32_t *__restrict__ hist1)
+{
+    __shared__ int32_t lh[SEL_BINS];
+    const int seg = blockIdx.y;
+    Sel2State *s = state + seg;
+    const int n = s->n_b;
+    if (n <= SEL_SORT_CAP) return;
+    int shift, width;
+    sel2_digit_plan(s, shift, width);
+    for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS) lh[b] = 0;
+    __syncthreads();
+    const uint64_t *k = blist + (int64_t)seg * blist_stride;
+    for (int64_t i = (int64_t)blockIdx.x * SEL_THREADS + threadIdx.x; i < n; i += (int64_t)gridDim.x * SEL_THREADS)
+        atomicAdd(&lh[digit_of(k[i], shift, width)], 1);
+    __syncthreads();
+    int32_t *gh = hist1 + (int64_t)seg * SEL_BINS;
+    for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS)
+        if (lh[b]) atomicAdd(&gh[b], lh[b]);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        s->shift1 = shift;
+        s->width1 = width;
+    }
+}
+
+// Digit filter of an over-long boundary list (no-op otherwise): smaller digits are selected, the boundary digit
+// goes to blist1.
+__global__ __launch_bounds__(SEL_THREADS) void sel2_digit_filter_kernel(const uint64_t *__restrict__ blist,
+                                                                        int64_t blist_stride, Sel2State *state,
+                                                                        const int32_t *__restrict__ hist1,
+                                                                        uint64_t *__restrict__ out, int64_t out_stride,
+                                                                        uint64_t *__restrict__ blist1,
+                                                                        int64_t blist1_stride)
+{
+    __shared__ int32_t scan[SEL_THREADS];
+    __shared__ int32_t res[2];
+    const int seg = blockIdx.y;
+    Sel2State *s = state + seg;
+    const int n = s->n_b;
+    if (n <= SEL_SORT_CAP) return;
+    int shift, width;
+    sel2_digit_plan(s, shift, width);
+    const int32_t m_rem = s->m_rem;
+    int bstar, before;
+    find_boundary(hist1 + (int64_t)seg * SEL_BINS, m_rem, scan, res, bstar, before);
+    if (blockIdx.x == 0 && threadIdx.x == 0) s->m_rem1 = m_rem - before;
+    const uint64_t *k = blist + (int64_t)seg * blist_stride;
+    uint64_t *my_out = out + (int64_t)seg * out_stride;
+    uint64_t *my_bl = blist1 + (int64_t)seg * blist1_stride;
+    const int lane = threadIdx.x & 63;
+    const int64_t n_round = ((int64_t)n + 63) & ~63ll;
+    for (int64_t i = (int64_t)blockIdx.x * SEL_THREADS + threadIdx.x; i < n_round; i += (int64_t)gridDim.x * SEL_THREADS) {
+        uint64_t key = 0;
+        int cls = 2;
+        if (i < n) {
+            key = k[i];
+            const int d = digit_of(key, shift, width);
+            cls = d < bstar ? 0 : (d == bstar ? 1 : 2);
+        }
+        const unsigned long long b0 = __ballot(cls == 0), b1 = __ballot(cls == 1);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        int base0 = 0, base1 = 0;
+        if (lane == 0) {
+            if (b0) base0 = atomicAdd(&s->n_sure, __popcll(b0));
+            if (b1) base1 = atomicAdd(&s->n_b1, __popcll(b1));
+        }
+        base0 = __shfl(base0, 0);
+        base1 = __shfl(base1, 0);
+        if (cls == 0) my_out[base0 + __popcll(b0 & below)] = key;
+        if (cls == 1) my_bl[base1 + __popcll(b1 & below)] = key;
+    }
+}
+
+// One workgroup per query: finish the boundary list, then append empty-bag candidates in pid order.
+__global__ __launch_bounds__(FIN_THREADS) void sel2_finish_kernel(const uint64_t *__restrict__ blist, int64_t blist_stride,
+                                                                  const uint64_t *__restrict__ blist1,
+                                                                  int64_t blist1_stride, const Sel2State *state,
+                                                                  const uint32_t *__restrict__ emptybits,
+                                                                  int64_t cand_words, int64_t P, int32_t m,
+                                                                  uint64_t *__restrict__ out, int64_t out_stride,
+                                                                  int32_t *__restrict__ out_counts)
+{
+    __shared__ uint64_t sk[SEL_SORT_CAP];
+    __shared__ int32_t h256[256];
+    __shared__ int32_t sh[4];
+    const int seg = blockIdx.x;
+    const Sel2State *s = state + seg;
+    const bool two = s->n_b > SEL_SORT_CAP;
+    const uint64_t *bl = two ? blist1 + (int64_t)seg * blist1_stride : blist + (int64_t)seg * blist_stride;
+    const int nb = two ? s->n_b1 : s->n_b;
+    const int m_rem = two ? s->m_rem1 : s->m_rem;
+    const int n_sure = s->n_sure;
+    const int top_bit = two ? s->shift1 : 64;  // boundary keys agree on every bit at or above this position
+    uint64_t *o = out + (int64_t)seg * out_stride;
+    int total = n_sure + m_rem;
+
+    if (nb <= SEL_SORT_CAP) {
+        const int n2 = next_pow2(nb > 1 ? nb : 1);
+        for (int i = threadIdx.x; i < n2; i += FIN_THREADS) sk[i] = i < nb ? bl[i] : PLAID_KEY_MAX;
+        __syncthreads();
+        lds_bitonic_sort(sk, n2);
+        for (int i = threadIdx.x; i < m_rem; i += FIN_THREADS) o[n_sure + i] = sk[i];
+    } else {
+        // still long (huge tie groups): radix selection over global memory by this one workgroup
+        uint64_t prefix = 0, pmask = 0;
+        int r = m_rem;
+        int pos = top_bit;
+        while (pos > 0 && r > 0) {
+            const int w = pos < 8 ? pos : 8;
+            pos -= w;
+            for (int b = threadIdx.x; b < 256; b += FIN_THREADS) h256[b] = 0;
+            __syncthreads();
+            for (int i = threadIdx.x; i < nb; i += FIN_THREADS) {
+                const uint64_t key = bl[i];
+                if ((key & pmask) == prefix) atomicAdd(&h256[(int)((key >> pos) & ((1u << w) - 1u))], 1);
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                int run = 0, b = 0;
+                for (; b < (1 << w); ++b) {
+                    if (run + h256[b] >= r) break;
+                    run += h256[b];
+                }
+                sh[0] = b;
+                sh[1] = run;
+            }
+            __syncthreads();
+            prefix |= (uint64_t)sh[0] << pos;
+            pmask |= (uint64_t)((1u << w) - 1u) << pos;
+            r -= sh[1];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) sh[2] = 0;
+        __syncthreads();
+        if (m_rem > 0)
+            for (int i = threadIdx.x; i < nb; i += FIN_THREADS) {
+                const uint64_t key = bl[i];
+                if ((key & pmask) <= prefix) o[n_sure + atomicAdd(&sh[2], 1)] = key;
+            }
+    }
+    __syncthreads();
+
+    // empty-bag candidates: ascending pid, until m slots are filled
+    if (total < m) {
+        int32_t *scan = h256;  // reused: FIN_THREADS / 4 words are not enough, so scan in chunks of 256 words
+        const uint32_t *eb = emptybits + (int64_t)seg * cand_words;
+        if (threadIdx.x == 0) sh[3] = total;
+        __syncthreads();
+        for (int64_t w0 = 0; w0 < cand_words; w0 += 256) {
+            const int64_t w = w0 + threadIdx.x;
+            uint32_t v = 0u;
+            if (threadIdx.x < 256 && w < cand_words) {
+                v = eb[w];
+                if ((w + 1) * 32 > P) {
+                    const int64_t keep = P - w * 32;
+                    v = keep <= 0 ? 0u : (keep >= 32 ? v : (v & ((1u << keep) - 1u)));
+                }
+            }
+            const int cnt = __popc(v);
+            if (threadIdx.x < 256) scan[threadIdx.x] = cnt;
+            __syncthreads();
+            for (int d = 1; d < 256; d <<= 1) {
+                int t = 0;
+                if (threadIdx.x < 256 && threadIdx.x >= d) t = scan[threadIdx.x - d];
+                __syncthreads();
+                if (threadIdx.x < 256) scan[threadIdx.x] += t;
+                __syncthreads();
+            }
+            const int start = sh[3];
+            if (threadIdx.x < 256) {
+                int pos = start + scan[threadIdx.x] - cnt;
+                while (v && pos < m) {
+                    const int bit = __ffs(v) - 1;
+                    v &= v - 1;
+                    o[pos++] = plaid_make_key(-INFINITY, (uint32_t)(w * 32 + bit));
+                }
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) sh[3] = start + scan[255] < m ? start + scan[255] : m;
+            __syncthreads();
+            if (sh[3] >= m) break;
+        }
+        total = sh[3];
+    }
+    if (threadIdx.x == 0) out_counts[seg] = total;
+}
+
+void plaid_launch_select2(hipStream_t st, uint64_t *keys2, int64_t key_stride, int nq, int64_t P, int64_t cand_words,
+                          int32_t m, const Stage2Buffers &b, uint64_t *out, int64_t out_stride, int32_t *out_counts)
+{
+    const int gx = blocks_for(P, nq);
+    hipLaunchKernelGGL(sel2_filter_kernel, dim3(gx, nq), dim3(SEL_THREADS), 0, st, keys2, key_stride, b.n_ne, m, b.meta,
+                       b.hist, b.state, out, out_stride, b.blist, P);
+    if (P > SEL_SORT_CAP) {
+        // only a boundary bin longer than SEL_SORT_CAP makes these two do anything; keys2 serves as blist1
+        hipLaunchKernelGGL(sel2_digit_hist_kernel, dim3(gx, nq), dim3(SEL_THREADS), 0, st, b.blist, P, b.state, b.hist1);
+        hipLaunchKernelGGL(sel2_digit_filter_kernel, dim3(gx, nq), dim3(SEL_THREADS), 0, st, b.blist, P, b.state, b.hist1,
+                           out, out_stride, keys2, key_stride);
+    }
+    hipLaunchKernelGGL(sel2_finish_kernel, dim3(nq), dim3(FIN_THREADS), 0, st, b.blist, P, keys2, key_stride, b.state,
+                       b.emptybits, cand_words, P, m, out, out_stride, out_counts);
+}

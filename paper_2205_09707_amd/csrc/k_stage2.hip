@@ -1,0 +1,476 @@
+// Stage 2: centroid interaction with centroid pruning (Eq. 3-5) over every candidate passage.
+//
+// A passage's pruned score is sum_i max_j S_cq[code_j][i] over its tokens whose centroid passes
+// Eq. 5, so it depends only on WHICH surviving centroids occur in the passage.  Few centroids
+// survive t_cs (a small tail of high scores, Section 3.4), so the work splits in two:
+//
+//   streaming part   the candidates' token codes are read once, coalesced, straight from HBM
+//                    (128-byte lines that no candidate touches are skipped); each code is looked
+//                    up in a tiny LDS hash table of the K surviving centroids and turned into a
+//                    slot number; one lane per passage then folds its slots into a K-bit set;
+//   scoring part     the lane takes the column maxima of the <= K surviving rows named by the
+//                    set (rows staged in LDS) and sums the 32 maxima in double, in index order.
+//
+// No matrix D~ is ever stacked (Section 4.5's padding-free idea), nothing is padded, and the
+// order-independent max plus the fixed-order sum make a score a pure function of the passage.
+// Queries with more than S2_MAX_KEPT surviving centroids (very low thresholds) take the gather
+// kernel instead: one wave per passage fetching surviving rows from the L2-resident S_cq.
+//
+// Output of either kernel, per query: ranking keys of the candidates with a non-empty bag
+// (unordered, with a histogram of their bins for the selection that follows) and a bitmap of the
+// candidates whose bag is empty (score -infinity; they rank last, in passage-id order).
+#include "plaid_internal.h"
+
+#include <math.h>
+
+#define S2_THREADS 256
+#define S2W_PASS 64      // passages per wave tile = 2 words of the candidate bitmap
+#ifndef S2W_CAP
+#define S2W_CAP 6144     // tokens a wave stages per round (one byte each)
+#endif
+#define S2_HASH 128      // hash table entries (K <= 63 keeps the load below one half)
+#define S2_TSTRIDE 36    // floats per staged S_cq row (16-byte aligned, rows spread over the banks)
+
+// ------------------------------------------------------------------ per-query table of surviving centroids
+// One workgroup per query.  meta.K = number of centroids with max_i S[c][i] >= t_cs; when K <= S2_MAX_KEPT the
+// ids are listed ascending in kept_ids and their rows copied to T (slot s = 1..K at T[s]); bin_hi / bin_scale
+// define the selection bins from bounds of any non-empty passage's score.
+__global__ __launch_bounds__(1024) void s2_meta_kernel(const float *__restrict__ S, int64_t C,
+                                                       const uint32_t *__restrict__ keepbits, int64_t keep_words,
+                                                       const int32_t *__restrict__ probed, int nprobe, S2Meta *meta,
+                                                       int32_t *__restrict__ kept_ids, float *__restrict__ T)
+{
+    __shared__ int32_t scan[1024];
+    __shared__ int32_t base_s;
+    __shared__ int32_t ids[S2_MAX_KEPT];
+    __shared__ float colmax[QLEN], colmin[QLEN];
+    const int q = blockIdx.x;
+    const float *Sq = S + (int64_t)q * C * QLEN;
+    const uint32_t *kb = keepbits + (int64_t)q * keep_words;
+    if (threadIdx.x == 0) base_s = 0;
+    __syncthreads();
+    for (int64_t w0 = 0; w0 < keep_words; w0 += 1024) {
+        const int64_t w = w0 + threadIdx.x;
+        uint32_t v = w < keep_words ? kb[w] : 0u;
+        const int cnt = __popc(v);
+        scan[threadIdx.x] = cnt;
+        __syncthreads();
+        for (int d = 1; d < 1024; d <<= 1) {
+            const int t = threadIdx.x >= d ? scan[threadIdx.x - d] : 0;
+            __syncthreads();
+            scan[threadIdx.x] += t;
+            __syncthreads();
+        }
+        int pos = base_s + scan[threadIdx.x] - cnt;
+        while (v && pos < S2_MAX_KEPT) {
+            const int b = __ffs(v) - 1;
+            v &= v - 1;
+            ids[pos++] = (int32_t)(w * 32 + b);
+        }
+        __syncthreads();
+        if (threadIdx.x == 1023) base_s += scan[1023];
+        __syncthreads();
+    }
+    int K = base_s;
+    if (C > (1ll << 26) - 2 && K <= S2_MAX_KEPT) K = S2_MAX_KEPT + 1;  // ids must fit the 26-bit field of the hash table
+    float *Tq = T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN;
+    float hi, lo;
+    if (K <= S2_MAX_KEPT) {
+        for (int e = threadIdx.x; e < K * QLEN; e += 1024) {
+            const int s = e >> 5, i = e & 31;
+            Tq[(s + 1) * QLEN + i] = Sq[(int64_t)ids[s] * QLEN + i];
+        }
+        if (threadIdx.x < K) kept_ids[(int64_t)q * S2_MAX_KEPT + threadIdx.x] = ids[threadIdx.x];
+        if (threadIdx.x < QLEN) {
+            float mx = -INFINITY, mn = INFINITY;
+            for (int s = 0; s < K; ++s) {
+                const float v = Sq[(int64_t)ids[s] * QLEN + threadIdx.x];
+                mx = fmaxf(mx, v);
+                mn = fminf(mn, v);
+            }
+            colmax[threadIdx.x] = mx;
+            colmin[threadIdx.x] = mn;
+        }
+    } else if (threadIdx.x < QLEN) {
+        // many survivors: the best centroid of each token bounds every row from above
+        colmax[threadIdx.x] = Sq[(int64_t)probed[((int64_t)q * QLEN + threadIdx.x) * nprobe] * QLEN + threadIdx.x];
+        colmin[threadIdx.x] = -colmax[threadIdx.x] - 1.0f;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double u = 0.0, l = 0.0;
+        for (int i = 0; i < QLEN; ++i) {
+            u += (double)colmax[i];
+            l += (double)colmin[i];
+        }
+        hi = (float)u;
+        lo = (float)l;
+        S2Meta m;
+        m.K = K;
+        m.bin_hi = hi;
+        const float range = hi - lo;
+        m.bin_scale = (K > 0 && range > 0.f && range < INFINITY) ? (float)SEL_BINS / range : 0.f;
+        m.pad = 0;
+        meta[q] = m;
+    }
+}
+
+// ------------------------------------------------------------------ shared tail: emit one wave's 64 passages
+// cand / empty: per lane flags of the passage this lane scored; key valid when cand && !empty.
+__device__ __forceinline__ void s2_emit(bool cand, bool empty, float score, uint32_t pid, const S2Meta &mt,
+                                        uint64_t *__restrict__ out, int32_t *__restrict__ n_ne,
+                                        int32_t *__restrict__ hist, unsigned long long &k_or, unsigned long long &k_nor)
+{
+    const bool live = cand && !empty;
+    const unsigned long long b = __ballot(live);
+    if (b) {
+        const int lane = threadIdx.x & 63;
+        int base = 0;
+        if (lane == 0) base = atomicAdd(n_ne, __popcll(b));
+        base = __shfl(base, 0);
+        if (live) {
+            const uint64_t key = plaid_make_key(score, pid);
+            out[base + __popcll(b & ((1ull << lane) - 1ull))] = key;
+            atomicAdd(&hist[plaid_s2_bin(score, mt.bin_hi, mt.bin_scale)], 1);
+            k_or |= key;
+            k_nor |= ~key;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ streaming kernel (K <= S2_MAX_KEPT)
+// Hash table entry: (centroid id << 6) | slot, 0xFFFFFFFF = free.  Linear probing; at most 63 of 128 entries are
+// used, so a probe sequence meets a free entry after at most 64 steps.
+__device__ __forceinline__ uint32_t s2_lookup(const uint32_t *htab, uint32_t code)
+{
+    uint32_t h = code & (S2_HASH - 1);
+    uint32_t slot = 0u;
+    for (int probe = 0; probe < S2_HASH; ++probe) {
+        const uint32_t e = htab[h];
+        if ((e >> 6) == code) {
+            slot = e & 63u;
+            break;
+        }
+        if (e == 0xFFFFFFFFu) break;
+        h = (h + 1) & (S2_HASH - 1);
+    }
+    return slot;
+}
+
+// LDS traffic between the lanes of one wave needs no workgroup barrier: a wave's LDS operations complete in
+// program order.  This only stops the compiler from moving accesses across the hand-over point.
+__device__ __forceinline__ void s2_wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Every value that steers control flow below is wave-uniform and is forced into scalar registers with
+// readfirstlane, so that all cross-lane operations (__shfl, __ballot) run with the full wave active.
+__device__ __forceinline__ int s2_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Persistent workgroups; wave w of the grid scores the 64-passage tiles w, w + W, w + 2W, ... (lane = passage).
+__global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
+    const int32_t *__restrict__ codes, int64_t N, const int64_t *__restrict__ doc_offsets, int64_t P,
+    const uint32_t *__restrict__ candbits, int64_t cand_words, const S2Meta *__restrict__ meta,
+    const int32_t *__restrict__ kept_ids, const float *__restrict__ T, uint64_t *__restrict__ keys2, int64_t key_stride,
+    int32_t *__restrict__ n_ne, int32_t *__restrict__ hist, uint32_t *__restrict__ emptybits)
+{
+    __shared__ __align__(16) uint8_t stage_all[S2_THREADS / 64][S2W_CAP + 64];
+    __shared__ uint32_t linebits_all[S2_THREADS / 64][(S2W_CAP / 32 + 2 + 31) / 32 + 1];
+    __shared__ uint32_t htab[S2_HASH];
+    __shared__ __align__(16) float Tl[(S2_MAX_KEPT + 1) * S2_TSTRIDE];
+    const int q = blockIdx.y;
+    const int K = s2_uniform(meta[q].K);
+    if (K > S2_MAX_KEPT) return;  // the gather kernel serves this query (uniform for the whole workgroup)
+    const float bin_hi = meta[q].bin_hi, bin_scale = meta[q].bin_scale;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = s2_uniform(tid >> 6);
+    for (int e = tid; e < S2_HASH; e += S2_THREADS) htab[e] = 0xFFFFFFFFu;
+    const float *Tq = T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN;
+    for (int e = tid; e < (K + 1) * QLEN; e += S2_THREADS)
+        Tl[(e >> 5) * S2_TSTRIDE + (e & 31)] = (e >> 5) ? Tq[e] : -INFINITY;
+    __syncthreads();
+    if (tid < K) {
+        const uint32_t code = (uint32_t)kept_ids[(int64_t)q * S2_MAX_KEPT + tid];
+        uint32_t h = code & (S2_HASH - 1);
+        for (int probe = 0; probe < S2_HASH; ++probe) {
+            if (atomicCAS(&htab[h], 0xFFFFFFFFu, (code << 6) | (uint32_t)(tid + 1)) == 0xFFFFFFFFu) break;
+            h = (h + 1) & (S2_HASH - 1);
+        }
+    }
+    __syncthreads();
+
+    uint8_t *stage = stage_all[wave];
+    uint32_t *linebits = linebits_all[wave];
+    const uint32_t *cb = candbits + (int64_t)q * cand_words;
+    uint32_t *eb = emptybits + (int64_t)q * cand_words;
+    uint64_t *keys_out = keys2 + (int64_t)q * key_stride;
+    int32_t *hist_q = hist + (int64_t)q * SEL_BINS;
+    const int ntiles = (int)((P + S2W_PASS - 1) / S2W_PASS);
+    const int nwaves = (int)gridDim.x * (S2_THREADS / 64);
+
+    for (int tile = (int)blockIdx.x * (S2_THREADS / 64) + wave; tile < ntiles; tile += nwaves) {
+        const int64_t p0 = (int64_t)tile * S2W_PASS;
+        const int tp = (int)(P - p0 < S2W_PASS ? P - p0 : S2W_PASS);
+        const int64_t wi = (p0 >> 5) + (lane >> 5);
+        const uint32_t cword = (lane < tp && wi < cand_words) ? cb[wi] : 0u;
+        const bool cand = lane < tp && ((cword >> (lane & 31)) & 1u);
+        const bool any_cand = __ballot(cand) != 0ull;  // uniform
+        uint32_t set_lo = 0, set_hi = 0;  // bit s of (hi:lo) = slot s occurs in my passage; bit 0 = pruned tokens
+
+        if (any_cand) {
+            // token range of my passage relative to the tile's first token
+            const int64_t o0 = doc_offsets[p0];
+            const int64_t o_lane = doc_offsets[p0 + (lane <= tp ? lane : tp)];
+            int64_t r = o_lane - o0;
+            const int my_lo = r > 0x7FFFFFFFll ? 0x7FFFFFFF : (int)r;
+            int my_hi = __shfl_down(my_lo, 1);
+            if (lane == 63) {  // lane 63 has no right neighbour: its end is the tile's end
+                r = doc_offsets[p0 + tp] - o0;
+                my_hi = r > 0x7FFFFFFFll ? 0x7FFFFFFF : (int)r;
+            }
+            if (lane >= tp) my_hi = my_lo;
+
+            int ps = 0;
+            while (ps < tp) {  // ps, fit, pe are uniform; each round advances ps by at least one
+                const int base = s2_uniform(__shfl(my_lo, ps));
+                const int fit = s2_uniform(__popcll(__ballot(lane >= ps && lane < tp && my_hi - base <= S2W_CAP)));
+                if (fit == 0) {
+                    // a single passage longer than the staging buffer: its lane folds it straight from global memory
+                    if (lane == ps && cand) {
+                        for (int64_t j = o0 + my_lo; j < o0 + my_hi; ++j) {
+                            const uint32_t sl = s2_lookup(htab, (uint32_t)codes[j]);
+                            const uint32_t bit = 1u << (sl & 31);
+                            set_lo |= sl < 32 ? bit : 0u;
+                            set_hi |= sl < 32 ? 0u : bit;
+                        }
+                    }
+                    ps += 1;
+                } else {
+                    const int pe = ps + fit;
+                    const int end = s2_uniform(__shfl(my_hi, pe - 1));
+                    const int64_t g0 = o0 + base;   // first token of the round
+                    const int64_t a0 = g0 & ~31ll;  // start of its 128-byte line
+                    const int shift = (int)(g0 - a0);
+                    const int nchunk = (shift + (end - base) + 31) >> 5;
+                    const bool mine = lane >= ps && lane < pe && cand;
+                    if (lane < (nchunk + 31) / 32) linebits[lane] = 0u;
+                    s2_wave_sync();
+                    if (mine && my_hi > my_lo) {
+                        const int c0 = (my_lo - base + shift) >> 5, c1 = (my_hi - 1 - base + shift) >> 5;
+                        for (int c = c0; c <= c1; ++c) atomicOr(&linebits[c >> 5], 1u << (c & 31));
+                    }
+                    s2_wave_sync();
+                    // stage one byte per token: the slot of its centroid (0 = pruned).  Four tokens per lane and
+                    // item, eight items in flight per lane.
+                    const int nitem = nchunk * 8;
+                    uint32_t hit = 0;
+                    for (int it0 = 0; it0 < nitem; it0 += 64 * 8) {  // uniform trip count
+                        int4 v[8];
+                        bool ok[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const int it = it0 + 64 * u + lane;
+                            const int c = it >> 3;
+                            ok[u] = it < nitem && ((linebits[c >> 5] >> (c & 31)) & 1u) && a0 + 4ll * it + 3 < N;
+                            v[u] = make_int4(-1, -1, -1, -1);
+                            if (ok[u]) v[u] = *reinterpret_cast<const int4 *>(codes + a0 + 4ll * it);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            if (ok[u]) {
+                                const uint32_t packed = s2_lookup(htab, (uint32_t)v[u].x) |
+                                                        (s2_lookup(htab, (uint32_t)v[u].y) << 8) |
+                                                        (s2_lookup(htab, (uint32_t)v[u].z) << 16) |
+                                                        (s2_lookup(htab, (uint32_t)v[u].w) << 24);
+                                *reinterpret_cast<uint32_t *>(stage + 4 * (it0 + 64 * u + lane)) = packed;
+                                hit |= packed;
+                            }
+                        }
+                    }
+                    // the one item that straddles the end of the code array (tokens past N belong to no passage)
+                    if (a0 + 4ll * nitem > N) {
+                        const int64_t it = (N - a0) >> 2;
+                        if (lane < 4 && it < nitem && a0 + 4 * it + lane < N) {
+                            const uint32_t sl = s2_lookup(htab, (uint32_t)codes[a0 + 4 * it + lane]);
+                            stage[4 * it + lane] = (uint8_t)sl;
+                            hit |= sl;
+                        }
+                    }
+                    s2_wave_sync();
+                    const bool any_hit = __ballot(hit != 0u) != 0ull;  // uniform
+                    if (any_hit && mine) {
+                        const int v0 = my_lo - base + shift, v1 = my_hi - base + shift;
+                        for (int vv = v0; vv < v1; ++vv) {
+                            const uint32_t sl = stage[vv];
+                            const uint32_t bit = 1u << (sl & 31);
+                            set_lo |= sl < 32 ? bit : 0u;
+                            set_hi |= sl < 32 ? 0u : bit;
+                        }
+                    }
+                    s2_wave_sync();
+                    ps = pe;
+                }
+            }
+        }
+
+        // score: column maxima of the rows in the set, summed over the query tokens in index order
+        const uint64_t members = (((uint64_t)set_hi << 32) | set_lo) & ~1ull;
+        const bool empty = members == 0;
+        float score = -INFINITY;
+        if (cand && !empty) {
+            float acc[QLEN];
+#pragma unroll
+            for (int i = 0; i < QLEN; ++i) acc[i] = -INFINITY;
+            uint64_t rest = members;
+            while (rest) {
+                const int s = __ffsll((long long)rest) - 1;
+                rest &= rest - 1;
+                const float4 *row = reinterpret_cast<const float4 *>(Tl + s * S2_TSTRIDE);
+#pragma unroll
+                for (int g = 0; g < QLEN / 4; ++g) {
+                    const float4 rr = row[g];
+                    acc[4 * g] = fmaxf(acc[4 * g], rr.x);
+                    acc[4 * g + 1] = fmaxf(acc[4 * g + 1], rr.y);
+                    acc[4 * g + 2] = fmaxf(acc[4 * g + 2], rr.z);
+                    acc[4 * g + 3] = fmaxf(acc[4 * g + 3], rr.w);
+                }
+            }
+            double d = 0.0;
+#pragma unroll
+            for (int i = 0; i < QLEN; ++i) d += (double)acc[i];
+            score = (float)d;
+        }
+        // emit (all lanes take part in the ballots)
+        const bool live = cand && !empty;
+        const unsigned long long lb = __ballot(live);
+        if (lb != 0ull) {
+            int basek = 0;
+            if (lane == 0) basek = atomicAdd(n_ne + q, __popcll(lb));
+            basek = __shfl(basek, 0);
+            if (live) {
+                keys_out[basek + __popcll(lb & ((1ull << lane) - 1ull))] = plaid_make_key(score, (uint32_t)(p0 + lane));
+                atomicAdd(&hist_q[plaid_s2_bin(score, bin_hi, bin_scale)], 1);
+            }
+        }
+        const unsigned long long eb64 = __ballot(cand && empty);
+        if (lane == 0) {
+            const int64_t w0 = p0 >> 5;
+            if (w0 < cand_words) eb[w0] = (uint32_t)eb64;
+            if (w0 + 1 < cand_words) eb[w0 + 1] = (uint32_t)(eb64 >> 32);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ gather kernel (K > S2_MAX_KEPT)
+__device__ __forceinline__ float s2_sum32_as_double(float m)
+{
+    double d = (double)m;
+#pragma unroll
+    for (int o = 1; o < 32; o <<= 1) d += __shfl_xor(d, o);
+    return (float)d;
+}
+
+// Pruned score of the passage with tokens [t0, t1): uniform across the wave; `any` tells whether a token survived.
+__device__ __forceinline__ float s2_gather_passage(const float *__restrict__ Sq, const uint32_t *__restrict__ kb,
+                                                   int64_t t0, int64_t t1, const int32_t *__restrict__ codes, int lane,
+                                                   bool &any)
+{
+    const int i = lane & 31, h = lane >> 5;
+    float m = -INFINITY;
+    any = false;
+    for (int64_t base = t0; base < t1; base += 64) {
+        const int cnt = t1 - base < 64 ? (int)(t1 - base) : 64;
+        const int32_t code = lane < cnt ? codes[base + lane] : 0;
+        bool hit = lane < cnt;
+        if (hit) hit = (kb[code >> 5] >> (code & 31)) & 1u;
+        unsigned long long mask = __ballot(hit);
+        any = any || mask != 0;
+        while (mask) {
+            const int j0 = __ffsll((long long)mask) - 1;
+            mask &= mask - 1;
+            int j1 = j0;
+            if (mask) {
+                j1 = __ffsll((long long)mask) - 1;
+                mask &= mask - 1;
+            }
+            const int c = __shfl(code, h ? j1 : j0);
+            m = fmaxf(m, Sq[(int64_t)c * QLEN + i]);
+        }
+    }
+    m = fmaxf(m, __shfl_xor(m, 32));
+    return s2_sum32_as_double(m);
+}
+
+__global__ __launch_bounds__(256) void s2_gather_kernel(const float *__restrict__ S, int64_t C,
+                                                        const uint32_t *__restrict__ keepbits, int64_t keep_words,
+                                                        const uint32_t *__restrict__ candbits, int64_t cand_words,
+                                                        int64_t P, const int64_t *__restrict__ doc_offsets,
+                                                        const int32_t *__restrict__ codes,
+                                                        const S2Meta *__restrict__ meta, uint64_t *__restrict__ keys2,
+                                                        int64_t key_stride, int32_t *__restrict__ n_ne,
+                                                        int32_t *__restrict__ hist, uint32_t *__restrict__ emptybits)
+{
+    const int q = blockIdx.y;
+    const S2Meta mt = meta[q];
+    if (mt.K <= S2_MAX_KEPT) return;  // the streaming kernel serves this query
+    const int lane = threadIdx.x & 63;
+    const float *Sq = S + (int64_t)q * C * QLEN;
+    const uint32_t *kb = keepbits + (int64_t)q * keep_words;
+    const uint32_t *cb = candbits + (int64_t)q * cand_words;
+    uint32_t *eb = emptybits + (int64_t)q * cand_words;
+    unsigned long long k_or = 0, k_nor = 0;
+    for (int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); w < cand_words; w += (int64_t)gridDim.x * 4) {
+        const uint32_t word = cb[w];
+        if (!word) {
+            if (lane == 0) eb[w] = 0u;
+            continue;
+        }
+        const int64_t p0 = w * 32;
+        int64_t off = 0;
+        if (lane <= 32 && p0 + lane <= P) off = doc_offsets[p0 + lane];
+        float my = -INFINITY;
+        bool my_empty = false;
+        uint32_t rest = word;
+        while (rest) {
+            const int b = __ffs(rest) - 1;
+            rest &= rest - 1;
+            const int64_t t0 = __shfl(off, b), t1 = __shfl(off, b + 1);
+            bool any;
+            const float sc = s2_gather_passage(Sq, kb, t0, t1, codes, lane, any);
+            if (lane == b) {
+                my = sc;
+                my_empty = !any;
+            }
+        }
+        const bool cand = lane < 32 && ((word >> lane) & 1u);
+        s2_emit(cand, my_empty, my, (uint32_t)(p0 + lane), mt, keys2 + (int64_t)q * key_stride, n_ne + q,
+                hist + (int64_t)q * SEL_BINS, k_or, k_nor);
+        const unsigned long long e64 = __ballot(cand && my_empty);
+        if (lane == 0) eb[w] = (uint32_t)e64;
+    }
+}
+
+// ------------------------------------------------------------------ host side
+void plaid_launch_stage2(hipStream_t st, const float *S, int64_t C, const uint32_t *keepbits, int64_t keep_words,
+                         const int32_t *probed, int nprobe, const uint32_t *candbits, int64_t cand_words, int64_t P,
+                         int64_t N, const int64_t *doc_offsets, const int32_t *codes, int nq, const Stage2Buffers &b,
+                         uint64_t *keys2, int64_t key_stride)
+{
+    hipLaunchKernelGGL(s2_meta_kernel, dim3(nq), dim3(1024), 0, st, S, C, keepbits, keep_words, probed, nprobe, b.meta,
+                       b.kept_ids, b.T);
+    // persistent workgroups; enough of them to fill the chip for one query, fewer per query in a large chunk
+    const int64_t ntiles = (P + S2W_PASS - 1) / S2W_PASS;
+    int64_t gs = (ntiles + 3) / 4;
+    const int64_t gcap = nq >= 16 ? 96 : (nq >= 4 ? 320 : 1280);
+    if (gs > gcap) gs = gcap;
+    hipLaunchKernelGGL(s2_stream_kernel, dim3((unsigned)gs, nq), dim3(S2_THREADS), 0, st, codes, N, doc_offsets, P, candbits,
+                       cand_words, b.meta, b.kept_ids, b.T, keys2, key_stride, b.n_ne, b.hist, b.emptybits);
+    int64_t gx = (cand_words + 3) / 4;
+    const int64_t cap = nq >= 16 ? 256 : (nq >= 4 ? 1024 : 4096);
+    if (gx > cap) gx = cap;
+    hipLaunchKernelGGL(s2_gather_kernel, dim3((unsigned)gx, nq), dim3(256), 0, st, S, C, keepbits, keep_words, candbits,
+                       cand_words, P, doc_offsets, codes, b.meta, keys2, key_stride, b.n_ne, b.hist, b.emptybits);
+}

@@ -307,8 +307,8 @@ struct Workspace {
     char *zero_base;
     size_t zero_bytes;
     uint32_t *candbits;  // [qc][cand_words]
-    int32_t *n_cand;     // [qc]
-    void *sel2_zero, *sel3_zero, *sel4_zero;
+    Stage2Buffers s2;    // n_ne, hist, hist1, state live in the zeroed region
+    void *sel3_zero, *sel4_zero;
     // everything else
     double *Qd;          // [qc][128][32]
     float *S;            // [qc][C][32]
@@ -327,7 +327,7 @@ struct Workspace {
     uint64_t *keys4;  // [qc][m3]
     uint64_t *topk;   // [qc][kk]
     int32_t *n_out;   // [qc]
-    void *sel2_body, *sel3_body, *sel4_body;
+    void *sel3_body, *sel4_body;
     int64_t keep_words, cand_words;
     int uniq_stride;
     size_t total;
@@ -354,8 +354,10 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     };
     w.zero_base = take(0);
     w.candbits = (uint32_t *)take((size_t)qc * w.cand_words * 4);
-    w.n_cand = (int32_t *)take((size_t)qc * 4);
-    w.sel2_zero = take(plaid_select_zero_bytes(qc));
+    w.s2.n_ne = (int32_t *)take((size_t)qc * 4);
+    w.s2.hist = (int32_t *)take((size_t)qc * SEL_BINS * 4);
+    w.s2.hist1 = (int32_t *)take((size_t)qc * SEL_BINS * 4);
+    w.s2.state = (Sel2State *)take((size_t)qc * sizeof(Sel2State));
     w.sel3_zero = take(plaid_select_zero_bytes(qc));
     w.sel4_zero = take(plaid_select_zero_bytes(qc));
     w.zero_bytes = off;
@@ -368,6 +370,11 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     w.probe_scratch_bytes = plaid_top_nprobe_scratch_bytes(C, qc, pl.nprobe);
     w.probe_scratch = take(w.probe_scratch_bytes);
     w.keys2 = (uint64_t *)take((size_t)qc * P * 8);
+    w.s2.blist = (uint64_t *)take((size_t)qc * P * 8);
+    w.s2.meta = (S2Meta *)take((size_t)qc * sizeof(S2Meta));
+    w.s2.kept_ids = (int32_t *)take((size_t)qc * S2_MAX_KEPT * 4);
+    w.s2.T = (float *)take((size_t)qc * (S2_MAX_KEPT + 1) * QLEN * 4);
+    w.s2.emptybits = (uint32_t *)take((size_t)qc * w.cand_words * 4);
     w.sel2 = (uint64_t *)take((size_t)qc * pl.nd * 8);
     w.n2 = (int32_t *)take((size_t)qc * 4);
     w.keys3 = (uint64_t *)take((size_t)qc * pl.nd * 8);
@@ -376,7 +383,6 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     w.keys4 = (uint64_t *)take((size_t)qc * pl.m3 * 8);
     w.topk = (uint64_t *)take((size_t)qc * pl.kk * 8);
     w.n_out = (int32_t *)take((size_t)qc * 4);
-    w.sel2_body = take(plaid_select_body_bytes(qc, P, pl.nd));
     w.sel3_body = take(plaid_select_body_bytes(qc, pl.nd, pl.m3));
     w.sel4_body = take(plaid_select_body_bytes(qc, pl.m3, pl.kk));
     w.total = off;
@@ -448,7 +454,6 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
         const int n = nq - q0 < qc ? nq - q0 : qc;
         const Workspace w = carve((char *)ix->ws, ix, n, pl);
         const float *Qc = Q + (int64_t)q0 * QLEN * DIM;
-        const SelScratch sc2 = plaid_select_scratch_carve2(w.sel2_zero, w.sel2_body, n, P, pl.nd);
         const SelScratch sc3 = plaid_select_scratch_carve2(w.sel3_zero, w.sel3_body, n, pl.nd, pl.m3);
         const SelScratch sc4 = plaid_select_scratch_carve2(w.sel4_zero, w.sel4_body, n, pl.m3, pl.kk);
         int e = 0;
@@ -469,10 +474,10 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
                                w.cand_words);
         STAMP();
         // stage 2: centroid interaction with pruning over every candidate (Eq. 3-5), keep ndocs
-        plaid_launch_ci_pruned(st, w.S, C, w.keepbits, w.keep_words, w.candbits, w.cand_words, P, ix->doc_offsets,
-                               ix->codes, n, w.keys2, P, w.n_cand, sc2.state);
+        plaid_launch_stage2(st, w.S, C, w.keepbits, w.keep_words, w.probed, nprobe, w.candbits, w.cand_words, P, ix->N,
+                            ix->doc_offsets, ix->codes, n, w.s2, w.keys2, P);
         STAMP();
-        plaid_launch_select(st, w.keys2, P, w.n_cand, n, P, pl.nd, w.sel2, pl.nd, w.n2, 0, sc2, 1);
+        plaid_launch_select2(st, w.keys2, P, n, P, w.cand_words, pl.nd, w.s2, w.sel2, pl.nd, w.n2);
         STAMP();
         // stage 3: centroid interaction without pruning (Eq. 3-4), keep ndocs/4
         plaid_launch_ci_list(st, w.S, C, ix->doc_offsets, ix->codes, n, w.sel2, pl.nd, w.n2, pl.nd, w.keys3, pl.nd);

@@ -97,11 +97,65 @@ void plaid_launch_ivf_union(hipStream_t st, const int32_t *uniq, const int32_t *
                             const int64_t *ivf_offsets, const int32_t *ivf_pids, int nq, uint32_t *candbits,
                             int64_t cand_words);
 
-// Eq. 3-5 over every candidate (stage 2): appends one key per candidate to keys2[q] and counts them.
-void plaid_launch_ci_pruned(hipStream_t st, const float *S, int64_t C, const uint32_t *keepbits, int64_t keep_words,
-                            const uint32_t *candbits, int64_t cand_words, int64_t P, const int64_t *doc_offsets,
-                            const int32_t *codes, int nq, uint64_t *keys2, int64_t key_stride, int32_t *n_cand,
-                            SelState *state);
+// ---------------------------------------------------------------------------------------------
+// Stage 2 (k_stage2.hip) and its selection (k_select.hip)
+// ---------------------------------------------------------------------------------------------
+#define S2_MAX_KEPT 63  // surviving centroids the streaming kernel handles (slots 1..63 of a 64-bit set)
+
+struct S2Meta {        // per query
+    int32_t K;         // number of centroids passing Eq. 5
+    float bin_hi;      // upper bound of any non-empty passage's pruned score
+    float bin_scale;   // SEL_BINS / (upper bound - lower bound), 0 when every key falls into bin 0
+    int32_t pad;
+};
+
+// Per-query state of the stage-2 selection (device memory, 64 bytes, zeroed before each use).
+struct Sel2State {
+    unsigned long long b_or, b_nor;  // OR over the boundary keys / over their complements
+    int32_t n_sure;                  // keys already written to the output
+    int32_t n_b;                     // boundary list after the bin filter
+    int32_t m_rem;                   // keys still to take from it
+    int32_t n_b1;                    // boundary list after the digit filter (only when n_b > SEL_SORT_CAP)
+    int32_t m_rem1;
+    int32_t shift1, width1;          // digit examined by the digit filter
+    int32_t pad[5];
+};
+static_assert(sizeof(Sel2State) == 64, "Sel2State is a 64-byte record");
+
+// Bin of a finite pruned score: 0 for the best scores, SEL_BINS-1 for the worst.  Monotone in the score, so bins
+// never contradict the ranking; producer and selection call this same function on the same inputs.
+__device__ __forceinline__ int plaid_s2_bin(float score, float bin_hi, float bin_scale)
+{
+    float x = (bin_hi - score) * bin_scale;
+    x = fminf(fmaxf(x, 0.f), (float)(SEL_BINS - 1));
+    return (int)x;
+}
+
+struct Stage2Buffers {   // all device pointers, leading dimension = query of the chunk
+    // zeroed before each chunk
+    int32_t *n_ne;       // [nq]            candidates with a non-empty bag (= keys written)
+    int32_t *hist;       // [nq][SEL_BINS]  their bin histogram
+    int32_t *hist1;      // [nq][SEL_BINS]  digit histogram of an over-long boundary list
+    Sel2State *state;    // [nq]
+    // no initialisation needed
+    S2Meta *meta;        // [nq]
+    int32_t *kept_ids;   // [nq][S2_MAX_KEPT]
+    float *T;            // [nq][S2_MAX_KEPT+1][32] rows of the surviving centroids (slot 0 unused)
+    uint32_t *emptybits; // [nq][cand_words] candidates whose bag is empty
+    uint64_t *blist;     // [nq][P] boundary list after the bin filter
+};
+
+// Eq. 3-5 over every candidate: keys of the non-empty candidates (unordered) into keys2[q], their count and bin
+// histogram, and the bitmap of empty candidates.
+void plaid_launch_stage2(hipStream_t st, const float *S, int64_t C, const uint32_t *keepbits, int64_t keep_words,
+                         const int32_t *probed, int nprobe, const uint32_t *candbits, int64_t cand_words, int64_t P,
+                         int64_t N, const int64_t *doc_offsets, const int32_t *codes, int nq, const Stage2Buffers &b,
+                         uint64_t *keys2, int64_t key_stride);
+
+// Best min(m, #candidates) candidates by (score desc, pid asc): from the keys by bin filter (+ digit filter when the
+// boundary bin is over-long), then from the empty candidates in pid order.  keys2 is overwritten (scratch).
+void plaid_launch_select2(hipStream_t st, uint64_t *keys2, int64_t key_stride, int nq, int64_t P, int64_t cand_words,
+                          int32_t m, const Stage2Buffers &b, uint64_t *out, int64_t out_stride, int32_t *out_counts);
 
 // Eq. 3-4 over a key list (stage 3): out_keys[q][j] is the key of the passage of in_keys[q][j].
 void plaid_launch_ci_list(hipStream_t st, const float *S, int64_t C, const int64_t *doc_offsets, const int32_t *codes,

@@ -28,7 +28,9 @@
 #ifndef S2W_CAP
 #define S2W_CAP 6144     // tokens a wave stages per round (one byte each)
 #endif
-#define S2_HASH 128      // hash table entries (K <= 63 keeps the load below one half)
+#define S2_HASH 1024     // entries of the survivor table: direct-mapped, collision-free by choice of hash
+#define S2_NHASH 24      // hash functions tried per query
+#define S2_SHIFT0 5      // the first one shifts by 5 bits
 #define S2_TSTRIDE 36    // floats per staged S_cq row (16-byte aligned, rows spread over the banks)
 
 // ------------------------------------------------------------------ per-query table of surviving centroids
@@ -72,7 +74,32 @@ __global__ __launch_bounds__(1024) void s2_meta_kernel(const float *__restrict__
         __syncthreads();
     }
     int K = base_s;
-    if (C > (1ll << 26) - 2 && K <= S2_MAX_KEPT) K = S2_MAX_KEPT + 1;  // ids must fit the 26-bit field of the hash table
+    if (C > (1ll << 26) - 2 && K <= S2_MAX_KEPT) K = S2_MAX_KEPT + 1;  // ids must fit the 26-bit field of a table entry
+    // pick a hash h(c) = (c ^ (c >> sh)) & (S2_HASH-1) that maps the survivors to distinct entries, so that a lookup
+    // is one probe; thread t tries shift S2_SHIFT0 + t on a private bitmap.  No such shift (very rare): gather kernel.
+    __shared__ uint32_t trial[S2_NHASH][S2_HASH / 32];
+    __shared__ int32_t chosen;
+    if (threadIdx.x == 0) chosen = -1;
+    if (threadIdx.x < S2_NHASH)
+        for (int w = 0; w < S2_HASH / 32; ++w) trial[threadIdx.x][w] = 0u;
+    __syncthreads();
+    if (K <= S2_MAX_KEPT) {
+        bool ok = threadIdx.x < S2_NHASH;
+        if (ok) {
+            const int sh = S2_SHIFT0 + threadIdx.x;
+            for (int s = 0; s < K; ++s) {
+                const uint32_t c = (uint32_t)ids[s];
+                const uint32_t h = (c ^ (c >> sh)) & (S2_HASH - 1);
+                const uint32_t bit = 1u << (h & 31);
+                if (trial[threadIdx.x][h >> 5] & bit) ok = false;
+                trial[threadIdx.x][h >> 5] |= bit;
+            }
+        }
+        if (ok) atomicMax(&chosen, S2_NHASH - 1 - (int)threadIdx.x);  // smallest successful shift wins
+        __syncthreads();
+        if (chosen < 0) K = S2_MAX_KEPT + 1;
+    }
+    const int hash_shift = (K <= S2_MAX_KEPT) ? S2_SHIFT0 + (S2_NHASH - 1 - chosen) : 0;
     float *Tq = T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN;
     float hi, lo;
     if (K <= S2_MAX_KEPT) {
@@ -110,7 +137,7 @@ __global__ __launch_bounds__(1024) void s2_meta_kernel(const float *__restrict__
         m.bin_hi = hi;
         const float range = hi - lo;
         m.bin_scale = (K > 0 && range > 0.f && range < INFINITY) ? (float)SEL_BINS / range : 0.f;
-        m.pad = 0;
+        m.hash_shift = hash_shift;
         meta[q] = m;
     }
 }
@@ -139,22 +166,12 @@ __device__ __forceinline__ void s2_emit(bool cand, bool empty, float score, uint
 }
 
 // ------------------------------------------------------------------ streaming kernel (K <= S2_MAX_KEPT)
-// Hash table entry: (centroid id << 6) | slot, 0xFFFFFFFF = free.  Linear probing; at most 63 of 128 entries are
-// used, so a probe sequence meets a free entry after at most 64 steps.
-__device__ __forceinline__ uint32_t s2_lookup(const uint32_t *htab, uint32_t code)
+// Survivor table entry: (centroid id << 6) | slot, 0xFFFFFFFF = free.  The hash is collision-free on the survivors,
+// so one probe decides: returns the slot (1..63) of a surviving centroid, 0 otherwise.
+__device__ __forceinline__ uint32_t s2_lookup(const uint32_t *htab, uint32_t code, int hash_shift)
 {
-    uint32_t h = code & (S2_HASH - 1);
-    uint32_t slot = 0u;
-    for (int probe = 0; probe < S2_HASH; ++probe) {
-        const uint32_t e = htab[h];
-        if ((e >> 6) == code) {
-            slot = e & 63u;
-            break;
-        }
-        if (e == 0xFFFFFFFFu) break;
-        h = (h + 1) & (S2_HASH - 1);
-    }
-    return slot;
+    const uint32_t e = htab[(code ^ (code >> hash_shift)) & (S2_HASH - 1)] ^ (code << 6);
+    return e < 64u ? e : 0u;
 }
 
 // LDS traffic between the lanes of one wave needs no workgroup barrier: a wave's LDS operations complete in
@@ -185,6 +202,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
     const int K = s2_uniform(meta[q].K);
     if (K > S2_MAX_KEPT) return;  // the gather kernel serves this query (uniform for the whole workgroup)
     const float bin_hi = meta[q].bin_hi, bin_scale = meta[q].bin_scale;
+    const int hsh = s2_uniform(meta[q].hash_shift);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = s2_uniform(tid >> 6);
     for (int e = tid; e < S2_HASH; e += S2_THREADS) htab[e] = 0xFFFFFFFFu;
@@ -194,11 +212,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
     __syncthreads();
     if (tid < K) {
         const uint32_t code = (uint32_t)kept_ids[(int64_t)q * S2_MAX_KEPT + tid];
-        uint32_t h = code & (S2_HASH - 1);
-        for (int probe = 0; probe < S2_HASH; ++probe) {
-            if (atomicCAS(&htab[h], 0xFFFFFFFFu, (code << 6) | (uint32_t)(tid + 1)) == 0xFFFFFFFFu) break;
-            h = (h + 1) & (S2_HASH - 1);
-        }
+        htab[(code ^ (code >> hsh)) & (S2_HASH - 1)] = (code << 6) | (uint32_t)(tid + 1);
     }
     __syncthreads();
 
@@ -218,7 +232,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
         const uint32_t cword = (lane < tp && wi < cand_words) ? cb[wi] : 0u;
         const bool cand = lane < tp && ((cword >> (lane & 31)) & 1u);
         const bool any_cand = __ballot(cand) != 0ull;  // uniform
-        uint32_t set_lo = 0, set_hi = 0;  // bit s of (hi:lo) = slot s occurs in my passage; bit 0 = pruned tokens
+        uint64_t set = 0;  // bit s = slot s occurs in my passage; bit 0 collects the pruned tokens
 
         if (any_cand) {
             // token range of my passage relative to the tile's first token
@@ -241,10 +255,8 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
                     // a single passage longer than the staging buffer: its lane folds it straight from global memory
                     if (lane == ps && cand) {
                         for (int64_t j = o0 + my_lo; j < o0 + my_hi; ++j) {
-                            const uint32_t sl = s2_lookup(htab, (uint32_t)codes[j]);
-                            const uint32_t bit = 1u << (sl & 31);
-                            set_lo |= sl < 32 ? bit : 0u;
-                            set_hi |= sl < 32 ? 0u : bit;
+                            const uint32_t sl = s2_lookup(htab, (uint32_t)codes[j], hsh);
+                            set |= 1ull << sl;
                         }
                     }
                     ps += 1;
@@ -281,10 +293,10 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
 #pragma unroll
                         for (int u = 0; u < 8; ++u) {
                             if (ok[u]) {
-                                const uint32_t packed = s2_lookup(htab, (uint32_t)v[u].x) |
-                                                        (s2_lookup(htab, (uint32_t)v[u].y) << 8) |
-                                                        (s2_lookup(htab, (uint32_t)v[u].z) << 16) |
-                                                        (s2_lookup(htab, (uint32_t)v[u].w) << 24);
+                                const uint32_t packed = s2_lookup(htab, (uint32_t)v[u].x, hsh) |
+                                                        (s2_lookup(htab, (uint32_t)v[u].y, hsh) << 8) |
+                                                        (s2_lookup(htab, (uint32_t)v[u].z, hsh) << 16) |
+                                                        (s2_lookup(htab, (uint32_t)v[u].w, hsh) << 24);
                                 *reinterpret_cast<uint32_t *>(stage + 4 * (it0 + 64 * u + lane)) = packed;
                                 hit |= packed;
                             }
@@ -294,7 +306,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
                     if (a0 + 4ll * nitem > N) {
                         const int64_t it = (N - a0) >> 2;
                         if (lane < 4 && it < nitem && a0 + 4 * it + lane < N) {
-                            const uint32_t sl = s2_lookup(htab, (uint32_t)codes[a0 + 4 * it + lane]);
+                            const uint32_t sl = s2_lookup(htab, (uint32_t)codes[a0 + 4 * it + lane], hsh);
                             stage[4 * it + lane] = (uint8_t)sl;
                             hit |= sl;
                         }
@@ -305,9 +317,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
                         const int v0 = my_lo - base + shift, v1 = my_hi - base + shift;
                         for (int vv = v0; vv < v1; ++vv) {
                             const uint32_t sl = stage[vv];
-                            const uint32_t bit = 1u << (sl & 31);
-                            set_lo |= sl < 32 ? bit : 0u;
-                            set_hi |= sl < 32 ? 0u : bit;
+                            set |= 1ull << sl;
                         }
                     }
                     s2_wave_sync();
@@ -317,7 +327,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
         }
 
         // score: column maxima of the rows in the set, summed over the query tokens in index order
-        const uint64_t members = (((uint64_t)set_hi << 32) | set_lo) & ~1ull;
+        const uint64_t members = set & ~1ull;
         const bool empty = members == 0;
         float score = -INFINITY;
         if (cand && !empty) {

@@ -106,7 +106,7 @@ struct S2Meta {        // per query
     int32_t K;         // number of centroids passing Eq. 5
     float bin_hi;      // upper bound of any non-empty passage's pruned score
     float bin_scale;   // SEL_BINS / (upper bound - lower bound), 0 when every key falls into bin 0
-    int32_t pad;
+    int32_t hash_shift;  // hash of the streaming kernel's survivor table
 };
 
 // Per-query state of the stage-2 selection (device memory, 64 bytes, zeroed before each use).

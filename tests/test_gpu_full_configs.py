@@ -1,0 +1,75 @@
+"""GPU parity at the benchmark configurations' full sizes, in the launch configuration bench.py times.
+
+The index is generated on the GPU (seeded), handed to the library without a copy, and searched (a) with the
+whole query batch in one call and (b) one query per call; a sample of queries is then recomputed by the CPU
+oracle from host copies of the same buffers and compared stage by stage.  cfg4 / cfg5 (0.6 and 1.4 billion
+embeddings) take minutes to generate and are run only when PLAID_BIG_CONFIGS=1.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from synth import get_config, make_workload
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+BIG = os.environ.get("PLAID_BIG_CONFIGS", "0") == "1"
+
+
+def _run(cfg_name, noise, n_sample, n_dump):
+    import paper_2205_09707_amd as pl
+    pl.load_library()
+    cfg = get_config(cfg_name)
+    dev = torch.device("cuda:0")
+    print(f"[full] generating {cfg_name}/{noise}", flush=True)
+    w = make_workload(cfg, device=dev, noise=noise)
+    names = ("centroids", "doc_offsets", "codes", "residuals", "bucket_weights", "ivf_offsets", "ivf_pids")
+    gidx = pl.plaid_index_from_view({n: getattr(w, n) for n in names}, cfg.nbits, device=0, copy=False)
+    params = (cfg.nprobe, cfg.t_cs, cfg.ndocs, cfg.k)
+    Q = w.queries
+    nq = Q.shape[0]
+    try:
+        print(f"[full] {cfg_name}/{noise}: N={w.N}, batch search of {nq} queries", flush=True)
+        ids, sc = pl.plaid_search(gidx, Q, *params)
+        torch.cuda.synchronize()
+        rng = np.random.default_rng(cfg.query_seed)
+        sample = sorted(rng.choice(nq, size=min(n_sample, nq), replace=False).tolist())
+        # (b) one query per call must give the same bits as the batch
+        for q in sample:
+            i1, s1 = pl.plaid_search(gidx, Q[q:q + 1], *params)
+            assert torch.equal(i1[0], ids[q]) and torch.equal(s1[0], sc[q]), f"batch-1 differs from batch at q{q}"
+        ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+        ix = orc.Index(w.numpy(), cfg.nbits)
+        Qh = Q.cpu().numpy()
+        identical = 0
+        for n, q in enumerate(sample):
+            g = dict(ids=ids[q], scores=sc[q])
+            if n < n_dump:   # stage-by-stage dumps for a few queries (S_cq alone is 128*C bytes per query)
+                out = pu.run_gpu_debug(pl, gidx, Q[q:q + 1], params)
+                g = pu.slice_query(out, 0)
+                assert np.array_equal(g["ids"], ids[q]) and np.array_equal(pu.bits(g["scores"]), pu.bits(sc[q]))
+            print(f"[full] {cfg_name}/{noise} q{q} vs oracle", flush=True)
+            identical += bool(pu.compare_query(ix, Qh[q], params, g, ctx=f"{cfg_name}/{noise} q{q}"))
+        print(f"[full] {cfg_name}/{noise}: {identical}/{len(sample)} sampled queries with id lists identical to the oracle's")
+        assert identical >= len(sample) - 1
+    finally:
+        pl.plaid_index_free(gidx)
+        del w
+        torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("cfg_name,noise", [("cfg2", "literal"), ("cfg2", "calibrated"), ("cfg3", "literal"),
+                                            ("cfg3", "calibrated")])
+def test_mid_configs(cfg_name, noise):
+    _run(cfg_name, noise, n_sample=12, n_dump=3)
+
+
+@pytest.mark.skipif(not BIG, reason="set PLAID_BIG_CONFIGS=1: generating 0.6-1.4 billion embeddings takes minutes")
+@pytest.mark.parametrize("cfg_name,noise", [("cfg4", "literal"), ("cfg4", "calibrated"), ("cfg5", "literal"),
+                                            ("cfg5", "calibrated")])
+def test_big_configs(cfg_name, noise):
+    _run(cfg_name, noise, n_sample=4, n_dump=1)

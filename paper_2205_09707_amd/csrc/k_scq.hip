@@ -1,120 +1,462 @@
-// Query-centroid scores S_cq = C . Q^T (Eq. 2) with the centroid pruning map of Eq. 5 fused in.
+// Stage 1 in one kernel: query-centroid scores S_cq = C . Q^T (Eq. 2), the centroid pruning map of
+// Eq. 5, the nprobe best centroids of every query token (Section 4.1) and the table of surviving
+// centroids that stage 2 consumes.
 //
 // Every later decision of the pipeline (which centroids are probed, which survive t_cs, which
-// passages make the ndocs and ndocs/4 cuts) is a comparison of these values or of sums of them,
+// passages make the ndocs and ndocs/4 cuts) is a comparison of S_cq values or of sums of them,
 // so they are computed the way the definition reads: each S[c][i] is the dot product accumulated
 // in double over the dimensions in index order, rounded once to fp32.  A product of two fp32
 // values is exact in double, so a chain of fused multiply-adds in that order gives the same bits
 // as "multiply, then add" on any machine -- the scores carry no accumulation-order freedom.
 //
-// Mapping: one lane owns one centroid row and keeps TOK double accumulators (one per query
-// token of its token group); the query, pre-converted to double and transposed to [dim][32], is
-// uniform across the wave and is fetched through the scalar unit, so the inner loop is one
-// v_fma_f64 per (dimension, token) with no per-lane operand traffic besides the centroid row.
-// Output row c of S is the 128-byte record that a token's centroid id later gathers.
+// Mapping: a workgroup of eight waves owns 64 centroid rows, staged once in LDS with coalesced
+// loads; wave g computes query tokens 4g..4g+3 for all 64 rows (lane = centroid, four double
+// accumulators).  The query, pre-converted to double and laid out [token group][dim][4], is
+// uniform across a wave and is fetched through the scalar unit, so the inner loop is one
+// v_fma_f64 per (dimension, token) whose only per-lane operand is the LDS-resident centroid row.
+// The 64x32 tile of results then yields, still in LDS, the row maxima (pruning bits) and each
+// token's best centroids of the tile; a one-workgroup-per-query kernel merges the tiles' lists
+// into the probes, their duplicate-free union, and the survivor table.
 #include "plaid_internal.h"
 
-// Qd[q][t][i] = (double) Q[q][i][t]
-__global__ void scq_prepare_kernel(const float *__restrict__ Q, double *__restrict__ Qd)
+#include <math.h>
+
+
+#define SCQ_THREADS 512
+#define SCQ_ROWS 64
+#define SCQ_HALF 64      // dimensions staged at a time
+#define SCQ_RSTRIDE 68   // floats per staged half row: 16-byte aligned, consecutive rows 4 banks apart
+#define SCQ_SSTRIDE 33   // floats per row of the result tile (conflict-free column and row walks)
+#define SCQ_GROUPS 8     // token groups = waves per workgroup
+#define SCQ_TOK 4        // query tokens per wave
+#define TAIL_THREADS 1024
+#define TAIL_LANES 32     // lanes of the tail kernel that share one query token
+
+// Clears the workspace region that must start at zero and lays out the queries for scq_fused_kernel:
+// Qd[q][g][t][u] = (double) Q[q][4g + u][t].
+__global__ __launch_bounds__(256) void stage1_prep_kernel(const float *__restrict__ Q, double *__restrict__ Qd, int nq,
+                                                          uint32_t *__restrict__ zero, int64_t zero_words)
 {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < zero_words; i += (int64_t)gridDim.x * blockDim.x)
+        zero[i] = 0u;
+    for (int q = blockIdx.x; q < nq; q += gridDim.x)
+        for (int e = threadIdx.x; e < QLEN * DIM; e += blockDim.x) {
+            const int u = e & 3, t = (e >> 2) & (DIM - 1), g = e >> 9;
+            Qd[(int64_t)q * QLEN * DIM + e] = (double)Q[(int64_t)q * QLEN * DIM + (4 * g + u) * DIM + t];
+        }
+}
+
+template <int NP>
+__device__ __forceinline__ void scq_insert_key(uint64_t (&best)[NP], uint64_t key)
+{
+    if (key < best[NP - 1]) {
+#pragma unroll
+        for (int j = NP - 1; j >= 0; --j) {
+            if (key < best[j]) {
+                if (j + 1 < NP) best[j + 1] = best[j];
+                best[j] = key;
+            }
+        }
+    }
+}
+
+struct Stage1Out {          // per-query outputs of the tail (device pointers, leading dimension = query)
+    int32_t *probed;        // [nq][32][nprobe] best first
+    int32_t *uniq;          // [nq][uniq_stride] ascending distinct probed centroids
+    int32_t *n_uniq;        // [nq]
+    int uniq_stride;
+    S2Meta *meta;           // [nq]
+    int32_t *kept_ids;      // [nq][S2_MAX_KEPT]
+    float *T;               // [nq][S2_MAX_KEPT + 1][32]
+};
+
+// Survivor table of one query (runs in one workgroup, all of whose threads call it).  K = number of centroids
+// passing Eq. 5; when K <= S2_MAX_KEPT their ids are listed ascending, their rows copied to T (slot s at T[s],
+// s = 1..K), a collision-free hash shift is chosen for stage 2's table, and bin_hi / bin_scale are set from bounds
+// of any non-empty passage's pruned score.  top1[i] = best centroid of token i (gives the bounds when K is large).
+__device__ void stage1_survivor_table(const float *__restrict__ Sq, int64_t C, const uint32_t *__restrict__ kb,
+                                      int64_t keep_words, const int32_t *top1, S2Meta *meta_q,
+                                      int32_t *__restrict__ kept_ids_q, float *__restrict__ Tq, int32_t *scan /*[waves]*/,
+                                      int32_t *ids /*[S2_MAX_KEPT + 1]*/, uint32_t *trial /*[S2_NHASH][S2_HASH / 32]*/,
+                                      float *colmm /*[2][32]*/, int32_t *misc /*[2]*/)
+{
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    if (tid == 0) {
+        misc[0] = 0;   // running count of survivors
+        misc[1] = -1;  // chosen hash trial
+    }
+    for (int e = tid; e < S2_NHASH * (S2_HASH / 32); e += nthreads) trial[e] = 0u;
+    __syncthreads();
+    // survivors in ascending id order: thread t owns the contiguous words [t * per, (t + 1) * per); positions come from
+    // a wave-level prefix sum of the per-thread counts plus the wave totals (scan[wave])
+    {
+        const int64_t per = (keep_words + nthreads - 1) / nthreads;
+        const int64_t wa = (int64_t)tid * per, wb = wa + per < keep_words ? wa + per : keep_words;
+        int cnt = 0;
+        for (int64_t w = wa; w < wb; ++w) cnt += __popc(kb[w]);
+        int incl = cnt;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int t = __shfl_up(incl, d);
+            if ((tid & 63) >= d) incl += t;
+        }
+        if ((tid & 63) == 63) scan[tid >> 6] = incl;
+        __syncthreads();
+        int start = incl - cnt;
+        for (int wv = 0; wv < (tid >> 6); ++wv) start += scan[wv];
+        int pos = start;
+        for (int64_t w = wa; w < wb && pos < S2_MAX_KEPT; ++w) {
+            uint32_t v = kb[w];
+            while (v && pos < S2_MAX_KEPT) {
+                const int b = __ffs(v) - 1;
+                v &= v - 1;
+                ids[pos++] = (int32_t)(w * 32 + b);
+            }
+        }
+        if (tid == nthreads - 1) misc[0] = start + cnt;  // total number of survivors
+        __syncthreads();
+    }
+    int K = misc[0];
+    if (C > (1ll << 26) - 2 && K <= S2_MAX_KEPT) K = S2_MAX_KEPT + 1;  // ids must fit the 26-bit field of a table entry
+    // a hash h(c) = (c ^ (c >> sh)) & (S2_HASH - 1) that maps the survivors to distinct entries makes a lookup one
+    // probe; thread t tries shift S2_SHIFT0 + t on a private bitmap.  No such shift (very rare): gather kernel.
+    if (K <= S2_MAX_KEPT) {
+        bool ok = tid < S2_NHASH;
+        if (ok) {
+            const int sh = S2_SHIFT0 + tid;
+            uint32_t *mine = trial + tid * (S2_HASH / 32);
+            for (int s = 0; s < K; ++s) {
+                const uint32_t c = (uint32_t)ids[s];
+                const uint32_t h = (c ^ (c >> sh)) & (S2_HASH - 1);
+                const uint32_t bit = 1u << (h & 31);
+                if (mine[h >> 5] & bit) ok = false;
+                mine[h >> 5] |= bit;
+            }
+        }
+        if (ok) atomicMax(&misc[1], S2_NHASH - 1 - tid);  // smallest successful shift wins
+        __syncthreads();
+        if (misc[1] < 0) K = S2_MAX_KEPT + 1;
+    }
+    const int hash_shift = (K <= S2_MAX_KEPT) ? S2_SHIFT0 + (S2_NHASH - 1 - misc[1]) : 0;
+    if (K <= S2_MAX_KEPT) {
+        for (int e = tid; e < K * QLEN; e += nthreads)
+            Tq[QLEN + e] = Sq[(int64_t)ids[e >> 5] * QLEN + (e & 31)];
+        if (tid < K) kept_ids_q[tid] = ids[tid];
+        if (tid < QLEN) {
+            float mx = -INFINITY, mn = INFINITY;
+            for (int s = 0; s < K; ++s) {
+                const float v = Sq[(int64_t)ids[s] * QLEN + tid];
+                mx = fmaxf(mx, v);
+                mn = fminf(mn, v);
+            }
+            colmm[tid] = mx;
+            colmm[QLEN + tid] = mn;
+        }
+    } else if (tid < QLEN) {
+        // many survivors: the best centroid of each token bounds every row from above
+        const float mx = Sq[(int64_t)top1[tid] * QLEN + tid];
+        colmm[tid] = mx;
+        colmm[QLEN + tid] = -mx - 1.0f;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double u = 0.0, l = 0.0;
+        for (int i = 0; i < QLEN; ++i) {
+            u += (double)colmm[i];
+            l += (double)colmm[QLEN + i];
+        }
+        S2Meta m;
+        m.K = K;
+        m.bin_hi = (float)u;
+        const float range = (float)u - (float)l;
+        m.bin_scale = (K > 0 && range > 0.f && range < INFINITY) ? (float)SEL_BINS / range : 0.f;
+        m.hash_shift = hash_shift;
+        *meta_q = m;
+    }
+}
+
+// Standalone form for the general top-nprobe path (nprobe > 8), where the probes come from the generic selection.
+__global__ __launch_bounds__(512) void stage1_survivor_kernel(const float *__restrict__ S, int64_t C,
+                                                              const uint32_t *__restrict__ keepbits, int64_t keep_words,
+                                                              const int32_t *__restrict__ probed, int nprobe, Stage1Out o)
+{
+    __shared__ int32_t scan[512];
+    __shared__ int32_t ids[S2_MAX_KEPT + 1];
+    __shared__ uint32_t trial[S2_NHASH * (S2_HASH / 32)];
+    __shared__ float colmm[2 * QLEN];
+    __shared__ int32_t misc[2];
+    __shared__ int32_t top1[QLEN];
     const int q = blockIdx.x;
-    for (int e = threadIdx.x; e < QLEN * DIM; e += blockDim.x) {
-        const int t = e >> 5, i = e & 31;
-        Qd[(int64_t)q * QLEN * DIM + e] = (double)Q[(int64_t)q * QLEN * DIM + i * DIM + t];
-    }
+    if (threadIdx.x < QLEN) top1[threadIdx.x] = probed[((int64_t)q * QLEN + threadIdx.x) * nprobe];
+    __syncthreads();
+    stage1_survivor_table(S + (int64_t)q * C * QLEN, C, keepbits + (int64_t)q * keep_words, keep_words, top1, o.meta + q,
+                          o.kept_ids + (int64_t)q * S2_MAX_KEPT, o.T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN, scan, ids, trial,
+                          colmm, misc);
 }
 
-template <int TOK>  // query tokens per wave: 16 or 8 (smaller = more waves when C is small)
-__global__ __launch_bounds__(256) void scq_kernel(const float *__restrict__ Cm, int64_t C, const double *__restrict__ Qd,
-                                                  float *__restrict__ S)
+// NP = capacity of the per-token candidate lists (1, 2, 4 or 8 >= nprobe); NP = 0: scores and pruning bits only.
+template <int NP>
+__global__ __launch_bounds__(SCQ_THREADS) void scq_fused_kernel(const float *__restrict__ Cm, int64_t C,
+                                                                const double *__restrict__ Qd, float t_cs,
+                                                                float *__restrict__ S, uint32_t *__restrict__ keepbits,
+                                                                int64_t keep_words, uint64_t *__restrict__ partial)
 {
-    constexpr int GROUPS = QLEN / TOK;
+    constexpr int NPK = NP > 0 ? NP : 1;
+    // one LDS arena: half of the centroid tile (64 dimensions) at a time during the contraction; afterwards the 64x32
+    // result tile and the lists
+    constexpr int ARENA_FLOATS = SCQ_ROWS * SCQ_RSTRIDE > SCQ_ROWS * SCQ_SSTRIDE + 8 * QLEN * NPK * 2
+                                     ? SCQ_ROWS * SCQ_RSTRIDE
+                                     : SCQ_ROWS * SCQ_SSTRIDE + 8 * QLEN * NPK * 2;
+    __shared__ __align__(16) float arena[ARENA_FLOATS];
+    float *tile = arena;                                                         // [64][SCQ_SSTRIDE]
+    uint64_t *lk = reinterpret_cast<uint64_t *>(arena + SCQ_ROWS * SCQ_SSTRIDE);  // [8][32][NPK], 8-byte aligned
+    static_assert((SCQ_ROWS * SCQ_SSTRIDE) % 2 == 0, "list area must be 8-byte aligned");
     const int q = blockIdx.y;
-    const int lane = threadIdx.x & 63;
-    // wave-uniform, so that the query operands below are fetched by scalar loads
-    const int64_t wave = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t c = (wave / GROUPS) * 64 + lane;
-    const int i0 = (int)(wave % GROUPS) * TOK;
-    if ((wave / GROUPS) * 64 >= C) return;
-    const double *__restrict__ qd = Qd + (int64_t)q * QLEN * DIM + i0;
-    const float *__restrict__ row = Cm + (c < C ? c : C - 1) * DIM;
-    double acc[TOK];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int g = __builtin_amdgcn_readfirstlane(tid >> 6);  // token group of this wave (uniform -> scalar loads of Qd)
+    const int64_t c0 = (int64_t)blockIdx.x * SCQ_ROWS;
+    const int nrows = (int)(C - c0 < SCQ_ROWS ? C - c0 : SCQ_ROWS);
+
+    // staging: a half tile is 64 rows x 64 dims = 1024 float4, two per thread; 256-byte row halves read contiguously.
+    // The second half is requested before the first is multiplied, so only the first load's latency is exposed.
+    const int r0 = tid >> 4, c4 = tid & 15;  // this thread stages rows r0 and r0 + 32, float4 column c4
+    float4 pre[2];
 #pragma unroll
-    for (int i = 0; i < TOK; ++i) acc[i] = 0.0;
-    // the row is consumed in four 32-dimension chunks; chunk k+1 is in flight while chunk k is multiplied
-    float4 cur[8], nxt[8];
-#pragma unroll
-    for (int v = 0; v < 8; ++v) cur[v] = *reinterpret_cast<const float4 *>(row + 4 * v);
+    for (int k = 0; k < 2; ++k) {
+        const int r = r0 + 32 * k;
+        pre[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r < nrows) pre[k] = *reinterpret_cast<const float4 *>(Cm + (c0 + r) * DIM + 4 * c4);
+    }
+    const double *__restrict__ qd = Qd + ((int64_t)q * SCQ_GROUPS + g) * DIM * SCQ_TOK;
+    const float4 *row = reinterpret_cast<const float4 *>(arena + lane * SCQ_RSTRIDE);
+    double acc[SCQ_TOK] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll 1
-    for (int tb = 0; tb < DIM; tb += 32) {
-        const int tn = tb + 32 < DIM ? tb + 32 : tb;  // the last round reloads its own chunk (unused)
+    for (int half = 0; half < DIM / SCQ_HALF; ++half) {
 #pragma unroll
-        for (int v = 0; v < 8; ++v) nxt[v] = *reinterpret_cast<const float4 *>(row + tn + 4 * v);
+        for (int k = 0; k < 2; ++k)
+            *reinterpret_cast<float4 *>(arena + (r0 + 32 * k) * SCQ_RSTRIDE + 4 * c4) = pre[k];
+        __syncthreads();
+        if (half + 1 < DIM / SCQ_HALF) {
 #pragma unroll
-        for (int v = 0; v < 8; ++v) {
-            const double a[4] = {(double)cur[v].x, (double)cur[v].y, (double)cur[v].z, (double)cur[v].w};
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int i = 0; i < TOK; ++i) acc[i] = fma(a[u], qd[(tb + 4 * v + u) * QLEN + i], acc[i]);
+            for (int k = 0; k < 2; ++k) {
+                const int r = r0 + 32 * k;
+                if (r < nrows) pre[k] = *reinterpret_cast<const float4 *>(Cm + (c0 + r) * DIM + SCQ_HALF * (half + 1) + 4 * c4);
+            }
         }
+        // the query operands of the next four dimensions are requested (scalar loads) before the current four are used
+        const double *__restrict__ qh = qd + half * SCQ_HALF * SCQ_TOK;
+        double qa[4 * SCQ_TOK], qb[4 * SCQ_TOK];
 #pragma unroll
-        for (int v = 0; v < 8; ++v) cur[v] = nxt[v];
-    }
-    if (c < C) {
-        float *o = S + ((int64_t)q * C + c) * QLEN + i0;
+        for (int e = 0; e < 4 * SCQ_TOK; ++e) qa[e] = qh[e];
+#pragma unroll 1
+        for (int t8 = 0; t8 < SCQ_HALF / 8; ++t8) {
+            {
 #pragma unroll
-        for (int i = 0; i < TOK; i += 4)
-            *reinterpret_cast<float4 *>(o + i) =
-                make_float4((float)acc[i], (float)acc[i + 1], (float)acc[i + 2], (float)acc[i + 3]);
+                for (int e = 0; e < 4 * SCQ_TOK; ++e) qb[e] = qh[(8 * t8 + 4) * SCQ_TOK + e];
+                const float4 a4 = row[2 * t8];
+                const double a[4] = {(double)a4.x, (double)a4.y, (double)a4.z, (double)a4.w};
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int i = 0; i < SCQ_TOK; ++i) acc[i] = fma(a[u], qa[u * SCQ_TOK + i], acc[i]);
+            }
+            {
+                const int tn = t8 + 1 < SCQ_HALF / 8 ? 8 * t8 + 8 : 0;  // the last round re-reads the first operands (unused)
+#pragma unroll
+                for (int e = 0; e < 4 * SCQ_TOK; ++e) qa[e] = qh[tn * SCQ_TOK + e];
+                const float4 a4 = row[2 * t8 + 1];
+                const double a[4] = {(double)a4.x, (double)a4.y, (double)a4.z, (double)a4.w};
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int i = 0; i < SCQ_TOK; ++i) acc[i] = fma(a[u], qb[u * SCQ_TOK + i], acc[i]);
+            }
+        }
+        __syncthreads();  // every wave is done with this half: the arena is rewritten next
     }
-}
+    const float4 s4 = make_float4((float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]);
+    if (lane < nrows) *reinterpret_cast<float4 *>(S + ((int64_t)q * C + c0 + lane) * QLEN + SCQ_TOK * g) = s4;
+    float *trow = tile + lane * SCQ_SSTRIDE + SCQ_TOK * g;
+    trow[0] = s4.x;
+    trow[1] = s4.y;
+    trow[2] = s4.z;
+    trow[3] = s4.w;
+    __syncthreads();
 
-// Eq. 5: bit c of keepbits[q] = (max_i S[q][c][i] >= t_cs), inclusive.  Eight lanes share a row.
-__global__ __launch_bounds__(256) void keep_kernel(const float *__restrict__ S, int64_t C, float t_cs,
-                                                   uint32_t *__restrict__ keepbits, int64_t keep_words)
-{
-    const int q = blockIdx.y;
-    const float *Sq = S + (int64_t)q * C * QLEN;
-    uint32_t *kb = keepbits + (int64_t)q * keep_words;
-    const int sub = threadIdx.x & 7;
-    __shared__ uint32_t part[4];
-    // a block covers 32 rows per step, i.e. one bitmap word
-    for (int64_t w = blockIdx.x; w < keep_words; w += gridDim.x) {
-        const int64_t c = w * 32 + (threadIdx.x >> 3);
+    // Eq. 5: pruning bits of the 64 rows (wave 0)
+    if (tid < 64) {
         float m = -INFINITY;
-        if (c < C) {
-            const float4 v = *reinterpret_cast<const float4 *>(Sq + c * QLEN + 4 * sub);
-            m = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
+#pragma unroll
+        for (int i = 0; i < QLEN; ++i) m = fmaxf(m, tile[tid * SCQ_SSTRIDE + i]);
+        const unsigned long long b = __ballot(tid < nrows && m >= t_cs);
+        if (tid == 0) {
+            uint32_t *kb = keepbits + (int64_t)q * keep_words + (c0 >> 5);
+            kb[0] = (uint32_t)b;
+            if ((c0 >> 5) + 1 < keep_words) kb[1] = (uint32_t)(b >> 32);
         }
-        m = fmaxf(m, __shfl_xor(m, 1));
-        m = fmaxf(m, __shfl_xor(m, 2));
-        m = fmaxf(m, __shfl_xor(m, 4));
-        const bool keep = c < C && m >= t_cs;
-        const unsigned long long b = __ballot(keep && sub == 0);  // bit 8r of the wave's ballot = row r of this wave
-        // compress bits 0, 8, ..., 56 into one byte
-        unsigned long long x = b & 0x0101010101010101ull;
-        x = (x * 0x0102040810204080ull) >> 56;
-        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = (uint32_t)x;
-        __syncthreads();
-        if (threadIdx.x == 0) kb[w] = part[0] | (part[1] << 8) | (part[2] << 16) | (part[3] << 24);
-        __syncthreads();
     }
+    if (NP == 0) return;
+
+    // Section 4.1: each token's NP best centroids of this tile.  Thread (i, p) ranks rows 8p .. 8p+7 of column i.
+    uint64_t best[NPK];
+#pragma unroll
+    for (int j = 0; j < NPK; ++j) best[j] = PLAID_KEY_MAX;
+    if (tid < 256) {
+        const int i = tid & 31, p = tid >> 5;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int rr = 8 * p + r;
+            if (rr < nrows) scq_insert_key<NPK>(best, plaid_make_key(tile[rr * SCQ_SSTRIDE + i], (uint32_t)(c0 + rr)));
+        }
+#pragma unroll
+        for (int j = 0; j < NPK; ++j) lk[(p * QLEN + i) * NPK + j] = best[j];
+    }
+    __syncthreads();
+    if (tid < QLEN) {
+        for (int p = 1; p < 8; ++p)
+#pragma unroll
+            for (int j = 0; j < NPK; ++j) scq_insert_key<NPK>(best, lk[(p * QLEN + tid) * NPK + j]);
+        uint64_t *po = partial + (((int64_t)q * QLEN + tid) * gridDim.x + blockIdx.x) * NPK;  // [q][token][tile][NPK]
+#pragma unroll
+        for (int j = 0; j < NPK; ++j) po[j] = best[j];
+    }
+
 }
 
-void plaid_launch_scq(hipStream_t st, const float *centroids, int64_t C, const float *Q, double *Qd, int nq, float t_cs,
-                      float *S, uint32_t *keepbits, int64_t keep_words)
+// One workgroup per query: merge the tiles' lists into the probes (rank order), their ascending duplicate-free union,
+// and build the survivor table.  32 lanes share a query token: each folds every 32nd tile list (coalesced: the lists
+// of a token are contiguous), then the 32 partial lists are merged by a shuffle tree inside the wave.
+template <int NP>
+__global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *__restrict__ S, int64_t C,
+                                                                   const uint32_t *__restrict__ keepbits, int64_t keep_words,
+                                                                   const uint64_t *__restrict__ partial, int nblk, int nprobe,
+                                                                   Stage1Out o)
 {
-    hipLaunchKernelGGL(scq_prepare_kernel, dim3(nq), dim3(256), 0, st, Q, Qd);
-    const int64_t rows64 = (C + 63) / 64;
-    // enough waves to cover the 1024 SIMDs of the chip when C (times the queries of the chunk) is small
-    if (rows64 * 2 * nq >= 2048)
-        hipLaunchKernelGGL(scq_kernel<16>, dim3((unsigned)((rows64 * 2 + 3) / 4), nq), dim3(256), 0, st, centroids, C, Qd,
-                           S);
-    else
-        hipLaunchKernelGGL(scq_kernel<8>, dim3((unsigned)((rows64 * 4 + 3) / 4), nq), dim3(256), 0, st, centroids, C, Qd, S);
-    int64_t gx = keep_words;
-    const int64_t cap = nq >= 8 ? 256 : 2048;
-    if (gx > cap) gx = cap;
-    hipLaunchKernelGGL(keep_kernel, dim3((unsigned)gx, nq), dim3(256), 0, st, S, C, t_cs, keepbits, keep_words);
+    __shared__ int32_t idl[256];   // probed ids
+    __shared__ int32_t top1[QLEN];
+    __shared__ int32_t scan[TAIL_THREADS / 64 + 1];
+    __shared__ int32_t ids[S2_MAX_KEPT + 1];
+    __shared__ uint32_t trial[S2_NHASH * (S2_HASH / 32)];
+    __shared__ float colmm[2 * QLEN];
+    __shared__ int32_t misc[2];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    {
+        const int i = tid / TAIL_LANES, l = tid % TAIL_LANES;
+        uint64_t best[NP];
+#pragma unroll
+        for (int j = 0; j < NP; ++j) best[j] = PLAID_KEY_MAX;
+        const uint64_t *pq = partial + ((int64_t)q * QLEN + i) * nblk * NP;
+        constexpr int FLY = NP <= 2 ? 8 : (NP == 4 ? 4 : 2);  // lists in flight per lane
+        int b = l;
+        for (; b + (FLY - 1) * TAIL_LANES < nblk; b += FLY * TAIL_LANES) {
+            uint64_t v[FLY][NP];
+#pragma unroll
+            for (int u = 0; u < FLY; ++u)
+#pragma unroll
+                for (int j = 0; j < NP; ++j) v[u][j] = pq[(int64_t)(b + TAIL_LANES * u) * NP + j];
+#pragma unroll
+            for (int u = 0; u < FLY; ++u)
+#pragma unroll
+                for (int j = 0; j < NP; ++j) scq_insert_key<NP>(best, v[u][j]);
+        }
+        for (; b < nblk; b += TAIL_LANES)
+#pragma unroll
+            for (int j = 0; j < NP; ++j) scq_insert_key<NP>(best, pq[(int64_t)b * NP + j]);
+        // shuffle tree over the 32 lanes of this token (lanes l and l ^ d exchange lists; both keep the merged list)
+#pragma unroll
+        for (int d = 1; d < TAIL_LANES; d <<= 1) {
+            uint64_t other[NP];
+#pragma unroll
+            for (int j = 0; j < NP; ++j) other[j] = __shfl_xor(best[j], d);
+#pragma unroll
+            for (int j = 0; j < NP; ++j) scq_insert_key<NP>(best, other[j]);
+        }
+        if (l == 0) {
+#pragma unroll
+            for (int j = 0; j < NP; ++j)
+                if (j < nprobe) {
+                    const int32_t id = (int32_t)(best[j] & 0xFFFFFFFFu);
+                    o.probed[((int64_t)q * QLEN + i) * nprobe + j] = id;
+                    idl[i * nprobe + j] = id;
+                }
+            top1[i] = (int32_t)(best[0] & 0xFFFFFFFFu);
+        }
+    }
+    __syncthreads();
+    // ascending duplicate-free union of the n = 32 * nprobe (<= 256) probed ids by counting: an id is kept at its first
+    // occurrence, at position = number of distinct smaller ids.  Four lanes share the n comparisons of one id.
+    {
+        const int n = QLEN * nprobe;
+        const int t = tid >> 2, part = tid & 3;
+        const int32_t id = t < n ? idl[t] : 0x7FFFFFFF;
+        int earlier_same = 0;
+        for (int u = part; u < n; u += 4) earlier_same += (idl[u] == id && u < t) ? 1 : 0;
+        earlier_same += __shfl_xor(earlier_same, 1);
+        earlier_same += __shfl_xor(earlier_same, 2);
+        const bool fo = t < n && earlier_same == 0;
+        // position = number of first occurrences with a smaller id
+        __shared__ int32_t first[256];
+        if (part == 0 && t < n) first[t] = fo ? 1 : 0;
+        __syncthreads();
+        int pos = 0;
+        for (int u = part; u < n; u += 4) pos += (first[u] && idl[u] < id) ? 1 : 0;
+        pos += __shfl_xor(pos, 1);
+        pos += __shfl_xor(pos, 2);
+        if (fo && part == 0) o.uniq[(int64_t)q * o.uniq_stride + pos] = id;
+        const int total = __syncthreads_count(fo && part == 0);
+        if (tid == 0) o.n_uniq[q] = total;
+    }
+    stage1_survivor_table(S + (int64_t)q * C * QLEN, C, keepbits + (int64_t)q * keep_words, keep_words, top1, o.meta + q,
+                          o.kept_ids + (int64_t)q * S2_MAX_KEPT, o.T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN, scan, ids, trial,
+                          colmm, misc);
+}
+
+template <int NP>
+static void launch_fused(hipStream_t st, const float *centroids, int64_t C, const double *Qd, int nq, float t_cs, float *S,
+                         uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int nprobe, const Stage1Out &o)
+{
+    const unsigned nblk = (unsigned)((C + SCQ_ROWS - 1) / SCQ_ROWS);
+    hipLaunchKernelGGL(scq_fused_kernel<NP>, dim3(nblk, nq), dim3(SCQ_THREADS), 0, st, centroids, C, Qd, t_cs, S, keepbits,
+                       keep_words, partial);
+    if (NP > 0)
+        hipLaunchKernelGGL(stage1_tail_kernel<(NP > 0 ? NP : 1)>, dim3(nq), dim3(TAIL_THREADS), 0, st, S, C, keepbits,
+                           keep_words, partial, (int)nblk, nprobe, o);
+}
+
+size_t plaid_stage1_partial_bytes(int64_t C, int nq, int nprobe)
+{
+    if (nprobe > PLAID_PROBE_FAST_MAX) return 256;
+    const int np = nprobe == 1 ? 1 : (nprobe == 2 ? 2 : (nprobe <= 4 ? 4 : 8));
+    return (size_t)nq * ((C + SCQ_ROWS - 1) / SCQ_ROWS) * QLEN * np * 8;
+}
+
+void plaid_launch_stage1(hipStream_t st, const float *centroids, int64_t C, const float *Q, double *Qd, int nq, float t_cs,
+                         int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int32_t *done,
+                         uint32_t *zero, int64_t zero_words, int32_t *probed, int32_t *uniq, int uniq_stride,
+                         int32_t *n_uniq, const Stage2Buffers &s2, void *probe_scratch, size_t probe_scratch_bytes)
+{
+    int64_t gz = (zero_words + 256 * 8 - 1) / (256 * 8);
+    if (gz < nq) gz = nq;
+    if (gz > 1024) gz = 1024;
+    hipLaunchKernelGGL(stage1_prep_kernel, dim3((unsigned)gz), dim3(256), 0, st, Q, Qd, nq, zero, zero_words);
+    Stage1Out o;
+    o.probed = probed;
+    o.uniq = uniq;
+    o.n_uniq = n_uniq;
+    o.uniq_stride = uniq_stride;
+    o.meta = s2.meta;
+    o.kept_ids = s2.kept_ids;
+    o.T = s2.T;
+    if (nprobe == 1) launch_fused<1>(st, centroids, C, Qd, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+    else if (nprobe == 2) launch_fused<2>(st, centroids, C, Qd, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+    else if (nprobe <= 4) launch_fused<4>(st, centroids, C, Qd, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+    else if (nprobe <= PLAID_PROBE_FAST_MAX)
+        launch_fused<8>(st, centroids, C, Qd, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+    else {
+        // large nprobe: scores and pruning bits here, probes through the generic selection, survivor table after it
+        launch_fused<0>(st, centroids, C, Qd, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+        plaid_launch_top_nprobe_general(st, S, C, nq, nprobe, probed, uniq, uniq_stride, n_uniq, probe_scratch,
+                                        probe_scratch_bytes);
+        hipLaunchKernelGGL(stage1_survivor_kernel, dim3(nq), dim3(512), 0, st, S, C, keepbits, keep_words, probed, nprobe, o);
+    }
 }

@@ -11,6 +11,8 @@
 // Nothing is read back to the host; all counts live in device memory.
 #include "plaid_internal.h"
 
+#include <math.h>
+
 #define SEL_THREADS 256
 #define FIN_THREADS 1024
 
@@ -344,6 +346,79 @@ __global__ void sel_copy_back_kernel(const uint64_t *__restrict__ src, int64_t n
         dst[(int64_t)seg * dst_stride + i] = src[(int64_t)seg * n2 + i];
 }
 
+// ------------------------------------------------------------------ short lists: selection by rank counting
+// Lists of up to SEL_SORT_CAP keys: the rank of a key is the number of smaller keys (keys are unique), so key j
+// goes to out[rank] when rank < m -- the output is in rank order without a sort.  A workgroup holds the whole list
+// in LDS and ranks 32 of its keys, eight lanes sharing the comparisons of one key.
+#define RANK_KEYS_PER_BLOCK 32
+__global__ __launch_bounds__(256) void sel_rank_kernel(const uint64_t *__restrict__ keys, int64_t key_stride,
+                                                       const int32_t *__restrict__ counts, int32_t m,
+                                                       uint64_t *__restrict__ out, int64_t out_stride,
+                                                       int32_t *__restrict__ out_counts)
+{
+    __shared__ uint64_t sk[SEL_SORT_CAP];
+    const int seg = blockIdx.y;
+    int n = counts[seg];
+    if (n > SEL_SORT_CAP) n = SEL_SORT_CAP;
+    if (blockIdx.x == 0 && threadIdx.x == 0) out_counts[seg] = m < n ? m : n;
+    const int j0 = blockIdx.x * RANK_KEYS_PER_BLOCK;
+    if (j0 >= n) return;
+    const uint64_t *k = keys + (int64_t)seg * key_stride;
+    for (int i = threadIdx.x; i < n; i += 256) sk[i] = k[i];
+    __syncthreads();
+    const int j = j0 + (threadIdx.x >> 3), part = threadIdx.x & 7;
+    const uint64_t key = j < n ? sk[j] : PLAID_KEY_MAX;
+    int rank = 0;
+    for (int i = part; i < n; i += 8) rank += sk[i] < key ? 1 : 0;
+    rank += __shfl_xor(rank, 1);
+    rank += __shfl_xor(rank, 2);
+    rank += __shfl_xor(rank, 4);
+    if (part == 0 && j < n && rank < m) out[(int64_t)seg * out_stride + rank] = key;
+}
+
+// The same selection for the final ranking: ids and scores go straight to the caller's buffers, best first, and the
+// slots beyond min(k, count) are filled with (-1, -infinity).
+__global__ __launch_bounds__(256) void sel_rank_output_kernel(const uint64_t *__restrict__ keys, int64_t key_stride,
+                                                              const int32_t *__restrict__ counts, int32_t k,
+                                                              int32_t *__restrict__ out_ids, float *__restrict__ out_scores)
+{
+    __shared__ uint64_t sk[SEL_SORT_CAP];
+    const int seg = blockIdx.y;
+    int n = counts[seg];
+    if (n > SEL_SORT_CAP) n = SEL_SORT_CAP;
+    int32_t *oi = out_ids + (int64_t)seg * k;
+    float *os = out_scores + (int64_t)seg * k;
+    if (blockIdx.x == 0)
+        for (int j = (n < k ? n : k) + threadIdx.x; j < k; j += 256) {
+            oi[j] = -1;
+            os[j] = -INFINITY;
+        }
+    const int j0 = blockIdx.x * RANK_KEYS_PER_BLOCK;
+    if (j0 >= n) return;
+    const uint64_t *kk = keys + (int64_t)seg * key_stride;
+    for (int i = threadIdx.x; i < n; i += 256) sk[i] = kk[i];
+    __syncthreads();
+    const int j = j0 + (threadIdx.x >> 3), part = threadIdx.x & 7;
+    const uint64_t key = j < n ? sk[j] : PLAID_KEY_MAX;
+    int rank = 0;
+    for (int i = part; i < n; i += 8) rank += sk[i] < key ? 1 : 0;
+    rank += __shfl_xor(rank, 1);
+    rank += __shfl_xor(rank, 2);
+    rank += __shfl_xor(rank, 4);
+    if (part == 0 && j < n && rank < k) {
+        oi[rank] = (int32_t)(key & 0xFFFFFFFFu);
+        os[rank] = plaid_ord_to_score((uint32_t)(key >> 32));
+    }
+}
+
+void plaid_launch_rank_output(hipStream_t st, const uint64_t *keys, int64_t key_stride, const int32_t *counts, int nseg,
+                              int64_t n_upper, int32_t k, int32_t *out_ids, float *out_scores)
+{
+    const int gx = (int)((n_upper + RANK_KEYS_PER_BLOCK - 1) / RANK_KEYS_PER_BLOCK);
+    hipLaunchKernelGGL(sel_rank_output_kernel, dim3(gx > 0 ? gx : 1, nseg), dim3(256), 0, st, keys, key_stride, counts, k,
+                       out_ids, out_scores);
+}
+
 // ------------------------------------------------------------------ host side
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 static inline int64_t pow2_at_least(int64_t n)
@@ -416,8 +491,10 @@ void plaid_launch_select(hipStream_t st, const uint64_t *keys, int64_t key_strid
     // the caller zeroes state + hist (plaid_launch_fill_u32 over the head of the scratch) before the
     // producer runs; see search.hip
     if (n_upper <= SEL_SORT_CAP) {
-        hipLaunchKernelGGL(sel_finish_kernel<true>, dim3(nseg), dim3(FIN_THREADS), 0, st, keys, key_stride, counts, m,
-                           sc.state, nullptr, 0, nullptr, 0, out, out_stride, out_counts, sorted);
+        const int gx = (int)((n_upper + RANK_KEYS_PER_BLOCK - 1) / RANK_KEYS_PER_BLOCK);
+        hipLaunchKernelGGL(sel_rank_kernel, dim3(gx > 0 ? gx : 1, nseg), dim3(256), 0, st, keys, key_stride, counts, m, out,
+                           out_stride, out_counts);
+        return;
     } else {
         const int gx = blocks_for(n_upper, nseg);
         if (!state_ready)
@@ -670,16 +747,16 @@ __global__ __launch_bounds__(FIN_THREADS) void sel2_finish_kernel(const uint64_t
     }
     __syncthreads();
 
-    // empty-bag candidates: ascending pid, until m slots are filled
+    // empty-bag candidates: ascending pid, until m slots are filled.  One bitmap word per thread and round; positions
+    // from a wave-level prefix sum of the popcounts plus the wave totals.
     if (total < m) {
-        int32_t *scan = h256;  // reused: FIN_THREADS / 4 words are not enough, so scan in chunks of 256 words
+        int32_t *wsum = h256;  // [FIN_THREADS / 64] wave totals
         const uint32_t *eb = emptybits + (int64_t)seg * cand_words;
-        if (threadIdx.x == 0) sh[3] = total;
-        __syncthreads();
-        for (int64_t w0 = 0; w0 < cand_words; w0 += 256) {
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        for (int64_t w0 = 0; w0 < cand_words && total < m; w0 += FIN_THREADS) {
             const int64_t w = w0 + threadIdx.x;
             uint32_t v = 0u;
-            if (threadIdx.x < 256 && w < cand_words) {
+            if (w < cand_words) {
                 v = eb[w];
                 if ((w + 1) * 32 > P) {
                     const int64_t keep = P - w * 32;
@@ -687,30 +764,28 @@ __global__ __launch_bounds__(FIN_THREADS) void sel2_finish_kernel(const uint64_t
                 }
             }
             const int cnt = __popc(v);
-            if (threadIdx.x < 256) scan[threadIdx.x] = cnt;
-            __syncthreads();
-            for (int d = 1; d < 256; d <<= 1) {
-                int t = 0;
-                if (threadIdx.x < 256 && threadIdx.x >= d) t = scan[threadIdx.x - d];
-                __syncthreads();
-                if (threadIdx.x < 256) scan[threadIdx.x] += t;
-                __syncthreads();
+            int incl = cnt;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int t = __shfl_up(incl, d);
+                if (lane >= d) incl += t;
             }
-            const int start = sh[3];
-            if (threadIdx.x < 256) {
-                int pos = start + scan[threadIdx.x] - cnt;
-                while (v && pos < m) {
-                    const int bit = __ffs(v) - 1;
-                    v &= v - 1;
-                    o[pos++] = plaid_make_key(-INFINITY, (uint32_t)(w * 32 + bit));
-                }
+            __syncthreads();  // the previous round's readers of wsum are done
+            if (lane == 63) wsum[wave] = incl;
+            __syncthreads();
+            int pos = total + incl - cnt, all = 0;
+            for (int wv = 0; wv < FIN_THREADS / 64; ++wv) {
+                const int t = wsum[wv];
+                if (wv < wave) pos += t;
+                all += t;
             }
-            __syncthreads();
-            if (threadIdx.x == 0) sh[3] = start + scan[255] < m ? start + scan[255] : m;
-            __syncthreads();
-            if (sh[3] >= m) break;
+            while (v && pos < m) {
+                const int bit = __ffs(v) - 1;
+                v &= v - 1;
+                o[pos++] = plaid_make_key(-INFINITY, (uint32_t)(w * 32 + bit));
+            }
+            total = total + all < m ? total + all : m;  // uniform: every thread adds the same wave totals
         }
-        total = sh[3];
     }
     if (threadIdx.x == 0) out_counts[seg] = total;
 }

@@ -28,119 +28,7 @@
 #ifndef S2W_CAP
 #define S2W_CAP 6144     // tokens a wave stages per round (one byte each)
 #endif
-#define S2_HASH 1024     // entries of the survivor table: direct-mapped, collision-free by choice of hash
-#define S2_NHASH 24      // hash functions tried per query
-#define S2_SHIFT0 5      // the first one shifts by 5 bits
 #define S2_TSTRIDE 36    // floats per staged S_cq row (16-byte aligned, rows spread over the banks)
-
-// ------------------------------------------------------------------ per-query table of surviving centroids
-// One workgroup per query.  meta.K = number of centroids with max_i S[c][i] >= t_cs; when K <= S2_MAX_KEPT the
-// ids are listed ascending in kept_ids and their rows copied to T (slot s = 1..K at T[s]); bin_hi / bin_scale
-// define the selection bins from bounds of any non-empty passage's score.
-__global__ __launch_bounds__(1024) void s2_meta_kernel(const float *__restrict__ S, int64_t C,
-                                                       const uint32_t *__restrict__ keepbits, int64_t keep_words,
-                                                       const int32_t *__restrict__ probed, int nprobe, S2Meta *meta,
-                                                       int32_t *__restrict__ kept_ids, float *__restrict__ T)
-{
-    __shared__ int32_t scan[1024];
-    __shared__ int32_t base_s;
-    __shared__ int32_t ids[S2_MAX_KEPT];
-    __shared__ float colmax[QLEN], colmin[QLEN];
-    const int q = blockIdx.x;
-    const float *Sq = S + (int64_t)q * C * QLEN;
-    const uint32_t *kb = keepbits + (int64_t)q * keep_words;
-    if (threadIdx.x == 0) base_s = 0;
-    __syncthreads();
-    for (int64_t w0 = 0; w0 < keep_words; w0 += 1024) {
-        const int64_t w = w0 + threadIdx.x;
-        uint32_t v = w < keep_words ? kb[w] : 0u;
-        const int cnt = __popc(v);
-        scan[threadIdx.x] = cnt;
-        __syncthreads();
-        for (int d = 1; d < 1024; d <<= 1) {
-            const int t = threadIdx.x >= d ? scan[threadIdx.x - d] : 0;
-            __syncthreads();
-            scan[threadIdx.x] += t;
-            __syncthreads();
-        }
-        int pos = base_s + scan[threadIdx.x] - cnt;
-        while (v && pos < S2_MAX_KEPT) {
-            const int b = __ffs(v) - 1;
-            v &= v - 1;
-            ids[pos++] = (int32_t)(w * 32 + b);
-        }
-        __syncthreads();
-        if (threadIdx.x == 1023) base_s += scan[1023];
-        __syncthreads();
-    }
-    int K = base_s;
-    if (C > (1ll << 26) - 2 && K <= S2_MAX_KEPT) K = S2_MAX_KEPT + 1;  // ids must fit the 26-bit field of a table entry
-    // pick a hash h(c) = (c ^ (c >> sh)) & (S2_HASH-1) that maps the survivors to distinct entries, so that a lookup
-    // is one probe; thread t tries shift S2_SHIFT0 + t on a private bitmap.  No such shift (very rare): gather kernel.
-    __shared__ uint32_t trial[S2_NHASH][S2_HASH / 32];
-    __shared__ int32_t chosen;
-    if (threadIdx.x == 0) chosen = -1;
-    if (threadIdx.x < S2_NHASH)
-        for (int w = 0; w < S2_HASH / 32; ++w) trial[threadIdx.x][w] = 0u;
-    __syncthreads();
-    if (K <= S2_MAX_KEPT) {
-        bool ok = threadIdx.x < S2_NHASH;
-        if (ok) {
-            const int sh = S2_SHIFT0 + threadIdx.x;
-            for (int s = 0; s < K; ++s) {
-                const uint32_t c = (uint32_t)ids[s];
-                const uint32_t h = (c ^ (c >> sh)) & (S2_HASH - 1);
-                const uint32_t bit = 1u << (h & 31);
-                if (trial[threadIdx.x][h >> 5] & bit) ok = false;
-                trial[threadIdx.x][h >> 5] |= bit;
-            }
-        }
-        if (ok) atomicMax(&chosen, S2_NHASH - 1 - (int)threadIdx.x);  // smallest successful shift wins
-        __syncthreads();
-        if (chosen < 0) K = S2_MAX_KEPT + 1;
-    }
-    const int hash_shift = (K <= S2_MAX_KEPT) ? S2_SHIFT0 + (S2_NHASH - 1 - chosen) : 0;
-    float *Tq = T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN;
-    float hi, lo;
-    if (K <= S2_MAX_KEPT) {
-        for (int e = threadIdx.x; e < K * QLEN; e += 1024) {
-            const int s = e >> 5, i = e & 31;
-            Tq[(s + 1) * QLEN + i] = Sq[(int64_t)ids[s] * QLEN + i];
-        }
-        if (threadIdx.x < K) kept_ids[(int64_t)q * S2_MAX_KEPT + threadIdx.x] = ids[threadIdx.x];
-        if (threadIdx.x < QLEN) {
-            float mx = -INFINITY, mn = INFINITY;
-            for (int s = 0; s < K; ++s) {
-                const float v = Sq[(int64_t)ids[s] * QLEN + threadIdx.x];
-                mx = fmaxf(mx, v);
-                mn = fminf(mn, v);
-            }
-            colmax[threadIdx.x] = mx;
-            colmin[threadIdx.x] = mn;
-        }
-    } else if (threadIdx.x < QLEN) {
-        // many survivors: the best centroid of each token bounds every row from above
-        colmax[threadIdx.x] = Sq[(int64_t)probed[((int64_t)q * QLEN + threadIdx.x) * nprobe] * QLEN + threadIdx.x];
-        colmin[threadIdx.x] = -colmax[threadIdx.x] - 1.0f;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double u = 0.0, l = 0.0;
-        for (int i = 0; i < QLEN; ++i) {
-            u += (double)colmax[i];
-            l += (double)colmin[i];
-        }
-        hi = (float)u;
-        lo = (float)l;
-        S2Meta m;
-        m.K = K;
-        m.bin_hi = hi;
-        const float range = hi - lo;
-        m.bin_scale = (K > 0 && range > 0.f && range < INFINITY) ? (float)SEL_BINS / range : 0.f;
-        m.hash_shift = hash_shift;
-        meta[q] = m;
-    }
-}
 
 // ------------------------------------------------------------------ shared tail: emit one wave's 64 passages
 // cand / empty: per lane flags of the passage this lane scored; key valid when cand && !empty.
@@ -162,6 +50,92 @@ __device__ __forceinline__ void s2_emit(bool cand, bool empty, float score, uint
             k_or |= key;
             k_nor |= ~key;
         }
+    }
+}
+
+// ------------------------------------------------------------------ gather kernel (K > S2_MAX_KEPT)
+__device__ __forceinline__ float s2_sum32_as_double(float m)
+{
+    double d = (double)m;
+#pragma unroll
+    for (int o = 1; o < 32; o <<= 1) d += __shfl_xor(d, o);
+    return (float)d;
+}
+
+// Pruned score of the passage with tokens [t0, t1): uniform across the wave; `any` tells whether a token survived.
+__device__ __forceinline__ float s2_gather_passage(const float *__restrict__ Sq, const uint32_t *__restrict__ kb,
+                                                   int64_t t0, int64_t t1, const int32_t *__restrict__ codes, int lane,
+                                                   bool &any)
+{
+    const int i = lane & 31, h = lane >> 5;
+    float m = -INFINITY;
+    any = false;
+    for (int64_t base = t0; base < t1; base += 64) {
+        const int cnt = t1 - base < 64 ? (int)(t1 - base) : 64;
+        const int32_t code = lane < cnt ? codes[base + lane] : 0;
+        bool hit = lane < cnt;
+        if (hit) hit = (kb[code >> 5] >> (code & 31)) & 1u;
+        unsigned long long mask = __ballot(hit);
+        any = any || mask != 0;
+        while (mask) {
+            const int j0 = __ffsll((long long)mask) - 1;
+            mask &= mask - 1;
+            int j1 = j0;
+            if (mask) {
+                j1 = __ffsll((long long)mask) - 1;
+                mask &= mask - 1;
+            }
+            const int c = __shfl(code, h ? j1 : j0);
+            m = fmaxf(m, Sq[(int64_t)c * QLEN + i]);
+        }
+    }
+    m = fmaxf(m, __shfl_xor(m, 32));
+    return s2_sum32_as_double(m);
+}
+
+// Whole-grid body for one query: every wave walks bitmap words (32 passages each) with a grid stride.
+__device__ __forceinline__ void s2_gather_body(int q, const float *__restrict__ S, int64_t C,
+                                               const uint32_t *__restrict__ keepbits, int64_t keep_words,
+                                               const uint32_t *__restrict__ candbits, int64_t cand_words, int64_t P,
+                                               const int64_t *__restrict__ doc_offsets, const int32_t *__restrict__ codes,
+                                               const S2Meta &mt, uint64_t *__restrict__ keys2, int64_t key_stride,
+                                               int32_t *__restrict__ n_ne, int32_t *__restrict__ hist,
+                                               uint32_t *__restrict__ emptybits)
+{
+    const int lane = threadIdx.x & 63;
+    const float *Sq = S + (int64_t)q * C * QLEN;
+    const uint32_t *kb = keepbits + (int64_t)q * keep_words;
+    const uint32_t *cb = candbits + (int64_t)q * cand_words;
+    uint32_t *eb = emptybits + (int64_t)q * cand_words;
+    unsigned long long k_or = 0, k_nor = 0;
+    for (int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); w < cand_words; w += (int64_t)gridDim.x * 4) {
+        const uint32_t word = cb[w];
+        if (!word) {
+            if (lane == 0) eb[w] = 0u;
+            continue;
+        }
+        const int64_t p0 = w * 32;
+        int64_t off = 0;
+        if (lane <= 32 && p0 + lane <= P) off = doc_offsets[p0 + lane];
+        float my = -INFINITY;
+        bool my_empty = false;
+        uint32_t rest = word;
+        while (rest) {
+            const int b = __ffs(rest) - 1;
+            rest &= rest - 1;
+            const int64_t t0 = __shfl(off, b), t1 = __shfl(off, b + 1);
+            bool any;
+            const float sc = s2_gather_passage(Sq, kb, t0, t1, codes, lane, any);
+            if (lane == b) {
+                my = sc;
+                my_empty = !any;
+            }
+        }
+        const bool cand = lane < 32 && ((word >> lane) & 1u);
+        s2_emit(cand, my_empty, my, (uint32_t)(p0 + lane), mt, keys2 + (int64_t)q * key_stride, n_ne + q,
+                hist + (int64_t)q * SEL_BINS, k_or, k_nor);
+        const unsigned long long e64 = __ballot(cand && my_empty);
+        if (lane == 0) eb[w] = (uint32_t)e64;
     }
 }
 
@@ -189,6 +163,7 @@ __device__ __forceinline__ int s2_uniform(int v) { return __builtin_amdgcn_readf
 
 // Persistent workgroups; wave w of the grid scores the 64-passage tiles w, w + W, w + 2W, ... (lane = passage).
 __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
+    const float *__restrict__ S, int64_t C, const uint32_t *__restrict__ keepbits, int64_t keep_words,
     const int32_t *__restrict__ codes, int64_t N, const int64_t *__restrict__ doc_offsets, int64_t P,
     const uint32_t *__restrict__ candbits, int64_t cand_words, const S2Meta *__restrict__ meta,
     const int32_t *__restrict__ kept_ids, const float *__restrict__ T, uint64_t *__restrict__ keys2, int64_t key_stride,
@@ -200,7 +175,12 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
     __shared__ __align__(16) float Tl[(S2_MAX_KEPT + 1) * S2_TSTRIDE];
     const int q = blockIdx.y;
     const int K = s2_uniform(meta[q].K);
-    if (K > S2_MAX_KEPT) return;  // the gather kernel serves this query (uniform for the whole workgroup)
+    if (K > S2_MAX_KEPT) {  // too many survivors for slot sets (uniform for the whole workgroup): gather formulation
+        const S2Meta mt = meta[q];
+        s2_gather_body(q, S, C, keepbits, keep_words, candbits, cand_words, P, doc_offsets, codes, mt, keys2, key_stride, n_ne,
+                       hist, emptybits);
+        return;
+    }
     const float bin_hi = meta[q].bin_hi, bin_scale = meta[q].bin_scale;
     const int hsh = s2_uniform(meta[q].hash_shift);
     const int tid = threadIdx.x, lane = tid & 63;
@@ -374,113 +354,20 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
     }
 }
 
-// ------------------------------------------------------------------ gather kernel (K > S2_MAX_KEPT)
-__device__ __forceinline__ float s2_sum32_as_double(float m)
-{
-    double d = (double)m;
-#pragma unroll
-    for (int o = 1; o < 32; o <<= 1) d += __shfl_xor(d, o);
-    return (float)d;
-}
-
-// Pruned score of the passage with tokens [t0, t1): uniform across the wave; `any` tells whether a token survived.
-__device__ __forceinline__ float s2_gather_passage(const float *__restrict__ Sq, const uint32_t *__restrict__ kb,
-                                                   int64_t t0, int64_t t1, const int32_t *__restrict__ codes, int lane,
-                                                   bool &any)
-{
-    const int i = lane & 31, h = lane >> 5;
-    float m = -INFINITY;
-    any = false;
-    for (int64_t base = t0; base < t1; base += 64) {
-        const int cnt = t1 - base < 64 ? (int)(t1 - base) : 64;
-        const int32_t code = lane < cnt ? codes[base + lane] : 0;
-        bool hit = lane < cnt;
-        if (hit) hit = (kb[code >> 5] >> (code & 31)) & 1u;
-        unsigned long long mask = __ballot(hit);
-        any = any || mask != 0;
-        while (mask) {
-            const int j0 = __ffsll((long long)mask) - 1;
-            mask &= mask - 1;
-            int j1 = j0;
-            if (mask) {
-                j1 = __ffsll((long long)mask) - 1;
-                mask &= mask - 1;
-            }
-            const int c = __shfl(code, h ? j1 : j0);
-            m = fmaxf(m, Sq[(int64_t)c * QLEN + i]);
-        }
-    }
-    m = fmaxf(m, __shfl_xor(m, 32));
-    return s2_sum32_as_double(m);
-}
-
-__global__ __launch_bounds__(256) void s2_gather_kernel(const float *__restrict__ S, int64_t C,
-                                                        const uint32_t *__restrict__ keepbits, int64_t keep_words,
-                                                        const uint32_t *__restrict__ candbits, int64_t cand_words,
-                                                        int64_t P, const int64_t *__restrict__ doc_offsets,
-                                                        const int32_t *__restrict__ codes,
-                                                        const S2Meta *__restrict__ meta, uint64_t *__restrict__ keys2,
-                                                        int64_t key_stride, int32_t *__restrict__ n_ne,
-                                                        int32_t *__restrict__ hist, uint32_t *__restrict__ emptybits)
-{
-    const int q = blockIdx.y;
-    const S2Meta mt = meta[q];
-    if (mt.K <= S2_MAX_KEPT) return;  // the streaming kernel serves this query
-    const int lane = threadIdx.x & 63;
-    const float *Sq = S + (int64_t)q * C * QLEN;
-    const uint32_t *kb = keepbits + (int64_t)q * keep_words;
-    const uint32_t *cb = candbits + (int64_t)q * cand_words;
-    uint32_t *eb = emptybits + (int64_t)q * cand_words;
-    unsigned long long k_or = 0, k_nor = 0;
-    for (int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); w < cand_words; w += (int64_t)gridDim.x * 4) {
-        const uint32_t word = cb[w];
-        if (!word) {
-            if (lane == 0) eb[w] = 0u;
-            continue;
-        }
-        const int64_t p0 = w * 32;
-        int64_t off = 0;
-        if (lane <= 32 && p0 + lane <= P) off = doc_offsets[p0 + lane];
-        float my = -INFINITY;
-        bool my_empty = false;
-        uint32_t rest = word;
-        while (rest) {
-            const int b = __ffs(rest) - 1;
-            rest &= rest - 1;
-            const int64_t t0 = __shfl(off, b), t1 = __shfl(off, b + 1);
-            bool any;
-            const float sc = s2_gather_passage(Sq, kb, t0, t1, codes, lane, any);
-            if (lane == b) {
-                my = sc;
-                my_empty = !any;
-            }
-        }
-        const bool cand = lane < 32 && ((word >> lane) & 1u);
-        s2_emit(cand, my_empty, my, (uint32_t)(p0 + lane), mt, keys2 + (int64_t)q * key_stride, n_ne + q,
-                hist + (int64_t)q * SEL_BINS, k_or, k_nor);
-        const unsigned long long e64 = __ballot(cand && my_empty);
-        if (lane == 0) eb[w] = (uint32_t)e64;
-    }
-}
-
 // ------------------------------------------------------------------ host side
 void plaid_launch_stage2(hipStream_t st, const float *S, int64_t C, const uint32_t *keepbits, int64_t keep_words,
                          const int32_t *probed, int nprobe, const uint32_t *candbits, int64_t cand_words, int64_t P,
                          int64_t N, const int64_t *doc_offsets, const int32_t *codes, int nq, const Stage2Buffers &b,
                          uint64_t *keys2, int64_t key_stride)
 {
-    hipLaunchKernelGGL(s2_meta_kernel, dim3(nq), dim3(1024), 0, st, S, C, keepbits, keep_words, probed, nprobe, b.meta,
-                       b.kept_ids, b.T);
+    (void)probed;
+    (void)nprobe;
     // persistent workgroups; enough of them to fill the chip for one query, fewer per query in a large chunk
     const int64_t ntiles = (P + S2W_PASS - 1) / S2W_PASS;
     int64_t gs = (ntiles + 3) / 4;
     const int64_t gcap = nq >= 16 ? 96 : (nq >= 4 ? 320 : 1280);
     if (gs > gcap) gs = gcap;
-    hipLaunchKernelGGL(s2_stream_kernel, dim3((unsigned)gs, nq), dim3(S2_THREADS), 0, st, codes, N, doc_offsets, P, candbits,
-                       cand_words, b.meta, b.kept_ids, b.T, keys2, key_stride, b.n_ne, b.hist, b.emptybits);
-    int64_t gx = (cand_words + 3) / 4;
-    const int64_t cap = nq >= 16 ? 256 : (nq >= 4 ? 1024 : 4096);
-    if (gx > cap) gx = cap;
-    hipLaunchKernelGGL(s2_gather_kernel, dim3((unsigned)gx, nq), dim3(256), 0, st, S, C, keepbits, keep_words, candbits,
-                       cand_words, P, doc_offsets, codes, b.meta, keys2, key_stride, b.n_ne, b.hist, b.emptybits);
+    hipLaunchKernelGGL(s2_stream_kernel, dim3((unsigned)gs, nq), dim3(S2_THREADS), 0, st, S, C, keepbits, keep_words, codes, N,
+                       doc_offsets, P, candbits, cand_words, b.meta, b.kept_ids, b.T, keys2, key_stride, b.n_ne, b.hist,
+                       b.emptybits);
 }

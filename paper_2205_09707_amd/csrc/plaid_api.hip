@@ -318,6 +318,8 @@ struct Workspace {
     int32_t *n_uniq;     // [qc]
     void *probe_scratch;
     size_t probe_scratch_bytes;
+    uint64_t *partial;   // per-tile probe lists of the stage-1 kernel
+    int32_t *done;       // [qc] stage-1 tile counter (zeroed region)
     uint64_t *keys2;  // [qc][P]
     uint64_t *sel2;   // [qc][nd]
     int32_t *n2;      // [qc]
@@ -355,6 +357,7 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     w.zero_base = take(0);
     w.candbits = (uint32_t *)take((size_t)qc * w.cand_words * 4);
     w.s2.n_ne = (int32_t *)take((size_t)qc * 4);
+    w.done = (int32_t *)take((size_t)qc * 4);
     w.s2.hist = (int32_t *)take((size_t)qc * SEL_BINS * 4);
     w.s2.hist1 = (int32_t *)take((size_t)qc * SEL_BINS * 4);
     w.s2.state = (Sel2State *)take((size_t)qc * sizeof(Sel2State));
@@ -369,6 +372,7 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     w.n_uniq = (int32_t *)take((size_t)qc * 4);
     w.probe_scratch_bytes = plaid_top_nprobe_scratch_bytes(C, qc, pl.nprobe);
     w.probe_scratch = take(w.probe_scratch_bytes);
+    w.partial = (uint64_t *)take(plaid_stage1_partial_bytes(C, qc, pl.nprobe));
     w.keys2 = (uint64_t *)take((size_t)qc * P * 8);
     w.s2.blist = (uint64_t *)take((size_t)qc * P * 8);
     w.s2.meta = (S2Meta *)take((size_t)qc * sizeof(S2Meta));
@@ -464,11 +468,10 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
 
         STAMP();
         // stage 1: S_cq (Eq. 2), pruning map (Eq. 5), probes and candidates (Section 4.1)
-        plaid_launch_fill_u32(st, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), 0u);
-        plaid_launch_scq(st, ix->centroids, C, Qc, w.Qd, n, t_cs, w.S, w.keepbits, w.keep_words);
+        plaid_launch_stage1(st, ix->centroids, C, Qc, w.Qd, n, t_cs, nprobe, w.S, w.keepbits, w.keep_words, w.partial, w.done,
+                            (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed, w.uniq, w.uniq_stride, w.n_uniq,
+                            w.s2, w.probe_scratch, w.probe_scratch_bytes);
         STAMP();
-        plaid_launch_top_nprobe(st, w.S, C, n, nprobe, w.probed, w.uniq, w.uniq_stride, w.n_uniq, w.probe_scratch,
-                                w.probe_scratch_bytes);
         STAMP();
         plaid_launch_ivf_union(st, w.uniq, w.n_uniq, w.uniq_stride, ix->ivf_offsets, ix->ivf_pids, n, w.candbits,
                                w.cand_words);
@@ -487,9 +490,14 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
         plaid_launch_decompress_maxsim(st, Qc, ix->centroids, ix->doc_offsets, ix->codes, ix->residuals, ix->weights,
                                        ix->nbits, n, w.sel3, pl.m3, w.n3, pl.m3, w.keys4, pl.m3);
         STAMP();
-        plaid_launch_select(st, w.keys4, pl.m3, w.n3, n, pl.m3, pl.kk, w.topk, pl.kk, w.n_out, 1, sc4, 0);
-        plaid_launch_keys_to_output(st, w.topk, pl.kk, w.n_out, n, k, out_ids + (int64_t)q0 * k,
-                                    out_scores + (int64_t)q0 * k);
+        if (pl.m3 <= SEL_SORT_CAP) {
+            plaid_launch_rank_output(st, w.keys4, pl.m3, w.n3, n, pl.m3, k, out_ids + (int64_t)q0 * k,
+                                     out_scores + (int64_t)q0 * k);
+        } else {
+            plaid_launch_select(st, w.keys4, pl.m3, w.n3, n, pl.m3, pl.kk, w.topk, pl.kk, w.n_out, 1, sc4, 0);
+            plaid_launch_keys_to_output(st, w.topk, pl.kk, w.n_out, n, k, out_ids + (int64_t)q0 * k,
+                                        out_scores + (int64_t)q0 * k);
+        }
         STAMP();
 #undef STAMP
         HIP_TRY(hipGetLastError());

@@ -75,6 +75,9 @@ void plaid_launch_select(hipStream_t st, const uint64_t *keys, int64_t key_strid
                          int64_t n_upper, int32_t m, uint64_t *out, int64_t out_stride, int32_t *out_counts,
                          int sorted, const SelScratch &sc, int state_ready);
 size_t plaid_select_scratch_bytes(int nseg, int64_t n_upper, int32_t m);
+// Final ranking of short lists (n_upper <= SEL_SORT_CAP) written straight to the caller's [nseg][k] buffers.
+void plaid_launch_rank_output(hipStream_t st, const uint64_t *keys, int64_t key_stride, const int32_t *counts, int nseg,
+                              int64_t n_upper, int32_t k, int32_t *out_ids, float *out_scores);
 size_t plaid_select_zero_bytes(int nseg);
 size_t plaid_select_body_bytes(int nseg, int64_t n_upper, int32_t m);
 SelScratch plaid_select_scratch_carve(void *base, int nseg, int64_t n_upper, int32_t m);
@@ -83,13 +86,19 @@ SelScratch plaid_select_scratch_carve2(void *zero_base, void *body_base, int nse
 // ---------------------------------------------------------------------------------------------
 // Stage kernels
 // ---------------------------------------------------------------------------------------------
-// Eq. 2 + Eq. 5: S[q][c][i] and the keep bitmap (bit c of keepbits[q] = max_i S[q][c][i] >= t_cs).
-void plaid_launch_scq(hipStream_t st, const float *centroids, int64_t C, const float *Q, double *Qd, int nq, float t_cs, float *S,
-                      uint32_t *keepbits, int64_t keep_words);
+// Stage 1 (k_scq.hip): clears the zero region, then S[q][c][i] (Eq. 2), the keep bitmap (Eq. 5; bit c of
+// keepbits[q] = max_i S[q][c][i] >= t_cs), per query token the nprobe best centroids in rank order and their
+// ascending duplicate-free union (Section 4.1), and stage 2's survivor table (s2.meta / kept_ids / T).
+#define PLAID_PROBE_FAST_MAX 8  // nprobe handled inside the fused kernel; larger values go through the selection
+void plaid_launch_stage1(hipStream_t st, const float *centroids, int64_t C, const float *Q, double *Qd, int nq, float t_cs,
+                         int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int32_t *done,
+                         uint32_t *zero, int64_t zero_words, int32_t *probed, int32_t *uniq, int uniq_stride,
+                         int32_t *n_uniq, const struct Stage2Buffers &s2, void *probe_scratch, size_t probe_scratch_bytes);
+size_t plaid_stage1_partial_bytes(int64_t C, int nq, int nprobe);
 
-// Section 4.1: per query token the nprobe best centroids (rank order) + the ascending unique union.
-void plaid_launch_top_nprobe(hipStream_t st, const float *S, int64_t C, int nq, int nprobe, int32_t *probed,
-                             int32_t *uniq, int uniq_stride, int32_t *n_uniq, void *scratch, size_t scratch_bytes);
+// General top-nprobe (nprobe > PLAID_PROBE_FAST_MAX): ranking keys of every S column through the generic selection.
+void plaid_launch_top_nprobe_general(hipStream_t st, const float *S, int64_t C, int nq, int nprobe, int32_t *probed,
+                                     int32_t *uniq, int uniq_stride, int32_t *n_uniq, void *scratch, size_t scratch_bytes);
 size_t plaid_top_nprobe_scratch_bytes(int64_t C, int nq, int nprobe);
 
 // Section 4.1: candidate bitmap = union of the inverted lists of the unique probed centroids.
@@ -101,6 +110,9 @@ void plaid_launch_ivf_union(hipStream_t st, const int32_t *uniq, const int32_t *
 // Stage 2 (k_stage2.hip) and its selection (k_select.hip)
 // ---------------------------------------------------------------------------------------------
 #define S2_MAX_KEPT 63  // surviving centroids the streaming kernel handles (slots 1..63 of a 64-bit set)
+#define S2_HASH 1024    // entries of the survivor table: direct-mapped, collision-free by choice of hash
+#define S2_NHASH 24     // hash functions tried per query: h(c) = (c ^ (c >> (S2_SHIFT0 + t))) & (S2_HASH - 1)
+#define S2_SHIFT0 5
 
 struct S2Meta {        // per query
     int32_t K;         // number of centroids passing Eq. 5

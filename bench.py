@@ -22,6 +22,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch of the stage-2 kernel (64 queries), from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of this
+# file, each scaled by the counter's reading on a 1 GiB device copy (fetch reads half the bytes: x2; write: x1).
+# Source and date of every figure: profiles/s2_stream_<config>_<noise>.txt.  None = not measured.
+MEASURED_TRAFFIC_PER_LAUNCH = {
+    ("cfg3", "literal"): int((980377.8 * 2.0 + 11660.3 * 1.0) * 1024),
+}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -35,7 +42,7 @@ def algorithmic_stage2_bytes(pl, idx, w_dev, Q, params):
     lens = (w_dev.doc_offsets[1:] - w_dev.doc_offsets[:-1])
     total = 0
     ncand = []
-    step = 16
+    step = 64   # the library's chunk size, so that these launches look like the timed ones to a profiler
     for q0 in range(0, Q.shape[0], step):
         _, _, b = pl.plaid_search_debug(idx, Q[q0:q0 + step], nprobe, t_cs, ndocs, k, want=("cand", "n_cand"))
         torch.cuda.synchronize()
@@ -57,6 +64,8 @@ def main():
     ap.add_argument("--latency-queries", type=int, default=512, help="queries timed one per call for p50/p99")
     ap.add_argument("--cpu-sample", type=int, default=16, help="queries the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run four 1 GiB device-to-device copies (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -71,6 +80,15 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     pl.load_library()
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)     # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log("[bench] copy calibration: 4 copies, each reads 1 GiB (1048576 KiB) and writes 1 GiB")
+        return
     cfg = get_config(args.config)
     t0 = time.time()
     w = make_workload(cfg, device=dev, noise=args.noise)
@@ -86,6 +104,9 @@ def main():
     out_sc = torch.empty((nq, cfg.k), dtype=torch.float32, device=dev)
 
     # ---- throughput: K steps of the full batch, stage events on (they cost one sync per query chunk)
+    CHUNK = 64   # queries per internal launch
+    pl.plaid_set_max_chunk(idx, CHUNK)
+    launches = (nq + CHUNK - 1) // CHUNK
     pl.plaid_set_stage_timing(idx, True)
     for _ in range(args.warmup):
         pl.plaid_search(idx, Q, *params, out_ids=out_ids, out_scores=out_sc)
@@ -106,12 +127,12 @@ def main():
 
     # ---- batch-1 latency: one query per call, host clock around call + stream sync
     nlat = min(args.latency_queries, nq)
-    for q in range(min(20, nq)):
+    for q in range(min(20, nq) if nlat else 0):
         pl.plaid_search(idx, Q[q:q + 1], *params, out_ids=out_ids[q:q + 1], out_scores=out_sc[q:q + 1])
     torch.cuda.synchronize()
     best = None
     enq = None
-    for _trial in range(3):
+    for _trial in range(3 if nlat else 0):
         lat = np.empty(nlat)
         enq_t = np.empty(nlat)
         for q in range(nlat):
@@ -123,7 +144,8 @@ def main():
             enq_t[q] = (t2 - t1) * 1e3
         if best is None or lat.mean() < best.mean():
             best, enq = lat, enq_t
-    lat = best
+    lat = best if nlat else np.zeros(1)
+    enq = enq if nlat else np.zeros(1)
     log(f"[bench] batch-1 latency over {nlat} queries (best of 3 trials): p50 {np.percentile(lat, 50):.4f} ms, "
         f"p99 {np.percentile(lat, 99):.4f} ms, mean {lat.mean():.4f} ms; host enqueue p50 {np.percentile(enq, 50):.4f} ms")
 
@@ -135,8 +157,12 @@ def main():
         achieved = alg_bytes / t_s2 / 1e9 if t_s2 > 0 else 0.0
         roofline = {"bound": "hbm", "kernel": "stage-2 centroid interaction (Eq. 3-5) over all candidates",
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": MEASURED_TRAFFIC_PER_LAUNCH.get((cfg.name, args.noise)),
                     "algorithmic_bytes_per_step": alg_bytes, "kernel_ms_per_step": round(stage_ms["stage2_ci"], 4),
+                    "launches_per_step": launches, "queries_per_launch": CHUNK,
+                    "algorithmic_bytes_per_launch": alg_bytes // launches,
+                    "kernel_ms_per_launch": round(stage_ms["stage2_ci"] / launches, 4),
                     "mean_candidates_per_query": float(np.mean(ncand))}
         log(f"[bench] stage 2: {alg_bytes / 1e6:.1f} MB algorithmic per step in {stage_ms['stage2_ci']:.3f} ms "
             f"-> {achieved:.0f} GB/s ({achieved / HBM_PEAK_GBS:.1%} of {HBM_PEAK_GBS:.0f})")
@@ -169,7 +195,7 @@ def main():
                    "queries_per_step": nq, "index_generated_on": "cuda"},
         "latency_batch1_ms": {"p50": round(float(np.percentile(lat, 50)), 4), "p99": round(float(np.percentile(lat, 99)), 4),
                               "mean": round(float(lat.mean()), 4), "queries": int(nlat), "trials": 3, "host_enqueue_p50": round(float(np.percentile(enq, 50)), 4),
-                              "qps": round(1e3 / float(lat.mean()), 1)},
+                              "qps": round(1e3 / float(lat.mean()), 1) if nlat else None},
         "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items()},
         "roofline": roofline, "cpu_baseline": cpu,
     }

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(SEL_THREADS) void sel_hist0_kernel(const uint64_t *
 // Finds the boundary bin of a histogram: the smallest b with count(bins <= b) >= m_rem.  Every thread of
 // the block returns the same (bstar, before).  bstar = SEL_BINS when the whole list is taken.
 __device__ void find_boundary(const int32_t *__restrict__ gh, int32_t m_rem, int32_t *scan /* [SEL_THREADS] */,
-                              int32_t *res /* [2] */, int &bstar, int &before)
+                              int32_t *res /* [2] */, int &bstar, int &before, int32_t m_cap = 0x7FFFFFFF)
 {
     constexpr int PER = SEL_BINS / SEL_THREADS;
     int32_t loc[PER];
@@ -111,6 +111,7 @@ __device__ void find_boundary(const int32_t *__restrict__ gh, int32_t m_rem, int
         __syncthreads();
     }
     const int32_t incl = scan[threadIdx.x], excl = incl - sum;
+    if (m_cap != 0x7FFFFFFF) m_rem = m_cap < scan[SEL_THREADS - 1] ? m_cap : scan[SEL_THREADS - 1];  // min(m, #keys)
     if (m_rem > 0 && excl < m_rem && m_rem <= incl) {
         int32_t run = excl;
         for (int j = 0; j < PER; ++j) {
@@ -538,8 +539,8 @@ void plaid_launch_select(hipStream_t st, const uint64_t *keys, int64_t key_strid
 // their bitmap.
 // =================================================================================================
 __global__ __launch_bounds__(SEL_THREADS) void sel2_filter_kernel(const uint64_t *__restrict__ keys, int64_t key_stride,
-                                                                  const int32_t *__restrict__ n_ne, int32_t m,
-                                                                  const S2Meta *__restrict__ meta,
+                                                                  const uint32_t *__restrict__ candbits, int64_t cand_words,
+                                                                  int64_t P, int32_t m, const S2Meta *__restrict__ meta,
                                                                   const int32_t *__restrict__ hist, Sel2State *state,
                                                                   uint64_t *__restrict__ out, int64_t out_stride,
                                                                   uint64_t *__restrict__ blist, int64_t blist_stride)
@@ -547,25 +548,26 @@ __global__ __launch_bounds__(SEL_THREADS) void sel2_filter_kernel(const uint64_t
     __shared__ int32_t scan[SEL_THREADS];
     __shared__ int32_t res[2];
     const int seg = blockIdx.y;
-    const int n = n_ne[seg];
-    if ((int64_t)blockIdx.x * SEL_THREADS >= (((int64_t)n + 63) & ~63ll) && blockIdx.x != 0) return;
     Sel2State *s = state + seg;
     const S2Meta mt = meta[seg];
-    const int32_t m_eff = m < n ? m : n;
     int bstar, before;
-    find_boundary(hist + (int64_t)seg * SEL_BINS, m_eff, scan, res, bstar, before);
-    if (blockIdx.x == 0 && threadIdx.x == 0) s->m_rem = m_eff - before;
+    find_boundary(hist + (int64_t)seg * SEL_BINS, 0, scan, res, bstar, before, m);  // takes min(m, number of keys)
+    const int32_t n_keys = scan[SEL_THREADS - 1];
+    if (blockIdx.x == 0 && threadIdx.x == 0) s->m_rem = (m < n_keys ? m : n_keys) - before;
+    if (n_keys == 0) return;
     const uint64_t *k = keys + (int64_t)seg * key_stride;
+    const uint32_t *cb = candbits + (int64_t)seg * cand_words;
     uint64_t *my_out = out + (int64_t)seg * out_stride;
     uint64_t *my_bl = blist + (int64_t)seg * blist_stride;
     const int lane = threadIdx.x & 63;
-    const int64_t n_round = ((int64_t)n + 63) & ~63ll;
+    const int64_t n_round = (P + 63) & ~63ll;  // whole waves iterate together (ballots below)
     unsigned long long o = 0, no = 0;
     for (int64_t i = (int64_t)blockIdx.x * SEL_THREADS + threadIdx.x; i < n_round; i += (int64_t)gridDim.x * SEL_THREADS) {
-        uint64_t key = 0;
+        // slot i is meaningful only when passage i is a candidate; it then holds its key or the invalid key
+        uint64_t key = PLAID_KEY_MAX;
+        if (i < P && ((cb[i >> 5] >> (i & 31)) & 1u)) key = k[i];
         int cls = 2;  // 0 = surely selected, 1 = boundary, 2 = dropped
-        if (i < n) {
-            key = k[i];
+        if (key != PLAID_KEY_MAX) {
             const int d = plaid_s2_bin(plaid_ord_to_score((uint32_t)(key >> 32)), mt.bin_hi, mt.bin_scale);
             cls = d < bstar ? 0 : (d == bstar ? 1 : 2);
         }
@@ -790,12 +792,13 @@ __global__ __launch_bounds__(FIN_THREADS) void sel2_finish_kernel(const uint64_t
     if (threadIdx.x == 0) out_counts[seg] = total;
 }
 
-void plaid_launch_select2(hipStream_t st, uint64_t *keys2, int64_t key_stride, int nq, int64_t P, int64_t cand_words,
-                          int32_t m, const Stage2Buffers &b, uint64_t *out, int64_t out_stride, int32_t *out_counts)
+void plaid_launch_select2(hipStream_t st, uint64_t *keys2, int64_t key_stride, const uint32_t *candbits, int nq, int64_t P,
+                          int64_t cand_words, int32_t m, const Stage2Buffers &b, uint64_t *out, int64_t out_stride,
+                          int32_t *out_counts)
 {
     const int gx = blocks_for(P, nq);
-    hipLaunchKernelGGL(sel2_filter_kernel, dim3(gx, nq), dim3(SEL_THREADS), 0, st, keys2, key_stride, b.n_ne, m, b.meta,
-                       b.hist, b.state, out, out_stride, b.blist, P);
+    hipLaunchKernelGGL(sel2_filter_kernel, dim3(gx, nq), dim3(SEL_THREADS), 0, st, keys2, key_stride, candbits, cand_words, P,
+                       m, b.meta, b.hist, b.state, out, out_stride, b.blist, P);
     if (P > SEL_SORT_CAP) {
         // only a boundary bin longer than SEL_SORT_CAP makes these two do anything; keys2 serves as blist1
         hipLaunchKernelGGL(sel2_digit_hist_kernel, dim3(gx, nq), dim3(SEL_THREADS), 0, st, b.blist, P, b.state, b.hist1);

@@ -6,54 +6,36 @@
 //
 //   streaming part   the candidates' token codes are read once, coalesced, straight from HBM
 //                    (128-byte lines that no candidate touches are skipped); each code is looked
-//                    up in a tiny LDS hash table of the K surviving centroids and turned into a
-//                    slot number; one lane per passage then folds its slots into a K-bit set;
+//                    up in a small LDS table of the K surviving centroids and turned into a slot
+//                    number; one lane per passage then folds its slots into a K-bit set;
 //   scoring part     the lane takes the column maxima of the <= K surviving rows named by the
 //                    set (rows staged in LDS) and sums the 32 maxima in double, in index order.
 //
 // No matrix D~ is ever stacked (Section 4.5's padding-free idea), nothing is padded, and the
 // order-independent max plus the fixed-order sum make a score a pure function of the passage.
 // Queries with more than S2_MAX_KEPT surviving centroids (very low thresholds) take the gather
-// kernel instead: one wave per passage fetching surviving rows from the L2-resident S_cq.
+// form instead: one wave per passage fetching surviving rows from the L2-resident S_cq.
 //
-// Output of either kernel, per query: ranking keys of the candidates with a non-empty bag
-// (unordered, with a histogram of their bins for the selection that follows) and a bitmap of the
-// candidates whose bag is empty (score -infinity; they rank last, in passage-id order).
+// Output of either form, per query: slot p of the key array holds the ranking key of candidate p
+// when its bag is non-empty and the invalid key otherwise (slots of non-candidates are neither
+// written nor read), a histogram of the valid keys' bins for the selection that follows, and a
+// bitmap of the candidates whose bag is empty (score -infinity; they rank last, in passage-id
+// order).  No counters and no atomics with a return value on this path.
 #include "plaid_internal.h"
 
 #include <math.h>
 
 #define S2_THREADS 256
 #define S2W_PASS 64      // passages per wave tile = 2 words of the candidate bitmap
-#ifndef S2W_CAP
-#define S2W_CAP 6144     // tokens a wave stages per round (one byte each)
+#ifndef S2_ITEMS
+#define S2_ITEMS 9       // 16-byte loads per lane and round, all in flight at once
 #endif
+#define S2W_CAP (64 * 4 * S2_ITEMS - 32)  // tokens a wave stages per round (one byte each), whatever their alignment
+#define S2_LBWORDS ((S2_ITEMS + 3) / 4)   // words of the round's line bitmap (8 lines per item)
 #define S2_TSTRIDE 36    // floats per staged S_cq row (16-byte aligned, rows spread over the banks)
+static_assert(S2_LBWORDS <= 64, "one lane clears one word of the line bitmap");
 
-// ------------------------------------------------------------------ shared tail: emit one wave's 64 passages
-// cand / empty: per lane flags of the passage this lane scored; key valid when cand && !empty.
-__device__ __forceinline__ void s2_emit(bool cand, bool empty, float score, uint32_t pid, const S2Meta &mt,
-                                        uint64_t *__restrict__ out, int32_t *__restrict__ n_ne,
-                                        int32_t *__restrict__ hist, unsigned long long &k_or, unsigned long long &k_nor)
-{
-    const bool live = cand && !empty;
-    const unsigned long long b = __ballot(live);
-    if (b) {
-        const int lane = threadIdx.x & 63;
-        int base = 0;
-        if (lane == 0) base = atomicAdd(n_ne, __popcll(b));
-        base = __shfl(base, 0);
-        if (live) {
-            const uint64_t key = plaid_make_key(score, pid);
-            out[base + __popcll(b & ((1ull << lane) - 1ull))] = key;
-            atomicAdd(&hist[plaid_s2_bin(score, mt.bin_hi, mt.bin_scale)], 1);
-            k_or |= key;
-            k_nor |= ~key;
-        }
-    }
-}
-
-// ------------------------------------------------------------------ gather kernel (K > S2_MAX_KEPT)
+// ------------------------------------------------------------------ gather form (K > S2_MAX_KEPT)
 __device__ __forceinline__ float s2_sum32_as_double(float m)
 {
     double d = (double)m;
@@ -98,16 +80,14 @@ __device__ __forceinline__ void s2_gather_body(int q, const float *__restrict__ 
                                                const uint32_t *__restrict__ keepbits, int64_t keep_words,
                                                const uint32_t *__restrict__ candbits, int64_t cand_words, int64_t P,
                                                const int64_t *__restrict__ doc_offsets, const int32_t *__restrict__ codes,
-                                               const S2Meta &mt, uint64_t *__restrict__ keys2, int64_t key_stride,
-                                               int32_t *__restrict__ n_ne, int32_t *__restrict__ hist,
-                                               uint32_t *__restrict__ emptybits)
+                                               float bin_hi, float bin_scale, uint64_t *__restrict__ keys_out,
+                                               int32_t *__restrict__ hist_q, uint32_t *__restrict__ emptybits)
 {
     const int lane = threadIdx.x & 63;
     const float *Sq = S + (int64_t)q * C * QLEN;
     const uint32_t *kb = keepbits + (int64_t)q * keep_words;
     const uint32_t *cb = candbits + (int64_t)q * cand_words;
     uint32_t *eb = emptybits + (int64_t)q * cand_words;
-    unsigned long long k_or = 0, k_nor = 0;
     for (int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); w < cand_words; w += (int64_t)gridDim.x * 4) {
         const uint32_t word = cb[w];
         if (!word) {
@@ -132,14 +112,15 @@ __device__ __forceinline__ void s2_gather_body(int q, const float *__restrict__ 
             }
         }
         const bool cand = lane < 32 && ((word >> lane) & 1u);
-        s2_emit(cand, my_empty, my, (uint32_t)(p0 + lane), mt, keys2 + (int64_t)q * key_stride, n_ne + q,
-                hist + (int64_t)q * SEL_BINS, k_or, k_nor);
+        const bool live = cand && !my_empty;
+        if (cand) keys_out[p0 + lane] = live ? plaid_make_key(my, (uint32_t)(p0 + lane)) : PLAID_KEY_MAX;
+        if (live) atomicAdd(&hist_q[plaid_s2_bin(my, bin_hi, bin_scale)], 1);
         const unsigned long long e64 = __ballot(cand && my_empty);
         if (lane == 0) eb[w] = (uint32_t)e64;
     }
 }
 
-// ------------------------------------------------------------------ streaming kernel (K <= S2_MAX_KEPT)
+// ------------------------------------------------------------------ streaming form (K <= S2_MAX_KEPT)
 // Survivor table entry: (centroid id << 6) | slot, 0xFFFFFFFF = free.  The hash is collision-free on the survivors,
 // so one probe decides: returns the slot (1..63) of a surviving centroid, 0 otherwise.
 __device__ __forceinline__ uint32_t s2_lookup(const uint32_t *htab, uint32_t code, int hash_shift)
@@ -161,27 +142,35 @@ __device__ __forceinline__ void s2_wave_sync()
 // readfirstlane, so that all cross-lane operations (__shfl, __ballot) run with the full wave active.
 __device__ __forceinline__ int s2_uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
+// First set bit of m at position >= from, 64 when there is none (all operands uniform).
+__device__ __forceinline__ int s2_next_bit(unsigned long long m, int from)
+{
+    const unsigned long long rest = from < 64 ? (m >> from) << from : 0ull;
+    return rest ? __ffsll((long long)rest) - 1 : 64;
+}
+
 // Persistent workgroups; wave w of the grid scores the 64-passage tiles w, w + W, w + 2W, ... (lane = passage).
 __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
     const float *__restrict__ S, int64_t C, const uint32_t *__restrict__ keepbits, int64_t keep_words,
     const int32_t *__restrict__ codes, int64_t N, const int64_t *__restrict__ doc_offsets, int64_t P,
     const uint32_t *__restrict__ candbits, int64_t cand_words, const S2Meta *__restrict__ meta,
     const int32_t *__restrict__ kept_ids, const float *__restrict__ T, uint64_t *__restrict__ keys2, int64_t key_stride,
-    int32_t *__restrict__ n_ne, int32_t *__restrict__ hist, uint32_t *__restrict__ emptybits)
+    int32_t *__restrict__ hist, uint32_t *__restrict__ emptybits)
 {
     __shared__ __align__(16) uint8_t stage_all[S2_THREADS / 64][S2W_CAP + 64];
-    __shared__ uint32_t linebits_all[S2_THREADS / 64][(S2W_CAP / 32 + 2 + 31) / 32 + 1];
+    __shared__ uint32_t linebits_all[S2_THREADS / 64][S2_LBWORDS];
     __shared__ uint32_t htab[S2_HASH];
     __shared__ __align__(16) float Tl[(S2_MAX_KEPT + 1) * S2_TSTRIDE];
     const int q = blockIdx.y;
     const int K = s2_uniform(meta[q].K);
-    if (K > S2_MAX_KEPT) {  // too many survivors for slot sets (uniform for the whole workgroup): gather formulation
-        const S2Meta mt = meta[q];
-        s2_gather_body(q, S, C, keepbits, keep_words, candbits, cand_words, P, doc_offsets, codes, mt, keys2, key_stride, n_ne,
-                       hist, emptybits);
+    const float bin_hi = meta[q].bin_hi, bin_scale = meta[q].bin_scale;
+    uint64_t *keys_out = keys2 + (int64_t)q * key_stride;
+    int32_t *hist_q = hist + (int64_t)q * SEL_BINS;
+    if (K > S2_MAX_KEPT) {  // too many survivors for slot sets (uniform for the whole workgroup): gather form
+        s2_gather_body(q, S, C, keepbits, keep_words, candbits, cand_words, P, doc_offsets, codes, bin_hi, bin_scale, keys_out,
+                       hist_q, emptybits);
         return;
     }
-    const float bin_hi = meta[q].bin_hi, bin_scale = meta[q].bin_scale;
     const int hsh = s2_uniform(meta[q].hash_shift);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = s2_uniform(tid >> 6);
@@ -200,151 +189,170 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
     uint32_t *linebits = linebits_all[wave];
     const uint32_t *cb = candbits + (int64_t)q * cand_words;
     uint32_t *eb = emptybits + (int64_t)q * cand_words;
-    uint64_t *keys_out = keys2 + (int64_t)q * key_stride;
-    int32_t *hist_q = hist + (int64_t)q * SEL_BINS;
     const int ntiles = (int)((P + S2W_PASS - 1) / S2W_PASS);
     const int nwaves = (int)gridDim.x * (S2_THREADS / 64);
 
-    for (int tile = (int)blockIdx.x * (S2_THREADS / 64) + wave; tile < ntiles; tile += nwaves) {
+    // A tile's metadata (candidate words, passage offsets) is requested one tile ahead of its use.
+    int tile = (int)blockIdx.x * (S2_THREADS / 64) + wave;
+    uint32_t cword_n = 0u;
+    int64_t olane_n = 0, oend_n = 0;
+    auto request_meta = [&](int t) {
+        if (t < ntiles) {  // uniform
+            const int64_t p0n = (int64_t)t * S2W_PASS;
+            const int tpn = (int)(P - p0n < S2W_PASS ? P - p0n : S2W_PASS);
+            const int64_t win = (p0n >> 5) + (lane >> 5);
+            cword_n = (lane < tpn && win < cand_words) ? cb[win] : 0u;
+            olane_n = doc_offsets[p0n + (lane <= tpn ? lane : tpn)];
+            oend_n = doc_offsets[p0n + tpn];
+        }
+    };
+    request_meta(tile);
+    for (; tile < ntiles; tile += nwaves) {
         const int64_t p0 = (int64_t)tile * S2W_PASS;
         const int tp = (int)(P - p0 < S2W_PASS ? P - p0 : S2W_PASS);
-        const int64_t wi = (p0 >> 5) + (lane >> 5);
-        const uint32_t cword = (lane < tp && wi < cand_words) ? cb[wi] : 0u;
+        const uint32_t cword = cword_n;
+        const int64_t o_lane = olane_n, o_end = oend_n;
+        request_meta(tile + nwaves);
         const bool cand = lane < tp && ((cword >> (lane & 31)) & 1u);
-        const bool any_cand = __ballot(cand) != 0ull;  // uniform
+        const unsigned long long candm = __ballot(cand);
+        if (candm == 0ull) {  // (uniform) no candidate here: only the empty-bag words are cleared
+            const int64_t wi = (p0 >> 5) + (lane >> 5);
+            if ((lane & 31) == 0 && wi < cand_words) eb[wi] = 0u;
+            continue;
+        }
         uint64_t set = 0;  // bit s = slot s occurs in my passage; bit 0 collects the pruned tokens
 
-        if (any_cand) {
-            // token range of my passage relative to the tile's first token
-            const int64_t o0 = doc_offsets[p0];
-            const int64_t o_lane = doc_offsets[p0 + (lane <= tp ? lane : tp)];
-            int64_t r = o_lane - o0;
-            const int my_lo = r > 0x7FFFFFFFll ? 0x7FFFFFFF : (int)r;
-            int my_hi = __shfl_down(my_lo, 1);
-            if (lane == 63) {  // lane 63 has no right neighbour: its end is the tile's end
-                r = doc_offsets[p0 + tp] - o0;
-                my_hi = r > 0x7FFFFFFFll ? 0x7FFFFFFF : (int)r;
-            }
-            if (lane >= tp) my_hi = my_lo;
+        // token range of my passage relative to the tile's first token
+        const int64_t o0 = __shfl(o_lane, 0);
+        int64_t r = o_lane - o0;
+        const int my_lo = r > 0x7FFFFFFFll ? 0x7FFFFFFF : (int)r;
+        int my_hi = __shfl_down(my_lo, 1);
+        if (lane == 63) {  // lane 63 has no right neighbour: its end is the tile's end
+            r = o_end - o0;
+            my_hi = r > 0x7FFFFFFFll ? 0x7FFFFFFF : (int)r;
+        }
+        if (lane >= tp) my_hi = my_lo;
 
-            int ps = 0;
-            while (ps < tp) {  // ps, fit, pe are uniform; each round advances ps by at least one
-                const int base = s2_uniform(__shfl(my_lo, ps));
-                const int fit = s2_uniform(__popcll(__ballot(lane >= ps && lane < tp && my_hi - base <= S2W_CAP)));
-                if (fit == 0) {
-                    // a single passage longer than the staging buffer: its lane folds it straight from global memory
-                    if (lane == ps && cand) {
-                        for (int64_t j = o0 + my_lo; j < o0 + my_hi; ++j) {
-                            const uint32_t sl = s2_lookup(htab, (uint32_t)codes[j], hsh);
-                            set |= 1ull << sl;
-                        }
-                    }
-                    ps += 1;
-                } else {
-                    const int pe = ps + fit;
-                    const int end = s2_uniform(__shfl(my_hi, pe - 1));
-                    const int64_t g0 = o0 + base;   // first token of the round
-                    const int64_t a0 = g0 & ~31ll;  // start of its 128-byte line
-                    const int shift = (int)(g0 - a0);
-                    const int nchunk = (shift + (end - base) + 31) >> 5;
-                    const bool mine = lane >= ps && lane < pe && cand;
-                    if (lane < (nchunk + 31) / 32) linebits[lane] = 0u;
-                    s2_wave_sync();
-                    if (mine && my_hi > my_lo) {
-                        const int c0 = (my_lo - base + shift) >> 5, c1 = (my_hi - 1 - base + shift) >> 5;
-                        for (int c = c0; c <= c1; ++c) atomicOr(&linebits[c >> 5], 1u << (c & 31));
-                    }
-                    s2_wave_sync();
-                    // stage one byte per token: the slot of its centroid (0 = pruned).  Four tokens per lane and
-                    // item, eight items in flight per lane.
-                    const int nitem = nchunk * 8;
-                    uint32_t hit = 0;
-                    for (int it0 = 0; it0 < nitem; it0 += 64 * 8) {  // uniform trip count
-                        int4 v[8];
-                        bool ok[8];
-#pragma unroll
-                        for (int u = 0; u < 8; ++u) {
-                            const int it = it0 + 64 * u + lane;
-                            const int c = it >> 3;
-                            ok[u] = it < nitem && ((linebits[c >> 5] >> (c & 31)) & 1u) && a0 + 4ll * it + 3 < N;
-                            v[u] = make_int4(-1, -1, -1, -1);
-                            if (ok[u]) v[u] = *reinterpret_cast<const int4 *>(codes + a0 + 4ll * it);
-                        }
-#pragma unroll
-                        for (int u = 0; u < 8; ++u) {
-                            if (ok[u]) {
-                                const uint32_t packed = s2_lookup(htab, (uint32_t)v[u].x, hsh) |
-                                                        (s2_lookup(htab, (uint32_t)v[u].y, hsh) << 8) |
-                                                        (s2_lookup(htab, (uint32_t)v[u].z, hsh) << 16) |
-                                                        (s2_lookup(htab, (uint32_t)v[u].w, hsh) << 24);
-                                *reinterpret_cast<uint32_t *>(stage + 4 * (it0 + 64 * u + lane)) = packed;
-                                hit |= packed;
-                            }
-                        }
-                    }
-                    // the one item that straddles the end of the code array (tokens past N belong to no passage)
-                    if (a0 + 4ll * nitem > N) {
-                        const int64_t it = (N - a0) >> 2;
-                        if (lane < 4 && it < nitem && a0 + 4 * it + lane < N) {
-                            const uint32_t sl = s2_lookup(htab, (uint32_t)codes[a0 + 4 * it + lane], hsh);
-                            stage[4 * it + lane] = (uint8_t)sl;
-                            hit |= sl;
-                        }
-                    }
-                    s2_wave_sync();
-                    const bool any_hit = __ballot(hit != 0u) != 0ull;  // uniform
-                    if (any_hit && mine) {
-                        const int v0 = my_lo - base + shift, v1 = my_hi - base + shift;
-                        for (int vv = v0; vv < v1; ++vv) {
-                            const uint32_t sl = stage[vv];
-                            set |= 1ull << sl;
-                        }
-                    }
-                    s2_wave_sync();
-                    ps = pe;
+        // Rounds of consecutive whole passages that fit the staging buffer, each starting at a candidate; the passages
+        // after the tile's last candidate are never staged.
+        int ps = s2_uniform(__ffsll((long long)candm) - 1);
+        const int plast = s2_uniform(63 - __clzll((long long)candm));
+        while (ps <= plast) {  // ps, fit, pe are uniform; each round advances ps by at least one
+            const int base = s2_uniform(__shfl(my_lo, ps));
+            const int fit = s2_uniform(__popcll(__ballot(lane >= ps && lane <= plast && my_hi - base <= S2W_CAP)));
+            if (fit == 0) {
+                // a single passage longer than the staging buffer: its lane folds it straight from global memory
+                if (lane == ps)
+                    for (int64_t j = o0 + my_lo; j < o0 + my_hi; ++j) set |= 1ull << s2_lookup(htab, (uint32_t)codes[j], hsh);
+                ps = s2_uniform(s2_next_bit(candm, ps + 1));
+            } else {
+                const int pe = ps + fit;
+                const int end = s2_uniform(__shfl(my_hi, pe - 1));
+                const int64_t g0 = o0 + base;   // first token of the round
+                const int64_t a0 = g0 & ~31ll;  // start of its 128-byte line
+                const int shift = (int)(g0 - a0);
+                const int nchunk = (shift + (end - base) + 31) >> 5;  // 128-byte lines of the round, <= 8 * S2_ITEMS
+                const bool mine = lane >= ps && lane < pe && cand;
+                if (lane < S2_LBWORDS) linebits[lane] = 0u;
+                s2_wave_sync();
+                if (mine && my_hi > my_lo) {
+                    const int c0 = (my_lo - base + shift) >> 5, c1 = (my_hi - 1 - base + shift) >> 5;
+                    for (int c = c0; c <= c1; ++c) atomicOr(&linebits[c >> 5], 1u << (c & 31));
                 }
+                s2_wave_sync();
+                // Stage one byte per token: the slot of its centroid (0 = pruned).  Item u of a lane is the 16 bytes at token
+                // 4 * (64 u + lane), so item u of the wave covers lines 8u .. 8u+7, which is byte u of the line bitmap: a
+                // uniform test skips the item when no candidate touches those lines.  All loads of the round are issued
+                // before the first is used, so a round costs one memory latency.
+                const int nitem = nchunk * 8;
+                const int32_t *__restrict__ src = codes + a0;  // uniform base, 32-bit lane offsets
+                uint32_t need[S2_LBWORDS];
+    #pragma unroll
+                for (int k = 0; k < S2_LBWORDS; ++k) need[k] = (uint32_t)s2_uniform((int)linebits[k]);
+                int4 v[S2_ITEMS];
+                uint32_t okm = 0u;
+    #pragma unroll
+                for (int u = 0; u < S2_ITEMS; ++u) {
+                    v[u] = make_int4(-1, -1, -1, -1);
+                    const uint32_t lines8 = (need[u >> 2] >> (8 * (u & 3))) & 0xFFu;  // uniform
+                    if (lines8 != 0u) {
+                        const int it = 64 * u + lane;
+                        const bool ok = it < nitem && ((lines8 >> (lane >> 3)) & 1u) && a0 + 4ll * it + 3 < N;
+                        if (ok) v[u] = *reinterpret_cast<const int4 *>(src + 4 * it);
+                        okm |= ok ? 1u << u : 0u;
+                    }
+                }
+                uint32_t hit = 0u;
+    #pragma unroll
+                for (int u = 0; u < S2_ITEMS; ++u) {
+                    const uint32_t lines8 = (need[u >> 2] >> (8 * (u & 3))) & 0xFFu;  // uniform
+                    if (lines8 != 0u) {
+                        if ((okm >> u) & 1u) {
+                            const uint32_t packed = s2_lookup(htab, (uint32_t)v[u].x, hsh) |
+                                                    (s2_lookup(htab, (uint32_t)v[u].y, hsh) << 8) |
+                                                    (s2_lookup(htab, (uint32_t)v[u].z, hsh) << 16) |
+                                                    (s2_lookup(htab, (uint32_t)v[u].w, hsh) << 24);
+                            *reinterpret_cast<uint32_t *>(stage + 4 * (64 * u + lane)) = packed;
+                            hit |= packed;
+                        }
+                    }
+                }
+                // the one item that straddles the end of the code array (tokens past N belong to no passage)
+                if (a0 + 4ll * nitem > N) {
+                    const int64_t it = (N - a0) >> 2;
+                    if (lane < 4 && it < nitem && a0 + 4 * it + lane < N) {
+                        const uint32_t sl = s2_lookup(htab, (uint32_t)codes[a0 + 4 * it + lane], hsh);
+                        stage[4 * it + lane] = (uint8_t)sl;
+                        hit |= sl;
+                    }
+                }
+                s2_wave_sync();
+                const bool any_hit = __ballot(hit != 0u) != 0ull;  // uniform
+                if (any_hit && mine) {
+                    const int v0 = my_lo - base + shift, v1 = my_hi - base + shift;
+                    for (int vv = v0; vv < v1; ++vv) set |= 1ull << stage[vv];
+                }
+                s2_wave_sync();
+                ps = s2_uniform(s2_next_bit(candm, pe));
             }
         }
 
-        // score: column maxima of the rows in the set, summed over the query tokens in index order
+        // score: column maxima of the rows in the set, summed over the query tokens in index order; eight query tokens
+        // at a time, so that few registers are live
         const uint64_t members = set & ~1ull;
         const bool empty = members == 0;
         float score = -INFINITY;
         if (cand && !empty) {
-            float acc[QLEN];
-#pragma unroll
-            for (int i = 0; i < QLEN; ++i) acc[i] = -INFINITY;
-            uint64_t rest = members;
-            while (rest) {
-                const int s = __ffsll((long long)rest) - 1;
-                rest &= rest - 1;
-                const float4 *row = reinterpret_cast<const float4 *>(Tl + s * S2_TSTRIDE);
-#pragma unroll
-                for (int g = 0; g < QLEN / 4; ++g) {
-                    const float4 rr = row[g];
-                    acc[4 * g] = fmaxf(acc[4 * g], rr.x);
-                    acc[4 * g + 1] = fmaxf(acc[4 * g + 1], rr.y);
-                    acc[4 * g + 2] = fmaxf(acc[4 * g + 2], rr.z);
-                    acc[4 * g + 3] = fmaxf(acc[4 * g + 3], rr.w);
-                }
-            }
             double d = 0.0;
+#pragma unroll 1
+            for (int g = 0; g < QLEN / 8; ++g) {
+                float acc[8];
 #pragma unroll
-            for (int i = 0; i < QLEN; ++i) d += (double)acc[i];
+                for (int i = 0; i < 8; ++i) acc[i] = -INFINITY;
+                uint64_t rest = members;
+                while (rest) {
+                    const int s = __ffsll((long long)rest) - 1;
+                    rest &= rest - 1;
+                    const float4 *row = reinterpret_cast<const float4 *>(Tl + s * S2_TSTRIDE + 8 * g);
+                    const float4 r0 = row[0], r1 = row[1];
+                    acc[0] = fmaxf(acc[0], r0.x);
+                    acc[1] = fmaxf(acc[1], r0.y);
+                    acc[2] = fmaxf(acc[2], r0.z);
+                    acc[3] = fmaxf(acc[3], r0.w);
+                    acc[4] = fmaxf(acc[4], r1.x);
+                    acc[5] = fmaxf(acc[5], r1.y);
+                    acc[6] = fmaxf(acc[6], r1.z);
+                    acc[7] = fmaxf(acc[7], r1.w);
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) d += (double)acc[i];
+            }
             score = (float)d;
         }
-        // emit (all lanes take part in the ballots)
+        // emit: slot p of the key array belongs to candidate p; no counters, no ordering between waves
         const bool live = cand && !empty;
-        const unsigned long long lb = __ballot(live);
-        if (lb != 0ull) {
-            int basek = 0;
-            if (lane == 0) basek = atomicAdd(n_ne + q, __popcll(lb));
-            basek = __shfl(basek, 0);
-            if (live) {
-                keys_out[basek + __popcll(lb & ((1ull << lane) - 1ull))] = plaid_make_key(score, (uint32_t)(p0 + lane));
-                atomicAdd(&hist_q[plaid_s2_bin(score, bin_hi, bin_scale)], 1);
-            }
-        }
+        if (cand) keys_out[p0 + lane] = live ? plaid_make_key(score, (uint32_t)(p0 + lane)) : PLAID_KEY_MAX;
+        if (live) atomicAdd(&hist_q[plaid_s2_bin(score, bin_hi, bin_scale)], 1);
         const unsigned long long eb64 = __ballot(cand && empty);
         if (lane == 0) {
             const int64_t w0 = p0 >> 5;
@@ -368,6 +376,6 @@ void plaid_launch_stage2(hipStream_t st, const float *S, int64_t C, const uint32
     const int64_t gcap = nq >= 16 ? 96 : (nq >= 4 ? 320 : 1280);
     if (gs > gcap) gs = gcap;
     hipLaunchKernelGGL(s2_stream_kernel, dim3((unsigned)gs, nq), dim3(S2_THREADS), 0, st, S, C, keepbits, keep_words, codes, N,
-                       doc_offsets, P, candbits, cand_words, b.meta, b.kept_ids, b.T, keys2, key_stride, b.n_ne, b.hist,
+                       doc_offsets, P, candbits, cand_words, b.meta, b.kept_ids, b.T, keys2, key_stride, b.hist,
                        b.emptybits);
 }

@@ -356,7 +356,6 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     };
     w.zero_base = take(0);
     w.candbits = (uint32_t *)take((size_t)qc * w.cand_words * 4);
-    w.s2.n_ne = (int32_t *)take((size_t)qc * 4);
     w.done = (int32_t *)take((size_t)qc * 4);
     w.s2.hist = (int32_t *)take((size_t)qc * SEL_BINS * 4);
     w.s2.hist1 = (int32_t *)take((size_t)qc * SEL_BINS * 4);
@@ -480,7 +479,7 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
         plaid_launch_stage2(st, w.S, C, w.keepbits, w.keep_words, w.probed, nprobe, w.candbits, w.cand_words, P, ix->N,
                             ix->doc_offsets, ix->codes, n, w.s2, w.keys2, P);
         STAMP();
-        plaid_launch_select2(st, w.keys2, P, n, P, w.cand_words, pl.nd, w.s2, w.sel2, pl.nd, w.n2);
+        plaid_launch_select2(st, w.keys2, P, w.candbits, n, P, w.cand_words, pl.nd, w.s2, w.sel2, pl.nd, w.n2);
         STAMP();
         // stage 3: centroid interaction without pruning (Eq. 3-4), keep ndocs/4
         plaid_launch_ci_list(st, w.S, C, ix->doc_offsets, ix->codes, n, w.sel2, pl.nd, w.n2, pl.nd, w.keys3, pl.nd);

@@ -145,8 +145,7 @@ __device__ __forceinline__ int plaid_s2_bin(float score, float bin_hi, float bin
 
 struct Stage2Buffers {   // all device pointers, leading dimension = query of the chunk
     // zeroed before each chunk
-    int32_t *n_ne;       // [nq]            candidates with a non-empty bag (= keys written)
-    int32_t *hist;       // [nq][SEL_BINS]  their bin histogram
+    int32_t *hist;       // [nq][SEL_BINS]  bin histogram of the valid keys
     int32_t *hist1;      // [nq][SEL_BINS]  digit histogram of an over-long boundary list
     Sel2State *state;    // [nq]
     // no initialisation needed
@@ -157,8 +156,9 @@ struct Stage2Buffers {   // all device pointers, leading dimension = query of th
     uint64_t *blist;     // [nq][P] boundary list after the bin filter
 };
 
-// Eq. 3-5 over every candidate: keys of the non-empty candidates (unordered) into keys2[q], their count and bin
-// histogram, and the bitmap of empty candidates.
+// Eq. 3-5 over every candidate: keys2[q][p] = key of candidate p (invalid key when its bag is empty; slots of
+// 32-passage groups without candidates are left untouched), the bin histogram of the valid keys, and the bitmap
+// of empty candidates.
 void plaid_launch_stage2(hipStream_t st, const float *S, int64_t C, const uint32_t *keepbits, int64_t keep_words,
                          const int32_t *probed, int nprobe, const uint32_t *candbits, int64_t cand_words, int64_t P,
                          int64_t N, const int64_t *doc_offsets, const int32_t *codes, int nq, const Stage2Buffers &b,
@@ -166,8 +166,9 @@ void plaid_launch_stage2(hipStream_t st, const float *S, int64_t C, const uint32
 
 // Best min(m, #candidates) candidates by (score desc, pid asc): from the keys by bin filter (+ digit filter when the
 // boundary bin is over-long), then from the empty candidates in pid order.  keys2 is overwritten (scratch).
-void plaid_launch_select2(hipStream_t st, uint64_t *keys2, int64_t key_stride, int nq, int64_t P, int64_t cand_words,
-                          int32_t m, const Stage2Buffers &b, uint64_t *out, int64_t out_stride, int32_t *out_counts);
+void plaid_launch_select2(hipStream_t st, uint64_t *keys2, int64_t key_stride, const uint32_t *candbits, int nq, int64_t P,
+                          int64_t cand_words, int32_t m, const Stage2Buffers &b, uint64_t *out, int64_t out_stride,
+                          int32_t *out_counts);
 
 // Eq. 3-4 over a key list (stage 3): out_keys[q][j] is the key of the passage of in_keys[q][j].
 void plaid_launch_ci_list(hipStream_t st, const float *S, int64_t C, const int64_t *doc_offsets, const int32_t *codes,

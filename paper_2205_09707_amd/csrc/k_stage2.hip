@@ -20,7 +20,9 @@
 // when its bag is non-empty and the invalid key otherwise (slots of non-candidates are neither
 // written nor read), a histogram of the valid keys' bins for the selection that follows, and a
 // bitmap of the candidates whose bag is empty (score -infinity; they rank last, in passage-id
-// order).  No counters and no atomics with a return value on this path.
+// order).  No counters and no atomics with a return value on this path; a workgroup counts bins
+// in LDS and adds its non-zero bins to the query's histogram once, at its end, so that queries
+// whose passages all share one score (a single surviving centroid) do not queue up on one address.
 #include "plaid_internal.h"
 
 #include <math.h>
@@ -81,7 +83,7 @@ __device__ __forceinline__ void s2_gather_body(int q, const float *__restrict__ 
                                                const uint32_t *__restrict__ candbits, int64_t cand_words, int64_t P,
                                                const int64_t *__restrict__ doc_offsets, const int32_t *__restrict__ codes,
                                                float bin_hi, float bin_scale, uint64_t *__restrict__ keys_out,
-                                               int32_t *__restrict__ hist_q, uint32_t *__restrict__ emptybits)
+                                               int32_t *lhist, uint32_t *__restrict__ emptybits)
 {
     const int lane = threadIdx.x & 63;
     const float *Sq = S + (int64_t)q * C * QLEN;
@@ -114,7 +116,7 @@ __device__ __forceinline__ void s2_gather_body(int q, const float *__restrict__ 
         const bool cand = lane < 32 && ((word >> lane) & 1u);
         const bool live = cand && !my_empty;
         if (cand) keys_out[p0 + lane] = live ? plaid_make_key(my, (uint32_t)(p0 + lane)) : PLAID_KEY_MAX;
-        if (live) atomicAdd(&hist_q[plaid_s2_bin(my, bin_hi, bin_scale)], 1);
+        if (live) atomicAdd(&lhist[plaid_s2_bin(my, bin_hi, bin_scale)], 1);
         const unsigned long long e64 = __ballot(cand && my_empty);
         if (lane == 0) eb[w] = (uint32_t)e64;
     }
@@ -149,6 +151,16 @@ __device__ __forceinline__ int s2_next_bit(unsigned long long m, int from)
     return rest ? __ffsll((long long)rest) - 1 : 64;
 }
 
+// End of a workgroup: its LDS bin counts go to the query's histogram (all threads of the workgroup call this).
+__device__ __forceinline__ void s2_flush_hist(const int32_t *lhist, int32_t *__restrict__ hist_q)
+{
+    __syncthreads();
+    for (int e = threadIdx.x; e < SEL_BINS; e += S2_THREADS) {
+        const int32_t n = lhist[e];
+        if (n) atomicAdd(&hist_q[e], n);
+    }
+}
+
 // Persistent workgroups; wave w of the grid scores the 64-passage tiles w, w + W, w + 2W, ... (lane = passage).
 __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
     const float *__restrict__ S, int64_t C, const uint32_t *__restrict__ keepbits, int64_t keep_words,
@@ -161,18 +173,22 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
     __shared__ uint32_t linebits_all[S2_THREADS / 64][S2_LBWORDS];
     __shared__ uint32_t htab[S2_HASH];
     __shared__ __align__(16) float Tl[(S2_MAX_KEPT + 1) * S2_TSTRIDE];
+    __shared__ int32_t lhist[SEL_BINS];
     const int q = blockIdx.y;
     const int K = s2_uniform(meta[q].K);
     const float bin_hi = meta[q].bin_hi, bin_scale = meta[q].bin_scale;
     uint64_t *keys_out = keys2 + (int64_t)q * key_stride;
     int32_t *hist_q = hist + (int64_t)q * SEL_BINS;
+    const int tid = threadIdx.x, lane = tid & 63;
+    for (int e = tid; e < SEL_BINS; e += S2_THREADS) lhist[e] = 0;
     if (K > S2_MAX_KEPT) {  // too many survivors for slot sets (uniform for the whole workgroup): gather form
+        __syncthreads();
         s2_gather_body(q, S, C, keepbits, keep_words, candbits, cand_words, P, doc_offsets, codes, bin_hi, bin_scale, keys_out,
-                       hist_q, emptybits);
+                       lhist, emptybits);
+        s2_flush_hist(lhist, hist_q);
         return;
     }
     const int hsh = s2_uniform(meta[q].hash_shift);
-    const int tid = threadIdx.x, lane = tid & 63;
     const int wave = s2_uniform(tid >> 6);
     for (int e = tid; e < S2_HASH; e += S2_THREADS) htab[e] = 0xFFFFFFFFu;
     const float *Tq = T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN;
@@ -352,7 +368,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
         // emit: slot p of the key array belongs to candidate p; no counters, no ordering between waves
         const bool live = cand && !empty;
         if (cand) keys_out[p0 + lane] = live ? plaid_make_key(score, (uint32_t)(p0 + lane)) : PLAID_KEY_MAX;
-        if (live) atomicAdd(&hist_q[plaid_s2_bin(score, bin_hi, bin_scale)], 1);
+        if (live) atomicAdd(&lhist[plaid_s2_bin(score, bin_hi, bin_scale)], 1);
         const unsigned long long eb64 = __ballot(cand && empty);
         if (lane == 0) {
             const int64_t w0 = p0 >> 5;
@@ -360,6 +376,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
             if (w0 + 1 < cand_words) eb[w0 + 1] = (uint32_t)(eb64 >> 32);
         }
     }
+    s2_flush_hist(lhist, hist_q);
 }
 
 // ------------------------------------------------------------------ host side

@@ -135,6 +135,13 @@ int plaid_decompress_passages(plaid_index *idx, const int32_t *pids, int32_t n, 
 int plaid_index_info(const plaid_index *idx, int64_t *num_centroids, int64_t *num_passages,
                      int64_t *num_embeddings, int32_t *nbits, int64_t *ivf_len);
 
+/* Which kernel computes S_cq (Eq. 2) for this index: HOST *form = 1 when it is built on the double-precision matrix
+ * instruction, 0 for the vector fused-multiply-add chain.  Both accumulate each score over the dimensions in index
+ * order and give the same bits; the matrix form is used when a check run on the device at the first index creation of
+ * the process confirms that, and the environment variable PLAID_SCQ_FORM=vector|matrix (read at index creation)
+ * overrides the choice (matrix is an error when the check fails). */
+int plaid_get_score_kernel(const plaid_index *idx, int32_t *form);
+
 /* Per-stage GPU time of the most recent plaid_search on this index when stage timing is on
  * (plaid_set_stage_timing(idx, 1)): HOST out_ms[PLAID_NUM_STAGES], summed over the call's query chunks.
  * Turning timing on makes every search synchronise at its end. */

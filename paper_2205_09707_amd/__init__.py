@@ -9,6 +9,7 @@ from .plaid import (  # noqa: F401
     PlaidError,
     load_library,
     plaid_decompress_passages,
+    plaid_get_score_kernel,
     plaid_get_stage_ms,
     plaid_index_free,
     plaid_index_from_view,

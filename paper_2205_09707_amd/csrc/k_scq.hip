@@ -9,12 +9,23 @@
 // values is exact in double, so a chain of fused multiply-adds in that order gives the same bits
 // as "multiply, then add" on any machine -- the scores carry no accumulation-order freedom.
 //
-// Mapping: a workgroup of eight waves owns 64 centroid rows, staged once in LDS with coalesced
+// Two kernels compute the same bits.
+//
+// Matrix form (scq_mfma_kernel): the double-precision matrix instruction D = A(16x4) B(4x16) + C adds its four
+// products to C one after the other, rounding after each, i.e. it IS the chain of fused multiply-adds over four
+// consecutive dimensions; 32 of them in a row walk the 128 dimensions in index order.  A workgroup of four waves
+// owns 128 centroid rows and the 64 token columns of two queries; centroid rows are staged in LDS 32 dimensions at
+// a time with coalesced loads, next to the same 32 dimensions of the queries in operand order, and a wave holds a
+// 32 x 64 block of double accumulators.  That the instruction reproduces the chain is checked once per process on
+// the device (plaid_scq_matrix_form_ok): if it ever did not, the vector form below is used instead.
+//
+// Vector form (scq_fused_kernel): a workgroup of eight waves owns 64 centroid rows, staged once in LDS with coalesced
 // loads; wave g computes query tokens 4g..4g+3 for all 64 rows (lane = centroid, four double
 // accumulators).  The query, pre-converted to double and laid out [token group][dim][4], is
 // uniform across a wave and is fetched through the scalar unit, so the inner loop is one
 // v_fma_f64 per (dimension, token) whose only per-lane operand is the LDS-resident centroid row.
-// The 64x32 tile of results then yields, still in LDS, the row maxima (pruning bits) and each
+//
+// Either way the tile of results then yields, still in LDS, the row maxima (pruning bits) and each
 // token's best centroids of the tile; a one-workgroup-per-query kernel merges the tiles' lists
 // into the probes, their duplicate-free union, and the survivor table.
 #include "plaid_internal.h"
@@ -32,17 +43,25 @@
 #define TAIL_THREADS 1024
 #define TAIL_LANES 32     // lanes of the tail kernel that share one query token
 
-// Clears the workspace region that must start at zero and lays out the queries for scq_fused_kernel:
-// Qd[q][g][t][u] = (double) Q[q][4g + u][t].
-__global__ __launch_bounds__(256) void stage1_prep_kernel(const float *__restrict__ Q, double *__restrict__ Qd, int nq,
-                                                          uint32_t *__restrict__ zero, int64_t zero_words)
+// Clears the workspace region that must start at zero and lays out the queries for the score kernel:
+// vector form   Qd[q][g][t][u] = (double) Q[q][4g + u][t];
+// matrix form   Qm[q][s][h][lane] = Q[q][16h + (lane & 15)][4s + (lane >> 4)]  (the B operand of step s, column tile h).
+__global__ __launch_bounds__(256) void stage1_prep_kernel(const float *__restrict__ Q, void *__restrict__ Qx, int nq,
+                                                          int matrix_form, uint32_t *__restrict__ zero, int64_t zero_words)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < zero_words; i += (int64_t)gridDim.x * blockDim.x)
         zero[i] = 0u;
     for (int q = blockIdx.x; q < nq; q += gridDim.x)
         for (int e = threadIdx.x; e < QLEN * DIM; e += blockDim.x) {
-            const int u = e & 3, t = (e >> 2) & (DIM - 1), g = e >> 9;
-            Qd[(int64_t)q * QLEN * DIM + e] = (double)Q[(int64_t)q * QLEN * DIM + (4 * g + u) * DIM + t];
+            if (matrix_form) {
+                const int lane = e & 63, h = (e >> 6) & 1, s = e >> 7;
+                reinterpret_cast<float *>(Qx)[(int64_t)q * QLEN * DIM + e] =
+                    Q[(int64_t)q * QLEN * DIM + (16 * h + (lane & 15)) * DIM + 4 * s + (lane >> 4)];
+            } else {
+                const int u = e & 3, t = (e >> 2) & (DIM - 1), g = e >> 9;
+                reinterpret_cast<double *>(Qx)[(int64_t)q * QLEN * DIM + e] =
+                    (double)Q[(int64_t)q * QLEN * DIM + (4 * g + u) * DIM + t];
+            }
         }
 }
 
@@ -323,6 +342,240 @@ __global__ __launch_bounds__(SCQ_THREADS) void scq_fused_kernel(const float *__r
 
 }
 
+
+// ------------------------------------------------------------------ matrix form
+typedef double scq_double4 __attribute__((ext_vector_type(4)));
+#define SM_THREADS 256
+#define SM_RT 2                      // 16-row tiles per wave
+#define SM_ROWS (4 * 16 * SM_RT)     // centroid rows per workgroup
+#define SM_KC 32                     // dimensions staged at a time
+#define SM_ASTRIDE 36                // floats per staged row chunk: the 64 operand reads of a step hit 64 banks
+#define SM_TSTRIDE 33                // floats per row of the result tile
+#ifndef SM_MIN_WAVES
+#define SM_MIN_WAVES 4               // waves per SIMD the register allocation leaves room for
+#endif
+
+// Operand and result layout of v_mfma_f64_16x16x4_f64 for lane = 16 g + i: A operand = A[i][g], B operand = B[g][i],
+// result register r = D[4 r + g][i].
+__device__ __forceinline__ scq_double4 scq_mma(double a, double b, scq_double4 c)
+{
+    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+
+template <int NP>
+__device__ __forceinline__ void scq_insert_pair(uint32_t (&bo)[NP], uint32_t (&bi)[NP], uint32_t o, uint32_t id)
+{
+    // callers present ids in ascending order, so a strict comparison keeps the smaller id among equal scores
+    if (o < bo[NP - 1]) {
+#pragma unroll
+        for (int j = NP - 1; j >= 0; --j) {
+            if (o < bo[j]) {
+                if (j + 1 < NP) {
+                    bo[j + 1] = bo[j];
+                    bi[j + 1] = bi[j];
+                }
+                bo[j] = o;
+                bi[j] = id;
+            }
+        }
+    }
+}
+
+// NP as in scq_fused_kernel; NQ = queries per workgroup (1 or 2).  Grid: x = query group, y = row block.
+// partial: [q][token][row block][NP].
+template <int NP, int NQ>
+__global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(const float *__restrict__ Cm, int64_t C,
+                                                              const float *__restrict__ Qm, int nq, float t_cs,
+                                                              float *__restrict__ S, uint32_t *__restrict__ keepbits,
+                                                              int64_t keep_words, uint64_t *__restrict__ partial)
+{
+    constexpr int NPK = NP > 0 ? NP : 1;
+    constexpr int NT = 2 * NQ;  // 16-column tiles
+    constexpr int LIST_FLOATS = 8 * QLEN * NPK * 2;
+    constexpr int ARENA_FLOATS = SM_ROWS * SM_ASTRIDE > SM_ROWS * SM_TSTRIDE + LIST_FLOATS ? SM_ROWS * SM_ASTRIDE
+                                                                                           : SM_ROWS * SM_TSTRIDE + LIST_FLOATS;
+    __shared__ __align__(16) float arena[ARENA_FLOATS];   // staged centroid chunk, later the result tile and the lists
+    __shared__ __align__(16) float Bq[(SM_KC / 4) * NT * 64];    // the chunk's query operands: [step][column tile][lane]
+    static_assert((SM_ROWS * SM_TSTRIDE) % 2 == 0, "list area must be 8-byte aligned");
+    float *tile = arena;
+    uint64_t *lk = reinterpret_cast<uint64_t *>(arena + SM_ROWS * SM_TSTRIDE);  // [8][32][NPK]
+    const int tid = threadIdx.x, lane = tid & 63, li = lane & 15, lg = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q0 = blockIdx.x * NQ;
+    const int64_t c0 = (int64_t)blockIdx.y * SM_ROWS;
+    const int nrows = (int)(C - c0 < SM_ROWS ? C - c0 : SM_ROWS);
+
+    // staging: a chunk is SM_ROWS rows x 32 dims = 8 float4 per row; thread -> rows tid/8 + 32k, float4 column tid%8
+    const int r0 = tid >> 3, c4 = tid & 7;
+    float4 pre[SM_ROWS / 32];
+#pragma unroll
+    for (int k = 0; k < SM_ROWS / 32; ++k) {
+        const int r = r0 + 32 * k;
+        pre[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r < nrows) pre[k] = *reinterpret_cast<const float4 *>(Cm + (c0 + r) * DIM + 4 * c4);
+    }
+    // the queries' operands of a chunk are 8 steps x 2 halves x 64 lanes = 256 float4 per query, one per thread
+    // (zeros for a query past the end)
+    const int bdst = (((tid >> 5) * NT + ((tid >> 4) & 1)) * 64 + 4 * (tid & 15));  // + 2 qi column tiles
+    float4 preb[NQ];
+#pragma unroll
+    for (int qi = 0; qi < NQ; ++qi) {
+        preb[qi] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (q0 + qi < nq) preb[qi] = reinterpret_cast<const float4 *>(Qm + (int64_t)(q0 + qi) * QLEN * DIM)[tid];
+    }
+    scq_double4 acc[SM_RT][NT];
+#pragma unroll
+    for (int m = 0; m < SM_RT; ++m)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[m][t] = scq_double4{0.0, 0.0, 0.0, 0.0};
+    const float *arow = arena + (wave * 16 * SM_RT + li) * SM_ASTRIDE + lg;  // + 16 m rows, + 4 j floats
+    const float *bcol = Bq + lane;
+#pragma unroll 1
+    for (int ch = 0; ch < DIM / SM_KC; ++ch) {
+#pragma unroll
+        for (int k = 0; k < SM_ROWS / 32; ++k)
+            *reinterpret_cast<float4 *>(arena + (r0 + 32 * k) * SM_ASTRIDE + 4 * c4) = pre[k];
+#pragma unroll
+        for (int qi = 0; qi < NQ; ++qi) *reinterpret_cast<float4 *>(Bq + bdst + 2 * qi * 64) = preb[qi];
+        __syncthreads();
+        if (ch + 1 < DIM / SM_KC) {
+#pragma unroll
+            for (int k = 0; k < SM_ROWS / 32; ++k) {
+                const int r = r0 + 32 * k;
+                if (r < nrows) pre[k] = *reinterpret_cast<const float4 *>(Cm + (c0 + r) * DIM + SM_KC * (ch + 1) + 4 * c4);
+            }
+#pragma unroll
+            for (int qi = 0; qi < NQ; ++qi)
+                if (q0 + qi < nq)
+                    preb[qi] = reinterpret_cast<const float4 *>(Qm + (int64_t)(q0 + qi) * QLEN * DIM)[(ch + 1) * SM_THREADS + tid];
+        }
+#pragma unroll
+        for (int j = 0; j < SM_KC / 4; ++j) {
+            double a[SM_RT], b[NT];
+#pragma unroll
+            for (int m = 0; m < SM_RT; ++m) a[m] = (double)arow[16 * m * SM_ASTRIDE + 4 * j];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) b[t] = (double)bcol[(j * NT + t) * 64];
+#pragma unroll
+            for (int m = 0; m < SM_RT; ++m)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[m][t] = scq_mma(a[m], b[t], acc[m][t]);
+        }
+        __syncthreads();  // every wave is done with this chunk: the arena is rewritten next
+    }
+
+    // epilogue, one query at a time through the LDS tile
+#pragma unroll
+    for (int qi = 0; qi < NQ; ++qi) {
+        const int q = q0 + qi;
+        if (q >= nq) break;  // uniform
+#pragma unroll
+        for (int m = 0; m < SM_RT; ++m)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    tile[(wave * 16 * SM_RT + 16 * m + 4 * r + lg) * SM_TSTRIDE + 16 * h + li] = (float)acc[m][2 * qi + h][r];
+        __syncthreads();
+        // scores, coalesced: the tile's rows are contiguous in S
+        for (int e = tid; e < SM_ROWS * (QLEN / 4); e += SM_THREADS) {
+            const int r = e >> 3, k4 = e & 7;
+            if (r < nrows) {
+                const float *tr = tile + r * SM_TSTRIDE + 4 * k4;
+                *reinterpret_cast<float4 *>(S + ((int64_t)q * C + c0 + r) * QLEN + 4 * k4) = make_float4(tr[0], tr[1], tr[2], tr[3]);
+            }
+        }
+        // Eq. 5: pruning bits of the rows (thread = row)
+        if (tid < SM_ROWS) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < QLEN; ++i) mx = fmaxf(mx, tile[tid * SM_TSTRIDE + i]);
+            const unsigned long long b = __ballot(tid < nrows && mx >= t_cs);
+            if ((tid & 63) == 0) {
+                const int64_t w0 = (c0 + tid) >> 5;
+                uint32_t *kb = keepbits + (int64_t)q * keep_words;
+                if (w0 < keep_words) kb[w0] = (uint32_t)b;
+                if (w0 + 1 < keep_words) kb[w0 + 1] = (uint32_t)(b >> 32);
+            }
+        }
+        if (NP > 0) {
+            // Section 4.1: each token's NP best centroids of this tile.  Thread (i, p) ranks rows p, p + 8, ... of column i.
+            const int i = tid & 31, p = tid >> 5;
+            uint32_t bo[NPK], bi[NPK];
+#pragma unroll
+            for (int j = 0; j < NPK; ++j) {
+                bo[j] = 0xFFFFFFFFu;
+                bi[j] = 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int k = 0; k < SM_ROWS / 8; ++k) {
+                const int rr = 8 * k + p;
+                if (rr < nrows) scq_insert_pair<NPK>(bo, bi, plaid_score_to_ord(tile[rr * SM_TSTRIDE + i]), (uint32_t)(c0 + rr));
+            }
+#pragma unroll
+            for (int j = 0; j < NPK; ++j) lk[(p * QLEN + i) * NPK + j] = ((uint64_t)bo[j] << 32) | bi[j];
+            __syncthreads();
+            if (tid < QLEN) {
+                uint64_t best[NPK];
+#pragma unroll
+                for (int j = 0; j < NPK; ++j) best[j] = lk[tid * NPK + j];
+                for (int pp = 1; pp < 8; ++pp)
+#pragma unroll
+                    for (int j = 0; j < NPK; ++j) scq_insert_key<NPK>(best, lk[(pp * QLEN + tid) * NPK + j]);
+                uint64_t *po = partial + (((int64_t)q * QLEN + tid) * gridDim.y + blockIdx.y) * NPK;
+#pragma unroll
+                for (int j = 0; j < NPK; ++j) po[j] = best[j];
+            }
+        }
+        __syncthreads();  // the tile is rewritten for the next query
+    }
+}
+
+// One wave: the matrix instruction chained over 128 dimensions against the chain of fused multiply-adds, on
+// pseudo-random fp32 operands; mismatch[0] counts results whose bits differ.
+__global__ __launch_bounds__(64) void scq_matrix_form_check_kernel(uint32_t seed, int32_t *__restrict__ mismatch)
+{
+    __shared__ float A[16][DIM], B[DIM][16];
+    const int lane = threadIdx.x, li = lane & 15, lg = lane >> 4;
+    uint32_t x = seed * 2654435761u + (uint32_t)lane * 40503u + 12345u;
+    for (int e = lane; e < 16 * DIM; e += 64) {
+        x = x * 1664525u + 1013904223u;
+        (&A[0][0])[e] = (float)(int32_t)(x >> 8) * (1.0f / 8388608.0f) - 1.0f;
+        x = x * 1664525u + 1013904223u;
+        (&B[0][0])[e] = (float)(int32_t)(x >> 8) * (1.0f / 8388608.0f) - 1.0f;
+    }
+    __syncthreads();
+    scq_double4 acc = {0.0, 0.0, 0.0, 0.0};
+    for (int s = 0; s < DIM / 4; ++s) acc = scq_mma((double)A[li][4 * s + lg], (double)B[4 * s + lg][li], acc);
+    int bad = 0;
+    for (int r = 0; r < 4; ++r) {
+        const int row = 4 * r + lg;
+        double c = 0.0;
+        for (int k = 0; k < DIM; ++k) c = fma((double)A[row][k], (double)B[k][li], c);
+        bad += __double_as_longlong(c) != __double_as_longlong(acc[r]) ? 1 : 0;
+    }
+    if (bad) atomicAdd(mismatch, bad);
+}
+
+int plaid_scq_matrix_form_ok(hipStream_t st, int *ok)
+{
+    *ok = 0;
+    int32_t *d = nullptr;
+    hipError_t e = hipMalloc((void **)&d, sizeof(int32_t));
+    if (e != hipSuccess) return (int)e;
+    int32_t h = -1;
+    e = hipMemsetAsync(d, 0, sizeof(int32_t), st);
+    for (uint32_t seed = 1; e == hipSuccess && seed <= 64; ++seed)
+        hipLaunchKernelGGL(scq_matrix_form_check_kernel, dim3(1), dim3(64), 0, st, seed, d);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(&h, d, sizeof(int32_t), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    (void)hipFree(d);
+    if (e != hipSuccess) return (int)e;
+    *ok = h == 0 ? 1 : 0;
+    return 0;
+}
+
 // One workgroup per query: merge the tiles' lists into the probes (rank order), their ascending duplicate-free union,
 // and build the survivor table.  32 lanes share a query token: each folds every 32nd tile list (coalesced: the lists
 // of a token are contiguous), then the 32 partial lists are merged by a shuffle tree inside the wave.
@@ -412,12 +665,23 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
 }
 
 template <int NP>
-static void launch_fused(hipStream_t st, const float *centroids, int64_t C, const double *Qd, int nq, float t_cs, float *S,
-                         uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int nprobe, const Stage1Out &o)
+static void launch_fused(hipStream_t st, const float *centroids, int64_t C, const void *Qx, int matrix_form, int nq, float t_cs,
+                         float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int nprobe, const Stage1Out &o)
 {
-    const unsigned nblk = (unsigned)((C + SCQ_ROWS - 1) / SCQ_ROWS);
-    hipLaunchKernelGGL(scq_fused_kernel<NP>, dim3(nblk, nq), dim3(SCQ_THREADS), 0, st, centroids, C, Qd, t_cs, S, keepbits,
-                       keep_words, partial);
+    unsigned nblk;
+    if (matrix_form) {
+        nblk = (unsigned)((C + SM_ROWS - 1) / SM_ROWS);
+        if (nq == 1)
+            hipLaunchKernelGGL((scq_mfma_kernel<NP, 1>), dim3(1, nblk), dim3(SM_THREADS), 0, st, centroids, C, (const float *)Qx,
+                               nq, t_cs, S, keepbits, keep_words, partial);
+        else
+            hipLaunchKernelGGL((scq_mfma_kernel<NP, 2>), dim3((unsigned)((nq + 1) / 2), nblk), dim3(SM_THREADS), 0, st, centroids,
+                               C, (const float *)Qx, nq, t_cs, S, keepbits, keep_words, partial);
+    } else {
+        nblk = (unsigned)((C + SCQ_ROWS - 1) / SCQ_ROWS);
+        hipLaunchKernelGGL(scq_fused_kernel<NP>, dim3(nblk, nq), dim3(SCQ_THREADS), 0, st, centroids, C, (const double *)Qx, t_cs,
+                           S, keepbits, keep_words, partial);
+    }
     if (NP > 0)
         hipLaunchKernelGGL(stage1_tail_kernel<(NP > 0 ? NP : 1)>, dim3(nq), dim3(TAIL_THREADS), 0, st, S, C, keepbits,
                            keep_words, partial, (int)nblk, nprobe, o);
@@ -430,15 +694,15 @@ size_t plaid_stage1_partial_bytes(int64_t C, int nq, int nprobe)
     return (size_t)nq * ((C + SCQ_ROWS - 1) / SCQ_ROWS) * QLEN * np * 8;
 }
 
-void plaid_launch_stage1(hipStream_t st, const float *centroids, int64_t C, const float *Q, double *Qd, int nq, float t_cs,
-                         int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int32_t *done,
+void plaid_launch_stage1(hipStream_t st, const float *centroids, int64_t C, const float *Q, void *Qd, int matrix_form, int nq,
+                         float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int32_t *done,
                          uint32_t *zero, int64_t zero_words, int32_t *probed, int32_t *uniq, int uniq_stride,
                          int32_t *n_uniq, const Stage2Buffers &s2, void *probe_scratch, size_t probe_scratch_bytes)
 {
     int64_t gz = (zero_words + 256 * 8 - 1) / (256 * 8);
     if (gz < nq) gz = nq;
     if (gz > 1024) gz = 1024;
-    hipLaunchKernelGGL(stage1_prep_kernel, dim3((unsigned)gz), dim3(256), 0, st, Q, Qd, nq, zero, zero_words);
+    hipLaunchKernelGGL(stage1_prep_kernel, dim3((unsigned)gz), dim3(256), 0, st, Q, Qd, nq, matrix_form, zero, zero_words);
     Stage1Out o;
     o.probed = probed;
     o.uniq = uniq;
@@ -447,14 +711,14 @@ void plaid_launch_stage1(hipStream_t st, const float *centroids, int64_t C, cons
     o.meta = s2.meta;
     o.kept_ids = s2.kept_ids;
     o.T = s2.T;
-    if (nprobe == 1) launch_fused<1>(st, centroids, C, Qd, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
-    else if (nprobe == 2) launch_fused<2>(st, centroids, C, Qd, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
-    else if (nprobe <= 4) launch_fused<4>(st, centroids, C, Qd, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+    if (nprobe == 1) launch_fused<1>(st, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+    else if (nprobe == 2) launch_fused<2>(st, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+    else if (nprobe <= 4) launch_fused<4>(st, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
     else if (nprobe <= PLAID_PROBE_FAST_MAX)
-        launch_fused<8>(st, centroids, C, Qd, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+        launch_fused<8>(st, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
     else {
         // large nprobe: scores and pruning bits here, probes through the generic selection, survivor table after it
-        launch_fused<0>(st, centroids, C, Qd, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+        launch_fused<0>(st, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
         plaid_launch_top_nprobe_general(st, S, C, nq, nprobe, probed, uniq, uniq_stride, n_uniq, probe_scratch,
                                         probe_scratch_bytes);
         hipLaunchKernelGGL(stage1_survivor_kernel, dim3(nq), dim3(512), 0, st, S, C, keepbits, keep_words, probed, nprobe, o);

@@ -50,6 +50,7 @@ struct plaid_index {
     size_t ws_bytes = 0;
     int32_t max_chunk = 0;
     int32_t timing = 0;
+    int32_t scq_matrix_form = 0;  // score kernel: 1 = double-precision matrix instruction, 0 = vector FMA chain
     float stage_ms[PLAID_NUM_STAGES] = {0};
     hipEvent_t ev[N_EVENTS] = {nullptr};
 };
@@ -66,6 +67,29 @@ struct DeviceGuard {
         if (prev >= 0) (void)hipSetDevice(prev);
     }
 };
+
+// Which of the two bit-identical score kernels this handle uses.  PLAID_SCQ_FORM=vector|matrix overrides the choice
+// (matrix is refused when the device check fails); the check itself runs once per process and device.
+static int choose_scq_form(plaid_index *ix)
+{
+    static int checked[64] = {0};  // 0 = not yet, 1 = matrix form verified, 2 = not usable
+    const char *env = getenv("PLAID_SCQ_FORM");
+    if (env && !strcmp(env, "vector")) {
+        ix->scq_matrix_form = 0;
+        return PLAID_OK;
+    }
+    if (env && strcmp(env, "matrix")) return fail(PLAID_EINVAL, "PLAID_SCQ_FORM must be 'vector' or 'matrix'");
+    const int slot = ix->device < 64 ? ix->device : 63;
+    if (!checked[slot] || ix->device >= 64) {
+        int ok = 0;
+        const int e = plaid_scq_matrix_form_ok(nullptr, &ok);
+        if (e) return fail(PLAID_EHIP, "score-kernel self check failed: %s", hipGetErrorString((hipError_t)e));
+        checked[slot] = ok ? 1 : 2;
+    }
+    if (env && checked[slot] != 1) return fail(PLAID_EHIP, "PLAID_SCQ_FORM=matrix, but the matrix instruction does not reproduce the FMA chain here");
+    ix->scq_matrix_form = checked[slot] == 1;
+    return PLAID_OK;
+}
 
 static inline size_t a256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -194,6 +218,11 @@ extern "C" int plaid_index_from_view(const plaid_index_view *v, int device, int 
         ix->ivf_offsets = v->ivf_offsets;
         ix->ivf_pids = v->ivf_pids;
     }
+    rc = choose_scq_form(ix);
+    if (rc) {
+        plaid_index_free(ix);
+        return rc;
+    }
     *out = ix;
     return PLAID_OK;
 }
@@ -275,6 +304,13 @@ extern "C" int plaid_index_info(const plaid_index *idx, int64_t *num_centroids, 
     if (num_embeddings) *num_embeddings = idx->N;
     if (nbits) *nbits = idx->nbits;
     if (ivf_len) *ivf_len = idx->ivf_len;
+    return PLAID_OK;
+}
+
+extern "C" int plaid_get_score_kernel(const plaid_index *idx, int32_t *form)
+{
+    if (!idx || !form) return fail(PLAID_EINVAL, "null argument");
+    *form = idx->scq_matrix_form;
     return PLAID_OK;
 }
 
@@ -467,7 +503,7 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
 
         STAMP();
         // stage 1: S_cq (Eq. 2), pruning map (Eq. 5), probes and candidates (Section 4.1)
-        plaid_launch_stage1(st, ix->centroids, C, Qc, w.Qd, n, t_cs, nprobe, w.S, w.keepbits, w.keep_words, w.partial, w.done,
+        plaid_launch_stage1(st, ix->centroids, C, Qc, w.Qd, ix->scq_matrix_form, n, t_cs, nprobe, w.S, w.keepbits, w.keep_words, w.partial, w.done,
                             (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed, w.uniq, w.uniq_stride, w.n_uniq,
                             w.s2, w.probe_scratch, w.probe_scratch_bytes);
         STAMP();

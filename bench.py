@@ -4,9 +4,10 @@
 A step is one pass of the whole path (S_cq, probes, candidates, both centroid-interaction stages,
 decompression + MaxSim, top-k) over the configuration's full query batch, submitted as a single
 plaid_search call with the index and the queries already resident in HBM.  The JSON line also
-carries the batch-1 latency distribution (one query per call), the roofline of the dominant
-kernel (stage-2 centroid interaction, HBM-bound: algorithmic bytes / event-timed duration), and
-the CPU oracle timed on the host cores on a bounded sample of the same queries.
+carries the batch-1 latency distribution (one query per call), the roofline of the kernel that
+takes the largest share of a step (algorithmic work / event-timed duration; the other two large
+kernels are listed beside it), and the CPU oracle timed on the host cores on a bounded sample of
+the same queries.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg3] [--noise literal]
 """
@@ -21,12 +22,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+FP64_MFMA_PEAK_TFLOPS = 78.6   # MI355X published dense fp64 matrix rate (the vector fp64 rate is the same figure)
+FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
 
-# HBM bytes per launch of the stage-2 kernel (64 queries), from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of this
-# file, each scaled by the counter's reading on a 1 GiB device copy (fetch reads half the bytes: x2; write: x1).
-# Source and date of every figure: profiles/s2_stream_<config>_<noise>.txt.  None = not measured.
+# HBM bytes per launch (64 queries) of each kernel, from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of this file,
+# each scaled by the counter's reading on a 1 GiB device copy (fetch reads half the bytes: x2; write: x1).
+# Source of every figure: the profiles/ summary named here.  Missing = not measured (reported as null).
 MEASURED_TRAFFIC_PER_LAUNCH = {
-    ("cfg3", "literal"): int((980377.8 * 2.0 + 11660.3 * 1.0) * 1024),
+    # (config, noise, stage): bytes
 }
 
 
@@ -34,24 +37,34 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_stage2_bytes(pl, idx, w_dev, Q, params):
-    """Sum over queries of (8 bytes of passage offsets + 4 bytes per token code) over the candidate passages:
-    what the pruned centroid interaction must read (codes of every candidate, Eq. 3-5)."""
+def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
+    """What the method must move, from the library's own candidate and survivor lists.
+    Stage 2 (Eq. 3-5): per candidate passage 8 bytes of offsets + 4 bytes per token code.
+    Stage 4 (Section 4.5, Eq. 1): per surviving passage 8 bytes of offsets and per token its 4-byte code, its packed
+    residual (16 * nbits bytes) and the 128-byte S_cq row that carries the centroid's share of the dot products."""
     import torch
     nprobe, t_cs, ndocs, k = params
     lens = (w_dev.doc_offsets[1:] - w_dev.doc_offsets[:-1])
-    total = 0
+    s2 = 0
+    s4 = 0
+    s4_tokens = 0
     ncand = []
     step = 64   # the library's chunk size, so that these launches look like the timed ones to a profiler
     for q0 in range(0, Q.shape[0], step):
-        _, _, b = pl.plaid_search_debug(idx, Q[q0:q0 + step], nprobe, t_cs, ndocs, k, want=("cand", "n_cand"))
+        _, _, b = pl.plaid_search_debug(idx, Q[q0:q0 + step], nprobe, t_cs, ndocs, k,
+                                        want=("cand", "n_cand", "sel3_ids", "n3"))
         torch.cuda.synchronize()
         for j in range(b["cand"].shape[0]):
             n = int(b["n_cand"][j])
             c = b["cand"][j, :n].long()
-            total += 8 * n + 4 * int(lens[c].sum())
+            s2 += 8 * n + 4 * int(lens[c].sum())
             ncand.append(n)
-    return total, ncand
+            n3 = int(b["n3"][j])
+            t = int(lens[b["sel3_ids"][j, :n3].long()].sum())
+            s4_tokens += t
+            s4 += 8 * n3 + t * (4 + 16 * cfg.nbits + 128)
+    return {"stage2_bytes": s2, "stage4_bytes": s4, "stage4_tokens": s4_tokens,
+            "mean_candidates": float(sum(ncand)) / max(1, len(ncand))}
 
 
 def main():
@@ -149,23 +162,44 @@ def main():
     log(f"[bench] batch-1 latency over {nlat} queries (best of 3 trials): p50 {np.percentile(lat, 50):.4f} ms, "
         f"p99 {np.percentile(lat, 99):.4f} ms, mean {lat.mean():.4f} ms; host enqueue p50 {np.percentile(enq, 50):.4f} ms")
 
-    # ---- roofline of the dominant kernel (stage-2 centroid interaction over all candidates)
+    # ---- rooflines of the three large kernels; the one with the largest share of the step is the headline
     roofline = None
+    rooflines = {}
     if not args.no_roofline:
-        alg_bytes, ncand = algorithmic_stage2_bytes(pl, idx, w, Q, params)
-        t_s2 = stage_ms["stage2_ci"] * 1e-3
-        achieved = alg_bytes / t_s2 / 1e9 if t_s2 > 0 else 0.0
-        roofline = {"bound": "hbm", "kernel": "stage-2 centroid interaction (Eq. 3-5) over all candidates",
-                    "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": MEASURED_TRAFFIC_PER_LAUNCH.get((cfg.name, args.noise)),
-                    "algorithmic_bytes_per_step": alg_bytes, "kernel_ms_per_step": round(stage_ms["stage2_ci"], 4),
-                    "launches_per_step": launches, "queries_per_launch": CHUNK,
-                    "algorithmic_bytes_per_launch": alg_bytes // launches,
-                    "kernel_ms_per_launch": round(stage_ms["stage2_ci"] / launches, 4),
-                    "mean_candidates_per_query": float(np.mean(ncand))}
-        log(f"[bench] stage 2: {alg_bytes / 1e6:.1f} MB algorithmic per step in {stage_ms['stage2_ci']:.3f} ms "
-            f"-> {achieved:.0f} GB/s ({achieved / HBM_PEAK_GBS:.1%} of {HBM_PEAK_GBS:.0f})")
+        work = algorithmic_work(pl, idx, w, Q, params, cfg)
+
+        def entry(stage, kernel, bound, amount, unit_scale, peak, unit, extra):
+            t = stage_ms[stage] * 1e-3
+            ach = amount / t / unit_scale if t > 0 else 0.0
+            e = {"bound": bound, "kernel": kernel, "achieved": round(ach, 1), "peak": peak, "unit": unit,
+                 "frac": round(ach / peak, 4), "traffic": MEASURED_TRAFFIC_PER_LAUNCH.get((cfg.name, args.noise, stage)),
+                 "kernel_ms_per_step": round(stage_ms[stage], 4), "launches_per_step": launches, "queries_per_launch": CHUNK,
+                 "kernel_ms_per_launch": round(stage_ms[stage] / launches, 4)}
+            e.update(extra)
+            log(f"[bench] {stage}: {ach:.1f} {unit} = {ach / peak:.1%} of {peak:g} ({bound}); {stage_ms[stage]:.3f} ms/step")
+            return e
+
+        scq_flop = 2.0 * cfg.C * 128 * 32 * nq
+        rooflines["scq"] = entry(
+            "scq", "S_cq = C.Q^T (Eq. 2) in double through the fp64 matrix instruction" if pl.plaid_get_score_kernel(idx)
+            else "S_cq = C.Q^T (Eq. 2), fp64 fused multiply-add chain", "mfma", scq_flop, 1e12, FP64_MFMA_PEAK_TFLOPS, "TFLOP/s",
+            {"algorithmic_flop_per_step": scq_flop, "algorithmic_flop_per_launch": scq_flop / launches, "dtype": "f64"})
+        rooflines["stage2_ci"] = entry(
+            "stage2_ci", "stage-2 centroid interaction (Eq. 3-5) over all candidates", "hbm", work["stage2_bytes"], 1e9,
+            HBM_PEAK_GBS, "GB/s",
+            {"algorithmic_bytes_per_step": work["stage2_bytes"], "algorithmic_bytes_per_launch": work["stage2_bytes"] // launches,
+             "mean_candidates_per_query": work["mean_candidates"]})
+        rooflines["stage4_maxsim"] = entry(
+            "stage4_maxsim", "stage-4 decompression + MaxSim (Section 4.5, Eq. 1) over the ndocs/4 survivors", "hbm",
+            work["stage4_bytes"], 1e9, HBM_PEAK_GBS, "GB/s",
+            {"algorithmic_bytes_per_step": work["stage4_bytes"], "algorithmic_bytes_per_launch": work["stage4_bytes"] // launches,
+             "tokens_per_step": work["stage4_tokens"],
+             "fp32_mfma_tflops": round(work["stage4_tokens"] * 8192 / (stage_ms["stage4_maxsim"] * 1e-3) / 1e12, 2),
+             "fp32_mfma_frac": round(work["stage4_tokens"] * 8192 / (stage_ms["stage4_maxsim"] * 1e-3) / 1e12
+                                     / FP32_MFMA_PEAK_TFLOPS, 4)})
+        dominant = max(rooflines, key=lambda s: stage_ms[s])
+        roofline = dict(rooflines[dominant])
+        roofline["stage"] = dominant
 
     # ---- CPU oracle on a bounded sample of the same queries (rank 0, N = 1)
     cpu = None
@@ -188,16 +222,17 @@ def main():
     line = {
         "metric": "queries_per_sec", "value": round(qps, 2), "unit": "queries/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64/f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name} ({args.noise} noise): C={cfg.C} centroids, P={cfg.P} passages, N={w.N} "
                                f"embeddings, {cfg.nbits}-bit residuals, {nq} queries x 32 x 128",
                    "nprobe": cfg.nprobe, "t_cs": cfg.t_cs, "ndocs": cfg.ndocs, "k": cfg.k,
-                   "queries_per_step": nq, "index_generated_on": "cuda"},
+                   "queries_per_step": nq, "index_generated_on": "cuda",
+                   "arithmetic": "S_cq and the centroid-interaction sums accumulate in f64 (stored f32); MaxSim in f32"},
         "latency_batch1_ms": {"p50": round(float(np.percentile(lat, 50)), 4), "p99": round(float(np.percentile(lat, 99)), 4),
                               "mean": round(float(lat.mean()), 4), "queries": int(nlat), "trials": 3, "host_enqueue_p50": round(float(np.percentile(enq, 50)), 4),
                               "qps": round(1e3 / float(lat.mean()), 1) if nlat else None},
         "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items()},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "roofline_by_stage": rooflines or None, "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
 

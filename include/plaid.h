@@ -93,7 +93,8 @@ int plaid_index_load(const char *path, int device, plaid_index **out);
 
 /* Build a handle from caller memory.  copy = 1: the arrays (host or device) are copied into
  * library-owned device memory.  copy = 0: requires on_device = 1; the library keeps the caller's device
- * pointers and the caller must keep them alive and unchanged until plaid_index_free.  Host-side views are
+ * pointers (centroids, codes and residuals must then be aligned to 16 bytes, else PLAID_EINVAL) and the caller
+ * must keep them alive and unchanged until plaid_index_free.  Host-side views are
  * validated (offsets monotone, codes and pids in range); device-side views are validated for sizes only. */
 int plaid_index_from_view(const plaid_index_view *view, int device, int copy, plaid_index **out);
 
@@ -145,9 +146,10 @@ int plaid_get_score_kernel(const plaid_index *idx, int32_t *form);
 /* Per-stage GPU time of the most recent plaid_search on this index when stage timing is on
  * (plaid_set_stage_timing(idx, 1)): HOST out_ms[PLAID_NUM_STAGES], summed over the call's query chunks.
  * Turning timing on makes every search synchronise at its end. */
-#define PLAID_NUM_STAGES 8
-/* stage order: 0 S_cq+prune map, 1 top-nprobe, 2 candidate union, 3 stage-2 interaction, 4 select ndocs,
- * 5 stage-3 interaction+select, 6 stage-4 decompress+MaxSim, 7 top-k */
+#define PLAID_NUM_STAGES 10
+/* stage order: 0 workspace clearing + query layout, 1 S_cq + pruning map (Eq. 2, 5), 2 top-nprobe, probe union and
+ * table of surviving centroids, 3 candidate union (Section 4.1), 4 stage-2 interaction (Eq. 3-5), 5 select ndocs,
+ * 6 stage-3 interaction (Eq. 3-4), 7 select ndocs/4, 8 stage-4 decompress + MaxSim (Section 4.5, Eq. 1), 9 top-k */
 int plaid_set_stage_timing(plaid_index *idx, int32_t on);
 int plaid_get_stage_ms(const plaid_index *idx, float *out_ms);
 

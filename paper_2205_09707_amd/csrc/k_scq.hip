@@ -665,12 +665,13 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
 }
 
 template <int NP>
-static void launch_fused(hipStream_t st, const float *centroids, int64_t C, const void *Qx, int matrix_form, int nq, float t_cs,
-                         float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int nprobe, const Stage1Out &o)
+static void launch_fused(hipStream_t st, int phases, const float *centroids, int64_t C, const void *Qx, int matrix_form, int nq,
+                         float t_cs, float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int nprobe,
+                         const Stage1Out &o)
 {
-    unsigned nblk;
-    if (matrix_form) {
-        nblk = (unsigned)((C + SM_ROWS - 1) / SM_ROWS);
+    const unsigned nblk = (unsigned)(matrix_form ? (C + SM_ROWS - 1) / SM_ROWS : (C + SCQ_ROWS - 1) / SCQ_ROWS);
+    if (!(phases & PLAID_STAGE1_SCORES)) {
+    } else if (matrix_form) {
         if (nq == 1)
             hipLaunchKernelGGL((scq_mfma_kernel<NP, 1>), dim3(1, nblk), dim3(SM_THREADS), 0, st, centroids, C, (const float *)Qx,
                                nq, t_cs, S, keepbits, keep_words, partial);
@@ -678,11 +679,10 @@ static void launch_fused(hipStream_t st, const float *centroids, int64_t C, cons
             hipLaunchKernelGGL((scq_mfma_kernel<NP, 2>), dim3((unsigned)((nq + 1) / 2), nblk), dim3(SM_THREADS), 0, st, centroids,
                                C, (const float *)Qx, nq, t_cs, S, keepbits, keep_words, partial);
     } else {
-        nblk = (unsigned)((C + SCQ_ROWS - 1) / SCQ_ROWS);
         hipLaunchKernelGGL(scq_fused_kernel<NP>, dim3(nblk, nq), dim3(SCQ_THREADS), 0, st, centroids, C, (const double *)Qx, t_cs,
                            S, keepbits, keep_words, partial);
     }
-    if (NP > 0)
+    if (NP > 0 && (phases & PLAID_STAGE1_PROBES))
         hipLaunchKernelGGL(stage1_tail_kernel<(NP > 0 ? NP : 1)>, dim3(nq), dim3(TAIL_THREADS), 0, st, S, C, keepbits,
                            keep_words, partial, (int)nblk, nprobe, o);
 }
@@ -694,15 +694,18 @@ size_t plaid_stage1_partial_bytes(int64_t C, int nq, int nprobe)
     return (size_t)nq * ((C + SCQ_ROWS - 1) / SCQ_ROWS) * QLEN * np * 8;
 }
 
-void plaid_launch_stage1(hipStream_t st, const float *centroids, int64_t C, const float *Q, void *Qd, int matrix_form, int nq,
-                         float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int32_t *done,
+void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int64_t C, const float *Q, void *Qd, int matrix_form,
+                         int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int32_t *done,
                          uint32_t *zero, int64_t zero_words, int32_t *probed, int32_t *uniq, int uniq_stride,
                          int32_t *n_uniq, const Stage2Buffers &s2, void *probe_scratch, size_t probe_scratch_bytes)
 {
-    int64_t gz = (zero_words + 256 * 8 - 1) / (256 * 8);
-    if (gz < nq) gz = nq;
-    if (gz > 1024) gz = 1024;
-    hipLaunchKernelGGL(stage1_prep_kernel, dim3((unsigned)gz), dim3(256), 0, st, Q, Qd, nq, matrix_form, zero, zero_words);
+    if (phases & PLAID_STAGE1_PREP) {
+        int64_t gz = (zero_words + 256 * 8 - 1) / (256 * 8);
+        if (gz < nq) gz = nq;
+        if (gz > 1024) gz = 1024;
+        hipLaunchKernelGGL(stage1_prep_kernel, dim3((unsigned)gz), dim3(256), 0, st, Q, Qd, nq, matrix_form, zero, zero_words);
+    }
+    if (!(phases & (PLAID_STAGE1_SCORES | PLAID_STAGE1_PROBES))) return;
     Stage1Out o;
     o.probed = probed;
     o.uniq = uniq;
@@ -711,16 +714,18 @@ void plaid_launch_stage1(hipStream_t st, const float *centroids, int64_t C, cons
     o.meta = s2.meta;
     o.kept_ids = s2.kept_ids;
     o.T = s2.T;
-    if (nprobe == 1) launch_fused<1>(st, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
-    else if (nprobe == 2) launch_fused<2>(st, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
-    else if (nprobe <= 4) launch_fused<4>(st, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+    if (nprobe == 1) launch_fused<1>(st, phases, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+    else if (nprobe == 2) launch_fused<2>(st, phases, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+    else if (nprobe <= 4) launch_fused<4>(st, phases, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
     else if (nprobe <= PLAID_PROBE_FAST_MAX)
-        launch_fused<8>(st, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+        launch_fused<8>(st, phases, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
     else {
         // large nprobe: scores and pruning bits here, probes through the generic selection, survivor table after it
-        launch_fused<0>(st, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
-        plaid_launch_top_nprobe_general(st, S, C, nq, nprobe, probed, uniq, uniq_stride, n_uniq, probe_scratch,
-                                        probe_scratch_bytes);
-        hipLaunchKernelGGL(stage1_survivor_kernel, dim3(nq), dim3(512), 0, st, S, C, keepbits, keep_words, probed, nprobe, o);
+        launch_fused<0>(st, phases, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+        if (phases & PLAID_STAGE1_PROBES) {
+            plaid_launch_top_nprobe_general(st, S, C, nq, nprobe, probed, uniq, uniq_stride, n_uniq, probe_scratch,
+                                            probe_scratch_bytes);
+            hipLaunchKernelGGL(stage1_survivor_kernel, dim3(nq), dim3(512), 0, st, S, C, keepbits, keep_words, probed, nprobe, o);
+        }
     }
 }

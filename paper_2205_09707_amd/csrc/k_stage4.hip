@@ -3,11 +3,14 @@
 // Decompression follows the lookup-table idea of Section 4.5: a packed byte indexes a 256-entry
 // table held in LDS.  The table stores the bucket WEIGHTS of the byte's dimensions (4 for 2-bit,
 // 8 for 1-bit codes) instead of the bucket indices, so one 16-byte LDS read yields four residual
-// values; a reconstructed value is centroid + weight, one fp32 addition, exactly as stored form
-// defines it.  The reconstructed 32-token x 128 tile never leaves registers: each lane decodes
-// the half row of its own passage token and feeds it as the A operand of v_mfma_f32_32x32x2_f32
-// against the query (B operand, 64 VGPRs), giving a 32 passage-token x 32 query-token block of dot
-// products whose column maxima are the MaxSim terms.  One workgroup scores one passage.
+// values.  A reconstructed token is centroid + residual, so its dot product with a query token
+// is S_cq[code][i] (already computed, Eq. 2) plus the residual's dot product: the scoring kernel
+// gathers the 128-byte S_cq row of each token instead of its 512-byte centroid, and the decoded
+// 32-token x 128 residual tile never leaves registers: each lane decodes the half row of its own
+// passage token and feeds it as the A operand of v_mfma_f32_32x32x2_f32 against the query
+// (B operand, 64 VGPRs), giving a 32 passage-token x 32 query-token block whose column maxima,
+// after the S_cq term is added, are the MaxSim terms.  The standalone decompression kernel below
+// produces the reconstructed vectors themselves (centroid + weight, one fp32 addition).
 #include "plaid_internal.h"
 
 #include <math.h>
@@ -41,9 +44,14 @@ __device__ __forceinline__ int table_slot(const uint8_t *__restrict__ r, int qua
     return 2 * r[quad >> 1] + (quad & 1);
 }
 
-template <int NBITS>
-__global__ __launch_bounds__(256) void decompress_maxsim_kernel(
-    const float *__restrict__ Q, const float *__restrict__ centroids, const int64_t *__restrict__ doc_offsets,
+// Passages are scored 32 tokens per step.  Lane = 32 h + r: for the A operand r is the passage token of the step and
+// h the half of each 8-dimension group, for the B operand and the result r is the query token.
+// COOP = false: one wave scores one passage at a time and the waves of the grid stride over the query's list (many
+// passages per wave: throughput).  COOP = true: the four waves of a workgroup share a passage, each taking every
+// fourth step, and combine their maxima in LDS (short lists: latency).
+template <int NBITS, bool COOP>
+__global__ __launch_bounds__(256, 4) void decompress_maxsim_kernel(
+    const float *__restrict__ Q, const float *__restrict__ S, int64_t C, const int64_t *__restrict__ doc_offsets,
     const int32_t *__restrict__ codes, const uint8_t *__restrict__ residuals, const float *__restrict__ weights,
     const uint64_t *__restrict__ in_keys, int64_t in_stride, const int32_t *__restrict__ in_counts,
     uint64_t *__restrict__ out_keys, int64_t out_stride)
@@ -51,67 +59,107 @@ __global__ __launch_bounds__(256) void decompress_maxsim_kernel(
     constexpr int RB = 16 * NBITS;
     __shared__ float4 wlut[256 * (NBITS == 2 ? 1 : 2)];
     __shared__ float wmax[4][QLEN];
-    const int q = blockIdx.y, j = blockIdx.x;
-    if (j >= in_counts[q]) return;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int q = blockIdx.y;
+    const int count = in_counts[q];
+    if ((int)blockIdx.x * (COOP ? 1 : 4) >= count) return;  // uniform for the workgroup
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r32 = lane & 31, h = lane >> 5;
     build_tables<NBITS>(wlut, nullptr, weights, threadIdx.x, 256);
     const float *Qq = Q + (int64_t)q * QLEN * DIM;
+    const float *Sq = S + (int64_t)q * C * QLEN;
     float4 qf[16];
 #pragma unroll
     for (int g = 0; g < 16; ++g) qf[g] = *reinterpret_cast<const float4 *>(Qq + r32 * DIM + 8 * g + 4 * h);
-    const uint32_t pid = (uint32_t)(in_keys[(int64_t)q * in_stride + j] & 0xFFFFFFFFu);
-    const int64_t t0 = doc_offsets[pid];
-    const int len = (int)(doc_offsets[pid + 1] - t0);
     __syncthreads();
 
-    float m = -INFINITY;  // running maximum for query token r32 over this wave's passage tokens
-    for (int tile = wave; tile * 32 < len; tile += 4) {
-        const int row = tile * 32 + r32;  // this lane's passage token
-        const bool valid = row < len;
-        const int64_t tok = t0 + (valid ? row : 0);
-        const float *crow = centroids + (int64_t)codes[tok] * DIM;
-        const uint8_t *rrow = residuals + tok * RB;
-        floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    for (int j = COOP ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave; j < count; j += (int)gridDim.x * (COOP ? 1 : 4)) {
+        // passage id, first token and length are the same in every lane: kept in scalar registers, so that the loops
+        // below run with the whole wave active
+        const uint32_t pid = (uint32_t)__builtin_amdgcn_readfirstlane((int)(in_keys[(int64_t)q * in_stride + j] & 0xFFFFFFFFu));
+        const int64_t t0v = doc_offsets[pid];
+        const int64_t t0 = ((int64_t)__builtin_amdgcn_readfirstlane((int)(t0v >> 32)) << 32) |
+                           (uint32_t)__builtin_amdgcn_readfirstlane((int)(t0v & 0xFFFFFFFFll));
+        const int len = __builtin_amdgcn_readfirstlane((int)(doc_offsets[pid + 1] - t0v));
+        float m = -INFINITY;  // running maximum for query token r32 over the rows this lane sees
+        for (int base = COOP ? 32 * wave : 0; base < len; base += COOP ? 128 : 32) {
+            const int row = base + r32;  // this lane's passage token
+            const int64_t tok = t0 + (row < len ? row : len - 1);
+            const int32_t code = codes[tok];
+            // the token's packed residual: both halves of the wave read all of it, each uses every other byte
+            const uint4 *rp = reinterpret_cast<const uint4 *>(residuals + tok * RB);
+            uint32_t rw[RB / 4];
+            {
+                const uint4 v0 = rp[0];
+                rw[0] = v0.x, rw[1] = v0.y, rw[2] = v0.z, rw[3] = v0.w;
+                if (NBITS == 2) {
+                    const uint4 v1 = rp[1];
+                    rw[4] = v1.x, rw[5] = v1.y, rw[6] = v1.z, rw[7] = v1.w;
+                }
+            }
+            floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-        for (int g = 0; g < 16; ++g) {
-            const int quad = 2 * g + h;  // dimensions 8g+4h .. 8g+4h+3
-            const float4 c = *reinterpret_cast<const float4 *>(crow + 4 * quad);
-            const float4 w = wlut[table_slot<NBITS>(rrow, quad)];
-            const float4 a = make_float4(c.x + w.x, c.y + w.y, c.z + w.z, c.w + w.w);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, qf[g].x, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, qf[g].y, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, qf[g].z, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, qf[g].w, acc, 0, 0, 0);
+            for (int g = 0; g < 16; ++g) {
+                // dimensions 8g+4h .. 8g+4h+3: byte 2g+h of a 2-bit code, half h of byte g of a 1-bit code
+                int slot;
+                if (NBITS == 2)
+                    slot = (rw[g >> 1] >> (16 * (g & 1) + 8 * h)) & 0xFF;
+                else
+                    slot = 2 * ((rw[g >> 2] >> (8 * (g & 3))) & 0xFF) + h;
+                const float4 w = wlut[slot];
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.x, qf[g].x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.y, qf[g].y, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.z, qf[g].z, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.w, qf[g].w, acc, 0, 0, 0);
+            }
+            // acc[v] = (residual of passage token base + 8 (v/4) + 4h + v%4) . (query token r32); the centroid's share
+            // of the dot product is S_cq[code][r32]
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rr = 8 * (v >> 2) + 4 * h + (v & 3);
+                const int32_t cv = __shfl(code, rr);
+                const float sv = Sq[(int64_t)cv * QLEN + r32];
+                if (base + rr < len) m = fmaxf(m, acc[v] + sv);
+            }
         }
-        // acc[v] = (passage token tile*32 + 8*(v/4) + 4h + v%4) . (query token r32)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-            if (tile * 32 + 8 * (v >> 2) + 4 * h + (v & 3) < len) m = fmaxf(m, acc[v]);
-    }
-    m = fmaxf(m, __shfl_xor(m, 32));
-    if (h == 0) wmax[wave][r32] = m;
-    __syncthreads();
-    if (wave == 0) {
-        float mm = fmaxf(fmaxf(wmax[0][r32], wmax[1][r32]), fmaxf(wmax[2][r32], wmax[3][r32]));
-        double d = (double)mm;
+        m = fmaxf(m, __shfl_xor(m, 32));
+        if (COOP) {  // j, len are the same in the four waves
+            if (h == 0) wmax[wave][r32] = m;
+            __syncthreads();
+            m = fmaxf(fmaxf(wmax[0][r32], wmax[1][r32]), fmaxf(wmax[2][r32], wmax[3][r32]));
+            __syncthreads();
+        }
+        double d = (double)m;
 #pragma unroll
         for (int o = 1; o < 32; o <<= 1) d += __shfl_xor(d, o);
-        if (lane == 0) out_keys[(int64_t)q * out_stride + j] = plaid_make_key((float)d, pid);
+        if (lane == 0 && (!COOP || wave == 0))
+            out_keys[(int64_t)q * out_stride + j] = plaid_make_key(len > 0 ? (float)d : -INFINITY, pid);
     }
 }
 
-void plaid_launch_decompress_maxsim(hipStream_t st, const float *Q, const float *centroids, const int64_t *doc_offsets,
+void plaid_launch_decompress_maxsim(hipStream_t st, const float *Q, const float *S, int64_t C, const int64_t *doc_offsets,
                                     const int32_t *codes, const uint8_t *residuals, const float *bucket_weights,
                                     int nbits, int nq, const uint64_t *in_keys, int64_t in_stride,
                                     const int32_t *in_counts, int n_upper, uint64_t *out_keys, int64_t out_stride)
 {
-    if (nbits == 2)
-        hipLaunchKernelGGL(decompress_maxsim_kernel<2>, dim3(n_upper, nq), dim3(256), 0, st, Q, centroids, doc_offsets,
-                           codes, residuals, bucket_weights, in_keys, in_stride, in_counts, out_keys, out_stride);
-    else
-        hipLaunchKernelGGL(decompress_maxsim_kernel<1>, dim3(n_upper, nq), dim3(256), 0, st, Q, centroids, doc_offsets,
-                           codes, residuals, bucket_weights, in_keys, in_stride, in_counts, out_keys, out_stride);
+    if (n_upper <= 0 || nq <= 0) return;
+    // few passages in all (short lists of few queries): a workgroup per passage; otherwise waves stride over the lists,
+    // several passages each, so that the per-workgroup set-up (table, query operands) is paid rarely
+    const bool coop = (int64_t)n_upper * nq <= 2048;
+    int gx = coop ? n_upper : (n_upper + 3) / 4;
+    const int cap = coop ? 2048 : (nq >= 16 ? 16 : (nq >= 4 ? 64 : 512));
+    if (gx > cap) gx = cap;
+#define PLAID_S4_LAUNCH(NB, CO)                                                                                           \
+    hipLaunchKernelGGL((decompress_maxsim_kernel<NB, CO>), dim3(gx, nq), dim3(256), 0, st, Q, S, C, doc_offsets, codes,       \
+                       residuals, bucket_weights, in_keys, in_stride, in_counts, out_keys, out_stride)
+    if (nbits == 2) {
+        if (coop) PLAID_S4_LAUNCH(2, true);
+        else PLAID_S4_LAUNCH(2, false);
+    } else {
+        if (coop) PLAID_S4_LAUNCH(1, true);
+        else PLAID_S4_LAUNCH(1, false);
+    }
+#undef PLAID_S4_LAUNCH
 }
 
 // ------------------------------------------------------------------ decompression alone (parity of the codec)

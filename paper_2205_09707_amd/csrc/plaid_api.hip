@@ -161,6 +161,8 @@ extern "C" int plaid_index_from_view(const plaid_index_view *v, int device, int 
         return fail(PLAID_EINVAL, "null array in view");
     if (v->num_embeddings > 0 && (!v->codes || !v->residuals)) return fail(PLAID_EINVAL, "null codes/residuals");
     if (!copy && !v->on_device) return fail(PLAID_EINVAL, "copy = 0 requires device arrays");
+    if (!copy && ((((uintptr_t)v->centroids) | ((uintptr_t)v->codes) | ((uintptr_t)v->residuals)) & 15))
+        return fail(PLAID_EINVAL, "copy = 0 requires centroids, codes and residuals aligned to 16 bytes");
     int rc = check_sizes(v->dim, v->nbits, v->num_centroids, v->num_passages, v->num_embeddings, 0);
     if (rc) return rc;
     const int64_t C = v->num_centroids, P = v->num_passages, N = v->num_embeddings;
@@ -503,11 +505,12 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
 
         STAMP();
         // stage 1: S_cq (Eq. 2), pruning map (Eq. 5), probes and candidates (Section 4.1)
-        plaid_launch_stage1(st, ix->centroids, C, Qc, w.Qd, ix->scq_matrix_form, n, t_cs, nprobe, w.S, w.keepbits, w.keep_words, w.partial, w.done,
-                            (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed, w.uniq, w.uniq_stride, w.n_uniq,
-                            w.s2, w.probe_scratch, w.probe_scratch_bytes);
-        STAMP();
-        STAMP();
+        for (int phase = PLAID_STAGE1_PREP; phase <= PLAID_STAGE1_PROBES; phase <<= 1) {
+            plaid_launch_stage1(st, phase, ix->centroids, C, Qc, w.Qd, ix->scq_matrix_form, n, t_cs, nprobe, w.S, w.keepbits,
+                                w.keep_words, w.partial, w.done, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed,
+                                w.uniq, w.uniq_stride, w.n_uniq, w.s2, w.probe_scratch, w.probe_scratch_bytes);
+            STAMP();
+        }
         plaid_launch_ivf_union(st, w.uniq, w.n_uniq, w.uniq_stride, ix->ivf_offsets, ix->ivf_pids, n, w.candbits,
                                w.cand_words);
         STAMP();
@@ -519,10 +522,11 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
         STAMP();
         // stage 3: centroid interaction without pruning (Eq. 3-4), keep ndocs/4
         plaid_launch_ci_list(st, w.S, C, ix->doc_offsets, ix->codes, n, w.sel2, pl.nd, w.n2, pl.nd, w.keys3, pl.nd);
+        STAMP();
         plaid_launch_select(st, w.keys3, pl.nd, w.n2, n, pl.nd, pl.m3, w.sel3, pl.m3, w.n3, 0, sc3, 0);
         STAMP();
         // stage 4: decompression (Section 4.5) + exact MaxSim (Eq. 1), best k
-        plaid_launch_decompress_maxsim(st, Qc, ix->centroids, ix->doc_offsets, ix->codes, ix->residuals, ix->weights,
+        plaid_launch_decompress_maxsim(st, Qc, w.S, C, ix->doc_offsets, ix->codes, ix->residuals, ix->weights,
                                        ix->nbits, n, w.sel3, pl.m3, w.n3, pl.m3, w.keys4, pl.m3);
         STAMP();
         if (pl.m3 <= SEL_SORT_CAP) {

@@ -94,8 +94,13 @@ SelScratch plaid_select_scratch_carve2(void *zero_base, void *body_base, int nse
 // double-precision matrix instruction; plaid_scq_matrix_form_ok tells (once per process) whether that instruction
 // adds its four products in index order with a rounding after each, which is what makes the two forms bit-identical.
 int plaid_scq_matrix_form_ok(hipStream_t st, int *ok);  // returns a hipError_t value
-void plaid_launch_stage1(hipStream_t st, const float *centroids, int64_t C, const float *Q, void *Qx, int matrix_form, int nq,
-                         float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int32_t *done,
+// phases: which of the three steps to enqueue (the caller may time them apart): PREP = clear + query layout,
+// SCORES = the score kernel (S, keep bits, per-tile lists), PROBES = probes, their union and the survivor table.
+#define PLAID_STAGE1_PREP 1
+#define PLAID_STAGE1_SCORES 2
+#define PLAID_STAGE1_PROBES 4
+void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int64_t C, const float *Q, void *Qx, int matrix_form,
+                         int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int32_t *done,
                          uint32_t *zero, int64_t zero_words, int32_t *probed, int32_t *uniq, int uniq_stride,
                          int32_t *n_uniq, const struct Stage2Buffers &s2, void *probe_scratch, size_t probe_scratch_bytes);
 size_t plaid_stage1_partial_bytes(int64_t C, int nq, int nprobe);
@@ -179,8 +184,8 @@ void plaid_launch_ci_list(hipStream_t st, const float *S, int64_t C, const int64
                           int nq, const uint64_t *in_keys, int64_t in_stride, const int32_t *in_counts, int n_upper,
                           uint64_t *out_keys, int64_t out_stride);
 
-// Section 4.5 + Eq. 1 over a key list (stage 4).
-void plaid_launch_decompress_maxsim(hipStream_t st, const float *Q, const float *centroids, const int64_t *doc_offsets,
+// Section 4.5 + Eq. 1 over a key list (stage 4); S = this chunk's S_cq, whose rows supply the centroids' share.
+void plaid_launch_decompress_maxsim(hipStream_t st, const float *Q, const float *S, int64_t C, const int64_t *doc_offsets,
                                     const int32_t *codes, const uint8_t *residuals, const float *bucket_weights,
                                     int nbits, int nq, const uint64_t *in_keys, int64_t in_stride,
                                     const int32_t *in_counts, int n_upper, uint64_t *out_keys, int64_t out_stride);

@@ -17,9 +17,9 @@ LIB_PATH = os.path.join(_HERE, "libplaid.so")
 
 PLAID_QLEN = 32
 PLAID_DIM = 128
-PLAID_NUM_STAGES = 8
-STAGE_NAMES = ("scq", "top_nprobe", "ivf_union", "stage2_ci", "select_ndocs", "stage3_ci_select", "stage4_maxsim",
-               "topk")
+PLAID_NUM_STAGES = 10
+STAGE_NAMES = ("prep", "scq", "probes", "ivf_union", "stage2_ci", "select_ndocs", "stage3_ci", "select_ndocs4",
+               "stage4_maxsim", "topk")
 
 PLAID_OK, PLAID_EINVAL, PLAID_ENOMEM, PLAID_EHIP, PLAID_EIO, PLAID_EFORMAT = 0, -1, -2, -3, -4, -5
 _STATUS = {0: "PLAID_OK", -1: "PLAID_EINVAL", -2: "PLAID_ENOMEM", -3: "PLAID_EHIP", -4: "PLAID_EIO", -5: "PLAID_EFORMAT"}

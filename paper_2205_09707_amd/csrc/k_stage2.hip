@@ -20,7 +20,8 @@
 // when its bag is non-empty and the invalid key otherwise (slots of non-candidates are neither
 // written nor read), a histogram of the valid keys' bins for the selection that follows, and a
 // bitmap of the candidates whose bag is empty (score -infinity; they rank last, in passage-id
-// order).  No counters and no atomics with a return value on this path; a workgroup counts bins
+// order).  A query without any surviving centroid skips all of this: its candidates are exactly
+// its empty-bag set.  No counters and no atomics with a return value on this path; a workgroup counts bins
 // in LDS and adds its non-zero bins to the query's histogram once, at its end, so that queries
 // whose passages all share one score (a single surviving centroid) do not queue up on one address.
 #include "plaid_internal.h"
@@ -174,12 +175,22 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
     __shared__ uint32_t htab[S2_HASH];
     __shared__ __align__(16) float Tl[(S2_MAX_KEPT + 1) * S2_TSTRIDE];
     __shared__ int32_t lhist[SEL_BINS];
+    __shared__ float rowsum[S2_MAX_KEPT + 1];  // score of a bag holding only slot s
     const int q = blockIdx.y;
     const int K = s2_uniform(meta[q].K);
     const float bin_hi = meta[q].bin_hi, bin_scale = meta[q].bin_scale;
     uint64_t *keys_out = keys2 + (int64_t)q * key_stride;
     int32_t *hist_q = hist + (int64_t)q * SEL_BINS;
     const int tid = threadIdx.x, lane = tid & 63;
+    if (K == 0) {
+        // no centroid passes Eq. 5: every bag is empty whatever the codes are, so they are not read.  There is no valid
+        // key and the histogram stays zero; the candidates themselves are the empty-bag set.
+        const uint32_t *cb0 = candbits + (int64_t)q * cand_words;
+        uint32_t *eb0 = emptybits + (int64_t)q * cand_words;
+        for (int64_t w = (int64_t)blockIdx.x * S2_THREADS + tid; w < cand_words; w += (int64_t)gridDim.x * S2_THREADS)
+            eb0[w] = cb0[w];
+        return;
+    }
     for (int e = tid; e < SEL_BINS; e += S2_THREADS) lhist[e] = 0;
     if (K > S2_MAX_KEPT) {  // too many survivors for slot sets (uniform for the whole workgroup): gather form
         __syncthreads();
@@ -198,6 +209,10 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
     if (tid < K) {
         const uint32_t code = (uint32_t)kept_ids[(int64_t)q * S2_MAX_KEPT + tid];
         htab[(code ^ (code >> hsh)) & (S2_HASH - 1)] = (code << 6) | (uint32_t)(tid + 1);
+        // one survivor in the bag: the maxima are its row, summed in the same order as below
+        double d = 0.0;
+        for (int i = 0; i < QLEN; ++i) d += (double)Tl[(tid + 1) * S2_TSTRIDE + i];
+        rowsum[tid + 1] = (float)d;
     }
     __syncthreads();
 
@@ -269,13 +284,19 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
                 const int shift = (int)(g0 - a0);
                 const int nchunk = (shift + (end - base) + 31) >> 5;  // 128-byte lines of the round, <= 8 * S2_ITEMS
                 const bool mine = lane >= ps && lane < pe && cand;
-                if (lane < S2_LBWORDS) linebits[lane] = 0u;
+                // lines of the round that hold a candidate's tokens; when every passage of the round is a candidate
+                // that is all of them
+                const unsigned long long round_mask = (pe < 64 ? (1ull << pe) : 0ull) - (1ull << ps);
+                const bool dense = (candm & round_mask) == round_mask;  // uniform
+                if (lane < S2_LBWORDS) linebits[lane] = dense ? 0xFFFFFFFFu : 0u;
                 s2_wave_sync();
-                if (mine && my_hi > my_lo) {
-                    const int c0 = (my_lo - base + shift) >> 5, c1 = (my_hi - 1 - base + shift) >> 5;
-                    for (int c = c0; c <= c1; ++c) atomicOr(&linebits[c >> 5], 1u << (c & 31));
+                if (!dense) {
+                    if (mine && my_hi > my_lo) {
+                        const int c0 = (my_lo - base + shift) >> 5, c1 = (my_hi - 1 - base + shift) >> 5;
+                        for (int c = c0; c <= c1; ++c) atomicOr(&linebits[c >> 5], 1u << (c & 31));
+                    }
+                    s2_wave_sync();
                 }
-                s2_wave_sync();
                 // Stage one byte per token: the slot of its centroid (0 = pruned).  Item u of a lane is the 16 bytes at token
                 // 4 * (64 u + lane), so item u of the wave covers lines 8u .. 8u+7, which is byte u of the line bitmap: a
                 // uniform test skips the item when no candidate touches those lines.  All loads of the round are issued
@@ -324,9 +345,21 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
                 }
                 s2_wave_sync();
                 const bool any_hit = __ballot(hit != 0u) != 0ull;  // uniform
-                if (any_hit && mine) {
+                if (any_hit && mine && my_hi > my_lo) {
+                    // four staged bytes at a time; most are zero (pruned tokens) and are skipped as a word
                     const int v0 = my_lo - base + shift, v1 = my_hi - base + shift;
-                    for (int vv = v0; vv < v1; ++vv) set |= 1ull << stage[vv];
+                    const uint32_t *stage32 = reinterpret_cast<const uint32_t *>(stage);
+                    for (int wd = v0 >> 2; wd <= (v1 - 1) >> 2; ++wd) {
+                        uint32_t x = stage32[wd];
+                        if (4 * wd < v0) x &= 0xFFFFFFFFu << (8 * (v0 - 4 * wd));       // bytes before the passage
+                        if (4 * wd + 4 > v1) x &= 0xFFFFFFFFu >> (8 * (4 * wd + 4 - v1));  // bytes after it
+                        if (x) {
+                            set |= 1ull << (x & 0xFFu);
+                            set |= 1ull << ((x >> 8) & 0xFFu);
+                            set |= 1ull << ((x >> 16) & 0xFFu);
+                            set |= 1ull << (x >> 24);
+                        }
+                    }
                 }
                 s2_wave_sync();
                 ps = s2_uniform(s2_next_bit(candm, pe));
@@ -338,7 +371,9 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
         const uint64_t members = set & ~1ull;
         const bool empty = members == 0;
         float score = -INFINITY;
-        if (cand && !empty) {
+        if (cand && !empty && (members & (members - 1)) == 0) {
+            score = rowsum[__ffsll((long long)members) - 1];
+        } else if (cand && !empty) {
             double d = 0.0;
 #pragma unroll 1
             for (int g = 0; g < QLEN / 8; ++g) {

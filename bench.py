@@ -39,7 +39,8 @@ def log(*a):
 
 def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
     """What the method must move, from the library's own candidate and survivor lists.
-    Stage 2 (Eq. 3-5): per candidate passage 8 bytes of offsets + 4 bytes per token code.
+    Stage 2 (Eq. 3-5): per candidate passage 8 bytes of offsets + 4 bytes per token code; for a query none of whose
+    centroids passes Eq. 5 every bag is empty whatever the codes hold, and only the candidate bitmap is read and written.
     Stage 4 (Section 4.5, Eq. 1): per surviving passage 8 bytes of offsets and per token its 4-byte code, its packed
     residual (16 * nbits bytes) and the 128-byte S_cq row that carries the centroid's share of the dot products."""
     import torch
@@ -48,65 +49,40 @@ def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
     s2 = 0
     s4 = 0
     s4_tokens = 0
+    n_skipped = 0
     ncand = []
     step = 64   # the library's chunk size, so that these launches look like the timed ones to a profiler
     for q0 in range(0, Q.shape[0], step):
         _, _, b = pl.plaid_search_debug(idx, Q[q0:q0 + step], nprobe, t_cs, ndocs, k,
-                                        want=("cand", "n_cand", "sel3_ids", "n3"))
+                                        want=("S_cq", "cand", "n_cand", "sel3_ids", "n3"))
         torch.cuda.synchronize()
+        survivors = (b["S_cq"].max(dim=2).values >= t_cs).sum(dim=1).tolist()   # centroids passing Eq. 5, per query
+        del b["S_cq"]
         for j in range(b["cand"].shape[0]):
             n = int(b["n_cand"][j])
             c = b["cand"][j, :n].long()
-            s2 += 8 * n + 4 * int(lens[c].sum())
+            if survivors[j] > 0:
+                s2 += 8 * n + 4 * int(lens[c].sum())
+            else:
+                s2 += 8 * ((cfg.P + 31) // 32)
+                n_skipped += 1
             ncand.append(n)
             n3 = int(b["n3"][j])
             t = int(lens[b["sel3_ids"][j, :n3].long()].sum())
             s4_tokens += t
             s4 += 8 * n3 + t * (4 + 16 * cfg.nbits + 128)
     return {"stage2_bytes": s2, "stage4_bytes": s4, "stage4_tokens": s4_tokens,
-            "mean_candidates": float(sum(ncand)) / max(1, len(ncand))}
+            "mean_candidates": float(sum(ncand)) / max(1, len(ncand)), "queries_without_survivors": n_skipped}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="cfg3", help="cfg1 .. cfg5 (synth/workload.py)")
-    ap.add_argument("--noise", default="literal", choices=["literal", "calibrated"])
-    ap.add_argument("--latency-queries", type=int, default=512, help="queries timed one per call for p50/p99")
-    ap.add_argument("--cpu-sample", type=int, default=16, help="queries the CPU oracle is timed on (0 = skip)")
-    ap.add_argument("--no-roofline", action="store_true")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="only run four 1 GiB device-to-device copies (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
-    import torch
-
-    import paper_2205_09707_amd as pl
-    from synth import get_config, make_workload
-
-    assert torch.cuda.is_available(), "bench.py needs the GPU"
-    pl.load_library()
+def measure(pl, torch, np, cfg, noise, args, latency=True):
+    """Generate the workload on the GPU, time K steps of the full batch (and, if asked, batch-1 latency) and derive the
+    rooflines.  Returns a dict of results plus the objects the caller still needs."""
     dev = torch.device("cuda:0")
-    if args.copy_calibration:
-        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)     # 1 GiB
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        for _ in range(4):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        log("[bench] copy calibration: 4 copies, each reads 1 GiB (1048576 KiB) and writes 1 GiB")
-        return
-    cfg = get_config(args.config)
     t0 = time.time()
-    w = make_workload(cfg, device=dev, noise=args.noise)
+    w = make_workload_(cfg, device=dev, noise=noise)
     torch.cuda.synchronize()
-    log(f"[bench] generated {cfg.name}/{args.noise}: C={cfg.C} P={cfg.P} N={w.N} nbits={cfg.nbits} "
+    log(f"[bench] generated {cfg.name}/{noise}: C={cfg.C} P={cfg.P} N={w.N} nbits={cfg.nbits} "
         f"ivf={w.ivf_pids.numel()} in {time.time() - t0:.1f}s")
     names = ("centroids", "doc_offsets", "codes", "residuals", "bucket_weights", "ivf_offsets", "ivf_pids")
     idx = pl.plaid_index_from_view({n: getattr(w, n) for n in names}, cfg.nbits, device=0, copy=False)
@@ -115,7 +91,6 @@ def main():
     params = (cfg.nprobe, cfg.t_cs, cfg.ndocs, cfg.k)
     out_ids = torch.empty((nq, cfg.k), dtype=torch.int32, device=dev)
     out_sc = torch.empty((nq, cfg.k), dtype=torch.float32, device=dev)
-
     # ---- throughput: K steps of the full batch, stage events on (they cost one sync per query chunk)
     CHUNK = 64   # queries per internal launch
     pl.plaid_set_max_chunk(idx, CHUNK)
@@ -139,7 +114,7 @@ def main():
     pl.plaid_set_stage_timing(idx, False)
 
     # ---- batch-1 latency: one query per call, host clock around call + stream sync
-    nlat = min(args.latency_queries, nq)
+    nlat = min(args.latency_queries, nq) if latency else 0
     for q in range(min(20, nq) if nlat else 0):
         pl.plaid_search(idx, Q[q:q + 1], *params, out_ids=out_ids[q:q + 1], out_scores=out_sc[q:q + 1])
     torch.cuda.synchronize()
@@ -172,7 +147,7 @@ def main():
             t = stage_ms[stage] * 1e-3
             ach = amount / t / unit_scale if t > 0 else 0.0
             e = {"bound": bound, "kernel": kernel, "achieved": round(ach, 1), "peak": peak, "unit": unit,
-                 "frac": round(ach / peak, 4), "traffic": MEASURED_TRAFFIC_PER_LAUNCH.get((cfg.name, args.noise, stage)),
+                 "frac": round(ach / peak, 4), "traffic": MEASURED_TRAFFIC_PER_LAUNCH.get((cfg.name, noise, stage)),
                  "kernel_ms_per_step": round(stage_ms[stage], 4), "launches_per_step": launches, "queries_per_launch": CHUNK,
                  "kernel_ms_per_launch": round(stage_ms[stage] / launches, 4)}
             e.update(extra)
@@ -188,7 +163,8 @@ def main():
             "stage2_ci", "stage-2 centroid interaction (Eq. 3-5) over all candidates", "hbm", work["stage2_bytes"], 1e9,
             HBM_PEAK_GBS, "GB/s",
             {"algorithmic_bytes_per_step": work["stage2_bytes"], "algorithmic_bytes_per_launch": work["stage2_bytes"] // launches,
-             "mean_candidates_per_query": work["mean_candidates"]})
+             "mean_candidates_per_query": work["mean_candidates"],
+             "queries_without_surviving_centroid": work["queries_without_survivors"]})
         rooflines["stage4_maxsim"] = entry(
             "stage4_maxsim", "stage-4 decompression + MaxSim (Section 4.5, Eq. 1) over the ndocs/4 survivors", "hbm",
             work["stage4_bytes"], 1e9, HBM_PEAK_GBS, "GB/s",
@@ -200,6 +176,54 @@ def main():
         dominant = max(rooflines, key=lambda s: stage_ms[s])
         roofline = dict(rooflines[dominant])
         roofline["stage"] = dominant
+
+    return {"w": w, "idx": idx, "Q": Q, "nq": nq, "params": params, "out_ids": out_ids, "qps": qps, "ms_per_step": ms_per_step,
+            "stage_ms": stage_ms, "lat": lat, "enq": enq, "nlat": nlat, "roofline": roofline, "rooflines": rooflines}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="cfg3", help="cfg1 .. cfg5 (synth/workload.py)")
+    ap.add_argument("--noise", default="literal", choices=["literal", "calibrated"])
+    ap.add_argument("--latency-queries", type=int, default=512, help="queries timed one per call for p50/p99")
+    ap.add_argument("--cpu-sample", type=int, default=16, help="queries the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--single-noise", action="store_true", help="skip the run on the other reading of the noise scale")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run four 1 GiB device-to-device copies (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2205_09707_amd as pl
+    from synth import get_config, make_workload
+    global make_workload_
+    make_workload_ = make_workload
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    pl.load_library()
+    dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)     # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log("[bench] copy calibration: 4 copies, each reads 1 GiB (1048576 KiB) and writes 1 GiB")
+        return
+    cfg = get_config(args.config)
+    r = measure(pl, torch, np, cfg, args.noise, args)
+    w, idx, Q, nq, params, out_ids = r["w"], r["idx"], r["Q"], r["nq"], r["params"], r["out_ids"]
+    qps, ms_per_step, stage_ms, lat, enq, nlat = r["qps"], r["ms_per_step"], r["stage_ms"], r["lat"], r["enq"], r["nlat"]
+    roofline, rooflines = r["roofline"], r["rooflines"]
 
     # ---- CPU oracle on a bounded sample of the same queries (rank 0, N = 1)
     cpu = None
@@ -219,6 +243,19 @@ def main():
         log(f"[bench] CPU oracle: {ns} queries in {dt_cpu:.2f}s on {used} threads; id agreement with GPU {agree:.4f}")
 
     pl.plaid_index_free(idx)
+    del w, idx, Q, r
+    torch.cuda.empty_cache()
+
+    # ---- the other reading of the generator's noise scale, throughput and rooflines only (never mixed into `value`)
+    other = None
+    if not args.single_noise:
+        on = "calibrated" if args.noise == "literal" else "literal"
+        r2 = measure(pl, torch, np, cfg, on, args, latency=False)
+        pl.plaid_index_free(r2["idx"])
+        other = {"noise": on, "value": round(r2["qps"], 2), "unit": "queries/s", "ms_per_step": round(r2["ms_per_step"], 4),
+                 "stage_ms_per_step": {s_: round(v, 4) for s_, v in r2["stage_ms"].items()},
+                 "roofline_by_stage": r2["rooflines"] or None}
+        del r2
     line = {
         "metric": "queries_per_sec", "value": round(qps, 2), "unit": "queries/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -233,6 +270,7 @@ def main():
                               "qps": round(1e3 / float(lat.mean()), 1) if nlat else None},
         "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items()},
         "roofline": roofline, "roofline_by_stage": rooflines or None, "cpu_baseline": cpu,
+        "other_noise_reading": other,
     }
     print(json.dumps(line), flush=True)
 

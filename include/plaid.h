@@ -143,6 +143,14 @@ int plaid_index_info(const plaid_index *idx, int64_t *num_centroids, int64_t *nu
  * overrides the choice (matrix is an error when the check fails). */
 int plaid_get_score_kernel(const plaid_index *idx, int32_t *form);
 
+/* How candidates and their pruned scores (Section 4.1, Eq. 3-5) are computed for this index: HOST *form = 1 for the
+ * inverted form (a passage holds centroid c exactly when c's inverted list holds the passage, so the candidate set and
+ * every pruned bag follow from the lists of the probed and the surviving centroids), 0 for the union of the probed lists
+ * followed by a stream over the candidates' token codes.  Same results either way.  The inverted form needs a table of
+ * num_centroids x (num_passages / 2048 + 1) 32-bit positions, built at index creation when that is at most 32 MiB or at
+ * most the size of the inverted lists; PLAID_STAGE2_FORM=stream|inverted (read at index creation) overrides. */
+int plaid_get_stage2_kernel(const plaid_index *idx, int32_t *form);
+
 /* Per-stage GPU time of the most recent plaid_search on this index when stage timing is on
  * (plaid_set_stage_timing(idx, 1)): HOST out_ms[PLAID_NUM_STAGES], summed over the call's query chunks.
  * Turning timing on makes every search synchronise at its end. */

@@ -10,6 +10,7 @@ from .plaid import (  # noqa: F401
     load_library,
     plaid_decompress_passages,
     plaid_get_score_kernel,
+    plaid_get_stage2_kernel,
     plaid_get_stage_ms,
     plaid_index_free,
     plaid_index_from_view,

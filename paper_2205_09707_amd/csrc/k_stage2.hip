@@ -36,6 +36,8 @@
 #define S2W_CAP (64 * 4 * S2_ITEMS - 32)  // tokens a wave stages per round (one byte each), whatever their alignment
 #define S2_LBWORDS ((S2_ITEMS + 3) / 4)   // words of the round's line bitmap (8 lines per item)
 #define S2_TSTRIDE 36    // floats per staged S_cq row (16-byte aligned, rows spread over the banks)
+#define IVR_SHIFT 11     // inverted form: a workgroup owns 2^IVR_SHIFT consecutive passages
+#define IVR_RANGE (1 << IVR_SHIFT)
 static_assert(S2_LBWORDS <= 64, "one lane clears one word of the line bitmap");
 
 // ------------------------------------------------------------------ gather form (K > S2_MAX_KEPT)
@@ -78,21 +80,22 @@ __device__ __forceinline__ float s2_gather_passage(const float *__restrict__ Sq,
     return s2_sum32_as_double(m);
 }
 
-// Whole-grid body for one query: every wave walks bitmap words (32 passages each) with a grid stride.
+// Body for one query over the bitmap words w_first + k * w_step < w_end (32 passages each), one wave per word at a
+// time; cb[w - cb_first] is the candidate word w (global memory or LDS).
 __device__ __forceinline__ void s2_gather_body(int q, const float *__restrict__ S, int64_t C,
-                                               const uint32_t *__restrict__ keepbits, int64_t keep_words,
-                                               const uint32_t *__restrict__ candbits, int64_t cand_words, int64_t P,
-                                               const int64_t *__restrict__ doc_offsets, const int32_t *__restrict__ codes,
-                                               float bin_hi, float bin_scale, uint64_t *__restrict__ keys_out,
-                                               int32_t *lhist, uint32_t *__restrict__ emptybits)
+                                               const uint32_t *__restrict__ keepbits, int64_t keep_words, const uint32_t *cb,
+                                               int64_t cb_first, int64_t w_first, int64_t w_step, int64_t w_end,
+                                               int64_t cand_words, int64_t P, const int64_t *__restrict__ doc_offsets,
+                                               const int32_t *__restrict__ codes, float bin_hi, float bin_scale,
+                                               uint64_t *__restrict__ keys_out, int32_t *lhist,
+                                               uint32_t *__restrict__ emptybits)
 {
     const int lane = threadIdx.x & 63;
     const float *Sq = S + (int64_t)q * C * QLEN;
     const uint32_t *kb = keepbits + (int64_t)q * keep_words;
-    const uint32_t *cb = candbits + (int64_t)q * cand_words;
     uint32_t *eb = emptybits + (int64_t)q * cand_words;
-    for (int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); w < cand_words; w += (int64_t)gridDim.x * 4) {
-        const uint32_t word = cb[w];
+    for (int64_t w = w_first; w < w_end; w += w_step) {
+        const uint32_t word = cb[w - cb_first];
         if (!word) {
             if (lane == 0) eb[w] = 0u;
             continue;
@@ -162,6 +165,61 @@ __device__ __forceinline__ void s2_flush_hist(const int32_t *lhist, int32_t *__r
     }
 }
 
+// Pruned score of a bag whose surviving centroids are the slots in `members` (non-empty, bit 0 clear): column maxima
+// of those rows of the staged table, summed over the query tokens in index order; eight query tokens at a time, so
+// that few registers are live.  A bag with one survivor takes that row's precomputed sum (same additions, same order).
+__device__ __forceinline__ float s2_score_members(uint64_t members, const float *Tl, const float *rowsum)
+{
+    if ((members & (members - 1)) == 0) return rowsum[__ffsll((long long)members) - 1];
+    double d = 0.0;
+#pragma unroll 1
+    for (int g = 0; g < QLEN / 8; ++g) {
+        float acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = -INFINITY;
+        uint64_t rest = members;
+        while (rest) {
+            const int s = __ffsll((long long)rest) - 1;
+            rest &= rest - 1;
+            const float4 *row = reinterpret_cast<const float4 *>(Tl + s * S2_TSTRIDE + 8 * g);
+            const float4 r0 = row[0], r1 = row[1];
+            acc[0] = fmaxf(acc[0], r0.x);
+            acc[1] = fmaxf(acc[1], r0.y);
+            acc[2] = fmaxf(acc[2], r0.z);
+            acc[3] = fmaxf(acc[3], r0.w);
+            acc[4] = fmaxf(acc[4], r1.x);
+            acc[5] = fmaxf(acc[5], r1.y);
+            acc[6] = fmaxf(acc[6], r1.z);
+            acc[7] = fmaxf(acc[7], r1.w);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) d += (double)acc[i];
+    }
+    return (float)d;
+}
+
+// The query's survivor table in LDS: hash table, rows (slot 0 = -infinity) and single-survivor sums.  All threads of
+// the workgroup call this; K <= S2_MAX_KEPT.
+__device__ __forceinline__ void s2_stage_tables(int q, int K, int hsh, const int32_t *__restrict__ kept_ids,
+                                                const float *__restrict__ T, uint32_t *htab, float *Tl, float *rowsum)
+{
+    const int tid = threadIdx.x;
+    for (int e = tid; e < S2_HASH; e += S2_THREADS) htab[e] = 0xFFFFFFFFu;
+    const float *Tq = T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN;
+    for (int e = tid; e < (K + 1) * QLEN; e += S2_THREADS)
+        Tl[(e >> 5) * S2_TSTRIDE + (e & 31)] = (e >> 5) ? Tq[e] : -INFINITY;
+    __syncthreads();
+    if (tid < K) {
+        const uint32_t code = (uint32_t)kept_ids[(int64_t)q * S2_MAX_KEPT + tid];
+        htab[(code ^ (code >> hsh)) & (S2_HASH - 1)] = (code << 6) | (uint32_t)(tid + 1);
+        // one survivor in the bag: the maxima are its row, summed in the same order as in s2_score_members
+        double d = 0.0;
+        for (int i = 0; i < QLEN; ++i) d += (double)Tl[(tid + 1) * S2_TSTRIDE + i];
+        rowsum[tid + 1] = (float)d;
+    }
+    __syncthreads();
+}
+
 // Persistent workgroups; wave w of the grid scores the 64-passage tiles w, w + W, w + 2W, ... (lane = passage).
 __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
     const float *__restrict__ S, int64_t C, const uint32_t *__restrict__ keepbits, int64_t keep_words,
@@ -194,27 +252,15 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
     for (int e = tid; e < SEL_BINS; e += S2_THREADS) lhist[e] = 0;
     if (K > S2_MAX_KEPT) {  // too many survivors for slot sets (uniform for the whole workgroup): gather form
         __syncthreads();
-        s2_gather_body(q, S, C, keepbits, keep_words, candbits, cand_words, P, doc_offsets, codes, bin_hi, bin_scale, keys_out,
-                       lhist, emptybits);
+        s2_gather_body(q, S, C, keepbits, keep_words, candbits + (int64_t)q * cand_words, 0,
+                       (int64_t)blockIdx.x * 4 + (tid >> 6), (int64_t)gridDim.x * 4, cand_words, cand_words, P, doc_offsets, codes,
+                       bin_hi, bin_scale, keys_out, lhist, emptybits);
         s2_flush_hist(lhist, hist_q);
         return;
     }
     const int hsh = s2_uniform(meta[q].hash_shift);
     const int wave = s2_uniform(tid >> 6);
-    for (int e = tid; e < S2_HASH; e += S2_THREADS) htab[e] = 0xFFFFFFFFu;
-    const float *Tq = T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN;
-    for (int e = tid; e < (K + 1) * QLEN; e += S2_THREADS)
-        Tl[(e >> 5) * S2_TSTRIDE + (e & 31)] = (e >> 5) ? Tq[e] : -INFINITY;
-    __syncthreads();
-    if (tid < K) {
-        const uint32_t code = (uint32_t)kept_ids[(int64_t)q * S2_MAX_KEPT + tid];
-        htab[(code ^ (code >> hsh)) & (S2_HASH - 1)] = (code << 6) | (uint32_t)(tid + 1);
-        // one survivor in the bag: the maxima are its row, summed in the same order as below
-        double d = 0.0;
-        for (int i = 0; i < QLEN; ++i) d += (double)Tl[(tid + 1) * S2_TSTRIDE + i];
-        rowsum[tid + 1] = (float)d;
-    }
-    __syncthreads();
+    s2_stage_tables(q, K, hsh, kept_ids, T, htab, Tl, rowsum);
 
     uint8_t *stage = stage_all[wave];
     uint32_t *linebits = linebits_all[wave];
@@ -371,35 +417,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
         const uint64_t members = set & ~1ull;
         const bool empty = members == 0;
         float score = -INFINITY;
-        if (cand && !empty && (members & (members - 1)) == 0) {
-            score = rowsum[__ffsll((long long)members) - 1];
-        } else if (cand && !empty) {
-            double d = 0.0;
-#pragma unroll 1
-            for (int g = 0; g < QLEN / 8; ++g) {
-                float acc[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i] = -INFINITY;
-                uint64_t rest = members;
-                while (rest) {
-                    const int s = __ffsll((long long)rest) - 1;
-                    rest &= rest - 1;
-                    const float4 *row = reinterpret_cast<const float4 *>(Tl + s * S2_TSTRIDE + 8 * g);
-                    const float4 r0 = row[0], r1 = row[1];
-                    acc[0] = fmaxf(acc[0], r0.x);
-                    acc[1] = fmaxf(acc[1], r0.y);
-                    acc[2] = fmaxf(acc[2], r0.z);
-                    acc[3] = fmaxf(acc[3], r0.w);
-                    acc[4] = fmaxf(acc[4], r1.x);
-                    acc[5] = fmaxf(acc[5], r1.y);
-                    acc[6] = fmaxf(acc[6], r1.z);
-                    acc[7] = fmaxf(acc[7], r1.w);
-                }
-#pragma unroll
-                for (int i = 0; i < 8; ++i) d += (double)acc[i];
-            }
-            score = (float)d;
-        }
+        if (cand && !empty) score = s2_score_members(members, Tl, rowsum);
         // emit: slot p of the key array belongs to candidate p; no counters, no ordering between waves
         const bool live = cand && !empty;
         if (cand) keys_out[p0 + lane] = live ? plaid_make_key(score, (uint32_t)(p0 + lane)) : PLAID_KEY_MAX;
@@ -412,6 +430,230 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
         }
     }
     s2_flush_hist(lhist, hist_q);
+}
+
+
+// ------------------------------------------------------------------ inverted form: candidates and bags from the inverted lists
+// A passage contains centroid c exactly when it is in c's inverted list (Section 4.1 stores unique passage ids per
+// centroid).  So the candidate set is the union of the probed centroids' lists, and the pruned bag of a passage
+// (Eq. 5) is the set of surviving centroids whose lists contain it: both follow from the inverted lists of at most
+// 32 nprobe + S2_MAX_KEPT centroids, far fewer bytes than the candidates' token codes whenever few centroids
+// survive.  A workgroup owns a range of IVR_RANGE consecutive passages: it ORs the lists' entries that fall into
+// its range into 64-bit words in LDS (bit 0 = candidate, bit s = surviving slot s), then scores, emits keys, the bin
+// histogram, the candidate words and the empty-bag words of the range exactly as the streaming form does.  Where a
+// list enters a range comes from a table built once per index: table[c][r] = position in list c of its first entry
+// with passage id >= r * IVR_RANGE.
+#define IVR_EMPTY 0xFFFFFFFFu
+#define IVR_LISTS 256  // lists handled per LDS round
+
+// table[c][r] for every non-empty (list, range) pair; the others keep IVR_EMPTY until ivr_fill_kernel.
+__global__ __launch_bounds__(256) void ivr_mark_kernel(const int64_t *__restrict__ ivf_offsets,
+                                                       const int32_t *__restrict__ ivf_pids, int64_t C, int64_t nr,
+                                                       uint32_t *__restrict__ table)
+{
+    for (int64_t c = blockIdx.x; c < C; c += gridDim.x) {
+        const int64_t s = ivf_offsets[c], t = ivf_offsets[c + 1];
+        for (int64_t e = s + threadIdx.x; e < t; e += blockDim.x) {
+            const int64_t r = (int64_t)(uint32_t)ivf_pids[e] >> IVR_SHIFT;
+            const bool first = e == s || ((int64_t)(uint32_t)ivf_pids[e - 1] >> IVR_SHIFT) != r;
+            if (first && r < nr) table[c * (nr + 1) + r] = (uint32_t)(e - s);
+        }
+    }
+}
+// A range a list has no entry in starts where the next one does; the last column is the list's length.
+__global__ __launch_bounds__(256) void ivr_fill_kernel(const int64_t *__restrict__ ivf_offsets, int64_t C, int64_t nr,
+                                                       uint32_t *__restrict__ table)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    uint32_t next = (uint32_t)(ivf_offsets[c + 1] - ivf_offsets[c]);
+    uint32_t *row = table + c * (nr + 1);
+    row[nr] = next;
+    for (int64_t r = nr - 1; r >= 0; --r) {
+        const uint32_t v = row[r];
+        if (v == IVR_EMPTY || v > next) row[r] = next;  // (v > next only if a list is not ascending: keep the row monotone)
+        else next = v;
+    }
+}
+
+size_t plaid_ivf_range_table_bytes(int64_t C, int64_t P)
+{
+    const int64_t nr = (P + IVR_RANGE - 1) >> IVR_SHIFT;
+    return (size_t)C * (size_t)(nr + 1) * sizeof(uint32_t);
+}
+void plaid_launch_ivf_range_table(hipStream_t st, const int64_t *ivf_offsets, const int32_t *ivf_pids, int64_t C, int64_t P,
+                                  uint32_t *table)
+{
+    const int64_t nr = (P + IVR_RANGE - 1) >> IVR_SHIFT;
+    plaid_launch_fill_u32(st, table, C * (nr + 1), IVR_EMPTY);
+    hipLaunchKernelGGL(ivr_mark_kernel, dim3((unsigned)(C < 8192 ? C : 8192)), dim3(256), 0, st, ivf_offsets, ivf_pids, C, nr, table);
+    hipLaunchKernelGGL(ivr_fill_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, ivf_offsets, C, nr, table);
+}
+
+// ORs `value | (slot bit)` into the set words of the passages that lists [0, nl) hold inside the range.  lst_start /
+// lst_pref / lst_val describe the lists (position of the first entry in range, exclusive prefix sum of the counts,
+// bits to OR); all threads of the workgroup call this.
+__device__ __forceinline__ void ivr_apply_lists(const int32_t *__restrict__ ivf_pids, const int64_t *lst_start,
+                                                const int32_t *lst_pref, const unsigned long long *lst_val, int nl,
+                                                uint32_t r0, unsigned long long *lsets)
+{
+    const int total = lst_pref[nl];
+    for (int w = threadIdx.x; w < total; w += S2_THREADS) {
+        int lo = 0, hi = nl;  // largest lo with pref[lo] <= w
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (lst_pref[mid] <= w) lo = mid;
+            else hi = mid;
+        }
+        const uint32_t loc = (uint32_t)ivf_pids[lst_start[lo] + (w - lst_pref[lo])] - r0;
+        if (loc < (uint32_t)IVR_RANGE) atomicOr(&lsets[loc], lst_val[lo]);  // (always true for ascending lists)
+    }
+}
+
+// Exclusive prefix sum of one value per thread over the workgroup, into out[0 .. S2_THREADS]; scratch: one int per wave.
+__device__ __forceinline__ void ivr_block_scan(int v, int32_t *out, int32_t *wave_tot)
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    int incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int t = __shfl_up(incl, d);
+        if (lane >= d) incl += t;
+    }
+    if (lane == 63) wave_tot[tid >> 6] = incl;
+    __syncthreads();
+    int base = 0;
+    for (int wv = 0; wv < (tid >> 6); ++wv) base += wave_tot[wv];
+    out[tid + 1] = base + incl;
+    if (tid == 0) out[0] = 0;
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
+    const int32_t *__restrict__ uniq, const int32_t *__restrict__ n_uniq, int uniq_stride,
+    const int64_t *__restrict__ ivf_offsets, const int32_t *__restrict__ ivf_pids, const uint32_t *__restrict__ table,
+    int64_t nr, const float *__restrict__ S, int64_t C, const uint32_t *__restrict__ keepbits, int64_t keep_words,
+    const int32_t *__restrict__ codes, const int64_t *__restrict__ doc_offsets, int64_t P, const S2Meta *__restrict__ meta,
+    const int32_t *__restrict__ kept_ids, const float *__restrict__ T, uint32_t *__restrict__ candbits, int64_t cand_words,
+    uint64_t *__restrict__ keys2, int64_t key_stride, int32_t *__restrict__ hist, uint32_t *__restrict__ emptybits)
+{
+    __shared__ unsigned long long lsets[IVR_RANGE];
+    __shared__ uint32_t lcand[IVR_RANGE / 32];
+    __shared__ uint32_t htab[S2_HASH];
+    __shared__ __align__(16) float Tl[(S2_MAX_KEPT + 1) * S2_TSTRIDE];
+    __shared__ float rowsum[S2_MAX_KEPT + 1];
+    __shared__ int32_t lhist[SEL_BINS];
+    __shared__ int64_t lst_start[IVR_LISTS];
+    __shared__ int32_t lst_pref[IVR_LISTS + 1];
+    __shared__ unsigned long long lst_val[IVR_LISTS];
+    __shared__ int32_t wave_tot[S2_THREADS / 64];
+    __shared__ uint32_t slot_probed[2];  // bit s: surviving slot s is also a probed centroid
+    const int q = blockIdx.y;
+    const int64_t r = blockIdx.x;
+    const uint32_t r0 = (uint32_t)(r << IVR_SHIFT);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = s2_uniform(tid >> 6);
+    const int K = s2_uniform(meta[q].K);
+    const bool slots = K > 0 && K <= S2_MAX_KEPT;  // bags are kept as slot sets
+    const int hsh = s2_uniform(meta[q].hash_shift);
+    for (int e = tid; e < IVR_RANGE; e += S2_THREADS) lsets[e] = 0ull;
+    for (int e = tid; e < SEL_BINS; e += S2_THREADS) lhist[e] = 0;
+    if (tid < 2) slot_probed[tid] = 0u;
+    if (slots) s2_stage_tables(q, K, hsh, kept_ids, T, htab, Tl, rowsum);
+    else __syncthreads();
+
+    // probed lists: candidate bit, plus the slot bit when the centroid also survives
+    const int nu = n_uniq[q];
+    for (int u0 = 0; u0 < nu; u0 += IVR_LISTS) {
+        const int nb = nu - u0 < IVR_LISTS ? nu - u0 : IVR_LISTS;
+        int cnt = 0;
+        if (tid < nb) {
+            const int32_t c = uniq[(int64_t)q * uniq_stride + u0 + tid];
+            const uint32_t a = table[(int64_t)c * (nr + 1) + r], b = table[(int64_t)c * (nr + 1) + r + 1];
+            lst_start[tid] = ivf_offsets[c] + a;
+            cnt = b > a ? (int)(b - a) : 0;
+            const uint32_t sl = slots ? s2_lookup(htab, (uint32_t)c, hsh) : 0u;
+            lst_val[tid] = 1ull | (sl ? 1ull << sl : 0ull);
+            if (sl) atomicOr(&slot_probed[sl >> 5], 1u << (sl & 31));
+        }
+        ivr_block_scan(cnt, lst_pref, wave_tot);
+        ivr_apply_lists(ivf_pids, lst_start, lst_pref, lst_val, nb, r0, lsets);
+        __syncthreads();
+    }
+    // surviving centroids that were not probed: slot bit only
+    if (slots) {
+        int cnt = 0;
+        if (tid < K) {
+            const int sl = tid + 1;
+            const int32_t c = kept_ids[(int64_t)q * S2_MAX_KEPT + tid];
+            const bool seen = (slot_probed[sl >> 5] >> (sl & 31)) & 1u;
+            const uint32_t a = table[(int64_t)c * (nr + 1) + r], b = table[(int64_t)c * (nr + 1) + r + 1];
+            lst_start[tid] = ivf_offsets[c] + a;
+            cnt = (!seen && b > a) ? (int)(b - a) : 0;
+            lst_val[tid] = 1ull << sl;
+        }
+        ivr_block_scan(cnt, lst_pref, wave_tot);
+        ivr_apply_lists(ivf_pids, lst_start, lst_pref, lst_val, K, r0, lsets);
+        __syncthreads();
+    }
+
+    // emit the range: lane = passage, 64 passages per step
+    const float bin_hi = meta[q].bin_hi, bin_scale = meta[q].bin_scale;
+    uint64_t *keys_out = keys2 + (int64_t)q * key_stride;
+    uint32_t *cbq = candbits + (int64_t)q * cand_words;
+    uint32_t *ebq = emptybits + (int64_t)q * cand_words;
+    const int64_t w_first = (int64_t)r0 >> 5;  // first bitmap word of the range
+    for (int g = wave; g < IVR_RANGE / 64; g += S2_THREADS / 64) {
+        const unsigned long long v = lsets[64 * g + lane];
+        const int64_t pid = (int64_t)r0 + 64 * g + lane;
+        const bool cand = (v & 1ull) && pid < P;
+        const unsigned long long members = v & ~1ull;
+        const unsigned long long cm = __ballot(cand);
+        bool empty = true;
+        if (slots) {
+            empty = members == 0;
+            if (cand) {
+                const float score = empty ? -INFINITY : s2_score_members(members, Tl, rowsum);
+                keys_out[pid] = empty ? PLAID_KEY_MAX : plaid_make_key(score, (uint32_t)pid);
+                if (!empty) atomicAdd(&lhist[plaid_s2_bin(score, bin_hi, bin_scale)], 1);
+            }
+        }
+        const unsigned long long em = __ballot(cand && empty);
+        if (lane == 0) {
+            const int64_t w0 = w_first + 2 * g;
+            if (w0 < cand_words) {
+                cbq[w0] = (uint32_t)cm;
+                lcand[2 * g] = (uint32_t)cm;
+                if (K <= S2_MAX_KEPT) ebq[w0] = (uint32_t)em;
+            }
+            if (w0 + 1 < cand_words) {
+                cbq[w0 + 1] = (uint32_t)(cm >> 32);
+                lcand[2 * g + 1] = (uint32_t)(cm >> 32);
+                if (K <= S2_MAX_KEPT) ebq[w0 + 1] = (uint32_t)(em >> 32);
+            }
+        }
+    }
+    if (K > S2_MAX_KEPT) {
+        // too many survivors for slot sets: the range's candidates are scored from their token codes
+        __syncthreads();
+        int64_t w_end = w_first + IVR_RANGE / 32;
+        if (w_end > cand_words) w_end = cand_words;
+        s2_gather_body(q, S, C, keepbits, keep_words, lcand, w_first, w_first + wave, S2_THREADS / 64, w_end, cand_words, P,
+                       doc_offsets, codes, bin_hi, bin_scale, keys_out, lhist, emptybits);
+    }
+    if (K > 0) s2_flush_hist(lhist, hist + (int64_t)q * SEL_BINS);
+}
+
+void plaid_launch_stage2_inverted(hipStream_t st, const int32_t *uniq, const int32_t *n_uniq, int uniq_stride,
+                                  const int64_t *ivf_offsets, const int32_t *ivf_pids, const uint32_t *table, const float *S,
+                                  int64_t C, const uint32_t *keepbits, int64_t keep_words, const int32_t *codes,
+                                  const int64_t *doc_offsets, int64_t P, int nq, const Stage2Buffers &b, uint32_t *candbits,
+                                  int64_t cand_words, uint64_t *keys2, int64_t key_stride)
+{
+    const int64_t nr = (P + IVR_RANGE - 1) >> IVR_SHIFT;
+    hipLaunchKernelGGL(s2_invert_kernel, dim3((unsigned)nr, nq), dim3(S2_THREADS), 0, st, uniq, n_uniq, uniq_stride, ivf_offsets,
+                       ivf_pids, table, nr, S, C, keepbits, keep_words, codes, doc_offsets, P, b.meta, b.kept_ids, b.T, candbits,
+                       cand_words, keys2, key_stride, b.hist, b.emptybits);
 }
 
 // ------------------------------------------------------------------ host side

@@ -51,6 +51,7 @@ struct plaid_index {
     int32_t max_chunk = 0;
     int32_t timing = 0;
     int32_t scq_matrix_form = 0;  // score kernel: 1 = double-precision matrix instruction, 0 = vector FMA chain
+    uint32_t *ivr_table = nullptr;  // range table of the inverted lists (owned); null: union + code stream are used
     float stage_ms[PLAID_NUM_STAGES] = {0};
     hipEvent_t ev[N_EVENTS] = {nullptr};
 };
@@ -88,6 +89,33 @@ static int choose_scq_form(plaid_index *ix)
     }
     if (env && checked[slot] != 1) return fail(PLAID_EHIP, "PLAID_SCQ_FORM=matrix, but the matrix instruction does not reproduce the FMA chain here");
     ix->scq_matrix_form = checked[slot] == 1;
+    return PLAID_OK;
+}
+
+// The inverted form of candidate generation + stage 2 needs a table of C x (P / 2048 + 1) positions.  It is built when
+// it is small next to the inverted lists themselves (or tiny in absolute terms); PLAID_STAGE2_FORM=stream|inverted
+// (read at index creation) overrides that.
+static int build_range_table(plaid_index *ix)
+{
+    const char *env = getenv("PLAID_STAGE2_FORM");
+    if (env && strcmp(env, "stream") && strcmp(env, "inverted")) return fail(PLAID_EINVAL, "PLAID_STAGE2_FORM must be 'stream' or 'inverted'");
+    const size_t bytes = plaid_ivf_range_table_bytes(ix->C, ix->P);
+    const size_t list_bytes = (size_t)ix->ivf_len * 4;
+    bool want = bytes <= (size_t)32 << 20 || bytes <= list_bytes;
+    if (env) want = !strcmp(env, "inverted");
+    if (!want || ix->P == 0) return PLAID_OK;
+    void *d = nullptr;
+    hipError_t e = hipMalloc(&d, bytes ? bytes : 4);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        if (env) return fail(PLAID_ENOMEM, "hipMalloc(%zu) for the inverted-list range table failed", bytes);
+        return PLAID_OK;  // not essential: the streaming form is used
+    }
+    ix->owned.push_back(d);
+    plaid_launch_ivf_range_table(nullptr, ix->ivf_offsets, ix->ivf_pids, ix->C, ix->P, (uint32_t *)d);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(nullptr));
+    ix->ivr_table = (uint32_t *)d;
     return PLAID_OK;
 }
 
@@ -221,6 +249,7 @@ extern "C" int plaid_index_from_view(const plaid_index_view *v, int device, int 
         ix->ivf_pids = v->ivf_pids;
     }
     rc = choose_scq_form(ix);
+    if (!rc) rc = build_range_table(ix);
     if (rc) {
         plaid_index_free(ix);
         return rc;
@@ -313,6 +342,13 @@ extern "C" int plaid_get_score_kernel(const plaid_index *idx, int32_t *form)
 {
     if (!idx || !form) return fail(PLAID_EINVAL, "null argument");
     *form = idx->scq_matrix_form;
+    return PLAID_OK;
+}
+
+extern "C" int plaid_get_stage2_kernel(const plaid_index *idx, int32_t *form)
+{
+    if (!idx || !form) return fail(PLAID_EINVAL, "null argument");
+    *form = idx->ivr_table ? 1 : 0;
     return PLAID_OK;
 }
 
@@ -511,12 +547,18 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
                                 w.uniq, w.uniq_stride, w.n_uniq, w.s2, w.probe_scratch, w.probe_scratch_bytes);
             STAMP();
         }
-        plaid_launch_ivf_union(st, w.uniq, w.n_uniq, w.uniq_stride, ix->ivf_offsets, ix->ivf_pids, n, w.candbits,
-                               w.cand_words);
+        if (!ix->ivr_table)
+            plaid_launch_ivf_union(st, w.uniq, w.n_uniq, w.uniq_stride, ix->ivf_offsets, ix->ivf_pids, n, w.candbits,
+                                   w.cand_words);
         STAMP();
         // stage 2: centroid interaction with pruning over every candidate (Eq. 3-5), keep ndocs
-        plaid_launch_stage2(st, w.S, C, w.keepbits, w.keep_words, w.probed, nprobe, w.candbits, w.cand_words, P, ix->N,
-                            ix->doc_offsets, ix->codes, n, w.s2, w.keys2, P);
+        if (ix->ivr_table)
+            plaid_launch_stage2_inverted(st, w.uniq, w.n_uniq, w.uniq_stride, ix->ivf_offsets, ix->ivf_pids, ix->ivr_table, w.S,
+                                         C, w.keepbits, w.keep_words, ix->codes, ix->doc_offsets, P, n, w.s2, w.candbits,
+                                         w.cand_words, w.keys2, P);
+        else
+            plaid_launch_stage2(st, w.S, C, w.keepbits, w.keep_words, w.probed, nprobe, w.candbits, w.cand_words, P, ix->N,
+                                ix->doc_offsets, ix->codes, n, w.s2, w.keys2, P);
         STAMP();
         plaid_launch_select2(st, w.keys2, P, w.candbits, n, P, w.cand_words, pl.nd, w.s2, w.sel2, pl.nd, w.n2);
         STAMP();

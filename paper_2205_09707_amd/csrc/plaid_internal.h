@@ -173,6 +173,19 @@ void plaid_launch_stage2(hipStream_t st, const float *S, int64_t C, const uint32
                          int64_t N, const int64_t *doc_offsets, const int32_t *codes, int nq, const Stage2Buffers &b,
                          uint64_t *keys2, int64_t key_stride);
 
+// Inverted form of candidate generation + stage 2 (k_stage2.hip): the same outputs as plaid_launch_ivf_union followed by
+// plaid_launch_stage2 (candbits included, which need not be cleared beforehand), computed from the inverted lists of
+// the probed and the surviving centroids.  table: plaid_ivf_range_table_bytes(C, P) bytes filled once per index by
+// plaid_launch_ivf_range_table.
+size_t plaid_ivf_range_table_bytes(int64_t C, int64_t P);
+void plaid_launch_ivf_range_table(hipStream_t st, const int64_t *ivf_offsets, const int32_t *ivf_pids, int64_t C, int64_t P,
+                                  uint32_t *table);
+void plaid_launch_stage2_inverted(hipStream_t st, const int32_t *uniq, const int32_t *n_uniq, int uniq_stride,
+                                  const int64_t *ivf_offsets, const int32_t *ivf_pids, const uint32_t *table, const float *S,
+                                  int64_t C, const uint32_t *keepbits, int64_t keep_words, const int32_t *codes,
+                                  const int64_t *doc_offsets, int64_t P, int nq, const Stage2Buffers &b, uint32_t *candbits,
+                                  int64_t cand_words, uint64_t *keys2, int64_t key_stride);
+
 // Best min(m, #candidates) candidates by (score desc, pid asc): from the keys by bin filter (+ digit filter when the
 // boundary bin is over-long), then from the empty candidates in pid order.  keys2 is overwritten (scratch).
 void plaid_launch_select2(hipStream_t st, uint64_t *keys2, int64_t key_stride, const uint32_t *candbits, int nq, int64_t P,

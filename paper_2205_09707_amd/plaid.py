@@ -45,7 +45,7 @@ class plaid_debug_buffers(ct.Structure):
 
 EXPORTS = ("plaid_index_load", "plaid_index_from_view", "plaid_index_free", "plaid_search", "plaid_search_debug",
            "plaid_decompress_passages", "plaid_index_info", "plaid_set_stage_timing", "plaid_get_stage_ms",
-           "plaid_set_max_chunk", "plaid_get_score_kernel", "plaid_last_error")
+           "plaid_set_max_chunk", "plaid_get_score_kernel", "plaid_get_stage2_kernel", "plaid_last_error")
 
 _lib = None
 
@@ -75,6 +75,7 @@ def load_library() -> ct.CDLL:
         lib.plaid_get_stage_ms.argtypes = [ct.c_void_p, ct.c_void_p]
         lib.plaid_set_max_chunk.argtypes = [ct.c_void_p, ct.c_int32]
         lib.plaid_get_score_kernel.argtypes = [ct.c_void_p, ct.c_void_p]
+        lib.plaid_get_stage2_kernel.argtypes = [ct.c_void_p, ct.c_void_p]
         _lib = lib
     return _lib
 
@@ -256,4 +257,11 @@ def plaid_get_score_kernel(idx: Index) -> int:
     """1 when S_cq is computed with the double-precision matrix instruction, 0 for the vector FMA chain."""
     form = ct.c_int32(-1)
     _check(load_library().plaid_get_score_kernel(idx.handle, ct.byref(form)))
+    return int(form.value)
+
+
+def plaid_get_stage2_kernel(idx: Index) -> int:
+    """1 when candidates and pruned scores come from the inverted lists, 0 for list union + code stream."""
+    form = ct.c_int32(-1)
+    _check(load_library().plaid_get_stage2_kernel(idx.handle, ct.byref(form)))
     return int(form.value)

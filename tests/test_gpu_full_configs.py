@@ -20,7 +20,8 @@ pytestmark = pytest.mark.gpu
 BIG = os.environ.get("PLAID_BIG_CONFIGS", "0") == "1"
 
 
-def _run(cfg_name, noise, n_sample, n_dump):
+def _run(cfg_name, noise, n_sample, n_dump, stage2=None):
+    """stage2: None = the library's choice of the stage-2 form, "stream" / "inverted" = forced (PLAID_STAGE2_FORM)."""
     import paper_2205_09707_amd as pl
     pl.load_library()
     cfg = get_config(cfg_name)
@@ -28,7 +29,20 @@ def _run(cfg_name, noise, n_sample, n_dump):
     print(f"[full] generating {cfg_name}/{noise}", flush=True)
     w = make_workload(cfg, device=dev, noise=noise)
     names = ("centroids", "doc_offsets", "codes", "residuals", "bucket_weights", "ivf_offsets", "ivf_pids")
-    gidx = pl.plaid_index_from_view({n: getattr(w, n) for n in names}, cfg.nbits, device=0, copy=False)
+    old = os.environ.get("PLAID_STAGE2_FORM")
+    if stage2 is not None:
+        os.environ["PLAID_STAGE2_FORM"] = stage2
+    try:
+        gidx = pl.plaid_index_from_view({n: getattr(w, n) for n in names}, cfg.nbits, device=0, copy=False)
+    finally:
+        if stage2 is not None:
+            if old is None:
+                os.environ.pop("PLAID_STAGE2_FORM", None)
+            else:
+                os.environ["PLAID_STAGE2_FORM"] = old
+    if stage2 is not None:
+        assert pl.plaid_get_stage2_kernel(gidx) == (1 if stage2 == "inverted" else 0)
+    print(f"[full] {cfg_name}/{noise}: stage-2 form {'inverted' if pl.plaid_get_stage2_kernel(gidx) else 'stream'}", flush=True)
     params = (cfg.nprobe, cfg.t_cs, cfg.ndocs, cfg.k)
     Q = w.queries
     nq = Q.shape[0]
@@ -66,10 +80,11 @@ def _run(cfg_name, noise, n_sample, n_dump):
         torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("cfg_name,noise", [("cfg2", "literal"), ("cfg2", "calibrated"), ("cfg3", "literal"),
-                                            ("cfg3", "calibrated")])
-def test_mid_configs(cfg_name, noise):
-    _run(cfg_name, noise, n_sample=12, n_dump=3)
+@pytest.mark.parametrize("cfg_name,noise,stage2", [("cfg2", "literal", None), ("cfg2", "calibrated", None),
+                                                   ("cfg3", "literal", None), ("cfg3", "calibrated", None),
+                                                   ("cfg3", "literal", "stream"), ("cfg3", "calibrated", "stream")])
+def test_mid_configs(cfg_name, noise, stage2):
+    _run(cfg_name, noise, n_sample=12, n_dump=3, stage2=stage2)
 
 
 @pytest.mark.skipif(not BIG, reason="set PLAID_BIG_CONFIGS=1: generating 0.6-1.4 billion embeddings takes minutes")

@@ -27,29 +27,34 @@ def pl():
 
 
 @contextlib.contextmanager
-def _score_kernel(form):
-    """Index creation reads PLAID_SCQ_FORM: 'matrix' / 'vector' force one of the two S_cq kernels, None leaves the
-    library's own choice."""
-    old = os.environ.get("PLAID_SCQ_FORM")
-    if form is None:
-        os.environ.pop("PLAID_SCQ_FORM", None)
-    else:
-        os.environ["PLAID_SCQ_FORM"] = form
+def _kernel_forms(form=None, stage2=None):
+    """Index creation reads PLAID_SCQ_FORM ('matrix' / 'vector': the two S_cq kernels) and PLAID_STAGE2_FORM ('inverted' /
+    'stream': the two ways to candidates and pruned scores); None leaves the library's own choice."""
+    wanted = {"PLAID_SCQ_FORM": form, "PLAID_STAGE2_FORM": stage2}
+    old = {k: os.environ.get(k) for k in wanted}
+    for k, v in wanted.items():
+        if v is None:
+            os.environ.pop(k, None)
+        else:
+            os.environ[k] = v
     try:
         yield
     finally:
-        if old is None:
-            os.environ.pop("PLAID_SCQ_FORM", None)
-        else:
-            os.environ["PLAID_SCQ_FORM"] = old
+        for k, v in old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
 
 
-def _check_workload(pl, w, params_list, want=None, queries=None, copy=False, form=None):
+def _check_workload(pl, w, params_list, want=None, queries=None, copy=False, form=None, stage2=None):
     ix = pu.oracle_index(w)
-    with _score_kernel(form):
+    with _kernel_forms(form, stage2):
         gidx = pl.plaid_index_from_view(pu.device_arrays(w), w.cfg.nbits, device=0, copy=copy)
     if form is not None:
         assert pl.plaid_get_score_kernel(gidx) == (1 if form == "matrix" else 0)
+    if stage2 is not None:
+        assert pl.plaid_get_stage2_kernel(gidx) == (1 if stage2 == "inverted" else 0)
     Qdev = w.queries.to("cuda:0")
     Qh = w.queries.numpy()
     nq = Qh.shape[0]
@@ -68,32 +73,35 @@ def _check_workload(pl, w, params_list, want=None, queries=None, copy=False, for
     return identical, total
 
 
-@pytest.mark.parametrize("form", ["matrix", "vector"])
+@pytest.mark.parametrize("form,stage2", [("matrix", "inverted"), ("vector", "stream"), ("matrix", "stream")])
 @pytest.mark.parametrize("noise", ["literal", "calibrated"])
-def test_cfg1_all_stages(pl, noise, form):
+def test_cfg1_all_stages(pl, noise, form, stage2):
     cfg = get_config("cfg1")
     w = make_workload(cfg, device="cpu", noise=noise)
-    same, total = _check_workload(pl, w, [(cfg.nprobe, cfg.t_cs, cfg.ndocs, cfg.k)], form=form)
+    same, total = _check_workload(pl, w, [(cfg.nprobe, cfg.t_cs, cfg.ndocs, cfg.k)], form=form, stage2=stage2)
     print(f"cfg1/{noise}: {same}/{total} queries with id lists identical to the oracle's")
     assert same >= total - 1   # near-ties inside 1e-4 at the final cut are the only allowed difference
 
 
-@pytest.mark.parametrize("form", ["matrix", "vector"])
-def test_cfg1_other_operating_points(pl, form):
-    """Table 2's other two triples, and a threshold low enough that many centroids survive."""
+@pytest.mark.parametrize("form,stage2", [("matrix", "inverted"), ("vector", "stream")])
+def test_cfg1_other_operating_points(pl, form, stage2):
+    """Table 2's other two triples, and thresholds low enough that many centroids survive (more than the slot sets hold:
+    both forms then score candidates from their token codes)."""
     cfg = get_config("cfg1")
     w = make_workload(cfg, device="cpu", noise="calibrated")
-    _check_workload(pl, w, [(2, 0.45, 1024, 100), (4, 0.4, 4096, 1000), (3, 0.2, 300, 40), (1, -np.inf, 64, 16)], form=form)
+    _check_workload(pl, w, [(2, 0.45, 1024, 100), (4, 0.4, 4096, 1000), (3, 0.2, 300, 40), (1, -np.inf, 64, 16)], form=form,
+                    stage2=stage2)
 
 
 def test_default_score_kernel_is_the_matrix_form(pl):
     """On gfx950 the device check passes, so an index created without an override uses the matrix instruction."""
     cfg = tiny_config(C=64, P=50, lo=3, hi=9, nbits=2, nq=1, seed=5)
     w = make_workload(cfg, device="cpu", noise="calibrated")
-    with _score_kernel(None):
+    with _kernel_forms(None, None):
         gidx = pl.plaid_index_from_view(pu.device_arrays(w), w.cfg.nbits, device=0, copy=True)
     try:
         assert pl.plaid_get_score_kernel(gidx) == 1
+        assert pl.plaid_get_stage2_kernel(gidx) == 1   # a small index: the range table is tiny
     finally:
         pl.plaid_index_free(gidx)
 
@@ -122,20 +130,23 @@ def test_pipeline_equals_exhaustive_when_nothing_is_filtered(pl):
 
 
 SWEEP = [
-    # C, P, lo, hi, nbits, seed, noise, nq, S_cq kernel (None = the library's choice)
-    (16, 50, 1, 9, 2, 1, "calibrated", 4, None),
-    (16, 50, 1, 9, 1, 2, "literal", 4, None),
-    (5, 7, 1, 3, 2, 3, "calibrated", 3, None),          # an odd number of queries: the last column block is half empty
-    (33, 200, 1, 130, 2, 4, "calibrated", 4, None),     # passages longer than two waves of tokens
-    (70, 321, 0, 40, 1, 5, "calibrated", 4, "vector"),  # empty passages, ragged sizes
-    (1, 9, 1, 5, 2, 6, "literal", 4, None),             # a single centroid
-    (300, 1, 5, 5, 2, 7, "calibrated", 5, None),        # a single passage; three row blocks, the last one ragged
-    (129, 40, 2, 12, 2, 8, "calibrated", 1, "matrix"),  # one row past a row block, one query
+    # C, P, lo, hi, nbits, seed, noise, nq, S_cq kernel, stage-2 form (None = the library's choice)
+    (16, 50, 1, 9, 2, 1, "calibrated", 4, None, None),
+    (16, 50, 1, 9, 1, 2, "literal", 4, None, "stream"),
+    (5, 7, 1, 3, 2, 3, "calibrated", 3, None, None),          # an odd number of queries: the last column block is half empty
+    (33, 200, 1, 130, 2, 4, "calibrated", 4, None, "stream"),  # passages longer than two waves of tokens
+    (33, 200, 1, 130, 2, 4, "calibrated", 4, None, "inverted"),
+    (70, 321, 0, 40, 1, 5, "calibrated", 4, "vector", None),  # empty passages, ragged sizes
+    (1, 9, 1, 5, 2, 6, "literal", 4, None, None),             # a single centroid
+    (300, 1, 5, 5, 2, 7, "calibrated", 5, None, None),        # a single passage; three row blocks, the last one ragged
+    (129, 40, 2, 12, 2, 8, "calibrated", 1, "matrix", "stream"),  # one row past a row block, one query
+    (40, 5000, 1, 6, 2, 9, "calibrated", 3, None, "inverted"),    # three passage ranges, the last one ragged
+    (40, 5000, 1, 6, 2, 9, "calibrated", 3, None, "stream"),
 ]
 
 
-@pytest.mark.parametrize("C,P,lo,hi,nbits,seed,noise,nq,form", SWEEP)
-def test_small_index_sweep(pl, C, P, lo, hi, nbits, seed, noise, nq, form):
+@pytest.mark.parametrize("C,P,lo,hi,nbits,seed,noise,nq,form,stage2", SWEEP)
+def test_small_index_sweep(pl, C, P, lo, hi, nbits, seed, noise, nq, form, stage2):
     w = make_workload(tiny_config(C=C, P=P, lo=lo, hi=hi, nbits=nbits, nq=nq, seed=seed), noise=noise)
     S = orc.scq(w.centroids.numpy(), w.queries[0].numpy())
     qs = np.quantile(S.max(axis=1), [0.3, 0.9]).tolist()
@@ -146,7 +157,7 @@ def test_small_index_sweep(pl, C, P, lo, hi, nbits, seed, noise, nq, form):
                 params.append((nprobe, float(t_cs), ndocs, k))
     # a deterministic subset keeps the run short while every value of every parameter appears
     params = params[:: 3] + params[-2:]
-    _check_workload(pl, w, params, form=form)
+    _check_workload(pl, w, params, form=form, stage2=stage2)
 
 
 def test_codec_bit_exact(pl):

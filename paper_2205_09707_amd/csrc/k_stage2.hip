@@ -198,6 +198,40 @@ __device__ __forceinline__ float s2_score_members(uint64_t members, const float 
     return (float)d;
 }
 
+// The same score with all 32 running maxima in registers and two rows folded per step: one pass over the members.
+// For kernels with registers to spare; the additions are the same and in the same order as in s2_score_members.
+__device__ __forceinline__ float s2_score_members_wide(uint64_t members, const float *Tl, const float *rowsum)
+{
+    if ((members & (members - 1)) == 0) return rowsum[__ffsll((long long)members) - 1];
+    float acc[QLEN];
+#pragma unroll
+    for (int i = 0; i < QLEN; ++i) acc[i] = -INFINITY;
+    uint64_t rest = members;
+    while (rest) {
+        const int s0 = __ffsll((long long)rest) - 1;
+        rest &= rest - 1;
+        int s1 = 0;  // row 0 holds -infinity: a neutral second operand when the member count is odd
+        if (rest) {
+            s1 = __ffsll((long long)rest) - 1;
+            rest &= rest - 1;
+        }
+        const float4 *ra = reinterpret_cast<const float4 *>(Tl + s0 * S2_TSTRIDE);
+        const float4 *rb = reinterpret_cast<const float4 *>(Tl + s1 * S2_TSTRIDE);
+#pragma unroll
+        for (int g = 0; g < QLEN / 4; ++g) {
+            const float4 a = ra[g], b = rb[g];
+            acc[4 * g] = fmaxf(acc[4 * g], fmaxf(a.x, b.x));
+            acc[4 * g + 1] = fmaxf(acc[4 * g + 1], fmaxf(a.y, b.y));
+            acc[4 * g + 2] = fmaxf(acc[4 * g + 2], fmaxf(a.z, b.z));
+            acc[4 * g + 3] = fmaxf(acc[4 * g + 3], fmaxf(a.w, b.w));
+        }
+    }
+    double d = 0.0;
+#pragma unroll
+    for (int i = 0; i < QLEN; ++i) d += (double)acc[i];
+    return (float)d;
+}
+
 // The query's survivor table in LDS: hash table, rows (slot 0 = -infinity) and single-survivor sums.  All threads of
 // the workgroup call this; K <= S2_MAX_KEPT.
 __device__ __forceinline__ void s2_stage_tables(int q, int K, int hsh, const int32_t *__restrict__ kept_ids,
@@ -490,23 +524,37 @@ void plaid_launch_ivf_range_table(hipStream_t st, const int64_t *ivf_offsets, co
     hipLaunchKernelGGL(ivr_fill_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, ivf_offsets, C, nr, table);
 }
 
-// ORs `value | (slot bit)` into the set words of the passages that lists [0, nl) hold inside the range.  lst_start /
-// lst_pref / lst_val describe the lists (position of the first entry in range, exclusive prefix sum of the counts,
-// bits to OR); all threads of the workgroup call this.
+// ORs lst_val[l] into the set words of the passages that list l holds inside the range, for the nl lists described by
+// lst_start (position of the first entry in range), lst_cnt (> 0: entries in range) and lst_val.  A wave takes one list
+// at a time from the shared counter *next (zero on entry) and walks it 256 entries per step, four loads in flight;
+// all threads of the workgroup call this.
 __device__ __forceinline__ void ivr_apply_lists(const int32_t *__restrict__ ivf_pids, const int64_t *lst_start,
-                                                const int32_t *lst_pref, const unsigned long long *lst_val, int nl,
-                                                uint32_t r0, unsigned long long *lsets)
+                                                const int32_t *lst_cnt, const unsigned long long *lst_val, int nl,
+                                                uint32_t r0, unsigned long long *lsets, int32_t *next)
 {
-    const int total = lst_pref[nl];
-    for (int w = threadIdx.x; w < total; w += S2_THREADS) {
-        int lo = 0, hi = nl;  // largest lo with pref[lo] <= w
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (lst_pref[mid] <= w) lo = mid;
-            else hi = mid;
+    const int lane = threadIdx.x & 63;
+    for (;;) {
+        int l = 0;
+        if (lane == 0) l = atomicAdd(next, 1);
+        l = s2_uniform(__shfl(l, 0));
+        if (l >= nl) break;
+        const int cnt = s2_uniform(lst_cnt[l]);
+        const int32_t *__restrict__ src = ivf_pids + lst_start[l];
+        const unsigned long long val = lst_val[l];
+        for (int e0 = 0; e0 < cnt; e0 += 256) {
+            uint32_t pid[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + 64 * u + lane;
+                pid[u] = e < cnt ? (uint32_t)src[e] : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t loc = pid[u] - r0;
+                // (a passage id outside the range, other than the padding value, means a list that is not ascending)
+                if (pid[u] != 0xFFFFFFFFu && loc < (uint32_t)IVR_RANGE) atomicOr(&lsets[loc], val);
+            }
         }
-        const uint32_t loc = (uint32_t)ivf_pids[lst_start[lo] + (w - lst_pref[lo])] - r0;
-        if (loc < (uint32_t)IVR_RANGE) atomicOr(&lsets[loc], lst_val[lo]);  // (always true for ascending lists)
     }
 }
 
@@ -544,9 +592,11 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
     __shared__ float rowsum[S2_MAX_KEPT + 1];
     __shared__ int32_t lhist[SEL_BINS];
     __shared__ int64_t lst_start[IVR_LISTS];
+    __shared__ int32_t lst_cnt[IVR_LISTS];
     __shared__ int32_t lst_pref[IVR_LISTS + 1];
     __shared__ unsigned long long lst_val[IVR_LISTS];
     __shared__ int32_t wave_tot[S2_THREADS / 64];
+    __shared__ int32_t next_list;
     __shared__ uint32_t slot_probed[2];  // bit s: surviving slot s is also a probed centroid
     const int q = blockIdx.y;
     const int64_t r = blockIdx.x;
@@ -567,33 +617,54 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
     for (int u0 = 0; u0 < nu; u0 += IVR_LISTS) {
         const int nb = nu - u0 < IVR_LISTS ? nu - u0 : IVR_LISTS;
         int cnt = 0;
+        int64_t first = 0;
+        unsigned long long val = 0;
         if (tid < nb) {
             const int32_t c = uniq[(int64_t)q * uniq_stride + u0 + tid];
             const uint32_t a = table[(int64_t)c * (nr + 1) + r], b = table[(int64_t)c * (nr + 1) + r + 1];
-            lst_start[tid] = ivf_offsets[c] + a;
+            first = ivf_offsets[c] + a;
             cnt = b > a ? (int)(b - a) : 0;
             const uint32_t sl = slots ? s2_lookup(htab, (uint32_t)c, hsh) : 0u;
-            lst_val[tid] = 1ull | (sl ? 1ull << sl : 0ull);
+            val = 1ull | (sl ? 1ull << sl : 0ull);
             if (sl) atomicOr(&slot_probed[sl >> 5], 1u << (sl & 31));
         }
-        ivr_block_scan(cnt, lst_pref, wave_tot);
-        ivr_apply_lists(ivf_pids, lst_start, lst_pref, lst_val, nb, r0, lsets);
+        // the lists with entries in this range, compacted
+        if (tid == 0) next_list = 0;
+        ivr_block_scan(cnt > 0 ? 1 : 0, lst_pref, wave_tot);
+        if (cnt > 0) {
+            const int at = lst_pref[tid];
+            lst_start[at] = first;
+            lst_cnt[at] = cnt;
+            lst_val[at] = val;
+        }
+        __syncthreads();
+        ivr_apply_lists(ivf_pids, lst_start, lst_cnt, lst_val, lst_pref[S2_THREADS], r0, lsets, &next_list);
         __syncthreads();
     }
     // surviving centroids that were not probed: slot bit only
     if (slots) {
         int cnt = 0;
+        int64_t first = 0;
         if (tid < K) {
             const int sl = tid + 1;
-            const int32_t c = kept_ids[(int64_t)q * S2_MAX_KEPT + tid];
             const bool seen = (slot_probed[sl >> 5] >> (sl & 31)) & 1u;
-            const uint32_t a = table[(int64_t)c * (nr + 1) + r], b = table[(int64_t)c * (nr + 1) + r + 1];
-            lst_start[tid] = ivf_offsets[c] + a;
-            cnt = (!seen && b > a) ? (int)(b - a) : 0;
-            lst_val[tid] = 1ull << sl;
+            if (!seen) {
+                const int32_t c = kept_ids[(int64_t)q * S2_MAX_KEPT + tid];
+                const uint32_t a = table[(int64_t)c * (nr + 1) + r], b = table[(int64_t)c * (nr + 1) + r + 1];
+                first = ivf_offsets[c] + a;
+                cnt = b > a ? (int)(b - a) : 0;
+            }
         }
-        ivr_block_scan(cnt, lst_pref, wave_tot);
-        ivr_apply_lists(ivf_pids, lst_start, lst_pref, lst_val, K, r0, lsets);
+        if (tid == 0) next_list = 0;
+        ivr_block_scan(cnt > 0 ? 1 : 0, lst_pref, wave_tot);
+        if (cnt > 0) {
+            const int at = lst_pref[tid];
+            lst_start[at] = first;
+            lst_cnt[at] = cnt;
+            lst_val[at] = 1ull << (tid + 1);
+        }
+        __syncthreads();
+        ivr_apply_lists(ivf_pids, lst_start, lst_cnt, lst_val, lst_pref[S2_THREADS], r0, lsets, &next_list);
         __syncthreads();
     }
 
@@ -613,7 +684,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
         if (slots) {
             empty = members == 0;
             if (cand) {
-                const float score = empty ? -INFINITY : s2_score_members(members, Tl, rowsum);
+                const float score = empty ? -INFINITY : s2_score_members_wide(members, Tl, rowsum);
                 keys_out[pid] = empty ? PLAID_KEY_MAX : plaid_make_key(score, (uint32_t)pid);
                 if (!empty) atomicAdd(&lhist[plaid_s2_bin(score, bin_hi, bin_scale)], 1);
             }

@@ -189,7 +189,7 @@ def main():
     ap.add_argument("--config", default="cfg3", help="cfg1 .. cfg5 (synth/workload.py)")
     ap.add_argument("--noise", default="literal", choices=["literal", "calibrated"])
     ap.add_argument("--latency-queries", type=int, default=512, help="queries timed one per call for p50/p99")
-    ap.add_argument("--cpu-sample", type=int, default=16, help="queries the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=512, help="queries the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--single-noise", action="store_true", help="skip the run on the other reading of the noise scale")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -242,6 +242,9 @@ def main():
                "seconds": round(dt_cpu, 2), "id_agreement_with_gpu": agree}
         log(f"[bench] CPU oracle: {ns} queries in {dt_cpu:.2f}s on {used} threads; id agreement with GPU {agree:.4f}")
 
+    forms = {"score_kernel": "matrix" if pl.plaid_get_score_kernel(idx) else "vector",
+             "stage2_kernel": "inverted" if pl.plaid_get_stage2_kernel(idx) else "stream"}
+    n_embeddings = int(w.N)
     pl.plaid_index_free(idx)
     del w, idx, Q, r
     torch.cuda.empty_cache()
@@ -260,10 +263,10 @@ def main():
         "metric": "queries_per_sec", "value": round(qps, 2), "unit": "queries/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64/f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name} ({args.noise} noise): C={cfg.C} centroids, P={cfg.P} passages, N={w.N} "
+        "config": {"workload": f"{cfg.name} ({args.noise} noise): C={cfg.C} centroids, P={cfg.P} passages, N={n_embeddings} "
                                f"embeddings, {cfg.nbits}-bit residuals, {nq} queries x 32 x 128",
                    "nprobe": cfg.nprobe, "t_cs": cfg.t_cs, "ndocs": cfg.ndocs, "k": cfg.k,
-                   "queries_per_step": nq, "index_generated_on": "cuda",
+                   "queries_per_step": nq, "index_generated_on": "cuda", **forms,
                    "arithmetic": "S_cq and the centroid-interaction sums accumulate in f64 (stored f32); MaxSim in f32"},
         "latency_batch1_ms": {"p50": round(float(np.percentile(lat, 50)), 4), "p99": round(float(np.percentile(lat, 99)), 4),
                               "mean": round(float(lat.mean()), 4), "queries": int(nlat), "trials": 3, "host_enqueue_p50": round(float(np.percentile(enq, 50)), 4),

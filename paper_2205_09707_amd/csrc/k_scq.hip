@@ -43,25 +43,17 @@
 #define TAIL_THREADS 1024
 #define TAIL_LANES 32     // lanes of the tail kernel that share one query token
 
-// Clears the workspace region that must start at zero and lays out the queries for the score kernel:
-// vector form   Qd[q][g][t][u] = (double) Q[q][4g + u][t];
-// matrix form   Qm[q][s][h][lane] = Q[q][16h + (lane & 15)][4s + (lane >> 4)]  (the B operand of step s, column tile h).
-__global__ __launch_bounds__(256) void stage1_prep_kernel(const float *__restrict__ Q, void *__restrict__ Qx, int nq,
-                                                          int matrix_form, uint32_t *__restrict__ zero, int64_t zero_words)
+// Vector form only (the matrix form does both inside its score kernel): clears the workspace region that must start
+// at zero and lays out the queries, Qd[q][g][t][u] = (double) Q[q][4g + u][t].
+__global__ __launch_bounds__(256) void stage1_prep_kernel(const float *__restrict__ Q, double *__restrict__ Qd, int nq,
+                                                          uint32_t *__restrict__ zero, int64_t zero_words)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < zero_words; i += (int64_t)gridDim.x * blockDim.x)
         zero[i] = 0u;
     for (int q = blockIdx.x; q < nq; q += gridDim.x)
         for (int e = threadIdx.x; e < QLEN * DIM; e += blockDim.x) {
-            if (matrix_form) {
-                const int lane = e & 63, h = (e >> 6) & 1, s = e >> 7;
-                reinterpret_cast<float *>(Qx)[(int64_t)q * QLEN * DIM + e] =
-                    Q[(int64_t)q * QLEN * DIM + (16 * h + (lane & 15)) * DIM + 4 * s + (lane >> 4)];
-            } else {
-                const int u = e & 3, t = (e >> 2) & (DIM - 1), g = e >> 9;
-                reinterpret_cast<double *>(Qx)[(int64_t)q * QLEN * DIM + e] =
-                    (double)Q[(int64_t)q * QLEN * DIM + (4 * g + u) * DIM + t];
-            }
+            const int u = e & 3, t = (e >> 2) & (DIM - 1), g = e >> 9;
+            Qd[(int64_t)q * QLEN * DIM + e] = (double)Q[(int64_t)q * QLEN * DIM + (4 * g + u) * DIM + t];
         }
 }
 
@@ -385,9 +377,10 @@ __device__ __forceinline__ void scq_insert_pair(uint32_t (&bo)[NP], uint32_t (&b
 // partial: [q][token][row block][NP].
 template <int NP, int NQ>
 __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(const float *__restrict__ Cm, int64_t C,
-                                                              const float *__restrict__ Qm, int nq, float t_cs,
+                                                              const float *__restrict__ Q, int nq, float t_cs,
                                                               float *__restrict__ S, uint32_t *__restrict__ keepbits,
-                                                              int64_t keep_words, uint64_t *__restrict__ partial)
+                                                              int64_t keep_words, uint64_t *__restrict__ partial,
+                                                              uint32_t *__restrict__ zero, int64_t zero_words)
 {
     constexpr int NPK = NP > 0 ? NP : 1;
     constexpr int NT = 2 * NQ;  // 16-column tiles
@@ -401,6 +394,11 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
     uint64_t *lk = reinterpret_cast<uint64_t *>(arena + SM_ROWS * SM_TSTRIDE);  // [8][32][NPK]
     const int tid = threadIdx.x, lane = tid & 63, li = lane & 15, lg = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // the workspace words that later kernels expect to be zero are cleared here, by the whole grid (no kernel of this
+    // search has touched them yet, and every kernel of the previous one has finished)
+    for (int64_t i = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * SM_THREADS + tid; i < zero_words;
+         i += (int64_t)gridDim.x * gridDim.y * SM_THREADS)
+        zero[i] = 0u;
     const int q0 = blockIdx.x * NQ;
     const int64_t c0 = (int64_t)blockIdx.y * SM_ROWS;
     const int nrows = (int)(C - c0 < SM_ROWS ? C - c0 : SM_ROWS);
@@ -414,14 +412,19 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
         pre[k] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (r < nrows) pre[k] = *reinterpret_cast<const float4 *>(Cm + (c0 + r) * DIM + 4 * c4);
     }
-    // the queries' operands of a chunk are 8 steps x 2 halves x 64 lanes = 256 float4 per query, one per thread
-    // (zeros for a query past the end)
+    // The queries' operands of a chunk, in operand order [step][column tile][lane]: 8 steps x 2 halves x 64 lanes per
+    // query, four consecutive lanes per thread (zeros for a query past the end).  Lane 16 g + i of step s, half h holds
+    // Q[16 h + i][4 s + g], so a thread's four values are one column of four consecutive query tokens.
     const int bdst = (((tid >> 5) * NT + ((tid >> 4) & 1)) * 64 + 4 * (tid & 15));  // + 2 qi column tiles
+    const int bsrc = (16 * ((tid >> 4) & 1) + 4 * (tid & 3)) * DIM + 4 * (tid >> 5) + ((tid >> 2) & 3);  // + 32 ch
     float4 preb[NQ];
 #pragma unroll
     for (int qi = 0; qi < NQ; ++qi) {
         preb[qi] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (q0 + qi < nq) preb[qi] = reinterpret_cast<const float4 *>(Qm + (int64_t)(q0 + qi) * QLEN * DIM)[tid];
+        if (q0 + qi < nq) {
+            const float *src = Q + (int64_t)(q0 + qi) * QLEN * DIM + bsrc;
+            preb[qi] = make_float4(src[0], src[DIM], src[2 * DIM], src[3 * DIM]);
+        }
     }
     scq_double4 acc[SM_RT][NT];
 #pragma unroll
@@ -446,8 +449,10 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
             }
 #pragma unroll
             for (int qi = 0; qi < NQ; ++qi)
-                if (q0 + qi < nq)
-                    preb[qi] = reinterpret_cast<const float4 *>(Qm + (int64_t)(q0 + qi) * QLEN * DIM)[(ch + 1) * SM_THREADS + tid];
+                if (q0 + qi < nq) {
+                    const float *src = Q + (int64_t)(q0 + qi) * QLEN * DIM + bsrc + SM_KC * (ch + 1);
+                    preb[qi] = make_float4(src[0], src[DIM], src[2 * DIM], src[3 * DIM]);
+                }
         }
 #pragma unroll
         for (int j = 0; j < SM_KC / 4; ++j) {
@@ -665,19 +670,19 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
 }
 
 template <int NP>
-static void launch_fused(hipStream_t st, int phases, const float *centroids, int64_t C, const void *Qx, int matrix_form, int nq,
-                         float t_cs, float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int nprobe,
-                         const Stage1Out &o)
+static void launch_fused(hipStream_t st, int phases, const float *centroids, int64_t C, const float *Q, const void *Qx,
+                         int matrix_form, int nq, float t_cs, float *S, uint32_t *keepbits, int64_t keep_words,
+                         uint64_t *partial, int nprobe, const Stage1Out &o, uint32_t *zero, int64_t zero_words)
 {
     const unsigned nblk = (unsigned)(matrix_form ? (C + SM_ROWS - 1) / SM_ROWS : (C + SCQ_ROWS - 1) / SCQ_ROWS);
     if (!(phases & PLAID_STAGE1_SCORES)) {
     } else if (matrix_form) {
         if (nq == 1)
-            hipLaunchKernelGGL((scq_mfma_kernel<NP, 1>), dim3(1, nblk), dim3(SM_THREADS), 0, st, centroids, C, (const float *)Qx,
-                               nq, t_cs, S, keepbits, keep_words, partial);
+            hipLaunchKernelGGL((scq_mfma_kernel<NP, 1>), dim3(1, nblk), dim3(SM_THREADS), 0, st, centroids, C, Q, nq, t_cs, S,
+                               keepbits, keep_words, partial, zero, zero_words);
         else
             hipLaunchKernelGGL((scq_mfma_kernel<NP, 2>), dim3((unsigned)((nq + 1) / 2), nblk), dim3(SM_THREADS), 0, st, centroids,
-                               C, (const float *)Qx, nq, t_cs, S, keepbits, keep_words, partial);
+                               C, Q, nq, t_cs, S, keepbits, keep_words, partial, zero, zero_words);
     } else {
         hipLaunchKernelGGL(scq_fused_kernel<NP>, dim3(nblk, nq), dim3(SCQ_THREADS), 0, st, centroids, C, (const double *)Qx, t_cs,
                            S, keepbits, keep_words, partial);
@@ -699,11 +704,11 @@ void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int
                          uint32_t *zero, int64_t zero_words, int32_t *probed, int32_t *uniq, int uniq_stride,
                          int32_t *n_uniq, const Stage2Buffers &s2, void *probe_scratch, size_t probe_scratch_bytes)
 {
-    if (phases & PLAID_STAGE1_PREP) {
+    if ((phases & PLAID_STAGE1_PREP) && !matrix_form) {
         int64_t gz = (zero_words + 256 * 8 - 1) / (256 * 8);
         if (gz < nq) gz = nq;
         if (gz > 1024) gz = 1024;
-        hipLaunchKernelGGL(stage1_prep_kernel, dim3((unsigned)gz), dim3(256), 0, st, Q, Qd, nq, matrix_form, zero, zero_words);
+        hipLaunchKernelGGL(stage1_prep_kernel, dim3((unsigned)gz), dim3(256), 0, st, Q, (double *)Qd, nq, zero, zero_words);
     }
     if (!(phases & (PLAID_STAGE1_SCORES | PLAID_STAGE1_PROBES))) return;
     Stage1Out o;
@@ -714,14 +719,19 @@ void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int
     o.meta = s2.meta;
     o.kept_ids = s2.kept_ids;
     o.T = s2.T;
-    if (nprobe == 1) launch_fused<1>(st, phases, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
-    else if (nprobe == 2) launch_fused<2>(st, phases, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
-    else if (nprobe <= 4) launch_fused<4>(st, phases, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+    if (nprobe == 1) launch_fused<1>(st, phases, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o, zero,
+                        zero_words);
+    else if (nprobe == 2) launch_fused<2>(st, phases, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o, zero,
+                        zero_words);
+    else if (nprobe <= 4) launch_fused<4>(st, phases, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o, zero,
+                        zero_words);
     else if (nprobe <= PLAID_PROBE_FAST_MAX)
-        launch_fused<8>(st, phases, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+        launch_fused<8>(st, phases, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o, zero,
+                        zero_words);
     else {
         // large nprobe: scores and pruning bits here, probes through the generic selection, survivor table after it
-        launch_fused<0>(st, phases, centroids, C, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o);
+        launch_fused<0>(st, phases, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o, zero,
+                        zero_words);
         if (phases & PLAID_STAGE1_PROBES) {
             plaid_launch_top_nprobe_general(st, S, C, nq, nprobe, probed, uniq, uniq_stride, n_uniq, probe_scratch,
                                             probe_scratch_bytes);

@@ -550,6 +550,7 @@ __global__ __launch_bounds__(SEL_THREADS) void sel2_filter_kernel(const uint64_t
     const int seg = blockIdx.y;
     Sel2State *s = state + seg;
     const S2Meta mt = meta[seg];
+    if (mt.K == 0) return;  // no surviving centroid: no valid key, the state stays zero and the fill takes over
     int bstar, before;
     find_boundary(hist + (int64_t)seg * SEL_BINS, 0, scan, res, bstar, before, m);  // takes min(m, number of keys)
     const int32_t n_keys = scan[SEL_THREADS - 1];
@@ -560,31 +561,54 @@ __global__ __launch_bounds__(SEL_THREADS) void sel2_filter_kernel(const uint64_t
     uint64_t *my_out = out + (int64_t)seg * out_stride;
     uint64_t *my_bl = blist + (int64_t)seg * blist_stride;
     const int lane = threadIdx.x & 63;
-    const int64_t n_round = (P + 63) & ~63ll;  // whole waves iterate together (ballots below)
+    // A wave takes SEL2_GROUPS x 64 consecutive slots per step and reserves its output positions with one pair of
+    // counter updates per step (the updates return a value, so their round trip is the step's latency).
+    constexpr int SEL2_GROUPS = 4;
+    const int64_t wave_id = (int64_t)blockIdx.x * (SEL_THREADS / 64) + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int64_t n_waves = (int64_t)gridDim.x * (SEL_THREADS / 64);
     unsigned long long o = 0, no = 0;
-    for (int64_t i = (int64_t)blockIdx.x * SEL_THREADS + threadIdx.x; i < n_round; i += (int64_t)gridDim.x * SEL_THREADS) {
-        // slot i is meaningful only when passage i is a candidate; it then holds its key or the invalid key
-        uint64_t key = PLAID_KEY_MAX;
-        if (i < P && ((cb[i >> 5] >> (i & 31)) & 1u)) key = k[i];
-        int cls = 2;  // 0 = surely selected, 1 = boundary, 2 = dropped
-        if (key != PLAID_KEY_MAX) {
-            const int d = plaid_s2_bin(plaid_ord_to_score((uint32_t)(key >> 32)), mt.bin_hi, mt.bin_scale);
-            cls = d < bstar ? 0 : (d == bstar ? 1 : 2);
+    for (int64_t i0 = wave_id * (64 * SEL2_GROUPS); i0 < P; i0 += n_waves * (64 * SEL2_GROUPS)) {  // uniform per wave
+        uint64_t key[SEL2_GROUPS];
+        int cls[SEL2_GROUPS];  // 0 = surely selected, 1 = boundary, 2 = dropped
+        unsigned long long b0[SEL2_GROUPS], b1[SEL2_GROUPS];
+        int n0 = 0, n1 = 0;
+#pragma unroll
+        for (int u = 0; u < SEL2_GROUPS; ++u) {
+            // slot i is meaningful only when passage i is a candidate; it then holds its key or the invalid key
+            const int64_t i = i0 + 64 * u + lane;
+            key[u] = PLAID_KEY_MAX;
+            if (i < P && ((cb[i >> 5] >> (i & 31)) & 1u)) key[u] = k[i];
         }
-        const unsigned long long b0 = __ballot(cls == 0), b1 = __ballot(cls == 1);
+#pragma unroll
+        for (int u = 0; u < SEL2_GROUPS; ++u) {
+            cls[u] = 2;
+            if (key[u] != PLAID_KEY_MAX) {
+                const int d = plaid_s2_bin(plaid_ord_to_score((uint32_t)(key[u] >> 32)), mt.bin_hi, mt.bin_scale);
+                cls[u] = d < bstar ? 0 : (d == bstar ? 1 : 2);
+            }
+            b0[u] = __ballot(cls[u] == 0);
+            b1[u] = __ballot(cls[u] == 1);
+            n0 += __popcll(b0[u]);
+            n1 += __popcll(b1[u]);
+        }
         const unsigned long long below = (1ull << lane) - 1ull;
         int base0 = 0, base1 = 0;
         if (lane == 0) {
-            if (b0) base0 = atomicAdd(&s->n_sure, __popcll(b0));
-            if (b1) base1 = atomicAdd(&s->n_b, __popcll(b1));
+            if (n0) base0 = atomicAdd(&s->n_sure, n0);
+            if (n1) base1 = atomicAdd(&s->n_b, n1);
         }
         base0 = __shfl(base0, 0);
         base1 = __shfl(base1, 0);
-        if (cls == 0) my_out[base0 + __popcll(b0 & below)] = key;
-        if (cls == 1) {
-            my_bl[base1 + __popcll(b1 & below)] = key;
-            o |= key;
-            no |= ~key;
+#pragma unroll
+        for (int u = 0; u < SEL2_GROUPS; ++u) {
+            if (cls[u] == 0) my_out[base0 + __popcll(b0[u] & below)] = key[u];
+            if (cls[u] == 1) {
+                my_bl[base1 + __popcll(b1[u] & below)] = key[u];
+                o |= key[u];
+                no |= ~key[u];
+            }
+            base0 += __popcll(b0[u]);
+            base1 += __popcll(b1[u]);
         }
     }
     for (int d = 1; d < 64; d <<= 1) {

@@ -29,7 +29,10 @@ FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
 # each scaled by the counter's reading on a 1 GiB device copy (fetch reads half the bytes: x2; write: x1).
 # Source of every figure: the profiles/ summary named here.  Missing = not measured (reported as null).
 MEASURED_TRAFFIC_PER_LAUNCH = {
-    # (config, noise, stage): bytes
+    # (config, noise, stage): bytes; profiles/bench_cfg3.txt
+    ("cfg3", "literal", "scq"): int((131828.2 * 2.0 + 547842.9) * 1024),
+    ("cfg3", "literal", "stage2_ci"): int((123879.7 * 2.0 + 124991.3) * 1024),
+    ("cfg3", "literal", "stage4_maxsim"): int((70114.2 * 2.0 + 139.2) * 1024),
 }
 
 
@@ -39,8 +42,11 @@ def log(*a):
 
 def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
     """What the method must move, from the library's own candidate and survivor lists.
-    Stage 2 (Eq. 3-5): per candidate passage 8 bytes of offsets + 4 bytes per token code; for a query none of whose
-    centroids passes Eq. 5 every bag is empty whatever the codes hold, and only the candidate bitmap is read and written.
+    Stage 2 (Eq. 3-5), code-stream figure: per candidate passage 8 bytes of offsets + 4 bytes per token code; for a query
+    none of whose centroids passes Eq. 5 every bag is empty whatever the codes hold, and only the candidate bitmap is read
+    and written.  Inverted-list figure (what the inverted form of candidate generation + stage 2 must move instead): 4 bytes
+    per entry of the inverted lists of the probed and the surviving centroids, 8 bytes per key written (queries with a
+    surviving centroid) and the candidate and empty-bag words.
     Stage 4 (Section 4.5, Eq. 1): per surviving passage 8 bytes of offsets and per token its 4-byte code, its packed
     residual (16 * nbits bytes) and the 128-byte S_cq row that carries the centroid's share of the dot products."""
     import torch
@@ -50,19 +56,27 @@ def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
     s4 = 0
     s4_tokens = 0
     n_skipped = 0
+    inv = 0
+    ivf_len = (w_dev.ivf_offsets[1:] - w_dev.ivf_offsets[:-1])
     ncand = []
     step = 64   # the library's chunk size, so that these launches look like the timed ones to a profiler
     for q0 in range(0, Q.shape[0], step):
         _, _, b = pl.plaid_search_debug(idx, Q[q0:q0 + step], nprobe, t_cs, ndocs, k,
-                                        want=("S_cq", "cand", "n_cand", "sel3_ids", "n3"))
+                                        want=("S_cq", "probed", "cand", "n_cand", "sel3_ids", "n3"))
         torch.cuda.synchronize()
-        survivors = (b["S_cq"].max(dim=2).values >= t_cs).sum(dim=1).tolist()   # centroids passing Eq. 5, per query
+        keep = b["S_cq"].max(dim=2).values >= t_cs                              # [queries, C]: centroids passing Eq. 5
+        survivors = keep.sum(dim=1).tolist()
         del b["S_cq"]
+        for j in range(keep.shape[0]):
+            lists = keep[j].clone() if survivors[j] <= 63 else torch.zeros_like(keep[j])
+            lists[b["probed"][j].flatten().long()] = True
+            inv += 4 * int(ivf_len[lists].sum()) + 2 * 4 * ((cfg.P + 31) // 32)
         for j in range(b["cand"].shape[0]):
             n = int(b["n_cand"][j])
             c = b["cand"][j, :n].long()
             if survivors[j] > 0:
                 s2 += 8 * n + 4 * int(lens[c].sum())
+                inv += 8 * n if survivors[j] <= 63 else 8 * n + 4 * int(lens[c].sum())
             else:
                 s2 += 8 * ((cfg.P + 31) // 32)
                 n_skipped += 1
@@ -71,7 +85,7 @@ def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
             t = int(lens[b["sel3_ids"][j, :n3].long()].sum())
             s4_tokens += t
             s4 += 8 * n3 + t * (4 + 16 * cfg.nbits + 128)
-    return {"stage2_bytes": s2, "stage4_bytes": s4, "stage4_tokens": s4_tokens,
+    return {"stage2_bytes": s2, "stage2_inverted_bytes": inv, "stage4_bytes": s4, "stage4_tokens": s4_tokens,
             "mean_candidates": float(sum(ncand)) / max(1, len(ncand)), "queries_without_survivors": n_skipped}
 
 
@@ -159,10 +173,14 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
             "scq", "S_cq = C.Q^T (Eq. 2) in double through the fp64 matrix instruction" if pl.plaid_get_score_kernel(idx)
             else "S_cq = C.Q^T (Eq. 2), fp64 fused multiply-add chain", "mfma", scq_flop, 1e12, FP64_MFMA_PEAK_TFLOPS, "TFLOP/s",
             {"algorithmic_flop_per_step": scq_flop, "algorithmic_flop_per_launch": scq_flop / launches, "dtype": "f64"})
+        inverted = bool(pl.plaid_get_stage2_kernel(idx))
+        s2_bytes = work["stage2_inverted_bytes"] if inverted else work["stage2_bytes"]
         rooflines["stage2_ci"] = entry(
-            "stage2_ci", "stage-2 centroid interaction (Eq. 3-5) over all candidates", "hbm", work["stage2_bytes"], 1e9,
+            "stage2_ci", ("candidates + stage-2 centroid interaction (Section 4.1, Eq. 3-5) from the inverted lists" if inverted
+                          else "stage-2 centroid interaction (Eq. 3-5) streaming the candidates' codes"), "hbm", s2_bytes, 1e9,
             HBM_PEAK_GBS, "GB/s",
-            {"algorithmic_bytes_per_step": work["stage2_bytes"], "algorithmic_bytes_per_launch": work["stage2_bytes"] // launches,
+            {"algorithmic_bytes_per_step": s2_bytes, "algorithmic_bytes_per_launch": s2_bytes // launches,
+             "code_stream_bytes_per_step": work["stage2_bytes"],
              "mean_candidates_per_query": work["mean_candidates"],
              "queries_without_surviving_centroid": work["queries_without_survivors"]})
         rooflines["stage4_maxsim"] = entry(

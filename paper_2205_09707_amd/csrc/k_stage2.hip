@@ -586,7 +586,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
     uint64_t *__restrict__ keys2, int64_t key_stride, int32_t *__restrict__ hist, uint32_t *__restrict__ emptybits)
 {
     __shared__ unsigned long long lsets[IVR_RANGE];
-    __shared__ uint32_t lcand[IVR_RANGE / 32];
+    __shared__ uint32_t lcand[IVR_RANGE / 32], lempty[IVR_RANGE / 32];
     __shared__ uint32_t htab[S2_HASH];
     __shared__ __align__(16) float Tl[(S2_MAX_KEPT + 1) * S2_TSTRIDE];
     __shared__ float rowsum[S2_MAX_KEPT + 1];
@@ -691,24 +691,21 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
         }
         const unsigned long long em = __ballot(cand && empty);
         if (lane == 0) {
-            const int64_t w0 = w_first + 2 * g;
-            if (w0 < cand_words) {
-                cbq[w0] = (uint32_t)cm;
-                lcand[2 * g] = (uint32_t)cm;
-                if (K <= S2_MAX_KEPT) ebq[w0] = (uint32_t)em;
-            }
-            if (w0 + 1 < cand_words) {
-                cbq[w0 + 1] = (uint32_t)(cm >> 32);
-                lcand[2 * g + 1] = (uint32_t)(cm >> 32);
-                if (K <= S2_MAX_KEPT) ebq[w0 + 1] = (uint32_t)(em >> 32);
-            }
+            lcand[2 * g] = (uint32_t)cm;
+            lcand[2 * g + 1] = (uint32_t)(cm >> 32);
+            lempty[2 * g] = (uint32_t)em;
+            lempty[2 * g + 1] = (uint32_t)(em >> 32);
         }
     }
+    __syncthreads();
+    // the range's candidate and empty-bag words, one contiguous store each
+    int64_t w_end = w_first + IVR_RANGE / 32;
+    if (w_end > cand_words) w_end = cand_words;
+    if (tid < IVR_RANGE / 32 && w_first + tid < w_end) cbq[w_first + tid] = lcand[tid];
+    if (K <= S2_MAX_KEPT && tid >= 64 && tid < 64 + IVR_RANGE / 32 && w_first + (tid - 64) < w_end)
+        ebq[w_first + tid - 64] = lempty[tid - 64];
     if (K > S2_MAX_KEPT) {
         // too many survivors for slot sets: the range's candidates are scored from their token codes
-        __syncthreads();
-        int64_t w_end = w_first + IVR_RANGE / 32;
-        if (w_end > cand_words) w_end = cand_words;
         s2_gather_body(q, S, C, keepbits, keep_words, lcand, w_first, w_first + wave, S2_THREADS / 64, w_end, cand_words, P,
                        doc_offsets, codes, bin_hi, bin_scale, keys_out, lhist, emptybits);
     }

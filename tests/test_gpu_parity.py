@@ -160,6 +160,29 @@ def test_small_index_sweep(pl, C, P, lo, hi, nbits, seed, noise, nq, form, stage
     _check_workload(pl, w, params, form=form, stage2=stage2)
 
 
+RARE = [
+    # name, config, parameter list, stage-2 forms
+    # two centroids: thousands of passages share each pruned score, so the stage-2 cut falls inside a tie group far
+    # longer than one workgroup can sort (digit filter on the passage-id bits), and ndocs > 8192 sends stage 3's
+    # selection through the multi-level radix path
+    ("tie_groups", dict(C=2, P=40000, lo=1, hi=3, nbits=2, nq=2, seed=31), [(2, -np.inf, 9000, 10), (1, 0.0, 300, 5)],
+     ("inverted", "stream")),
+    # passages longer than the streaming kernel's staging buffer (2272 tokens) and than many 32-token steps of stage 4
+    ("long_passages", dict(C=50, P=6, lo=2300, hi=2400, nbits=1, nq=2, seed=32), [(2, 0.1, 4, 2), (50, -np.inf, 6, 6)],
+     ("stream", "inverted")),
+    # ndocs/4 and k beyond 8192: radix selection of the stage-3 survivors and of the final ranking, sorted output
+    # through the global bitonic network
+    ("big_lists", dict(C=8, P=40000, lo=1, hi=2, nbits=2, nq=1, seed=33), [(8, -np.inf, 40000, 12000)], ("inverted",)),
+]
+
+
+@pytest.mark.parametrize("name,cfgkw,params,forms", RARE, ids=[r[0] for r in RARE])
+def test_rare_paths(pl, name, cfgkw, params, forms):
+    w = make_workload(tiny_config(**cfgkw), noise="calibrated")
+    for stage2 in forms:
+        _check_workload(pl, w, params, stage2=stage2)
+
+
 def test_codec_bit_exact(pl):
     """Unpacked bucket indices and reconstructed vectors (Section 4.5) are bit-identical to the oracle's."""
     for nbits, seed in ((2, 21), (1, 22)):

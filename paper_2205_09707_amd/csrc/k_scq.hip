@@ -354,6 +354,15 @@ __device__ __forceinline__ scq_double4 scq_mma(double a, double b, scq_double4 c
     return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
 }
 
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits for every outstanding global store, and
+// this kernel has 16 KB of score stores in flight per query when it reaches the barriers that guard the LDS tile.
+__device__ __forceinline__ void scq_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 template <int NP>
 __device__ __forceinline__ void scq_insert_pair(uint32_t (&bo)[NP], uint32_t (&bi)[NP], uint32_t o, uint32_t id)
 {
@@ -384,14 +393,10 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
 {
     constexpr int NPK = NP > 0 ? NP : 1;
     constexpr int NT = 2 * NQ;  // 16-column tiles
-    constexpr int LIST_FLOATS = 8 * QLEN * NPK * 2;
-    constexpr int ARENA_FLOATS = SM_ROWS * SM_ASTRIDE > SM_ROWS * SM_TSTRIDE + LIST_FLOATS ? SM_ROWS * SM_ASTRIDE
-                                                                                           : SM_ROWS * SM_TSTRIDE + LIST_FLOATS;
-    __shared__ __align__(16) float arena[ARENA_FLOATS];   // staged centroid chunk, later the result tile and the lists
+    constexpr int ARENA_FLOATS = SM_ROWS * (SM_ASTRIDE > SM_TSTRIDE ? SM_ASTRIDE : SM_TSTRIDE);
+    __shared__ __align__(16) float arena[ARENA_FLOATS];   // staged centroid chunk, later the result tile
     __shared__ __align__(16) float Bq[(SM_KC / 4) * NT * 64];    // the chunk's query operands: [step][column tile][lane]
-    static_assert((SM_ROWS * SM_TSTRIDE) % 2 == 0, "list area must be 8-byte aligned");
     float *tile = arena;
-    uint64_t *lk = reinterpret_cast<uint64_t *>(arena + SM_ROWS * SM_TSTRIDE);  // [8][32][NPK]
     const int tid = threadIdx.x, lane = tid & 63, li = lane & 15, lg = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // the workspace words that later kernels expect to be zero are cleared here, by the whole grid (no kernel of this
@@ -440,7 +445,7 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
             *reinterpret_cast<float4 *>(arena + (r0 + 32 * k) * SM_ASTRIDE + 4 * c4) = pre[k];
 #pragma unroll
         for (int qi = 0; qi < NQ; ++qi) *reinterpret_cast<float4 *>(Bq + bdst + 2 * qi * 64) = preb[qi];
-        __syncthreads();
+        scq_lds_barrier();
         if (ch + 1 < DIM / SM_KC) {
 #pragma unroll
             for (int k = 0; k < SM_ROWS / 32; ++k) {
@@ -466,22 +471,41 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
 #pragma unroll
                 for (int t = 0; t < NT; ++t) acc[m][t] = scq_mma(a[m], b[t], acc[m][t]);
         }
-        __syncthreads();  // every wave is done with this chunk: the arena is rewritten next
+        scq_lds_barrier();  // every wave is done with this chunk: the arena is rewritten next
     }
 
     // epilogue, one query at a time through the LDS tile
+    static_assert(SM_RT == 2, "a wave's 32 rows are one word of the pruning bitmap");
 #pragma unroll
     for (int qi = 0; qi < NQ; ++qi) {
         const int q = q0 + qi;
         if (q >= nq) break;  // uniform
+        // results to the tile; Eq. 5 on the way: a row's maximum over the 32 tokens is the maximum over this lane's two
+        // columns, then over the 16 lanes that share the row (two quad swaps, then the mirrors of 8 and of 16 lanes)
+        uint32_t kbits = 0u;
 #pragma unroll
         for (int m = 0; m < SM_RT; ++m)
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    tile[(wave * 16 * SM_RT + 16 * m + 4 * r + lg) * SM_TSTRIDE + 16 * h + li] = (float)acc[m][2 * qi + h][r];
-        __syncthreads();
+            for (int r = 0; r < 4; ++r) {
+                const int row = 16 * m + 4 * r + lg;  // within the wave's 32 rows
+                const float v0 = (float)acc[m][2 * qi][r], v1 = (float)acc[m][2 * qi + 1][r];
+                float *trow = tile + (wave * 16 * SM_RT + row) * SM_TSTRIDE + li;
+                trow[0] = v0;
+                trow[16] = v1;
+                float mx = fmaxf(v0, v1);
+                mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0xB1, 0xF, 0xF, false)));
+                mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x4E, 0xF, 0xF, false)));
+                mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x141, 0xF, 0xF, false)));
+                mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x140, 0xF, 0xF, false)));
+                if (wave * 16 * SM_RT + row < nrows && mx >= t_cs) kbits |= 1u << row;
+            }
+        kbits |= __shfl_xor(kbits, 16);
+        kbits |= __shfl_xor(kbits, 32);
+        if (lane == 0) {
+            const int64_t w0 = (c0 >> 5) + wave;
+            if (w0 < keep_words) keepbits[(int64_t)q * keep_words + w0] = kbits;
+        }
+        scq_lds_barrier();
         // scores, coalesced: the tile's rows are contiguous in S
         for (int e = tid; e < SM_ROWS * (QLEN / 4); e += SM_THREADS) {
             const int r = e >> 3, k4 = e & 7;
@@ -490,49 +514,71 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
                 *reinterpret_cast<float4 *>(S + ((int64_t)q * C + c0 + r) * QLEN + 4 * k4) = make_float4(tr[0], tr[1], tr[2], tr[3]);
             }
         }
-        // Eq. 5: pruning bits of the rows (thread = row)
-        if (tid < SM_ROWS) {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int i = 0; i < QLEN; ++i) mx = fmaxf(mx, tile[tid * SM_TSTRIDE + i]);
-            const unsigned long long b = __ballot(tid < nrows && mx >= t_cs);
-            if ((tid & 63) == 0) {
-                const int64_t w0 = (c0 + tid) >> 5;
-                uint32_t *kb = keepbits + (int64_t)q * keep_words;
-                if (w0 < keep_words) kb[w0] = (uint32_t)b;
-                if (w0 + 1 < keep_words) kb[w0 + 1] = (uint32_t)(b >> 32);
-            }
-        }
         if (NP > 0) {
-            // Section 4.1: each token's NP best centroids of this tile.  Thread (i, p) ranks rows p, p + 8, ... of column i.
-            const int i = tid & 31, p = tid >> 5;
-            uint32_t bo[NPK], bi[NPK];
+            // Section 4.1: each token's NP best centroids of this tile.  Lane = 8 t + p: token 8 wave + t, rows p, p + 8, ...
+            // (ascending, so a strict comparison keeps the smaller id among equal scores); the eight lists of a token
+            // are then merged inside the wave.
+            const int i = 8 * wave + (lane >> 3), p = lane & 7;
+            float bs[NPK];
+            uint32_t bi[NPK];
 #pragma unroll
             for (int j = 0; j < NPK; ++j) {
-                bo[j] = 0xFFFFFFFFu;
+                bs[j] = -INFINITY;
                 bi[j] = 0xFFFFFFFFu;
             }
 #pragma unroll
             for (int k = 0; k < SM_ROWS / 8; ++k) {
                 const int rr = 8 * k + p;
-                if (rr < nrows) scq_insert_pair<NPK>(bo, bi, plaid_score_to_ord(tile[rr * SM_TSTRIDE + i]), (uint32_t)(c0 + rr));
+                const float sv = tile[rr * SM_TSTRIDE + i] + 0.0f;  // -0 -> +0, as in the ranking keys
+                if (rr < nrows && sv > bs[NPK - 1]) {
+#pragma unroll
+                    for (int j = NPK - 1; j >= 0; --j)
+                        if (sv > bs[j]) {
+                            if (j + 1 < NPK) {
+                                bs[j + 1] = bs[j];
+                                bi[j + 1] = bi[j];
+                            }
+                            bs[j] = sv;
+                            bi[j] = (uint32_t)(c0 + rr);
+                        }
+                }
             }
 #pragma unroll
-            for (int j = 0; j < NPK; ++j) lk[(p * QLEN + i) * NPK + j] = ((uint64_t)bo[j] << 32) | bi[j];
-            __syncthreads();
-            if (tid < QLEN) {
-                uint64_t best[NPK];
+            for (int d = 1; d < 8; d <<= 1) {
+                float os[NPK];
+                uint32_t oi[NPK];
 #pragma unroll
-                for (int j = 0; j < NPK; ++j) best[j] = lk[tid * NPK + j];
-                for (int pp = 1; pp < 8; ++pp)
+                for (int j = 0; j < NPK; ++j) {
+                    os[j] = __shfl_xor(bs[j], d);
+                    oi[j] = __shfl_xor(bi[j], d);
+                }
 #pragma unroll
-                    for (int j = 0; j < NPK; ++j) scq_insert_key<NPK>(best, lk[(pp * QLEN + tid) * NPK + j]);
-                uint64_t *po = partial + (((int64_t)q * QLEN + tid) * gridDim.y + blockIdx.y) * NPK;
+                for (int jo = 0; jo < NPK; ++jo) {
+                    const float sv = os[jo];
+                    const uint32_t id = oi[jo];
+                    // (score descending, id ascending); an entry equal to one already held is the same row
+                    if (sv > bs[NPK - 1] || (sv == bs[NPK - 1] && id < bi[NPK - 1])) {
 #pragma unroll
-                for (int j = 0; j < NPK; ++j) po[j] = best[j];
+                        for (int j = NPK - 1; j >= 0; --j)
+                            if (sv > bs[j] || (sv == bs[j] && id < bi[j])) {
+                                if (j + 1 < NPK) {
+                                    bs[j + 1] = bs[j];
+                                    bi[j + 1] = bi[j];
+                                }
+                                bs[j] = sv;
+                                bi[j] = id;
+                            }
+                    }
+                }
+            }
+            if (p == 0) {
+                uint64_t *po = partial + (((int64_t)q * QLEN + i) * gridDim.y + blockIdx.y) * NPK;
+#pragma unroll
+                for (int j = 0; j < NPK; ++j)
+                    po[j] = bi[j] == 0xFFFFFFFFu ? PLAID_KEY_MAX : plaid_make_key(bs[j], bi[j]);
             }
         }
-        __syncthreads();  // the tile is rewritten for the next query
+        scq_lds_barrier();  // the tile is rewritten for the next query
     }
 }
 

@@ -480,8 +480,9 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
     for (int qi = 0; qi < NQ; ++qi) {
         const int q = q0 + qi;
         if (q >= nq) break;  // uniform
-        // results to the tile; Eq. 5 on the way: a row's maximum over the 32 tokens is the maximum over this lane's two
-        // columns, then over the 16 lanes that share the row (two quad swaps, then the mirrors of 8 and of 16 lanes)
+        // results to the tile; Eq. 5 on the way: a row passes when any of its 32 scores reaches t_cs, so each lane marks
+        // the rows in which one of its two columns does (bit = row within the wave's 32 rows), and the marks are OR-ed over
+        // the 16 lanes that share rows (two quad swaps, then the mirrors of 8 and of 16 lanes) and over the four row groups
         uint32_t kbits = 0u;
 #pragma unroll
         for (int m = 0; m < SM_RT; ++m)
@@ -492,15 +493,16 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
                 float *trow = tile + (wave * 16 * SM_RT + row) * SM_TSTRIDE + li;
                 trow[0] = v0;
                 trow[16] = v1;
-                float mx = fmaxf(v0, v1);
-                mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0xB1, 0xF, 0xF, false)));
-                mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x4E, 0xF, 0xF, false)));
-                mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x141, 0xF, 0xF, false)));
-                mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(mx), 0x140, 0xF, 0xF, false)));
-                if (wave * 16 * SM_RT + row < nrows && mx >= t_cs) kbits |= 1u << row;
+                if (v0 >= t_cs || v1 >= t_cs) kbits |= 1u << row;
             }
+        kbits |= (uint32_t)__builtin_amdgcn_update_dpp((int)kbits, (int)kbits, 0xB1, 0xF, 0xF, false);
+        kbits |= (uint32_t)__builtin_amdgcn_update_dpp((int)kbits, (int)kbits, 0x4E, 0xF, 0xF, false);
+        kbits |= (uint32_t)__builtin_amdgcn_update_dpp((int)kbits, (int)kbits, 0x141, 0xF, 0xF, false);
+        kbits |= (uint32_t)__builtin_amdgcn_update_dpp((int)kbits, (int)kbits, 0x140, 0xF, 0xF, false);
         kbits |= __shfl_xor(kbits, 16);
         kbits |= __shfl_xor(kbits, 32);
+        // rows past the end of the centroid table (a ragged last block) never pass
+        if (nrows - wave * 16 * SM_RT < 32) kbits &= nrows - wave * 16 * SM_RT > 0 ? (1u << (nrows - wave * 16 * SM_RT)) - 1u : 0u;
         if (lane == 0) {
             const int64_t w0 = (c0 >> 5) + wave;
             if (w0 < keep_words) keepbits[(int64_t)q * keep_words + w0] = kbits;
@@ -526,11 +528,12 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
                 bs[j] = -INFINITY;
                 bi[j] = 0xFFFFFFFFu;
             }
+            // (comparisons treat -0 and +0 alike, as the ranking keys do)
 #pragma unroll
             for (int k = 0; k < SM_ROWS / 8; ++k) {
                 const int rr = 8 * k + p;
-                const float sv = tile[rr * SM_TSTRIDE + i] + 0.0f;  // -0 -> +0, as in the ranking keys
-                if (rr < nrows && sv > bs[NPK - 1]) {
+                const float sv = rr < nrows ? tile[rr * SM_TSTRIDE + i] : -INFINITY;
+                if (sv > bs[NPK - 1]) {
 #pragma unroll
                     for (int j = NPK - 1; j >= 0; --j)
                         if (sv > bs[j]) {

@@ -32,6 +32,7 @@ MEASURED_TRAFFIC_PER_LAUNCH = {
     # (config, noise, stage): bytes; profiles/bench_cfg3.txt
     ("cfg3", "literal", "scq"): int((131828.2 * 2.0 + 547842.9) * 1024),
     ("cfg3", "literal", "stage2_ci"): int((123879.7 * 2.0 + 124991.3) * 1024),
+    ("cfg3", "literal", "stage3_ci"): int((108549.3 * 2.0 + 524.3) * 1024),
     ("cfg3", "literal", "stage4_maxsim"): int((70114.2 * 2.0 + 139.2) * 1024),
 }
 
@@ -47,6 +48,8 @@ def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
     and written.  Inverted-list figure (what the inverted form of candidate generation + stage 2 must move instead): 4 bytes
     per entry of the inverted lists of the probed and the surviving centroids, 8 bytes per key written (queries with a
     surviving centroid) and the candidate and empty-bag words.
+    Stage 3 (Eq. 3-4): per passage kept by stage 2, 8 bytes of offsets and per token its 4-byte code and the 128-byte
+    S_cq row it selects.
     Stage 4 (Section 4.5, Eq. 1): per surviving passage 8 bytes of offsets and per token its 4-byte code, its packed
     residual (16 * nbits bytes) and the 128-byte S_cq row that carries the centroid's share of the dot products."""
     import torch
@@ -56,13 +59,14 @@ def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
     s4 = 0
     s4_tokens = 0
     n_skipped = 0
+    s3 = 0
     inv = 0
     ivf_len = (w_dev.ivf_offsets[1:] - w_dev.ivf_offsets[:-1])
     ncand = []
     step = 64   # the library's chunk size, so that these launches look like the timed ones to a profiler
     for q0 in range(0, Q.shape[0], step):
         _, _, b = pl.plaid_search_debug(idx, Q[q0:q0 + step], nprobe, t_cs, ndocs, k,
-                                        want=("S_cq", "probed", "cand", "n_cand", "sel3_ids", "n3"))
+                                        want=("S_cq", "probed", "cand", "n_cand", "sel2_ids", "n2", "sel3_ids", "n3"))
         torch.cuda.synchronize()
         keep = b["S_cq"].max(dim=2).values >= t_cs                              # [queries, C]: centroids passing Eq. 5
         survivors = keep.sum(dim=1).tolist()
@@ -81,11 +85,13 @@ def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
                 s2 += 8 * ((cfg.P + 31) // 32)
                 n_skipped += 1
             ncand.append(n)
+            n2 = int(b["n2"][j])
+            s3 += 8 * n2 + (4 + 128) * int(lens[b["sel2_ids"][j, :n2].long()].sum())
             n3 = int(b["n3"][j])
             t = int(lens[b["sel3_ids"][j, :n3].long()].sum())
             s4_tokens += t
             s4 += 8 * n3 + t * (4 + 16 * cfg.nbits + 128)
-    return {"stage2_bytes": s2, "stage2_inverted_bytes": inv, "stage4_bytes": s4, "stage4_tokens": s4_tokens,
+    return {"stage2_bytes": s2, "stage2_inverted_bytes": inv, "stage3_bytes": s3, "stage4_bytes": s4, "stage4_tokens": s4_tokens,
             "mean_candidates": float(sum(ncand)) / max(1, len(ncand)), "queries_without_survivors": n_skipped}
 
 
@@ -183,6 +189,10 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
              "code_stream_bytes_per_step": work["stage2_bytes"],
              "mean_candidates_per_query": work["mean_candidates"],
              "queries_without_surviving_centroid": work["queries_without_survivors"]})
+        rooflines["stage3_ci"] = entry(
+            "stage3_ci", "stage-3 centroid interaction without pruning (Eq. 3-4): codes and S_cq rows of the ndocs survivors",
+            "hbm", work["stage3_bytes"], 1e9, HBM_PEAK_GBS, "GB/s",
+            {"algorithmic_bytes_per_step": work["stage3_bytes"], "algorithmic_bytes_per_launch": work["stage3_bytes"] // launches})
         rooflines["stage4_maxsim"] = entry(
             "stage4_maxsim", "stage-4 decompression + MaxSim (Section 4.5, Eq. 1) over the ndocs/4 survivors", "hbm",
             work["stage4_bytes"], 1e9, HBM_PEAK_GBS, "GB/s",

@@ -478,7 +478,9 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
 // list enters a range comes from a table built once per index: table[c][r] = position in list c of its first entry
 // with passage id >= r * IVR_RANGE.
 #define IVR_EMPTY 0xFFFFFFFFu
-#define IVR_LISTS 256  // lists handled per LDS round
+#define IVR_LISTS 256  // lists handled per LDS round (= threads of the workgroup)
+#define IVR_SHORT 64   // a list with at most this many entries in the range joins the pooled pass
+static_assert(IVR_LISTS == S2_THREADS, "one list per thread and round");
 
 // table[c][r] for every non-empty (list, range) pair; the others keep IVR_EMPTY until ivr_fill_kernel.
 __global__ __launch_bounds__(256) void ivr_mark_kernel(const int64_t *__restrict__ ivf_offsets,
@@ -524,40 +526,6 @@ void plaid_launch_ivf_range_table(hipStream_t st, const int64_t *ivf_offsets, co
     hipLaunchKernelGGL(ivr_fill_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, ivf_offsets, C, nr, table);
 }
 
-// ORs lst_val[l] into the set words of the passages that list l holds inside the range, for the nl lists described by
-// lst_start (position of the first entry in range), lst_cnt (> 0: entries in range) and lst_val.  A wave takes one list
-// at a time from the shared counter *next (zero on entry) and walks it 256 entries per step, four loads in flight;
-// all threads of the workgroup call this.
-__device__ __forceinline__ void ivr_apply_lists(const int32_t *__restrict__ ivf_pids, const int64_t *lst_start,
-                                                const int32_t *lst_cnt, const unsigned long long *lst_val, int nl,
-                                                uint32_t r0, unsigned long long *lsets, int32_t *next)
-{
-    const int lane = threadIdx.x & 63;
-    for (;;) {
-        int l = 0;
-        if (lane == 0) l = atomicAdd(next, 1);
-        l = s2_uniform(__shfl(l, 0));
-        if (l >= nl) break;
-        const int cnt = s2_uniform(lst_cnt[l]);
-        const int32_t *__restrict__ src = ivf_pids + lst_start[l];
-        const unsigned long long val = lst_val[l];
-        for (int e0 = 0; e0 < cnt; e0 += 256) {
-            uint32_t pid[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int e = e0 + 64 * u + lane;
-                pid[u] = e < cnt ? (uint32_t)src[e] : 0xFFFFFFFFu;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint32_t loc = pid[u] - r0;
-                // (a passage id outside the range, other than the padding value, means a list that is not ascending)
-                if (pid[u] != 0xFFFFFFFFu && loc < (uint32_t)IVR_RANGE) atomicOr(&lsets[loc], val);
-            }
-        }
-    }
-}
-
 // Exclusive prefix sum of one value per thread over the workgroup, into out[0 .. S2_THREADS]; scratch: one int per wave.
 __device__ __forceinline__ void ivr_block_scan(int v, int32_t *out, int32_t *wave_tot)
 {
@@ -577,6 +545,78 @@ __device__ __forceinline__ void ivr_block_scan(int v, int32_t *out, int32_t *wav
     __syncthreads();
 }
 
+// LDS work arrays of ivr_apply_round.
+struct IvrLists {
+    int64_t long_start[IVR_LISTS];              // compacted lists with more than IVR_SHORT entries in the range
+    int32_t long_cnt[IVR_LISTS];
+    unsigned long long long_val[IVR_LISTS];
+    int64_t short_start[S2_THREADS];            // per thread: its list when it has 1 .. IVR_SHORT entries in the range
+    unsigned long long short_val[S2_THREADS];
+    int32_t pref[S2_THREADS + 1];               // packed prefix sums: long-list count << 20 | short entries
+    int32_t wave_tot[S2_THREADS / 64];
+    int32_t next;
+};
+
+// One round of list application: thread t brings one list (cnt entries of ivf_pids from `first` on fall into the range,
+// cnt = 0: none) and the bits `val` to OR into the set words of those passages.  Lists with few entries are pooled into
+// one flat index range that all threads share (a lane finds its entry by binary search in the prefix sums), so that
+// fifty lists of two entries cost one memory round trip instead of fifty; a long list is walked by one wave, 512
+// entries per step with eight loads in flight, waves taking lists from a shared counter.  All threads call this.
+__device__ __forceinline__ void ivr_apply_round(int cnt, int64_t first, unsigned long long val,
+                                                const int32_t *__restrict__ ivf_pids, uint32_t r0, unsigned long long *lsets,
+                                                IvrLists &L)
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    const bool is_long = cnt > IVR_SHORT;
+    const int packed = is_long ? (1 << 20) : cnt;
+    if (tid == 0) L.next = 0;
+    ivr_block_scan(packed, L.pref, L.wave_tot);
+    if (is_long) {
+        const int at = L.pref[tid] >> 20;
+        L.long_start[at] = first;
+        L.long_cnt[at] = cnt;
+        L.long_val[at] = val;
+    } else if (cnt > 0) {
+        L.short_start[tid] = first;
+        L.short_val[tid] = val;
+    }
+    __syncthreads();
+    const int n_long = L.pref[S2_THREADS] >> 20, n_short = L.pref[S2_THREADS] & 0xFFFFF;
+    for (int w = tid; w < n_short; w += S2_THREADS) {
+        int lo = 0, hi = S2_THREADS;  // largest lo whose short-entry prefix is <= w: the list that holds entry w
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if ((L.pref[mid] & 0xFFFFF) <= w) lo = mid;
+            else hi = mid;
+        }
+        const uint32_t loc = (uint32_t)ivf_pids[L.short_start[lo] + (w - (L.pref[lo] & 0xFFFFF))] - r0;
+        if (loc < (uint32_t)IVR_RANGE) atomicOr(&lsets[loc], L.short_val[lo]);  // (false only if a list is not ascending)
+    }
+    for (;;) {
+        int l = 0;
+        if (lane == 0) l = atomicAdd(&L.next, 1);
+        l = s2_uniform(__shfl(l, 0));
+        if (l >= n_long) break;
+        const int n = s2_uniform(L.long_cnt[l]);
+        const int32_t *__restrict__ src = ivf_pids + L.long_start[l];
+        const unsigned long long v = L.long_val[l];
+        for (int e0 = 0; e0 < n; e0 += 512) {
+            uint32_t pid[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + 64 * u + lane;
+                pid[u] = e < n ? (uint32_t)src[e] : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const uint32_t loc = pid[u] - r0;
+                if (pid[u] != 0xFFFFFFFFu && loc < (uint32_t)IVR_RANGE) atomicOr(&lsets[loc], v);
+            }
+        }
+    }
+    __syncthreads();
+}
+
 __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
     const int32_t *__restrict__ uniq, const int32_t *__restrict__ n_uniq, int uniq_stride,
     const int64_t *__restrict__ ivf_offsets, const int32_t *__restrict__ ivf_pids, const uint32_t *__restrict__ table,
@@ -591,12 +631,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
     __shared__ __align__(16) float Tl[(S2_MAX_KEPT + 1) * S2_TSTRIDE];
     __shared__ float rowsum[S2_MAX_KEPT + 1];
     __shared__ int32_t lhist[SEL_BINS];
-    __shared__ int64_t lst_start[IVR_LISTS];
-    __shared__ int32_t lst_cnt[IVR_LISTS];
-    __shared__ int32_t lst_pref[IVR_LISTS + 1];
-    __shared__ unsigned long long lst_val[IVR_LISTS];
-    __shared__ int32_t wave_tot[S2_THREADS / 64];
-    __shared__ int32_t next_list;
+    __shared__ IvrLists lists;
     __shared__ uint32_t slot_probed[2];  // bit s: surviving slot s is also a probed centroid
     const int q = blockIdx.y;
     const int64_t r = blockIdx.x;
@@ -628,18 +663,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
             val = 1ull | (sl ? 1ull << sl : 0ull);
             if (sl) atomicOr(&slot_probed[sl >> 5], 1u << (sl & 31));
         }
-        // the lists with entries in this range, compacted
-        if (tid == 0) next_list = 0;
-        ivr_block_scan(cnt > 0 ? 1 : 0, lst_pref, wave_tot);
-        if (cnt > 0) {
-            const int at = lst_pref[tid];
-            lst_start[at] = first;
-            lst_cnt[at] = cnt;
-            lst_val[at] = val;
-        }
-        __syncthreads();
-        ivr_apply_lists(ivf_pids, lst_start, lst_cnt, lst_val, lst_pref[S2_THREADS], r0, lsets, &next_list);
-        __syncthreads();
+        ivr_apply_round(cnt, first, val, ivf_pids, r0, lsets, lists);
     }
     // surviving centroids that were not probed: slot bit only
     if (slots) {
@@ -655,17 +679,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
                 cnt = b > a ? (int)(b - a) : 0;
             }
         }
-        if (tid == 0) next_list = 0;
-        ivr_block_scan(cnt > 0 ? 1 : 0, lst_pref, wave_tot);
-        if (cnt > 0) {
-            const int at = lst_pref[tid];
-            lst_start[at] = first;
-            lst_cnt[at] = cnt;
-            lst_val[at] = 1ull << (tid + 1);
-        }
-        __syncthreads();
-        ivr_apply_lists(ivf_pids, lst_start, lst_cnt, lst_val, lst_pref[S2_THREADS], r0, lsets, &next_list);
-        __syncthreads();
+        ivr_apply_round(cnt, first, 1ull << (tid + 1), ivf_pids, r0, lsets, lists);
     }
 
     // emit the range: lane = passage, 64 passages per step

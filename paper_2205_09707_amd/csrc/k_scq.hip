@@ -337,9 +337,21 @@ __global__ __launch_bounds__(SCQ_THREADS) void scq_fused_kernel(const float *__r
 
 // ------------------------------------------------------------------ matrix form
 typedef double scq_double4 __attribute__((ext_vector_type(4)));
+// Four waves of 32 rows measured best: eight waves of 16 rows (more waves per SIMD to fill the matrix pipe while
+// others are in their epilogue) lose more to the per-wave epilogue instructions than they gain (5.2 vs 4.95 ms per 512
+// queries on C = 65536), 64 rows per wave halve the occupancy.
+#ifndef SM_THREADS
 #define SM_THREADS 256
+#endif
+#ifndef SM_RT
 #define SM_RT 2                      // 16-row tiles per wave
-#define SM_ROWS (4 * 16 * SM_RT)     // centroid rows per workgroup
+#endif
+#define SM_WAVES (SM_THREADS / 64)
+#define SM_WROWS (16 * SM_RT)        // centroid rows per wave
+#define SM_ROWS (SM_WAVES * SM_WROWS)  // centroid rows per workgroup
+#define SM_PARTS (SM_THREADS / QLEN) // threads that share a query token in the per-tile ranking
+static_assert(SM_WROWS == 16 || SM_WROWS == 32, "pruning bits are assembled from 16- or 32-row pieces");
+static_assert(SM_PARTS <= 64 && SM_ROWS % SM_PARTS == 0 && SM_ROWS % (SM_THREADS / 8) == 0, "tile shape");
 #define SM_KC 32                     // dimensions staged at a time
 #define SM_ASTRIDE 36                // floats per staged row chunk: the 64 operand reads of a step hit 64 banks
 #define SM_TSTRIDE 33                // floats per row of the result tile
@@ -408,27 +420,33 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
     const int64_t c0 = (int64_t)blockIdx.y * SM_ROWS;
     const int nrows = (int)(C - c0 < SM_ROWS ? C - c0 : SM_ROWS);
 
-    // staging: a chunk is SM_ROWS rows x 32 dims = 8 float4 per row; thread -> rows tid/8 + 32k, float4 column tid%8
+    // staging: a chunk is SM_ROWS rows x 32 dims = 8 float4 per row; thread -> rows tid/8 + SM_RPP k, float4 column tid%8
+    constexpr int SM_RPP = SM_THREADS / 8;  // rows per staging pass
     const int r0 = tid >> 3, c4 = tid & 7;
-    float4 pre[SM_ROWS / 32];
+    float4 pre[SM_ROWS / SM_RPP];
 #pragma unroll
-    for (int k = 0; k < SM_ROWS / 32; ++k) {
-        const int r = r0 + 32 * k;
+    for (int k = 0; k < SM_ROWS / SM_RPP; ++k) {
+        const int r = r0 + SM_RPP * k;
         pre[k] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (r < nrows) pre[k] = *reinterpret_cast<const float4 *>(Cm + (c0 + r) * DIM + 4 * c4);
     }
     // The queries' operands of a chunk, in operand order [step][column tile][lane]: 8 steps x 2 halves x 64 lanes per
-    // query, four consecutive lanes per thread (zeros for a query past the end).  Lane 16 g + i of step s, half h holds
-    // Q[16 h + i][4 s + g], so a thread's four values are one column of four consecutive query tokens.
-    const int bdst = (((tid >> 5) * NT + ((tid >> 4) & 1)) * 64 + 4 * (tid & 15));  // + 2 qi column tiles
-    const int bsrc = (16 * ((tid >> 4) & 1) + 4 * (tid & 3)) * DIM + 4 * (tid >> 5) + ((tid >> 2) & 3);  // + 32 ch
-    float4 preb[NQ];
+    // query, four consecutive lanes per thread: 256 threads per query, thread bt of them (zeros for a query past the
+    // end).  Lane 16 g + i of step s, half h holds Q[16 h + i][4 s + g], so a thread's four values are one column of
+    // four consecutive query tokens.
+    static_assert(SM_THREADS % 256 == 0, "query staging works in groups of 256 threads");
+    constexpr int BQ_PASSES = (NQ * 256 + SM_THREADS - 1) / SM_THREADS;  // queries staged per thread
+    const int bt = tid & 255;
+    const int bdst = (((bt >> 5) * NT + ((bt >> 4) & 1)) * 64 + 4 * (bt & 15));  // + 2 qi column tiles
+    const int bsrc = (16 * ((bt >> 4) & 1) + 4 * (bt & 3)) * DIM + 4 * (bt >> 5) + ((bt >> 2) & 3);  // + 32 ch
+    float4 preb[BQ_PASSES];
 #pragma unroll
-    for (int qi = 0; qi < NQ; ++qi) {
-        preb[qi] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (q0 + qi < nq) {
+    for (int k = 0; k < BQ_PASSES; ++k) {
+        const int qi = (tid >> 8) + (SM_THREADS / 256) * k;
+        preb[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (qi < NQ && q0 + qi < nq) {
             const float *src = Q + (int64_t)(q0 + qi) * QLEN * DIM + bsrc;
-            preb[qi] = make_float4(src[0], src[DIM], src[2 * DIM], src[3 * DIM]);
+            preb[k] = make_float4(src[0], src[DIM], src[2 * DIM], src[3 * DIM]);
         }
     }
     scq_double4 acc[SM_RT][NT];
@@ -436,28 +454,33 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
     for (int m = 0; m < SM_RT; ++m)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[m][t] = scq_double4{0.0, 0.0, 0.0, 0.0};
-    const float *arow = arena + (wave * 16 * SM_RT + li) * SM_ASTRIDE + lg;  // + 16 m rows, + 4 j floats
+    const float *arow = arena + (wave * SM_WROWS + li) * SM_ASTRIDE + lg;  // + 16 m rows, + 4 j floats
     const float *bcol = Bq + lane;
 #pragma unroll 1
     for (int ch = 0; ch < DIM / SM_KC; ++ch) {
 #pragma unroll
-        for (int k = 0; k < SM_ROWS / 32; ++k)
-            *reinterpret_cast<float4 *>(arena + (r0 + 32 * k) * SM_ASTRIDE + 4 * c4) = pre[k];
+        for (int k = 0; k < SM_ROWS / SM_RPP; ++k)
+            *reinterpret_cast<float4 *>(arena + (r0 + SM_RPP * k) * SM_ASTRIDE + 4 * c4) = pre[k];
 #pragma unroll
-        for (int qi = 0; qi < NQ; ++qi) *reinterpret_cast<float4 *>(Bq + bdst + 2 * qi * 64) = preb[qi];
+        for (int k = 0; k < BQ_PASSES; ++k) {
+            const int qi = (tid >> 8) + (SM_THREADS / 256) * k;
+            if (qi < NQ) *reinterpret_cast<float4 *>(Bq + bdst + 2 * qi * 64) = preb[k];
+        }
         scq_lds_barrier();
         if (ch + 1 < DIM / SM_KC) {
 #pragma unroll
-            for (int k = 0; k < SM_ROWS / 32; ++k) {
-                const int r = r0 + 32 * k;
+            for (int k = 0; k < SM_ROWS / SM_RPP; ++k) {
+                const int r = r0 + SM_RPP * k;
                 if (r < nrows) pre[k] = *reinterpret_cast<const float4 *>(Cm + (c0 + r) * DIM + SM_KC * (ch + 1) + 4 * c4);
             }
 #pragma unroll
-            for (int qi = 0; qi < NQ; ++qi)
-                if (q0 + qi < nq) {
+            for (int k = 0; k < BQ_PASSES; ++k) {
+                const int qi = (tid >> 8) + (SM_THREADS / 256) * k;
+                if (qi < NQ && q0 + qi < nq) {
                     const float *src = Q + (int64_t)(q0 + qi) * QLEN * DIM + bsrc + SM_KC * (ch + 1);
-                    preb[qi] = make_float4(src[0], src[DIM], src[2 * DIM], src[3 * DIM]);
+                    preb[k] = make_float4(src[0], src[DIM], src[2 * DIM], src[3 * DIM]);
                 }
+            }
         }
 #pragma unroll
         for (int j = 0; j < SM_KC / 4; ++j) {
@@ -475,7 +498,7 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
     }
 
     // epilogue, one query at a time through the LDS tile
-    static_assert(SM_RT == 2, "a wave's 32 rows are one word of the pruning bitmap");
+    __shared__ uint32_t kpiece[SM_WAVES];  // pruning bits of each wave's rows
 #pragma unroll
     for (int qi = 0; qi < NQ; ++qi) {
         const int q = q0 + qi;
@@ -488,9 +511,9 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
         for (int m = 0; m < SM_RT; ++m)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int row = 16 * m + 4 * r + lg;  // within the wave's 32 rows
+                const int row = 16 * m + 4 * r + lg;  // within the wave's rows
                 const float v0 = (float)acc[m][2 * qi][r], v1 = (float)acc[m][2 * qi + 1][r];
-                float *trow = tile + (wave * 16 * SM_RT + row) * SM_TSTRIDE + li;
+                float *trow = tile + (wave * SM_WROWS + row) * SM_TSTRIDE + li;
                 trow[0] = v0;
                 trow[16] = v1;
                 if (v0 >= t_cs || v1 >= t_cs) kbits |= 1u << row;
@@ -502,12 +525,15 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
         kbits |= __shfl_xor(kbits, 16);
         kbits |= __shfl_xor(kbits, 32);
         // rows past the end of the centroid table (a ragged last block) never pass
-        if (nrows - wave * 16 * SM_RT < 32) kbits &= nrows - wave * 16 * SM_RT > 0 ? (1u << (nrows - wave * 16 * SM_RT)) - 1u : 0u;
-        if (lane == 0) {
-            const int64_t w0 = (c0 >> 5) + wave;
-            if (w0 < keep_words) keepbits[(int64_t)q * keep_words + w0] = kbits;
-        }
+        if (nrows - wave * SM_WROWS < SM_WROWS)
+            kbits &= nrows - wave * SM_WROWS > 0 ? (1u << (nrows - wave * SM_WROWS)) - 1u : 0u;
+        if (lane == 0) kpiece[wave] = kbits;
         scq_lds_barrier();
+        if (tid < SM_ROWS / 32) {  // one 32-bit word of the pruning bitmap per 32 rows
+            const int64_t w0 = (c0 >> 5) + tid;
+            const uint32_t word = SM_WROWS == 32 ? kpiece[tid] : (kpiece[2 * tid] | (kpiece[2 * tid + 1] << 16));
+            if (w0 < keep_words) keepbits[(int64_t)q * keep_words + w0] = word;
+        }
         // scores, coalesced: the tile's rows are contiguous in S
         for (int e = tid; e < SM_ROWS * (QLEN / 4); e += SM_THREADS) {
             const int r = e >> 3, k4 = e & 7;
@@ -517,10 +543,10 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
             }
         }
         if (NP > 0) {
-            // Section 4.1: each token's NP best centroids of this tile.  Lane = 8 t + p: token 8 wave + t, rows p, p + 8, ...
-            // (ascending, so a strict comparison keeps the smaller id among equal scores); the eight lists of a token
-            // are then merged inside the wave.
-            const int i = 8 * wave + (lane >> 3), p = lane & 7;
+            // Section 4.1: each token's NP best centroids of this tile.  SM_PARTS consecutive lanes share a token; lane p of
+            // them takes rows p, p + SM_PARTS, ... (ascending, so a strict comparison keeps the smaller id among equal
+            // scores); the lists of a token are then merged inside the wave.
+            const int i = tid / SM_PARTS, p = tid % SM_PARTS;
             float bs[NPK];
             uint32_t bi[NPK];
 #pragma unroll
@@ -530,8 +556,8 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
             }
             // (comparisons treat -0 and +0 alike, as the ranking keys do)
 #pragma unroll
-            for (int k = 0; k < SM_ROWS / 8; ++k) {
-                const int rr = 8 * k + p;
+            for (int k = 0; k < SM_ROWS / SM_PARTS; ++k) {
+                const int rr = SM_PARTS * k + p;
                 const float sv = rr < nrows ? tile[rr * SM_TSTRIDE + i] : -INFINITY;
                 if (sv > bs[NPK - 1]) {
 #pragma unroll
@@ -547,7 +573,7 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
                 }
             }
 #pragma unroll
-            for (int d = 1; d < 8; d <<= 1) {
+            for (int d = 1; d < SM_PARTS; d <<= 1) {
                 float os[NPK];
                 uint32_t oi[NPK];
 #pragma unroll

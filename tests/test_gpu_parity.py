@@ -89,8 +89,8 @@ def test_cfg1_other_operating_points(pl, form, stage2):
     both forms then score candidates from their token codes)."""
     cfg = get_config("cfg1")
     w = make_workload(cfg, device="cpu", noise="calibrated")
-    _check_workload(pl, w, [(2, 0.45, 1024, 100), (4, 0.4, 4096, 1000), (3, 0.2, 300, 40), (1, -np.inf, 64, 16)], form=form,
-                    stage2=stage2)
+    _check_workload(pl, w, [(2, 0.45, 1024, 100), (4, 0.4, 4096, 1000), (3, 0.2, 300, 40), (1, -np.inf, 64, 16),
+                            (6, 0.5, 200, 20), (8, 0.45, 512, 50), (12, 0.5, 128, 10)], form=form, stage2=stage2)
 
 
 def test_default_score_kernel_is_the_matrix_form(pl):

@@ -16,6 +16,9 @@
 #include <math.h>
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+#ifndef S4_RESIDENT_BLOCKS
+#define S4_RESIDENT_BLOCKS 768
+#endif
 
 // Table entry (byte v, quad s): weights of dimensions 4s .. 4s+3 of the 8/NBITS dimensions packed in v.
 // Bucket indices are stored most-significant first.
@@ -50,7 +53,7 @@ __device__ __forceinline__ int table_slot(const uint8_t *__restrict__ r, int qua
 // passages per wave: throughput).  COOP = true: the four waves of a workgroup share a passage, each taking every
 // fourth step, and combine their maxima in LDS (short lists: latency).
 template <int NBITS, bool COOP>
-__global__ __launch_bounds__(256, 4) void decompress_maxsim_kernel(
+__global__ __launch_bounds__(256, 3) void decompress_maxsim_kernel(
     const float *__restrict__ Q, const float *__restrict__ S, int64_t C, const int64_t *__restrict__ doc_offsets,
     const int32_t *__restrict__ codes, const uint8_t *__restrict__ residuals, const float *__restrict__ weights,
     const uint64_t *__restrict__ in_keys, int64_t in_stride, const int32_t *__restrict__ in_counts,
@@ -82,21 +85,39 @@ __global__ __launch_bounds__(256, 4) void decompress_maxsim_kernel(
                            (uint32_t)__builtin_amdgcn_readfirstlane((int)(t0v & 0xFFFFFFFFll));
         const int len = __builtin_amdgcn_readfirstlane((int)(doc_offsets[pid + 1] - t0v));
         float m = -INFINITY;  // running maximum for query token r32 over the rows this lane sees
-        for (int base = COOP ? 32 * wave : 0; base < len; base += COOP ? 128 : 32) {
-            const int row = base + r32;  // this lane's passage token
+        // The loop is software-pipelined: the code and packed residual of the next step and the S_cq values of this
+        // step are requested before this step's 64 matrix instructions are issued, so their latency runs under them.
+        constexpr int STEP = COOP ? 128 : 32;
+        int base = COOP ? 32 * wave : 0;
+        int32_t code = 0;
+        uint32_t rw[RB / 4] = {0};
+        auto request = [&](int b, int32_t &c, uint32_t (&r)[RB / 4]) {
+            const int row = b + r32;  // this lane's passage token
             const int64_t tok = t0 + (row < len ? row : len - 1);
-            const int32_t code = codes[tok];
+            c = codes[tok];
             // the token's packed residual: both halves of the wave read all of it, each uses every other byte
             const uint4 *rp = reinterpret_cast<const uint4 *>(residuals + tok * RB);
-            uint32_t rw[RB / 4];
-            {
-                const uint4 v0 = rp[0];
-                rw[0] = v0.x, rw[1] = v0.y, rw[2] = v0.z, rw[3] = v0.w;
-                if (NBITS == 2) {
-                    const uint4 v1 = rp[1];
-                    rw[4] = v1.x, rw[5] = v1.y, rw[6] = v1.z, rw[7] = v1.w;
-                }
+            const uint4 v0 = rp[0];
+            r[0] = v0.x, r[1] = v0.y, r[2] = v0.z, r[3] = v0.w;
+            if (NBITS == 2) {
+                const uint4 v1 = rp[1];
+                r[4] = v1.x, r[5] = v1.y, r[6] = v1.z, r[7] = v1.w;
             }
+        };
+        if (base < len) request(base, code, rw);
+        for (; base < len; base += STEP) {
+            // the centroid's share of each dot product: row code of S_cq, element r32 (requested now, used after the
+            // matrix instructions); acc[v] will hold passage token base + 8 (v/4) + 4h + v%4 against query token r32
+            float sv[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rr = 8 * (v >> 2) + 4 * h + (v & 3);
+                const uint32_t cv = (uint32_t)__shfl(code, rr);
+                sv[v] = Sq[cv * (uint32_t)QLEN + (uint32_t)r32];
+            }
+            int32_t code_next = 0;
+            uint32_t rw_next[RB / 4] = {0};
+            if (base + STEP < len) request(base + STEP, code_next, rw_next);  // uniform
             floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
             for (int g = 0; g < 16; ++g) {
@@ -112,15 +133,17 @@ __global__ __launch_bounds__(256, 4) void decompress_maxsim_kernel(
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.z, qf[g].z, acc, 0, 0, 0);
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.w, qf[g].w, acc, 0, 0, 0);
             }
-            // acc[v] = (residual of passage token base + 8 (v/4) + 4h + v%4) . (query token r32); the centroid's share
-            // of the dot product is S_cq[code][r32]
+            if (base + 32 <= len) {  // (uniform) a full step: every row counts
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int rr = 8 * (v >> 2) + 4 * h + (v & 3);
-                const int32_t cv = __shfl(code, rr);
-                const float sv = Sq[(int64_t)cv * QLEN + r32];
-                if (base + rr < len) m = fmaxf(m, acc[v] + sv);
+                for (int v = 0; v < 16; ++v) m = fmaxf(m, acc[v] + sv[v]);
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (base + 8 * (v >> 2) + 4 * h + (v & 3) < len) m = fmaxf(m, acc[v] + sv[v]);
             }
+            code = code_next;
+#pragma unroll
+            for (int e = 0; e < RB / 4; ++e) rw[e] = rw_next[e];
         }
         m = fmaxf(m, __shfl_xor(m, 32));
         if (COOP) {  // j, len are the same in the four waves
@@ -147,7 +170,8 @@ void plaid_launch_decompress_maxsim(hipStream_t st, const float *Q, const float 
     // several passages each, so that the per-workgroup set-up (table, query operands) is paid rarely
     const bool coop = (int64_t)n_upper * nq <= 2048;
     int gx = coop ? n_upper : (n_upper + 3) / 4;
-    const int cap = coop ? 2048 : (nq >= 16 ? 16 : (nq >= 4 ? 64 : 512));
+    // (256 compute units x 3 resident workgroups: one full round of waves, each striding over several passages)
+    const int cap = coop ? 2048 : (S4_RESIDENT_BLOCKS + nq - 1) / nq;
     if (gx > cap) gx = cap;
 #define PLAID_S4_LAUNCH(NB, CO)                                                                                           \
     hipLaunchKernelGGL((decompress_maxsim_kernel<NB, CO>), dim3(gx, nq), dim3(256), 0, st, Q, S, C, doc_offsets, codes,       \

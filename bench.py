@@ -112,7 +112,7 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
     out_ids = torch.empty((nq, cfg.k), dtype=torch.int32, device=dev)
     out_sc = torch.empty((nq, cfg.k), dtype=torch.float32, device=dev)
     # ---- throughput: K steps of the full batch, stage events on (they cost one sync per query chunk)
-    CHUNK = 64   # queries per internal launch
+    CHUNK = 512  # queries per internal launch (the library default)
     pl.plaid_set_max_chunk(idx, CHUNK)
     launches = (nq + CHUNK - 1) // CHUNK
     pl.plaid_set_stage_timing(idx, True)

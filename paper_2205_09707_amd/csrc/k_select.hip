@@ -347,20 +347,107 @@ __global__ void sel_copy_back_kernel(const uint64_t *__restrict__ src, int64_t n
         dst[(int64_t)seg * dst_stride + i] = src[(int64_t)seg * n2 + i];
 }
 
-// ------------------------------------------------------------------ short lists: selection by rank counting
-// Lists of up to SEL_SORT_CAP keys: the rank of a key is the number of smaller keys (keys are unique), so key j
-// goes to out[rank] when rank < m -- the output is in rank order without a sort.  A workgroup holds the whole list
-// in LDS and ranks 32 of its keys, eight lanes sharing the comparisons of one key.
+// ------------------------------------------------------------------ short lists: one workgroup sorts the list in LDS
+// Lists of up to SEL_SORT_CAP keys: a workgroup loads the list into LDS padded with PLAID_KEY_MAX to the next power of
+// two of its actual length, runs a bitonic network over it (one compare-exchange per thread and pass: thread t owns
+// the pair (lo, lo | j) with lo = t with a zero inserted at bit log2(j)), and the first min(m, n) keys are the result
+// in rank order.  n log^2 n compare-exchanges instead of the n^2 comparisons of rank counting, and only as much LDS as
+// the longest list of the launch needs (the launcher passes it as dynamic shared memory).
+// The 64 pairs a wave owns in one pass lie inside one aligned block of 128 keys whenever j <= 64, and a wave owns the
+// same blocks in every pass, so those passes (most of the network) need no workgroup barrier: a wave's LDS
+// operations complete in program order.  Only the passes with j >= 128 exchange keys between waves.
+template <int THREADS>
+__device__ __forceinline__ int lds_sort_list(uint64_t *sk, const uint64_t *__restrict__ k, int n)
+{
+    int n2 = 2;
+    while (n2 < n) n2 <<= 1;
+    for (int i = threadIdx.x; i < n2; i += THREADS) sk[i] = i < n ? k[i] : PLAID_KEY_MAX;
+    __syncthreads();
+    const int half = n2 >> 1;
+    for (int kk = 2; kk <= n2; kk <<= 1)
+        for (int j = kk >> 1; j > 0; j >>= 1) {
+            const bool wide = j >= 128;  // uniform over the workgroup
+            if (wide)
+                __syncthreads();
+            else
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            for (int t = threadIdx.x; t < half; t += THREADS) {
+                const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
+                const uint64_t a = sk[lo], b = sk[hi];
+                const bool up = (lo & kk) == 0;
+                if ((a > b) == up) {
+                    sk[lo] = b;
+                    sk[hi] = a;
+                }
+            }
+            if (wide) __syncthreads();
+        }
+    __syncthreads();
+    return n2;
+}
+
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void sel_sort_kernel(const uint64_t *__restrict__ keys, int64_t key_stride,
+                                                           const int32_t *__restrict__ counts, int32_t n_cap, int32_t m,
+                                                           uint64_t *__restrict__ out, int64_t out_stride,
+                                                           int32_t *__restrict__ out_counts)
+{
+    extern __shared__ uint64_t sel_sort_lds[];
+    const int seg = blockIdx.x;
+    int n = counts[seg];
+    if (n > n_cap) n = n_cap;
+    const int n_out = m < n ? m : n;
+    if (threadIdx.x == 0) out_counts[seg] = n_out;
+    if (n_out == 0) return;
+    lds_sort_list<THREADS>(sel_sort_lds, keys + (int64_t)seg * key_stride, n);
+    uint64_t *o = out + (int64_t)seg * out_stride;
+    for (int i = threadIdx.x; i < n_out; i += THREADS) o[i] = sel_sort_lds[i];
+}
+
+// The same for the final ranking: ids and scores go straight to the caller's buffers, best first, and the
+// slots beyond min(k, count) are filled with (-1, -infinity).
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void sel_sort_output_kernel(const uint64_t *__restrict__ keys, int64_t key_stride,
+                                                                  const int32_t *__restrict__ counts, int32_t n_cap,
+                                                                  int32_t k, int32_t *__restrict__ out_ids,
+                                                                  float *__restrict__ out_scores)
+{
+    extern __shared__ uint64_t sel_sort_lds[];
+    const int seg = blockIdx.x;
+    int n = counts[seg];
+    if (n > n_cap) n = n_cap;
+    const int n_out = k < n ? k : n;
+    int32_t *oi = out_ids + (int64_t)seg * k;
+    float *os = out_scores + (int64_t)seg * k;
+    for (int j = n_out + threadIdx.x; j < k; j += THREADS) {
+        oi[j] = -1;
+        os[j] = -INFINITY;
+    }
+    if (n_out == 0) return;
+    lds_sort_list<THREADS>(sel_sort_lds, keys + (int64_t)seg * key_stride, n);
+    for (int i = threadIdx.x; i < n_out; i += THREADS) {
+        const uint64_t key = sel_sort_lds[i];
+        oi[i] = (int32_t)(key & 0xFFFFFFFFu);
+        os[i] = plaid_ord_to_score((uint32_t)(key >> 32));
+    }
+}
+
+// ------------------------------------------------------------------ short lists, few of them: selection by rank counting
+// With only a few lists in the launch (single-query latency) one workgroup per list leaves the chip idle and the
+// network's passes are a chain of LDS round trips.  Then the n^2 form is quicker: the rank of a key is the number of
+// smaller keys (keys are unique), so key j goes to out[rank] when rank < m.  Every workgroup holds the whole list in
+// LDS and ranks 32 of its keys, eight lanes sharing the comparisons of one key.
+#define RANK_MAX_LISTS 16
 #define RANK_KEYS_PER_BLOCK 32
 __global__ __launch_bounds__(256) void sel_rank_kernel(const uint64_t *__restrict__ keys, int64_t key_stride,
-                                                       const int32_t *__restrict__ counts, int32_t m,
+                                                       const int32_t *__restrict__ counts, int32_t n_cap, int32_t m,
                                                        uint64_t *__restrict__ out, int64_t out_stride,
                                                        int32_t *__restrict__ out_counts)
 {
-    __shared__ uint64_t sk[SEL_SORT_CAP];
+    extern __shared__ uint64_t sk[];
     const int seg = blockIdx.y;
     int n = counts[seg];
-    if (n > SEL_SORT_CAP) n = SEL_SORT_CAP;
+    if (n > n_cap) n = n_cap;
     if (blockIdx.x == 0 && threadIdx.x == 0) out_counts[seg] = m < n ? m : n;
     const int j0 = blockIdx.x * RANK_KEYS_PER_BLOCK;
     if (j0 >= n) return;
@@ -377,16 +464,15 @@ __global__ __launch_bounds__(256) void sel_rank_kernel(const uint64_t *__restric
     if (part == 0 && j < n && rank < m) out[(int64_t)seg * out_stride + rank] = key;
 }
 
-// The same selection for the final ranking: ids and scores go straight to the caller's buffers, best first, and the
-// slots beyond min(k, count) are filled with (-1, -infinity).
+// Rank counting for the final ranking.
 __global__ __launch_bounds__(256) void sel_rank_output_kernel(const uint64_t *__restrict__ keys, int64_t key_stride,
-                                                              const int32_t *__restrict__ counts, int32_t k,
+                                                              const int32_t *__restrict__ counts, int32_t n_cap, int32_t k,
                                                               int32_t *__restrict__ out_ids, float *__restrict__ out_scores)
 {
-    __shared__ uint64_t sk[SEL_SORT_CAP];
+    extern __shared__ uint64_t sk[];
     const int seg = blockIdx.y;
     int n = counts[seg];
-    if (n > SEL_SORT_CAP) n = SEL_SORT_CAP;
+    if (n > n_cap) n = n_cap;
     int32_t *oi = out_ids + (int64_t)seg * k;
     float *os = out_scores + (int64_t)seg * k;
     if (blockIdx.x == 0)
@@ -412,12 +498,30 @@ __global__ __launch_bounds__(256) void sel_rank_output_kernel(const uint64_t *__
     }
 }
 
+static inline int64_t sort_pow2(int64_t n)
+{
+    int64_t p = 2;
+    while (p < n) p <<= 1;
+    return p;
+}
+
 void plaid_launch_rank_output(hipStream_t st, const uint64_t *keys, int64_t key_stride, const int32_t *counts, int nseg,
                               int64_t n_upper, int32_t k, int32_t *out_ids, float *out_scores)
 {
-    const int gx = (int)((n_upper + RANK_KEYS_PER_BLOCK - 1) / RANK_KEYS_PER_BLOCK);
-    hipLaunchKernelGGL(sel_rank_output_kernel, dim3(gx > 0 ? gx : 1, nseg), dim3(256), 0, st, keys, key_stride, counts, k,
-                       out_ids, out_scores);
+    const size_t lds = (size_t)sort_pow2(n_upper) * 8;  // one thread per pair of the padded list, 256 to 1024
+    if (nseg <= RANK_MAX_LISTS) {
+        const int gx = (int)((n_upper + RANK_KEYS_PER_BLOCK - 1) / RANK_KEYS_PER_BLOCK);
+        hipLaunchKernelGGL(sel_rank_output_kernel, dim3(gx > 0 ? gx : 1, nseg), dim3(256), lds, st, keys, key_stride, counts,
+                           (int32_t)n_upper, k, out_ids, out_scores);
+    } else if (n_upper <= 512)
+        hipLaunchKernelGGL(sel_sort_output_kernel<256>, dim3(nseg), dim3(256), lds, st, keys, key_stride, counts,
+                           (int32_t)n_upper, k, out_ids, out_scores);
+    else if (n_upper <= 1024)
+        hipLaunchKernelGGL(sel_sort_output_kernel<512>, dim3(nseg), dim3(512), lds, st, keys, key_stride, counts,
+                           (int32_t)n_upper, k, out_ids, out_scores);
+    else
+        hipLaunchKernelGGL(sel_sort_output_kernel<1024>, dim3(nseg), dim3(1024), lds, st, keys, key_stride, counts,
+                           (int32_t)n_upper, k, out_ids, out_scores);
 }
 
 // ------------------------------------------------------------------ host side
@@ -492,9 +596,20 @@ void plaid_launch_select(hipStream_t st, const uint64_t *keys, int64_t key_strid
     // the caller zeroes state + hist (plaid_launch_fill_u32 over the head of the scratch) before the
     // producer runs; see search.hip
     if (n_upper <= SEL_SORT_CAP) {
-        const int gx = (int)((n_upper + RANK_KEYS_PER_BLOCK - 1) / RANK_KEYS_PER_BLOCK);
-        hipLaunchKernelGGL(sel_rank_kernel, dim3(gx > 0 ? gx : 1, nseg), dim3(256), 0, st, keys, key_stride, counts, m, out,
-                           out_stride, out_counts);
+        const size_t lds = (size_t)sort_pow2(n_upper) * 8;
+        if (nseg <= RANK_MAX_LISTS) {
+            const int gx = (int)((n_upper + RANK_KEYS_PER_BLOCK - 1) / RANK_KEYS_PER_BLOCK);
+            hipLaunchKernelGGL(sel_rank_kernel, dim3(gx > 0 ? gx : 1, nseg), dim3(256), lds, st, keys, key_stride, counts,
+                               (int32_t)n_upper, m, out, out_stride, out_counts);
+        } else if (n_upper <= 512)
+            hipLaunchKernelGGL(sel_sort_kernel<256>, dim3(nseg), dim3(256), lds, st, keys, key_stride, counts,
+                               (int32_t)n_upper, m, out, out_stride, out_counts);
+        else if (n_upper <= 1024)
+            hipLaunchKernelGGL(sel_sort_kernel<512>, dim3(nseg), dim3(512), lds, st, keys, key_stride, counts,
+                               (int32_t)n_upper, m, out, out_stride, out_counts);
+        else
+            hipLaunchKernelGGL(sel_sort_kernel<1024>, dim3(nseg), dim3(1024), lds, st, keys, key_stride, counts,
+                               (int32_t)n_upper, m, out, out_stride, out_counts);
         return;
     } else {
         const int gx = blocks_for(n_upper, nseg);

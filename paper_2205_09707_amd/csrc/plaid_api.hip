@@ -509,11 +509,12 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
     pl.m3 = m3 < pl.nd ? m3 : pl.nd;
     pl.kk = k < pl.m3 ? k : pl.m3;
 
-    // queries per chunk: bounded by the caller's limit, else by a workspace budget of about 6 GiB
+    // queries per chunk: bounded by the caller's limit, else 512 (the kernels that run one workgroup per query only
+    // fill the chip from a few hundred queries on) within a workspace budget of about 24 GiB
     const Workspace one = carve(nullptr, ix, 1, pl);
-    int qc = ix->max_chunk > 0 ? ix->max_chunk : 64;
+    int qc = ix->max_chunk > 0 ? ix->max_chunk : 512;
     if (ix->max_chunk <= 0) {
-        const size_t budget = (size_t)6 << 30;
+        const size_t budget = (size_t)24 << 30;
         const size_t fit = budget / (one.total ? one.total : 1);
         if ((size_t)qc > fit) qc = fit < 1 ? 1 : (int)fit;
     }

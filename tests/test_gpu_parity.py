@@ -47,10 +47,12 @@ def _kernel_forms(form=None, stage2=None):
                 os.environ[k] = v
 
 
-def _check_workload(pl, w, params_list, want=None, queries=None, copy=False, form=None, stage2=None):
+def _check_workload(pl, w, params_list, want=None, queries=None, copy=False, form=None, stage2=None, max_chunk=None):
     ix = pu.oracle_index(w)
     with _kernel_forms(form, stage2):
         gidx = pl.plaid_index_from_view(pu.device_arrays(w), w.cfg.nbits, device=0, copy=copy)
+    if max_chunk is not None:
+        pl.plaid_set_max_chunk(gidx, max_chunk)
     if form is not None:
         assert pl.plaid_get_score_kernel(gidx) == (1 if form == "matrix" else 0)
     if stage2 is not None:
@@ -91,6 +93,15 @@ def test_cfg1_other_operating_points(pl, form, stage2):
     w = make_workload(cfg, device="cpu", noise="calibrated")
     _check_workload(pl, w, [(2, 0.45, 1024, 100), (4, 0.4, 4096, 1000), (3, 0.2, 300, 40), (1, -np.inf, 64, 16),
                             (6, 0.5, 200, 20), (8, 0.45, 512, 50), (12, 0.5, 128, 10)], form=form, stage2=stage2)
+
+
+@pytest.mark.parametrize("max_chunk", [1, 3, 5])
+def test_cfg1_in_ragged_chunks(pl, max_chunk):
+    """A batch larger than the per-launch limit is processed in chunks (the last one shorter): every chunk reuses the
+    same workspace, so anything a kernel leaves behind in it would show up in the next chunk's results."""
+    cfg = get_config("cfg1")
+    w = make_workload(cfg, device="cpu", noise="calibrated")
+    _check_workload(pl, w, [(cfg.nprobe, cfg.t_cs, cfg.ndocs, cfg.k), (2, 0.45, 1024, 100)], max_chunk=max_chunk)
 
 
 def test_default_score_kernel_is_the_matrix_form(pl):
@@ -142,6 +153,11 @@ SWEEP = [
     (129, 40, 2, 12, 2, 8, "calibrated", 1, "matrix", "stream"),  # one row past a row block, one query
     (40, 5000, 1, 6, 2, 9, "calibrated", 3, None, "inverted"),    # three passage ranges, the last one ragged
     (40, 5000, 1, 6, 2, 9, "calibrated", 3, None, "stream"),
+    # more than 16 queries: the short-list selections sort in LDS (one workgroup per list) instead of counting ranks;
+    # 900 and 3000 passages put the lists into the 512- and 1024-thread forms of that sort
+    (33, 200, 1, 30, 2, 11, "calibrated", 20, None, None),
+    (24, 900, 1, 4, 2, 12, "calibrated", 17, None, None),
+    (24, 3000, 1, 4, 2, 13, "literal", 17, None, "stream"),
 ]
 
 

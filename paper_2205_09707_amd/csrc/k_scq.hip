@@ -25,9 +25,13 @@
 // uniform across a wave and is fetched through the scalar unit, so the inner loop is one
 // v_fma_f64 per (dimension, token) whose only per-lane operand is the LDS-resident centroid row.
 //
-// Either way the tile of results then yields, still in LDS, the row maxima (pruning bits) and each
-// token's best centroids of the tile; a one-workgroup-per-query kernel merges the tiles' lists
-// into the probes, their duplicate-free union, and the survivor table.
+// Either way the tile of results then yields the row maxima (pruning bits) and, per query token, the maximum of the
+// tile's column.  The probes come from those maxima: with T the nprobe-th largest tile maximum of a token, each of
+// the nprobe best tiles holds a score >= T, so the nprobe-th best score is >= T and every centroid among the nprobe
+// best lies in a tile whose maximum is >= T -- normally just nprobe tiles.  A one-workgroup-per-query kernel finds T,
+// ranks the rows of those tiles from S_cq, and builds the duplicate-free union of the probes and the survivor table.
+// (Ranking inside the score kernel instead costs it a third of its running time: its waves' vector instructions
+// queue behind other waves' matrix instructions.)
 #include "plaid_internal.h"
 
 #include <math.h>
@@ -68,6 +72,20 @@ __device__ __forceinline__ void scq_insert_key(uint64_t (&best)[NP], uint64_t ke
                 best[j] = key;
             }
         }
+    }
+}
+
+// v into a descending list of NP values (the smallest drops out)
+template <int NP>
+__device__ __forceinline__ void scq_insert_desc(float (&top)[NP], float v)
+{
+    if (v > top[NP - 1]) {
+#pragma unroll
+        for (int j = NP - 1; j >= 0; --j)
+            if (v > top[j]) {
+                if (j + 1 < NP) top[j + 1] = top[j];
+                top[j] = v;
+            }
     }
 }
 
@@ -205,23 +223,20 @@ __global__ __launch_bounds__(512) void stage1_survivor_kernel(const float *__res
                           colmm, misc);
 }
 
-// NP = capacity of the per-token candidate lists (1, 2, 4 or 8 >= nprobe); NP = 0: scores and pruning bits only.
-template <int NP>
+// tilemax: [q][tile][32] column maxima of each tile (null: scores and pruning bits only).
 __global__ __launch_bounds__(SCQ_THREADS) void scq_fused_kernel(const float *__restrict__ Cm, int64_t C,
                                                                 const double *__restrict__ Qd, float t_cs,
                                                                 float *__restrict__ S, uint32_t *__restrict__ keepbits,
-                                                                int64_t keep_words, uint64_t *__restrict__ partial)
+                                                                int64_t keep_words, float *__restrict__ tilemax)
 {
-    constexpr int NPK = NP > 0 ? NP : 1;
     // one LDS arena: half of the centroid tile (64 dimensions) at a time during the contraction; afterwards the 64x32
-    // result tile and the lists
-    constexpr int ARENA_FLOATS = SCQ_ROWS * SCQ_RSTRIDE > SCQ_ROWS * SCQ_SSTRIDE + 8 * QLEN * NPK * 2
+    // result tile and the partial column maxima
+    constexpr int ARENA_FLOATS = SCQ_ROWS * SCQ_RSTRIDE > SCQ_ROWS * SCQ_SSTRIDE + 8 * QLEN
                                      ? SCQ_ROWS * SCQ_RSTRIDE
-                                     : SCQ_ROWS * SCQ_SSTRIDE + 8 * QLEN * NPK * 2;
+                                     : SCQ_ROWS * SCQ_SSTRIDE + 8 * QLEN;
     __shared__ __align__(16) float arena[ARENA_FLOATS];
-    float *tile = arena;                                                         // [64][SCQ_SSTRIDE]
-    uint64_t *lk = reinterpret_cast<uint64_t *>(arena + SCQ_ROWS * SCQ_SSTRIDE);  // [8][32][NPK], 8-byte aligned
-    static_assert((SCQ_ROWS * SCQ_SSTRIDE) % 2 == 0, "list area must be 8-byte aligned");
+    float *tile = arena;                             // [64][SCQ_SSTRIDE]
+    float *cm = arena + SCQ_ROWS * SCQ_SSTRIDE;      // [8][32]
     const int q = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63;
     const int g = __builtin_amdgcn_readfirstlane(tid >> 6);  // token group of this wave (uniform -> scalar loads of Qd)
@@ -306,32 +321,26 @@ __global__ __launch_bounds__(SCQ_THREADS) void scq_fused_kernel(const float *__r
             if ((c0 >> 5) + 1 < keep_words) kb[1] = (uint32_t)(b >> 32);
         }
     }
-    if (NP == 0) return;
+    if (!tilemax) return;  // uniform
 
-    // Section 4.1: each token's NP best centroids of this tile.  Thread (i, p) ranks rows 8p .. 8p+7 of column i.
-    uint64_t best[NPK];
-#pragma unroll
-    for (int j = 0; j < NPK; ++j) best[j] = PLAID_KEY_MAX;
+    // column maxima of the tile: thread (i, p) takes rows 8p .. 8p+7 of column i
     if (tid < 256) {
         const int i = tid & 31, p = tid >> 5;
+        float m = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const int rr = 8 * p + r;
-            if (rr < nrows) scq_insert_key<NPK>(best, plaid_make_key(tile[rr * SCQ_SSTRIDE + i], (uint32_t)(c0 + rr)));
+            if (rr < nrows) m = fmaxf(m, tile[rr * SCQ_SSTRIDE + i]);
         }
-#pragma unroll
-        for (int j = 0; j < NPK; ++j) lk[(p * QLEN + i) * NPK + j] = best[j];
+        cm[p * QLEN + i] = m;
     }
     __syncthreads();
     if (tid < QLEN) {
-        for (int p = 1; p < 8; ++p)
+        float m = cm[tid];
 #pragma unroll
-            for (int j = 0; j < NPK; ++j) scq_insert_key<NPK>(best, lk[(p * QLEN + tid) * NPK + j]);
-        uint64_t *po = partial + (((int64_t)q * QLEN + tid) * gridDim.x + blockIdx.x) * NPK;  // [q][token][tile][NPK]
-#pragma unroll
-        for (int j = 0; j < NPK; ++j) po[j] = best[j];
+        for (int p = 1; p < 8; ++p) m = fmaxf(m, cm[p * QLEN + tid]);
+        tilemax[((int64_t)q * gridDim.x + blockIdx.x) * QLEN + tid] = m;
     }
-
 }
 
 
@@ -349,12 +358,10 @@ typedef double scq_double4 __attribute__((ext_vector_type(4)));
 #define SM_WAVES (SM_THREADS / 64)
 #define SM_WROWS (16 * SM_RT)        // centroid rows per wave
 #define SM_ROWS (SM_WAVES * SM_WROWS)  // centroid rows per workgroup
-#define SM_PARTS (SM_THREADS / QLEN) // threads that share a query token in the per-tile ranking
 static_assert(SM_WROWS == 16 || SM_WROWS == 32, "pruning bits are assembled from 16- or 32-row pieces");
-static_assert(SM_PARTS <= 64 && SM_ROWS % SM_PARTS == 0 && SM_ROWS % (SM_THREADS / 8) == 0, "tile shape");
+static_assert(SM_ROWS % (SM_THREADS / 8) == 0 && SM_THREADS >= QLEN, "tile shape");
 #define SM_KC 32                     // dimensions staged at a time
 #define SM_ASTRIDE 36                // floats per staged row chunk: the 64 operand reads of a step hit 64 banks
-#define SM_TSTRIDE 33                // floats per row of the result tile
 #ifndef SM_MIN_WAVES
 #define SM_MIN_WAVES 4               // waves per SIMD the register allocation leaves room for
 #endif
@@ -375,42 +382,24 @@ __device__ __forceinline__ void scq_lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <int NP>
-__device__ __forceinline__ void scq_insert_pair(uint32_t (&bo)[NP], uint32_t (&bi)[NP], uint32_t o, uint32_t id)
-{
-    // callers present ids in ascending order, so a strict comparison keeps the smaller id among equal scores
-    if (o < bo[NP - 1]) {
-#pragma unroll
-        for (int j = NP - 1; j >= 0; --j) {
-            if (o < bo[j]) {
-                if (j + 1 < NP) {
-                    bo[j + 1] = bo[j];
-                    bi[j + 1] = bi[j];
-                }
-                bo[j] = o;
-                bi[j] = id;
-            }
-        }
-    }
-}
-
-// NP as in scq_fused_kernel; NQ = queries per workgroup (1 or 2).  Grid: x = query group, y = row block.
-// partial: [q][token][row block][NP].
-template <int NP, int NQ>
+// NQ = queries per workgroup (1 or 2).  Grid: x = query group, y = row block.
+// tilemax: [q][32-row block][32] column maxima over the 32 rows a wave owns (null: scores and pruning bits only).
+template <int NQ>
 __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(const float *__restrict__ Cm, int64_t C,
                                                               const float *__restrict__ Q, int nq, float t_cs,
                                                               float *__restrict__ S, uint32_t *__restrict__ keepbits,
-                                                              int64_t keep_words, uint64_t *__restrict__ partial,
+                                                              int64_t keep_words, float *__restrict__ tilemax,
                                                               uint32_t *__restrict__ zero, int64_t zero_words)
 {
-    constexpr int NPK = NP > 0 ? NP : 1;
     constexpr int NT = 2 * NQ;  // 16-column tiles
-    constexpr int ARENA_FLOATS = SM_ROWS * (SM_ASTRIDE > SM_TSTRIDE ? SM_ASTRIDE : SM_TSTRIDE);
-    __shared__ __align__(16) float arena[ARENA_FLOATS];   // staged centroid chunk, later the result tile
+    __shared__ __align__(16) float arena[SM_ROWS * SM_ASTRIDE];  // staged centroid chunk
     __shared__ __align__(16) float Bq[(SM_KC / 4) * NT * 64];    // the chunk's query operands: [step][column tile][lane]
-    float *tile = arena;
     const int tid = threadIdx.x, lane = tid & 63, li = lane & 15, lg = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // Outside the matrix loop a wave runs at raised priority: its few vector instructions (set-up, staging, epilogue)
+    // would otherwise wait their turn behind the matrix instructions of every other wave on the SIMD, and the sooner a
+    // wave is through them, the sooner it feeds the matrix pipe again.
+    __builtin_amdgcn_s_setprio(3);
     // the workspace words that later kernels expect to be zero are cleared here, by the whole grid (no kernel of this
     // search has touched them yet, and every kernel of the previous one has finished)
     for (int64_t i = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * SM_THREADS + tid; i < zero_words;
@@ -482,6 +471,7 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
                 }
             }
         }
+        __builtin_amdgcn_s_setprio(0);
 #pragma unroll
         for (int j = 0; j < SM_KC / 4; ++j) {
             double a[SM_RT], b[NT];
@@ -494,120 +484,61 @@ __global__ __launch_bounds__(SM_THREADS, SM_MIN_WAVES) void scq_mfma_kernel(cons
 #pragma unroll
                 for (int t = 0; t < NT; ++t) acc[m][t] = scq_mma(a[m], b[t], acc[m][t]);
         }
-        scq_lds_barrier();  // every wave is done with this chunk: the arena is rewritten next
+        __builtin_amdgcn_s_setprio(3);
+        if (ch + 1 < DIM / SM_KC) scq_lds_barrier();  // every wave is done with this chunk: the arena is rewritten next
     }
 
-    // epilogue, one query at a time through the LDS tile
-    __shared__ uint32_t kpiece[SM_WAVES];  // pruning bits of each wave's rows
+    // Epilogue, straight from the accumulators (no LDS, no barrier: every vector instruction here queues behind the
+    // matrix instructions of the other waves on the SIMD, so the fewer the better).  Lane 16 g + i holds rows 4 r + g of
+    // columns i and 16 + i of each 16-row tile: a store instruction writes four 64-byte row halves, the two halves of
+    // a row back to back.  Eq. 5: the comparison's lane mask holds, in its 16-bit field g, the columns of row 4 r + g, so
+    // a row passes when its field is not zero -- scalar work on the mask, none per lane.
+    const bool ragged = nrows < SM_ROWS;  // rows past the end of the table hold zeros: not stored, not in a maximum
+    const int wrow0 = wave * SM_WROWS;
+    const int wrows = nrows - wrow0 < 0 ? 0 : (nrows - wrow0 < SM_WROWS ? nrows - wrow0 : SM_WROWS);  // this wave's rows
+    static_assert(SM_WROWS == 32, "one word of the pruning bitmap per wave");
 #pragma unroll
     for (int qi = 0; qi < NQ; ++qi) {
         const int q = q0 + qi;
         if (q >= nq) break;  // uniform
-        // results to the tile; Eq. 5 on the way: a row passes when any of its 32 scores reaches t_cs, so each lane marks
-        // the rows in which one of its two columns does (bit = row within the wave's 32 rows), and the marks are OR-ed over
-        // the 16 lanes that share rows (two quad swaps, then the mirrors of 8 and of 16 lanes) and over the four row groups
-        uint32_t kbits = 0u;
+        uint32_t kbits = 0u;                     // uniform: bit = row within the wave's 32 rows
+        float cm0 = -INFINITY, cm1 = -INFINITY;  // maxima of this lane's two columns (tokens li and 16 + li) over its rows
+        float *srow = S + ((int64_t)q * C + c0 + wrow0 + lg) * QLEN + li;
 #pragma unroll
         for (int m = 0; m < SM_RT; ++m)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int row = 16 * m + 4 * r + lg;  // within the wave's rows
+                const int row = 16 * m + 4 * r;  // + lg
                 const float v0 = (float)acc[m][2 * qi][r], v1 = (float)acc[m][2 * qi + 1][r];
-                float *trow = tile + (wave * SM_WROWS + row) * SM_TSTRIDE + li;
-                trow[0] = v0;
-                trow[16] = v1;
-                if (v0 >= t_cs || v1 >= t_cs) kbits |= 1u << row;
+                if (!ragged || row + lg < wrows) {
+                    srow[row * QLEN] = v0;
+                    srow[row * QLEN + 16] = v1;
+                    // med3(a, b, +inf) = max(a, b) for ordered operands, without the canonicalising copies of fmaxf
+                    cm0 = __builtin_amdgcn_fmed3f(cm0, v0, INFINITY);
+                    cm1 = __builtin_amdgcn_fmed3f(cm1, v1, INFINITY);
+                }
+                const unsigned long long pass = __ballot(v0 >= t_cs || v1 >= t_cs);
+                const uint32_t lo = (uint32_t)pass, hi = (uint32_t)(pass >> 32);
+                const uint32_t nib = ((lo & 0xFFFFu) ? 1u : 0u) | ((lo >> 16) ? 2u : 0u) | ((hi & 0xFFFFu) ? 4u : 0u) |
+                                     ((hi >> 16) ? 8u : 0u);
+                kbits |= nib << row;
             }
-        kbits |= (uint32_t)__builtin_amdgcn_update_dpp((int)kbits, (int)kbits, 0xB1, 0xF, 0xF, false);
-        kbits |= (uint32_t)__builtin_amdgcn_update_dpp((int)kbits, (int)kbits, 0x4E, 0xF, 0xF, false);
-        kbits |= (uint32_t)__builtin_amdgcn_update_dpp((int)kbits, (int)kbits, 0x141, 0xF, 0xF, false);
-        kbits |= (uint32_t)__builtin_amdgcn_update_dpp((int)kbits, (int)kbits, 0x140, 0xF, 0xF, false);
-        kbits |= __shfl_xor(kbits, 16);
-        kbits |= __shfl_xor(kbits, 32);
+        if (tilemax) {  // uniform
+            cm0 = __builtin_amdgcn_fmed3f(cm0, __shfl_xor(cm0, 16), INFINITY);
+            cm1 = __builtin_amdgcn_fmed3f(cm1, __shfl_xor(cm1, 16), INFINITY);
+            cm0 = __builtin_amdgcn_fmed3f(cm0, __shfl_xor(cm0, 32), INFINITY);
+            cm1 = __builtin_amdgcn_fmed3f(cm1, __shfl_xor(cm1, 32), INFINITY);
+            const int64_t blk = (int64_t)blockIdx.y * SM_WAVES + wave, n_blk = (C + SM_WROWS - 1) / SM_WROWS;
+            if (lg == 0 && blk < n_blk) {  // a block with a row in range; rows past the end were left out above
+                float *tmx = tilemax + ((int64_t)q * n_blk + blk) * QLEN + li;
+                tmx[0] = cm0;
+                tmx[16] = cm1;
+            }
+        }
         // rows past the end of the centroid table (a ragged last block) never pass
-        if (nrows - wave * SM_WROWS < SM_WROWS)
-            kbits &= nrows - wave * SM_WROWS > 0 ? (1u << (nrows - wave * SM_WROWS)) - 1u : 0u;
-        if (lane == 0) kpiece[wave] = kbits;
-        scq_lds_barrier();
-        if (tid < SM_ROWS / 32) {  // one 32-bit word of the pruning bitmap per 32 rows
-            const int64_t w0 = (c0 >> 5) + tid;
-            const uint32_t word = SM_WROWS == 32 ? kpiece[tid] : (kpiece[2 * tid] | (kpiece[2 * tid + 1] << 16));
-            if (w0 < keep_words) keepbits[(int64_t)q * keep_words + w0] = word;
-        }
-        // scores, coalesced: the tile's rows are contiguous in S
-        for (int e = tid; e < SM_ROWS * (QLEN / 4); e += SM_THREADS) {
-            const int r = e >> 3, k4 = e & 7;
-            if (r < nrows) {
-                const float *tr = tile + r * SM_TSTRIDE + 4 * k4;
-                *reinterpret_cast<float4 *>(S + ((int64_t)q * C + c0 + r) * QLEN + 4 * k4) = make_float4(tr[0], tr[1], tr[2], tr[3]);
-            }
-        }
-        if (NP > 0) {
-            // Section 4.1: each token's NP best centroids of this tile.  SM_PARTS consecutive lanes share a token; lane p of
-            // them takes rows p, p + SM_PARTS, ... (ascending, so a strict comparison keeps the smaller id among equal
-            // scores); the lists of a token are then merged inside the wave.
-            const int i = tid / SM_PARTS, p = tid % SM_PARTS;
-            float bs[NPK];
-            uint32_t bi[NPK];
-#pragma unroll
-            for (int j = 0; j < NPK; ++j) {
-                bs[j] = -INFINITY;
-                bi[j] = 0xFFFFFFFFu;
-            }
-            // (comparisons treat -0 and +0 alike, as the ranking keys do)
-#pragma unroll
-            for (int k = 0; k < SM_ROWS / SM_PARTS; ++k) {
-                const int rr = SM_PARTS * k + p;
-                const float sv = rr < nrows ? tile[rr * SM_TSTRIDE + i] : -INFINITY;
-                if (sv > bs[NPK - 1]) {
-#pragma unroll
-                    for (int j = NPK - 1; j >= 0; --j)
-                        if (sv > bs[j]) {
-                            if (j + 1 < NPK) {
-                                bs[j + 1] = bs[j];
-                                bi[j + 1] = bi[j];
-                            }
-                            bs[j] = sv;
-                            bi[j] = (uint32_t)(c0 + rr);
-                        }
-                }
-            }
-#pragma unroll
-            for (int d = 1; d < SM_PARTS; d <<= 1) {
-                float os[NPK];
-                uint32_t oi[NPK];
-#pragma unroll
-                for (int j = 0; j < NPK; ++j) {
-                    os[j] = __shfl_xor(bs[j], d);
-                    oi[j] = __shfl_xor(bi[j], d);
-                }
-#pragma unroll
-                for (int jo = 0; jo < NPK; ++jo) {
-                    const float sv = os[jo];
-                    const uint32_t id = oi[jo];
-                    // (score descending, id ascending); an entry equal to one already held is the same row
-                    if (sv > bs[NPK - 1] || (sv == bs[NPK - 1] && id < bi[NPK - 1])) {
-#pragma unroll
-                        for (int j = NPK - 1; j >= 0; --j)
-                            if (sv > bs[j] || (sv == bs[j] && id < bi[j])) {
-                                if (j + 1 < NPK) {
-                                    bs[j + 1] = bs[j];
-                                    bi[j + 1] = bi[j];
-                                }
-                                bs[j] = sv;
-                                bi[j] = id;
-                            }
-                    }
-                }
-            }
-            if (p == 0) {
-                uint64_t *po = partial + (((int64_t)q * QLEN + i) * gridDim.y + blockIdx.y) * NPK;
-#pragma unroll
-                for (int j = 0; j < NPK; ++j)
-                    po[j] = bi[j] == 0xFFFFFFFFu ? PLAID_KEY_MAX : plaid_make_key(bs[j], bi[j]);
-            }
-        }
-        scq_lds_barrier();  // the tile is rewritten for the next query
+        if (wrows < SM_WROWS) kbits &= (1u << wrows) - 1u;
+        const int64_t w0 = (c0 >> 5) + wave;  // one 32-bit word of the pruning bitmap per 32 rows
+        if (lane == 0 && w0 < keep_words) keepbits[(int64_t)q * keep_words + w0] = kbits;
     }
 }
 
@@ -656,14 +587,21 @@ int plaid_scq_matrix_form_ok(hipStream_t st, int *ok)
     return 0;
 }
 
-// One workgroup per query: merge the tiles' lists into the probes (rank order), their ascending duplicate-free union,
-// and build the survivor table.  32 lanes share a query token: each folds every 32nd tile list (coalesced: the lists
-// of a token are contiguous), then the 32 partial lists are merged by a shuffle tree inside the wave.
+// One workgroup per query: the probes (rank order) from the tiles' column maxima, their ascending duplicate-free
+// union, and the survivor table.  tilemax is [tile][token]: a thread reads four tokens of every 128th tile (16-byte
+// loads, consecutive threads at consecutive addresses, eight loads in flight) and keeps each token's NP largest; the
+// eight lanes of a wave that share tokens merge their lists by shuffles.  Then 32 consecutive lanes share a token:
+// T = the nprobe-th largest of the token's tile maxima (nprobe rounds of "maximum over the 32 lanes, its first holder
+// drops it").  A second pass over tilemax lists the tiles whose maximum is >= T in LDS (normally nprobe of them; a
+// tie group too long for the list makes the lanes walk all tiles instead); their rows are ranked by (score
+// descending, id ascending) from S_cq, four loads per lane in flight, and the 32 lists are merged by a shuffle tree.
+// tile_rows = centroid rows per tile.
+#define TAIL_SEL 16  // listed tiles per token
 template <int NP>
 __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *__restrict__ S, int64_t C,
                                                                    const uint32_t *__restrict__ keepbits, int64_t keep_words,
-                                                                   const uint64_t *__restrict__ partial, int nblk, int nprobe,
-                                                                   Stage1Out o)
+                                                                   const float *__restrict__ tilemax, int nblk, int tile_rows,
+                                                                   int nprobe, Stage1Out o)
 {
     __shared__ int32_t idl[256];   // probed ids
     __shared__ int32_t top1[QLEN];
@@ -672,29 +610,141 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
     __shared__ uint32_t trial[S2_NHASH * (S2_HASH / 32)];
     __shared__ float colmm[2 * QLEN];
     __shared__ int32_t misc[2];
+    constexpr int TAIL_WAVES = TAIL_THREADS / 64;
+    constexpr int TAIL_FLY = 8;                          // loads in flight per thread
+    constexpr int TAIL_PARTS = TAIL_THREADS / (QLEN / 4);  // threads that share four tokens
+    __shared__ float cand[QLEN][TAIL_WAVES * NP + 1];  // each wave's NP largest tile maxima of every token
+    static_assert(TAIL_WAVES <= TAIL_LANES, "one lane per wave list");
+    __shared__ float Tsh[QLEN];
+    __shared__ int32_t sel_cnt[QLEN];
+    __shared__ int32_t sel_tile[QLEN][TAIL_SEL];
+    static_assert(TAIL_THREADS == QLEN * TAIL_LANES && TAIL_LANES == 32, "32 lanes per query token");
     const int q = blockIdx.x, tid = threadIdx.x;
+    const float *__restrict__ Sq = S + (int64_t)q * C * QLEN;
+    const float *__restrict__ tmq = tilemax + (int64_t)q * nblk * QLEN;
     {
-        const int i = tid / TAIL_LANES, l = tid % TAIL_LANES;
+        // pass 1: thread (tokens 4 tk4 .. 4 tk4 + 3, part) keeps the NP largest maxima of tiles part, part + 128, ...
+        const int tk4 = tid % (QLEN / 4), part = tid / (QLEN / 4);
+        float top[4][NP];
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int j = 0; j < NP; ++j) top[c][j] = -INFINITY;
+        for (int b0 = part; b0 < nblk; b0 += TAIL_PARTS * TAIL_FLY) {
+            float4 v[TAIL_FLY];
+#pragma unroll
+            for (int u = 0; u < TAIL_FLY; ++u) {
+                const int b = b0 + TAIL_PARTS * u;
+                v[u] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+                if (b < nblk) v[u] = *reinterpret_cast<const float4 *>(tmq + (int64_t)b * QLEN + 4 * tk4);
+            }
+#pragma unroll
+            for (int u = 0; u < TAIL_FLY; ++u) {
+                const float x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) scq_insert_desc<NP>(top[c], x[c]);
+            }
+        }
+        // the lanes of a wave with the same tk4 are 8 apart
+#pragma unroll
+        for (int d = QLEN / 4; d < 64; d <<= 1)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                float other[NP];
+#pragma unroll
+                for (int j = 0; j < NP; ++j) other[j] = __shfl_xor(top[c][j], d);
+#pragma unroll
+                for (int j = 0; j < NP; ++j) scq_insert_desc<NP>(top[c], other[j]);
+            }
+        if ((tid & 63) < QLEN / 4) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int j = 0; j < NP; ++j) cand[4 * tk4 + c][(tid >> 6) * NP + j] = top[c][j];
+        }
+    }
+    __syncthreads();
+    const int i = tid / TAIL_LANES, l = tid % TAIL_LANES;
+    {
+        float top[NP];  // descending
+#pragma unroll
+        for (int j = 0; j < NP; ++j) top[j] = l < TAIL_WAVES ? cand[i][l * NP + j] : -INFINITY;
+        float T = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < NP; ++r)
+            if (r < nprobe) {  // uniform
+                float m = top[0];
+#pragma unroll
+                for (int d = TAIL_LANES / 2; d > 0; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
+                T = m;
+                const unsigned long long who = __ballot(top[0] == m);
+                const uint32_t mine = (tid & 32) ? (uint32_t)(who >> 32) : (uint32_t)who;  // this token's 32 lanes
+                if (l == __ffs(mine) - 1) {
+#pragma unroll
+                    for (int j = 0; j + 1 < NP; ++j) top[j] = top[j + 1];
+                    top[NP - 1] = -INFINITY;
+                }
+            }
+        if (l == 0) {
+            Tsh[i] = T;
+            sel_cnt[i] = 0;
+        }
+    }
+    __syncthreads();
+    {
+        // pass 2, same thread -> (tokens, tiles) map: list the tiles that can hold one of the nprobe best
+        const int tk4 = tid % (QLEN / 4), part = tid / (QLEN / 4);
+        const float T4[4] = {Tsh[4 * tk4], Tsh[4 * tk4 + 1], Tsh[4 * tk4 + 2], Tsh[4 * tk4 + 3]};
+        for (int b0 = part; b0 < nblk; b0 += TAIL_PARTS * TAIL_FLY) {
+            float4 v[TAIL_FLY];
+#pragma unroll
+            for (int u = 0; u < TAIL_FLY; ++u) {
+                const int b = b0 + TAIL_PARTS * u;
+                v[u] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+                if (b < nblk) v[u] = *reinterpret_cast<const float4 *>(tmq + (int64_t)b * QLEN + 4 * tk4);
+            }
+#pragma unroll
+            for (int u = 0; u < TAIL_FLY; ++u) {
+                const int b = b0 + TAIL_PARTS * u;
+                const float x[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (b < nblk && x[c] >= T4[c]) {
+                        const int pos = atomicAdd(&sel_cnt[4 * tk4 + c], 1);
+                        if (pos < TAIL_SEL) sel_tile[4 * tk4 + c][pos] = b;
+                    }
+            }
+        }
+    }
+    __syncthreads();
+    {
         uint64_t best[NP];
 #pragma unroll
         for (int j = 0; j < NP; ++j) best[j] = PLAID_KEY_MAX;
-        const uint64_t *pq = partial + ((int64_t)q * QLEN + i) * nblk * NP;
-        constexpr int FLY = NP <= 2 ? 8 : (NP == 4 ? 4 : 2);  // lists in flight per lane
-        int b = l;
-        for (; b + (FLY - 1) * TAIL_LANES < nblk; b += FLY * TAIL_LANES) {
-            uint64_t v[FLY][NP];
+        const float T = Tsh[i];
+        const int n_sel = sel_cnt[i];
+        const bool listed = n_sel <= TAIL_SEL;
+        const int chunks = (tile_rows + TAIL_LANES - 1) / TAIL_LANES;  // 32-row pieces of a tile
+        const int n_items = (listed ? n_sel : nblk) * chunks;
+        for (int it0 = 0; it0 < n_items; it0 += 4) {
+            float sv[4];
+            int64_t cc[4];
+            bool ok[4];
 #pragma unroll
-            for (int u = 0; u < FLY; ++u)
+            for (int u = 0; u < 4; ++u) {
+                const int it = it0 + u;
+                ok[u] = it < n_items;
+                const int k = ok[u] ? it / chunks : 0, r = (it % chunks) * TAIL_LANES + l;
+                const int t = listed ? sel_tile[i][k] : k;
+                if (!listed && ok[u]) ok[u] = tmq[(int64_t)t * QLEN + i] >= T;
+                cc[u] = (int64_t)t * tile_rows + r;
+                ok[u] = ok[u] && r < tile_rows && cc[u] < C;
+                sv[u] = ok[u] ? Sq[cc[u] * QLEN + i] : 0.f;
+            }
 #pragma unroll
-                for (int j = 0; j < NP; ++j) v[u][j] = pq[(int64_t)(b + TAIL_LANES * u) * NP + j];
-#pragma unroll
-            for (int u = 0; u < FLY; ++u)
-#pragma unroll
-                for (int j = 0; j < NP; ++j) scq_insert_key<NP>(best, v[u][j]);
+            for (int u = 0; u < 4; ++u)
+                if (ok[u]) scq_insert_key<NP>(best, plaid_make_key(sv[u], (uint32_t)cc[u]));
         }
-        for (; b < nblk; b += TAIL_LANES)
-#pragma unroll
-            for (int j = 0; j < NP; ++j) scq_insert_key<NP>(best, pq[(int64_t)b * NP + j]);
         // shuffle tree over the 32 lanes of this token (lanes l and l ^ d exchange lists; both keep the merged list)
 #pragma unroll
         for (int d = 1; d < TAIL_LANES; d <<= 1) {
@@ -744,38 +794,49 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
                           colmm, misc);
 }
 
-template <int NP>
-static void launch_fused(hipStream_t st, int phases, const float *centroids, int64_t C, const float *Q, const void *Qx,
+// np = capacity of the tail's lists (1, 2, 4 or 8 >= nprobe); np = 0: scores and pruning bits only (large nprobe).
+static void launch_fused(hipStream_t st, int phases, int np, const float *centroids, int64_t C, const float *Q, const void *Qx,
                          int matrix_form, int nq, float t_cs, float *S, uint32_t *keepbits, int64_t keep_words,
-                         uint64_t *partial, int nprobe, const Stage1Out &o, uint32_t *zero, int64_t zero_words)
+                         float *tilemax, int nprobe, const Stage1Out &o, uint32_t *zero, int64_t zero_words)
 {
-    const unsigned nblk = (unsigned)(matrix_form ? (C + SM_ROWS - 1) / SM_ROWS : (C + SCQ_ROWS - 1) / SCQ_ROWS);
+    const int tile_rows = matrix_form ? SM_WROWS : SCQ_ROWS;  // rows per tile of column maxima
+    const int grid_rows = matrix_form ? SM_ROWS : SCQ_ROWS;   // rows per workgroup
+    const unsigned nblk = (unsigned)((C + grid_rows - 1) / grid_rows);
+    const int n_tiles = (int)((C + tile_rows - 1) / tile_rows);
+    float *tmx = np > 0 ? tilemax : nullptr;
     if (!(phases & PLAID_STAGE1_SCORES)) {
     } else if (matrix_form) {
         if (nq == 1)
-            hipLaunchKernelGGL((scq_mfma_kernel<NP, 1>), dim3(1, nblk), dim3(SM_THREADS), 0, st, centroids, C, Q, nq, t_cs, S,
-                               keepbits, keep_words, partial, zero, zero_words);
+            hipLaunchKernelGGL(scq_mfma_kernel<1>, dim3(1, nblk), dim3(SM_THREADS), 0, st, centroids, C, Q, nq, t_cs, S, keepbits,
+                               keep_words, tmx, zero, zero_words);
         else
-            hipLaunchKernelGGL((scq_mfma_kernel<NP, 2>), dim3((unsigned)((nq + 1) / 2), nblk), dim3(SM_THREADS), 0, st, centroids,
-                               C, Q, nq, t_cs, S, keepbits, keep_words, partial, zero, zero_words);
+            hipLaunchKernelGGL(scq_mfma_kernel<2>, dim3((unsigned)((nq + 1) / 2), nblk), dim3(SM_THREADS), 0, st, centroids, C, Q,
+                               nq, t_cs, S, keepbits, keep_words, tmx, zero, zero_words);
     } else {
-        hipLaunchKernelGGL(scq_fused_kernel<NP>, dim3(nblk, nq), dim3(SCQ_THREADS), 0, st, centroids, C, (const double *)Qx, t_cs,
-                           S, keepbits, keep_words, partial);
+        hipLaunchKernelGGL(scq_fused_kernel, dim3(nblk, nq), dim3(SCQ_THREADS), 0, st, centroids, C, (const double *)Qx, t_cs, S,
+                           keepbits, keep_words, tmx);
     }
-    if (NP > 0 && (phases & PLAID_STAGE1_PROBES))
-        hipLaunchKernelGGL(stage1_tail_kernel<(NP > 0 ? NP : 1)>, dim3(nq), dim3(TAIL_THREADS), 0, st, S, C, keepbits,
-                           keep_words, partial, (int)nblk, nprobe, o);
+    if (np > 0 && (phases & PLAID_STAGE1_PROBES)) {
+#define TAIL(NP_)                                                                                                          \
+    hipLaunchKernelGGL(stage1_tail_kernel<NP_>, dim3(nq), dim3(TAIL_THREADS), 0, st, S, C, keepbits, keep_words, tilemax, \
+                       n_tiles, tile_rows, nprobe, o)
+        if (np == 1) TAIL(1);
+        else if (np == 2) TAIL(2);
+        else if (np == 4) TAIL(4);
+        else TAIL(8);
+#undef TAIL
+    }
 }
 
-size_t plaid_stage1_partial_bytes(int64_t C, int nq, int nprobe)
+size_t plaid_stage1_tilemax_bytes(int64_t C, int nq, int nprobe)
 {
     if (nprobe > PLAID_PROBE_FAST_MAX) return 256;
-    const int np = nprobe == 1 ? 1 : (nprobe == 2 ? 2 : (nprobe <= 4 ? 4 : 8));
-    return (size_t)nq * ((C + SCQ_ROWS - 1) / SCQ_ROWS) * QLEN * np * 8;
+    const int rows = SM_WROWS < SCQ_ROWS ? SM_WROWS : SCQ_ROWS;  // sized for the smaller of the two tile heights
+    return (size_t)nq * ((C + rows - 1) / rows) * QLEN * 4;
 }
 
 void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int64_t C, const float *Q, void *Qd, int matrix_form,
-                         int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int32_t *done,
+                         int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, float *tilemax, int32_t *done,
                          uint32_t *zero, int64_t zero_words, int32_t *probed, int32_t *uniq, int uniq_stride,
                          int32_t *n_uniq, const Stage2Buffers &s2, void *probe_scratch, size_t probe_scratch_bytes)
 {
@@ -794,19 +855,14 @@ void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int
     o.meta = s2.meta;
     o.kept_ids = s2.kept_ids;
     o.T = s2.T;
-    if (nprobe == 1) launch_fused<1>(st, phases, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o, zero,
-                        zero_words);
-    else if (nprobe == 2) launch_fused<2>(st, phases, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o, zero,
-                        zero_words);
-    else if (nprobe <= 4) launch_fused<4>(st, phases, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o, zero,
-                        zero_words);
-    else if (nprobe <= PLAID_PROBE_FAST_MAX)
-        launch_fused<8>(st, phases, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o, zero,
-                        zero_words);
+    const int np = nprobe == 1 ? 1 : (nprobe == 2 ? 2 : (nprobe <= 4 ? 4 : (nprobe <= PLAID_PROBE_FAST_MAX ? 8 : 0)));
+    if (np > 0)
+        launch_fused(st, phases, np, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, tilemax, nprobe, o,
+                     zero, zero_words);
     else {
         // large nprobe: scores and pruning bits here, probes through the generic selection, survivor table after it
-        launch_fused<0>(st, phases, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, partial, nprobe, o, zero,
-                        zero_words);
+        launch_fused(st, phases, 0, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, tilemax, nprobe, o,
+                     zero, zero_words);
         if (phases & PLAID_STAGE1_PROBES) {
             plaid_launch_top_nprobe_general(st, S, C, nq, nprobe, probed, uniq, uniq_stride, n_uniq, probe_scratch,
                                             probe_scratch_bytes);

@@ -392,7 +392,7 @@ struct Workspace {
     int32_t *n_uniq;     // [qc]
     void *probe_scratch;
     size_t probe_scratch_bytes;
-    uint64_t *partial;   // per-tile probe lists of the stage-1 kernel
+    float *tilemax;      // [qc][tiles][32] column maxima of the score kernel's tiles
     int32_t *done;       // [qc] stage-1 tile counter (zeroed region)
     uint64_t *keys2;  // [qc][P]
     uint64_t *sel2;   // [qc][nd]
@@ -445,7 +445,7 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     w.n_uniq = (int32_t *)take((size_t)qc * 4);
     w.probe_scratch_bytes = plaid_top_nprobe_scratch_bytes(C, qc, pl.nprobe);
     w.probe_scratch = take(w.probe_scratch_bytes);
-    w.partial = (uint64_t *)take(plaid_stage1_partial_bytes(C, qc, pl.nprobe));
+    w.tilemax = (float *)take(plaid_stage1_tilemax_bytes(C, qc, pl.nprobe));
     w.keys2 = (uint64_t *)take((size_t)qc * P * 8);
     w.s2.blist = (uint64_t *)take((size_t)qc * P * 8);
     w.s2.meta = (S2Meta *)take((size_t)qc * sizeof(S2Meta));
@@ -544,7 +544,7 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
         // stage 1: S_cq (Eq. 2), pruning map (Eq. 5), probes and candidates (Section 4.1)
         for (int phase = PLAID_STAGE1_PREP; phase <= PLAID_STAGE1_PROBES; phase <<= 1) {
             plaid_launch_stage1(st, phase, ix->centroids, C, Qc, w.Qd, ix->scq_matrix_form, n, t_cs, nprobe, w.S, w.keepbits,
-                                w.keep_words, w.partial, w.done, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed,
+                                w.keep_words, w.tilemax, w.done, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed,
                                 w.uniq, w.uniq_stride, w.n_uniq, w.s2, w.probe_scratch, w.probe_scratch_bytes);
             STAMP();
         }

@@ -100,10 +100,10 @@ int plaid_scq_matrix_form_ok(hipStream_t st, int *ok);  // returns a hipError_t 
 #define PLAID_STAGE1_SCORES 2
 #define PLAID_STAGE1_PROBES 4
 void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int64_t C, const float *Q, void *Qx, int matrix_form,
-                         int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, uint64_t *partial, int32_t *done,
+                         int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, float *tilemax, int32_t *done,
                          uint32_t *zero, int64_t zero_words, int32_t *probed, int32_t *uniq, int uniq_stride,
                          int32_t *n_uniq, const struct Stage2Buffers &s2, void *probe_scratch, size_t probe_scratch_bytes);
-size_t plaid_stage1_partial_bytes(int64_t C, int nq, int nprobe);
+size_t plaid_stage1_tilemax_bytes(int64_t C, int nq, int nprobe);
 
 // General top-nprobe (nprobe > PLAID_PROBE_FAST_MAX): ranking keys of every S column through the generic selection.
 void plaid_launch_top_nprobe_general(hipStream_t st, const float *S, int64_t C, int nq, int nprobe, int32_t *probed,

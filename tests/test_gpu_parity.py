@@ -199,6 +199,16 @@ def test_rare_paths(pl, name, cfgkw, params, forms):
         _check_workload(pl, w, params, stage2=stage2)
 
 
+@pytest.mark.parametrize("form", ["matrix", "vector"])
+def test_all_zero_query_token(pl, form):
+    """A query token of zeros scores 0 against every centroid: all tiles of the score kernel tie on their column
+    maximum (more tiles than the probe kernel lists per token), and the probes are the lowest centroid ids."""
+    w = make_workload(tiny_config(C=2200, P=300, lo=2, hi=12, nbits=2, nq=3, seed=41), noise="calibrated")
+    w.queries[:, 0, :] = 0.0
+    w.queries[1, 7, :] = 0.0
+    _check_workload(pl, w, [(1, 0.3, 40, 5), (2, 0.3, 40, 5), (4, -np.inf, 64, 8), (7, 0.2, 30, 4)], form=form)
+
+
 def test_codec_bit_exact(pl):
     """Unpacked bucket indices and reconstructed vectors (Section 4.5) are bit-identical to the oracle's."""
     for nbits, seed in ((2, 21), (1, 22)):

@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 FP64_MFMA_PEAK_TFLOPS = 78.6   # MI355X published dense fp64 matrix rate (the vector fp64 rate is the same figure)
 FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
 
-# HBM bytes per launch (64 queries) of each kernel, from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of this file,
+# HBM bytes per launch (512 queries) of each kernel, from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of this file,
 # each scaled by the counter's reading on a 1 GiB device copy (fetch reads half the bytes: x2; write: x1).
 # Source of every figure: the profiles/ summary named here.  Missing = not measured (reported as null).
 MEASURED_TRAFFIC_PER_LAUNCH = {

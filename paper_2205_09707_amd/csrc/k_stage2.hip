@@ -480,6 +480,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
 #define IVR_EMPTY 0xFFFFFFFFu
 #define IVR_LISTS 256  // lists handled per LDS round (= threads of the workgroup)
 #define IVR_SHORT 64   // a list with at most this many entries in the range joins the pooled pass
+#define IVR_DENSE_DIV 16  // a list with at least P / 16 entries also gets a bitmap over the passages
 static_assert(IVR_LISTS == S2_THREADS, "one list per thread and round");
 
 // table[c][r] for every non-empty (list, range) pair; the others keep IVR_EMPTY until ivr_fill_kernel.
@@ -524,6 +525,47 @@ void plaid_launch_ivf_range_table(hipStream_t st, const int64_t *ivf_offsets, co
     plaid_launch_fill_u32(st, table, C * (nr + 1), IVR_EMPTY);
     hipLaunchKernelGGL(ivr_mark_kernel, dim3((unsigned)(C < 8192 ? C : 8192)), dim3(256), 0, st, ivf_offsets, ivf_pids, C, nr, table);
     hipLaunchKernelGGL(ivr_fill_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, ivf_offsets, C, nr, table);
+}
+
+// Dense lists.  The centroid of a frequent token occurs in a large share of the passages: its list is then longer than
+// a bitmap over the passages (P / 8 bytes), and a query that probes it would read megabytes of passage ids to set
+// nearly every candidate bit.  Lists with at least P / IVR_DENSE_DIV entries therefore also get such a bitmap at index
+// creation: dense_id[c] = row of the bitmap, or -1.
+__global__ __launch_bounds__(256) void ivr_dense_mark_kernel(const int64_t *__restrict__ ivf_offsets, int64_t C, int64_t P,
+                                                             int32_t *__restrict__ dense_id, int32_t *__restrict__ counter)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    const int64_t len = ivf_offsets[c + 1] - ivf_offsets[c];
+    dense_id[c] = (len > 0 && len * IVR_DENSE_DIV >= P) ? atomicAdd(counter, 1) : -1;
+}
+__global__ __launch_bounds__(256) void ivr_dense_fill_kernel(const int64_t *__restrict__ ivf_offsets,
+                                                             const int32_t *__restrict__ ivf_pids, int64_t C, int64_t P,
+                                                             const int32_t *__restrict__ dense_id, uint32_t *__restrict__ bits,
+                                                             int64_t words)
+{
+    for (int64_t c = blockIdx.x; c < C; c += gridDim.x) {
+        const int32_t d = dense_id[c];
+        if (d < 0) continue;  // uniform
+        uint32_t *row = bits + (int64_t)d * words;
+        const int64_t s = ivf_offsets[c], t = ivf_offsets[c + 1];
+        for (int64_t e = s + threadIdx.x; e < t; e += blockDim.x) {
+            const uint32_t pid = (uint32_t)ivf_pids[e];
+            if ((int64_t)pid < P) atomicOr(&row[pid >> 5], 1u << (pid & 31));
+        }
+    }
+}
+void plaid_launch_ivf_dense_mark(hipStream_t st, const int64_t *ivf_offsets, int64_t C, int64_t P, int32_t *dense_id,
+                                 int32_t *counter)
+{
+    hipLaunchKernelGGL(ivr_dense_mark_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, ivf_offsets, C, P, dense_id,
+                       counter);
+}
+void plaid_launch_ivf_dense_fill(hipStream_t st, const int64_t *ivf_offsets, const int32_t *ivf_pids, int64_t C, int64_t P,
+                                 const int32_t *dense_id, uint32_t *bits, int64_t words)
+{
+    hipLaunchKernelGGL(ivr_dense_fill_kernel, dim3((unsigned)(C < 8192 ? C : 8192)), dim3(256), 0, st, ivf_offsets, ivf_pids, C,
+                       P, dense_id, bits, words);
 }
 
 // Exclusive prefix sum of one value per thread over the workgroup, into out[0 .. S2_THREADS]; scratch: one int per wave.
@@ -617,13 +659,126 @@ __device__ __forceinline__ void ivr_apply_round(int cnt, int64_t first, unsigned
     __syncthreads();
 }
 
+// Queries none of whose centroids passes Eq. 5: every bag is empty, so stage 2 only has to produce the candidate set,
+// and a passage needs one bit instead of a set word.  A workgroup then covers 2^19 passages (64 KB of LDS bits): a wave
+// walks one probed centroid's list at a time (512 entries per step, eight loads in flight), and the bits are written
+// out once, as the candidate words and as the empty-bag words.  The fine-grained kernel below skips these queries.
+#define UW_SHIFT 19
+#define UW_WORDS (1 << (UW_SHIFT - 5))
+#define UW_THREADS 1024
+#define UW_LONG 4096  // entries from which on a list is walked by all waves together
+#define IVR_WIDE_MIN_QUERIES 32
+static_assert(UW_SHIFT >= IVR_SHIFT, "a wide range is a whole number of table ranges");
+__global__ __launch_bounds__(UW_THREADS) void s2_union_wide_kernel(
+    const int32_t *__restrict__ uniq, const int32_t *__restrict__ n_uniq, int uniq_stride,
+    const int64_t *__restrict__ ivf_offsets, const int32_t *__restrict__ ivf_pids, const uint32_t *__restrict__ table,
+    int64_t nr, int64_t P, const S2Meta *__restrict__ meta, const int32_t *__restrict__ dense_id,
+    const uint32_t *__restrict__ dense_bits, uint32_t *__restrict__ candbits, int64_t cand_words,
+    uint32_t *__restrict__ emptybits)
+{
+    __shared__ uint32_t bits[UW_WORDS];
+    __shared__ int64_t first[IVR_LISTS];
+    __shared__ int32_t count[IVR_LISTS];
+    __shared__ int32_t dense[IVR_LISTS];  // rows of the dense-list bitmaps probed in this round
+    __shared__ int32_t n_dense;
+    const int q = blockIdx.y;
+    if (s2_uniform(meta[q].K) != 0) return;  // uniform
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = s2_uniform(tid >> 6);
+    const int64_t fr0 = (int64_t)blockIdx.x << (UW_SHIFT - IVR_SHIFT);  // table ranges [fr0, fr1)
+    const int64_t fr1 = fr0 + (1ll << (UW_SHIFT - IVR_SHIFT)) < nr ? fr0 + (1ll << (UW_SHIFT - IVR_SHIFT)) : nr;
+    const uint32_t p0 = (uint32_t)blockIdx.x << UW_SHIFT;
+    for (int e = tid; e < UW_WORDS; e += UW_THREADS) bits[e] = 0u;
+    const int nu = n_uniq[q];
+    for (int u0 = 0; u0 < nu; u0 += IVR_LISTS) {
+        const int nb = nu - u0 < IVR_LISTS ? nu - u0 : IVR_LISTS;
+        __syncthreads();  // the bits are zero / the previous round's lists are done
+        if (tid == 0) n_dense = 0;
+        __syncthreads();
+        if (tid < nb) {
+            const int32_t c = uniq[(int64_t)q * uniq_stride + u0 + tid];
+            const int32_t d = dense_id[c];
+            if (d >= 0) {  // its bitmap is OR-ed in below
+                dense[atomicAdd(&n_dense, 1)] = d;
+                count[tid] = 0;
+            } else {
+                const uint32_t a = table[(int64_t)c * (nr + 1) + fr0], b = table[(int64_t)c * (nr + 1) + fr1];
+                first[tid] = ivf_offsets[c] + a;
+                count[tid] = b > a ? (int)(b - a) : 0;
+            }
+        }
+        __syncthreads();
+        // steps s0, s0 + stride, ... of list l (a step = 512 entries).  A lane takes eight consecutive entries and merges
+        // the bits that fall into one word before it touches LDS: in the list of a centroid that occurs in nearly every
+        // passage consecutive entries are consecutive passages, and one entry per lane would send 32 lanes to each word.
+        auto walk = [&](int l, int s0, int stride) {
+            const int n = s2_uniform(count[l]);
+            const int32_t *__restrict__ src = ivf_pids + first[l];
+            for (int e0 = s0 * 512; e0 < n; e0 += stride * 512) {
+                uint32_t pid[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int e = e0 + 8 * lane + u;
+                    pid[u] = e < n ? (uint32_t)src[e] : 0xFFFFFFFFu;
+                }
+                uint32_t cw = 0xFFFFFFFFu, acc = 0u;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const uint32_t loc = pid[u] - p0;
+                    if (pid[u] != 0xFFFFFFFFu && loc < (1u << UW_SHIFT)) {
+                        const uint32_t w = loc >> 5, bit = 1u << (loc & 31);
+                        if (w != cw) {
+                            if (acc) atomicOr(&bits[cw], acc);
+                            cw = w;
+                            acc = bit;
+                        } else {
+                            acc |= bit;
+                        }
+                    }
+                }
+                if (acc) atomicOr(&bits[cw], acc);
+            }
+        };
+        // a wave takes whole lists of ordinary length; the lists of centroids that occur in most passages (hundreds
+        // of thousands of entries) are shared by all waves
+        for (int l = wave; l < nb; l += UW_THREADS / 64)
+            if (count[l] <= UW_LONG) walk(l, 0, 1);
+        for (int l = 0; l < nb; ++l)
+            if (count[l] > UW_LONG) walk(l, wave, UW_THREADS / 64);
+        const int nd = n_dense;
+        if (nd > 0) {  // uniform
+            __syncthreads();  // the walks' atomics are done: each word now has one owner thread
+            const int64_t wf = (int64_t)p0 >> 5;
+            const int64_t nwr = cand_words - wf < UW_WORDS ? cand_words - wf : UW_WORDS;
+            for (int64_t w = tid; w < nwr; w += UW_THREADS) {
+                uint32_t v = bits[w];
+                for (int d = 0; d < nd; ++d) v |= dense_bits[(int64_t)dense[d] * cand_words + wf + w];
+                bits[w] = v;
+            }
+        }
+    }
+    __syncthreads();
+    const int64_t w_first = (int64_t)p0 >> 5;
+    uint32_t *cbq = candbits + (int64_t)q * cand_words + w_first;
+    uint32_t *ebq = emptybits + (int64_t)q * cand_words + w_first;
+    const int64_t nw = cand_words - w_first < UW_WORDS ? cand_words - w_first : UW_WORDS;
+    for (int64_t w = tid; w < nw; w += UW_THREADS) {
+        uint32_t v = bits[w];
+        const int64_t pbase = (int64_t)p0 + 32 * w;  // passages past the end never enter the lists; the mask is a guard
+        if (pbase + 32 > P) v &= pbase < P ? (1u << (uint32_t)(P - pbase)) - 1u : 0u;
+        cbq[w] = v;
+        ebq[w] = v;
+    }
+}
+
 __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
     const int32_t *__restrict__ uniq, const int32_t *__restrict__ n_uniq, int uniq_stride,
     const int64_t *__restrict__ ivf_offsets, const int32_t *__restrict__ ivf_pids, const uint32_t *__restrict__ table,
     int64_t nr, const float *__restrict__ S, int64_t C, const uint32_t *__restrict__ keepbits, int64_t keep_words,
     const int32_t *__restrict__ codes, const int64_t *__restrict__ doc_offsets, int64_t P, const S2Meta *__restrict__ meta,
     const int32_t *__restrict__ kept_ids, const float *__restrict__ T, uint32_t *__restrict__ candbits, int64_t cand_words,
-    uint64_t *__restrict__ keys2, int64_t key_stride, int32_t *__restrict__ hist, uint32_t *__restrict__ emptybits)
+    uint64_t *__restrict__ keys2, int64_t key_stride, int32_t *__restrict__ hist, uint32_t *__restrict__ emptybits,
+    int skip_k0)
 {
     __shared__ unsigned long long lsets[IVR_RANGE];
     __shared__ uint32_t lcand[IVR_RANGE / 32], lempty[IVR_RANGE / 32];
@@ -639,6 +794,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = s2_uniform(tid >> 6);
     const int K = s2_uniform(meta[q].K);
+    if (K == 0 && skip_k0) return;  // uniform: s2_union_wide_kernel has produced this query's candidate and empty-bag words
     const bool slots = K > 0 && K <= S2_MAX_KEPT;  // bags are kept as slot sets
     const int hsh = s2_uniform(meta[q].hash_shift);
     for (int e = tid; e < IVR_RANGE; e += S2_THREADS) lsets[e] = 0ull;
@@ -656,12 +812,12 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
         unsigned long long val = 0;
         if (tid < nb) {
             const int32_t c = uniq[(int64_t)q * uniq_stride + u0 + tid];
-            const uint32_t a = table[(int64_t)c * (nr + 1) + r], b = table[(int64_t)c * (nr + 1) + r + 1];
-            first = ivf_offsets[c] + a;
-            cnt = b > a ? (int)(b - a) : 0;
             const uint32_t sl = slots ? s2_lookup(htab, (uint32_t)c, hsh) : 0u;
             val = 1ull | (sl ? 1ull << sl : 0ull);
             if (sl) atomicOr(&slot_probed[sl >> 5], 1u << (sl & 31));
+            const uint32_t a = table[(int64_t)c * (nr + 1) + r], b = table[(int64_t)c * (nr + 1) + r + 1];
+            first = ivf_offsets[c] + a;
+            cnt = b > a ? (int)(b - a) : 0;
         }
         ivr_apply_round(cnt, first, val, ivf_pids, r0, lsets, lists);
     }
@@ -682,12 +838,12 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
         ivr_apply_round(cnt, first, 1ull << (tid + 1), ivf_pids, r0, lsets, lists);
     }
 
+    const int64_t w_first = (int64_t)r0 >> 5;  // first bitmap word of the range
     // emit the range: lane = passage, 64 passages per step
     const float bin_hi = meta[q].bin_hi, bin_scale = meta[q].bin_scale;
     uint64_t *keys_out = keys2 + (int64_t)q * key_stride;
     uint32_t *cbq = candbits + (int64_t)q * cand_words;
     uint32_t *ebq = emptybits + (int64_t)q * cand_words;
-    const int64_t w_first = (int64_t)r0 >> 5;  // first bitmap word of the range
     for (int g = wave; g < IVR_RANGE / 64; g += S2_THREADS / 64) {
         const unsigned long long v = lsets[64 * g + lane];
         const int64_t pid = (int64_t)r0 + 64 * g + lane;
@@ -730,12 +886,21 @@ void plaid_launch_stage2_inverted(hipStream_t st, const int32_t *uniq, const int
                                   const int64_t *ivf_offsets, const int32_t *ivf_pids, const uint32_t *table, const float *S,
                                   int64_t C, const uint32_t *keepbits, int64_t keep_words, const int32_t *codes,
                                   const int64_t *doc_offsets, int64_t P, int nq, const Stage2Buffers &b, uint32_t *candbits,
-                                  int64_t cand_words, uint64_t *keys2, int64_t key_stride)
+                                  int64_t cand_words, uint64_t *keys2, int64_t key_stride, const int32_t *dense_id,
+                                  const uint32_t *dense_bits)
 {
     const int64_t nr = (P + IVR_RANGE - 1) >> IVR_SHIFT;
+    const int64_t nwide = (P + (1ll << UW_SHIFT) - 1) >> UW_SHIFT;
+    // One workgroup per query and 2^19 passages pays off once the launch holds enough queries to fill the chip with such
+    // workgroups; below that the fine-grained kernel (one workgroup per 2048 passages) also takes the queries without
+    // a surviving centroid.
+    const int wide = nq >= IVR_WIDE_MIN_QUERIES ? 1 : 0;
+    if (wide)
+        hipLaunchKernelGGL(s2_union_wide_kernel, dim3((unsigned)nwide, nq), dim3(UW_THREADS), 0, st, uniq, n_uniq, uniq_stride,
+                           ivf_offsets, ivf_pids, table, nr, P, b.meta, dense_id, dense_bits, candbits, cand_words, b.emptybits);
     hipLaunchKernelGGL(s2_invert_kernel, dim3((unsigned)nr, nq), dim3(S2_THREADS), 0, st, uniq, n_uniq, uniq_stride, ivf_offsets,
                        ivf_pids, table, nr, S, C, keepbits, keep_words, codes, doc_offsets, P, b.meta, b.kept_ids, b.T, candbits,
-                       cand_words, keys2, key_stride, b.hist, b.emptybits);
+                       cand_words, keys2, key_stride, b.hist, b.emptybits, wide);
 }
 
 // ------------------------------------------------------------------ host side

@@ -52,6 +52,8 @@ struct plaid_index {
     int32_t timing = 0;
     int32_t scq_matrix_form = 0;  // score kernel: 1 = double-precision matrix instruction, 0 = vector FMA chain
     uint32_t *ivr_table = nullptr;  // range table of the inverted lists (owned); null: union + code stream are used
+    int32_t *dense_id = nullptr;    // with the range table: bitmap row of each centroid's list, -1 for all but the longest
+    uint32_t *dense_bits = nullptr; // [rows][ceil(P / 32)]
     float stage_ms[PLAID_NUM_STAGES] = {0};
     hipEvent_t ev[N_EVENTS] = {nullptr};
 };
@@ -115,6 +117,33 @@ static int build_range_table(plaid_index *ix)
     plaid_launch_ivf_range_table(nullptr, ix->ivf_offsets, ix->ivf_pids, ix->C, ix->P, (uint32_t *)d);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipStreamSynchronize(nullptr));
+    // bitmaps of the longest lists
+    const int64_t words = (ix->P + 31) / 32;
+    int32_t *did = nullptr, *counter = nullptr;
+    if (hipMalloc((void **)&did, (size_t)ix->C * 4) != hipSuccess || hipMalloc((void **)&counter, 4) != hipSuccess) {
+        (void)hipGetLastError();
+        if (did) (void)hipFree(did);
+        return fail(PLAID_ENOMEM, "hipMalloc for the dense-list index failed");
+    }
+    ix->owned.push_back(did);
+    ix->owned.push_back(counter);
+    HIP_TRY(hipMemset(counter, 0, 4));
+    plaid_launch_ivf_dense_mark(nullptr, ix->ivf_offsets, ix->C, ix->P, did, counter);
+    int32_t rows = 0;
+    HIP_TRY(hipMemcpy(&rows, counter, 4, hipMemcpyDeviceToHost));
+    void *db = nullptr;
+    const size_t dbytes = (size_t)(rows > 0 ? rows : 1) * (size_t)words * 4;
+    if (hipMalloc(&db, dbytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PLAID_ENOMEM, "hipMalloc(%zu) for the dense-list bitmaps failed", dbytes);
+    }
+    ix->owned.push_back(db);
+    HIP_TRY(hipMemset(db, 0, dbytes));
+    if (rows > 0) plaid_launch_ivf_dense_fill(nullptr, ix->ivf_offsets, ix->ivf_pids, ix->C, ix->P, did, (uint32_t *)db, words);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(nullptr));
+    ix->dense_id = did;
+    ix->dense_bits = (uint32_t *)db;
     ix->ivr_table = (uint32_t *)d;
     return PLAID_OK;
 }
@@ -556,7 +585,7 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
         if (ix->ivr_table)
             plaid_launch_stage2_inverted(st, w.uniq, w.n_uniq, w.uniq_stride, ix->ivf_offsets, ix->ivf_pids, ix->ivr_table, w.S,
                                          C, w.keepbits, w.keep_words, ix->codes, ix->doc_offsets, P, n, w.s2, w.candbits,
-                                         w.cand_words, w.keys2, P);
+                                         w.cand_words, w.keys2, P, ix->dense_id, ix->dense_bits);
         else
             plaid_launch_stage2(st, w.S, C, w.keepbits, w.keep_words, w.probed, nprobe, w.candbits, w.cand_words, P, ix->N,
                                 ix->doc_offsets, ix->codes, n, w.s2, w.keys2, P);

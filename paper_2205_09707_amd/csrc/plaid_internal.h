@@ -184,7 +184,15 @@ void plaid_launch_stage2_inverted(hipStream_t st, const int32_t *uniq, const int
                                   const int64_t *ivf_offsets, const int32_t *ivf_pids, const uint32_t *table, const float *S,
                                   int64_t C, const uint32_t *keepbits, int64_t keep_words, const int32_t *codes,
                                   const int64_t *doc_offsets, int64_t P, int nq, const Stage2Buffers &b, uint32_t *candbits,
-                                  int64_t cand_words, uint64_t *keys2, int64_t key_stride);
+                                  int64_t cand_words, uint64_t *keys2, int64_t key_stride, const int32_t *dense_id,
+                                  const uint32_t *dense_bits);
+// Bitmaps over the passages for the longest inverted lists (built once per index, next to the range table):
+// dense_id[c] = bitmap row of centroid c or -1 (counter[0], zero before the call, returns the number of rows);
+// bits: rows x words, zero before the call, words = ceil(P / 32).
+void plaid_launch_ivf_dense_mark(hipStream_t st, const int64_t *ivf_offsets, int64_t C, int64_t P, int32_t *dense_id,
+                                 int32_t *counter);
+void plaid_launch_ivf_dense_fill(hipStream_t st, const int64_t *ivf_offsets, const int32_t *ivf_pids, int64_t C, int64_t P,
+                                 const int32_t *dense_id, uint32_t *bits, int64_t words);
 
 // Best min(m, #candidates) candidates by (score desc, pid asc): from the keys by bin filter (+ digit filter when the
 // boundary bin is over-long), then from the empty candidates in pid order.  keys2 is overwritten (scratch).

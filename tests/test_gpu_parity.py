@@ -158,6 +158,11 @@ SWEEP = [
     (33, 200, 1, 30, 2, 11, "calibrated", 20, None, None),
     (24, 900, 1, 4, 2, 12, "calibrated", 17, None, None),
     (24, 3000, 1, 4, 2, 13, "literal", 17, None, "stream"),
+    # 32 queries or more: queries without a surviving centroid (t_cs = +inf in the parameter list) take the kernel that
+    # covers 2^19 passages per workgroup; 16 centroids over 300 passages make every inverted list long enough for a
+    # bitmap, 200 centroids over 3000 short passages none
+    (16, 300, 1, 9, 2, 14, "calibrated", 33, None, "inverted"),
+    (200, 3000, 1, 4, 2, 15, "literal", 40, None, "inverted"),
 ]
 
 

@@ -29,11 +29,11 @@ FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
 # each scaled by the counter's reading on a 1 GiB device copy (fetch reads half the bytes: x2; write: x1).
 # Source of every figure: the profiles/ summary named here.  Missing = not measured (reported as null).
 MEASURED_TRAFFIC_PER_LAUNCH = {
-    # (config, noise, stage): bytes; profiles/bench_cfg3.txt
-    ("cfg3", "literal", "scq"): int((131773.0 * 2.0 + 547472.7) * 1024),
-    ("cfg3", "literal", "stage2_ci"): int((123402.4 * 2.0 + 124990.8) * 1024),
-    ("cfg3", "literal", "stage3_ci"): int((108548.2 * 2.0 + 524.8) * 1024),
-    ("cfg3", "literal", "stage4_maxsim"): int((70111.2 * 2.0 + 139.1) * 1024),
+    # (config, noise, stage): bytes; profiles/bench_cfg3.txt (KiB figures: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0)
+    ("cfg3", "literal", "scq"): int((140826.9 * 2.0 + 4388136.5) * 1024),
+    ("cfg3", "literal", "stage2_ci"): int(((33917.0 + 22424.0) * 2.0 + 83349.9 + 44937.9) * 1024),  # both stage-2 kernels
+    ("cfg3", "literal", "stage3_ci"): int((787106.7 * 2.0 + 4257.6) * 1024),
+    ("cfg3", "literal", "stage4_maxsim"): int((521646.1 * 2.0 + 1758.2) * 1024),
 }
 
 
@@ -46,12 +46,13 @@ def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
     Stage 2 (Eq. 3-5), code-stream figure: per candidate passage 8 bytes of offsets + 4 bytes per token code; for a query
     none of whose centroids passes Eq. 5 every bag is empty whatever the codes hold, and only the candidate bitmap is read
     and written.  Inverted-list figure (what the inverted form of candidate generation + stage 2 must move instead): 4 bytes
-    per entry of the inverted lists of the probed and the surviving centroids, 8 bytes per key written (queries with a
-    surviving centroid) and the candidate and empty-bag words.
-    Stage 3 (Eq. 3-4): per passage kept by stage 2, 8 bytes of offsets and per token its 4-byte code and the 128-byte
-    S_cq row it selects.
-    Stage 4 (Section 4.5, Eq. 1): per surviving passage 8 bytes of offsets and per token its 4-byte code, its packed
-    residual (16 * nbits bytes) and the 128-byte S_cq row that carries the centroid's share of the dot products."""
+    per entry of the inverted lists of the probed and the surviving centroids (for a query without a surviving centroid,
+    which only needs the candidate set, a list longer than a bitmap over the passages counts as that bitmap), 8 bytes
+    per key written (queries with a surviving centroid) and the candidate and empty-bag words.
+    Stage 3 (Eq. 3-4): per passage kept by stage 2, 8 bytes of offsets and 4 bytes per token code, plus the 128-byte S_cq
+    row of every DISTINCT centroid among those tokens (a row shared by several tokens of a query has to be fetched once).
+    Stage 4 (Section 4.5, Eq. 1): per surviving passage 8 bytes of offsets and per token its 4-byte code and its packed
+    residual (16 * nbits bytes), plus the 128-byte S_cq row of every distinct centroid among those tokens."""
     import torch
     nprobe, t_cs, ndocs, k = params
     lens = (w_dev.doc_offsets[1:] - w_dev.doc_offsets[:-1])
@@ -63,7 +64,20 @@ def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
     inv = 0
     ivf_len = (w_dev.ivf_offsets[1:] - w_dev.ivf_offsets[:-1])
     ncand = []
-    step = 64   # the library's chunk size, so that these launches look like the timed ones to a profiler
+    step = 512  # the library's chunk size, so that these launches look like the timed ones to a profiler
+    bitmap_bytes = 4 * ((cfg.P + 31) // 32)
+
+    def token_codes(pids):
+        """codes of all tokens of the passages `pids` (1-D long tensor)"""
+        ln = lens[pids]
+        starts = w_dev.doc_offsets[pids]
+        total = int(ln.sum())
+        if total == 0:
+            return w_dev.codes[:0], 0
+        seg = torch.repeat_interleave(torch.arange(pids.numel(), device=pids.device), ln)
+        first = torch.cumsum(ln, 0) - ln
+        pos = torch.arange(total, device=pids.device) - first[seg] + starts[seg]
+        return w_dev.codes[pos], total
     for q0 in range(0, Q.shape[0], step):
         _, _, b = pl.plaid_search_debug(idx, Q[q0:q0 + step], nprobe, t_cs, ndocs, k,
                                         want=("S_cq", "probed", "cand", "n_cand", "sel2_ids", "n2", "sel3_ids", "n3"))
@@ -74,7 +88,10 @@ def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
         for j in range(keep.shape[0]):
             lists = keep[j].clone() if survivors[j] <= 63 else torch.zeros_like(keep[j])
             lists[b["probed"][j].flatten().long()] = True
-            inv += 4 * int(ivf_len[lists].sum()) + 2 * 4 * ((cfg.P + 31) // 32)
+            list_bytes = 4 * ivf_len[lists]
+            if survivors[j] == 0:
+                list_bytes = torch.clamp(list_bytes, max=bitmap_bytes)
+            inv += int(list_bytes.sum()) + 2 * bitmap_bytes
         for j in range(b["cand"].shape[0]):
             n = int(b["n_cand"][j])
             c = b["cand"][j, :n].long()
@@ -86,11 +103,12 @@ def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
                 n_skipped += 1
             ncand.append(n)
             n2 = int(b["n2"][j])
-            s3 += 8 * n2 + (4 + 128) * int(lens[b["sel2_ids"][j, :n2].long()].sum())
+            tc, t = token_codes(b["sel2_ids"][j, :n2].long())
+            s3 += 8 * n2 + 4 * t + 128 * int(torch.unique(tc).numel())
             n3 = int(b["n3"][j])
-            t = int(lens[b["sel3_ids"][j, :n3].long()].sum())
+            tc, t = token_codes(b["sel3_ids"][j, :n3].long())
             s4_tokens += t
-            s4 += 8 * n3 + t * (4 + 16 * cfg.nbits + 128)
+            s4 += 8 * n3 + t * (4 + 16 * cfg.nbits) + 128 * int(torch.unique(tc).numel())
     return {"stage2_bytes": s2, "stage2_inverted_bytes": inv, "stage3_bytes": s3, "stage4_bytes": s4, "stage4_tokens": s4_tokens,
             "mean_candidates": float(sum(ncand)) / max(1, len(ncand)), "queries_without_survivors": n_skipped}
 

@@ -10,6 +10,10 @@
 
 #include <math.h>
 
+#ifndef CI_FLY
+#define CI_FLY 8
+#endif
+
 __device__ __forceinline__ float sum32_as_double(float m)
 {
     double d = (double)m;
@@ -29,8 +33,17 @@ __device__ __forceinline__ float ci_passage(const float *__restrict__ Sq, const 
         const int cnt = t1 - base < 64 ? (int)(t1 - base) : 64;
         const int32_t code = lane < cnt ? codes[base + lane] : 0;
         if (!PRUNE) {
+            // CI_FLY row pairs in flight, then 4, then one at a time (a row is 128 bytes somewhere in the query's S_cq:
+            // the more requests a wave keeps in flight, the closer the gather gets to the memory system's rate)
             int j = 0;
-            for (; j + 8 <= cnt; j += 8) {  // 4 row pairs in flight
+            for (; j + 2 * CI_FLY <= cnt; j += 2 * CI_FLY) {
+                float v[CI_FLY];
+#pragma unroll
+                for (int u = 0; u < CI_FLY; ++u) v[u] = Sq[(int64_t)__shfl(code, j + 2 * u + h) * QLEN + i];
+#pragma unroll
+                for (int u = 0; u < CI_FLY; ++u) m = fmaxf(m, v[u]);
+            }
+            for (; j + 8 <= cnt; j += 8) {
                 const int c0 = __shfl(code, j + h), c1 = __shfl(code, j + 2 + h), c2 = __shfl(code, j + 4 + h),
                           c3 = __shfl(code, j + 6 + h);
                 const float v0 = Sq[(int64_t)c0 * QLEN + i], v1 = Sq[(int64_t)c1 * QLEN + i],

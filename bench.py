@@ -185,8 +185,11 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
         def entry(stage, kernel, bound, amount, unit_scale, peak, unit, extra):
             t = stage_ms[stage] * 1e-3
             ach = amount / t / unit_scale if t > 0 else 0.0
+            traffic = MEASURED_TRAFFIC_PER_LAUNCH.get((cfg.name, noise, stage))
             e = {"bound": bound, "kernel": kernel, "achieved": round(ach, 1), "peak": peak, "unit": unit,
-                 "frac": round(ach / peak, 4), "traffic": MEASURED_TRAFFIC_PER_LAUNCH.get((cfg.name, noise, stage)),
+                 "frac": round(ach / peak, 4), "traffic": traffic,
+                 # hardware bytes (rocprofv3 counters) over this run's kernel time, next to the algorithmic figure
+                 "traffic_gbs": round(traffic / (t / launches) / 1e9, 1) if traffic and t > 0 else None,
                  "kernel_ms_per_step": round(stage_ms[stage], 4), "launches_per_step": launches, "queries_per_launch": CHUNK,
                  "kernel_ms_per_launch": round(stage_ms[stage] / launches, 4)}
             e.update(extra)

@@ -164,6 +164,36 @@ int plaid_get_stage_ms(const plaid_index *idx, float *out_ms);
 /* Limit on queries processed per internal chunk (0 = library default).  Affects workspace size only. */
 int plaid_set_max_chunk(plaid_index *idx, int32_t max_queries_per_chunk);
 
+/* ---- Index construction: the step before the search path.  Every array is DEVICE memory of `device`; the calls
+ * synchronise `hip_stream` before they return (sizes and error flags are read back) and allocate temporary device
+ * memory, which they release. ---- */
+
+/* Nearest centroid of each vector (Section 3.1: a token is stored with the id of its closest centroid):
+ * codes[j] = the centroid with the largest dot product centroids[c] . x[j], the dot products accumulated in double over
+ * the dimensions in index order and rounded once to fp32, exactly as S_cq of Eq. 2 is (the same kernel computes them,
+ * 32 vectors at a time); among equal scores the smaller id wins.
+ *   centroids  [C][128] fp32, 16-byte aligned     x  [n][128] fp32, 16-byte aligned     codes  [n] int32 (output)
+ * Errors: PLAID_EINVAL (null or misaligned pointers, sizes out of range), PLAID_ENOMEM, PLAID_EHIP. */
+int plaid_assign_centroids(const float *centroids, int64_t C, const float *x, int64_t n, int32_t *codes, int device,
+                           void *hip_stream);
+
+/* Residual encoding (Section 3.1; the inverse of the byte table of Section 4.5): per dimension r = x - centroid (one
+ * fp32 subtraction), bucket = the number of cut-offs strictly below r, and 8 / nbits bucket indices per byte, the first
+ * dimension in the most significant bits.
+ *   cutoffs    [2^nbits - 1] fp32 ascending        codes  [n] in [0, C)
+ *   residuals  [n][16 * nbits] uint8 (output), 4-byte aligned
+ * Errors: PLAID_EINVAL (also when a code is outside [0, C): nothing is read out of bounds), PLAID_ENOMEM, PLAID_EHIP. */
+int plaid_encode_residuals(const float *centroids, int64_t C, const float *x, const int32_t *codes, int64_t n,
+                           const float *cutoffs, int32_t nbits, uint8_t *residuals, int device, void *hip_stream);
+
+/* Passage-level inverted lists (Section 4.1): list c = the ascending unique ids of the passages with a token coded c.
+ *   codes        [N] in [0, C)            doc_offsets  [P+1], from 0 to N, non-decreasing
+ *   ivf_offsets  [C+1] int64 (output)     ivf_pids     [capacity] int32 (output; NULL: offsets and length only)
+ *   ivf_len      HOST, receives ivf_offsets[C] (may be NULL)
+ * Errors: PLAID_EINVAL (malformed offsets, a code out of range, capacity below the length), PLAID_ENOMEM, PLAID_EHIP. */
+int plaid_build_ivf(const int32_t *codes, const int64_t *doc_offsets, int64_t P, int64_t N, int64_t C, int64_t *ivf_offsets,
+                    int32_t *ivf_pids, int64_t capacity, int64_t *ivf_len, int device, void *hip_stream);
+
 /* Thread-local message describing the most recent error on the calling thread ("" if none). */
 const char *plaid_last_error(void);
 

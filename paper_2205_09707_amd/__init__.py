@@ -8,7 +8,10 @@ from .plaid import (  # noqa: F401
     Index,
     PlaidError,
     load_library,
+    plaid_assign_centroids,
+    plaid_build_ivf,
     plaid_decompress_passages,
+    plaid_encode_residuals,
     plaid_get_score_kernel,
     plaid_get_stage2_kernel,
     plaid_get_stage_ms,

@@ -660,6 +660,151 @@ extern "C" int plaid_search_debug(plaid_index *idx, const float *Q, int32_t nq, 
     return search_impl(idx, Q, nq, nprobe, t_cs, ndocs, k, out_ids, out_scores, hip_stream, dbg);
 }
 
+// ------------------------------------------------------------------ index construction
+struct TempAlloc {  // device memory released when the call returns
+    void *p = nullptr;
+    ~TempAlloc()
+    {
+        if (p) (void)hipFree(p);
+    }
+};
+
+extern "C" int plaid_assign_centroids(const float *centroids, int64_t C, const float *x, int64_t n, int32_t *codes, int device,
+                                      void *hip_stream)
+{
+    if (!centroids || (n > 0 && (!x || !codes))) return fail(PLAID_EINVAL, "null buffer");
+    if (C < 1 || C >= (1ll << 31)) return fail(PLAID_EINVAL, "num_centroids out of range (%lld)", (long long)C);
+    if (n < 0) return fail(PLAID_EINVAL, "negative vector count");
+    if (((uintptr_t)centroids | (uintptr_t)x) & 15) return fail(PLAID_EINVAL, "centroids and x must be aligned to 16 bytes");
+    if (n == 0) return PLAID_OK;
+    DeviceGuard g(device);
+    if (!g.ok) return fail(PLAID_EHIP, "hipSetDevice(%d) failed", device);
+    hipStream_t st = (hipStream_t)hip_stream;
+    // the score kernel of the search path, 32 vectors in the place of a query's 32 tokens, and its top-1 probes
+    plaid_index fake;
+    fake.device = device;
+    fake.C = C;
+    fake.P = 1;
+    int rc = choose_scq_form(&fake);
+    if (rc) return rc;
+    Plan pl;
+    pl.nprobe = 1;
+    pl.nd = pl.m3 = pl.kk = 1;
+    const int64_t groups = (n + QLEN - 1) / QLEN;
+    const Workspace one = carve(nullptr, &fake, 1, pl);
+    int64_t qc = (int64_t)(((size_t)4 << 30) / (one.total ? one.total : 1));  // about 4 GiB of workspace
+    if (qc > 512) qc = 512;
+    if (qc > groups) qc = groups;
+    if (qc < 1) qc = 1;
+    const Workspace wsz = carve(nullptr, &fake, (int)qc, pl);
+    TempAlloc ws, tailbuf;
+    if (hipMalloc(&ws.p, wsz.total) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PLAID_ENOMEM, "hipMalloc(%zu) for the assignment workspace failed", wsz.total);
+    }
+    const int64_t tail = n % QLEN;  // vectors of a last, incomplete group: staged in a zero-padded buffer
+    if (tail) {
+        if (hipMalloc(&tailbuf.p, (size_t)QLEN * DIM * 4) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(PLAID_ENOMEM, "hipMalloc for the assignment tail failed");
+        }
+        HIP_TRY(hipMemsetAsync(tailbuf.p, 0, (size_t)QLEN * DIM * 4, st));
+        HIP_TRY(hipMemcpyAsync(tailbuf.p, x + (n - tail) * DIM, (size_t)tail * DIM * 4, hipMemcpyDeviceToDevice, st));
+    }
+    const int64_t full = n / QLEN;
+    // ng groups of 32 vectors from src -> the first cnt of their codes to dst
+    auto run = [&](const float *src, int64_t ng, int32_t *dst, int64_t cnt) -> int {
+        const Workspace w = carve((char *)ws.p, &fake, (int)ng, pl);
+        for (int phase = PLAID_STAGE1_PREP; phase <= PLAID_STAGE1_PROBES; phase <<= 1)
+            plaid_launch_stage1(st, phase, centroids, C, src, w.Qd, fake.scq_matrix_form, (int)ng, INFINITY, 1, w.S, w.keepbits,
+                                w.keep_words, w.tilemax, w.done, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed,
+                                w.uniq, w.uniq_stride, w.n_uniq, w.s2, w.probe_scratch, w.probe_scratch_bytes);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipMemcpyAsync(dst, w.probed, (size_t)cnt * 4, hipMemcpyDeviceToDevice, st));  // probed is [group][32][1]
+        return PLAID_OK;
+    };
+    for (int64_t g0 = 0; g0 < full; g0 += qc) {
+        const int64_t ng = full - g0 < qc ? full - g0 : qc;
+        rc = run(x + g0 * QLEN * DIM, ng, codes + g0 * QLEN, ng * QLEN);
+        if (rc) return rc;
+    }
+    if (tail) {
+        rc = run((const float *)tailbuf.p, 1, codes + full * QLEN, tail);
+        if (rc) return rc;
+    }
+    HIP_TRY(hipStreamSynchronize(st));  // the workspace is released on return
+    return PLAID_OK;
+}
+
+extern "C" int plaid_encode_residuals(const float *centroids, int64_t C, const float *x, const int32_t *codes, int64_t n,
+                                      const float *cutoffs, int32_t nbits, uint8_t *residuals, int device, void *hip_stream)
+{
+    if (!centroids || !cutoffs || (n > 0 && (!x || !codes || !residuals))) return fail(PLAID_EINVAL, "null buffer");
+    if (nbits != 1 && nbits != 2) return fail(PLAID_EINVAL, "nbits must be 1 or 2 (got %d)", nbits);
+    if (C < 1 || C >= (1ll << 31)) return fail(PLAID_EINVAL, "num_centroids out of range (%lld)", (long long)C);
+    if (n < 0) return fail(PLAID_EINVAL, "negative vector count");
+    if (((uintptr_t)centroids | (uintptr_t)x) & 15) return fail(PLAID_EINVAL, "centroids and x must be aligned to 16 bytes");
+    if ((uintptr_t)residuals & 3) return fail(PLAID_EINVAL, "residuals must be aligned to 4 bytes");
+    if (n == 0) return PLAID_OK;
+    DeviceGuard g(device);
+    if (!g.ok) return fail(PLAID_EHIP, "hipSetDevice(%d) failed", device);
+    hipStream_t st = (hipStream_t)hip_stream;
+    TempAlloc flag;
+    if (hipMalloc(&flag.p, 4) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PLAID_ENOMEM, "hipMalloc failed");
+    }
+    HIP_TRY(hipMemsetAsync(flag.p, 0, 4, st));
+    plaid_launch_encode_residuals(st, centroids, C, x, codes, n, cutoffs, nbits, residuals, (int32_t *)flag.p);
+    HIP_TRY(hipGetLastError());
+    int32_t bad = 0;
+    HIP_TRY(hipMemcpyAsync(&bad, flag.p, 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (bad) return fail(PLAID_EINVAL, "a centroid id is outside [0, %lld)", (long long)C);
+    return PLAID_OK;
+}
+
+extern "C" int plaid_build_ivf(const int32_t *codes, const int64_t *doc_offsets, int64_t P, int64_t N, int64_t C,
+                               int64_t *ivf_offsets, int32_t *ivf_pids, int64_t capacity, int64_t *ivf_len, int device,
+                               void *hip_stream)
+{
+    if (!doc_offsets || !ivf_offsets || (N > 0 && !codes)) return fail(PLAID_EINVAL, "null buffer");
+    if (C < 1 || C >= (1ll << 31)) return fail(PLAID_EINVAL, "num_centroids out of range (%lld)", (long long)C);
+    if (P < 1 || P >= (1ll << 31)) return fail(PLAID_EINVAL, "num_passages out of range (%lld)", (long long)P);
+    if (N < 0 || capacity < 0) return fail(PLAID_EINVAL, "negative size");
+    DeviceGuard g(device);
+    if (!g.ok) return fail(PLAID_EHIP, "hipSetDevice(%d) failed", device);
+    hipStream_t st = (hipStream_t)hip_stream;
+    int64_t ends[2] = {0, 0};
+    HIP_TRY(hipMemcpyAsync(&ends[0], doc_offsets, 8, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(&ends[1], doc_offsets + P, 8, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (ends[0] != 0 || ends[1] != N) return fail(PLAID_EINVAL, "doc_offsets must run from 0 to num_embeddings (%lld)", (long long)N);
+    const size_t sb = plaid_ivf_build_scratch_bytes(P, C);
+    TempAlloc scratch;
+    if (hipMalloc(&scratch.p, sb + 256) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PLAID_ENOMEM, "hipMalloc(%zu) for the inverted-list counts failed", sb);
+    }
+    HIP_TRY(hipMemsetAsync(scratch.p, 0, sb + 256, st));
+    int32_t *bad_d = (int32_t *)((char *)scratch.p + sb);  // the last 256 bytes: the error flag
+    plaid_launch_ivf_build_offsets(st, codes, doc_offsets, P, N, C, scratch.p, ivf_offsets, bad_d);
+    HIP_TRY(hipGetLastError());
+    int32_t bad = 0;
+    int64_t total = 0;
+    HIP_TRY(hipMemcpyAsync(&bad, bad_d, 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(&total, ivf_offsets + C, 8, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (bad) return fail(PLAID_EINVAL, "a centroid id is outside [0, %lld) or doc_offsets is not monotone within [0, N]", (long long)C);
+    if (ivf_len) *ivf_len = total;
+    if (!ivf_pids) return PLAID_OK;
+    if (capacity < total) return fail(PLAID_EINVAL, "the inverted lists hold %lld entries, capacity is %lld", (long long)total, (long long)capacity);
+    plaid_launch_ivf_build_fill(st, codes, doc_offsets, P, N, C, scratch.p, ivf_offsets, ivf_pids, capacity);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(st));  // the scratch area is released on return
+    return PLAID_OK;
+}
+
 // ------------------------------------------------------------------ decompression alone
 extern "C" int plaid_decompress_passages(plaid_index *ix, const int32_t *pids, int32_t n, int64_t *out_offsets,
                                          float *out_vectors, uint8_t *out_indices, int64_t capacity, void *hip_stream)

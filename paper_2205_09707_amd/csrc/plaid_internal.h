@@ -194,6 +194,19 @@ void plaid_launch_ivf_dense_mark(hipStream_t st, const int64_t *ivf_offsets, int
 void plaid_launch_ivf_dense_fill(hipStream_t st, const int64_t *ivf_offsets, const int32_t *ivf_pids, int64_t C, int64_t P,
                                  const int32_t *dense_id, uint32_t *bits, int64_t words);
 
+// ---------------------------------------------------------------------------------------------
+// Index construction (k_build.hip)
+// ---------------------------------------------------------------------------------------------
+// residuals[j] = packed bucket indices of x[j] - centroids[codes[j]]; bad[0] is set when a code is out of range.
+void plaid_launch_encode_residuals(hipStream_t st, const float *centroids, int64_t C, const float *x, const int32_t *codes,
+                                   int64_t n, const float *cutoffs, int nbits, uint8_t *residuals, int32_t *bad);
+// Inverted lists in two steps sharing a scratch area (zero on entry): offsets first, then the passage ids.
+size_t plaid_ivf_build_scratch_bytes(int64_t P, int64_t C);
+void plaid_launch_ivf_build_offsets(hipStream_t st, const int32_t *codes, const int64_t *doc_offsets, int64_t P, int64_t N,
+                                    int64_t C, void *scratch, int64_t *ivf_offsets, int32_t *bad);
+void plaid_launch_ivf_build_fill(hipStream_t st, const int32_t *codes, const int64_t *doc_offsets, int64_t P, int64_t N,
+                                 int64_t C, void *scratch, const int64_t *ivf_offsets, int32_t *ivf_pids, int64_t capacity);
+
 // Best min(m, #candidates) candidates by (score desc, pid asc): from the keys by bin filter (+ digit filter when the
 // boundary bin is over-long), then from the empty candidates in pid order.  keys2 is overwritten (scratch).
 void plaid_launch_select2(hipStream_t st, uint64_t *keys2, int64_t key_stride, const uint32_t *candbits, int nq, int64_t P,

@@ -45,7 +45,8 @@ class plaid_debug_buffers(ct.Structure):
 
 EXPORTS = ("plaid_index_load", "plaid_index_from_view", "plaid_index_free", "plaid_search", "plaid_search_debug",
            "plaid_decompress_passages", "plaid_index_info", "plaid_set_stage_timing", "plaid_get_stage_ms",
-           "plaid_set_max_chunk", "plaid_get_score_kernel", "plaid_get_stage2_kernel", "plaid_last_error")
+           "plaid_set_max_chunk", "plaid_get_score_kernel", "plaid_get_stage2_kernel", "plaid_assign_centroids",
+           "plaid_encode_residuals", "plaid_build_ivf", "plaid_last_error")
 
 _lib = None
 
@@ -76,6 +77,11 @@ def load_library() -> ct.CDLL:
         lib.plaid_set_max_chunk.argtypes = [ct.c_void_p, ct.c_int32]
         lib.plaid_get_score_kernel.argtypes = [ct.c_void_p, ct.c_void_p]
         lib.plaid_get_stage2_kernel.argtypes = [ct.c_void_p, ct.c_void_p]
+        lib.plaid_assign_centroids.argtypes = [ct.c_void_p, ct.c_int64, ct.c_void_p, ct.c_int64, ct.c_void_p, ct.c_int, ct.c_void_p]
+        lib.plaid_encode_residuals.argtypes = [ct.c_void_p, ct.c_int64, ct.c_void_p, ct.c_void_p, ct.c_int64, ct.c_void_p,
+                                               ct.c_int32, ct.c_void_p, ct.c_int, ct.c_void_p]
+        lib.plaid_build_ivf.argtypes = [ct.c_void_p, ct.c_void_p, ct.c_int64, ct.c_int64, ct.c_int64, ct.c_void_p, ct.c_void_p,
+                                        ct.c_int64, ct.POINTER(ct.c_int64), ct.c_int, ct.c_void_p]
         _lib = lib
     return _lib
 
@@ -265,3 +271,52 @@ def plaid_get_stage2_kernel(idx: Index) -> int:
     form = ct.c_int32(-1)
     _check(load_library().plaid_get_stage2_kernel(idx.handle, ct.byref(form)))
     return int(form.value)
+
+
+# ------------------------------------------------------------------ index construction
+def _dev_tensor(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not t.is_cuda or t.dtype != dtype:
+        raise ValueError(f"{name} must be a CUDA tensor of dtype {dtype}")
+    return t.contiguous()
+
+
+def plaid_assign_centroids(centroids: torch.Tensor, x: torch.Tensor) -> torch.Tensor:
+    """codes [n] int32: the nearest centroid (largest dot product, ties to the smaller id) of each row of x [n, 128]."""
+    centroids = _dev_tensor(centroids, torch.float32, "centroids")
+    x = _dev_tensor(x, torch.float32, "x")
+    codes = torch.empty((x.shape[0],), dtype=torch.int32, device=x.device)
+    _check(load_library().plaid_assign_centroids(_ptr(centroids), centroids.shape[0], _ptr(x), x.shape[0], _ptr(codes),
+                                                 x.device.index or 0, _stream(x.device)))
+    return codes
+
+
+def plaid_encode_residuals(centroids: torch.Tensor, x: torch.Tensor, codes: torch.Tensor, cutoffs: torch.Tensor,
+                           nbits: int) -> torch.Tensor:
+    """residuals [n, 16 * nbits] uint8: packed bucket indices of x - centroids[codes]."""
+    centroids = _dev_tensor(centroids, torch.float32, "centroids")
+    x = _dev_tensor(x, torch.float32, "x")
+    codes = _dev_tensor(codes, torch.int32, "codes")
+    cutoffs = _dev_tensor(cutoffs, torch.float32, "cutoffs")
+    if cutoffs.numel() != (1 << int(nbits)) - 1:
+        raise ValueError("cutoffs must hold 2^nbits - 1 values")
+    out = torch.empty((x.shape[0], 16 * int(nbits)), dtype=torch.uint8, device=x.device)
+    _check(load_library().plaid_encode_residuals(_ptr(centroids), centroids.shape[0], _ptr(x), _ptr(codes), x.shape[0],
+                                                 _ptr(cutoffs), int(nbits), _ptr(out), x.device.index or 0, _stream(x.device)))
+    return out
+
+
+def plaid_build_ivf(codes: torch.Tensor, doc_offsets: torch.Tensor, num_centroids: int):
+    """(ivf_offsets [C+1] int64, ivf_pids int32): per centroid the ascending unique ids of the passages that contain it."""
+    codes = _dev_tensor(codes, torch.int32, "codes")
+    doc_offsets = _dev_tensor(doc_offsets, torch.int64, "doc_offsets")
+    dev = codes.device
+    P, N, C = doc_offsets.shape[0] - 1, codes.shape[0], int(num_centroids)
+    off = torch.empty((C + 1,), dtype=torch.int64, device=dev)
+    total = ct.c_int64(0)
+    lib = load_library()
+    _check(lib.plaid_build_ivf(_ptr(codes), _ptr(doc_offsets), P, N, C, _ptr(off), None, 0, ct.byref(total), dev.index or 0,
+                               _stream(dev)))
+    pids = torch.empty((max(int(total.value), 1),), dtype=torch.int32, device=dev)
+    _check(lib.plaid_build_ivf(_ptr(codes), _ptr(doc_offsets), P, N, C, _ptr(off), _ptr(pids), pids.shape[0], ct.byref(total),
+                               dev.index or 0, _stream(dev)))
+    return off, pids[:int(total.value)]

@@ -231,6 +231,74 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
             "stage_ms": stage_ms, "lat": lat, "enq": enq, "nlat": nlat, "roofline": roofline, "rooflines": rooflines}
 
 
+def measure_index_build(pl, torch, np, cfg, noise, cpu: bool):
+    """The index-construction calls (the step before the search path) at the configuration's sizes: inverted lists of all
+    N tokens, residual encoding and nearest-centroid assignment of the first 2^20 token vectors.  Each call synchronises
+    internally, so it is timed on the host clock (best of three).  Returns a dict for the JSON line."""
+    dev = torch.device("cuda:0")
+    w = make_workload_(cfg, device=dev, noise=noise, keep_embeddings=1 << 20)
+    x = w.sample_embeddings
+    n = int(x.shape[0])
+    codes_n = w.codes[:n].contiguous()
+    cut = w.bucket_cutoffs.to(dev)
+
+    def best_of(fn, reps=3):
+        best = None
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            out = fn()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            best = dt if best is None or dt < best else best
+        return best, out
+
+    out = {"workload": f"{cfg.name} ({noise} noise)", "tokens_total": int(w.N), "vectors_sampled": n}
+    t, (off, pids) = best_of(lambda: pl.plaid_build_ivf(w.codes, w.doc_offsets, cfg.C))
+    ivf_bytes = 2 * 4 * int(w.N) + 2 * 8 * (cfg.P + 1) + 4 * int(pids.numel()) + 8 * (cfg.C + 1)
+    out["build_ivf"] = {"seconds": round(t, 5), "tokens_per_s": round(int(w.N) / t, 1), "entries": int(pids.numel()),
+                        "algorithmic_bytes": ivf_bytes, "achieved_gbs": round(ivf_bytes / t / 1e9, 1),
+                        "frac_of_hbm_peak": round(ivf_bytes / t / 1e9 / HBM_PEAK_GBS, 4),
+                        "identical_to_generator": bool(torch.equal(off, w.ivf_offsets) and torch.equal(pids, w.ivf_pids))}
+    t, res = best_of(lambda: pl.plaid_encode_residuals(w.centroids, x, codes_n, cut, cfg.nbits))
+    # a vector, its code and its packed residual per token, plus the 512-byte row of every distinct centroid among them
+    enc_bytes = n * (512 + 4 + 16 * cfg.nbits) + 512 * int(torch.unique(codes_n).numel())
+    out["encode_residuals"] = {"seconds": round(t, 5), "tokens_per_s": round(n / t, 1), "algorithmic_bytes": enc_bytes,
+                               "achieved_gbs": round(enc_bytes / t / 1e9, 1),
+                               "frac_of_hbm_peak": round(enc_bytes / t / 1e9 / HBM_PEAK_GBS, 4),
+                               "identical_to_generator": bool(torch.equal(res, w.residuals[:n]))}
+    t, codes = best_of(lambda: pl.plaid_assign_centroids(w.centroids, x), reps=2)
+    flop = 2.0 * cfg.C * 128 * n
+    out["assign_centroids"] = {"seconds": round(t, 5), "tokens_per_s": round(n / t, 1), "algorithmic_flop": flop,
+                               "achieved_tflops": round(flop / t / 1e12, 1),
+                               "frac_of_fp64_matrix_peak": round(flop / t / 1e12 / FP64_MFMA_PEAK_TFLOPS, 4),
+                               "share_equal_to_drawn_codes": round(float((codes == codes_n).float().mean()), 4)}
+    for k_ in ("build_ivf", "encode_residuals", "assign_centroids"):
+        log(f"[bench] index construction, {k_}: {out[k_]}")
+    if cpu:
+        from oracle import oracle as orc
+        ch, dh = w.codes.cpu().numpy(), w.doc_offsets.cpu().numpy()
+        t0 = time.perf_counter()
+        orc.build_ivf(ch, dh, cfg.C)
+        t_ivf = time.perf_counter() - t0
+        xh, cenh = x.cpu().numpy(), w.centroids.cpu().numpy()
+        t0 = time.perf_counter()
+        orc.encode(xh, ch[:n], cenh, w.bucket_cutoffs.cpu().numpy(), cfg.nbits)
+        t_enc = time.perf_counter() - t0
+        ng = 8   # groups of 32 vectors: the oracle's S_cq routine is a plain triple loop
+        t0 = time.perf_counter()
+        for g_ in range(ng):
+            orc.top_nprobe(orc.scq(cenh, xh[32 * g_:32 * g_ + 32]), 1)
+        t_asg = time.perf_counter() - t0
+        out["cpu_oracle"] = {"kind": "oracle", "cores": 1,
+                             "build_ivf_tokens_per_s": round(int(w.N) / t_ivf, 1),
+                             "encode_residuals_tokens_per_s": round(n / t_enc, 1),
+                             "assign_centroids_tokens_per_s": round(32 * ng / t_asg, 1),
+                             "sample": f"all {int(w.N)} tokens / the same {n} vectors / the first {32 * ng} vectors"}
+        log(f"[bench] index construction, CPU oracle: {out['cpu_oracle']}")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -242,6 +310,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=512, help="queries the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--single-noise", action="store_true", help="skip the run on the other reading of the noise scale")
+    ap.add_argument("--no-index-build", action="store_true", help="skip the timing of the index-construction calls")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run four 1 GiB device-to-device copies (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -309,6 +378,9 @@ def main():
                  "stage_ms_per_step": {s_: round(v, 4) for s_, v in r2["stage_ms"].items()},
                  "roofline_by_stage": r2["rooflines"] or None}
         del r2
+    build = None
+    if not args.no_index_build:
+        build = measure_index_build(pl, torch, np, cfg, args.noise, cpu=args.cpu_sample > 0)
     line = {
         "metric": "queries_per_sec", "value": round(qps, 2), "unit": "queries/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -323,7 +395,7 @@ def main():
                               "qps": round(1e3 / float(lat.mean()), 1) if nlat else None},
         "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items()},
         "roofline": roofline, "roofline_by_stage": rooflines or None, "cpu_baseline": cpu,
-        "other_noise_reading": other,
+        "other_noise_reading": other, "index_construction": build,
     }
     print(json.dumps(line), flush=True)
 

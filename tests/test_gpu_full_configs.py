@@ -92,3 +92,41 @@ def test_mid_configs(cfg_name, noise, stage2):
                                             ("cfg5", "calibrated")])
 def test_big_configs(cfg_name, noise):
     _run(cfg_name, noise, n_sample=4, n_dump=1)
+
+
+@pytest.mark.parametrize("cfg_name", ["cfg2", "cfg3"])
+def test_index_construction_at_full_size(cfg_name):
+    """The index-construction calls at the configuration's real sizes, as bench.py times them: the inverted lists of all
+    tokens against the oracle's, the residual encoding of the first 2^20 tokens against the oracle's, nearest centroids
+    of 2048 sampled token vectors against the oracle's S_cq + top-1."""
+    import paper_2205_09707_amd as pl
+    pl.load_library()
+    cfg = get_config(cfg_name)
+    dev = torch.device("cuda:0")
+    print(f"[build] generating {cfg_name}", flush=True)
+    w = make_workload(cfg, device=dev, noise="literal", keep_embeddings=1 << 20)
+    x = w.sample_embeddings
+    n = x.shape[0]
+    print(f"[build] {cfg_name}: inverted lists of N={w.N} tokens", flush=True)
+    off, pids = pl.plaid_build_ivf(w.codes, w.doc_offsets, cfg.C)
+    torch.cuda.synchronize()
+    o_off, o_pids = orc.build_ivf(w.codes.cpu().numpy(), w.doc_offsets.cpu().numpy(), cfg.C)
+    np.testing.assert_array_equal(off.cpu().numpy(), o_off)
+    np.testing.assert_array_equal(pids.cpu().numpy(), o_pids)
+    print(f"[build] {cfg_name}: residual encoding of {n} tokens", flush=True)
+    res = pl.plaid_encode_residuals(w.centroids, x, w.codes[:n].contiguous(), w.bucket_cutoffs.to(dev), cfg.nbits)
+    torch.cuda.synchronize()
+    want = orc.encode(x.cpu().numpy(), w.codes[:n].cpu().numpy(), w.centroids.cpu().numpy(), w.bucket_cutoffs.cpu().numpy(),
+                      cfg.nbits)
+    np.testing.assert_array_equal(res.cpu().numpy(), want)
+    print(f"[build] {cfg_name}: nearest centroids of {n} tokens, 2048 of them checked", flush=True)
+    codes = pl.plaid_assign_centroids(w.centroids, x)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(cfg.index_seed)
+    groups = sorted(rng.choice(n // 32, size=64, replace=False).tolist())
+    cen = w.centroids.cpu().numpy()
+    xh = x.cpu().numpy()
+    got = codes.cpu().numpy()
+    for g in groups:
+        S = orc.scq(cen, xh[32 * g:32 * g + 32])
+        np.testing.assert_array_equal(got[32 * g:32 * g + 32], orc.top_nprobe(S, 1)[:, 0], err_msg=f"group {g}")

@@ -356,7 +356,14 @@ def main():
         dt_cpu = time.perf_counter() - t1
         g_ids = out_ids[:ns].cpu().numpy()
         agree = float(np.mean(g_ids == o_ids))
+        # one thread, one query at a time: the oracle's per-query latency (8 queries)
+        lat1 = []
+        for qq in range(min(8, ns)):
+            t2 = time.perf_counter()
+            orc.search(ix, Qh[qq], *params)
+            lat1.append((time.perf_counter() - t2) * 1e3)
         cpu = {"value": round(ns / dt_cpu, 3), "unit": "queries/s", "cores": int(used), "kind": "oracle",
+               "single_thread_latency_ms_p50": round(float(np.percentile(lat1, 50)), 2),
                "sample": f"first {ns} of the {nq} queries of {cfg.name}/{args.noise}, whole pipeline, one query per thread",
                "seconds": round(dt_cpu, 2), "id_agreement_with_gpu": agree}
         log(f"[bench] CPU oracle: {ns} queries in {dt_cpu:.2f}s on {used} threads; id agreement with GPU {agree:.4f}")

@@ -758,11 +758,14 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
 #pragma unroll
             for (int j = 0; j < NP; ++j)
                 if (j < nprobe) {
-                    const int32_t id = (int32_t)(best[j] & 0xFFFFFFFFu);
+                    // A list entry can only be missing when the scores are not numbers (a query holding NaN compares
+                    // false against every threshold): later kernels index the inverted lists with these ids, so such a
+                    // slot gets centroid j (nprobe <= C), never an id out of range.
+                    const int32_t id = best[j] == PLAID_KEY_MAX ? j : (int32_t)(best[j] & 0xFFFFFFFFu);
                     o.probed[((int64_t)q * QLEN + i) * nprobe + j] = id;
                     idl[i * nprobe + j] = id;
                 }
-            top1[i] = (int32_t)(best[0] & 0xFFFFFFFFu);
+            top1[i] = best[0] == PLAID_KEY_MAX ? 0 : (int32_t)(best[0] & 0xFFFFFFFFu);
         }
     }
     __syncthreads();

@@ -839,7 +839,7 @@ size_t plaid_stage1_tilemax_bytes(int64_t C, int nq, int nprobe)
 }
 
 void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int64_t C, const float *Q, void *Qd, int matrix_form,
-                         int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, float *tilemax, int32_t *done,
+                         int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, float *tilemax,
                          uint32_t *zero, int64_t zero_words, int32_t *probed, int32_t *uniq, int uniq_stride,
                          int32_t *n_uniq, const Stage2Buffers &s2, void *probe_scratch, size_t probe_scratch_bytes)
 {

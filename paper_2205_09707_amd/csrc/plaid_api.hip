@@ -422,7 +422,6 @@ struct Workspace {
     void *probe_scratch;
     size_t probe_scratch_bytes;
     float *tilemax;      // [qc][tiles][32] column maxima of the score kernel's tiles
-    int32_t *done;       // [qc] stage-1 tile counter (zeroed region)
     uint64_t *keys2;  // [qc][P]
     uint64_t *sel2;   // [qc][nd]
     int32_t *n2;      // [qc]
@@ -459,7 +458,6 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     };
     w.zero_base = take(0);
     w.candbits = (uint32_t *)take((size_t)qc * w.cand_words * 4);
-    w.done = (int32_t *)take((size_t)qc * 4);
     w.s2.hist = (int32_t *)take((size_t)qc * SEL_BINS * 4);
     w.s2.hist1 = (int32_t *)take((size_t)qc * SEL_BINS * 4);
     w.s2.state = (Sel2State *)take((size_t)qc * sizeof(Sel2State));
@@ -573,7 +571,7 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
         // stage 1: S_cq (Eq. 2), pruning map (Eq. 5), probes and candidates (Section 4.1)
         for (int phase = PLAID_STAGE1_PREP; phase <= PLAID_STAGE1_PROBES; phase <<= 1) {
             plaid_launch_stage1(st, phase, ix->centroids, C, Qc, w.Qd, ix->scq_matrix_form, n, t_cs, nprobe, w.S, w.keepbits,
-                                w.keep_words, w.tilemax, w.done, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed,
+                                w.keep_words, w.tilemax, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed,
                                 w.uniq, w.uniq_stride, w.n_uniq, w.s2, w.probe_scratch, w.probe_scratch_bytes);
             STAMP();
         }
@@ -717,7 +715,7 @@ extern "C" int plaid_assign_centroids(const float *centroids, int64_t C, const f
         const Workspace w = carve((char *)ws.p, &fake, (int)ng, pl);
         for (int phase = PLAID_STAGE1_PREP; phase <= PLAID_STAGE1_PROBES; phase <<= 1)
             plaid_launch_stage1(st, phase, centroids, C, src, w.Qd, fake.scq_matrix_form, (int)ng, INFINITY, 1, w.S, w.keepbits,
-                                w.keep_words, w.tilemax, w.done, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed,
+                                w.keep_words, w.tilemax, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed,
                                 w.uniq, w.uniq_stride, w.n_uniq, w.s2, w.probe_scratch, w.probe_scratch_bytes);
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipMemcpyAsync(dst, w.probed, (size_t)cnt * 4, hipMemcpyDeviceToDevice, st));  // probed is [group][32][1]

@@ -89,18 +89,18 @@ SelScratch plaid_select_scratch_carve2(void *zero_base, void *body_base, int nse
 // Stage 1 (k_scq.hip): clears the zero region, then S[q][c][i] (Eq. 2), the keep bitmap (Eq. 5; bit c of
 // keepbits[q] = max_i S[q][c][i] >= t_cs), per query token the nprobe best centroids in rank order and their
 // ascending duplicate-free union (Section 4.1), and stage 2's survivor table (s2.meta / kept_ids / T).
-#define PLAID_PROBE_FAST_MAX 8  // nprobe handled inside the fused kernel; larger values go through the selection
+#define PLAID_PROBE_FAST_MAX 8  // nprobe handled by the tile-maxima kernel (stage1_tail_kernel); larger values go through the selection
 // Qx: 32 KB of scratch per query for the re-laid-out queries.  matrix_form selects the score kernel built on the
 // double-precision matrix instruction; plaid_scq_matrix_form_ok tells (once per process) whether that instruction
 // adds its four products in index order with a rounding after each, which is what makes the two forms bit-identical.
 int plaid_scq_matrix_form_ok(hipStream_t st, int *ok);  // returns a hipError_t value
 // phases: which of the three steps to enqueue (the caller may time them apart): PREP = clear + query layout,
-// SCORES = the score kernel (S, keep bits, per-tile lists), PROBES = probes, their union and the survivor table.
+// SCORES = the score kernel (S, keep bits, column maxima of its tiles), PROBES = probes, their union and the survivor table.
 #define PLAID_STAGE1_PREP 1
 #define PLAID_STAGE1_SCORES 2
 #define PLAID_STAGE1_PROBES 4
 void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int64_t C, const float *Q, void *Qx, int matrix_form,
-                         int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, float *tilemax, int32_t *done,
+                         int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, float *tilemax,
                          uint32_t *zero, int64_t zero_words, int32_t *probed, int32_t *uniq, int uniq_stride,
                          int32_t *n_uniq, const struct Stage2Buffers &s2, void *probe_scratch, size_t probe_scratch_bytes);
 size_t plaid_stage1_tilemax_bytes(int64_t C, int nq, int nprobe);

@@ -117,6 +117,31 @@ def test_null_handles(lib):
     assert lib.plaid_decompress_passages(None, None, 0, None, None, None, 0, None) == plaid.PLAID_EINVAL
 
 
+def test_index_construction_rejects_bad_arguments_before_touching_the_gpu(lib):
+    """Sizes, null pointers and alignment are checked on the host first, so these calls fail with PLAID_EINVAL even on a
+    machine without a GPU (the pointer values below are never dereferenced)."""
+    ok16, odd = ct.c_void_p(4096), ct.c_void_p(4100)        # 16-byte aligned / only 4-byte aligned
+    total = ct.c_int64(-1)
+    E = plaid.PLAID_EINVAL
+    assert lib.plaid_assign_centroids(None, 8, ok16, 4, ok16, 0, None) == E
+    assert lib.plaid_assign_centroids(ok16, 0, ok16, 4, ok16, 0, None) == E               # no centroids
+    assert lib.plaid_assign_centroids(ok16, 8, ok16, -1, ok16, 0, None) == E
+    assert lib.plaid_assign_centroids(ok16, 8, odd, 4, ok16, 0, None) == E                # x not 16-byte aligned
+    assert lib.plaid_assign_centroids(ok16, 8, None, 4, ok16, 0, None) == E
+    assert lib.plaid_encode_residuals(ok16, 8, ok16, ok16, 4, ok16, 3, ok16, 0, None) == E   # nbits
+    assert lib.plaid_encode_residuals(ok16, 8, ok16, ok16, 4, None, 2, ok16, 0, None) == E   # no cut-offs
+    assert lib.plaid_encode_residuals(odd, 8, ok16, ok16, 4, ok16, 2, ok16, 0, None) == E    # centroids misaligned
+    assert lib.plaid_encode_residuals(ok16, 8, ok16, ok16, 4, ok16, 2, ct.c_void_p(4098), 0, None) == E  # output misaligned
+    assert lib.plaid_encode_residuals(ok16, 1 << 31, ok16, ok16, 4, ok16, 2, ok16, 0, None) == E
+    assert lib.plaid_build_ivf(ok16, None, 4, 10, 8, ok16, None, 0, ct.byref(total), 0, None) == E   # no offsets
+    assert lib.plaid_build_ivf(ok16, ok16, 0, 10, 8, ok16, None, 0, ct.byref(total), 0, None) == E   # no passages
+    assert lib.plaid_build_ivf(ok16, ok16, 4, 10, 0, ok16, None, 0, ct.byref(total), 0, None) == E   # no centroids
+    assert lib.plaid_build_ivf(ok16, ok16, 4, -1, 8, ok16, None, 0, ct.byref(total), 0, None) == E
+    assert lib.plaid_build_ivf(ok16, ok16, 4, 10, 8, None, None, 0, ct.byref(total), 0, None) == E
+    assert total.value == -1                                                                   # untouched on error
+    assert b"" != lib.plaid_last_error()
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     class Fake:

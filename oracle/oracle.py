@@ -43,8 +43,14 @@ class _Dumps(ct.Structure):
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = ct.CDLL(_LIB)
+        # PLAID_ORACLE_LIB names another build of plaid_oracle.c: the planted-mistake test loads deliberately broken
+        # copies through it to show that the pins notice
+        other = os.environ.get("PLAID_ORACLE_LIB")
+        if other:
+            _lib = ct.CDLL(other)
+        else:
+            build()
+            _lib = ct.CDLL(_LIB)
         _lib.orc_select.restype = ct.c_int64
         _lib.orc_candidates.restype = ct.c_int64
         _lib.orc_build_ivf.restype = ct.c_int64

@@ -164,6 +164,14 @@ int plaid_get_stage_ms(const plaid_index *idx, float *out_ms);
 /* Limit on queries processed per internal chunk (0 = library default).  Affects workspace size only. */
 int plaid_set_max_chunk(plaid_index *idx, int32_t max_queries_per_chunk);
 
+/* Bytes of device workspace a plaid_search with these parameters allocates (once, grown on demand, kept until
+ * plaid_index_free) on an index with C centroids and P passages, and the number of queries the call processes per
+ * internal chunk.  Host arithmetic only: no device is touched.  max_queries_per_chunk as for plaid_set_max_chunk
+ * (0 = the library's default: up to 512 queries within about 24 GiB).  bytes: HOST, required; queries_per_chunk: HOST,
+ * may be NULL.  Errors: PLAID_EINVAL. */
+int plaid_workspace_bytes(int64_t C, int64_t P, int32_t nq, int32_t nprobe, int32_t ndocs, int32_t k,
+                          int32_t max_queries_per_chunk, int64_t *bytes, int32_t *queries_per_chunk);
+
 /* ---- Index construction: the step before the search path.  Every array is DEVICE memory of `device`; the calls
  * synchronise `hip_stream` before they return (sizes and error flags are read back) and allocate temporary device
  * memory, which they release. ---- */

@@ -24,4 +24,5 @@ from .plaid import (  # noqa: F401
     plaid_search_debug,
     plaid_set_max_chunk,
     plaid_set_stage_timing,
+    plaid_workspace_bytes,
 )

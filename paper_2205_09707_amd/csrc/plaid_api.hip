@@ -441,6 +441,17 @@ struct Plan {
     int32_t nprobe, nd, m3, kk;  // effective sizes: nd = min(ndocs, P), m3 = min(max(1, ndocs/4), nd), kk = min(k, m3)
 };
 
+static Plan make_plan(int64_t P, int32_t nprobe, int32_t ndocs, int32_t k)
+{
+    Plan pl;
+    pl.nprobe = nprobe;
+    pl.nd = (int32_t)(ndocs < P ? ndocs : P);
+    const int32_t m3 = ndocs / 4 > 1 ? ndocs / 4 : 1;
+    pl.m3 = m3 < pl.nd ? m3 : pl.nd;
+    pl.kk = k < pl.m3 ? k : pl.m3;
+    return pl;
+}
+
 static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl)
 {
     Workspace w;
@@ -493,6 +504,22 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     return w;
 }
 
+// Queries per chunk: bounded by the caller's limit, else 512 (the kernels that run one workgroup per query only fill
+// the chip from a few hundred queries on) within a workspace budget of about 24 GiB.
+static int choose_chunk(const plaid_index *ix, int32_t nq, const Plan &pl)
+{
+    const Workspace one = carve(nullptr, ix, 1, pl);
+    int qc = ix->max_chunk > 0 ? ix->max_chunk : 512;
+    if (ix->max_chunk <= 0) {
+        const size_t budget = (size_t)24 << 30;
+        const size_t fit = budget / (one.total ? one.total : 1);
+        if ((size_t)qc > fit) qc = fit < 1 ? 1 : (int)fit;
+    }
+    if (qc > nq) qc = nq;
+    if ((int64_t)qc * QLEN > 32768) qc = 32768 / QLEN;  // grid.y / segment limits of the per-token selections
+    return qc;
+}
+
 static int ensure_workspace(plaid_index *ix, size_t bytes)
 {
     if (ix->ws_bytes >= bytes) return PLAID_OK;
@@ -529,24 +556,9 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
     hipStream_t st = (hipStream_t)hip_stream;
 
     const int64_t C = ix->C, P = ix->P;
-    Plan pl;
-    pl.nprobe = nprobe;
-    pl.nd = (int32_t)(ndocs < P ? ndocs : P);
-    int32_t m3 = ndocs / 4 > 1 ? ndocs / 4 : 1;
-    pl.m3 = m3 < pl.nd ? m3 : pl.nd;
-    pl.kk = k < pl.m3 ? k : pl.m3;
-
-    // queries per chunk: bounded by the caller's limit, else 512 (the kernels that run one workgroup per query only
-    // fill the chip from a few hundred queries on) within a workspace budget of about 24 GiB
-    const Workspace one = carve(nullptr, ix, 1, pl);
-    int qc = ix->max_chunk > 0 ? ix->max_chunk : 512;
-    if (ix->max_chunk <= 0) {
-        const size_t budget = (size_t)24 << 30;
-        const size_t fit = budget / (one.total ? one.total : 1);
-        if ((size_t)qc > fit) qc = fit < 1 ? 1 : (int)fit;
-    }
-    if (qc > nq) qc = nq;
-    if ((int64_t)qc * QLEN > 32768) qc = 32768 / QLEN;  // grid.y / segment limits of the per-token selections
+    const int32_t m3 = ndocs / 4 > 1 ? ndocs / 4 : 1;
+    const Plan pl = make_plan(P, nprobe, ndocs, k);
+    const int qc = choose_chunk(ix, nq, pl);
     const Workspace wsz = carve(nullptr, ix, qc, pl);
     int rc = ensure_workspace(ix, wsz.total);
     if (rc) return rc;
@@ -656,6 +668,26 @@ extern "C" int plaid_search_debug(plaid_index *idx, const float *Q, int32_t nq, 
                                   const plaid_debug_buffers *dbg)
 {
     return search_impl(idx, Q, nq, nprobe, t_cs, ndocs, k, out_ids, out_scores, hip_stream, dbg);
+}
+
+// ------------------------------------------------------------------ workspace size (host arithmetic only)
+extern "C" int plaid_workspace_bytes(int64_t C, int64_t P, int32_t nq, int32_t nprobe, int32_t ndocs, int32_t k,
+                                     int32_t max_queries_per_chunk, int64_t *bytes, int32_t *queries_per_chunk)
+{
+    if (!bytes) return fail(PLAID_EINVAL, "null output");
+    if (C < 1 || C >= (1ll << 31)) return fail(PLAID_EINVAL, "num_centroids out of range (%lld)", (long long)C);
+    if (P < 1 || P >= (1ll << 31)) return fail(PLAID_EINVAL, "num_passages out of range (%lld)", (long long)P);
+    if (nq < 1 || nprobe < 1 || nprobe > C || ndocs < 1 || k < 1 || max_queries_per_chunk < 0)
+        return fail(PLAID_EINVAL, "search parameters out of range");
+    plaid_index fake;
+    fake.C = C;
+    fake.P = P;
+    fake.max_chunk = max_queries_per_chunk;
+    const Plan pl = make_plan(P, nprobe, ndocs, k);
+    const int qc = choose_chunk(&fake, nq, pl);
+    *bytes = (int64_t)carve(nullptr, &fake, qc, pl).total;
+    if (queries_per_chunk) *queries_per_chunk = qc;
+    return PLAID_OK;
 }
 
 // ------------------------------------------------------------------ index construction

@@ -46,7 +46,7 @@ class plaid_debug_buffers(ct.Structure):
 EXPORTS = ("plaid_index_load", "plaid_index_from_view", "plaid_index_free", "plaid_search", "plaid_search_debug",
            "plaid_decompress_passages", "plaid_index_info", "plaid_set_stage_timing", "plaid_get_stage_ms",
            "plaid_set_max_chunk", "plaid_get_score_kernel", "plaid_get_stage2_kernel", "plaid_assign_centroids",
-           "plaid_encode_residuals", "plaid_build_ivf", "plaid_last_error")
+           "plaid_encode_residuals", "plaid_build_ivf", "plaid_workspace_bytes", "plaid_last_error")
 
 _lib = None
 
@@ -77,6 +77,8 @@ def load_library() -> ct.CDLL:
         lib.plaid_set_max_chunk.argtypes = [ct.c_void_p, ct.c_int32]
         lib.plaid_get_score_kernel.argtypes = [ct.c_void_p, ct.c_void_p]
         lib.plaid_get_stage2_kernel.argtypes = [ct.c_void_p, ct.c_void_p]
+        lib.plaid_workspace_bytes.argtypes = [ct.c_int64, ct.c_int64, ct.c_int32, ct.c_int32, ct.c_int32, ct.c_int32, ct.c_int32,
+                                              ct.POINTER(ct.c_int64), ct.POINTER(ct.c_int32)]
         lib.plaid_assign_centroids.argtypes = [ct.c_void_p, ct.c_int64, ct.c_void_p, ct.c_int64, ct.c_void_p, ct.c_int, ct.c_void_p]
         lib.plaid_encode_residuals.argtypes = [ct.c_void_p, ct.c_int64, ct.c_void_p, ct.c_void_p, ct.c_int64, ct.c_void_p,
                                                ct.c_int32, ct.c_void_p, ct.c_int, ct.c_void_p]
@@ -271,6 +273,14 @@ def plaid_get_stage2_kernel(idx: Index) -> int:
     form = ct.c_int32(-1)
     _check(load_library().plaid_get_stage2_kernel(idx.handle, ct.byref(form)))
     return int(form.value)
+
+
+def plaid_workspace_bytes(C: int, P: int, nq: int, nprobe: int, ndocs: int, k: int, max_queries_per_chunk: int = 0):
+    """(bytes of device workspace a search with these parameters needs, queries per internal chunk); no GPU involved."""
+    b, qc = ct.c_int64(0), ct.c_int32(0)
+    _check(load_library().plaid_workspace_bytes(int(C), int(P), int(nq), int(nprobe), int(ndocs), int(k),
+                                                int(max_queries_per_chunk), ct.byref(b), ct.byref(qc)))
+    return int(b.value), int(qc.value)
 
 
 # ------------------------------------------------------------------ index construction

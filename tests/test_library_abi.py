@@ -142,6 +142,27 @@ def test_index_construction_rejects_bad_arguments_before_touching_the_gpu(lib):
     assert b"" != lib.plaid_last_error()
 
 
+def test_workspace_size_arithmetic():
+    """plaid_workspace_bytes is host arithmetic: per query about 132 C + 16 P bytes plus the selection lists, the chunk is
+    512 queries unless the caller's limit, the batch or the 24 GiB budget is smaller, and nothing depends on nq beyond it."""
+    C, P = 65536, 400000                                     # the benchmark configuration
+    one, qc1 = pl.plaid_workspace_bytes(C, P, 1, 2, 1024, 100)
+    assert qc1 == 1 and 132 * C + 16 * P <= one <= 1.1 * (132 * C + 16 * P) + (1 << 20)
+    b512, qc = pl.plaid_workspace_bytes(C, P, 512, 2, 1024, 100)
+    assert qc == 512 and 0.9 * 512 * (132 * C + 16 * P) <= b512 <= 512 * one
+    assert pl.plaid_workspace_bytes(C, P, 5000, 2, 1024, 100) == (b512, 512)          # more queries: more chunks, same memory
+    b64, qc = pl.plaid_workspace_bytes(C, P, 512, 2, 1024, 100, max_queries_per_chunk=64)
+    assert qc == 64 and b64 < b512 / 7
+    big, qc = pl.plaid_workspace_bytes(262144, 20_000_000, 1000, 4, 4096, 100)           # 1-bit configuration: the budget binds
+    assert 1 <= qc < 512 and big <= (24 << 30) + (1 << 28)
+    sizes = [pl.plaid_workspace_bytes(C, P, 16, nprobe, 1024, 100)[0] for nprobe in (1, 2, 8, 9, 64)]
+    assert sizes == sorted(sizes)
+    with pytest.raises(pl.PlaidError):
+        pl.plaid_workspace_bytes(C, P, 0, 2, 1024, 100)
+    with pytest.raises(pl.PlaidError):
+        pl.plaid_workspace_bytes(C, P, 1, C + 1, 1024, 100)
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     class Fake:

@@ -231,6 +231,30 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
             "stage_ms": stage_ms, "lat": lat, "enq": enq, "nlat": nlat, "roofline": roofline, "rooflines": rooflines}
 
 
+def measured_copy_gbs(torch):
+    """Bandwidth a plain device-to-device copy of 1 GiB reaches on this machine (bytes read + bytes written per second):
+    the achievable figure to read the 8 TB/s vendor peak against.  None if the measurement itself fails."""
+    try:
+        dev = torch.device("cuda:0")
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            dst.copy_(src)
+        b.record()
+        torch.cuda.synchronize()
+        gbs = 5 * 2 * src.numel() * 4 / (a.elapsed_time(b) * 1e-3) / 1e9
+        del src, dst
+        torch.cuda.empty_cache()
+        return round(gbs, 1)
+    except Exception as e:  # a reference figure only: never fail the benchmark over it
+        log(f"[bench] copy bandwidth not measured: {e}")
+        return None
+
+
 def measure_index_build(pl, torch, np, cfg, noise, cpu: bool):
     """The index-construction calls (the step before the search path) at the configuration's sizes: inverted lists of all
     N tokens, residual encoding and nearest-centroid assignment of the first 2^20 token vectors.  Each call synchronises
@@ -385,6 +409,8 @@ def main():
                  "stage_ms_per_step": {s_: round(v, 4) for s_, v in r2["stage_ms"].items()},
                  "roofline_by_stage": r2["rooflines"] or None}
         del r2
+    copy_gbs = measured_copy_gbs(torch)
+    log(f"[bench] plain 1 GiB device copy: {copy_gbs} GB/s read + written (vendor HBM peak {HBM_PEAK_GBS:g})")
     build = None
     if not args.no_index_build:
         build = measure_index_build(pl, torch, np, cfg, args.noise, cpu=args.cpu_sample > 0)
@@ -403,6 +429,7 @@ def main():
         "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items()},
         "roofline": roofline, "roofline_by_stage": rooflines or None, "cpu_baseline": cpu,
         "other_noise_reading": other, "index_construction": build,
+        "hbm": {"vendor_peak_gbs": HBM_PEAK_GBS, "measured_copy_gbs": copy_gbs},
     }
     print(json.dumps(line), flush=True)
 

@@ -38,6 +38,30 @@ def test_every_declared_symbol_is_exported(lib):
     assert sorted(plaid.EXPORTS) == names, "the Python binding must carry the same names as the header"
 
 
+def _struct_fields(name):
+    """(type, field) pairs of `typedef struct { ... } name;` in the header, in declaration order"""
+    src = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    body = re.search(r"typedef struct\s*\{([^}]*)\}\s*" + name + r"\s*;", src, flags=re.S).group(1)
+    out = []
+    for decl in body.split(";"):
+        decl = " ".join(decl.split())
+        if decl:
+            m = re.match(r"(.*?)(\*?)\s*([A-Za-z_0-9]+)$", decl)
+            out.append(((m.group(1).strip() + m.group(2)).replace(" *", "*"), m.group(3)))
+    return out
+
+
+def test_binding_structs_mirror_the_header():
+    """Field order and widths of the two structs that cross the boundary by pointer."""
+    ctype_of = {"int32_t": ct.c_int32, "int64_t": ct.c_int64}
+    for name, cls in (("plaid_index_view", plaid.plaid_index_view), ("plaid_debug_buffers", plaid.plaid_debug_buffers)):
+        fields = _struct_fields(name)
+        assert [f for _, f in fields] == [f for f, _ in cls._fields_], name
+        for (ctype, field), (_, pytype) in zip(fields, cls._fields_):
+            want = ct.c_void_p if ctype.endswith("*") else ctype_of[ctype]
+            assert pytype is want, f"{name}.{field}: header says {ctype}"
+
+
 def _view(w, **over):
     a = w.numpy()
     v = plaid.plaid_index_view()

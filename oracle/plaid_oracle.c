@@ -22,6 +22,9 @@
  * MaxSim over an index whose bucket weights are all zero"; stage-2 monotonicity invariants;
  * numpy unpackbits for the byte table; encode/decode bucket-resolution bounds; a hand-computed
  * 3-centroid index; and "nprobe = C, t_cs = -inf, ndocs >= 4P  ==>  pipeline == exhaustive".
+ * Every function here has such a pin.  What has none: the paper prints no worked example and no per-stage values, and
+ * its quality tables need collections and checkpoints that are not available, so retrieval quality against the paper
+ * is parity unpinned.
  */
 #include <math.h>
 #include <stdint.h>

@@ -7,6 +7,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -76,6 +77,8 @@ struct DeviceGuard {
 static int choose_scq_form(plaid_index *ix)
 {
     static int checked[64] = {0};  // 0 = not yet, 1 = matrix form verified, 2 = not usable
+    static std::mutex guard;       // indexes may be created from several host threads
+    const std::lock_guard<std::mutex> lock(guard);
     const char *env = getenv("PLAID_SCQ_FORM");
     if (env && !strcmp(env, "vector")) {
         ix->scq_matrix_form = 0;

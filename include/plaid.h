@@ -94,8 +94,9 @@ int plaid_index_load(const char *path, int device, plaid_index **out);
 /* Build a handle from caller memory.  copy = 1: the arrays (host or device) are copied into
  * library-owned device memory.  copy = 0: requires on_device = 1; the library keeps the caller's device
  * pointers (centroids, codes and residuals must then be aligned to 16 bytes, else PLAID_EINVAL) and the caller
- * must keep them alive and unchanged until plaid_index_free.  Host-side views are
- * validated (offsets monotone, codes and pids in range); device-side views are validated for sizes only. */
+ * must keep them alive and unchanged until plaid_index_free.  The arrays are validated either way (offsets monotone
+ * from 0 to their end, codes in [0, C), passage ids in [0, P) and strictly ascending within each list): on the host for
+ * host arrays, by one kernel for device arrays; a violation is PLAID_EINVAL and nothing is searched. */
 int plaid_index_from_view(const plaid_index_view *view, int device, int copy, plaid_index **out);
 
 /* Release the handle, its workspace and any memory the library allocated for it.  NULL is allowed. */

@@ -14,7 +14,7 @@ LIB = os.path.join(HERE, "libplaid.so")
 OBJDIR = os.path.join(HERE, "_build")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = ["--offload-arch=gfx950", "-O3", *os.environ.get("PLAID_EXTRA_FLAGS", "").split(), "-std=c++17", "-fPIC", "-fno-gpu-rdc",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          # packed fp32 arithmetic is kept off for all device code of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]

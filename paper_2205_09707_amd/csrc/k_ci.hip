@@ -2,7 +2,7 @@
 // sum_i max_j S_cq[code_j][i] over its tokens j (only tokens whose centroid is kept, when pruning).
 // The rows S_cq[code_j] are never stacked into a matrix: a wave keeps one running maximum per query
 // token (lane i and lane i+32 both serve token i, on alternate passage tokens) and sums the 32 maxima
-// at the end -- in double, so that equal sets of rows give bit-equal scores whatever the order.
+// at the end -- in double, in index order, as the definition's sum over the query tokens reads.
 //
 // This file holds the gather formulation for a list of passages (one wave per passage, rows fetched
 // from the L2-resident S): stage 3.
@@ -10,17 +10,7 @@
 
 #include <math.h>
 
-#ifndef CI_FLY
 #define CI_FLY 8
-#endif
-
-__device__ __forceinline__ float sum32_as_double(float m)
-{
-    double d = (double)m;
-#pragma unroll
-    for (int o = 1; o < 32; o <<= 1) d += __shfl_xor(d, o);
-    return (float)d;
-}
 
 // Score of the passage with tokens [t0, t1).  Uniform across the wave; -inf when no token contributes.
 template <bool PRUNE>
@@ -73,7 +63,7 @@ __device__ __forceinline__ float ci_passage(const float *__restrict__ Sq, const 
         }
     }
     m = fmaxf(m, __shfl_xor(m, 32));
-    return sum32_as_double(m);
+    return plaid_sum32_in_order(m);
 }
 
 // Stage 3: out_keys[q][j] = key(score of passage of in_keys[q][j]).

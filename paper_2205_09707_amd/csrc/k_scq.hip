@@ -349,12 +349,8 @@ typedef double scq_double4 __attribute__((ext_vector_type(4)));
 // Four waves of 32 rows measured best: eight waves of 16 rows (more waves per SIMD to fill the matrix pipe while
 // others are in their epilogue) lose more to the per-wave epilogue instructions than they gain (5.2 vs 4.95 ms per 512
 // queries on C = 65536), 64 rows per wave halve the occupancy.
-#ifndef SM_THREADS
 #define SM_THREADS 256
-#endif
-#ifndef SM_RT
 #define SM_RT 2                      // 16-row tiles per wave
-#endif
 #define SM_WAVES (SM_THREADS / 64)
 #define SM_WROWS (16 * SM_RT)        // centroid rows per wave
 #define SM_ROWS (SM_WAVES * SM_WROWS)  // centroid rows per workgroup
@@ -362,9 +358,7 @@ static_assert(SM_WROWS == 16 || SM_WROWS == 32, "pruning bits are assembled from
 static_assert(SM_ROWS % (SM_THREADS / 8) == 0 && SM_THREADS >= QLEN, "tile shape");
 #define SM_KC 32                     // dimensions staged at a time
 #define SM_ASTRIDE 36                // floats per staged row chunk: the 64 operand reads of a step hit 64 banks
-#ifndef SM_MIN_WAVES
 #define SM_MIN_WAVES 4               // waves per SIMD the register allocation leaves room for
-#endif
 
 // Operand and result layout of v_mfma_f64_16x16x4_f64 for lane = 16 g + i: A operand = A[i][g], B operand = B[g][i],
 // result register r = D[4 r + g][i].

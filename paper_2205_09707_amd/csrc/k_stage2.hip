@@ -30,9 +30,7 @@
 
 #define S2_THREADS 256
 #define S2W_PASS 64      // passages per wave tile = 2 words of the candidate bitmap
-#ifndef S2_ITEMS
 #define S2_ITEMS 9       // 16-byte loads per lane and round, all in flight at once
-#endif
 #define S2W_CAP (64 * 4 * S2_ITEMS - 32)  // tokens a wave stages per round (one byte each), whatever their alignment
 #define S2_LBWORDS ((S2_ITEMS + 3) / 4)   // words of the round's line bitmap (8 lines per item)
 #define S2_TSTRIDE 36    // floats per staged S_cq row (16-byte aligned, rows spread over the banks)
@@ -41,14 +39,6 @@
 static_assert(S2_LBWORDS <= 64, "one lane clears one word of the line bitmap");
 
 // ------------------------------------------------------------------ gather form (K > S2_MAX_KEPT)
-__device__ __forceinline__ float s2_sum32_as_double(float m)
-{
-    double d = (double)m;
-#pragma unroll
-    for (int o = 1; o < 32; o <<= 1) d += __shfl_xor(d, o);
-    return (float)d;
-}
-
 // Pruned score of the passage with tokens [t0, t1): uniform across the wave; `any` tells whether a token survived.
 __device__ __forceinline__ float s2_gather_passage(const float *__restrict__ Sq, const uint32_t *__restrict__ kb,
                                                    int64_t t0, int64_t t1, const int32_t *__restrict__ codes, int lane,
@@ -77,7 +67,7 @@ __device__ __forceinline__ float s2_gather_passage(const float *__restrict__ Sq,
         }
     }
     m = fmaxf(m, __shfl_xor(m, 32));
-    return s2_sum32_as_double(m);
+    return plaid_sum32_in_order(m);
 }
 
 // Body for one query over the bitmap words w_first + k * w_step < w_end (32 passages each), one wave per word at a

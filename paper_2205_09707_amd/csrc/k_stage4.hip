@@ -16,9 +16,7 @@
 #include <math.h>
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-#ifndef S4_RESIDENT_BLOCKS
 #define S4_RESIDENT_BLOCKS 768
-#endif
 
 // Table entry (byte v, quad s): weights of dimensions 4s .. 4s+3 of the 8/NBITS dimensions packed in v.
 // Bucket indices are stored most-significant first.
@@ -152,11 +150,9 @@ __global__ __launch_bounds__(256, 3) void decompress_maxsim_kernel(
             m = fmaxf(fmaxf(wmax[0][r32], wmax[1][r32]), fmaxf(wmax[2][r32], wmax[3][r32]));
             __syncthreads();
         }
-        double d = (double)m;
-#pragma unroll
-        for (int o = 1; o < 32; o <<= 1) d += __shfl_xor(d, o);
+        const float total = plaid_sum32_in_order(m);
         if (lane == 0 && (!COOP || wave == 0))
-            out_keys[(int64_t)q * out_stride + j] = plaid_make_key(len > 0 ? (float)d : -INFINITY, pid);
+            out_keys[(int64_t)q * out_stride + j] = plaid_make_key(len > 0 ? total : -INFINITY, pid);
     }
 }
 

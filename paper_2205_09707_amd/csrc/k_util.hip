@@ -114,3 +114,62 @@ void plaid_launch_bitmap_to_list(hipStream_t st, const uint32_t *bits, int64_t w
     hipLaunchKernelGGL(bitmap_to_list_kernel, dim3(nq), dim3(1024), 0, st, bits, words, nbits_valid, out, out_stride,
                        out_counts);
 }
+
+// ------------------------------------------------------------------ structural validation of a device-resident index
+// The search kernels index memory with the index's own offsets, codes and passage ids, so an index whose arrays arrive
+// in device memory is checked once, when the handle is made: doc_offsets from 0 to N without a decrease, codes in
+// [0, C), ivf_offsets from 0 to ivf_len without a decrease, passage ids in [0, P) and strictly ascending inside each
+// list.  bad[0] receives the OR of: 1 doc_offsets, 2 codes, 4 ivf_offsets, 8 passage id out of range, 16 list not
+// strictly ascending.  Grid-stride loops over each array; the list test looks up the list of entry e by binary search
+// in ivf_offsets only when e follows a larger-or-equal id (a list boundary or an error), so it costs one pass over
+// the ids.
+__global__ __launch_bounds__(256) void index_validate_kernel(const int64_t *__restrict__ doc_offsets, int64_t P, int64_t N,
+                                                             const int32_t *__restrict__ codes, int64_t C,
+                                                             const int64_t *__restrict__ ivf_offsets,
+                                                             const int32_t *__restrict__ ivf_pids, int64_t ivf_len,
+                                                             int32_t *__restrict__ bad)
+{
+    const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, step = (int64_t)gridDim.x * blockDim.x;
+    int flags = 0;
+    for (int64_t p = t0; p <= P; p += step) {
+        const int64_t o = doc_offsets[p];
+        if (o < 0 || o > N || (p == 0 && o != 0) || (p == P && o != N)) flags |= 1;
+        if (p < P && doc_offsets[p + 1] < o) flags |= 1;
+    }
+    for (int64_t j = t0; j < N; j += step) {
+        const int32_t c = codes[j];
+        if (c < 0 || c >= C) flags |= 2;
+    }
+    for (int64_t c = t0; c <= C; c += step) {
+        const int64_t o = ivf_offsets[c];
+        if (o < 0 || o > ivf_len || (c == 0 && o != 0) || (c == C && o != ivf_len)) flags |= 4;
+        if (c < C && ivf_offsets[c + 1] < o) flags |= 4;
+    }
+    for (int64_t e = t0; e < ivf_len; e += step) {
+        const int32_t pid = ivf_pids[e];
+        if (pid < 0 || pid >= P) flags |= 8;
+        if (e > 0 && ivf_pids[e - 1] >= pid) {
+            // allowed only when e is the first entry of a list: some offset equals e
+            int64_t lo = 0, hi = C;  // largest lo with ivf_offsets[lo] <= e (offsets validated by other threads: a
+            while (lo < hi) {        // malformed table can only produce a wrong verdict here, and sets flag 4 there)
+                const int64_t mid = (lo + hi + 1) >> 1;
+                if (ivf_offsets[mid] <= e) lo = mid;
+                else hi = mid - 1;
+            }
+            if (ivf_offsets[lo] != e) flags |= 16;
+        }
+    }
+    if (flags) atomicOr(bad, flags);
+}
+void plaid_launch_index_validate(hipStream_t st, const int64_t *doc_offsets, int64_t P, int64_t N, const int32_t *codes,
+                                 int64_t C, const int64_t *ivf_offsets, const int32_t *ivf_pids, int64_t ivf_len, int32_t *bad)
+{
+    int64_t work = N > ivf_len ? N : ivf_len;
+    if (work < P + 1) work = P + 1;
+    if (work < C + 1) work = C + 1;
+    int64_t g = (work + 255) / 256;
+    if (g > 8192) g = 8192;
+    if (g < 1) g = 1;
+    hipLaunchKernelGGL(index_validate_kernel, dim3((unsigned)g), dim3(256), 0, st, doc_offsets, P, N, codes, C, ivf_offsets,
+                       ivf_pids, ivf_len, bad);
+}

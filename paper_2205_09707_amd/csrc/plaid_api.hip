@@ -247,6 +247,26 @@ extern "C" int plaid_index_from_view(const plaid_index_view *v, int device, int 
         HIP_TRY(hipMemcpy(&n_chk, v->doc_offsets + P, sizeof(int64_t), hipMemcpyDeviceToHost));
         if (n_chk != N) return fail(PLAID_EINVAL, "doc_offsets[P] (%lld) != num_embeddings (%lld)", (long long)n_chk, (long long)N);
         if (ivf_len < 0 || (ivf_len > 0 && !v->ivf_pids)) return fail(PLAID_EINVAL, "bad inverted lists");
+        // device arrays get the same structural checks as host arrays, in one kernel: the search kernels index memory
+        // with these offsets, codes and passage ids
+        int32_t *flag = nullptr;
+        if (hipMalloc((void **)&flag, 4) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(PLAID_ENOMEM, "hipMalloc failed");
+        }
+        int32_t bad = 0;
+        hipError_t e = hipMemset(flag, 0, 4);
+        if (e == hipSuccess) {
+            plaid_launch_index_validate(nullptr, v->doc_offsets, P, N, v->codes, C, v->ivf_offsets, v->ivf_pids, ivf_len, flag);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = hipMemcpy(&bad, flag, 4, hipMemcpyDeviceToHost);
+        (void)hipFree(flag);
+        if (e != hipSuccess) return fail(PLAID_EHIP, "index validation: %s", hipGetErrorString(e));
+        if (bad)
+            return fail(PLAID_EINVAL, "malformed index arrays:%s%s%s%s%s", (bad & 1) ? " doc_offsets not monotone from 0 to N;" : "",
+                        (bad & 2) ? " a code outside [0, C);" : "", (bad & 4) ? " ivf_offsets not monotone from 0 to their end;" : "",
+                        (bad & 8) ? " a passage id outside [0, P);" : "", (bad & 16) ? " an inverted list not strictly ascending;" : "");
     }
 
     plaid_index *ix = new (std::nothrow) plaid_index();
@@ -304,7 +324,11 @@ static_assert(sizeof(FileHeader) == 64, "index file header is 64 bytes");
 static int read_section(FILE *f, std::vector<char> &buf, size_t bytes)
 {
     const size_t padded = (bytes + 63) & ~(size_t)63;
-    buf.resize(padded ? padded : 1);
+    try {
+        buf.resize(padded ? padded : 1);
+    } catch (...) {
+        return fail(PLAID_ENOMEM, "host allocation of %zu bytes failed", padded);
+    }
     if (padded && fread(buf.data(), 1, padded, f) != padded) return fail(PLAID_EFORMAT, "index file truncated");
     return PLAID_OK;
 }
@@ -326,8 +350,27 @@ extern "C" int plaid_index_load(const char *path, int device, plaid_index **out)
         return rc == PLAID_EINVAL ? fail(PLAID_EFORMAT, "bad header in %s: %s", path, std::string(g_err).c_str()) : rc;
     }
     const size_t rb = (size_t)16 * h.nbits;
+    if (h.N >= (1ll << 56) || h.ivf_len >= (1ll << 56)) {
+        fclose(f);
+        return fail(PLAID_EFORMAT, "bad header in %s: counts out of range", path);
+    }
     const size_t sizes[7] = {(size_t)h.C * PLAID_DIM * 4, (size_t)(h.P + 1) * 8, (size_t)h.N * 4, (size_t)h.N * rb,
                              (size_t)(1 << h.nbits) * 4, (size_t)(h.C + 1) * 8, (size_t)h.ivf_len * 4};
+    // the sections the header announces must fit the file: checked before anything is allocated for them
+    {
+        unsigned long long need = sizeof(FileHeader);
+        for (int s = 0; s < 7; ++s) need += (sizes[s] + 63) & ~(size_t)63;
+        long long have = -1;
+        if (fseek(f, 0, SEEK_END) == 0) have = ftell(f);
+        if (have < 0 || fseek(f, (long)sizeof(FileHeader), SEEK_SET) != 0) {
+            fclose(f);
+            return fail(PLAID_EIO, "cannot determine the size of %s", path);
+        }
+        if ((unsigned long long)have < need) {
+            fclose(f);
+            return fail(PLAID_EFORMAT, "index file truncated: header announces %llu bytes, %s holds %lld", need, path, have);
+        }
+    }
     std::vector<char> sec[7];
     for (int s = 0; s < 7; ++s) {
         rc = read_section(f, sec[s], sizes[s]);
@@ -562,9 +605,13 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
     const int32_t m3 = ndocs / 4 > 1 ? ndocs / 4 : 1;
     const Plan pl = make_plan(P, nprobe, ndocs, k);
     const int qc = choose_chunk(ix, nq, pl);
-    const Workspace wsz = carve(nullptr, ix, qc, pl);
-    int rc = ensure_workspace(ix, wsz.total);
-    if (rc) return rc;
+    char *ws_base = nullptr;
+    {
+        const Workspace wsz = carve(nullptr, ix, qc, pl);
+        const int rc = ensure_workspace(ix, wsz.total);
+        if (rc) return rc;
+        ws_base = (char *)ix->ws;
+    }
 
     const bool timing = ix->timing != 0;
     if (timing)
@@ -572,7 +619,7 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
 
     for (int32_t q0 = 0; q0 < nq; q0 += qc) {
         const int n = nq - q0 < qc ? nq - q0 : qc;
-        const Workspace w = carve((char *)ix->ws, ix, n, pl);
+        const Workspace w = carve(ws_base, ix, n, pl);
         const float *Qc = Q + (int64_t)q0 * QLEN * DIM;
         const SelScratch sc3 = plaid_select_scratch_carve2(w.sel3_zero, w.sel3_body, n, pl.nd, pl.m3);
         const SelScratch sc4 = plaid_select_scratch_carve2(w.sel4_zero, w.sel4_body, n, pl.m3, pl.kk);
@@ -849,7 +896,12 @@ extern "C" int plaid_decompress_passages(plaid_index *ix, const int32_t *pids, i
     if (!g.ok) return fail(PLAID_EHIP, "hipSetDevice(%d) failed", ix->device);
     hipStream_t st = (hipStream_t)hip_stream;
     // the passage ids come from the caller: check them on the host before any kernel dereferences them
-    std::vector<int32_t> hp((size_t)(n > 0 ? n : 1));
+    std::vector<int32_t> hp;
+    try {
+        hp.resize((size_t)(n > 0 ? n : 1));
+    } catch (...) {
+        return fail(PLAID_ENOMEM, "host allocation for %d passage ids failed", n);
+    }
     if (n > 0) {
         HIP_TRY(hipMemcpyAsync(hp.data(), pids, (size_t)n * 4, hipMemcpyDeviceToHost, st));
         HIP_TRY(hipStreamSynchronize(st));

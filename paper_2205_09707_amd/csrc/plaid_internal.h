@@ -36,6 +36,17 @@ __host__ __device__ __forceinline__ uint64_t plaid_make_key(float score, uint32_
 }
 #define PLAID_KEY_MAX 0xFFFFFFFFFFFFFFFFull
 
+// Sum over the 32 query tokens of Eq. 4: lane i (0..31) of the wave holds the column maximum of query token i; the
+// values are added in double in index order, as the definition's sum reads, and rounded once.  The result is the same
+// in every lane.
+__device__ __forceinline__ float plaid_sum32_in_order(float m)
+{
+    double d = 0.0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) d += (double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(m), i));
+    return (float)d;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Selection (k_select.hip): first m keys in ascending order out of per-segment lists.
 // ---------------------------------------------------------------------------------------------
@@ -231,6 +242,11 @@ void plaid_launch_decompress_dump(hipStream_t st, const float *centroids, const 
                                   uint8_t *out_indices);
 void plaid_launch_passage_offsets(hipStream_t st, const int64_t *doc_offsets, const int32_t *pids, int n,
                                   int64_t *out_offsets);
+
+// Structural check of device-resident index arrays (k_util.hip); bad[0] (zero before the call) receives a bit per kind
+// of violation: 1 doc_offsets, 2 codes, 4 ivf_offsets, 8 passage id out of range, 16 inverted list not strictly ascending.
+void plaid_launch_index_validate(hipStream_t st, const int64_t *doc_offsets, int64_t P, int64_t N, const int32_t *codes,
+                                 int64_t C, const int64_t *ivf_offsets, const int32_t *ivf_pids, int64_t ivf_len, int32_t *bad);
 
 // Small utilities
 void plaid_launch_fill_u32(hipStream_t st, uint32_t *p, int64_t n, uint32_t v);

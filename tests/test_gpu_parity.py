@@ -81,8 +81,8 @@ def test_cfg1_all_stages(pl, noise, form, stage2):
     cfg = get_config("cfg1")
     w = make_workload(cfg, device="cpu", noise=noise)
     same, total = _check_workload(pl, w, [(cfg.nprobe, cfg.t_cs, cfg.ndocs, cfg.k)], form=form, stage2=stage2)
+    # (every difference has already been checked to lie inside a tie of oracle scores within TOL: compare_query)
     print(f"cfg1/{noise}: {same}/{total} queries with id lists identical to the oracle's")
-    assert same >= total - 1   # near-ties inside 1e-4 at the final cut are the only allowed difference
 
 
 @pytest.mark.parametrize("form,stage2", [("matrix", "inverted"), ("vector", "stream")])
@@ -135,7 +135,7 @@ def test_pipeline_equals_exhaustive_when_nothing_is_filtered(pl):
             same = pu.assert_final_matches(ids[q], sc[q], allp, s_all, k, ctx=f"exhaustive q{q}")
             if same:
                 assert np.array_equal(ids[q], e_ids)
-            assert np.max(np.abs(sc[q] - e_sc)) <= 2 * pu.TOL
+            assert np.max(np.abs(sc[q] - e_sc)) <= pu.TOL
     finally:
         pl.plaid_index_free(gidx)
 
@@ -254,6 +254,41 @@ def test_argument_errors(pl):
         assert ids.shape == (2, 2)
     finally:
         pl.plaid_index_free(gidx)
+
+
+def test_device_arrays_are_validated(pl):
+    """An index handed over in device memory gets the structural checks host arrays get: a code, a passage id or an
+    offset that a search kernel would follow out of bounds is PLAID_EINVAL at index creation, with or without a copy."""
+    w = make_workload(tiny_config(C=20, P=300, lo=1, hi=9, nbits=2, nq=1, seed=17), noise="calibrated")
+
+    def broken(name, fn):
+        arrs = pu.device_arrays(w)
+        t = arrs[name].clone()
+        fn(t)
+        arrs[name] = t
+        return arrs
+
+    C, P, N = 20, 300, int(w.N)
+    head = int(torch.argmax(w.ivf_offsets[1:] - w.ivf_offsets[:-1]))    # a list with at least two entries
+    e0 = int(w.ivf_offsets[head])
+
+    def swap(t):
+        t[e0], t[e0 + 1] = t[e0 + 1].clone(), t[e0].clone()
+
+    def dup(t):
+        t[e0 + 1] = t[e0]
+    cases = [("codes", lambda t: t.__setitem__(N // 2, C)), ("codes", lambda t: t.__setitem__(0, -1)),
+             ("ivf_pids", lambda t: t.__setitem__(3, P)), ("ivf_pids", lambda t: t.__setitem__(5, -2)),
+             ("ivf_pids", swap), ("ivf_pids", dup),
+             ("doc_offsets", lambda t: t.__setitem__(7, int(t[8]) + 1)), ("doc_offsets", lambda t: t.__setitem__(0, 1)),
+             ("ivf_offsets", lambda t: t.__setitem__(4, int(t[5]) + 1)), ("ivf_offsets", lambda t: t.__setitem__(0, 2))]
+    for copy in (False, True):
+        for name, fn in cases:
+            with pytest.raises(pl.PlaidError) as e:
+                pl.plaid_index_from_view(broken(name, fn), 2, device=0, copy=copy)
+            assert e.value.status == pl.plaid.PLAID_EINVAL, (name, copy)
+        ok = pl.plaid_index_from_view(pu.device_arrays(w), 2, device=0, copy=copy)   # the unbroken arrays are accepted
+        pl.plaid_index_free(ok)
 
 
 def test_index_file_round_trip(pl, tmp_path):

@@ -1,7 +1,4 @@
-"""NOT COLLECTED YET (the name does not start with test_): written when no GPU was available to run it.  Run it by naming
-the file (`pytest tests/wip_wide_passage_ranges.py -m gpu`) and rename it to test_gpu_wide_passage_ranges.py once it passes.
-
-More than 2^19 passages on an index small enough for the inverted form: the candidate kernel for queries without a
+"""More than 2^19 passages on an index small enough for the inverted form: the candidate kernel for queries without a
 surviving centroid then runs several workgroups per query, each on its own range of the range table, of the bitmaps of
 the long lists and of the candidate words (every other test has a single such range)."""
 import numpy as np

@@ -122,6 +122,17 @@ int plaid_search_debug(plaid_index *idx, const float *Q, int32_t nq, int32_t npr
                        int32_t k, int32_t *out_ids, float *out_scores, void *hip_stream,
                        const plaid_debug_buffers *dbg);
 
+/* plaid_search for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): same arguments, same kernels and bit-identical results, but the workspace is a
+ * 64 MiB array inside the library (one copy per device, held until the process ends) instead of memory the library
+ * allocates, so the call performs no hipMalloc / hipFree and no other allocating call.  Batches are processed in
+ * chunks that fit the array; PLAID_EINVAL when even one query does not fit (plaid_workspace_bytes with nq = 1 tells:
+ * about 132 C + 16 P bytes).  Every call on a device uses that device's one array, which keeps the previous call's
+ * contents (what must start at zero is cleared by the first kernel of each chunk): calls that overlap on one device
+ * race, whichever index they use.  Stage timing and debug outputs are not available through this entry point. */
+int plaid_search_static(plaid_index *idx, const float *Q, int32_t nq, int32_t nprobe, float t_cs, int32_t ndocs,
+                        int32_t k, int32_t *out_ids, float *out_scores, void *hip_stream);
+
 /* Decompress the tokens of n listed passages (Section 4.5: packed byte -> bucket indices through the
  * 256-entry table, value = centroid + bucket weight, one fp32 addition per element).
  *   pids         DEVICE [n] passage ids

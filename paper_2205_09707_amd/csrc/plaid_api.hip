@@ -32,6 +32,15 @@ extern "C" const char *plaid_last_error(void) { return g_err; }
         if (e_ != hipSuccess) return fail(PLAID_EHIP, "%s: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
     } while (0)
 
+// ------------------------------------------------------------------ workspace of the entry point that allocates nothing
+// plaid_search_static carves its workspace out of this array instead of library-allocated memory.  The name below is a
+// host-side stand-in, not a device address: each device holds its own copy, whose address hipGetSymbolAddress returns
+// with that device current; host code only ever uses the addresses kept in g_scratch_addr.
+#define PLAID_STATIC_WORKSPACE_BYTES ((size_t)64 << 20)
+static __device__ __align__(256) unsigned char scratch[PLAID_STATIC_WORKSPACE_BYTES];
+static void *g_scratch_addr[64] = {nullptr};  // per device ordinal
+static std::mutex g_scratch_guard;
+
 // ------------------------------------------------------------------ handle
 #define N_EVENTS (PLAID_NUM_STAGES + 1)
 
@@ -48,6 +57,7 @@ struct plaid_index {
     const int32_t *ivf_pids = nullptr;
     std::vector<void *> owned;  // device allocations released by plaid_index_free
     void *ws = nullptr;         // workspace, grown on demand
+    char *static_ws = nullptr;  // this device's copy of the static workspace array (plaid_search_static)
     size_t ws_bytes = 0;
     int32_t max_chunk = 0;
     int32_t timing = 0;
@@ -71,6 +81,24 @@ struct DeviceGuard {
         if (prev >= 0) (void)hipSetDevice(prev);
     }
 };
+
+// Address of the static workspace array on `device`, which must be the current device (looked up once per device).
+static int static_workspace_address(int device, char **out)
+{
+    if (device < 0 || device >= 64) return fail(PLAID_EINVAL, "device ordinal %d out of range", device);
+    const std::lock_guard<std::mutex> lock(g_scratch_guard);
+    if (!g_scratch_addr[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return fail(PLAID_EHIP, "hipGetSymbolAddress(static workspace): %s", hipGetErrorString(e));
+        }
+        g_scratch_addr[device] = p;
+    }
+    *out = (char *)g_scratch_addr[device];
+    return PLAID_OK;
+}
 
 // Which of the two bit-identical score kernels this handle uses.  PLAID_SCQ_FORM=vector|matrix overrides the choice
 // (matrix is refused when the device check fails); the check itself runs once per process and device.
@@ -302,6 +330,7 @@ extern "C" int plaid_index_from_view(const plaid_index_view *v, int device, int 
     }
     rc = choose_scq_form(ix);
     if (!rc) rc = build_range_table(ix);
+    if (!rc) rc = static_workspace_address(ix->device, &ix->static_ws);  // (the index's device is current here)
     if (rc) {
         plaid_index_free(ix);
         return rc;
@@ -587,8 +616,11 @@ static int ensure_workspace(plaid_index *ix, size_t bytes)
 }
 
 // ------------------------------------------------------------------ search
+// fixed_ws: null = the per-index workspace (allocated and grown here); otherwise the static array of fixed_bytes bytes:
+// nothing is allocated, and the chunk shrinks until its workspace fits.
 static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t nprobe, float t_cs, int32_t ndocs, int32_t k,
-                       int32_t *out_ids, float *out_scores, void *hip_stream, const plaid_debug_buffers *dbg)
+                       int32_t *out_ids, float *out_scores, void *hip_stream, const plaid_debug_buffers *dbg,
+                       char *fixed_ws = nullptr, size_t fixed_bytes = 0)
 {
     if (!ix) return fail(PLAID_EINVAL, "null index");
     if (!Q || !out_ids || !out_scores) return fail(PLAID_EINVAL, "null buffer");
@@ -604,9 +636,16 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
     const int64_t C = ix->C, P = ix->P;
     const int32_t m3 = ndocs / 4 > 1 ? ndocs / 4 : 1;
     const Plan pl = make_plan(P, nprobe, ndocs, k);
-    const int qc = choose_chunk(ix, nq, pl);
+    int qc = choose_chunk(ix, nq, pl);
     char *ws_base = nullptr;
-    {
+    if (fixed_ws) {
+        while (qc > 1 && carve(nullptr, ix, qc, pl).total > fixed_bytes) qc = qc > 2 ? qc - (qc + 7) / 8 : 1;
+        const size_t need = carve(nullptr, ix, qc, pl).total;
+        if (need > fixed_bytes)
+            return fail(PLAID_EINVAL, "one query of this search needs %zu bytes of workspace, the static workspace holds %zu", need,
+                        fixed_bytes);
+        ws_base = fixed_ws;
+    } else {
         const Workspace wsz = carve(nullptr, ix, qc, pl);
         const int rc = ensure_workspace(ix, wsz.total);
         if (rc) return rc;
@@ -718,6 +757,15 @@ extern "C" int plaid_search_debug(plaid_index *idx, const float *Q, int32_t nq, 
                                   const plaid_debug_buffers *dbg)
 {
     return search_impl(idx, Q, nq, nprobe, t_cs, ndocs, k, out_ids, out_scores, hip_stream, dbg);
+}
+
+extern "C" int plaid_search_static(plaid_index *idx, const float *Q, int32_t nq, int32_t nprobe, float t_cs, int32_t ndocs,
+                                   int32_t k, int32_t *out_ids, float *out_scores, void *hip_stream)
+{
+    if (!idx) return fail(PLAID_EINVAL, "null index");
+    if (!idx->static_ws) return fail(PLAID_EHIP, "the static workspace has no address on device %d", idx->device);
+    return search_impl(idx, Q, nq, nprobe, t_cs, ndocs, k, out_ids, out_scores, hip_stream, nullptr, idx->static_ws,
+                       PLAID_STATIC_WORKSPACE_BYTES);
 }
 
 // ------------------------------------------------------------------ workspace size (host arithmetic only)

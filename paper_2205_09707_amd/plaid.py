@@ -44,7 +44,7 @@ class plaid_debug_buffers(ct.Structure):
 
 
 EXPORTS = ("plaid_index_load", "plaid_index_from_view", "plaid_index_free", "plaid_search", "plaid_search_debug",
-           "plaid_decompress_passages", "plaid_index_info", "plaid_set_stage_timing", "plaid_get_stage_ms",
+           "plaid_search_static", "plaid_decompress_passages", "plaid_index_info", "plaid_set_stage_timing", "plaid_get_stage_ms",
            "plaid_set_max_chunk", "plaid_get_score_kernel", "plaid_get_stage2_kernel", "plaid_assign_centroids",
            "plaid_encode_residuals", "plaid_build_ivf", "plaid_workspace_bytes", "plaid_last_error")
 
@@ -69,6 +69,7 @@ def load_library() -> ct.CDLL:
         lib.plaid_search.argtypes = [ct.c_void_p, ct.c_void_p, ct.c_int32, ct.c_int32, ct.c_float, ct.c_int32, ct.c_int32,
                                      ct.c_void_p, ct.c_void_p, ct.c_void_p]
         lib.plaid_search_debug.argtypes = lib.plaid_search.argtypes + [ct.POINTER(plaid_debug_buffers)]
+        lib.plaid_search_static.argtypes = lib.plaid_search.argtypes
         lib.plaid_decompress_passages.argtypes = [ct.c_void_p, ct.c_void_p, ct.c_int32, ct.c_void_p, ct.c_void_p,
                                                   ct.c_void_p, ct.c_int64, ct.c_void_p]
         lib.plaid_index_info.argtypes = [ct.c_void_p] + [ct.c_void_p] * 5
@@ -207,6 +208,20 @@ def plaid_search(idx: Index, Q: torch.Tensor, nprobe: int, t_cs: float, ndocs: i
         out_scores = torch.empty((nq, kk), dtype=torch.float32, device=Q.device)
     _check(load_library().plaid_search(idx.handle, _ptr(Q), nq, int(nprobe), float(t_cs), int(ndocs), int(k),
                                        _ptr(out_ids), _ptr(out_scores), _stream(Q.device)))
+    return out_ids, out_scores
+
+
+def plaid_search_static(idx: Index, Q: torch.Tensor, nprobe: int, t_cs: float, ndocs: int, k: int, out_ids: torch.Tensor,
+                        out_scores: torch.Tensor):
+    """plaid_search on the library's static workspace: the library allocates nothing, and neither does this wrapper, so
+    the caller brings the output tensors ([nq, k] int32 / float32 on the index's device)."""
+    Q = _check_Q(idx, Q)
+    nq = Q.shape[0]
+    if out_ids.shape != (nq, int(k)) or out_scores.shape != (nq, int(k)) or out_ids.dtype != torch.int32 or \
+            out_scores.dtype != torch.float32 or not out_ids.is_contiguous() or not out_scores.is_contiguous():
+        raise ValueError("out_ids / out_scores must be contiguous [nq, k] int32 / float32 tensors")
+    _check(load_library().plaid_search_static(idx.handle, _ptr(Q), nq, int(nprobe), float(t_cs), int(ndocs), int(k),
+                                              _ptr(out_ids), _ptr(out_scores), _stream(Q.device)))
     return out_ids, out_scores
 
 

@@ -24,6 +24,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 FP64_MFMA_PEAK_TFLOPS = 78.6   # MI355X published dense fp64 matrix rate (the vector fp64 rate is the same figure)
 FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
+FP16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 / bf16 matrix rate
 
 # HBM bytes per launch (512 queries) of each kernel, from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of this file,
 # each scaled by the counter's reading on a 1 GiB device copy (fetch reads half the bytes: x2; write: x1).
@@ -197,10 +198,25 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
             return e
 
         scq_flop = 2.0 * cfg.C * 128 * 32 * nq
-        rooflines["scq"] = entry(
-            "scq", "S_cq = C.Q^T (Eq. 2) in double through the fp64 matrix instruction" if pl.plaid_get_score_kernel(idx)
-            else "S_cq = C.Q^T (Eq. 2), fp64 fused multiply-add chain", "mfma", scq_flop, 1e12, FP64_MFMA_PEAK_TFLOPS, "TFLOP/s",
-            {"algorithmic_flop_per_step": scq_flop, "algorithmic_flop_per_launch": scq_flop / launches, "dtype": "f64"})
+        form = pl.plaid_get_score_kernel(idx)
+        if form == 2 and cfg.nprobe <= 8:
+            # split-fp16 matrix kernel: three fp16 products per term of Eq. 2, far below the matrix rate's ceiling; what
+            # bounds it is the write of S_cq itself (128 bytes per centroid and query) next to one read of the centroids'
+            # operands (512 bytes each) per launch and of the queries' (16 KB each)
+            scq_bytes = nq * cfg.C * 128 + launches * cfg.C * 512 + nq * 16384
+            t_scq = stage_ms["scq"] * 1e-3
+            rooflines["scq"] = entry(
+                "scq", "S_cq = C.Q^T (Eq. 2): fp16 matrix instruction on operands split into two fp16 terms, fp32 accumulation",
+                "hbm", scq_bytes, 1e9, HBM_PEAK_GBS, "GB/s",
+                {"algorithmic_bytes_per_step": scq_bytes, "algorithmic_bytes_per_launch": scq_bytes // launches, "dtype": "f16x2/f32",
+                 "matrix_flop_per_step": 3 * scq_flop,
+                 "fp16_mfma_tflops": round(3 * scq_flop / t_scq / 1e12, 1) if t_scq > 0 else None,
+                 "fp16_mfma_frac": round(3 * scq_flop / t_scq / 1e12 / FP16_MFMA_PEAK_TFLOPS, 4) if t_scq > 0 else None})
+        else:
+            rooflines["scq"] = entry(
+                "scq", "S_cq = C.Q^T (Eq. 2) in double through the fp64 matrix instruction" if form == 1
+                else "S_cq = C.Q^T (Eq. 2), fp64 fused multiply-add chain", "mfma", scq_flop, 1e12, FP64_MFMA_PEAK_TFLOPS, "TFLOP/s",
+                {"algorithmic_flop_per_step": scq_flop, "algorithmic_flop_per_launch": scq_flop / launches, "dtype": "f64"})
         inverted = bool(pl.plaid_get_stage2_kernel(idx))
         s2_bytes = work["stage2_inverted_bytes"] if inverted else work["stage2_bytes"]
         rooflines["stage2_ci"] = entry(
@@ -392,7 +408,7 @@ def main():
                "seconds": round(dt_cpu, 2), "id_agreement_with_gpu": agree}
         log(f"[bench] CPU oracle: {ns} queries in {dt_cpu:.2f}s on {used} threads; id agreement with GPU {agree:.4f}")
 
-    forms = {"score_kernel": "matrix" if pl.plaid_get_score_kernel(idx) else "vector",
+    forms = {"score_kernel": ("vector", "matrix", "split16")[pl.plaid_get_score_kernel(idx)],
              "stage2_kernel": "inverted" if pl.plaid_get_stage2_kernel(idx) else "stream"}
     n_embeddings = int(w.N)
     pl.plaid_index_free(idx)
@@ -417,12 +433,16 @@ def main():
     line = {
         "metric": "queries_per_sec", "value": round(qps, 2), "unit": "queries/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64/f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if forms["score_kernel"] == "split16" else "f64/f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name} ({args.noise} noise): C={cfg.C} centroids, P={cfg.P} passages, N={n_embeddings} "
                                f"embeddings, {cfg.nbits}-bit residuals, {nq} queries x 32 x 128",
                    "nprobe": cfg.nprobe, "t_cs": cfg.t_cs, "ndocs": cfg.ndocs, "k": cfg.k,
                    "queries_per_step": nq, "index_generated_on": "cuda", **forms,
-                   "arithmetic": "S_cq and the centroid-interaction sums accumulate in f64 (stored f32); MaxSim in f32"},
+                   "arithmetic": ("S_cq: fp16 matrix instruction on two-term fp16 splits of the fp32 operands, f32 accumulation, every "
+                                  "decision near its threshold re-evaluated in f64; centroid-interaction sums in f64; MaxSim in f32"
+                                  if forms["score_kernel"] == "split16" else
+                                  "S_cq and the centroid-interaction sums accumulate in f64 (stored f32); MaxSim in f32")},
         "latency_batch1_ms": {"p50": round(float(np.percentile(lat, 50)), 4), "p99": round(float(np.percentile(lat, 99)), 4),
                               "mean": round(float(lat.mean()), 4), "queries": int(nlat), "trials": 3, "host_enqueue_p50": round(float(np.percentile(enq, 50)), 4),
                               "qps": round(1e3 / float(lat.mean()), 1) if nlat else None},

@@ -72,7 +72,8 @@ typedef struct {
 /* Optional per-stage outputs of plaid_search_debug.  Every pointer is DEVICE, caller-owned, and may be
  * NULL (that output is skipped).  nq is the number of queries of the call. */
 typedef struct {
-    float *S_cq;          /* [nq][C][32]  Eq. 2 scores, row c = centroid c */
+    float *S_cq;          /* [nq][C][32]  Eq. 2 scores, row c = centroid c (the score kernel's values: see
+                             plaid_get_score_kernel for how close to the definition's they are) */
     int32_t *probed;      /* [nq][32][nprobe]  per query token, best first (Section 4.1) */
     int32_t *cand;        /* [nq][P]  ascending candidate pids, first n_cand[q] valid */
     int32_t *n_cand;      /* [nq] */
@@ -82,6 +83,7 @@ typedef struct {
     int32_t *sel3_ids;    /* [nq][max(1,ndocs/4)]  stage-3 survivors, unspecified order */
     float *sel3_scores;   /* [nq][max(1,ndocs/4)]  their unpruned centroid-interaction scores (Eq. 3-4) */
     int32_t *n3;          /* [nq]  = min(max(1,ndocs/4), n2) */
+    uint32_t *keep;       /* [nq][ceil(C/32)]  pruning map of Eq. 5: bit c%32 of word c/32 = centroid c is kept */
 } plaid_debug_buffers;
 
 /* Read an index file and upload it to `device` (a HIP device ordinal).  File layout, little-endian:
@@ -103,7 +105,7 @@ int plaid_index_from_view(const plaid_index_view *view, int device, int copy, pl
 void plaid_index_free(plaid_index *idx);
 
 /* Search nq queries (Figure 4 pipeline, stages as listed at the top of this file).
- *   Q           DEVICE  [nq][32][128] fp32 query token embeddings (unit norm expected, not checked)
+ *   Q           DEVICE  [nq][32][128] fp32 query token embeddings (unit norm expected, not checked), 16-byte aligned
  *   nprobe      centroids probed per query token, 1 <= nprobe <= C
  *   t_cs        pruning threshold of Eq. 5; -INFINITY disables pruning, +INFINITY prunes everything
  *   ndocs       passages kept by stage 2 (>= 1); stage 3 keeps max(1, ndocs/4)
@@ -148,11 +150,20 @@ int plaid_decompress_passages(plaid_index *idx, const int32_t *pids, int32_t n, 
 int plaid_index_info(const plaid_index *idx, int64_t *num_centroids, int64_t *num_passages,
                      int64_t *num_embeddings, int32_t *nbits, int64_t *ivf_len);
 
-/* Which kernel computes S_cq (Eq. 2) for this index: HOST *form = 1 when it is built on the double-precision matrix
- * instruction, 0 for the vector fused-multiply-add chain.  Both accumulate each score over the dimensions in index
- * order and give the same bits; the matrix form is used when a check run on the device at the first index creation of
- * the process confirms that, and the environment variable PLAID_SCQ_FORM=vector|matrix (read at index creation)
- * overrides the choice (matrix is an error when the check fails). */
+/* Which kernel computes S_cq (Eq. 2) for this index: HOST *form =
+ *   2  the half-precision matrix instruction on operands split into two fp16 terms each (the default).  Scores are
+ *      within 2^-16 of the exact dot products for vectors of norm <= 1 whose components lie in fp16's range (observed:
+ *      a few 1e-7); every decision taken on them -- probed centroids (Section 4.1), the pruning map (Eq. 5) -- is
+ *      completed in double wherever that bound leaves it open, and the rows of the surviving centroids that stage 2
+ *      scores with are re-evaluated in double, so probes, candidates, the pruning map and the stage-2 scores of
+ *      queries with at most 63 surviving centroids are those of forms 0 and 1; stage-3 and final scores inherit the
+ *      bound (32 entries per score).  Serves nprobe <= 8; a search with a larger nprobe runs form 1 (or 0).
+ *   1  the double-precision matrix instruction, 0  a vector fused-multiply-add chain: both accumulate each score in
+ *      double over the dimensions in index order and round once, the definition's bits.  Form 1 is used only when a
+ *      check run on the device at the first index creation of the process confirms that the instruction adds its
+ *      products in that order.
+ * The environment variable PLAID_SCQ_FORM=vector|matrix|split16 (read at index creation) overrides the choice (matrix is
+ * an error when the check fails). */
 int plaid_get_score_kernel(const plaid_index *idx, int32_t *form);
 
 /* How candidates and their pruned scores (Section 4.1, Eq. 3-5) are computed for this index: HOST *form = 1 for the

@@ -99,16 +99,42 @@ struct Stage1Out {          // per-query outputs of the tail (device pointers, l
     float *T;               // [nq][S2_MAX_KEPT + 1][32]
 };
 
+// One entry of S_cq as the definition reads: the products of the 128 dimensions accumulated in double in index order
+// (a product of two fp32 values is exact in double, so the fused multiply-add chain is "multiply, then add"), rounded
+// once to fp32.  Used where a decision must not rest on the split-fp16 kernel's approximate scores.
+__device__ __forceinline__ float scq_exact_entry(const float *__restrict__ crow, const float *__restrict__ qrow)
+{
+    double acc = 0.0;
+#pragma unroll 2
+    for (int d = 0; d < DIM; d += 4) {
+        const float4 c = *reinterpret_cast<const float4 *>(crow + d), x = *reinterpret_cast<const float4 *>(qrow + d);
+        acc = fma((double)c.x, (double)x.x, acc);
+        acc = fma((double)c.y, (double)x.y, acc);
+        acc = fma((double)c.z, (double)x.z, acc);
+        acc = fma((double)c.w, (double)x.w, acc);
+    }
+    return (float)acc;
+}
+
 // Survivor table of one query (runs in one workgroup, all of whose threads call it).  K = number of centroids
 // passing Eq. 5; when K <= S2_MAX_KEPT their ids are listed ascending, their rows copied to T (slot s at T[s],
 // s = 1..K), a collision-free hash shift is chosen for stage 2's table, and bin_hi / bin_scale are set from bounds
 // of any non-empty passage's pruned score.  top1[i] = best centroid of token i (gives the bounds when K is large).
+// APPROX (Sq comes from the split-fp16 kernel): the pruning bits were completed by this workgroup a moment ago with
+// atomics, so they are read past the first-level cache, and the rows of T are re-evaluated in double from the centroids
+// Cm and the query Qq, which makes every stage-2 score that is built from T the exact one.
+template <bool APPROX>
 __device__ void stage1_survivor_table(const float *__restrict__ Sq, int64_t C, const uint32_t *__restrict__ kb,
                                       int64_t keep_words, const int32_t *top1, S2Meta *meta_q,
                                       int32_t *__restrict__ kept_ids_q, float *__restrict__ Tq, int32_t *scan /*[waves]*/,
                                       int32_t *ids /*[S2_MAX_KEPT + 1]*/, uint32_t *trial /*[S2_NHASH][S2_HASH / 32]*/,
-                                      float *colmm /*[2][32]*/, int32_t *misc /*[2]*/)
+                                      float *colmm /*[2][32]*/, int32_t *misc /*[2]*/, const float *__restrict__ Cm = nullptr,
+                                      const float *__restrict__ Qq = nullptr)
 {
+    auto keep_word = [&](int64_t w) -> uint32_t {
+        if (APPROX) return __hip_atomic_load(kb + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return kb[w];
+    };
     const int tid = threadIdx.x, nthreads = blockDim.x;
     if (tid == 0) {
         misc[0] = 0;   // running count of survivors
@@ -122,7 +148,7 @@ __device__ void stage1_survivor_table(const float *__restrict__ Sq, int64_t C, c
         const int64_t per = (keep_words + nthreads - 1) / nthreads;
         const int64_t wa = (int64_t)tid * per, wb = wa + per < keep_words ? wa + per : keep_words;
         int cnt = 0;
-        for (int64_t w = wa; w < wb; ++w) cnt += __popc(kb[w]);
+        for (int64_t w = wa; w < wb; ++w) cnt += __popc(keep_word(w));
         int incl = cnt;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
@@ -135,7 +161,7 @@ __device__ void stage1_survivor_table(const float *__restrict__ Sq, int64_t C, c
         for (int wv = 0; wv < (tid >> 6); ++wv) start += scan[wv];
         int pos = start;
         for (int64_t w = wa; w < wb && pos < S2_MAX_KEPT; ++w) {
-            uint32_t v = kb[w];
+            uint32_t v = keep_word(w);
             while (v && pos < S2_MAX_KEPT) {
                 const int b = __ffs(v) - 1;
                 v &= v - 1;
@@ -169,7 +195,8 @@ __device__ void stage1_survivor_table(const float *__restrict__ Sq, int64_t C, c
     const int hash_shift = (K <= S2_MAX_KEPT) ? S2_SHIFT0 + (S2_NHASH - 1 - misc[1]) : 0;
     if (K <= S2_MAX_KEPT) {
         for (int e = tid; e < K * QLEN; e += nthreads)
-            Tq[QLEN + e] = Sq[(int64_t)ids[e >> 5] * QLEN + (e & 31)];
+            Tq[QLEN + e] = APPROX ? scq_exact_entry(Cm + (int64_t)ids[e >> 5] * DIM, Qq + (e & 31) * DIM)
+                                  : Sq[(int64_t)ids[e >> 5] * QLEN + (e & 31)];
         if (tid < K) kept_ids_q[tid] = ids[tid];
         if (tid < QLEN) {
             float mx = -INFINITY, mn = INFINITY;
@@ -218,9 +245,9 @@ __global__ __launch_bounds__(512) void stage1_survivor_kernel(const float *__res
     const int q = blockIdx.x;
     if (threadIdx.x < QLEN) top1[threadIdx.x] = probed[((int64_t)q * QLEN + threadIdx.x) * nprobe];
     __syncthreads();
-    stage1_survivor_table(S + (int64_t)q * C * QLEN, C, keepbits + (int64_t)q * keep_words, keep_words, top1, o.meta + q,
-                          o.kept_ids + (int64_t)q * S2_MAX_KEPT, o.T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN, scan, ids, trial,
-                          colmm, misc);
+    stage1_survivor_table<false>(S + (int64_t)q * C * QLEN, C, keepbits + (int64_t)q * keep_words, keep_words, top1, o.meta + q,
+                                 o.kept_ids + (int64_t)q * S2_MAX_KEPT, o.T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN, scan, ids,
+                                 trial, colmm, misc);
 }
 
 // tilemax: [q][tile][32] column maxima of each tile (null: scores and pruning bits only).
@@ -590,12 +617,30 @@ int plaid_scq_matrix_form_ok(hipStream_t st, int *ok)
 // tie group too long for the list makes the lanes walk all tiles instead); their rows are ranked by (score
 // descending, id ascending) from S_cq, four loads per lane in flight, and the 32 lists are merged by a shuffle tree.
 // tile_rows = centroid rows per tile.
+//
+// APPROX: S, its tile maxima and the pruning bits come from the split-fp16 kernel, every entry within eps =
+// PLAID_SCQ16_EPS of the exact one.  The decisions stay those of the exact scores:
+//   probes   at least nprobe entries are >= T (approximately), hence >= T - eps exactly, so the nprobe-th best exact
+//            score is >= T - eps and every centroid among the nprobe best has an approximate score >= T - 2 eps.  The
+//            tiles with maximum >= T - 2 eps are listed, and each of their rows with a score >= T - 2 eps (normally
+//            just the nprobe best) is re-evaluated in double and ranked by its exact score;
+//   pruning  a row whose approximate maximum lies within eps of t_cs was left open by the score kernel (ambbits): its
+//            entries >= t_cs - eps are re-evaluated and the row's bit is set when one of them reaches t_cs;
+//   table    the rows of the surviving centroids that stage 2 scores with are re-evaluated (stage1_survivor_table).
 #define TAIL_SEL 16  // listed tiles per token
-template <int NP>
+#define TAIL_AMB 2048  // ambiguous rows decided per round
+struct Stage1Exact {        // what the re-evaluations need (APPROX only)
+    const float *Cm;        // [C][128] centroids
+    const float *Q;         // [nq][32][128] queries
+    const uint32_t *ambbits;  // [nq][keep_words]
+    float t_cs, t_lo;       // threshold of Eq. 5 and the smallest approximate score that can still reach it
+    float margin;           // 2 eps
+};
+template <int NP, bool APPROX>
 __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *__restrict__ S, int64_t C,
-                                                                   const uint32_t *__restrict__ keepbits, int64_t keep_words,
+                                                                   uint32_t *__restrict__ keepbits, int64_t keep_words,
                                                                    const float *__restrict__ tilemax, int nblk, int tile_rows,
-                                                                   int nprobe, Stage1Out o)
+                                                                   int nprobe, Stage1Out o, Stage1Exact x)
 {
     __shared__ int32_t idl[256];   // probed ids
     __shared__ int32_t top1[QLEN];
@@ -616,6 +661,8 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
     const int q = blockIdx.x, tid = threadIdx.x;
     const float *__restrict__ Sq = S + (int64_t)q * C * QLEN;
     const float *__restrict__ tmq = tilemax + (int64_t)q * nblk * QLEN;
+    const float margin = APPROX ? x.margin : 0.f;
+    const float *__restrict__ Qq = APPROX ? x.Q + (int64_t)q * QLEN * DIM : nullptr;
     {
         // pass 1: thread (tokens 4 tk4 .. 4 tk4 + 3, part) keeps the NP largest maxima of tiles part, part + 128, ...
         const int tk4 = tid % (QLEN / 4), part = tid / (QLEN / 4);
@@ -688,7 +735,8 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
     {
         // pass 2, same thread -> (tokens, tiles) map: list the tiles that can hold one of the nprobe best
         const int tk4 = tid % (QLEN / 4), part = tid / (QLEN / 4);
-        const float T4[4] = {Tsh[4 * tk4], Tsh[4 * tk4 + 1], Tsh[4 * tk4 + 2], Tsh[4 * tk4 + 3]};
+        const float T4[4] = {Tsh[4 * tk4] - margin, Tsh[4 * tk4 + 1] - margin, Tsh[4 * tk4 + 2] - margin,
+                             Tsh[4 * tk4 + 3] - margin};
         for (int b0 = part; b0 < nblk; b0 += TAIL_PARTS * TAIL_FLY) {
             float4 v[TAIL_FLY];
 #pragma unroll
@@ -715,7 +763,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
         uint64_t best[NP];
 #pragma unroll
         for (int j = 0; j < NP; ++j) best[j] = PLAID_KEY_MAX;
-        const float T = Tsh[i];
+        const float T = Tsh[i] - margin;
         const int n_sel = sel_cnt[i];
         const bool listed = n_sel <= TAIL_SEL;
         const int chunks = (tile_rows + TAIL_LANES - 1) / TAIL_LANES;  // 32-row pieces of a tile
@@ -736,8 +784,15 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
                 sv[u] = ok[u] ? Sq[cc[u] * QLEN + i] : 0.f;
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (ok[u]) scq_insert_key<NP>(best, plaid_make_key(sv[u], (uint32_t)cc[u]));
+            for (int u = 0; u < 4; ++u) {
+                if (APPROX) {
+                    // only a row that can be among the nprobe best is ranked, by its exact score
+                    if (ok[u] && sv[u] >= T)
+                        scq_insert_key<NP>(best, plaid_make_key(scq_exact_entry(x.Cm + cc[u] * DIM, Qq + i * DIM), (uint32_t)cc[u]));
+                } else if (ok[u]) {
+                    scq_insert_key<NP>(best, plaid_make_key(sv[u], (uint32_t)cc[u]));
+                }
+            }
         }
         // shuffle tree over the 32 lanes of this token (lanes l and l ^ d exchange lists; both keep the merged list)
 #pragma unroll
@@ -786,22 +841,71 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
         const int total = __syncthreads_count(fo && part == 0);
         if (tid == 0) o.n_uniq[q] = total;
     }
-    stage1_survivor_table(S + (int64_t)q * C * QLEN, C, keepbits + (int64_t)q * keep_words, keep_words, top1, o.meta + q,
-                          o.kept_ids + (int64_t)q * S2_MAX_KEPT, o.T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN, scan, ids, trial,
-                          colmm, misc);
+    if (APPROX) {
+        // Eq. 5 for the rows the score kernel left open.  Rounds of at most TAIL_AMB rows: the rows of a range of bitmap
+        // words are listed in LDS, then their 32 entries each are spread over the workgroup.  (One round, a handful of
+        // rows, unless the threshold sits where many row maxima do.)
+        __shared__ int32_t amb_rows[TAIL_AMB];
+        __shared__ int32_t amb_n, amb_total;
+        uint32_t *kbq = keepbits + (int64_t)q * keep_words;
+        const uint32_t *abq = x.ambbits + (int64_t)q * keep_words;
+        if (tid == 0) amb_total = 0;
+        __syncthreads();
+        {
+            int cnt = 0;
+            for (int64_t w = tid; w < keep_words; w += TAIL_THREADS) cnt += __popc(abq[w]);
+            if (cnt) atomicAdd(&amb_total, cnt);
+        }
+        __syncthreads();
+        const int total = amb_total;  // uniform
+        // words taken per round: all of them when every open row fits the list (the usual case: one round), else as
+        // many as always fit
+        const int64_t round_words = total <= TAIL_AMB ? keep_words : TAIL_AMB / 32;
+        for (int64_t w0 = 0; total > 0 && w0 < keep_words; w0 += round_words) {
+            __syncthreads();
+            if (tid == 0) amb_n = 0;
+            __syncthreads();
+            const int64_t w1 = w0 + round_words < keep_words ? w0 + round_words : keep_words;
+            for (int64_t w = w0 + tid; w < w1; w += TAIL_THREADS) {
+                uint32_t v = abq[w];
+                while (v) {
+                    const int b = __ffs(v) - 1;
+                    v &= v - 1;
+                    amb_rows[atomicAdd(&amb_n, 1)] = (int32_t)(w * 32 + b);
+                }
+            }
+            __syncthreads();
+            const int n_amb = amb_n;
+            for (int p = tid; p < n_amb * QLEN; p += TAIL_THREADS) {
+                const int64_t c = amb_rows[p >> 5];
+                const int tok = p & 31;
+                if (Sq[c * QLEN + tok] >= x.t_lo && scq_exact_entry(x.Cm + c * DIM, Qq + tok * DIM) >= x.t_cs)
+                    atomicOr(&kbq[c >> 5], 1u << (c & 31));
+            }
+        }
+        __threadfence();
+        __syncthreads();
+    }
+    stage1_survivor_table<APPROX>(S + (int64_t)q * C * QLEN, C, keepbits + (int64_t)q * keep_words, keep_words, top1,
+                                  o.meta + q, o.kept_ids + (int64_t)q * S2_MAX_KEPT,
+                                  o.T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN, scan, ids, trial, colmm, misc, x.Cm, Qq);
 }
 
 // np = capacity of the tail's lists (1, 2, 4 or 8 >= nprobe); np = 0: scores and pruning bits only (large nprobe).
 static void launch_fused(hipStream_t st, int phases, int np, const float *centroids, int64_t C, const float *Q, const void *Qx,
-                         int matrix_form, int nq, float t_cs, float *S, uint32_t *keepbits, int64_t keep_words,
-                         float *tilemax, int nprobe, const Stage1Out &o, uint32_t *zero, int64_t zero_words)
+                         int form, const void *A16, int nq, float t_cs, float *S, uint32_t *keepbits, uint32_t *ambbits,
+                         int64_t keep_words, float *tilemax, int nprobe, const Stage1Out &o, uint32_t *zero, int64_t zero_words)
 {
-    const int tile_rows = matrix_form ? SM_WROWS : SCQ_ROWS;  // rows per tile of column maxima
-    const int grid_rows = matrix_form ? SM_ROWS : SCQ_ROWS;   // rows per workgroup
+    const bool matrix_form = form == PLAID_SCQ_MATRIX;
+    const int tile_rows = form == PLAID_SCQ_VECTOR ? SCQ_ROWS : SM_WROWS;  // rows per tile of column maxima
+    const int grid_rows = matrix_form ? SM_ROWS : SCQ_ROWS;   // rows per workgroup (the two double-precision forms)
     const unsigned nblk = (unsigned)((C + grid_rows - 1) / grid_rows);
     const int n_tiles = (int)((C + tile_rows - 1) / tile_rows);
     float *tmx = np > 0 ? tilemax : nullptr;
+    static_assert(SM_WROWS == 32, "the split-fp16 kernel emits column maxima per 32 rows, like the matrix form");
     if (!(phases & PLAID_STAGE1_SCORES)) {
+    } else if (form == PLAID_SCQ_SPLIT16) {
+        plaid_launch_scq16(st, A16, C, Qx, nq, t_cs, S, keepbits, ambbits, keep_words, tmx);
     } else if (matrix_form) {
         if (nq == 1)
             hipLaunchKernelGGL(scq_mfma_kernel<1>, dim3(1, nblk), dim3(SM_THREADS), 0, st, centroids, C, Q, nq, t_cs, S, keepbits,
@@ -814,13 +918,27 @@ static void launch_fused(hipStream_t st, int phases, int np, const float *centro
                            keepbits, keep_words, tmx);
     }
     if (np > 0 && (phases & PLAID_STAGE1_PROBES)) {
-#define TAIL(NP_)                                                                                                          \
-    hipLaunchKernelGGL(stage1_tail_kernel<NP_>, dim3(nq), dim3(TAIL_THREADS), 0, st, S, C, keepbits, keep_words, tilemax, \
-                       n_tiles, tile_rows, nprobe, o)
-        if (np == 1) TAIL(1);
-        else if (np == 2) TAIL(2);
-        else if (np == 4) TAIL(4);
-        else TAIL(8);
+        Stage1Exact x;
+        x.Cm = centroids;
+        x.Q = Q;
+        x.ambbits = ambbits;
+        x.t_cs = t_cs;
+        x.t_lo = (t_cs > -INFINITY && t_cs < INFINITY) ? nextafterf(t_cs - PLAID_SCQ16_EPS, -INFINITY) : t_cs;
+        x.margin = 2.0f * PLAID_SCQ16_EPS;
+#define TAIL(NP_, AP_)                                                                                                     \
+    hipLaunchKernelGGL((stage1_tail_kernel<NP_, AP_>), dim3(nq), dim3(TAIL_THREADS), 0, st, S, C, keepbits, keep_words,     \
+                       tilemax, n_tiles, tile_rows, nprobe, o, x)
+        if (form == PLAID_SCQ_SPLIT16) {
+            if (np == 1) TAIL(1, true);
+            else if (np == 2) TAIL(2, true);
+            else if (np == 4) TAIL(4, true);
+            else TAIL(8, true);
+        } else {
+            if (np == 1) TAIL(1, false);
+            else if (np == 2) TAIL(2, false);
+            else if (np == 4) TAIL(4, false);
+            else TAIL(8, false);
+        }
 #undef TAIL
     }
 }
@@ -832,12 +950,14 @@ size_t plaid_stage1_tilemax_bytes(int64_t C, int nq, int nprobe)
     return (size_t)nq * ((C + rows - 1) / rows) * QLEN * 4;
 }
 
-void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int64_t C, const float *Q, void *Qd, int matrix_form,
-                         int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, float *tilemax,
-                         uint32_t *zero, int64_t zero_words, int32_t *probed, int32_t *uniq, int uniq_stride,
-                         int32_t *n_uniq, const Stage2Buffers &s2, void *probe_scratch, size_t probe_scratch_bytes)
+void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int64_t C, const float *Q, void *Qd, int form,
+                         const void *A16, int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, uint32_t *ambbits,
+                         int64_t keep_words, float *tilemax, uint32_t *zero, int64_t zero_words, int32_t *probed,
+                         int32_t *uniq, int uniq_stride, int32_t *n_uniq, const Stage2Buffers &s2, void *probe_scratch,
+                         size_t probe_scratch_bytes)
 {
-    if ((phases & PLAID_STAGE1_PREP) && !matrix_form) {
+    if ((phases & PLAID_STAGE1_PREP) && form == PLAID_SCQ_SPLIT16) plaid_launch_scq16_split_queries(st, Q, nq, Qd, zero, zero_words);
+    if ((phases & PLAID_STAGE1_PREP) && form == PLAID_SCQ_VECTOR) {
         int64_t gz = (zero_words + 256 * 8 - 1) / (256 * 8);
         if (gz < nq) gz = nq;
         if (gz > 1024) gz = 1024;
@@ -854,12 +974,12 @@ void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int
     o.T = s2.T;
     const int np = nprobe == 1 ? 1 : (nprobe == 2 ? 2 : (nprobe <= 4 ? 4 : (nprobe <= PLAID_PROBE_FAST_MAX ? 8 : 0)));
     if (np > 0)
-        launch_fused(st, phases, np, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, tilemax, nprobe, o,
-                     zero, zero_words);
+        launch_fused(st, phases, np, centroids, C, Q, Qd, form, A16, nq, t_cs, S, keepbits, ambbits, keep_words, tilemax, nprobe,
+                     o, zero, zero_words);
     else {
         // large nprobe: scores and pruning bits here, probes through the generic selection, survivor table after it
-        launch_fused(st, phases, 0, centroids, C, Q, Qd, matrix_form, nq, t_cs, S, keepbits, keep_words, tilemax, nprobe, o,
-                     zero, zero_words);
+        launch_fused(st, phases, 0, centroids, C, Q, Qd, form, A16, nq, t_cs, S, keepbits, ambbits, keep_words, tilemax, nprobe,
+                     o, zero, zero_words);
         if (phases & PLAID_STAGE1_PROBES) {
             plaid_launch_top_nprobe_general(st, S, C, nq, nprobe, probed, uniq, uniq_stride, n_uniq, probe_scratch,
                                             probe_scratch_bytes);

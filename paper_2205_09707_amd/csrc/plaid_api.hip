@@ -61,7 +61,9 @@ struct plaid_index {
     size_t ws_bytes = 0;
     int32_t max_chunk = 0;
     int32_t timing = 0;
-    int32_t scq_matrix_form = 0;  // score kernel: 1 = double-precision matrix instruction, 0 = vector FMA chain
+    int32_t scq_matrix_form = 0;  // double-precision score kernel: 1 = matrix instruction, 0 = vector FMA chain
+    int32_t scq_form = 0;         // score kernel of a search: PLAID_SCQ_VECTOR / _MATRIX / _SPLIT16
+    void *A16 = nullptr;          // split-fp16 operand form of the centroids (owned), when scq_form is PLAID_SCQ_SPLIT16
     uint32_t *ivr_table = nullptr;  // range table of the inverted lists (owned); null: union + code stream are used
     int32_t *dense_id = nullptr;    // with the range table: bitmap row of each centroid's list, -1 for all but the longest
     uint32_t *dense_bits = nullptr; // [rows][ceil(P / 32)]
@@ -100,19 +102,23 @@ static int static_workspace_address(int device, char **out)
     return PLAID_OK;
 }
 
-// Which of the two bit-identical score kernels this handle uses.  PLAID_SCQ_FORM=vector|matrix overrides the choice
-// (matrix is refused when the device check fails); the check itself runs once per process and device.
+// Which score kernel this handle uses.  Default: the split-fp16 matrix kernel, with the double-precision matrix kernel
+// (or, should the device check of that instruction fail, the vector chain) behind it for nprobe values the fast probe
+// kernel does not serve.  PLAID_SCQ_FORM=vector|matrix|split16 overrides the choice (matrix is refused when the device
+// check fails); the check itself runs once per process and device.
 static int choose_scq_form(plaid_index *ix)
 {
     static int checked[64] = {0};  // 0 = not yet, 1 = matrix form verified, 2 = not usable
     static std::mutex guard;       // indexes may be created from several host threads
     const std::lock_guard<std::mutex> lock(guard);
     const char *env = getenv("PLAID_SCQ_FORM");
+    if (env && strcmp(env, "vector") && strcmp(env, "matrix") && strcmp(env, "split16"))
+        return fail(PLAID_EINVAL, "PLAID_SCQ_FORM must be 'vector', 'matrix' or 'split16'");
     if (env && !strcmp(env, "vector")) {
         ix->scq_matrix_form = 0;
+        ix->scq_form = PLAID_SCQ_VECTOR;
         return PLAID_OK;
     }
-    if (env && strcmp(env, "matrix")) return fail(PLAID_EINVAL, "PLAID_SCQ_FORM must be 'vector' or 'matrix'");
     const int slot = ix->device < 64 ? ix->device : 63;
     if (!checked[slot] || ix->device >= 64) {
         int ok = 0;
@@ -120,8 +126,29 @@ static int choose_scq_form(plaid_index *ix)
         if (e) return fail(PLAID_EHIP, "score-kernel self check failed: %s", hipGetErrorString((hipError_t)e));
         checked[slot] = ok ? 1 : 2;
     }
-    if (env && checked[slot] != 1) return fail(PLAID_EHIP, "PLAID_SCQ_FORM=matrix, but the matrix instruction does not reproduce the FMA chain here");
+    const bool want_matrix = env && !strcmp(env, "matrix");
+    if (want_matrix && checked[slot] != 1)
+        return fail(PLAID_EHIP, "PLAID_SCQ_FORM=matrix, but the matrix instruction does not reproduce the FMA chain here");
     ix->scq_matrix_form = checked[slot] == 1;
+    ix->scq_form = want_matrix ? PLAID_SCQ_MATRIX : PLAID_SCQ_SPLIT16;
+    return PLAID_OK;
+}
+
+// Operand form of the centroid table for the split-fp16 score kernel (512 bytes per centroid, built once).
+static int build_scq16_operands(plaid_index *ix)
+{
+    if (ix->scq_form != PLAID_SCQ_SPLIT16) return PLAID_OK;
+    const size_t bytes = plaid_scq16_centroid_bytes(ix->C);
+    void *d = nullptr;
+    if (hipMalloc(&d, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PLAID_ENOMEM, "hipMalloc(%zu) for the centroids' matrix operands failed", bytes);
+    }
+    ix->owned.push_back(d);
+    plaid_launch_scq16_split_centroids(nullptr, ix->centroids, ix->C, d);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(nullptr));
+    ix->A16 = d;
     return PLAID_OK;
 }
 
@@ -329,6 +356,7 @@ extern "C" int plaid_index_from_view(const plaid_index_view *v, int device, int 
         ix->ivf_pids = v->ivf_pids;
     }
     rc = choose_scq_form(ix);
+    if (!rc) rc = build_scq16_operands(ix);
     if (!rc) rc = build_range_table(ix);
     if (!rc) rc = static_workspace_address(ix->device, &ix->static_ws);  // (the index's device is current here)
     if (rc) {
@@ -445,7 +473,7 @@ extern "C" int plaid_index_info(const plaid_index *idx, int64_t *num_centroids, 
 extern "C" int plaid_get_score_kernel(const plaid_index *idx, int32_t *form)
 {
     if (!idx || !form) return fail(PLAID_EINVAL, "null argument");
-    *form = idx->scq_matrix_form;
+    *form = idx->scq_form;
     return PLAID_OK;
 }
 
@@ -491,6 +519,7 @@ struct Workspace {
     double *Qd;          // [qc][128][32]
     float *S;            // [qc][C][32]
     uint32_t *keepbits;  // [qc][keep_words]
+    uint32_t *ambbits;   // [qc][keep_words] rows whose pruning test the split-fp16 scores leave open
     int32_t *probed;     // [qc][32][nprobe]
     int32_t *uniq;       // [qc][uniq_stride]
     int32_t *n_uniq;     // [qc]
@@ -553,6 +582,7 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     w.Qd = (double *)take((size_t)qc * QLEN * DIM * 8);
     w.S = (float *)take((size_t)qc * C * QLEN * 4);
     w.keepbits = (uint32_t *)take((size_t)qc * w.keep_words * 4);
+    w.ambbits = (uint32_t *)take((size_t)qc * w.keep_words * 4);
     w.probed = (int32_t *)take((size_t)qc * QLEN * pl.nprobe * 4);
     w.uniq = (int32_t *)take((size_t)qc * w.uniq_stride * 4);
     w.n_uniq = (int32_t *)take((size_t)qc * 4);
@@ -624,6 +654,7 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
 {
     if (!ix) return fail(PLAID_EINVAL, "null index");
     if (!Q || !out_ids || !out_scores) return fail(PLAID_EINVAL, "null buffer");
+    if ((uintptr_t)Q & 15) return fail(PLAID_EINVAL, "Q must be aligned to 16 bytes");
     if (nq < 1) return fail(PLAID_EINVAL, "nq must be >= 1 (got %d)", nq);
     if (nprobe < 1 || nprobe > ix->C) return fail(PLAID_EINVAL, "nprobe must be in [1, C] (got %d, C = %lld)", nprobe, (long long)ix->C);
     if (ndocs < 1) return fail(PLAID_EINVAL, "ndocs must be >= 1 (got %d)", ndocs);
@@ -652,6 +683,10 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
         ws_base = (char *)ix->ws;
     }
 
+    // the split-fp16 kernel pairs with the fast probe kernel only: larger nprobe values take a double-precision form
+    const int form = (ix->scq_form == PLAID_SCQ_SPLIT16 && nprobe > PLAID_PROBE_FAST_MAX)
+                         ? (ix->scq_matrix_form ? PLAID_SCQ_MATRIX : PLAID_SCQ_VECTOR)
+                         : ix->scq_form;
     const bool timing = ix->timing != 0;
     if (timing)
         for (int s = 0; s < PLAID_NUM_STAGES; ++s) ix->stage_ms[s] = 0.f;
@@ -671,7 +706,7 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
         STAMP();
         // stage 1: S_cq (Eq. 2), pruning map (Eq. 5), probes and candidates (Section 4.1)
         for (int phase = PLAID_STAGE1_PREP; phase <= PLAID_STAGE1_PROBES; phase <<= 1) {
-            plaid_launch_stage1(st, phase, ix->centroids, C, Qc, w.Qd, ix->scq_matrix_form, n, t_cs, nprobe, w.S, w.keepbits,
+            plaid_launch_stage1(st, phase, ix->centroids, C, Qc, w.Qd, form, ix->A16, n, t_cs, nprobe, w.S, w.keepbits, w.ambbits,
                                 w.keep_words, w.tilemax, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed,
                                 w.uniq, w.uniq_stride, w.n_uniq, w.s2, w.probe_scratch, w.probe_scratch_bytes);
             STAMP();
@@ -715,6 +750,9 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
         if (dbg) {
             if (dbg->S_cq)
                 HIP_TRY(hipMemcpyAsync(dbg->S_cq + (int64_t)q0 * C * QLEN, w.S, (size_t)n * C * QLEN * 4,
+                                       hipMemcpyDeviceToDevice, st));
+            if (dbg->keep)
+                HIP_TRY(hipMemcpyAsync(dbg->keep + (int64_t)q0 * w.keep_words, w.keepbits, (size_t)n * w.keep_words * 4,
                                        hipMemcpyDeviceToDevice, st));
             if (dbg->probed)
                 HIP_TRY(hipMemcpyAsync(dbg->probed + (int64_t)q0 * QLEN * nprobe, w.probed, (size_t)n * QLEN * nprobe * 4,
@@ -815,6 +853,15 @@ extern "C" int plaid_assign_centroids(const float *centroids, int64_t C, const f
     fake.P = 1;
     int rc = choose_scq_form(&fake);
     if (rc) return rc;
+    TempAlloc a16;
+    if (fake.scq_form == PLAID_SCQ_SPLIT16) {
+        const size_t ab = plaid_scq16_centroid_bytes(C);
+        if (hipMalloc(&a16.p, ab) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(PLAID_ENOMEM, "hipMalloc(%zu) for the centroids' matrix operands failed", ab);
+        }
+        plaid_launch_scq16_split_centroids(st, centroids, C, a16.p);
+    }
     Plan pl;
     pl.nprobe = 1;
     pl.nd = pl.m3 = pl.kk = 1;
@@ -844,8 +891,8 @@ extern "C" int plaid_assign_centroids(const float *centroids, int64_t C, const f
     auto run = [&](const float *src, int64_t ng, int32_t *dst, int64_t cnt) -> int {
         const Workspace w = carve((char *)ws.p, &fake, (int)ng, pl);
         for (int phase = PLAID_STAGE1_PREP; phase <= PLAID_STAGE1_PROBES; phase <<= 1)
-            plaid_launch_stage1(st, phase, centroids, C, src, w.Qd, fake.scq_matrix_form, (int)ng, INFINITY, 1, w.S, w.keepbits,
-                                w.keep_words, w.tilemax, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed,
+            plaid_launch_stage1(st, phase, centroids, C, src, w.Qd, fake.scq_form, a16.p, (int)ng, INFINITY, 1, w.S, w.keepbits,
+                                w.ambbits, w.keep_words, w.tilemax, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed,
                                 w.uniq, w.uniq_stride, w.n_uniq, w.s2, w.probe_scratch, w.probe_scratch_bytes);
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipMemcpyAsync(dst, w.probed, (size_t)cnt * 4, hipMemcpyDeviceToDevice, st));  // probed is [group][32][1]

@@ -110,11 +110,30 @@ int plaid_scq_matrix_form_ok(hipStream_t st, int *ok);  // returns a hipError_t 
 #define PLAID_STAGE1_PREP 1
 #define PLAID_STAGE1_SCORES 2
 #define PLAID_STAGE1_PROBES 4
-void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int64_t C, const float *Q, void *Qx, int matrix_form,
-                         int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, int64_t keep_words, float *tilemax,
-                         uint32_t *zero, int64_t zero_words, int32_t *probed, int32_t *uniq, int uniq_stride,
-                         int32_t *n_uniq, const struct Stage2Buffers &s2, void *probe_scratch, size_t probe_scratch_bytes);
+// form: which kernel computes the scores.  The two double-precision forms give the definition's bits; the split-fp16
+// form (A16 = operand form of the centroids, ambbits = [nq][keep_words] scratch) gives scores within PLAID_SCQ16_EPS and
+// the same probes, pruning bits and survivor table, completed in double where the bound leaves a decision open; it
+// serves nprobe <= PLAID_PROBE_FAST_MAX only (the caller falls back to a double-precision form beyond).
+#define PLAID_SCQ_VECTOR 0
+#define PLAID_SCQ_MATRIX 1
+#define PLAID_SCQ_SPLIT16 2
+void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int64_t C, const float *Q, void *Qx, int form,
+                         const void *A16, int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, uint32_t *ambbits,
+                         int64_t keep_words, float *tilemax, uint32_t *zero, int64_t zero_words, int32_t *probed,
+                         int32_t *uniq, int uniq_stride, int32_t *n_uniq, const struct Stage2Buffers &s2, void *probe_scratch,
+                         size_t probe_scratch_bytes);
 size_t plaid_stage1_tilemax_bytes(int64_t C, int nq, int nprobe);
+
+// Split-fp16 form of Eq. 2 (k_scq16.hip).  S differs from the exact dot products by at most PLAID_SCQ16_EPS for
+// vectors of norm <= 1 (components within fp16's range); keepbits holds the rows that pass Eq. 5 even if every entry
+// were that much lower, ambbits the rows whose test the bound leaves open (decided in double by the probe kernel).
+#define PLAID_SCQ16_EPS 1.52587890625e-05f  // 2^-16
+size_t plaid_scq16_centroid_bytes(int64_t C);  // operand form of the centroid table, built once per index
+size_t plaid_scq16_query_bytes(int nq);        // operand form of nq queries
+void plaid_launch_scq16_split_centroids(hipStream_t st, const float *centroids, int64_t C, void *A16);
+void plaid_launch_scq16_split_queries(hipStream_t st, const float *Q, int nq, void *B16, uint32_t *zero, int64_t zero_words);
+void plaid_launch_scq16(hipStream_t st, const void *A16, int64_t C, const void *B16, int nq, float t_cs, float *S,
+                        uint32_t *keepbits, uint32_t *ambbits, int64_t keep_words, float *tilemax);
 
 // General top-nprobe (nprobe > PLAID_PROBE_FAST_MAX): ranking keys of every S column through the generic selection.
 void plaid_launch_top_nprobe_general(hipStream_t st, const float *S, int64_t C, int nq, int nprobe, int32_t *probed,

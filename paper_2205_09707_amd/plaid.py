@@ -40,7 +40,7 @@ class plaid_index_view(ct.Structure):
 
 class plaid_debug_buffers(ct.Structure):
     _fields_ = [(n, ct.c_void_p) for n in ("S_cq", "probed", "cand", "n_cand", "sel2_ids", "sel2_scores", "n2",
-                                            "sel3_ids", "sel3_scores", "n3")]
+                                            "sel3_ids", "sel3_scores", "n3", "keep")]
 
 
 EXPORTS = ("plaid_index_load", "plaid_index_from_view", "plaid_index_free", "plaid_search", "plaid_search_debug",
@@ -236,7 +236,7 @@ def plaid_search_debug(idx: Index, Q: torch.Tensor, nprobe: int, t_cs: float, nd
                   cand=((nq, idx.P), torch.int32), n_cand=((nq,), torch.int32),
                   sel2_ids=((nq, int(ndocs)), torch.int32), sel2_scores=((nq, int(ndocs)), torch.float32),
                   n2=((nq,), torch.int32), sel3_ids=((nq, m3), torch.int32), sel3_scores=((nq, m3), torch.float32),
-                  n3=((nq,), torch.int32))
+                  n3=((nq,), torch.int32), keep=((nq, (idx.C + 31) // 32), torch.int32))
     names = list(shapes) if want is None else list(want)
     bufs = {n: torch.zeros(shapes[n][0], dtype=shapes[n][1], device=dev) for n in names}
     dbg = plaid_debug_buffers(**{n: bufs[n].data_ptr() for n in names})

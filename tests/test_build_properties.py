@@ -16,8 +16,11 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 KERNELS = {
     "scq_mfma_kernelILi2E": ("k_scq.hip", 128, 40 << 10),          # four waves per SIMD, four workgroups per CU
     "scq_mfma_kernelILi1E": ("k_scq.hip", 128, 40 << 10),
-    "stage1_tail_kernelILi2E": ("k_scq.hip", 128, 64 << 10),       # 1024 threads: 128 registers at most
-    "stage1_tail_kernelILi8E": ("k_scq.hip", 128, 64 << 10),
+    "stage1_tail_kernelILi2ELb0E": ("k_scq.hip", 128, 64 << 10),   # 1024 threads: 128 registers at most
+    "stage1_tail_kernelILi8ELb0E": ("k_scq.hip", 128, 64 << 10),
+    "stage1_tail_kernelILi2ELb1E": ("k_scq.hip", 128, 64 << 10),   # ... also with the re-evaluations in double
+    "stage1_tail_kernelILi8ELb1E": ("k_scq.hip", 128, 64 << 10),
+    "scq16_kernel": ("k_scq16.hip", 256, 40 << 10),                # two waves per SIMD, two to four workgroups per CU
     "s2_invert_kernel": ("k_stage2.hip", 128, 64 << 10),
     "s2_union_wide_kernel": ("k_stage2.hip", 128, 80 << 10),       # two workgroups of 1024 threads per CU
     "s2_stream_kernel": ("k_stage2.hip", 128, 40 << 10),

@@ -16,7 +16,8 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.mark.parametrize("form,stage2", [("matrix", "inverted"), ("vector", "stream"), (None, None)])
+@pytest.mark.parametrize("form,stage2", [("split16", "inverted"), ("split16", "stream"), ("matrix", "inverted"),
+                                         ("vector", "stream")])
 def test_nonfinite_query_tokens(form, stage2):
     import paper_2205_09707_amd as pl
     pl.load_library()

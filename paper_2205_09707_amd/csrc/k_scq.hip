@@ -102,16 +102,24 @@ struct Stage1Out {          // per-query outputs of the tail (device pointers, l
 // One entry of S_cq as the definition reads: the products of the 128 dimensions accumulated in double in index order
 // (a product of two fp32 values is exact in double, so the fused multiply-add chain is "multiply, then add"), rounded
 // once to fp32.  Used where a decision must not rest on the split-fp16 kernel's approximate scores.
-__device__ __forceinline__ float scq_exact_entry(const float *__restrict__ crow, const float *__restrict__ qrow)
+// crow: the centroid's row in global memory, fetched 32 dimensions at a time (eight 16-byte loads in flight); qrow: the
+// query token's row, which the caller keeps in LDS.
+__device__ __forceinline__ float scq_exact_entry(const float *__restrict__ crow, const float *qrow)
 {
     double acc = 0.0;
-#pragma unroll 2
-    for (int d = 0; d < DIM; d += 4) {
-        const float4 c = *reinterpret_cast<const float4 *>(crow + d), x = *reinterpret_cast<const float4 *>(qrow + d);
-        acc = fma((double)c.x, (double)x.x, acc);
-        acc = fma((double)c.y, (double)x.y, acc);
-        acc = fma((double)c.z, (double)x.z, acc);
-        acc = fma((double)c.w, (double)x.w, acc);
+#pragma unroll 1
+    for (int d0 = 0; d0 < DIM; d0 += 32) {
+        float4 c[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) c[u] = *reinterpret_cast<const float4 *>(crow + d0 + 4 * u);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float4 x = *reinterpret_cast<const float4 *>(qrow + d0 + 4 * u);
+            acc = fma((double)c[u].x, (double)x.x, acc);
+            acc = fma((double)c[u].y, (double)x.y, acc);
+            acc = fma((double)c[u].z, (double)x.z, acc);
+            acc = fma((double)c[u].w, (double)x.w, acc);
+        }
     }
     return (float)acc;
 }
@@ -129,7 +137,7 @@ __device__ void stage1_survivor_table(const float *__restrict__ Sq, int64_t C, c
                                       int32_t *__restrict__ kept_ids_q, float *__restrict__ Tq, int32_t *scan /*[waves]*/,
                                       int32_t *ids /*[S2_MAX_KEPT + 1]*/, uint32_t *trial /*[S2_NHASH][S2_HASH / 32]*/,
                                       float *colmm /*[2][32]*/, int32_t *misc /*[2]*/, const float *__restrict__ Cm = nullptr,
-                                      const float *__restrict__ Qq = nullptr)
+                                      const float *Qq = nullptr /* the query's rows, in LDS */)
 {
     auto keep_word = [&](int64_t w) -> uint32_t {
         if (APPROX) return __hip_atomic_load(kb + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -662,7 +670,16 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
     const float *__restrict__ Sq = S + (int64_t)q * C * QLEN;
     const float *__restrict__ tmq = tilemax + (int64_t)q * nblk * QLEN;
     const float margin = APPROX ? x.margin : 0.f;
-    const float *__restrict__ Qq = APPROX ? x.Q + (int64_t)q * QLEN * DIM : nullptr;
+    // APPROX: the query's rows in LDS for the re-evaluations, and per token the rows to re-evaluate
+    constexpr int TAIL_XCAP = TAIL_LANES;  // listed rows per token: one per lane
+    __shared__ __align__(16) float Qs[APPROX ? QLEN * DIM : 4];
+    __shared__ int32_t xc_id[APPROX ? QLEN : 1][TAIL_XCAP];
+    __shared__ int32_t xc_cnt[QLEN];
+    const float *Qq = Qs;
+    if (APPROX) {
+        static_assert(TAIL_THREADS * 4 == QLEN * DIM, "one 16-byte load per thread stages the query");
+        *reinterpret_cast<float4 *>(Qs + 4 * tid) = *reinterpret_cast<const float4 *>(x.Q + (int64_t)q * QLEN * DIM + 4 * tid);
+    }
     {
         // pass 1: thread (tokens 4 tk4 .. 4 tk4 + 3, part) keeps the NP largest maxima of tiles part, part + 128, ...
         const int tk4 = tid % (QLEN / 4), part = tid / (QLEN / 4);
@@ -729,6 +746,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
         if (l == 0) {
             Tsh[i] = T;
             sel_cnt[i] = 0;
+            xc_cnt[i] = 0;
         }
     }
     __syncthreads();
@@ -768,30 +786,51 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
         const bool listed = n_sel <= TAIL_SEL;
         const int chunks = (tile_rows + TAIL_LANES - 1) / TAIL_LANES;  // 32-row pieces of a tile
         const int n_items = (listed ? n_sel : nblk) * chunks;
-        for (int it0 = 0; it0 < n_items; it0 += 4) {
-            float sv[4];
-            int64_t cc[4];
-            bool ok[4];
+        // walk: every listed row with its score; what happens to a row is up to `visit`
+        auto walk = [&](auto visit) {
+            for (int it0 = 0; it0 < n_items; it0 += 4) {
+                float sv[4];
+                int64_t cc[4];
+                bool ok[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int it = it0 + u;
-                ok[u] = it < n_items;
-                const int k = ok[u] ? it / chunks : 0, r = (it % chunks) * TAIL_LANES + l;
-                const int t = listed ? sel_tile[i][k] : k;
-                if (!listed && ok[u]) ok[u] = tmq[(int64_t)t * QLEN + i] >= T;
-                cc[u] = (int64_t)t * tile_rows + r;
-                ok[u] = ok[u] && r < tile_rows && cc[u] < C;
-                sv[u] = ok[u] ? Sq[cc[u] * QLEN + i] : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (APPROX) {
-                    // only a row that can be among the nprobe best is ranked, by its exact score
-                    if (ok[u] && sv[u] >= T)
-                        scq_insert_key<NP>(best, plaid_make_key(scq_exact_entry(x.Cm + cc[u] * DIM, Qq + i * DIM), (uint32_t)cc[u]));
-                } else if (ok[u]) {
-                    scq_insert_key<NP>(best, plaid_make_key(sv[u], (uint32_t)cc[u]));
+                for (int u = 0; u < 4; ++u) {
+                    const int it = it0 + u;
+                    ok[u] = it < n_items;
+                    const int k = ok[u] ? it / chunks : 0, r = (it % chunks) * TAIL_LANES + l;
+                    const int t = listed ? sel_tile[i][k] : k;
+                    if (!listed && ok[u]) ok[u] = tmq[(int64_t)t * QLEN + i] >= T;
+                    cc[u] = (int64_t)t * tile_rows + r;
+                    ok[u] = ok[u] && r < tile_rows && cc[u] < C;
+                    sv[u] = ok[u] ? Sq[cc[u] * QLEN + i] : 0.f;
                 }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (ok[u]) visit(sv[u], cc[u]);
+            }
+        };
+        if (!APPROX) {
+            walk([&](float sv, int64_t cc) { scq_insert_key<NP>(best, plaid_make_key(sv, (uint32_t)cc)); });
+        } else {
+            // Only a row that can be among the nprobe best (score >= T - 2 eps) is ranked, and by its exact score.  The
+            // rows are listed first and re-evaluated one per lane, all at once; a token with more such rows than lanes
+            // (many equal scores) re-evaluates them as it meets them.
+            walk([&](float sv, int64_t cc) {
+                if (sv >= T) {
+                    const int pos = atomicAdd(&xc_cnt[i], 1);
+                    if (pos < TAIL_XCAP) xc_id[i][pos] = (int32_t)cc;
+                }
+            });
+            __syncthreads();
+            const int n_x = xc_cnt[i];
+            if (n_x <= TAIL_XCAP) {
+                if (l < n_x) {
+                    const int32_t c = xc_id[i][l];
+                    best[0] = plaid_make_key(scq_exact_entry(x.Cm + (int64_t)c * DIM, Qq + i * DIM), (uint32_t)c);
+                }
+            } else {
+                walk([&](float sv, int64_t cc) {
+                    if (sv >= T) scq_insert_key<NP>(best, plaid_make_key(scq_exact_entry(x.Cm + cc * DIM, Qq + i * DIM), (uint32_t)cc));
+                });
             }
         }
         // shuffle tree over the 32 lanes of this token (lanes l and l ^ d exchange lists; both keep the merged list)

@@ -27,7 +27,7 @@ typedef float scq16_floatx16 __attribute__((ext_vector_type(16)));
 #define H16_THREADS 256
 #define H16_WAVES (H16_THREADS / 64)
 #define H16_NT 2                                  // 32-row tiles per wave
-#define H16_WG_TILES (H16_WAVES * H16_NT)         // tiles per workgroup
+#define H16_WG_TILES (H16_WAVES * H16_NT)         // tiles per workgroup (the operand table is padded to a multiple of it)
 #define H16_STEPS (DIM / 16)                      // matrix instructions along the 128 dimensions
 #define H16_TILE_VEC (2 * H16_STEPS * 64)         // 16-byte operand vectors per tile: [term][step][lane]
 #define H16_SCALE 2048.0f                         // 2^11: keeps the second term in fp16's normal range
@@ -65,92 +65,130 @@ __global__ __launch_bounds__(256) void scq16_split_kernel(const float *__restric
     }
 }
 
-// Grid: x = block of 256 centroids, y = group of qg queries.  A16: ceil(C / 256) * 8 tiles (rows past C are zero).
-// keepbits / ambbits: [q][keep_words], bit c = row c passes Eq. 5 for sure / is ambiguous; tilemax: [q][ceil(C/32)][32].
-__global__ __launch_bounds__(H16_THREADS, 2) void scq16_kernel(const scq16_half8 *__restrict__ A16, int64_t C,
-                                                               const scq16_half8 *__restrict__ B16, int nq, int qg,
-                                                               float t_lo, float t_hi, float *__restrict__ S,
-                                                               uint32_t *__restrict__ keepbits, uint32_t *__restrict__ ambbits,
-                                                               int64_t keep_words, float *__restrict__ tilemax)
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() would also wait for every outstanding global
+// store, and this kernel keeps a query's worth of score stores in flight per wave when it reaches the barrier.
+__device__ __forceinline__ void scq16_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Grid: x = block of 32 * H16_WAVES * NT centroids, y = group of qg queries.  A16: a whole number of workgroups' tiles
+// (rows past C are zero).  keepbits / ambbits: [q][keep_words], bit c = row c passes Eq. 5 for sure / is ambiguous;
+// tilemax: [q][ceil(C/32)][32].
+// The loop over the group's queries is software-pipelined so that no wait covers a score store: the operands of query
+// q + 1 are requested before the matrix instructions of query q, moved into the other LDS buffer right after them (by
+// then they have arrived), the operands of q + 2 are requested, and only then are the scores of q stored.
+template <int NT>
+__global__ __launch_bounds__(H16_THREADS, NT == 2 ? 2 : 4) void scq16_kernel(
+    const scq16_half8 *__restrict__ A16, int64_t C, const scq16_half8 *__restrict__ B16, int nq, int qg, float t_lo, float t_hi,
+    float *__restrict__ S, uint32_t *__restrict__ keepbits, uint32_t *__restrict__ ambbits, int64_t keep_words,
+    float *__restrict__ tilemax)
 {
     __shared__ scq16_half8 Bs[2][H16_TILE_VEC];
+    constexpr int NPRE = H16_TILE_VEC / H16_THREADS;  // operand vectors a thread moves per query
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t tile0 = ((int64_t)blockIdx.x * H16_WAVES + wave) * H16_NT;
+    const int64_t tile0 = ((int64_t)blockIdx.x * H16_WAVES + wave) * NT;
     const int64_t n_blk = (C + 31) >> 5;
     const int q_begin = blockIdx.y * qg, q_end = q_begin + qg < nq ? q_begin + qg : nq;
 
-    scq16_half8 pre[H16_TILE_VEC / H16_THREADS];
+    scq16_half8 pre[NPRE];
     const scq16_half8 *bsrc = B16 + (int64_t)q_begin * H16_TILE_VEC + tid;
 #pragma unroll
-    for (int k = 0; k < H16_TILE_VEC / H16_THREADS; ++k) pre[k] = bsrc[k * H16_THREADS];
+    for (int k = 0; k < NPRE; ++k) pre[k] = bsrc[k * H16_THREADS];
 
-    scq16_half8 a[H16_NT][2][H16_STEPS];
+    scq16_half8 a[NT][2][H16_STEPS];
 #pragma unroll
-    for (int t = 0; t < H16_NT; ++t)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int term = 0; term < 2; ++term)
 #pragma unroll
             for (int s = 0; s < H16_STEPS; ++s)
                 a[t][term][s] = A16[((tile0 + t) * 2 + term) * (H16_STEPS * 64) + s * 64 + lane];
 
+#pragma unroll
+    for (int k = 0; k < NPRE; ++k) Bs[0][tid + k * H16_THREADS] = pre[k];
+    if (q_begin + 1 < q_end) {
+        bsrc += H16_TILE_VEC;
+#pragma unroll
+        for (int k = 0; k < NPRE; ++k) pre[k] = bsrc[k * H16_THREADS];
+    }
+    scq16_lds_barrier();
+
     for (int q = q_begin; q < q_end; ++q) {
-        scq16_half8 *buf = Bs[(q - q_begin) & 1];
+        const scq16_half8 *buf = Bs[(q - q_begin) & 1];
+        scq16_half8 *nxt = Bs[(q - q_begin + 1) & 1];
+        scq16_floatx16 hi[NT], lo[NT];
 #pragma unroll
-        for (int k = 0; k < H16_TILE_VEC / H16_THREADS; ++k) buf[tid + k * H16_THREADS] = pre[k];
-        // one barrier per query: it publishes this buffer, and a wave reaches it only after its reads of the other buffer
-        __syncthreads();
-        if (q + 1 < q_end) {
-            bsrc += H16_TILE_VEC;
-#pragma unroll
-            for (int k = 0; k < H16_TILE_VEC / H16_THREADS; ++k) pre[k] = bsrc[k * H16_THREADS];
-        }
-        scq16_floatx16 hi[H16_NT], lo[H16_NT];
-#pragma unroll
-        for (int t = 0; t < H16_NT; ++t)
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int v = 0; v < 16; ++v) hi[t][v] = 0.f, lo[t][v] = 0.f;
 #pragma unroll
         for (int s = 0; s < H16_STEPS; ++s) {
             const scq16_half8 b1 = buf[s * 64 + lane], b2 = buf[(H16_STEPS + s) * 64 + lane];
 #pragma unroll
-            for (int t = 0; t < H16_NT; ++t) {
+            for (int t = 0; t < NT; ++t) {
                 hi[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[t][0][s], b1, hi[t], 0, 0, 0);
                 lo[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[t][0][s], b2, lo[t], 0, 0, 0);
                 lo[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[t][1][s], b1, lo[t], 0, 0, 0);
             }
         }
+        // the next query's operands: into the buffer that every wave finished reading before the last barrier
+        if (q + 1 < q_end) {
+#pragma unroll
+            for (int k = 0; k < NPRE; ++k) nxt[tid + k * H16_THREADS] = pre[k];
+        }
+        if (q + 2 < q_end) {
+            bsrc += H16_TILE_VEC;
+#pragma unroll
+            for (int k = 0; k < NPRE; ++k) pre[k] = bsrc[k * H16_THREADS];
+        }
         // Epilogue.  Accumulator v of lane 32 h + n is row 8 (v / 4) + 4 h + v % 4 of the tile, column (query token) n.
 #pragma unroll
-        for (int t = 0; t < H16_NT; ++t) {
+        for (int t = 0; t < NT; ++t) {
             const int64_t tile = tile0 + t;
             if (tile >= n_blk) break;  // (uniform) a tile past the end of the table
             const int64_t row0 = tile << 5;
             const int nvalid = C - row0 < 32 ? (int)(C - row0) : 32;
             float *srow = S + ((int64_t)q * C + row0 + 4 * h) * QLEN + n;
-            float cmax = -INFINITY;
-            uint32_t maybe = 0u;  // uniform: bit = row of the tile with an entry >= t_lo
             float val[16];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int r = 8 * (v >> 2) + (v & 3);  // + 4 h
-                val[v] = fmaf(lo[t][v], 1.0f / H16_SCALE, hi[t][v]);
-                if (nvalid == 32 || r + 4 * h < nvalid) {
-                    srow[r * QLEN] = val[v];
+            for (int v = 0; v < 16; ++v) val[v] = fmaf(lo[t][v], 1.0f / H16_SCALE, hi[t][v]);
+            float cmax = -INFINITY;
+            if (nvalid == 32) {  // (uniform) a whole tile: sixteen unconditional stores of two 128-byte rows each, marked
+                                 // as streaming (4 GB per launch pass through: nothing of it is worth a cache line)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    __builtin_nontemporal_store(val[v], &srow[(8 * (v >> 2) + (v & 3)) * QLEN]);
                     cmax = fmaxf(cmax, val[v]);
                 }
-                const unsigned long long m = __ballot(val[v] >= t_lo);
-                maybe |= (((uint32_t)m) ? 1u : 0u) << r;
-                maybe |= (((uint32_t)(m >> 32)) ? 1u : 0u) << (r + 4);
-            }
-            uint32_t sure = 0u;
-            if (maybe) {  // uniform, and rare: few rows come near the threshold
+            } else {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int r = 8 * (v >> 2) + (v & 3);
-                    const unsigned long long m = __ballot(val[v] >= t_hi);
-                    sure |= (((uint32_t)m) ? 1u : 0u) << r;
-                    sure |= (((uint32_t)(m >> 32)) ? 1u : 0u) << (r + 4);
+                    if (r + 4 * h < nvalid) {
+                        srow[r * QLEN] = val[v];
+                        cmax = fmaxf(cmax, val[v]);
+                    }
+                }
+            }
+            // Eq. 5.  A row can only pass when some lane's maximum reaches t_lo, which no lane's does for all but a few
+            // tiles: one comparison settles those.  (Rows past the end hold zeros and are masked below.)
+            float lmax = val[0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) lmax = fmaxf(lmax, val[v]);
+            uint32_t maybe = 0u, sure = 0u;  // uniform: bit = row of the tile with an entry >= t_lo / >= t_hi
+            if (__ballot(lmax >= t_lo) != 0ull) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = 8 * (v >> 2) + (v & 3);
+                    const unsigned long long m = __ballot(val[v] >= t_lo), ms = __ballot(val[v] >= t_hi);
+                    maybe |= (((uint32_t)m) ? 1u : 0u) << r;
+                    maybe |= (((uint32_t)(m >> 32)) ? 1u : 0u) << (r + 4);
+                    sure |= (((uint32_t)ms) ? 1u : 0u) << r;
+                    sure |= (((uint32_t)(ms >> 32)) ? 1u : 0u) << (r + 4);
                 }
             }
             const uint32_t valid = nvalid == 32 ? 0xFFFFFFFFu : (1u << nvalid) - 1u;  // rows past the end never pass
@@ -161,6 +199,7 @@ __global__ __launch_bounds__(H16_THREADS, 2) void scq16_kernel(const scq16_half8
                 ambbits[(int64_t)q * keep_words + tile] = maybe & ~sure & valid;
             }
         }
+        scq16_lds_barrier();  // publishes nxt; every wave is done reading buf
     }
 }
 
@@ -209,6 +248,6 @@ void plaid_launch_scq16(hipStream_t st, const void *A16, int64_t C, const void *
     if (qg > 64) qg = 64;
     if (qg > nq) qg = nq;
     const unsigned gy = (unsigned)((nq + qg - 1) / qg);
-    hipLaunchKernelGGL(scq16_kernel, dim3(gx, gy), dim3(H16_THREADS), 0, st, (const scq16_half8 *)A16, C, (const scq16_half8 *)B16, nq,
-                       qg, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax);
+    hipLaunchKernelGGL(scq16_kernel<H16_NT>, dim3(gx, gy), dim3(H16_THREADS), 0, st, (const scq16_half8 *)A16, C,
+                       (const scq16_half8 *)B16, nq, qg, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax);
 }

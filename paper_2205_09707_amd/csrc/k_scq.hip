@@ -97,6 +97,7 @@ struct Stage1Out {          // per-query outputs of the tail (device pointers, l
     S2Meta *meta;           // [nq]
     int32_t *kept_ids;      // [nq][S2_MAX_KEPT]
     float *T;               // [nq][S2_MAX_KEPT + 1][32]
+    const int64_t *ivf_offsets;  // [C + 1] inverted-list offsets: slots are numbered by list length (null: by id)
 };
 
 // One entry of S_cq as the definition reads: the products of the 128 dimensions accumulated in double in index order
@@ -132,12 +133,13 @@ __device__ __forceinline__ float scq_exact_entry(const float *__restrict__ crow,
 // atomics, so they are read past the first-level cache, and the rows of T are re-evaluated in double from the centroids
 // Cm and the query Qq, which makes every stage-2 score that is built from T the exact one.
 template <bool APPROX>
-__device__ void stage1_survivor_table(const float *__restrict__ Sq, int64_t C, const uint32_t *__restrict__ kb,
+__device__ __forceinline__ void stage1_survivor_table(const float *__restrict__ Sq, int64_t C, const uint32_t *__restrict__ kb,
                                       int64_t keep_words, const int32_t *top1, S2Meta *meta_q,
                                       int32_t *__restrict__ kept_ids_q, float *__restrict__ Tq, int32_t *scan /*[waves]*/,
                                       int32_t *ids /*[S2_MAX_KEPT + 1]*/, uint32_t *trial /*[S2_NHASH][S2_HASH / 32]*/,
                                       float *colmm /*[2][32]*/, int32_t *misc /*[2]*/, const float *__restrict__ Cm = nullptr,
-                                      const float *Qq = nullptr /* the query's rows, in LDS */)
+                                      const float *Qq = nullptr /* the query's rows, in LDS */,
+                                      const int64_t *__restrict__ ivf_offsets = nullptr)
 {
     auto keep_word = [&](int64_t w) -> uint32_t {
         if (APPROX) return __hip_atomic_load(kb + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -181,6 +183,24 @@ __device__ void stage1_survivor_table(const float *__restrict__ Sq, int64_t C, c
     }
     int K = misc[0];
     if (C > (1ll << 26) - 2 && K <= S2_MAX_KEPT) K = S2_MAX_KEPT + 1;  // ids must fit the 26-bit field of a table entry
+    // Slots in the order of decreasing inverted-list length (ties: smaller id first): the centroids most passages hold
+    // get the lowest slots, which stage 2 scores through a table of their subsets.
+    if (ivf_offsets && K > 1 && K <= S2_MAX_KEPT) {
+        int32_t my_id = 0;
+        int rank = 0;
+        if (tid < K) {
+            my_id = ids[tid];
+            const int64_t my_len = ivf_offsets[my_id + 1] - ivf_offsets[my_id];
+            for (int u = 0; u < K; ++u) {
+                const int32_t c = ids[u];
+                const int64_t len = ivf_offsets[c + 1] - ivf_offsets[c];
+                rank += (len > my_len || (len == my_len && u < tid)) ? 1 : 0;
+            }
+        }
+        __syncthreads();
+        if (tid < K) ids[rank] = my_id;
+        __syncthreads();
+    }
     // a hash h(c) = (c ^ (c >> sh)) & (S2_HASH - 1) that maps the survivors to distinct entries makes a lookup one
     // probe; thread t tries shift S2_SHIFT0 + t on a private bitmap.  No such shift (very rare): gather kernel.
     if (K <= S2_MAX_KEPT) {
@@ -255,7 +275,7 @@ __global__ __launch_bounds__(512) void stage1_survivor_kernel(const float *__res
     __syncthreads();
     stage1_survivor_table<false>(S + (int64_t)q * C * QLEN, C, keepbits + (int64_t)q * keep_words, keep_words, top1, o.meta + q,
                                  o.kept_ids + (int64_t)q * S2_MAX_KEPT, o.T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN, scan, ids,
-                                 trial, colmm, misc);
+                                 trial, colmm, misc, nullptr, nullptr, o.ivf_offsets);
 }
 
 // tilemax: [q][tile][32] column maxima of each tile (null: scores and pruning bits only).
@@ -927,7 +947,8 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
     }
     stage1_survivor_table<APPROX>(S + (int64_t)q * C * QLEN, C, keepbits + (int64_t)q * keep_words, keep_words, top1,
                                   o.meta + q, o.kept_ids + (int64_t)q * S2_MAX_KEPT,
-                                  o.T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN, scan, ids, trial, colmm, misc, x.Cm, Qq);
+                                  o.T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN, scan, ids, trial, colmm, misc, x.Cm, Qq,
+                                  o.ivf_offsets);
 }
 
 // np = capacity of the tail's lists (1, 2, 4 or 8 >= nprobe); np = 0: scores and pruning bits only (large nprobe).
@@ -1011,6 +1032,7 @@ void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int
     o.meta = s2.meta;
     o.kept_ids = s2.kept_ids;
     o.T = s2.T;
+    o.ivf_offsets = s2.ivf_offsets;
     const int np = nprobe == 1 ? 1 : (nprobe == 2 ? 2 : (nprobe <= 4 ? 4 : (nprobe <= PLAID_PROBE_FAST_MAX ? 8 : 0)));
     if (np > 0)
         launch_fused(st, phases, np, centroids, C, Q, Qd, form, A16, nq, t_cs, S, keepbits, ambbits, keep_words, tilemax, nprobe,

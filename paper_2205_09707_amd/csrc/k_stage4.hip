@@ -1,22 +1,38 @@
 // Stage 4 (Sections 4.4-4.5): residual decompression fused with exact MaxSim (Eq. 1).
 //
 // Decompression follows the lookup-table idea of Section 4.5: a packed byte indexes a 256-entry
-// table held in LDS.  The table stores the bucket WEIGHTS of the byte's dimensions (4 for 2-bit,
-// 8 for 1-bit codes) instead of the bucket indices, so one 16-byte LDS read yields four residual
-// values.  A reconstructed token is centroid + residual, so its dot product with a query token
-// is S_cq[code][i] (already computed, Eq. 2) plus the residual's dot product: the scoring kernel
-// gathers the 128-byte S_cq row of each token instead of its 512-byte centroid, and the decoded
-// 32-token x 128 residual tile never leaves registers: each lane decodes the half row of its own
-// passage token and feeds it as the A operand of v_mfma_f32_32x32x2_f32 against the query
-// (B operand, 64 VGPRs), giving a 32 passage-token x 32 query-token block whose column maxima,
-// after the S_cq term is added, are the MaxSim terms.  The standalone decompression kernel below
-// produces the reconstructed vectors themselves (centroid + weight, one fp32 addition).
+// table held in LDS.  A reconstructed token is centroid + residual, so its dot product with a query
+// token is S_cq[code][i] (already computed, Eq. 2) plus the residual's dot product: the scoring kernel
+// gathers the 128-byte S_cq row of each token instead of its 512-byte centroid and contracts only the
+// residuals, which take one of 2^nbits bucket weights per dimension.
+//
+// The contraction runs on the half-precision matrix instruction with both operands split into two fp16
+// terms, x = x1 + 2^-11 x2 (|x - x1 - 2^-11 x2| <= 2^-22 |x|): three products per term, each exact in
+// fp32, the leading one in one accumulator and the two cross terms in a second, scaled one.  The table
+// therefore stores, per byte value, the fp16 terms of the bucket weights of the byte's dimensions, in
+// the order the instruction wants them: one 16-byte LDS read yields the operand halves of four
+// dimensions (2-bit codes) or the eight leading / eight trailing terms of a byte (1-bit codes), and the
+// decoded 32-token x 128 residual tile never leaves registers.  Against fp32 arithmetic the residual's
+// dot product loses at most 3 * 2^-22 |r||q|, far inside the score tolerance; it is 16 times cheaper on
+// the matrix pipe, which leaves the kernel bound by its gathers and its decoding.
+// The standalone decompression kernel below produces the reconstructed vectors themselves
+// (centroid + weight, one fp32 addition).
 #include "plaid_internal.h"
 
 #include <math.h>
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef _Float16 s4_half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 s4_half4 __attribute__((ext_vector_type(4)));
 #define S4_RESIDENT_BLOCKS 768
+#define S4_SCALE 2048.0f  // 2^11
+
+// The two fp16 terms of x: x1 = fp16(x) (0 below fp16's normal range), x2 = fp16(2^11 (x - x1)).
+__device__ __forceinline__ void s4_split(float x, _Float16 &x1, _Float16 &x2)
+{
+    x1 = fabsf(x) >= 6.103515625e-05f ? (_Float16)x : (_Float16)0.0f;
+    x2 = (_Float16)((x - (float)x1) * S4_SCALE);
+}
 
 // Table entry (byte v, quad s): weights of dimensions 4s .. 4s+3 of the 8/NBITS dimensions packed in v.
 // Bucket indices are stored most-significant first.
@@ -45,8 +61,34 @@ __device__ __forceinline__ int table_slot(const uint8_t *__restrict__ r, int qua
     return 2 * r[quad >> 1] + (quad & 1);
 }
 
-// Passages are scored 32 tokens per step.  Lane = 32 h + r: for the A operand r is the passage token of the step and
-// h the half of each 8-dimension group, for the B operand and the result r is the query token.
+// Operand table of the scoring kernel.  2-bit codes: hlut[v] = {x1 of the byte's four dimensions, x2 of the same}.
+// 1-bit codes: hlut[v] = x1 of the byte's eight dimensions, hlut[256 + v] = their x2.
+template <int NBITS>
+__device__ __forceinline__ void build_half_tables(s4_half8 *hlut, const float *__restrict__ weights, int tid, int nthreads)
+{
+    for (int v = tid; v < 256; v += nthreads) {
+        s4_half8 a, b;
+#pragma unroll
+        for (int d = 0; d < 8 / NBITS; ++d) {
+            const int idx = (v >> (8 - NBITS * (d + 1))) & ((1 << NBITS) - 1);
+            _Float16 x1, x2;
+            s4_split(weights[idx], x1, x2);
+            if (NBITS == 2) {
+                a[d] = x1;
+                a[4 + d] = x2;
+            } else {
+                a[d] = x1;
+                b[d] = x2;
+            }
+        }
+        hlut[v] = a;
+        if (NBITS == 1) hlut[256 + v] = b;
+    }
+}
+
+// Passages are scored 32 tokens per step with v_mfma_f32_32x32x16_f16.  Lane = 32 h + r: for the A operand r is the
+// passage token of the step, for the B operand and the result r is the query token; both operands hold dimensions
+// 16 s + 8 h .. 16 s + 8 h + 7 at step s of the 128 dimensions.
 // COOP = false: one wave scores one passage at a time and the waves of the grid stride over the query's list (many
 // passages per wave: throughput).  COOP = true: the four waves of a workgroup share a passage, each taking every
 // fourth step, and combine their maxima in LDS (short lists: latency).
@@ -58,7 +100,7 @@ __global__ __launch_bounds__(256, 3) void decompress_maxsim_kernel(
     uint64_t *__restrict__ out_keys, int64_t out_stride)
 {
     constexpr int RB = 16 * NBITS;
-    __shared__ float4 wlut[256 * (NBITS == 2 ? 1 : 2)];
+    __shared__ s4_half8 hlut[256 * (NBITS == 2 ? 1 : 2)];
     __shared__ float wmax[4][QLEN];
     const int q = blockIdx.y;
     const int count = in_counts[q];
@@ -66,12 +108,24 @@ __global__ __launch_bounds__(256, 3) void decompress_maxsim_kernel(
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r32 = lane & 31, h = lane >> 5;
-    build_tables<NBITS>(wlut, nullptr, weights, threadIdx.x, 256);
+    build_half_tables<NBITS>(hlut, weights, threadIdx.x, 256);
     const float *Qq = Q + (int64_t)q * QLEN * DIM;
     const float *Sq = S + (int64_t)q * C * QLEN;
-    float4 qf[16];
+    // B operands: the two fp16 terms of query token r32, dimensions 16 s + 8 h .. + 7
+    s4_half8 q1[8], q2[8];
 #pragma unroll
-    for (int g = 0; g < 16; ++g) qf[g] = *reinterpret_cast<const float4 *>(Qq + r32 * DIM + 8 * g + 4 * h);
+    for (int s = 0; s < 8; ++s) {
+        const float4 *p = reinterpret_cast<const float4 *>(Qq + r32 * DIM + 16 * s + 8 * h);
+        const float4 u = p[0], w = p[1];
+        const float x[8] = {u.x, u.y, u.z, u.w, w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            _Float16 x1, x2;
+            s4_split(x[j], x1, x2);
+            q1[s][j] = x1;
+            q2[s][j] = x2;
+        }
+    }
     __syncthreads();
 
     for (int j = COOP ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave; j < count; j += (int)gridDim.x * (COOP ? 1 : 4)) {
@@ -84,7 +138,7 @@ __global__ __launch_bounds__(256, 3) void decompress_maxsim_kernel(
         const int len = __builtin_amdgcn_readfirstlane((int)(doc_offsets[pid + 1] - t0v));
         float m = -INFINITY;  // running maximum for query token r32 over the rows this lane sees
         // The loop is software-pipelined: the code and packed residual of the next step and the S_cq values of this
-        // step are requested before this step's 64 matrix instructions are issued, so their latency runs under them.
+        // step are requested before this step's matrix instructions are issued, so their latency runs under them.
         constexpr int STEP = COOP ? 128 : 32;
         int base = COOP ? 32 * wave : 0;
         int32_t code = 0;
@@ -93,7 +147,7 @@ __global__ __launch_bounds__(256, 3) void decompress_maxsim_kernel(
             const int row = b + r32;  // this lane's passage token
             const int64_t tok = t0 + (row < len ? row : len - 1);
             c = codes[tok];
-            // the token's packed residual: both halves of the wave read all of it, each uses every other byte
+            // the token's packed residual: both halves of the wave read all of it, each uses half of the bytes
             const uint4 *rp = reinterpret_cast<const uint4 *>(residuals + tok * RB);
             const uint4 v0 = rp[0];
             r[0] = v0.x, r[1] = v0.y, r[2] = v0.z, r[3] = v0.w;
@@ -117,27 +171,32 @@ __global__ __launch_bounds__(256, 3) void decompress_maxsim_kernel(
             uint32_t rw_next[RB / 4] = {0};
             if (base + STEP < len) request(base + STEP, code_next, rw_next);  // uniform
             floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            floatx16 acx = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};  // cross terms, scaled by 2^11
 #pragma unroll
-            for (int g = 0; g < 16; ++g) {
-                // dimensions 8g+4h .. 8g+4h+3: byte 2g+h of a 2-bit code, half h of byte g of a 1-bit code
-                int slot;
-                if (NBITS == 2)
-                    slot = (rw[g >> 1] >> (16 * (g & 1) + 8 * h)) & 0xFF;
-                else
-                    slot = 2 * ((rw[g >> 2] >> (8 * (g & 3))) & 0xFF) + h;
-                const float4 w = wlut[slot];
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.x, qf[g].x, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.y, qf[g].y, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.z, qf[g].z, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.w, qf[g].w, acc, 0, 0, 0);
+            for (int s = 0; s < 8; ++s) {
+                // dimensions 16 s + 8 h .. + 7: bytes 4 s + 2 h and 4 s + 2 h + 1 of a 2-bit code, byte 2 s + h of a 1-bit one
+                s4_half8 a1, a2;
+                if (NBITS == 2) {
+                    const uint32_t two = rw[s] >> (16 * h);
+                    const s4_half8 e0 = hlut[two & 0xFF], e1 = hlut[(two >> 8) & 0xFF];
+                    a1 = s4_half8{e0[0], e0[1], e0[2], e0[3], e1[0], e1[1], e1[2], e1[3]};
+                    a2 = s4_half8{e0[4], e0[5], e0[6], e0[7], e1[4], e1[5], e1[6], e1[7]};
+                } else {
+                    const uint32_t b = (rw[s >> 1] >> (16 * (s & 1) + 8 * h)) & 0xFF;
+                    a1 = hlut[b];
+                    a2 = hlut[256 + b];
+                }
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, q1[s], acc, 0, 0, 0);
+                acx = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, q2[s], acx, 0, 0, 0);
+                acx = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, q1[s], acx, 0, 0, 0);
             }
             if (base + 32 <= len) {  // (uniform) a full step: every row counts
 #pragma unroll
-                for (int v = 0; v < 16; ++v) m = fmaxf(m, acc[v] + sv[v]);
+                for (int v = 0; v < 16; ++v) m = fmaxf(m, fmaf(acx[v], 1.0f / S4_SCALE, acc[v]) + sv[v]);
             } else {
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
-                    if (base + 8 * (v >> 2) + 4 * h + (v & 3) < len) m = fmaxf(m, acc[v] + sv[v]);
+                    if (base + 8 * (v >> 2) + 4 * h + (v & 3) < len) m = fmaxf(m, fmaf(acx[v], 1.0f / S4_SCALE, acc[v]) + sv[v]);
             }
             code = code_next;
 #pragma unroll

@@ -595,6 +595,7 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     w.s2.kept_ids = (int32_t *)take((size_t)qc * S2_MAX_KEPT * 4);
     w.s2.T = (float *)take((size_t)qc * (S2_MAX_KEPT + 1) * QLEN * 4);
     w.s2.emptybits = (uint32_t *)take((size_t)qc * w.cand_words * 4);
+    w.s2.ivf_offsets = ix->ivf_offsets;
     w.sel2 = (uint64_t *)take((size_t)qc * pl.nd * 8);
     w.n2 = (int32_t *)take((size_t)qc * 4);
     w.keys3 = (uint64_t *)take((size_t)qc * pl.nd * 8);

@@ -193,6 +193,8 @@ struct Stage2Buffers {   // all device pointers, leading dimension = query of th
     float *T;            // [nq][S2_MAX_KEPT+1][32] rows of the surviving centroids (slot 0 unused)
     uint32_t *emptybits; // [nq][cand_words] candidates whose bag is empty
     uint64_t *blist;     // [nq][P] boundary list after the bin filter
+    // of the index (null when there is none: nearest-centroid assignment)
+    const int64_t *ivf_offsets;  // [C + 1]: the probe kernel numbers the surviving centroids by list length
 };
 
 // Eq. 3-5 over every candidate: keys2[q][p] = key of candidate p (invalid key when its bag is empty; slots of

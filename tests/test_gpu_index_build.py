@@ -142,7 +142,8 @@ def test_index_built_on_the_gpu_searches_like_the_oracle(pl):
         for params in [(2, 0.45, 64, 10), (4, -np.inf, 1700, 30)]:
             out = pu.run_gpu_debug(pl, gidx, Qdev, params)
             for q in range(w.queries.shape[0]):
-                pu.compare_query(ix, w.queries[q].numpy(), params, pu.slice_query(out, q), ctx=f"gpu-built {params} q{q}")
+                pu.compare_query(ix, w.queries[q].numpy(), params, pu.slice_query(out, q), ctx=f"gpu-built {params} q{q}",
+                                 approx=pu.is_approx(pl, gidx, params))
     finally:
         pl.plaid_index_free(gidx)
 

@@ -26,16 +26,23 @@ FP64_MFMA_PEAK_TFLOPS = 78.6   # MI355X published dense fp64 matrix rate (the ve
 FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
 FP16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 / bf16 matrix rate
 
-# HBM bytes per launch (512 queries) of each kernel, from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs of this file,
-# each scaled by the counter's reading on a 1 GiB device copy (fetch reads half the bytes: x2; write: x1).
-# Source of every figure: the profiles/ summary named here.  Missing = not measured (reported as null).
-MEASURED_TRAFFIC_PER_LAUNCH = {
-    # (config, noise, stage): bytes; profiles/bench_cfg3.txt (KiB figures: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0)
-    ("cfg3", "literal", "scq"): int((140826.9 * 2.0 + 4388136.5) * 1024),
-    ("cfg3", "literal", "stage2_ci"): int(((33917.0 + 22424.0) * 2.0 + 83349.9 + 44937.9) * 1024),  # both stage-2 kernels
-    ("cfg3", "literal", "stage3_ci"): int((787106.7 * 2.0 + 4257.6) * 1024),
-    ("cfg3", "literal", "stage4_maxsim"): int((521646.1 * 2.0 + 1758.2) * 1024),
-}
+# HBM bytes per launch of each kernel as measured with `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` are read from the
+# profile summary that holds them (lines "traffic <config> <noise> <stage> <bytes per launch> <kernel ms in that run>"),
+# never typed in here: a stage without such a line reports null.
+PROFILE_WITH_TRAFFIC = os.path.join(ROOT, "profiles", "bench_cfg3.txt")
+
+
+def profiled_traffic():
+    """(config, noise, stage) -> (HBM bytes per launch, kernel ms per launch in the profiled run) from the profile summary."""
+    out = {}
+    try:
+        for line in open(PROFILE_WITH_TRAFFIC):
+            f = line.split()
+            if len(f) == 6 and f[0] == "traffic":
+                out[(f[1], f[2], f[3])] = (int(f[4]), float(f[5]))
+    except OSError:
+        pass
+    return out
 
 
 def log(*a):
@@ -131,8 +138,8 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
     out_ids = torch.empty((nq, cfg.k), dtype=torch.int32, device=dev)
     out_sc = torch.empty((nq, cfg.k), dtype=torch.float32, device=dev)
     # ---- throughput: K steps of the full batch, stage events on (they cost one sync per query chunk)
-    CHUNK = 512  # queries per internal launch (the library default)
-    pl.plaid_set_max_chunk(idx, CHUNK)
+    # queries per internal launch: the library's own choice (512, fewer when the per-query workspace is large: cfg4, cfg5)
+    _, CHUNK = pl.plaid_workspace_bytes(cfg.C, cfg.P, nq, cfg.nprobe, cfg.ndocs, cfg.k)
     launches = (nq + CHUNK - 1) // CHUNK
     pl.plaid_set_stage_timing(idx, True)
     for _ in range(args.warmup):
@@ -182,15 +189,19 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
     rooflines = {}
     if not args.no_roofline:
         work = algorithmic_work(pl, idx, w, Q, params, cfg)
+        traffic_table = profiled_traffic()
 
         def entry(stage, kernel, bound, amount, unit_scale, peak, unit, extra):
             t = stage_ms[stage] * 1e-3
             ach = amount / t / unit_scale if t > 0 else 0.0
-            traffic = MEASURED_TRAFFIC_PER_LAUNCH.get((cfg.name, noise, stage))
+            prof = traffic_table.get((cfg.name, noise, stage))
             e = {"bound": bound, "kernel": kernel, "achieved": round(ach, 1), "peak": peak, "unit": unit,
-                 "frac": round(ach / peak, 4), "traffic": traffic,
-                 # hardware bytes (rocprofv3 counters) over this run's kernel time, next to the algorithmic figure
-                 "traffic_gbs": round(traffic / (t / launches) / 1e9, 1) if traffic and t > 0 else None,
+                 "frac": round(ach / peak, 4),
+                 # hardware bytes per launch from the rocprofv3 counter runs recorded in the named profile summary (not
+                 # measured in this run), and the rate they give over the kernel time of that same profiled run
+                 "traffic": prof[0] if prof else None,
+                 "traffic_source": os.path.relpath(PROFILE_WITH_TRAFFIC, ROOT) if prof else None,
+                 "traffic_gbs_in_profiled_run": round(prof[0] / (prof[1] * 1e-3) / 1e9, 1) if prof and prof[1] > 0 else None,
                  "kernel_ms_per_step": round(stage_ms[stage], 4), "launches_per_step": launches, "queries_per_launch": CHUNK,
                  "kernel_ms_per_launch": round(stage_ms[stage] / launches, 4)}
             e.update(extra)
@@ -245,6 +256,17 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
 
     return {"w": w, "idx": idx, "Q": Q, "nq": nq, "params": params, "out_ids": out_ids, "qps": qps, "ms_per_step": ms_per_step,
             "stage_ms": stage_ms, "lat": lat, "enq": enq, "nlat": nlat, "roofline": roofline, "rooflines": rooflines}
+
+
+def memory_shortfall(torch, cfg):
+    """None when the configuration's index fits the free device memory three times over (generation temporaries, the
+    library's workspace), else the reason it does not."""
+    mean_len = {"cfg1": 40, "cfg2": 60, "cfg3": 65, "cfg4": 68, "cfg5": 70}.get(cfg.name, 70)
+    index_bytes = cfg.P * mean_len * (4 + 16 * cfg.nbits + 4)
+    free_dev, _ = torch.cuda.mem_get_info(0)
+    if free_dev < 3 * index_bytes:
+        return f"{free_dev / 2**30:.0f} GiB of free device memory, {3 * index_bytes / 2**30:.0f} GiB wanted for {cfg.name}"
+    return None
 
 
 def measured_copy_gbs(torch):
@@ -351,6 +373,8 @@ def main():
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--single-noise", action="store_true", help="skip the run on the other reading of the noise scale")
     ap.add_argument("--no-index-build", action="store_true", help="skip the timing of the index-construction calls")
+    ap.add_argument("--no-operating-points", action="store_true",
+                    help="skip the k = 10 (cfg2) and k = 1000 (cfg4) operating points reported beside the headline")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run four 1 GiB device-to-device copies (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -427,6 +451,35 @@ def main():
         del r2
     copy_gbs = measured_copy_gbs(torch)
     log(f"[bench] plain 1 GiB device copy: {copy_gbs} GB/s read + written (vendor HBM peak {HBM_PEAK_GBS:g})")
+    # ---- the other operating points of the metric (k = 10 and k = 1000; the headline configuration has k = 100):
+    # throughput of the full batch and batch-1 latency, both readings of the noise scale
+    points = None
+    if not args.no_operating_points and args.config == "cfg3":
+        points = {}
+        for name in ("cfg2", "cfg4"):
+            c2 = get_config(name)
+            short = memory_shortfall(torch, c2)
+            if short:
+                points[name] = {"skipped": short}
+                log(f"[bench] operating point {name} skipped: {short}")
+                continue
+            a2 = argparse.Namespace(**vars(args))
+            a2.no_roofline, a2.steps, a2.warmup = True, max(2, args.steps // 3), 1
+            a2.latency_queries = min(args.latency_queries, 128)
+            points[name] = {"k": c2.k, "nprobe": c2.nprobe, "t_cs": c2.t_cs, "ndocs": c2.ndocs}
+            for nz in ("literal", "calibrated"):
+                r3 = measure(pl, torch, np, c2, nz, a2, latency=True)
+                l3 = r3["lat"]
+                points[name][nz] = {
+                    "workload": f"{name} ({nz} noise): C={c2.C}, P={c2.P}, N={int(r3['w'].N)}, {c2.nbits}-bit, {r3['nq']} queries",
+                    "value": round(r3["qps"], 2), "unit": "queries/s", "ms_per_step": round(r3["ms_per_step"], 4), "steps": a2.steps,
+                    "stage2_kernel": "inverted" if pl.plaid_get_stage2_kernel(r3["idx"]) else "stream",
+                    "stage_ms_per_step": {s_: round(v, 4) for s_, v in r3["stage_ms"].items()},
+                    "latency_batch1_ms": {"p50": round(float(np.percentile(l3, 50)), 4), "p99": round(float(np.percentile(l3, 99)), 4),
+                                          "mean": round(float(l3.mean()), 4), "queries": int(r3["nlat"]), "trials": 3}}
+                pl.plaid_index_free(r3["idx"])
+                del r3
+                torch.cuda.empty_cache()
     build = None
     if not args.no_index_build:
         build = measure_index_build(pl, torch, np, cfg, args.noise, cpu=args.cpu_sample > 0)
@@ -448,7 +501,7 @@ def main():
                               "qps": round(1e3 / float(lat.mean()), 1) if nlat else None},
         "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items()},
         "roofline": roofline, "roofline_by_stage": rooflines or None, "cpu_baseline": cpu,
-        "other_noise_reading": other, "index_construction": build,
+        "other_noise_reading": other, "operating_points": points, "index_construction": build,
         "hbm": {"vendor_peak_gbs": HBM_PEAK_GBS, "measured_copy_gbs": copy_gbs},
     }
     print(json.dumps(line), flush=True)

@@ -34,8 +34,9 @@
 #define S2W_CAP (64 * 4 * S2_ITEMS - 32)  // tokens a wave stages per round (one byte each), whatever their alignment
 #define S2_LBWORDS ((S2_ITEMS + 3) / 4)   // words of the round's line bitmap (8 lines per item)
 #define S2_TSTRIDE 36    // floats per staged S_cq row (16-byte aligned, rows spread over the banks)
-#define IVR_SHIFT 11     // inverted form: a workgroup owns 2^IVR_SHIFT consecutive passages
-#define IVR_RANGE (1 << IVR_SHIFT)
+// Inverted form: a workgroup owns 2^SHIFT consecutive passages, SHIFT = 11 (256 threads) for indexes whose range table
+// stays small at that granularity, 13 (1024 threads) for large ones; both are instances of one kernel template.
+#define IVR_THREADS(SHIFT) (256 << ((SHIFT) - 11))
 static_assert(S2_LBWORDS <= 64, "one lane clears one word of the line bitmap");
 
 // ------------------------------------------------------------------ gather form (K > S2_MAX_KEPT)
@@ -149,7 +150,7 @@ __device__ __forceinline__ int s2_next_bit(unsigned long long m, int from)
 __device__ __forceinline__ void s2_flush_hist(const int32_t *lhist, int32_t *__restrict__ hist_q)
 {
     __syncthreads();
-    for (int e = threadIdx.x; e < SEL_BINS; e += S2_THREADS) {
+    for (int e = threadIdx.x; e < SEL_BINS; e += blockDim.x) {
         const int32_t n = lhist[e];
         if (n) atomicAdd(&hist_q[e], n);
     }
@@ -228,9 +229,9 @@ __device__ __forceinline__ void s2_stage_tables(int q, int K, int hsh, const int
                                                 const float *__restrict__ T, uint32_t *htab, float *Tl, float *rowsum)
 {
     const int tid = threadIdx.x;
-    for (int e = tid; e < S2_HASH; e += S2_THREADS) htab[e] = 0xFFFFFFFFu;
+    for (int e = tid; e < S2_HASH; e += blockDim.x) htab[e] = 0xFFFFFFFFu;
     const float *Tq = T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN;
-    for (int e = tid; e < (K + 1) * QLEN; e += S2_THREADS)
+    for (int e = tid; e < (K + 1) * QLEN; e += blockDim.x)
         Tl[(e >> 5) * S2_TSTRIDE + (e & 31)] = (e >> 5) ? Tq[e] : -INFINITY;
     __syncthreads();
     if (tid < K) {
@@ -462,27 +463,26 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
 // centroid).  So the candidate set is the union of the probed centroids' lists, and the pruned bag of a passage
 // (Eq. 5) is the set of surviving centroids whose lists contain it: both follow from the inverted lists of at most
 // 32 nprobe + S2_MAX_KEPT centroids, far fewer bytes than the candidates' token codes whenever few centroids
-// survive.  A workgroup owns a range of IVR_RANGE consecutive passages: it ORs the lists' entries that fall into
+// survive.  A workgroup owns a range of 2^SHIFT consecutive passages: it ORs the lists' entries that fall into
 // its range into 64-bit words in LDS (bit 0 = candidate, bit s = surviving slot s), then scores, emits keys, the bin
 // histogram, the candidate words and the empty-bag words of the range exactly as the streaming form does.  Where a
 // list enters a range comes from a table built once per index: table[c][r] = position in list c of its first entry
-// with passage id >= r * IVR_RANGE.
+// with passage id >= r * 2^SHIFT.
 #define IVR_EMPTY 0xFFFFFFFFu
-#define IVR_LISTS 256  // lists handled per LDS round (= threads of the workgroup)
+#define IVR_LISTS 256  // lists handled per LDS round (brought by the first IVR_LISTS threads of the workgroup)
 #define IVR_SHORT 64   // a list with at most this many entries in the range joins the pooled pass
 #define IVR_DENSE_DIV 16  // a list with at least P / 16 entries also gets a bitmap over the passages
-static_assert(IVR_LISTS == S2_THREADS, "one list per thread and round");
 
 // table[c][r] for every non-empty (list, range) pair; the others keep IVR_EMPTY until ivr_fill_kernel.
 __global__ __launch_bounds__(256) void ivr_mark_kernel(const int64_t *__restrict__ ivf_offsets,
                                                        const int32_t *__restrict__ ivf_pids, int64_t C, int64_t nr,
-                                                       uint32_t *__restrict__ table)
+                                                       int shift, uint32_t *__restrict__ table)
 {
     for (int64_t c = blockIdx.x; c < C; c += gridDim.x) {
         const int64_t s = ivf_offsets[c], t = ivf_offsets[c + 1];
         for (int64_t e = s + threadIdx.x; e < t; e += blockDim.x) {
-            const int64_t r = (int64_t)(uint32_t)ivf_pids[e] >> IVR_SHIFT;
-            const bool first = e == s || ((int64_t)(uint32_t)ivf_pids[e - 1] >> IVR_SHIFT) != r;
+            const int64_t r = (int64_t)(uint32_t)ivf_pids[e] >> shift;
+            const bool first = e == s || ((int64_t)(uint32_t)ivf_pids[e - 1] >> shift) != r;
             if (first && r < nr) table[c * (nr + 1) + r] = (uint32_t)(e - s);
         }
     }
@@ -503,17 +503,17 @@ __global__ __launch_bounds__(256) void ivr_fill_kernel(const int64_t *__restrict
     }
 }
 
-size_t plaid_ivf_range_table_bytes(int64_t C, int64_t P)
+size_t plaid_ivf_range_table_bytes(int64_t C, int64_t P, int shift)
 {
-    const int64_t nr = (P + IVR_RANGE - 1) >> IVR_SHIFT;
+    const int64_t nr = (P + (1ll << shift) - 1) >> shift;
     return (size_t)C * (size_t)(nr + 1) * sizeof(uint32_t);
 }
 void plaid_launch_ivf_range_table(hipStream_t st, const int64_t *ivf_offsets, const int32_t *ivf_pids, int64_t C, int64_t P,
-                                  uint32_t *table)
+                                  int shift, uint32_t *table)
 {
-    const int64_t nr = (P + IVR_RANGE - 1) >> IVR_SHIFT;
+    const int64_t nr = (P + (1ll << shift) - 1) >> shift;
     plaid_launch_fill_u32(st, table, C * (nr + 1), IVR_EMPTY);
-    hipLaunchKernelGGL(ivr_mark_kernel, dim3((unsigned)(C < 8192 ? C : 8192)), dim3(256), 0, st, ivf_offsets, ivf_pids, C, nr, table);
+    hipLaunchKernelGGL(ivr_mark_kernel, dim3((unsigned)(C < 8192 ? C : 8192)), dim3(256), 0, st, ivf_offsets, ivf_pids, C, nr, shift, table);
     hipLaunchKernelGGL(ivr_fill_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, ivf_offsets, C, nr, table);
 }
 
@@ -558,10 +558,16 @@ void plaid_launch_ivf_dense_fill(hipStream_t st, const int64_t *ivf_offsets, con
                        P, dense_id, bits, words);
 }
 
-// Exclusive prefix sum of one value per thread over the workgroup, into out[0 .. S2_THREADS]; scratch: one int per wave.
+// Exclusive prefix sum of one value per thread over the first IVR_LISTS threads of the workgroup, into
+// out[0 .. IVR_LISTS]; scratch: one int per wave of those threads.  All threads of the workgroup call this.
 __device__ __forceinline__ void ivr_block_scan(int v, int32_t *out, int32_t *wave_tot)
 {
     const int tid = threadIdx.x, lane = tid & 63;
+    if (tid >= IVR_LISTS) {  // (whole waves) the other threads only keep the barriers company
+        __syncthreads();
+        __syncthreads();
+        return;
+    }
     int incl = v;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -582,21 +588,21 @@ struct IvrLists {
     int64_t long_start[IVR_LISTS];              // compacted lists with more than IVR_SHORT entries in the range
     int32_t long_cnt[IVR_LISTS];
     unsigned long long long_val[IVR_LISTS];
-    int64_t short_start[S2_THREADS];            // per thread: its list when it has 1 .. IVR_SHORT entries in the range
-    unsigned long long short_val[S2_THREADS];
-    int32_t pref[S2_THREADS + 1];               // packed prefix sums: long-list count << 20 | short entries
-    int32_t wave_tot[S2_THREADS / 64];
+    int64_t short_start[IVR_LISTS];             // per thread: its list when it has 1 .. IVR_SHORT entries in the range
+    unsigned long long short_val[IVR_LISTS];
+    int32_t pref[IVR_LISTS + 1];                // packed prefix sums: long-list count << 20 | short entries
+    int32_t wave_tot[IVR_LISTS / 64];
     int32_t next;
 };
 
-// One round of list application: thread t brings one list (cnt entries of ivf_pids from `first` on fall into the range,
-// cnt = 0: none) and the bits `val` to OR into the set words of those passages.  Lists with few entries are pooled into
+// One round of list application: thread t < IVR_LISTS brings one list (cnt entries of ivf_pids from `first` on fall into
+// the range of `range` passages, cnt = 0: none; the other threads bring none) and the bits `val` to OR into the set words of those passages.  Lists with few entries are pooled into
 // one flat index range that all threads share (a lane finds its entry by binary search in the prefix sums), so that
 // fifty lists of two entries cost one memory round trip instead of fifty; a long list is walked by one wave, 512
 // entries per step with eight loads in flight, waves taking lists from a shared counter.  All threads call this.
 __device__ __forceinline__ void ivr_apply_round(int cnt, int64_t first, unsigned long long val,
-                                                const int32_t *__restrict__ ivf_pids, uint32_t r0, unsigned long long *lsets,
-                                                IvrLists &L)
+                                                const int32_t *__restrict__ ivf_pids, uint32_t r0, uint32_t range,
+                                                unsigned long long *lsets, IvrLists &L)
 {
     const int tid = threadIdx.x, lane = tid & 63;
     const bool is_long = cnt > IVR_SHORT;
@@ -613,16 +619,16 @@ __device__ __forceinline__ void ivr_apply_round(int cnt, int64_t first, unsigned
         L.short_val[tid] = val;
     }
     __syncthreads();
-    const int n_long = L.pref[S2_THREADS] >> 20, n_short = L.pref[S2_THREADS] & 0xFFFFF;
-    for (int w = tid; w < n_short; w += S2_THREADS) {
-        int lo = 0, hi = S2_THREADS;  // largest lo whose short-entry prefix is <= w: the list that holds entry w
+    const int n_long = L.pref[IVR_LISTS] >> 20, n_short = L.pref[IVR_LISTS] & 0xFFFFF;
+    for (int w = tid; w < n_short; w += (int)blockDim.x) {
+        int lo = 0, hi = IVR_LISTS;  // largest lo whose short-entry prefix is <= w: the list that holds entry w
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
             if ((L.pref[mid] & 0xFFFFF) <= w) lo = mid;
             else hi = mid;
         }
         const uint32_t loc = (uint32_t)ivf_pids[L.short_start[lo] + (w - (L.pref[lo] & 0xFFFFF))] - r0;
-        if (loc < (uint32_t)IVR_RANGE) atomicOr(&lsets[loc], L.short_val[lo]);  // (false only if a list is not ascending)
+        if (loc < range) atomicOr(&lsets[loc], L.short_val[lo]);  // (false only if a list is not ascending)
     }
     for (;;) {
         int l = 0;
@@ -642,7 +648,7 @@ __device__ __forceinline__ void ivr_apply_round(int cnt, int64_t first, unsigned
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const uint32_t loc = pid[u] - r0;
-                if (pid[u] != 0xFFFFFFFFu && loc < (uint32_t)IVR_RANGE) atomicOr(&lsets[loc], v);
+                if (pid[u] != 0xFFFFFFFFu && loc < range) atomicOr(&lsets[loc], v);
             }
         }
     }
@@ -658,11 +664,11 @@ __device__ __forceinline__ void ivr_apply_round(int cnt, int64_t first, unsigned
 #define UW_THREADS 1024
 #define UW_LONG 4096  // entries from which on a list is walked by all waves together
 #define IVR_WIDE_MIN_QUERIES 32
-static_assert(UW_SHIFT >= IVR_SHIFT, "a wide range is a whole number of table ranges");
+static_assert(UW_SHIFT >= 13, "a wide range is a whole number of table ranges");
 __global__ __launch_bounds__(UW_THREADS) void s2_union_wide_kernel(
     const int32_t *__restrict__ uniq, const int32_t *__restrict__ n_uniq, int uniq_stride,
     const int64_t *__restrict__ ivf_offsets, const int32_t *__restrict__ ivf_pids, const uint32_t *__restrict__ table,
-    int64_t nr, int64_t P, const S2Meta *__restrict__ meta, const int32_t *__restrict__ dense_id,
+    int64_t nr, int shift, int64_t P, const S2Meta *__restrict__ meta, const int32_t *__restrict__ dense_id,
     const uint32_t *__restrict__ dense_bits, uint32_t *__restrict__ candbits, int64_t cand_words,
     uint32_t *__restrict__ emptybits)
 {
@@ -675,8 +681,8 @@ __global__ __launch_bounds__(UW_THREADS) void s2_union_wide_kernel(
     if (s2_uniform(meta[q].K) != 0) return;  // uniform
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = s2_uniform(tid >> 6);
-    const int64_t fr0 = (int64_t)blockIdx.x << (UW_SHIFT - IVR_SHIFT);  // table ranges [fr0, fr1)
-    const int64_t fr1 = fr0 + (1ll << (UW_SHIFT - IVR_SHIFT)) < nr ? fr0 + (1ll << (UW_SHIFT - IVR_SHIFT)) : nr;
+    const int64_t fr0 = (int64_t)blockIdx.x << (UW_SHIFT - shift);  // table ranges [fr0, fr1)
+    const int64_t fr1 = fr0 + (1ll << (UW_SHIFT - shift)) < nr ? fr0 + (1ll << (UW_SHIFT - shift)) : nr;
     const uint32_t p0 = (uint32_t)blockIdx.x << UW_SHIFT;
     for (int e = tid; e < UW_WORDS; e += UW_THREADS) bits[e] = 0u;
     const int nu = n_uniq[q];
@@ -761,7 +767,8 @@ __global__ __launch_bounds__(UW_THREADS) void s2_union_wide_kernel(
     }
 }
 
-__global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
+template <int SHIFT>
+__global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
     const int32_t *__restrict__ uniq, const int32_t *__restrict__ n_uniq, int uniq_stride,
     const int64_t *__restrict__ ivf_offsets, const int32_t *__restrict__ ivf_pids, const uint32_t *__restrict__ table,
     int64_t nr, const float *__restrict__ S, int64_t C, const uint32_t *__restrict__ keepbits, int64_t keep_words,
@@ -770,8 +777,9 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
     uint64_t *__restrict__ keys2, int64_t key_stride, int32_t *__restrict__ hist, uint32_t *__restrict__ emptybits,
     int skip_k0)
 {
-    __shared__ unsigned long long lsets[IVR_RANGE];
-    __shared__ uint32_t lcand[IVR_RANGE / 32], lempty[IVR_RANGE / 32];
+    constexpr int RANGE = 1 << SHIFT, THREADS = IVR_THREADS(SHIFT);
+    __shared__ unsigned long long lsets[RANGE];
+    __shared__ uint32_t lcand[RANGE / 32], lempty[RANGE / 32];
     __shared__ uint32_t htab[S2_HASH];
     __shared__ __align__(16) float Tl[(S2_MAX_KEPT + 1) * S2_TSTRIDE];
     __shared__ float rowsum[S2_MAX_KEPT + 1];
@@ -780,15 +788,15 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
     __shared__ uint32_t slot_probed[2];  // bit s: surviving slot s is also a probed centroid
     const int q = blockIdx.y;
     const int64_t r = blockIdx.x;
-    const uint32_t r0 = (uint32_t)(r << IVR_SHIFT);
+    const uint32_t r0 = (uint32_t)(r << SHIFT);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = s2_uniform(tid >> 6);
     const int K = s2_uniform(meta[q].K);
     if (K == 0 && skip_k0) return;  // uniform: s2_union_wide_kernel has produced this query's candidate and empty-bag words
     const bool slots = K > 0 && K <= S2_MAX_KEPT;  // bags are kept as slot sets
     const int hsh = s2_uniform(meta[q].hash_shift);
-    for (int e = tid; e < IVR_RANGE; e += S2_THREADS) lsets[e] = 0ull;
-    for (int e = tid; e < SEL_BINS; e += S2_THREADS) lhist[e] = 0;
+    for (int e = tid; e < RANGE; e += THREADS) lsets[e] = 0ull;
+    for (int e = tid; e < SEL_BINS; e += THREADS) lhist[e] = 0;
     if (tid < 2) slot_probed[tid] = 0u;
     if (slots) s2_stage_tables(q, K, hsh, kept_ids, T, htab, Tl, rowsum);
     else __syncthreads();
@@ -809,7 +817,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
             first = ivf_offsets[c] + a;
             cnt = b > a ? (int)(b - a) : 0;
         }
-        ivr_apply_round(cnt, first, val, ivf_pids, r0, lsets, lists);
+        ivr_apply_round(cnt, first, val, ivf_pids, r0, (uint32_t)RANGE, lsets, lists);
     }
     // surviving centroids that were not probed: slot bit only
     if (slots) {
@@ -825,7 +833,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
                 cnt = b > a ? (int)(b - a) : 0;
             }
         }
-        ivr_apply_round(cnt, first, 1ull << (tid + 1), ivf_pids, r0, lsets, lists);
+        ivr_apply_round(cnt, first, 1ull << ((tid & 63) + 1), ivf_pids, r0, (uint32_t)RANGE, lsets, lists);
     }
 
     const int64_t w_first = (int64_t)r0 >> 5;  // first bitmap word of the range
@@ -834,7 +842,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
     uint64_t *keys_out = keys2 + (int64_t)q * key_stride;
     uint32_t *cbq = candbits + (int64_t)q * cand_words;
     uint32_t *ebq = emptybits + (int64_t)q * cand_words;
-    for (int g = wave; g < IVR_RANGE / 64; g += S2_THREADS / 64) {
+    for (int g = wave; g < RANGE / 64; g += THREADS / 64) {
         const unsigned long long v = lsets[64 * g + lane];
         const int64_t pid = (int64_t)r0 + 64 * g + lane;
         const bool cand = (v & 1ull) && pid < P;
@@ -859,14 +867,15 @@ __global__ __launch_bounds__(S2_THREADS) void s2_invert_kernel(
     }
     __syncthreads();
     // the range's candidate and empty-bag words, one contiguous store each
-    int64_t w_end = w_first + IVR_RANGE / 32;
+    int64_t w_end = w_first + RANGE / 32;
     if (w_end > cand_words) w_end = cand_words;
-    if (tid < IVR_RANGE / 32 && w_first + tid < w_end) cbq[w_first + tid] = lcand[tid];
-    if (K <= S2_MAX_KEPT && tid >= 64 && tid < 64 + IVR_RANGE / 32 && w_first + (tid - 64) < w_end)
-        ebq[w_first + tid - 64] = lempty[tid - 64];
+    static_assert(2 * (RANGE / 32) <= THREADS, "one thread per word of the two bitmaps");
+    if (tid < RANGE / 32 && w_first + tid < w_end) cbq[w_first + tid] = lcand[tid];
+    if (K <= S2_MAX_KEPT && tid >= RANGE / 32 && tid < 2 * (RANGE / 32) && w_first + (tid - RANGE / 32) < w_end)
+        ebq[w_first + tid - RANGE / 32] = lempty[tid - RANGE / 32];
     if (K > S2_MAX_KEPT) {
         // too many survivors for slot sets: the range's candidates are scored from their token codes
-        s2_gather_body(q, S, C, keepbits, keep_words, lcand, w_first, w_first + wave, S2_THREADS / 64, w_end, cand_words, P,
+        s2_gather_body(q, S, C, keepbits, keep_words, lcand, w_first, w_first + wave, THREADS / 64, w_end, cand_words, P,
                        doc_offsets, codes, bin_hi, bin_scale, keys_out, lhist, emptybits);
     }
     if (K > 0) s2_flush_hist(lhist, hist + (int64_t)q * SEL_BINS);
@@ -877,20 +886,26 @@ void plaid_launch_stage2_inverted(hipStream_t st, const int32_t *uniq, const int
                                   int64_t C, const uint32_t *keepbits, int64_t keep_words, const int32_t *codes,
                                   const int64_t *doc_offsets, int64_t P, int nq, const Stage2Buffers &b, uint32_t *candbits,
                                   int64_t cand_words, uint64_t *keys2, int64_t key_stride, const int32_t *dense_id,
-                                  const uint32_t *dense_bits)
+                                  const uint32_t *dense_bits, int shift)
 {
-    const int64_t nr = (P + IVR_RANGE - 1) >> IVR_SHIFT;
+    const int64_t nr = (P + (1ll << shift) - 1) >> shift;
     const int64_t nwide = (P + (1ll << UW_SHIFT) - 1) >> UW_SHIFT;
     // One workgroup per query and 2^19 passages pays off once the launch holds enough queries to fill the chip with such
-    // workgroups; below that the fine-grained kernel (one workgroup per 2048 passages) also takes the queries without
-    // a surviving centroid.
+    // workgroups; below that the fine-grained kernel (one workgroup per 2^shift passages) also takes the queries
+    // without a surviving centroid.
     const int wide = nq >= IVR_WIDE_MIN_QUERIES ? 1 : 0;
     if (wide)
         hipLaunchKernelGGL(s2_union_wide_kernel, dim3((unsigned)nwide, nq), dim3(UW_THREADS), 0, st, uniq, n_uniq, uniq_stride,
-                           ivf_offsets, ivf_pids, table, nr, P, b.meta, dense_id, dense_bits, candbits, cand_words, b.emptybits);
-    hipLaunchKernelGGL(s2_invert_kernel, dim3((unsigned)nr, nq), dim3(S2_THREADS), 0, st, uniq, n_uniq, uniq_stride, ivf_offsets,
-                       ivf_pids, table, nr, S, C, keepbits, keep_words, codes, doc_offsets, P, b.meta, b.kept_ids, b.T, candbits,
-                       cand_words, keys2, key_stride, b.hist, b.emptybits, wide);
+                           ivf_offsets, ivf_pids, table, nr, shift, P, b.meta, dense_id, dense_bits, candbits, cand_words,
+                           b.emptybits);
+    if (shift == 11)
+        hipLaunchKernelGGL(s2_invert_kernel<11>, dim3((unsigned)nr, nq), dim3(IVR_THREADS(11)), 0, st, uniq, n_uniq, uniq_stride,
+                           ivf_offsets, ivf_pids, table, nr, S, C, keepbits, keep_words, codes, doc_offsets, P, b.meta, b.kept_ids,
+                           b.T, candbits, cand_words, keys2, key_stride, b.hist, b.emptybits, wide);
+    else
+        hipLaunchKernelGGL(s2_invert_kernel<13>, dim3((unsigned)nr, nq), dim3(IVR_THREADS(13)), 0, st, uniq, n_uniq, uniq_stride,
+                           ivf_offsets, ivf_pids, table, nr, S, C, keepbits, keep_words, codes, doc_offsets, P, b.meta, b.kept_ids,
+                           b.T, candbits, cand_words, keys2, key_stride, b.hist, b.emptybits, wide);
 }
 
 // ------------------------------------------------------------------ host side

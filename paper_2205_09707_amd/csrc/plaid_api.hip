@@ -65,6 +65,7 @@ struct plaid_index {
     int32_t scq_form = 0;         // score kernel of a search: PLAID_SCQ_VECTOR / _MATRIX / _SPLIT16
     void *A16 = nullptr;          // split-fp16 operand form of the centroids (owned), when scq_form is PLAID_SCQ_SPLIT16
     uint32_t *ivr_table = nullptr;  // range table of the inverted lists (owned); null: union + code stream are used
+    int32_t ivr_shift = 11;         // log2 of the passages per table column (11 or 13)
     int32_t *dense_id = nullptr;    // with the range table: bitmap row of each centroid's list, -1 for all but the longest
     uint32_t *dense_bits = nullptr; // [rows][ceil(P / 32)]
     float stage_ms[PLAID_NUM_STAGES] = {0};
@@ -152,27 +153,39 @@ static int build_scq16_operands(plaid_index *ix)
     return PLAID_OK;
 }
 
-// The inverted form of candidate generation + stage 2 needs a table of C x (P / 2048 + 1) positions.  It is built when
-// it is small next to the inverted lists themselves (or tiny in absolute terms); PLAID_STAGE2_FORM=stream|inverted
-// (read at index creation) overrides that.
+// The inverted form of candidate generation + stage 2 needs a table of C x (P / 2^shift + 1) positions, shift = 11 or
+// 13 (2048 or 8192 passages per workgroup).  It is built at the finer granularity whose table is small next to the
+// inverted lists themselves (or tiny in absolute terms); PLAID_STAGE2_FORM=stream|inverted|inverted11|inverted13 (read
+// at index creation) overrides that.
 static int build_range_table(plaid_index *ix)
 {
     const char *env = getenv("PLAID_STAGE2_FORM");
-    if (env && strcmp(env, "stream") && strcmp(env, "inverted")) return fail(PLAID_EINVAL, "PLAID_STAGE2_FORM must be 'stream' or 'inverted'");
-    const size_t bytes = plaid_ivf_range_table_bytes(ix->C, ix->P);
+    if (env && strcmp(env, "stream") && strcmp(env, "inverted") && strcmp(env, "inverted11") && strcmp(env, "inverted13"))
+        return fail(PLAID_EINVAL, "PLAID_STAGE2_FORM must be 'stream', 'inverted', 'inverted11' or 'inverted13'");
     const size_t list_bytes = (size_t)ix->ivf_len * 4;
-    bool want = bytes <= (size_t)32 << 20 || bytes <= list_bytes;
-    if (env) want = !strcmp(env, "inverted");
-    if (!want || ix->P == 0) return PLAID_OK;
+    auto fits = [&](int shift) {
+        const size_t b = plaid_ivf_range_table_bytes(ix->C, ix->P, shift);
+        return b <= (size_t)32 << 20 || b <= list_bytes;
+    };
+    int shift = fits(11) ? 11 : (fits(13) ? 13 : 0);
+    if (env && !strcmp(env, "stream")) shift = 0;
+    if (env && !strcmp(env, "inverted") && !shift) shift = 13;
+    if (env && !strcmp(env, "inverted11")) shift = 11;
+    if (env && !strcmp(env, "inverted13")) shift = 13;
+    if (!shift || ix->P == 0) return PLAID_OK;
+    if (env && !strcmp(env, "inverted")) env = nullptr;  // an allocation failure falls back to the streaming form
+    const bool forced = env != nullptr;
+    const size_t bytes = plaid_ivf_range_table_bytes(ix->C, ix->P, shift);
+    ix->ivr_shift = shift;
     void *d = nullptr;
     hipError_t e = hipMalloc(&d, bytes ? bytes : 4);
     if (e != hipSuccess) {
         (void)hipGetLastError();
-        if (env) return fail(PLAID_ENOMEM, "hipMalloc(%zu) for the inverted-list range table failed", bytes);
+        if (forced) return fail(PLAID_ENOMEM, "hipMalloc(%zu) for the inverted-list range table failed", bytes);
         return PLAID_OK;  // not essential: the streaming form is used
     }
     ix->owned.push_back(d);
-    plaid_launch_ivf_range_table(nullptr, ix->ivf_offsets, ix->ivf_pids, ix->C, ix->P, (uint32_t *)d);
+    plaid_launch_ivf_range_table(nullptr, ix->ivf_offsets, ix->ivf_pids, ix->C, ix->P, shift, (uint32_t *)d);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipStreamSynchronize(nullptr));
     // bitmaps of the longest lists
@@ -480,7 +493,7 @@ extern "C" int plaid_get_score_kernel(const plaid_index *idx, int32_t *form)
 extern "C" int plaid_get_stage2_kernel(const plaid_index *idx, int32_t *form)
 {
     if (!idx || !form) return fail(PLAID_EINVAL, "null argument");
-    *form = idx->ivr_table ? 1 : 0;
+    *form = idx->ivr_table ? (idx->ivr_shift == 11 ? 1 : 2) : 0;
     return PLAID_OK;
 }
 
@@ -720,7 +733,7 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
         if (ix->ivr_table)
             plaid_launch_stage2_inverted(st, w.uniq, w.n_uniq, w.uniq_stride, ix->ivf_offsets, ix->ivf_pids, ix->ivr_table, w.S,
                                          C, w.keepbits, w.keep_words, ix->codes, ix->doc_offsets, P, n, w.s2, w.candbits,
-                                         w.cand_words, w.keys2, P, ix->dense_id, ix->dense_bits);
+                                         w.cand_words, w.keys2, P, ix->dense_id, ix->dense_bits, ix->ivr_shift);
         else
             plaid_launch_stage2(st, w.S, C, w.keepbits, w.keep_words, w.probed, nprobe, w.candbits, w.cand_words, P, ix->N,
                                 ix->doc_offsets, ix->codes, n, w.s2, w.keys2, P);

@@ -207,17 +207,18 @@ void plaid_launch_stage2(hipStream_t st, const float *S, int64_t C, const uint32
 
 // Inverted form of candidate generation + stage 2 (k_stage2.hip): the same outputs as plaid_launch_ivf_union followed by
 // plaid_launch_stage2 (candbits included, which need not be cleared beforehand), computed from the inverted lists of
-// the probed and the surviving centroids.  table: plaid_ivf_range_table_bytes(C, P) bytes filled once per index by
-// plaid_launch_ivf_range_table.
-size_t plaid_ivf_range_table_bytes(int64_t C, int64_t P);
+// the probed and the surviving centroids.  table: plaid_ivf_range_table_bytes(C, P, shift) bytes filled once per index
+// by plaid_launch_ivf_range_table.
+// shift: log2 of the passages per table column = per workgroup of the inverted kernel, 11 or 13.
+size_t plaid_ivf_range_table_bytes(int64_t C, int64_t P, int shift);
 void plaid_launch_ivf_range_table(hipStream_t st, const int64_t *ivf_offsets, const int32_t *ivf_pids, int64_t C, int64_t P,
-                                  uint32_t *table);
+                                  int shift, uint32_t *table);
 void plaid_launch_stage2_inverted(hipStream_t st, const int32_t *uniq, const int32_t *n_uniq, int uniq_stride,
                                   const int64_t *ivf_offsets, const int32_t *ivf_pids, const uint32_t *table, const float *S,
                                   int64_t C, const uint32_t *keepbits, int64_t keep_words, const int32_t *codes,
                                   const int64_t *doc_offsets, int64_t P, int nq, const Stage2Buffers &b, uint32_t *candbits,
                                   int64_t cand_words, uint64_t *keys2, int64_t key_stride, const int32_t *dense_id,
-                                  const uint32_t *dense_bits);
+                                  const uint32_t *dense_bits, int shift);
 // Bitmaps over the passages for the longest inverted lists (built once per index, next to the range table):
 // dense_id[c] = bitmap row of centroid c or -1 (counter[0], zero before the call, returns the number of rows);
 // bits: rows x words, zero before the call, words = ceil(P / 32).

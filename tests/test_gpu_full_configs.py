@@ -52,8 +52,9 @@ def _run(cfg_name, noise, n_sample, n_dump, stage2=None, form=None):
     if form is not None:
         assert pl.plaid_get_score_kernel(gidx) == {"vector": 0, "matrix": 1, "split16": 2}[form]
     if stage2 is not None:
-        assert pl.plaid_get_stage2_kernel(gidx) == (1 if stage2 == "inverted" else 0)
-    print(f"[full] {cfg_name}/{noise}: stage-2 form {'inverted' if pl.plaid_get_stage2_kernel(gidx) else 'stream'}", flush=True)
+        assert bool(pl.plaid_get_stage2_kernel(gidx)) == stage2.startswith("inverted")
+    print(f"[full] {cfg_name}/{noise}: stage-2 form {('stream', 'inverted, 2048 passages per workgroup', 'inverted, 8192 passages per workgroup')[pl.plaid_get_stage2_kernel(gidx)]}",
+          flush=True)
     params = (cfg.nprobe, cfg.t_cs, cfg.ndocs, cfg.k)
     Q = w.queries
     nq = Q.shape[0]

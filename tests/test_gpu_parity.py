@@ -56,7 +56,7 @@ def _check_workload(pl, w, params_list, want=None, queries=None, copy=False, for
     if form is not None:
         assert pl.plaid_get_score_kernel(gidx) == {"vector": 0, "matrix": 1, "split16": 2}[form]
     if stage2 is not None:
-        assert pl.plaid_get_stage2_kernel(gidx) == (1 if stage2 == "inverted" else 0)
+        assert pl.plaid_get_stage2_kernel(gidx) == {"stream": 0, "inverted": 1, "inverted11": 1, "inverted13": 2}[stage2]
     Qdev = w.queries.to("cuda:0")
     Qh = w.queries.numpy()
     nq = Qh.shape[0]
@@ -77,8 +77,8 @@ def _check_workload(pl, w, params_list, want=None, queries=None, copy=False, for
     return identical, total
 
 
-@pytest.mark.parametrize("form,stage2", [("split16", "inverted"), ("split16", "stream"), ("matrix", "inverted"),
-                                         ("vector", "stream"), ("matrix", "stream")])
+@pytest.mark.parametrize("form,stage2", [("split16", "inverted"), ("split16", "stream"), ("split16", "inverted13"),
+                                         ("matrix", "inverted"), ("vector", "stream"), ("matrix", "stream")])
 @pytest.mark.parametrize("noise", ["literal", "calibrated"])
 def test_cfg1_all_stages(pl, noise, form, stage2):
     cfg = get_config("cfg1")
@@ -117,7 +117,7 @@ def test_default_kernel_forms(pl):
         gidx = pl.plaid_index_from_view(pu.device_arrays(w), w.cfg.nbits, device=0, copy=True)
     try:
         assert pl.plaid_get_score_kernel(gidx) == 2
-        assert pl.plaid_get_stage2_kernel(gidx) == 1   # a small index: the range table is tiny
+        assert pl.plaid_get_stage2_kernel(gidx) == 1   # a small index: the range table is tiny at 2048 passages per column
     finally:
         pl.plaid_index_free(gidx)
     with _kernel_forms("matrix", None):
@@ -164,6 +164,9 @@ SWEEP = [
     (129, 40, 2, 12, 2, 8, "calibrated", 1, "matrix", "stream"),  # one row past a row block, one query
     (40, 5000, 1, 6, 2, 9, "calibrated", 3, None, "inverted"),    # three passage ranges, the last one ragged
     (40, 5000, 1, 6, 2, 9, "calibrated", 3, None, "stream"),
+    # 8192 passages per workgroup (the form large indexes take): one ragged range, then three ranges with the last ragged
+    (40, 5000, 1, 6, 2, 9, "calibrated", 3, None, "inverted13"),
+    (33, 20000, 1, 5, 2, 10, "calibrated", 35, None, "inverted13"),
     # more than 16 queries: the short-list selections sort in LDS (one workgroup per list) instead of counting ranks;
     # 900 and 3000 passages put the lists into the 512- and 1024-thread forms of that sort
     (33, 200, 1, 30, 2, 11, "calibrated", 20, None, None),
@@ -198,10 +201,10 @@ RARE = [
     # longer than one workgroup can sort (digit filter on the passage-id bits), and ndocs > 8192 sends stage 3's
     # selection through the multi-level radix path
     ("tie_groups", dict(C=2, P=40000, lo=1, hi=3, nbits=2, nq=2, seed=31), [(2, -np.inf, 9000, 10), (1, 0.0, 300, 5)],
-     ("inverted", "stream")),
+     ("inverted", "stream", "inverted13")),
     # passages longer than the streaming kernel's staging buffer (2272 tokens) and than many 32-token steps of stage 4
     ("long_passages", dict(C=50, P=6, lo=2300, hi=2400, nbits=1, nq=2, seed=32), [(2, 0.1, 4, 2), (50, -np.inf, 6, 6)],
-     ("stream", "inverted")),
+     ("stream", "inverted", "inverted13")),
     # ndocs/4 and k beyond 8192: radix selection of the stage-3 survivors and of the final ranking, sorted output
     # through the global bitonic network
     ("big_lists", dict(C=8, P=40000, lo=1, hi=2, nbits=2, nq=1, seed=33), [(8, -np.inf, 40000, 12000)], ("inverted",)),

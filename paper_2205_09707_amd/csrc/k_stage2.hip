@@ -600,9 +600,10 @@ struct IvrLists {
 // one flat index range that all threads share (a lane finds its entry by binary search in the prefix sums), so that
 // fifty lists of two entries cost one memory round trip instead of fifty; a long list is walked by one wave, 512
 // entries per step with eight loads in flight, waves taking lists from a shared counter.  All threads call this.
+template <typename SetT>
 __device__ __forceinline__ void ivr_apply_round(int cnt, int64_t first, unsigned long long val,
                                                 const int32_t *__restrict__ ivf_pids, uint32_t r0, uint32_t range,
-                                                unsigned long long *lsets, IvrLists &L)
+                                                SetT *lsets, IvrLists &L)
 {
     const int tid = threadIdx.x, lane = tid & 63;
     const bool is_long = cnt > IVR_SHORT;
@@ -628,7 +629,7 @@ __device__ __forceinline__ void ivr_apply_round(int cnt, int64_t first, unsigned
             else hi = mid;
         }
         const uint32_t loc = (uint32_t)ivf_pids[L.short_start[lo] + (w - (L.pref[lo] & 0xFFFFF))] - r0;
-        if (loc < range) atomicOr(&lsets[loc], L.short_val[lo]);  // (false only if a list is not ascending)
+        if (loc < range) atomicOr(&lsets[loc], (SetT)L.short_val[lo]);  // (false only if a list is not ascending)
     }
     for (;;) {
         int l = 0;
@@ -637,7 +638,7 @@ __device__ __forceinline__ void ivr_apply_round(int cnt, int64_t first, unsigned
         if (l >= n_long) break;
         const int n = s2_uniform(L.long_cnt[l]);
         const int32_t *__restrict__ src = ivf_pids + L.long_start[l];
-        const unsigned long long v = L.long_val[l];
+        const SetT v = (SetT)L.long_val[l];
         for (int e0 = 0; e0 < n; e0 += 512) {
             uint32_t pid[8];
 #pragma unroll
@@ -767,7 +768,10 @@ __global__ __launch_bounds__(UW_THREADS) void s2_union_wide_kernel(
     }
 }
 
-template <int SHIFT>
+// SetT: the per-passage set word.  Queries with at most 31 surviving centroids fit 32-bit words (bit 0 = candidate,
+// bits 1..31 = slots), which halves the kernel's largest LDS array and lets two of the 1024-thread workgroups share a
+// compute unit; the 64-bit instance serves the other queries.  Both are launched; each leaves the other's queries alone.
+template <int SHIFT, typename SetT>
 __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
     const int32_t *__restrict__ uniq, const int32_t *__restrict__ n_uniq, int uniq_stride,
     const int64_t *__restrict__ ivf_offsets, const int32_t *__restrict__ ivf_pids, const uint32_t *__restrict__ table,
@@ -778,7 +782,7 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
     int skip_k0)
 {
     constexpr int RANGE = 1 << SHIFT, THREADS = IVR_THREADS(SHIFT);
-    __shared__ unsigned long long lsets[RANGE];
+    __shared__ SetT lsets[RANGE];
     __shared__ uint32_t lcand[RANGE / 32], lempty[RANGE / 32];
     __shared__ uint32_t htab[S2_HASH];
     __shared__ __align__(16) float Tl[(S2_MAX_KEPT + 1) * S2_TSTRIDE];
@@ -793,9 +797,10 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
     const int wave = s2_uniform(tid >> 6);
     const int K = s2_uniform(meta[q].K);
     if (K == 0 && skip_k0) return;  // uniform: s2_union_wide_kernel has produced this query's candidate and empty-bag words
+    if ((K <= 31) != (sizeof(SetT) == 4)) return;  // uniform: the other instance's query
     const bool slots = K > 0 && K <= S2_MAX_KEPT;  // bags are kept as slot sets
     const int hsh = s2_uniform(meta[q].hash_shift);
-    for (int e = tid; e < RANGE; e += THREADS) lsets[e] = 0ull;
+    for (int e = tid; e < RANGE; e += THREADS) lsets[e] = (SetT)0;
     for (int e = tid; e < SEL_BINS; e += THREADS) lhist[e] = 0;
     if (tid < 2) slot_probed[tid] = 0u;
     if (slots) s2_stage_tables(q, K, hsh, kept_ids, T, htab, Tl, rowsum);
@@ -843,7 +848,7 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
     uint32_t *cbq = candbits + (int64_t)q * cand_words;
     uint32_t *ebq = emptybits + (int64_t)q * cand_words;
     for (int g = wave; g < RANGE / 64; g += THREADS / 64) {
-        const unsigned long long v = lsets[64 * g + lane];
+        const unsigned long long v = (unsigned long long)lsets[64 * g + lane];
         const int64_t pid = (int64_t)r0 + 64 * g + lane;
         const bool cand = (v & 1ull) && pid < P;
         const unsigned long long members = v & ~1ull;
@@ -898,14 +903,18 @@ void plaid_launch_stage2_inverted(hipStream_t st, const int32_t *uniq, const int
         hipLaunchKernelGGL(s2_union_wide_kernel, dim3((unsigned)nwide, nq), dim3(UW_THREADS), 0, st, uniq, n_uniq, uniq_stride,
                            ivf_offsets, ivf_pids, table, nr, shift, P, b.meta, dense_id, dense_bits, candbits, cand_words,
                            b.emptybits);
-    if (shift == 11)
-        hipLaunchKernelGGL(s2_invert_kernel<11>, dim3((unsigned)nr, nq), dim3(IVR_THREADS(11)), 0, st, uniq, n_uniq, uniq_stride,
-                           ivf_offsets, ivf_pids, table, nr, S, C, keepbits, keep_words, codes, doc_offsets, P, b.meta, b.kept_ids,
-                           b.T, candbits, cand_words, keys2, key_stride, b.hist, b.emptybits, wide);
-    else
-        hipLaunchKernelGGL(s2_invert_kernel<13>, dim3((unsigned)nr, nq), dim3(IVR_THREADS(13)), 0, st, uniq, n_uniq, uniq_stride,
-                           ivf_offsets, ivf_pids, table, nr, S, C, keepbits, keep_words, codes, doc_offsets, P, b.meta, b.kept_ids,
-                           b.T, candbits, cand_words, keys2, key_stride, b.hist, b.emptybits, wide);
+#define S2_INVERT(SH_, T_)                                                                                                  \
+    hipLaunchKernelGGL((s2_invert_kernel<SH_, T_>), dim3((unsigned)nr, nq), dim3(IVR_THREADS(SH_)), 0, st, uniq, n_uniq,       \
+                       uniq_stride, ivf_offsets, ivf_pids, table, nr, S, C, keepbits, keep_words, codes, doc_offsets, P,     \
+                       b.meta, b.kept_ids, b.T, candbits, cand_words, keys2, key_stride, b.hist, b.emptybits, wide)
+    if (shift == 11) {
+        S2_INVERT(11, uint32_t);
+        S2_INVERT(11, unsigned long long);
+    } else {
+        S2_INVERT(13, uint32_t);
+        S2_INVERT(13, unsigned long long);
+    }
+#undef S2_INVERT
 }
 
 // ------------------------------------------------------------------ host side

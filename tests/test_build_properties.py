@@ -21,8 +21,10 @@ KERNELS = {
     "stage1_tail_kernelILi2ELb1E": ("k_scq.hip", 128, 64 << 10),   # ... also with the re-evaluations in double
     "stage1_tail_kernelILi8ELb1E": ("k_scq.hip", 128, 64 << 10),
     "scq16_kernel": ("k_scq16.hip", 256, 40 << 10),                # two waves per SIMD, two to four workgroups per CU
-    "s2_invert_kernelILi11E": ("k_stage2.hip", 128, 64 << 10),     # 2048 passages per workgroup, three workgroups per CU
-    "s2_invert_kernelILi13E": ("k_stage2.hip", 128, 100 << 10),    # 8192 passages, 1024 threads: one workgroup per CU
+    "s2_invert_kernelILi11EjE": ("k_stage2.hip", 128, 53 << 10),   # 2048 passages per workgroup, three workgroups per CU
+    "s2_invert_kernelILi11EyE": ("k_stage2.hip", 128, 53 << 10),
+    "s2_invert_kernelILi13EjE": ("k_stage2.hip", 128, 80 << 10),   # 8192 passages, 1024 threads, 32-bit sets: two per CU
+    "s2_invert_kernelILi13EyE": ("k_stage2.hip", 128, 100 << 10),  # ... 64-bit sets: one per CU
     "s2_union_wide_kernel": ("k_stage2.hip", 128, 80 << 10),       # two workgroups of 1024 threads per CU
     "s2_stream_kernel": ("k_stage2.hip", 128, 40 << 10),
     "ci_list_kernel": ("k_ci.hip", 64, 0),

@@ -55,6 +55,8 @@ def _load():
         _lib.orc_candidates.restype = ct.c_int64
         _lib.orc_build_ivf.restype = ct.c_int64
         _lib.orc_search.restype = ct.c_int32
+        _lib.orc_vanilla_search.restype = ct.c_int32
+        _lib.orc_build_ivf_embeddings.restype = ct.c_int64
         _lib.orc_search_batch.restype = ct.c_int32
     return _lib
 
@@ -250,6 +252,51 @@ def search_batch(ix: Index, Q: np.ndarray, nprobe: int, t_cs: float, ndocs: int,
                                     ct.c_float(t_cs), ct.c_int32(ndocs), ct.c_int32(k), _p(ids), _p(sc),
                                     ct.c_int32(nthreads))
     return ids, sc, used
+
+
+# ---- vanilla ColBERTv2 retrieval (the paper's baseline) ---------------------------------------
+
+class _VanillaDumps(ct.Structure):
+    _fields_ = [(n, ct.c_void_p) for n in ("cand", "n_cand", "n_embeddings", "kept", "kept_scores", "n_kept", "pruned")]
+
+
+def build_ivf_embeddings(codes: np.ndarray, C: int):
+    """Embedding-level inverted lists: (offsets [C+1] int64, eids [N] int64), list c = ascending token indices coded c."""
+    codes = _chk(codes, np.int32)
+    off = np.empty(C + 1, np.int64)
+    eids = np.empty(codes.shape[0], np.int64)
+    _load().orc_build_ivf_embeddings(_p(codes), ct.c_int64(codes.shape[0]), ct.c_int64(C), _p(off), _p(eids))
+    return off, eids
+
+
+def vanilla_search(ix: Index, eoff: np.ndarray, eids: np.ndarray, Q: np.ndarray, nprobe: int, ncandidates: int, k: int,
+                   dumps: bool = False):
+    """One query through vanilla retrieval.  Returns (ids[k], scores[k]) or, with dumps, also a dict with the candidate
+    passages, |E|, the candidates kept by the ncandidates cap (ascending) with their pruning scores, and whether pruning ran."""
+    Q = _chk(Q, np.float32)
+    eoff = _chk(eoff, np.int64)
+    eids = _chk(eids, np.int64)
+    ids = np.empty(k, np.int32)
+    sc = np.empty(k, np.float32)
+    d = None
+    keep = {}
+    if dumps:
+        cap = max(1, min(int(ncandidates), ix.P))
+        keep = dict(cand=np.empty(max(ix.P, 1), np.int32), n_cand=np.zeros(1, np.int64), n_embeddings=np.zeros(1, np.int64),
+                    kept=np.empty(max(ix.P, 1), np.int32), kept_scores=np.full(cap, np.nan, np.float32),
+                    n_kept=np.zeros(1, np.int64), pruned=np.zeros(1, np.int32))
+        d = _VanillaDumps(*[keep[n].ctypes.data for n, _ in _VanillaDumps._fields_])
+    rc = _load().orc_vanilla_search(ct.byref(ix.c), _p(eoff), _p(eids), _p(Q), ct.c_int32(Q.shape[0]), ct.c_int32(nprobe),
+                                    ct.c_int64(ncandidates), ct.c_int32(k), _p(ids), _p(sc),
+                                    ct.byref(d) if d is not None else None)
+    if rc != 0:
+        raise ValueError("orc_vanilla_search: invalid arguments")
+    if not dumps:
+        return ids, sc
+    nc, nk = int(keep["n_cand"][0]), int(keep["n_kept"][0])
+    return ids, sc, dict(cand=keep["cand"][:nc].copy(), n_embeddings=int(keep["n_embeddings"][0]),
+                         kept=keep["kept"][:nk].copy(), kept_scores=keep["kept_scores"][:nk].copy(),
+                         pruned=bool(keep["pruned"][0]))
 
 
 def search_from_S(ix: Index, Q: np.ndarray, S: np.ndarray, nprobe: int, t_cs: float, ndocs: int, k: int):

@@ -22,6 +22,9 @@
  * MaxSim over an index whose bucket weights are all zero"; stage-2 monotonicity invariants;
  * numpy unpackbits for the byte table; encode/decode bucket-resolution bounds; a hand-computed
  * 3-centroid index; and "nprobe = C, t_cs = -inf, ndocs >= 4P  ==>  pipeline == exhaustive".
+ * The vanilla ColBERTv2 routines (the paper's baseline): embedding lists against a stable argsort of the codes; the
+ * candidate set against the passage-level candidates of the same probes; "nprobe = C, ncandidates >= P  ==>  vanilla ==
+ * exhaustive"; pruning scores against numpy on the decompressed embeddings of E, bounded above by exact MaxSim.
  * Every function here has such a pin.  What has none: the paper prints no worked example and no per-stage values, and
  * its quality tables need collections and checkpoints that are not available, so retrieval quality against the paper
  * is parity unpinned.
@@ -307,6 +310,144 @@ void orc_exhaustive(const orc_index *ix, const float *Q, int32_t qlen, int32_t k
     orc_select(pids, sc, P, k, out_ids, out_scores);
     free(pids);
     free(sc);
+}
+
+/* ------------------------------------------------------------------ vanilla ColBERTv2 retrieval (Sections 3.1-3.2, 4.1)
+ * What PLAID is measured against.  As far as this paper states it: the inverted list of a centroid holds the ids of the
+ * EMBEDDINGS assigned to it (Section 4.1); the embeddings in the lists of the probed centroids make up E, and the
+ * candidate passages are the passages those embeddings belong to; when there are more than ncandidates of them they are
+ * pruned by scoring the embeddings of E -- only those -- with full residual decompression (Section 4.1), after which
+ * every token of every remaining candidate is decompressed and scored exactly (Section 3.2: index lookup,
+ * decompression, MaxSim).  Readings where the text is silent: a candidate's pruning score is
+ * sum_i max_{j in E, j in the passage} Q_i . D_j (the late-interaction form of Eq. 1 restricted to E; every candidate
+ * owns at least one embedding of E); ranking by (score descending, pid ascending); pruning only when the candidate
+ * count exceeds ncandidates. */
+
+/* Embedding-level inverted lists: list c = the ascending indices of the tokens whose code is c.
+ * eids may be NULL (offsets only).  Returns N. */
+int64_t orc_build_ivf_embeddings(const int32_t *codes, int64_t N, int64_t C, int64_t *offsets /* [C+1] */, int64_t *eids /* [N] */)
+{
+    for (int64_t c = 0; c <= C; ++c) offsets[c] = 0;
+    for (int64_t j = 0; j < N; ++j) offsets[codes[j] + 1] += 1;
+    for (int64_t c = 0; c < C; ++c) offsets[c + 1] += offsets[c];
+    if (eids) {
+        int64_t *fill = (int64_t *)malloc((size_t)(C > 0 ? C : 1) * sizeof(int64_t));
+        for (int64_t c = 0; c < C; ++c) fill[c] = offsets[c];
+        for (int64_t j = 0; j < N; ++j) eids[fill[codes[j]]++] = j;
+        free(fill);
+    }
+    return N;
+}
+
+typedef struct {  /* optional dumps of orc_vanilla_search; any pointer may be NULL */
+    int32_t *cand;        /* [P] ascending candidate passages */
+    int64_t *n_cand;
+    int64_t *n_embeddings; /* |E| */
+    int32_t *kept;        /* [min(ncandidates, P)] candidates after pruning, ascending pid */
+    float *kept_scores;   /* their pruning scores (only when pruning happened, else untouched) */
+    int64_t *n_kept;
+    int32_t *pruned;      /* 1 when the candidate count exceeded ncandidates */
+} orc_vanilla_dumps;
+
+/* One query.  eoff / eids: embedding-level lists (orc_build_ivf_embeddings).  Unused output slots get (-1, -inf). */
+int32_t orc_vanilla_search(const orc_index *ix, const int64_t *eoff, const int64_t *eids, const float *Q, int32_t qlen,
+                           int32_t nprobe, int64_t ncandidates, int32_t k, int32_t *out_ids, float *out_scores,
+                           const orc_vanilla_dumps *dump)
+{
+    int64_t C = ix->C, P = ix->P, N = ix->N;
+    int32_t dim = ix->dim;
+    if (qlen > ORC_QLEN_MAX || nprobe < 1 || nprobe > C || ncandidates < 1 || k < 1) return -1;
+    float *S = (float *)malloc((size_t)C * qlen * sizeof(float));
+    int32_t *probed = (int32_t *)malloc((size_t)qlen * nprobe * sizeof(int32_t));
+    orc_scq(ix->centroids, C, Q, qlen, dim, S);
+    orc_top_nprobe(S, C, qlen, nprobe, probed);
+    /* E: a flag per embedding; which passage owns an embedding: by walking the passage offsets */
+    uint8_t *probed_c = (uint8_t *)calloc((size_t)C, 1), *inE = (uint8_t *)calloc((size_t)(N > 0 ? N : 1), 1);
+    for (int64_t a = 0; a < (int64_t)qlen * nprobe; ++a) probed_c[probed[a]] = 1;
+    int64_t nE = 0;
+    for (int64_t c = 0; c < C; ++c)
+        if (probed_c[c])
+            for (int64_t e = eoff[c]; e < eoff[c + 1]; ++e) {
+                inE[eids[e]] = 1;
+                nE += 1;
+            }
+    int32_t *cand = (int32_t *)malloc((size_t)(P > 0 ? P : 1) * sizeof(int32_t));
+    int64_t n_cand = 0;
+    for (int64_t p = 0; p < P; ++p) {
+        int any = 0;
+        for (int64_t j = ix->doc_offsets[p]; j < ix->doc_offsets[p + 1]; ++j) any |= inE[j];
+        if (any) cand[n_cand++] = (int32_t)p;
+    }
+    if (dump && dump->cand) memcpy(dump->cand, cand, (size_t)n_cand * sizeof(int32_t));
+    if (dump && dump->n_cand) *dump->n_cand = n_cand;
+    if (dump && dump->n_embeddings) *dump->n_embeddings = nE;
+    /* pruning of an over-large candidate set by the embeddings of E alone */
+    int64_t n_kept = n_cand;
+    int32_t *kept = cand;
+    int32_t *kbuf = NULL;
+    int32_t pruned = n_cand > ncandidates;
+    if (pruned) {
+        float *ps = (float *)malloc((size_t)n_cand * sizeof(float));
+        float *D = (float *)malloc((size_t)dim * sizeof(float));
+        for (int64_t a = 0; a < n_cand; ++a) {
+            int64_t p = cand[a];
+            float best[ORC_QLEN_MAX];
+            for (int32_t i = 0; i < qlen; ++i) best[i] = -INFINITY;
+            for (int64_t j = ix->doc_offsets[p]; j < ix->doc_offsets[p + 1]; ++j) {
+                if (!inE[j]) continue;
+                orc_decompress(ix, j, j + 1, D, NULL);
+                for (int32_t i = 0; i < qlen; ++i) {
+                    double dot = 0.0;
+                    for (int32_t t = 0; t < dim; ++t) dot += (double)Q[i * dim + t] * (double)D[t];
+                    float f = (float)dot;
+                    if (f > best[i]) best[i] = f;
+                }
+            }
+            double acc = 0.0;
+            for (int32_t i = 0; i < qlen; ++i) acc += (double)best[i];
+            ps[a] = (float)acc;
+        }
+        kbuf = (int32_t *)malloc((size_t)ncandidates * sizeof(int32_t));
+        float *ks = (float *)malloc((size_t)ncandidates * sizeof(float));
+        n_kept = orc_select(cand, ps, n_cand, ncandidates, kbuf, ks);
+        /* report the kept set in ascending pid order, scores alongside */
+        for (int64_t a = 1; a < n_kept; ++a) {
+            int32_t id = kbuf[a];
+            float sc = ks[a];
+            int64_t b = a - 1;
+            while (b >= 0 && kbuf[b] > id) {
+                kbuf[b + 1] = kbuf[b];
+                ks[b + 1] = ks[b];
+                --b;
+            }
+            kbuf[b + 1] = id;
+            ks[b + 1] = sc;
+        }
+        if (dump && dump->kept_scores) memcpy(dump->kept_scores, ks, (size_t)n_kept * sizeof(float));
+        kept = kbuf;
+        free(ps);
+        free(D);
+        free(ks);
+    }
+    if (dump && dump->kept) memcpy(dump->kept, kept, (size_t)n_kept * sizeof(int32_t));
+    if (dump && dump->n_kept) *dump->n_kept = n_kept;
+    if (dump && dump->pruned) *dump->pruned = pruned;
+    /* every token of every remaining candidate: exact MaxSim (Eq. 1), best k */
+    float *sc = (float *)malloc((size_t)(n_kept > 0 ? n_kept : 1) * sizeof(float));
+    orc_maxsim(ix, Q, qlen, kept, n_kept, sc);
+    for (int32_t j = 0; j < k; ++j) {
+        out_ids[j] = -1;
+        out_scores[j] = -INFINITY;
+    }
+    orc_select(kept, sc, n_kept, k, out_ids, out_scores);
+    free(sc);
+    free(kbuf);
+    free(cand);
+    free(inE);
+    free(probed_c);
+    free(probed);
+    free(S);
+    return 0;
 }
 
 /* ------------------------------------------------------------------ the four-stage pipeline (Figure 4, Sections 4.1-4.4) */

@@ -55,6 +55,12 @@ MISTAKES = [
      "orc_centroid_interaction(S, qlen, sel2, n2, ix->doc_offsets, ix->codes, keep, s3);", 1),
     ("stage3_keeps_half", "int64_t m3 = ndocs / 4 > 1 ? ndocs / 4 : 1;", "int64_t m3 = ndocs / 2 > 1 ? ndocs / 2 : 1;", 1),
     ("stage4_scores_the_stage2_survivors", "orc_maxsim(ix, Q, qlen, sel3, n3, s4);\n", "orc_maxsim(ix, Q, qlen, sel2, n3, s4);\n", 1),
+    # vanilla ColBERTv2 retrieval
+    ("vanilla_prunes_on_every_token", "if (!inE[j]) continue;", ";", 1),
+    ("vanilla_prunes_at_the_cap", "int32_t pruned = n_cand > ncandidates;", "int32_t pruned = n_cand >= ncandidates;", 1),
+    ("vanilla_misses_the_last_embedding_of_a_list", "for (int64_t e = eoff[c]; e < eoff[c + 1]; ++e) {",
+     "for (int64_t e = eoff[c]; e < eoff[c + 1] - 1; ++e) {", 1),
+    ("vanilla_embedding_lists_unsorted", "eids[fill[codes[j]]++] = j;", "eids[fill[codes[j]]++] = N - 1 - j;", 1),
 ]
 
 
@@ -68,7 +74,8 @@ def _pins_fail(name, old, new, count, tmp):
     subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", so, c, "-lm"])
     env = dict(os.environ, PLAID_ORACLE_LIB=so, OMP_NUM_THREADS="2")
     r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
-                        os.path.join(HERE, "test_oracle_pins.py"), os.path.join(HERE, "test_oracle_hand_example.py")],
+                        os.path.join(HERE, "test_oracle_pins.py"), os.path.join(HERE, "test_oracle_hand_example.py"),
+                        os.path.join(HERE, "test_oracle_vanilla.py")],
                        cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=600)
     tail = "\n".join(r.stdout.strip().splitlines()[-3:])
     return name, r.returncode, tail

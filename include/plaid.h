@@ -135,6 +135,31 @@ int plaid_search_debug(plaid_index *idx, const float *Q, int32_t nq, int32_t npr
 int plaid_search_static(plaid_index *idx, const float *Q, int32_t nq, int32_t nprobe, float t_cs, int32_t ndocs,
                         int32_t k, int32_t *out_ids, float *out_scores, void *hip_stream);
 
+/* Vanilla ColBERTv2 retrieval, the baseline the paper measures PLAID against (Sections 3.1-3.2, 4.1), on the same index
+ * and with the same kernels for Eq. 2, decompression and MaxSim:
+ *   1. S_cq and the nprobe best centroids of every query token, as in plaid_search;
+ *   2. the inverted list of a centroid holds the ids of the EMBEDDINGS assigned to it; the candidates are the passages
+ *      owning an embedding of a probed list (the library builds these lists and a token -> passage map on the first
+ *      call: 8 bytes per embedding, kept until plaid_index_free; fewer than 2^31 embeddings);
+ *   3. when a query has more than ncandidates candidates they are pruned by scoring the embeddings of the probed lists
+ *      -- only those -- with full residual decompression: score = sum over the query tokens of the maximum over the
+ *      passage's embeddings among them, the best ncandidates by (score descending, pid ascending) stay;
+ *   4. every token of every remaining candidate is decompressed and scored exactly (Eq. 1); the best k are returned
+ *      like plaid_search returns them.
+ * dbg may be NULL; its pointers are DEVICE, caller-owned and may each be NULL:
+ *   cand [nq][P] ascending candidate pids, n_cand [nq];  kept_ids / kept_scores [nq][ncandidates] the candidates after
+ *   step 3 in unspecified order with their pruning scores (0 for a query that needed no pruning), n_kept [nq].
+ * The first call synchronises the device.  Errors as plaid_search. */
+typedef struct {
+    int32_t *cand;
+    int32_t *n_cand;
+    int32_t *kept_ids;
+    float *kept_scores;
+    int32_t *n_kept;
+} plaid_vanilla_debug;
+int plaid_search_vanilla(plaid_index *idx, const float *Q, int32_t nq, int32_t nprobe, int32_t ncandidates, int32_t k,
+                         int32_t *out_ids, float *out_scores, void *hip_stream, const plaid_vanilla_debug *dbg);
+
 /* Decompress the tokens of n listed passages (Section 4.5: packed byte -> bucket indices through the
  * 256-entry table, value = centroid + bucket weight, one fp32 addition per element).
  *   pids         DEVICE [n] passage ids

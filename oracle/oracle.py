@@ -269,6 +269,17 @@ def build_ivf_embeddings(codes: np.ndarray, C: int):
     return off, eids
 
 
+def vanilla_prune_scores(ix: Index, Q: np.ndarray, probed: np.ndarray, pids: np.ndarray) -> np.ndarray:
+    """Pruning score of each listed passage from the embeddings of the probed centroids' lists alone."""
+    Q = _chk(Q, np.float32)
+    pids = _chk(pids, np.int32)
+    in_e = np.ascontiguousarray(np.isin(ix.codes, np.unique(np.asarray(probed).reshape(-1))).astype(np.uint8))
+    out = np.empty(pids.shape[0], np.float32)
+    _load().orc_vanilla_prune_scores(ct.byref(ix.c), _p(Q), ct.c_int32(Q.shape[0]), _p(in_e), _p(pids), ct.c_int64(pids.shape[0]),
+                                     _p(out))
+    return out
+
+
 def vanilla_search(ix: Index, eoff: np.ndarray, eids: np.ndarray, Q: np.ndarray, nprobe: int, ncandidates: int, k: int,
                    dumps: bool = False):
     """One query through vanilla retrieval.  Returns (ids[k], scores[k]) or, with dumps, also a dict with the candidate

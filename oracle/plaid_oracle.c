@@ -339,6 +339,36 @@ int64_t orc_build_ivf_embeddings(const int32_t *codes, int64_t N, int64_t C, int
     return N;
 }
 
+/* Pruning score of each listed candidate (Section 4.1): sum over the query tokens of the maximum, over the passage's
+ * embeddings in E (inE[j] != 0), of Q_i . D_j with D_j decompressed in full; -inf for a passage with no embedding in E. */
+void orc_vanilla_prune_scores(const orc_index *ix, const float *Q, int32_t qlen, const uint8_t *inE, const int32_t *pids,
+                              int64_t n, float *scores)
+{
+    int32_t dim = ix->dim;
+    float *D = (float *)malloc((size_t)dim * sizeof(float));
+    for (int64_t a = 0; a < n; ++a) {
+        int64_t p = pids[a];
+        float best[ORC_QLEN_MAX];
+        int any = 0;
+        for (int32_t i = 0; i < qlen; ++i) best[i] = -INFINITY;
+        for (int64_t j = ix->doc_offsets[p]; j < ix->doc_offsets[p + 1]; ++j) {
+            if (!inE[j]) continue;
+            any = 1;
+            orc_decompress(ix, j, j + 1, D, NULL);
+            for (int32_t i = 0; i < qlen; ++i) {
+                double dot = 0.0;
+                for (int32_t t = 0; t < dim; ++t) dot += (double)Q[i * dim + t] * (double)D[t];
+                float f = (float)dot;
+                if (f > best[i]) best[i] = f;
+            }
+        }
+        double acc = 0.0;
+        for (int32_t i = 0; i < qlen; ++i) acc += (double)best[i];
+        scores[a] = any ? (float)acc : -INFINITY;
+    }
+    free(D);
+}
+
 typedef struct {  /* optional dumps of orc_vanilla_search; any pointer may be NULL */
     int32_t *cand;        /* [P] ascending candidate passages */
     int64_t *n_cand;
@@ -388,25 +418,7 @@ int32_t orc_vanilla_search(const orc_index *ix, const int64_t *eoff, const int64
     int32_t pruned = n_cand > ncandidates;
     if (pruned) {
         float *ps = (float *)malloc((size_t)n_cand * sizeof(float));
-        float *D = (float *)malloc((size_t)dim * sizeof(float));
-        for (int64_t a = 0; a < n_cand; ++a) {
-            int64_t p = cand[a];
-            float best[ORC_QLEN_MAX];
-            for (int32_t i = 0; i < qlen; ++i) best[i] = -INFINITY;
-            for (int64_t j = ix->doc_offsets[p]; j < ix->doc_offsets[p + 1]; ++j) {
-                if (!inE[j]) continue;
-                orc_decompress(ix, j, j + 1, D, NULL);
-                for (int32_t i = 0; i < qlen; ++i) {
-                    double dot = 0.0;
-                    for (int32_t t = 0; t < dim; ++t) dot += (double)Q[i * dim + t] * (double)D[t];
-                    float f = (float)dot;
-                    if (f > best[i]) best[i] = f;
-                }
-            }
-            double acc = 0.0;
-            for (int32_t i = 0; i < qlen; ++i) acc += (double)best[i];
-            ps[a] = (float)acc;
-        }
+        orc_vanilla_prune_scores(ix, Q, qlen, inE, cand, n_cand, ps);
         kbuf = (int32_t *)malloc((size_t)ncandidates * sizeof(int32_t));
         float *ks = (float *)malloc((size_t)ncandidates * sizeof(float));
         n_kept = orc_select(cand, ps, n_cand, ncandidates, kbuf, ks);
@@ -426,7 +438,6 @@ int32_t orc_vanilla_search(const orc_index *ix, const int64_t *eoff, const int64
         if (dump && dump->kept_scores) memcpy(dump->kept_scores, ks, (size_t)n_kept * sizeof(float));
         kept = kbuf;
         free(ps);
-        free(D);
         free(ks);
     }
     if (dump && dump->kept) memcpy(dump->kept, kept, (size_t)n_kept * sizeof(int32_t));

@@ -23,6 +23,7 @@ from .plaid import (  # noqa: F401
     plaid_search,
     plaid_search_debug,
     plaid_search_static,
+    plaid_search_vanilla,
     plaid_set_max_chunk,
     plaid_set_stage_timing,
     plaid_workspace_bytes,

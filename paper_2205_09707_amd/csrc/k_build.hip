@@ -230,3 +230,88 @@ void plaid_launch_ivf_build_fill(hipStream_t st, const int32_t *codes, const int
     hipLaunchKernelGGL(ivb_fill_kernel, dim3((unsigned)G), dim3(64), 0, st, codes, doc_offsets, P, N, C, per, (int32_t *)scratch,
                        ivf_offsets, ivf_pids, capacity);
 }
+
+// ------------------------------------------------------------------ embedding-level inverted lists (vanilla ColBERTv2 retrieval)
+// list c = the ascending indices of the tokens coded c (Section 4.1 describes vanilla's lists as centroid -> embedding
+// ids).  Same plan as above with groups of consecutive TOKENS: counts per (group, centroid), the same scans, then one
+// wave per group walks its tokens 64 at a time; a lane's position is the cursor of its code plus the number of earlier
+// lanes of the chunk with the same code, so the list comes out in token order without a sort and without atomics.
+__global__ __launch_bounds__(256) void evb_count_kernel(const int32_t *__restrict__ codes, int64_t N, int64_t C, int64_t per,
+                                                        int32_t *__restrict__ counts, int32_t *__restrict__ bad)
+{
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < N; j += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t c = codes[j];
+        if (c < 0 || c >= C) {
+            *bad = 1;
+            continue;
+        }
+        atomicAdd(&counts[(j / per) * C + c], 1);
+    }
+}
+__global__ __launch_bounds__(64) void evb_fill_kernel(const int32_t *__restrict__ codes, int64_t N, int64_t C, int64_t per,
+                                                      int32_t *__restrict__ starts, const int64_t *__restrict__ offsets,
+                                                      int32_t *__restrict__ eids)
+{
+    const int lane = threadIdx.x;
+    const int64_t g = blockIdx.x;
+    const int64_t j0 = g * per, j1 = j0 + per < N ? j0 + per : N;
+    int32_t *row = starts + g * C;
+    for (int64_t base = j0; base < j1; base += 64) {
+        const int64_t j = base + lane;
+        int32_t c = j < j1 ? codes[j] : -1;
+        if (c >= C) c = -1;  // (reported by the counting pass)
+        // earlier lanes of this chunk with my code, and whether I am the last lane with it
+        int before = 0, after = 0;
+        for (int l = 0; l < 64; ++l) {
+            const int32_t cl = __builtin_amdgcn_readlane(c, l);
+            before += (cl == c && l < lane) ? 1 : 0;
+            after += (cl == c && l > lane) ? 1 : 0;
+        }
+        if (c >= 0) {
+            const int32_t at = row[c] + before;   // the cursor of (group, c): only this wave touches it
+            eids[offsets[c] + at] = (int32_t)j;
+            if (after == 0) row[c] = at + 1;      // the last lane with this code moves the cursor past the chunk
+        }
+        // (the next chunk's reads of row[] follow this chunk's writes in program order: one wave, in-order memory)
+        __threadfence_block();
+    }
+}
+// scratch: plaid_ivf_build_scratch_bytes(N, C) bytes, zero on entry.  offsets [C+1], eids [N] (N < 2^31).
+void plaid_launch_embedding_lists(hipStream_t st, const int32_t *codes, int64_t N, int64_t C, void *scratch, int64_t *offsets,
+                                  int32_t *eids, int32_t *bad)
+{
+    const int64_t G = plaid_ivf_build_groups(N), per = (N + G - 1) / G;
+    int32_t *counts = (int32_t *)scratch;
+    int64_t *total = (int64_t *)((char *)scratch + ((size_t)G * (size_t)C * 4 + 255) / 256 * 256);
+    int64_t blocks = (N + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(evb_count_kernel, dim3((unsigned)blocks), dim3(256), 0, st, codes, N, C, per > 0 ? per : 1, counts, bad);
+    hipLaunchKernelGGL(ivb_totals_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, counts, C, G, total);
+    hipLaunchKernelGGL(ivb_scan_kernel, dim3(1), dim3(1024), 0, st, total, C, offsets);
+    hipLaunchKernelGGL(ivb_starts_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, counts, C, G);
+    if (N > 0)
+        hipLaunchKernelGGL(evb_fill_kernel, dim3((unsigned)G), dim3(64), 0, st, codes, N, C, per, counts, offsets, eids);
+}
+
+// tok2pid[j] = the passage token j belongs to (binary search in the passage offsets; empty passages own no token).
+__global__ __launch_bounds__(256) void tok2pid_kernel(const int64_t *__restrict__ doc_offsets, int64_t P, int64_t N,
+                                                      int32_t *__restrict__ tok2pid)
+{
+    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < N; j += (int64_t)gridDim.x * blockDim.x) {
+        int64_t lo = 0, hi = P;  // largest lo with doc_offsets[lo] <= j
+        while (hi - lo > 1) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (doc_offsets[mid] <= j) lo = mid;
+            else hi = mid;
+        }
+        tok2pid[j] = (int32_t)lo;
+    }
+}
+void plaid_launch_tok2pid(hipStream_t st, const int64_t *doc_offsets, int64_t P, int64_t N, int32_t *tok2pid)
+{
+    if (N <= 0) return;
+    int64_t blocks = (N + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(tok2pid_kernel, dim3((unsigned)blocks), dim3(256), 0, st, doc_offsets, P, N, tok2pid);
+}

@@ -215,6 +215,146 @@ __global__ __launch_bounds__(256, 3) void decompress_maxsim_kernel(
     }
 }
 
+// Vanilla ColBERTv2's pruning of an over-large candidate set (Section 4.1): a candidate's score from the embeddings
+// of E alone, E = the tokens whose centroid was probed (probebits: bit c = centroid c probed), each decompressed in full
+// like in the kernel above.  One wave per candidate; the tokens of E are compacted through a small LDS ring so that
+// the matrix instructions run on full 32-token steps whatever share of a passage E covers.  Queries whose candidate
+// count does not exceed ncandidates keep every candidate and are not scored: their keys get score 0.
+//   cand: [q][cand_stride] ascending candidate pids, n_cand[q] of them;  out_keys[q][j] = key of cand[q][j].
+template <int NBITS>
+__global__ __launch_bounds__(256, 3) void vanilla_prune_kernel(
+    const float *__restrict__ Q, const float *__restrict__ S, int64_t C, const int64_t *__restrict__ doc_offsets,
+    const int32_t *__restrict__ codes, const uint8_t *__restrict__ residuals, const float *__restrict__ weights,
+    const uint32_t *__restrict__ probebits, int64_t keep_words, const int32_t *__restrict__ cand, int64_t cand_stride,
+    const int32_t *__restrict__ n_cand, int32_t ncandidates, uint64_t *__restrict__ out_keys, int64_t out_stride)
+{
+    constexpr int RB = 16 * NBITS;
+    __shared__ s4_half8 hlut[256 * (NBITS == 2 ? 1 : 2)];
+    __shared__ int32_t ring_all[4][128];
+    const int q = blockIdx.y;
+    const int count = n_cand[q];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int32_t *cq = cand + (int64_t)q * cand_stride;
+    if (count <= ncandidates) {  // (uniform) no pruning for this query
+        for (int j = blockIdx.x * 256 + threadIdx.x; j < count; j += gridDim.x * 256)
+            out_keys[(int64_t)q * out_stride + j] = plaid_make_key(0.0f, (uint32_t)cq[j]);
+        return;
+    }
+    const int r32 = lane & 31, h = lane >> 5;
+    build_half_tables<NBITS>(hlut, weights, threadIdx.x, 256);
+    const float *Qq = Q + (int64_t)q * QLEN * DIM;
+    const float *Sq = S + (int64_t)q * C * QLEN;
+    const uint32_t *pb = probebits + (int64_t)q * keep_words;
+    s4_half8 q1[8], q2[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        const float4 *p = reinterpret_cast<const float4 *>(Qq + r32 * DIM + 16 * s + 8 * h);
+        const float4 u = p[0], w = p[1];
+        const float x[8] = {u.x, u.y, u.z, u.w, w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            _Float16 x1, x2;
+            s4_split(x[j], x1, x2);
+            q1[s][j] = x1;
+            q2[s][j] = x2;
+        }
+    }
+    __syncthreads();
+    int32_t *ring = ring_all[wave];
+    for (int j = (int)blockIdx.x * 4 + wave; j < count; j += (int)gridDim.x * 4) {
+        const uint32_t pid = (uint32_t)__builtin_amdgcn_readfirstlane(cq[j]);
+        const int64_t t0v = doc_offsets[pid];
+        const int64_t t0 = ((int64_t)__builtin_amdgcn_readfirstlane((int)(t0v >> 32)) << 32) |
+                           (uint32_t)__builtin_amdgcn_readfirstlane((int)(t0v & 0xFFFFFFFFll));
+        const int len = __builtin_amdgcn_readfirstlane((int)(doc_offsets[pid + 1] - t0v));
+        float m = -INFINITY;
+        int have = 0, done = 0;  // uniform: tokens of E listed so far / scored so far
+        for (int src = 0; src < len || done < have; src += 64) {
+            if (src < len) {
+                const int row = src + lane;
+                const int32_t c = row < len ? codes[t0 + row] : 0;
+                const bool in = row < len && ((pb[c >> 5] >> (c & 31)) & 1u);
+                const unsigned long long mask = __ballot(in);
+                if (in) ring[(have + __popcll(mask & ((1ull << lane) - 1ull))) & 127] = row;
+                have += __popcll(mask);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+            // full steps while 32 listed tokens wait; the remainder once the passage has been read
+            while (have - done >= 32 || (src + 64 >= len && done < have)) {
+                const int nrow = have - done < 32 ? have - done : 32;  // uniform
+                const int row = ring[(done + (r32 < nrow ? r32 : 0)) & 127];
+                const int64_t tok = t0 + row;
+                const int32_t code = codes[tok];
+                uint32_t rw[RB / 4];
+                {
+                    const uint4 *rp = reinterpret_cast<const uint4 *>(residuals + tok * RB);
+                    const uint4 v0 = rp[0];
+                    rw[0] = v0.x, rw[1] = v0.y, rw[2] = v0.z, rw[3] = v0.w;
+                    if (NBITS == 2) {
+                        const uint4 v1 = rp[1];
+                        rw[4] = v1.x, rw[5] = v1.y, rw[6] = v1.z, rw[7] = v1.w;
+                    }
+                }
+                float sv[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int rr = 8 * (v >> 2) + 4 * h + (v & 3);
+                    const uint32_t cv = (uint32_t)__shfl(code, rr);
+                    sv[v] = Sq[cv * (uint32_t)QLEN + (uint32_t)r32];
+                }
+                floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                floatx16 acx = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    s4_half8 a1, a2;
+                    if (NBITS == 2) {
+                        const uint32_t two = rw[s] >> (16 * h);
+                        const s4_half8 e0 = hlut[two & 0xFF], e1 = hlut[(two >> 8) & 0xFF];
+                        a1 = s4_half8{e0[0], e0[1], e0[2], e0[3], e1[0], e1[1], e1[2], e1[3]};
+                        a2 = s4_half8{e0[4], e0[5], e0[6], e0[7], e1[4], e1[5], e1[6], e1[7]};
+                    } else {
+                        const uint32_t b = (rw[s >> 1] >> (16 * (s & 1) + 8 * h)) & 0xFF;
+                        a1 = hlut[b];
+                        a2 = hlut[256 + b];
+                    }
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, q1[s], acc, 0, 0, 0);
+                    acx = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, q2[s], acx, 0, 0, 0);
+                    acx = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, q1[s], acx, 0, 0, 0);
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (8 * (v >> 2) + 4 * h + (v & 3) < nrow) m = fmaxf(m, fmaf(acx[v], 1.0f / S4_SCALE, acc[v]) + sv[v]);
+                done += nrow;
+            }
+        }
+        m = fmaxf(m, __shfl_xor(m, 32));
+        const float total = plaid_sum32_in_order(m);
+        if (lane == 0) out_keys[(int64_t)q * out_stride + j] = plaid_make_key(have > 0 ? total : -INFINITY, pid);
+    }
+}
+
+void plaid_launch_vanilla_prune(hipStream_t st, const float *Q, const float *S, int64_t C, const int64_t *doc_offsets,
+                                const int32_t *codes, const uint8_t *residuals, const float *bucket_weights, int nbits,
+                                const uint32_t *probebits, int64_t keep_words, int nq, const int32_t *cand, int64_t cand_stride,
+                                const int32_t *n_cand, int64_t n_upper, int32_t ncandidates, uint64_t *out_keys,
+                                int64_t out_stride)
+{
+    if (n_upper <= 0 || nq <= 0) return;
+    int64_t gx = (n_upper + 3) / 4;
+    const int64_t cap = (S4_RESIDENT_BLOCKS * 4 + nq - 1) / nq;
+    if (gx > cap) gx = cap;
+    if (gx < 1) gx = 1;
+    if (nbits == 2)
+        hipLaunchKernelGGL(vanilla_prune_kernel<2>, dim3((unsigned)gx, nq), dim3(256), 0, st, Q, S, C, doc_offsets, codes, residuals,
+                           bucket_weights, probebits, keep_words, cand, cand_stride, n_cand, ncandidates, out_keys, out_stride);
+    else
+        hipLaunchKernelGGL(vanilla_prune_kernel<1>, dim3((unsigned)gx, nq), dim3(256), 0, st, Q, S, C, doc_offsets, codes, residuals,
+                           bucket_weights, probebits, keep_words, cand, cand_stride, n_cand, ncandidates, out_keys, out_stride);
+}
+
 void plaid_launch_decompress_maxsim(hipStream_t st, const float *Q, const float *S, int64_t C, const int64_t *doc_offsets,
                                     const int32_t *codes, const uint8_t *residuals, const float *bucket_weights,
                                     int nbits, int nq, const uint64_t *in_keys, int64_t in_stride,

@@ -68,6 +68,10 @@ struct plaid_index {
     int32_t ivr_shift = 11;         // log2 of the passages per table column (11 or 13)
     int32_t *dense_id = nullptr;    // with the range table: bitmap row of each centroid's list, -1 for all but the longest
     uint32_t *dense_bits = nullptr; // [rows][ceil(P / 32)]
+    // vanilla ColBERTv2 retrieval (built on its first use): embedding-level inverted lists and the passage of each token
+    int64_t *emb_offsets = nullptr;  // [C + 1]
+    int32_t *emb_ids = nullptr;      // [N] ascending token indices per centroid
+    int32_t *tok2pid = nullptr;      // [N]
     float stage_ms[PLAID_NUM_STAGES] = {0};
     hipEvent_t ev[N_EVENTS] = {nullptr};
 };
@@ -818,6 +822,125 @@ extern "C" int plaid_search_static(plaid_index *idx, const float *Q, int32_t nq,
     if (!idx->static_ws) return fail(PLAID_EHIP, "the static workspace has no address on device %d", idx->device);
     return search_impl(idx, Q, nq, nprobe, t_cs, ndocs, k, out_ids, out_scores, hip_stream, nullptr, idx->static_ws,
                        PLAID_STATIC_WORKSPACE_BYTES);
+}
+
+// ------------------------------------------------------------------ vanilla ColBERTv2 retrieval (the paper's baseline)
+static int ensure_vanilla_structures(plaid_index *ix)
+{
+    if (ix->emb_offsets) return PLAID_OK;
+    if (ix->N >= (1ll << 31)) return fail(PLAID_EINVAL, "vanilla retrieval needs fewer than 2^31 embeddings (index has %lld)", (long long)ix->N);
+    HIP_TRY(hipDeviceSynchronize());
+    void *off = nullptr, *ids = nullptr, *t2p = nullptr, *scratch = nullptr;
+    const size_t sb = plaid_ivf_build_scratch_bytes(ix->N, ix->C) + 256;
+    const size_t nb = (size_t)(ix->N > 0 ? ix->N : 1) * 4;
+    if (hipMalloc(&off, (size_t)(ix->C + 1) * 8) != hipSuccess || hipMalloc(&ids, nb) != hipSuccess ||
+        hipMalloc(&t2p, nb) != hipSuccess || hipMalloc(&scratch, sb) != hipSuccess) {
+        (void)hipGetLastError();
+        if (off) (void)hipFree(off);
+        if (ids) (void)hipFree(ids);
+        if (t2p) (void)hipFree(t2p);
+        if (scratch) (void)hipFree(scratch);
+        return fail(PLAID_ENOMEM, "device allocation for the embedding-level inverted lists failed");
+    }
+    ix->owned.push_back(off);
+    ix->owned.push_back(ids);
+    ix->owned.push_back(t2p);
+    int32_t bad = 0;
+    hipError_t e = hipMemset(scratch, 0, sb);
+    if (e == hipSuccess) {
+        int32_t *bad_d = (int32_t *)((char *)scratch + sb - 256);
+        plaid_launch_embedding_lists(nullptr, ix->codes, ix->N, ix->C, scratch, (int64_t *)off, (int32_t *)ids, bad_d);
+        plaid_launch_tok2pid(nullptr, ix->doc_offsets, ix->P, ix->N, (int32_t *)t2p);
+        e = hipGetLastError();
+        if (e == hipSuccess) e = hipMemcpy(&bad, bad_d, 4, hipMemcpyDeviceToHost);
+    }
+    (void)hipFree(scratch);
+    if (e != hipSuccess) return fail(PLAID_EHIP, "building the embedding-level inverted lists: %s", hipGetErrorString(e));
+    if (bad) return fail(PLAID_EINVAL, "a centroid id is outside [0, %lld)", (long long)ix->C);
+    ix->emb_offsets = (int64_t *)off;
+    ix->emb_ids = (int32_t *)ids;
+    ix->tok2pid = (int32_t *)t2p;
+    return PLAID_OK;
+}
+
+extern "C" int plaid_search_vanilla(plaid_index *ix, const float *Q, int32_t nq, int32_t nprobe, int32_t ncandidates, int32_t k,
+                                    int32_t *out_ids, float *out_scores, void *hip_stream, const plaid_vanilla_debug *dbg)
+{
+    if (!ix) return fail(PLAID_EINVAL, "null index");
+    if (!Q || !out_ids || !out_scores) return fail(PLAID_EINVAL, "null buffer");
+    if ((uintptr_t)Q & 15) return fail(PLAID_EINVAL, "Q must be aligned to 16 bytes");
+    if (nq < 1) return fail(PLAID_EINVAL, "nq must be >= 1 (got %d)", nq);
+    if (nprobe < 1 || nprobe > ix->C) return fail(PLAID_EINVAL, "nprobe must be in [1, C] (got %d, C = %lld)", nprobe, (long long)ix->C);
+    if (ncandidates < 1) return fail(PLAID_EINVAL, "ncandidates must be >= 1 (got %d)", ncandidates);
+    if (k < 1) return fail(PLAID_EINVAL, "k must be >= 1 (got %d)", k);
+    DeviceGuard g(ix->device);
+    if (!g.ok) return fail(PLAID_EHIP, "hipSetDevice(%d) failed", ix->device);
+    int rc = ensure_vanilla_structures(ix);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int64_t C = ix->C, P = ix->P;
+    Plan pl;
+    pl.nprobe = nprobe;
+    pl.nd = (int32_t)(ncandidates < P ? ncandidates : P);  // candidates kept by the cap
+    pl.m3 = pl.nd;
+    pl.kk = k < pl.nd ? k : pl.nd;
+    const int form = (ix->scq_form == PLAID_SCQ_SPLIT16 && nprobe > PLAID_PROBE_FAST_MAX)
+                         ? (ix->scq_matrix_form ? PLAID_SCQ_MATRIX : PLAID_SCQ_VECTOR)
+                         : ix->scq_form;
+    const int qc = choose_chunk(ix, nq, pl);
+    const Workspace wsz = carve(nullptr, ix, qc, pl);
+    // beyond the search workspace: the state and the lists of the selection that applies the ncandidates cap
+    const size_t selz = a256(plaid_select_zero_bytes(qc)), selb = a256(plaid_select_body_bytes(qc, P, pl.nd));
+    rc = ensure_workspace(ix, wsz.total + selz + selb);
+    if (rc) return rc;
+    for (int32_t q0 = 0; q0 < nq; q0 += qc) {
+        const int n = nq - q0 < qc ? nq - q0 : qc;
+        const Workspace w = carve((char *)ix->ws, ix, n, pl);
+        char *extra = (char *)ix->ws + wsz.total;
+        const SelScratch scp = plaid_select_scratch_carve2(extra, extra + selz, n, P, pl.nd);
+        const SelScratch sc4 = plaid_select_scratch_carve2(w.sel4_zero, w.sel4_body, n, pl.m3, pl.kk);
+        const float *Qc = Q + (int64_t)q0 * QLEN * DIM;
+        // Eq. 2 and the probes, as in plaid_search (no pruning map is needed: t_cs = +infinity)
+        for (int phase = PLAID_STAGE1_PREP; phase <= PLAID_STAGE1_PROBES; phase <<= 1)
+            plaid_launch_stage1(st, phase, ix->centroids, C, Qc, w.Qd, form, ix->A16, n, INFINITY, nprobe, w.S, w.keepbits, w.ambbits,
+                                w.keep_words, w.tilemax, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed, w.uniq,
+                                w.uniq_stride, w.n_uniq, w.s2, w.probe_scratch, w.probe_scratch_bytes);
+        // candidate passages from the embedding lists of the probed centroids (Section 4.1)
+        uint32_t *probebits = w.ambbits;       // free once the probes are known
+        int32_t *cand = (int32_t *)w.s2.blist;  // [n][P]
+        plaid_launch_fill_u32(st, probebits, (int64_t)n * w.keep_words, 0u);
+        plaid_launch_fill_u32(st, (uint32_t *)scp.state, (int64_t)(plaid_select_zero_bytes(n) / 4), 0u);
+        plaid_launch_vanilla_candidates(st, w.uniq, w.n_uniq, w.uniq_stride, ix->emb_offsets, ix->emb_ids, ix->tok2pid, n,
+                                        w.keep_words, probebits, w.candbits, w.cand_words);
+        plaid_launch_bitmap_to_list(st, w.candbits, w.cand_words, P, n, cand, P, w.n2);
+        // more than ncandidates: scored on the embeddings of the probed lists alone, the best ncandidates stay
+        plaid_launch_vanilla_prune(st, Qc, w.S, C, ix->doc_offsets, ix->codes, ix->residuals, ix->weights, ix->nbits, probebits,
+                                   w.keep_words, n, cand, P, w.n2, P, pl.nd, w.keys2, P);
+        plaid_launch_select(st, w.keys2, P, w.n2, n, P, pl.nd, w.sel2, pl.nd, w.n3, 0, scp, 0);
+        // every token of every remaining candidate: decompression + exact MaxSim (Section 3.2, Eq. 1), best k
+        plaid_launch_decompress_maxsim(st, Qc, w.S, C, ix->doc_offsets, ix->codes, ix->residuals, ix->weights, ix->nbits, n,
+                                       w.sel2, pl.nd, w.n3, pl.nd, w.keys4, pl.m3);
+        if (pl.m3 <= SEL_SORT_CAP) {
+            plaid_launch_rank_output(st, w.keys4, pl.m3, w.n3, n, pl.m3, k, out_ids + (int64_t)q0 * k, out_scores + (int64_t)q0 * k);
+        } else {
+            plaid_launch_select(st, w.keys4, pl.m3, w.n3, n, pl.m3, pl.kk, w.topk, pl.kk, w.n_out, 1, sc4, 0);
+            plaid_launch_keys_to_output(st, w.topk, pl.kk, w.n_out, n, k, out_ids + (int64_t)q0 * k, out_scores + (int64_t)q0 * k);
+        }
+        HIP_TRY(hipGetLastError());
+        if (dbg) {
+            if (dbg->cand)
+                HIP_TRY(hipMemcpy2DAsync(dbg->cand + (int64_t)q0 * P, (size_t)P * 4, cand, (size_t)P * 4, (size_t)P * 4, n,
+                                         hipMemcpyDeviceToDevice, st));
+            if (dbg->n_cand) HIP_TRY(hipMemcpyAsync(dbg->n_cand + q0, w.n2, (size_t)n * 4, hipMemcpyDeviceToDevice, st));
+            if (dbg->kept_ids || dbg->kept_scores || dbg->n_kept)
+                plaid_launch_keys_to_pairs(st, w.sel2, pl.nd, w.n3, n, ncandidates,
+                                           dbg->kept_ids ? dbg->kept_ids + (int64_t)q0 * ncandidates : nullptr,
+                                           dbg->kept_scores ? dbg->kept_scores + (int64_t)q0 * ncandidates : nullptr,
+                                           dbg->n_kept ? dbg->n_kept + q0 : nullptr);
+            HIP_TRY(hipGetLastError());
+        }
+    }
+    return PLAID_OK;
 }
 
 // ------------------------------------------------------------------ workspace size (host arithmetic only)

@@ -270,6 +270,27 @@ void plaid_launch_passage_offsets(hipStream_t st, const int64_t *doc_offsets, co
 void plaid_launch_index_validate(hipStream_t st, const int64_t *doc_offsets, int64_t P, int64_t N, const int32_t *codes,
                                  int64_t C, const int64_t *ivf_offsets, const int32_t *ivf_pids, int64_t ivf_len, int32_t *bad);
 
+// ---------------------------------------------------------------------------------------------
+// Vanilla ColBERTv2 retrieval, the paper's baseline (k_build.hip, k_vanilla.hip, k_stage4.hip)
+// ---------------------------------------------------------------------------------------------
+// Embedding-level inverted lists: offsets [C+1], eids [N] = ascending token indices per centroid (N < 2^31);
+// scratch: plaid_ivf_build_scratch_bytes(N, C) bytes, zero on entry; bad[0] is set when a code is out of range.
+void plaid_launch_embedding_lists(hipStream_t st, const int32_t *codes, int64_t N, int64_t C, void *scratch, int64_t *offsets,
+                                  int32_t *eids, int32_t *bad);
+void plaid_launch_tok2pid(hipStream_t st, const int64_t *doc_offsets, int64_t P, int64_t N, int32_t *tok2pid);
+// probebits (zero on entry) = bitmap of each query's probed centroids; candbits (zero on entry) |= the passages that own
+// an embedding of those centroids' embedding lists.
+void plaid_launch_vanilla_candidates(hipStream_t st, const int32_t *uniq, const int32_t *n_uniq, int uniq_stride,
+                                     const int64_t *eoff, const int32_t *eids, const int32_t *tok2pid, int nq, int64_t keep_words,
+                                     uint32_t *probebits, uint32_t *candbits, int64_t cand_words);
+// out_keys[q][j] = key of candidate cand[q][j] scored on the embeddings of the probed lists alone (score 0 for every
+// candidate of a query with at most ncandidates of them).
+void plaid_launch_vanilla_prune(hipStream_t st, const float *Q, const float *S, int64_t C, const int64_t *doc_offsets,
+                                const int32_t *codes, const uint8_t *residuals, const float *bucket_weights, int nbits,
+                                const uint32_t *probebits, int64_t keep_words, int nq, const int32_t *cand, int64_t cand_stride,
+                                const int32_t *n_cand, int64_t n_upper, int32_t ncandidates, uint64_t *out_keys,
+                                int64_t out_stride);
+
 // Small utilities
 void plaid_launch_fill_u32(hipStream_t st, uint32_t *p, int64_t n, uint32_t v);
 void plaid_launch_keys_to_output(hipStream_t st, const uint64_t *keys, int64_t key_stride, const int32_t *counts, int nq,

@@ -43,8 +43,12 @@ class plaid_debug_buffers(ct.Structure):
                                             "sel3_ids", "sel3_scores", "n3", "keep")]
 
 
+class plaid_vanilla_debug(ct.Structure):
+    _fields_ = [(n, ct.c_void_p) for n in ("cand", "n_cand", "kept_ids", "kept_scores", "n_kept")]
+
+
 EXPORTS = ("plaid_index_load", "plaid_index_from_view", "plaid_index_free", "plaid_search", "plaid_search_debug",
-           "plaid_search_static", "plaid_decompress_passages", "plaid_index_info", "plaid_set_stage_timing", "plaid_get_stage_ms",
+           "plaid_search_static", "plaid_search_vanilla", "plaid_decompress_passages", "plaid_index_info", "plaid_set_stage_timing", "plaid_get_stage_ms",
            "plaid_set_max_chunk", "plaid_get_score_kernel", "plaid_get_stage2_kernel", "plaid_assign_centroids",
            "plaid_encode_residuals", "plaid_build_ivf", "plaid_workspace_bytes", "plaid_last_error")
 
@@ -70,6 +74,8 @@ def load_library() -> ct.CDLL:
                                      ct.c_void_p, ct.c_void_p, ct.c_void_p]
         lib.plaid_search_debug.argtypes = lib.plaid_search.argtypes + [ct.POINTER(plaid_debug_buffers)]
         lib.plaid_search_static.argtypes = lib.plaid_search.argtypes
+        lib.plaid_search_vanilla.argtypes = [ct.c_void_p, ct.c_void_p, ct.c_int32, ct.c_int32, ct.c_int32, ct.c_int32, ct.c_void_p,
+                                             ct.c_void_p, ct.c_void_p, ct.POINTER(plaid_vanilla_debug)]
         lib.plaid_decompress_passages.argtypes = [ct.c_void_p, ct.c_void_p, ct.c_int32, ct.c_void_p, ct.c_void_p,
                                                   ct.c_void_p, ct.c_int64, ct.c_void_p]
         lib.plaid_index_info.argtypes = [ct.c_void_p] + [ct.c_void_p] * 5
@@ -223,6 +229,27 @@ def plaid_search_static(idx: Index, Q: torch.Tensor, nprobe: int, t_cs: float, n
     _check(load_library().plaid_search_static(idx.handle, _ptr(Q), nq, int(nprobe), float(t_cs), int(ndocs), int(k),
                                               _ptr(out_ids), _ptr(out_scores), _stream(Q.device)))
     return out_ids, out_scores
+
+
+def plaid_search_vanilla(idx: Index, Q: torch.Tensor, nprobe: int, ncandidates: int, k: int, debug: bool = False):
+    """Vanilla ColBERTv2 retrieval (the paper's baseline) on the same index.  Returns (ids, scores) [nq,k] or, with
+    debug, also a dict of device tensors: cand [nq,P], n_cand, kept_ids / kept_scores [nq,ncandidates], n_kept."""
+    Q = _check_Q(idx, Q)
+    nq = Q.shape[0]
+    dev = Q.device
+    out_ids = torch.empty((nq, int(k)), dtype=torch.int32, device=dev)
+    out_scores = torch.empty((nq, int(k)), dtype=torch.float32, device=dev)
+    bufs = None
+    dbg = None
+    if debug:
+        bufs = dict(cand=torch.zeros((nq, idx.P), dtype=torch.int32, device=dev), n_cand=torch.zeros(nq, dtype=torch.int32, device=dev),
+                    kept_ids=torch.zeros((nq, int(ncandidates)), dtype=torch.int32, device=dev),
+                    kept_scores=torch.zeros((nq, int(ncandidates)), dtype=torch.float32, device=dev),
+                    n_kept=torch.zeros(nq, dtype=torch.int32, device=dev))
+        dbg = ct.byref(plaid_vanilla_debug(**{n: t.data_ptr() for n, t in bufs.items()}))
+    _check(load_library().plaid_search_vanilla(idx.handle, _ptr(Q), nq, int(nprobe), int(ncandidates), int(k), _ptr(out_ids),
+                                               _ptr(out_scores), _stream(dev), dbg))
+    return (out_ids, out_scores, bufs) if debug else (out_ids, out_scores)
 
 
 def plaid_search_debug(idx: Index, Q: torch.Tensor, nprobe: int, t_cs: float, ndocs: int, k: int, want=None):

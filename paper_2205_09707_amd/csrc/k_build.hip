@@ -121,16 +121,20 @@ __global__ __launch_bounds__(256) void ivb_count_kernel(const int32_t *__restric
     }
 }
 
-// Scan, step 1: total[c] = sum over the groups; step 2 (after the scan of total into ivf_offsets):
-// counts[g][c] <- ivf_offsets[c] + sum of counts[g'][c] over g' < g, kept as a 32-bit offset inside the list.
-__global__ __launch_bounds__(256) void ivb_totals_kernel(const int32_t *__restrict__ counts, int64_t C, int64_t G,
+// One pass over the count table: counts[g][c] <- sum of counts[g'][c] over g' < g (the 32-bit position inside list c at
+// which group g starts writing), total[c] = the sum over all groups (the list's length).
+__global__ __launch_bounds__(256) void ivb_totals_kernel(int32_t *__restrict__ counts, int64_t C, int64_t G,
                                                          int64_t *__restrict__ total)
 {
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= C) return;
-    int64_t s = 0;
-    for (int64_t g = 0; g < G; ++g) s += counts[g * C + c];
-    total[c] = s;
+    int32_t run = 0;  // (a list has at most P < 2^31 entries)
+    for (int64_t g = 0; g < G; ++g) {
+        const int32_t v = counts[g * C + c];
+        counts[g * C + c] = run;
+        run += v;
+    }
+    total[c] = run;
 }
 // One workgroup: ivf_offsets[0 .. C] = exclusive prefix sum of total[0 .. C).
 __global__ __launch_bounds__(1024) void ivb_scan_kernel(const int64_t *__restrict__ total, int64_t C,
@@ -160,18 +164,6 @@ __global__ __launch_bounds__(1024) void ivb_scan_kernel(const int64_t *__restric
         run += total[c];
     }
 }
-__global__ __launch_bounds__(256) void ivb_starts_kernel(int32_t *__restrict__ counts, int64_t C, int64_t G)
-{
-    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
-    int32_t run = 0;  // position inside list c (a list has at most P < 2^31 entries)
-    for (int64_t g = 0; g < G; ++g) {
-        const int32_t v = counts[g * C + c];
-        counts[g * C + c] = run;
-        run += v;
-    }
-}
-
 // Pass 2: one wave per group, passages in ascending id order.  The position comes back from the atomic before the
 // passage id is stored, so the wave has finished one passage before it starts the next: every (group, centroid)
 // cursor hands out its positions in passage order.
@@ -221,7 +213,6 @@ void plaid_launch_ivf_build_offsets(hipStream_t st, const int32_t *codes, const 
     hipLaunchKernelGGL(ivb_count_kernel, dim3((unsigned)blocks), dim3(256), 0, st, codes, doc_offsets, P, N, C, per, counts, bad);
     hipLaunchKernelGGL(ivb_totals_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, counts, C, G, total);
     hipLaunchKernelGGL(ivb_scan_kernel, dim3(1), dim3(1024), 0, st, total, C, ivf_offsets);
-    hipLaunchKernelGGL(ivb_starts_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, counts, C, G);
 }
 void plaid_launch_ivf_build_fill(hipStream_t st, const int32_t *codes, const int64_t *doc_offsets, int64_t P, int64_t N,
                                  int64_t C, void *scratch, const int64_t *ivf_offsets, int32_t *ivf_pids, int64_t capacity)
@@ -289,7 +280,6 @@ void plaid_launch_embedding_lists(hipStream_t st, const int32_t *codes, int64_t 
     hipLaunchKernelGGL(evb_count_kernel, dim3((unsigned)blocks), dim3(256), 0, st, codes, N, C, per > 0 ? per : 1, counts, bad);
     hipLaunchKernelGGL(ivb_totals_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, counts, C, G, total);
     hipLaunchKernelGGL(ivb_scan_kernel, dim3(1), dim3(1024), 0, st, total, C, offsets);
-    hipLaunchKernelGGL(ivb_starts_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, st, counts, C, G);
     if (N > 0)
         hipLaunchKernelGGL(evb_fill_kernel, dim3((unsigned)G), dim3(64), 0, st, codes, N, C, per, counts, offsets, eids);
 }

@@ -366,9 +366,8 @@ def plaid_build_ivf(codes: torch.Tensor, doc_offsets: torch.Tensor, num_centroid
     off = torch.empty((C + 1,), dtype=torch.int64, device=dev)
     total = ct.c_int64(0)
     lib = load_library()
-    _check(lib.plaid_build_ivf(_ptr(codes), _ptr(doc_offsets), P, N, C, _ptr(off), None, 0, ct.byref(total), dev.index or 0,
-                               _stream(dev)))
-    pids = torch.empty((max(int(total.value), 1),), dtype=torch.int32, device=dev)
+    # one call: the lists hold at most one entry per token, so a buffer of N entries always suffices
+    pids = torch.empty((max(N, 1),), dtype=torch.int32, device=dev)
     _check(lib.plaid_build_ivf(_ptr(codes), _ptr(doc_offsets), P, N, C, _ptr(off), _ptr(pids), pids.shape[0], ct.byref(total),
                                dev.index or 0, _stream(dev)))
     return off, pids[:int(total.value)]

@@ -304,7 +304,8 @@ def plaid_set_max_chunk(idx: Index, max_queries_per_chunk: int) -> None:
 
 
 def plaid_get_score_kernel(idx: Index) -> int:
-    """1 when S_cq is computed with the double-precision matrix instruction, 0 for the vector FMA chain."""
+    """The kernel that computes S_cq for this index: 2 = fp16 matrix instruction on two-term operand splits (decisions
+    completed in double), 1 = double-precision matrix instruction, 0 = double-precision vector FMA chain."""
     form = ct.c_int32(-1)
     _check(load_library().plaid_get_score_kernel(idx.handle, ct.byref(form)))
     return int(form.value)

@@ -27,7 +27,7 @@ KERNELS = {
     "s2_invert_kernelILi13EyE": ("k_stage2.hip", 128, 100 << 10),  # ... 64-bit sets: one per CU
     "s2_union_wide_kernel": ("k_stage2.hip", 128, 80 << 10),       # two workgroups of 1024 threads per CU
     "s2_stream_kernel": ("k_stage2.hip", 128, 40 << 10),
-    "ci_list_kernel": ("k_ci.hip", 64, 0),
+    "ci_list_kernelILb0E": ("k_ci.hip", 96, 8 << 10),              # five waves per SIMD; wave-private LDS areas
     "decompress_maxsim_kernelILi2ELb0E": ("k_stage4.hip", 168, 16 << 10),   # three waves per SIMD
     "decompress_maxsim_kernelILi1ELb0E": ("k_stage4.hip", 168, 16 << 10),
     "sel_sort_kernelILi512E": ("k_select.hip", 64, 0),             # dynamic LDS only

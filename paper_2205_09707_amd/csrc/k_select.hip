@@ -849,18 +849,38 @@ __global__ __launch_bounds__(FIN_THREADS) void sel2_finish_kernel(const uint64_t
         lds_bitonic_sort(sk, n2);
         for (int i = threadIdx.x; i < m_rem; i += FIN_THREADS) o[n_sure + i] = sk[i];
     } else {
-        // still long (huge tie groups): radix selection over global memory by this one workgroup
+        // still long (huge tie groups): radix selection over global memory by this one workgroup.  The keys of such a
+        // list mostly share their digit (that is what made the list long), so a wave whose keys all have one digit
+        // counts them with a single LDS update instead of 64 updates of one address.
         uint64_t prefix = 0, pmask = 0;
         int r = m_rem;
         int pos = top_bit;
+        const int lane = threadIdx.x & 63;
+        const int nb_round = (nb + FIN_THREADS - 1) / FIN_THREADS * FIN_THREADS;  // whole waves in every step
         while (pos > 0 && r > 0) {
             const int w = pos < 8 ? pos : 8;
             pos -= w;
             for (int b = threadIdx.x; b < 256; b += FIN_THREADS) h256[b] = 0;
             __syncthreads();
-            for (int i = threadIdx.x; i < nb; i += FIN_THREADS) {
-                const uint64_t key = bl[i];
-                if ((key & pmask) == prefix) atomicAdd(&h256[(int)((key >> pos) & ((1u << w) - 1u))], 1);
+            for (int i0 = threadIdx.x; i0 < nb_round; i0 += 4 * FIN_THREADS) {
+                uint64_t key[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = i0 + u * FIN_THREADS;
+                    key[u] = i < nb ? bl[i] : ~prefix;  // a key past the end never matches the prefix
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = i0 + u * FIN_THREADS;
+                    const int dgt = (i < nb && (key[u] & pmask) == prefix) ? (int)((key[u] >> pos) & ((1u << w) - 1u)) : -1;
+                    const int first = __builtin_amdgcn_readfirstlane(dgt);
+                    const unsigned long long same = __ballot(dgt == first);
+                    if (same == __ballot(true)) {  // uniform digit (or no key in play) in this wave
+                        if (lane == (int)__builtin_ctzll(same) && first >= 0) atomicAdd(&h256[first], __popcll(same));
+                    } else if (dgt >= 0) {
+                        atomicAdd(&h256[dgt], 1);
+                    }
+                }
             }
             __syncthreads();
             if (threadIdx.x == 0) {
@@ -881,9 +901,16 @@ __global__ __launch_bounds__(FIN_THREADS) void sel2_finish_kernel(const uint64_t
         if (threadIdx.x == 0) sh[2] = 0;
         __syncthreads();
         if (m_rem > 0)
-            for (int i = threadIdx.x; i < nb; i += FIN_THREADS) {
-                const uint64_t key = bl[i];
-                if ((key & pmask) <= prefix) o[n_sure + atomicAdd(&sh[2], 1)] = key;
+            for (int i0 = threadIdx.x; i0 < nb_round; i0 += FIN_THREADS) {
+                const uint64_t key = i0 < nb ? bl[i0] : 0;
+                const bool take = i0 < nb && (key & pmask) <= prefix;
+                const unsigned long long tk = __ballot(take);
+                if (tk) {  // one counter update per wave
+                    int base = 0;
+                    if (lane == (int)__builtin_ctzll(tk)) base = atomicAdd(&sh[2], __popcll(tk));
+                    base = __shfl(base, (int)__builtin_ctzll(tk));
+                    if (take) o[n_sure + base + __popcll(tk & ((1ull << lane) - 1ull))] = key;
+                }
             }
     }
     __syncthreads();

@@ -188,17 +188,24 @@ __device__ __forceinline__ void stage1_survivor_table(const float *__restrict__ 
     if (ivf_offsets && K > 1 && K <= S2_MAX_KEPT) {
         int32_t my_id = 0;
         int rank = 0;
+        uint32_t *lens = trial;  // the first K words serve as the list lengths here and are cleared again below
         if (tid < K) {
             my_id = ids[tid];
-            const int64_t my_len = ivf_offsets[my_id + 1] - ivf_offsets[my_id];
+            lens[tid] = (uint32_t)(ivf_offsets[my_id + 1] - ivf_offsets[my_id]);  // at most P < 2^31 entries
+        }
+        __syncthreads();
+        if (tid < K) {
+            const uint32_t my_len = lens[tid];
             for (int u = 0; u < K; ++u) {
-                const int32_t c = ids[u];
-                const int64_t len = ivf_offsets[c + 1] - ivf_offsets[c];
+                const uint32_t len = lens[u];
                 rank += (len > my_len || (len == my_len && u < tid)) ? 1 : 0;
             }
         }
         __syncthreads();
-        if (tid < K) ids[rank] = my_id;
+        if (tid < K) {
+            ids[rank] = my_id;
+            lens[tid] = 0u;
+        }
         __syncthreads();
     }
     // a hash h(c) = (c ^ (c >> sh)) & (S2_HASH - 1) that maps the survivors to distinct entries makes a lookup one
@@ -228,10 +235,15 @@ __device__ __forceinline__ void stage1_survivor_table(const float *__restrict__ 
         if (tid < K) kept_ids_q[tid] = ids[tid];
         if (tid < QLEN) {
             float mx = -INFINITY, mn = INFINITY;
-            for (int s = 0; s < K; ++s) {
-                const float v = Sq[(int64_t)ids[s] * QLEN + tid];
-                mx = fmaxf(mx, v);
-                mn = fminf(mn, v);
+            for (int s0 = 0; s0 < K; s0 += 8) {  // eight rows in flight
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = Sq[(int64_t)ids[s0 + u < K ? s0 + u : s0] * QLEN + tid];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    mx = fmaxf(mx, v[u]);
+                    mn = fminf(mn, v[u]);
+                }
             }
             colmm[tid] = mx;
             colmm[QLEN + tid] = mn;
@@ -942,7 +954,9 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
                     atomicOr(&kbq[c >> 5], 1u << (c & 31));
             }
         }
-        __threadfence();
+        // The updates of the pruning words above are atomics, performed in the second-level cache, and the table below
+        // reads the words there too (atomic loads): the barrier's wait for this wave's outstanding memory operations is
+        // all the ordering the two need.
         __syncthreads();
     }
     stage1_survivor_table<APPROX>(S + (int64_t)q * C * QLEN, C, keepbits + (int64_t)q * keep_words, keep_words, top1,

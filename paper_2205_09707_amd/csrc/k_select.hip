@@ -736,6 +736,10 @@ __global__ __launch_bounds__(SEL_THREADS) void sel2_filter_kernel(const uint64_t
     }
 }
 
+// A boundary list longer than this goes through one digit pass (all workgroups of the query) before the finishing
+// workgroup sorts what is left: far below what that workgroup could sort (SEL_SORT_CAP), because its sort is the one
+// serial step of the selection.
+#define SEL2_DIGIT_MIN 1024
 __device__ __forceinline__ void sel2_digit_plan(const Sel2State *s, int &shift, int &width)
 {
     const unsigned long long diff = s->b_or & s->b_nor;
@@ -753,7 +757,7 @@ __global__ __launch_bounds__(SEL_THREADS) void sel2_digit_hist_kernel(const uint
     const int seg = blockIdx.y;
     Sel2State *s = state + seg;
     const int n = s->n_b;
-    if (n <= SEL_SORT_CAP) return;
+    if (n <= SEL2_DIGIT_MIN) return;
     int shift, width;
     sel2_digit_plan(s, shift, width);
     for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS) lh[b] = 0;
@@ -785,7 +789,7 @@ __global__ __launch_bounds__(SEL_THREADS) void sel2_digit_filter_kernel(const ui
     const int seg = blockIdx.y;
     Sel2State *s = state + seg;
     const int n = s->n_b;
-    if (n <= SEL_SORT_CAP) return;
+    if (n <= SEL2_DIGIT_MIN) return;
     int shift, width;
     sel2_digit_plan(s, shift, width);
     const int32_t m_rem = s->m_rem;
@@ -833,7 +837,7 @@ __global__ __launch_bounds__(FIN_THREADS) void sel2_finish_kernel(const uint64_t
     __shared__ int32_t sh[4];
     const int seg = blockIdx.x;
     const Sel2State *s = state + seg;
-    const bool two = s->n_b > SEL_SORT_CAP;
+    const bool two = s->n_b > SEL2_DIGIT_MIN;
     const uint64_t *bl = two ? blist1 + (int64_t)seg * blist1_stride : blist + (int64_t)seg * blist_stride;
     const int nb = two ? s->n_b1 : s->n_b;
     const int m_rem = two ? s->m_rem1 : s->m_rem;
@@ -965,8 +969,8 @@ void plaid_launch_select2(hipStream_t st, uint64_t *keys2, int64_t key_stride, c
     const int gx = blocks_for(P, nq);
     hipLaunchKernelGGL(sel2_filter_kernel, dim3(gx, nq), dim3(SEL_THREADS), 0, st, keys2, key_stride, candbits, cand_words, P,
                        m, b.meta, b.hist, b.state, out, out_stride, b.blist, P);
-    if (P > SEL_SORT_CAP) {
-        // only a boundary bin longer than SEL_SORT_CAP makes these two do anything; keys2 serves as blist1
+    if (P > SEL2_DIGIT_MIN) {
+        // only a boundary bin longer than SEL2_DIGIT_MIN makes these two do anything; keys2 serves as blist1
         hipLaunchKernelGGL(sel2_digit_hist_kernel, dim3(gx, nq), dim3(SEL_THREADS), 0, st, b.blist, P, b.state, b.hist1);
         hipLaunchKernelGGL(sel2_digit_filter_kernel, dim3(gx, nq), dim3(SEL_THREADS), 0, st, b.blist, P, b.state, b.hist1,
                            out, out_stride, keys2, key_stride);

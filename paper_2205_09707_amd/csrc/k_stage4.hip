@@ -86,32 +86,82 @@ __device__ __forceinline__ void build_half_tables(s4_half8 *hlut, const float *_
     }
 }
 
-// Passages are scored 32 tokens per step with v_mfma_f32_32x32x16_f16.  Lane = 32 h + r: for the A operand r is the
-// passage token of the step, for the B operand and the result r is the query token; both operands hold dimensions
-// 16 s + 8 h .. 16 s + 8 h + 7 at step s of the 128 dimensions.
+// Column maxima of a 32 x 32 result block spread over the wave as the matrix instruction leaves it: lane 32 h + n holds
+// mx[v] = the value of query token 8 (v / 4) + 4 h + v % 4 for passage-token column n.  Returns, in lane 32 h + 2 v (and
+// its odd neighbour), the maximum over the 32 columns for that query token: a butterfly in which each exchange halves the
+// number of values a lane still carries (16 exchanges instead of 16 x 5).
+__device__ __forceinline__ float s4_column_maxima(const float (&mx)[16], int lane)
+{
+    float a8[8], a4[4], a2[2];
+    const bool b4 = lane & 16, b3 = lane & 8, b2 = lane & 4, b1 = lane & 2;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float keep = b4 ? mx[8 + e] : mx[e], send = b4 ? mx[e] : mx[8 + e];
+        a8[e] = fmaxf(keep, __shfl_xor(send, 16));
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float keep = b3 ? a8[4 + e] : a8[e], send = b3 ? a8[e] : a8[4 + e];
+        a4[e] = fmaxf(keep, __shfl_xor(send, 8));
+    }
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const float keep = b2 ? a4[2 + e] : a4[e], send = b2 ? a4[e] : a4[2 + e];
+        a2[e] = fmaxf(keep, __shfl_xor(send, 4));
+    }
+    const float keep = b1 ? a2[1] : a2[0], send = b1 ? a2[0] : a2[1];
+    const float a1 = fmaxf(keep, __shfl_xor(send, 2));
+    return fmaxf(a1, __shfl_xor(a1, 1));
+}
+// The lane that holds query token i after s4_column_maxima, and the query token of an even lane.
+__device__ __forceinline__ constexpr int s4_lane_of_token(int i) { return 32 * ((i >> 2) & 1) + 2 * (4 * (i >> 3) + (i & 3)); }
+__device__ __forceinline__ int s4_token_of_lane(int lane)
+{
+    const int v = (lane >> 1) & 15;
+    return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+}
+
+// Passages are scored 32 tokens per step with v_mfma_f32_32x32x16_f16: rows = the 32 query tokens (A operand), columns
+// = 32 passage tokens (B operand); lane 32 h + r holds row / column r of its operand, dimensions 16 s + 8 h .. + 7 at
+// step s of the 128 dimensions.  A lane therefore decodes the residual of one passage token, gets the results of that
+// token's column (16 query tokens: 8 g + 4 h + 0..3), and adds the centroid's share from its own token's row of S_cq
+// (four 16-byte loads, no exchange between lanes).  It keeps 16 running maxima over the steps of a passage; the maxima
+// over the columns are taken once per passage (s4_column_maxima).
 // COOP = false: one wave scores one passage at a time and the waves of the grid stride over the query's list (many
 // passages per wave: throughput).  COOP = true: the four waves of a workgroup share a passage, each taking every
 // fourth step, and combine their maxima in LDS (short lists: latency).
+// The grid is one-dimensional; with eight queries or more (spread = 0) workgroup L serves query 8 (L / 8 / gx) + L % 8:
+// consecutive workgroups go to the chip's eight partitions in turn, so a query's workgroups share one partition's
+// second-level cache and the rows of S_cq its passages have in common are fetched once.
 template <int NBITS, bool COOP>
-__global__ __launch_bounds__(256, 3) void decompress_maxsim_kernel(
+__global__ __launch_bounds__(256, 2) void decompress_maxsim_kernel(
     const float *__restrict__ Q, const float *__restrict__ S, int64_t C, const int64_t *__restrict__ doc_offsets,
     const int32_t *__restrict__ codes, const uint8_t *__restrict__ residuals, const float *__restrict__ weights,
-    const uint64_t *__restrict__ in_keys, int64_t in_stride, const int32_t *__restrict__ in_counts,
-    uint64_t *__restrict__ out_keys, int64_t out_stride)
+    const uint64_t *__restrict__ in_keys, int64_t in_stride, const int32_t *__restrict__ in_counts, int nq, int gx,
+    int spread, uint64_t *__restrict__ out_keys, int64_t out_stride)
 {
     constexpr int RB = 16 * NBITS;
     __shared__ s4_half8 hlut[256 * (NBITS == 2 ? 1 : 2)];
     __shared__ float wmax[4][QLEN];
-    const int q = blockIdx.y;
+    int q, bx;
+    if (spread) {
+        q = blockIdx.x / gx;
+        bx = blockIdx.x % gx;
+    } else {
+        const int k = blockIdx.x >> 3;
+        q = 8 * (k / gx) + (blockIdx.x & 7);
+        bx = k % gx;
+    }
+    if (q >= nq) return;
     const int count = in_counts[q];
-    if ((int)blockIdx.x * (COOP ? 1 : 4) >= count) return;  // uniform for the workgroup
+    if (bx * (COOP ? 1 : 4) >= count) return;  // uniform for the workgroup
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r32 = lane & 31, h = lane >> 5;
     build_half_tables<NBITS>(hlut, weights, threadIdx.x, 256);
     const float *Qq = Q + (int64_t)q * QLEN * DIM;
-    const float *Sq = S + (int64_t)q * C * QLEN;
-    // B operands: the two fp16 terms of query token r32, dimensions 16 s + 8 h .. + 7
+    const char *Sq = reinterpret_cast<const char *>(S + (int64_t)q * C * QLEN);
+    // A operands: the two fp16 terms of query token r32, dimensions 16 s + 8 h .. + 7
     s4_half8 q1[8], q2[8];
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
@@ -128,48 +178,83 @@ __global__ __launch_bounds__(256, 3) void decompress_maxsim_kernel(
     }
     __syncthreads();
 
-    for (int j = COOP ? (int)blockIdx.x : (int)blockIdx.x * 4 + wave; j < count; j += (int)gridDim.x * (COOP ? 1 : 4)) {
-        // passage id, first token and length are the same in every lane: kept in scalar registers, so that the loops
-        // below run with the whole wave active
-        const uint32_t pid = (uint32_t)__builtin_amdgcn_readfirstlane((int)(in_keys[(int64_t)q * in_stride + j] & 0xFFFFFFFFu));
-        const int64_t t0v = doc_offsets[pid];
-        const int64_t t0 = ((int64_t)__builtin_amdgcn_readfirstlane((int)(t0v >> 32)) << 32) |
-                           (uint32_t)__builtin_amdgcn_readfirstlane((int)(t0v & 0xFFFFFFFFll));
-        const int len = __builtin_amdgcn_readfirstlane((int)(doc_offsets[pid + 1] - t0v));
-        float m = -INFINITY;  // running maximum for query token r32 over the rows this lane sees
-        // The loop is software-pipelined: the code and packed residual of the next step and the S_cq values of this
-        // step are requested before this step's matrix instructions are issued, so their latency runs under them.
-        constexpr int STEP = COOP ? 128 : 32;
-        int base = COOP ? 32 * wave : 0;
-        int32_t code = 0;
-        uint32_t rw[RB / 4] = {0};
-        auto request = [&](int b, int32_t &c, uint32_t (&r)[RB / 4]) {
-            const int row = b + r32;  // this lane's passage token
-            const int64_t tok = t0 + (row < len ? row : len - 1);
-            c = codes[tok];
-            // the token's packed residual: both halves of the wave read all of it, each uses half of the bytes
-            const uint4 *rp = reinterpret_cast<const uint4 *>(residuals + tok * RB);
-            const uint4 v0 = rp[0];
-            r[0] = v0.x, r[1] = v0.y, r[2] = v0.z, r[3] = v0.w;
-            if (NBITS == 2) {
-                const uint4 v1 = rp[1];
-                r[4] = v1.x, r[5] = v1.y, r[6] = v1.z, r[7] = v1.w;
-            }
-        };
-        if (base < len) request(base, code, rw);
-        for (; base < len; base += STEP) {
-            // the centroid's share of each dot product: row code of S_cq, element r32 (requested now, used after the
-            // matrix instructions); acc[v] will hold passage token base + 8 (v/4) + 4h + v%4 against query token r32
-            float sv[16];
+    // In front of a passage's first step stands a chain of dependent loads: its id (from the key list), its token range,
+    // its first codes and residuals.  The chain is started three passages ahead and advanced one link per passage, and the
+    // first step's operands of the next passage are requested during the last step of this one, so that a wave never
+    // waits for the whole chain.  Ids and ranges are the same in every lane; they are still fetched with vector loads
+    // (a zero the compiler cannot see through is added to the index), which return in order and are counted apart from
+    // LDS reads.  List positions past the end repeat the last passage (loaded, not scored).
+    int vz;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(vz));
+    const uint32_t *ik = reinterpret_cast<const uint32_t *>(in_keys + (int64_t)q * in_stride);  // low word: passage id
+    const int j0 = COOP ? bx : bx * 4 + wave, jstride = gx * (COOP ? 1 : 4);
+    auto load_id = [&](int n) -> uint32_t {
+        const int64_t jj = (int64_t)j0 + (int64_t)n * jstride;
+        return ik[2 * (jj < count ? jj : (int64_t)count - 1) + vz];
+    };
+    auto uniform64 = [](int64_t v) -> int64_t {
+        return ((int64_t)__builtin_amdgcn_readfirstlane((int)(v >> 32)) << 32) |
+               (uint32_t)__builtin_amdgcn_readfirstlane((int)(v & 0xFFFFFFFFll));
+    };
+    constexpr int RW = RB / 4;
+    auto request = [&](int64_t t0, int len, int b, int32_t &c, uint32_t (&r)[RW]) {
+        const int row = b + r32;  // this lane's passage token
+        const int64_t tok = t0 + (row < len ? row : len - 1);
+        c = codes[tok];
+        // the token's packed residual: both halves of the wave read all of it, each uses half of the bytes
+        const uint4 *rp = reinterpret_cast<const uint4 *>(residuals + tok * RB);
+        const uint4 v0 = rp[0];
+        r[0] = v0.x, r[1] = v0.y, r[2] = v0.z, r[3] = v0.w;
+        if (NBITS == 2) {
+            const uint4 v1 = rp[1];
+            r[4] = v1.x, r[5] = v1.y, r[6] = v1.z, r[7] = v1.w;
+        }
+    };
+    constexpr int STEP = COOP ? 128 : 32;
+    const int base0 = COOP ? 32 * wave : 0;
+    // warm-up: passage 0 completely, passage 1 up to its token range, passage 2's id
+    uint32_t pid = (uint32_t)__builtin_amdgcn_readfirstlane((int)load_id(0));
+    int64_t t0 = uniform64(doc_offsets[(int64_t)pid + vz]);
+    int len = (int)(uniform64(doc_offsets[(int64_t)pid + 1 + vz]) - t0);
+    int32_t code = 0;
+    uint32_t rw[RW] = {0};
+    if (base0 < len) request(t0, len, base0, code, rw);
+    uint32_t pid1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)load_id(1));
+    int64_t o1a = doc_offsets[(int64_t)pid1 + vz], o1b = doc_offsets[(int64_t)pid1 + 1 + vz];  // as loaded (same in every lane)
+    uint32_t id2 = load_id(2);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the loop's waits then cover only what the loop itself requests
+
+    for (int n = 0; (int64_t)j0 + (int64_t)n * jstride < count; ++n) {
+        const int j = j0 + n * jstride;
+        // one link further for the passages ahead
+        const int64_t t0_next = uniform64(o1a);
+        const int len_next = (int)(uniform64(o1b) - t0_next);
+        const uint32_t pid2 = (uint32_t)__builtin_amdgcn_readfirstlane((int)id2);
+        const int64_t o2a = doc_offsets[(int64_t)pid2 + vz], o2b = doc_offsets[(int64_t)pid2 + 1 + vz];
+        const uint32_t id3 = load_id(n + 3);
+        int32_t code_next = 0;
+        uint32_t rw_next[RW] = {0};
+        bool next_requested = false;
+        float mx[16];  // running maxima of this lane's column class: query token 8 (v / 4) + 4 h + v % 4
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int rr = 8 * (v >> 2) + 4 * h + (v & 3);
-                const uint32_t cv = (uint32_t)__shfl(code, rr);
-                sv[v] = Sq[cv * (uint32_t)QLEN + (uint32_t)r32];
+        for (int v = 0; v < 16; ++v) mx[v] = -INFINITY;
+        // The step loop is software-pipelined too: the code and packed residual of the next step and the S_cq values of
+        // this step are requested before this step's matrix instructions are issued.
+        for (int base = base0; base < len; base += STEP) {
+            // the centroid's share of each dot product: the token's row of S_cq, elements 8 g + 4 h .. + 3 (requested now,
+            // used after the matrix instructions)
+            float4 sv[4];
+            {
+                const uint32_t off = (uint32_t)code * (uint32_t)(QLEN * 4) + 16u * (uint32_t)h;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) sv[g] = *reinterpret_cast<const float4 *>(Sq + off + 32u * g);
             }
-            int32_t code_next = 0;
-            uint32_t rw_next[RB / 4] = {0};
-            if (base + STEP < len) request(base + STEP, code_next, rw_next);  // uniform
+            if (base + STEP < len) {  // uniform
+                request(t0, len, base + STEP, code_next, rw_next);
+            } else {  // last step: the first step of the next passage
+                if (base0 < len_next) request(t0_next, len_next, base0, code_next, rw_next);
+                next_requested = true;
+            }
             floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
             floatx16 acx = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};  // cross terms, scaled by 2^11
 #pragma unroll
@@ -186,32 +271,47 @@ __global__ __launch_bounds__(256, 3) void decompress_maxsim_kernel(
                     a1 = hlut[b];
                     a2 = hlut[256 + b];
                 }
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, q1[s], acc, 0, 0, 0);
-                acx = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, q2[s], acx, 0, 0, 0);
-                acx = __builtin_amdgcn_mfma_f32_32x32x16_f16(a2, q1[s], acx, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(q1[s], a1, acc, 0, 0, 0);
+                acx = __builtin_amdgcn_mfma_f32_32x32x16_f16(q2[s], a1, acx, 0, 0, 0);
+                acx = __builtin_amdgcn_mfma_f32_32x32x16_f16(q1[s], a2, acx, 0, 0, 0);
             }
-            if (base + 32 <= len) {  // (uniform) a full step: every row counts
+            const float svf[16] = {sv[0].x, sv[0].y, sv[0].z, sv[0].w, sv[1].x, sv[1].y, sv[1].z, sv[1].w,
+                                   sv[2].x, sv[2].y, sv[2].z, sv[2].w, sv[3].x, sv[3].y, sv[3].z, sv[3].w};
+            // (med3(a, b, +inf) = max(a, b) for ordered operands, without the canonicalising copies of fmaxf)
+            if (base + 32 <= len) {  // (uniform) a full step: every column counts
 #pragma unroll
-                for (int v = 0; v < 16; ++v) m = fmaxf(m, fmaf(acx[v], 1.0f / S4_SCALE, acc[v]) + sv[v]);
-            } else {
+                for (int v = 0; v < 16; ++v) mx[v] = __builtin_amdgcn_fmed3f(mx[v], fmaf(acx[v], 1.0f / S4_SCALE, acc[v]) + svf[v], INFINITY);
+            } else if (base + r32 < len) {  // this lane's column is a token of the passage
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    if (base + 8 * (v >> 2) + 4 * h + (v & 3) < len) m = fmaxf(m, fmaf(acx[v], 1.0f / S4_SCALE, acc[v]) + sv[v]);
+                for (int v = 0; v < 16; ++v) mx[v] = __builtin_amdgcn_fmed3f(mx[v], fmaf(acx[v], 1.0f / S4_SCALE, acc[v]) + svf[v], INFINITY);
             }
             code = code_next;
 #pragma unroll
-            for (int e = 0; e < RB / 4; ++e) rw[e] = rw_next[e];
+            for (int e = 0; e < RW; ++e) rw[e] = rw_next[e];
         }
-        m = fmaxf(m, __shfl_xor(m, 32));
+        if (!next_requested && base0 < len_next) request(t0_next, len_next, base0, code, rw);  // (uniform) no step was taken
+        const float cm = s4_column_maxima(mx, lane);  // query token s4_token_of_lane(lane), in even and odd lane alike
+        float total;
         if (COOP) {  // j, len are the same in the four waves
-            if (h == 0) wmax[wave][r32] = m;
+            if (!(lane & 1)) wmax[wave][s4_token_of_lane(lane)] = cm;
             __syncthreads();
-            m = fmaxf(fmaxf(wmax[0][r32], wmax[1][r32]), fmaxf(wmax[2][r32], wmax[3][r32]));
+            const float m = fmaxf(fmaxf(wmax[0][r32], wmax[1][r32]), fmaxf(wmax[2][r32], wmax[3][r32]));
             __syncthreads();
+            total = plaid_sum32_in_order(m);
+        } else {
+            // the sum over the query tokens of Eq. 1, in double, in index order
+            double d = 0.0;
+#pragma unroll
+            for (int i = 0; i < QLEN; ++i)
+                d += (double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(cm), s4_lane_of_token(i)));
+            total = (float)d;
         }
-        const float total = plaid_sum32_in_order(m);
         if (lane == 0 && (!COOP || wave == 0))
             out_keys[(int64_t)q * out_stride + j] = plaid_make_key(len > 0 ? total : -INFINITY, pid);
+        // the passages ahead move up
+        pid = pid1, t0 = t0_next, len = len_next;
+        pid1 = pid2, o1a = o2a, o1b = o2b;
+        id2 = id3;
     }
 }
 
@@ -368,9 +468,14 @@ void plaid_launch_decompress_maxsim(hipStream_t st, const float *Q, const float 
     // (256 compute units x 3 resident workgroups: one full round of waves, each striding over several passages)
     const int cap = coop ? 2048 : (S4_RESIDENT_BLOCKS + nq - 1) / nq;
     if (gx > cap) gx = cap;
+    const int spread = nq < 8 ? 1 : 0;
+    const int64_t slots = spread ? nq : 8 * (((int64_t)nq + 7) / 8);  // query slots of the one-dimensional grid
+    if (slots * gx > (1ll << 23)) gx = (int)((1ll << 23) / slots);  // (the waves stride over longer lists)
+    if (gx < 1) gx = 1;
 #define PLAID_S4_LAUNCH(NB, CO)                                                                                           \
-    hipLaunchKernelGGL((decompress_maxsim_kernel<NB, CO>), dim3(gx, nq), dim3(256), 0, st, Q, S, C, doc_offsets, codes,       \
-                       residuals, bucket_weights, in_keys, in_stride, in_counts, out_keys, out_stride)
+    hipLaunchKernelGGL((decompress_maxsim_kernel<NB, CO>), dim3((unsigned)(slots * gx)), dim3(256), 0, st, Q, S, C,          \
+                       doc_offsets, codes, residuals, bucket_weights, in_keys, in_stride, in_counts, nq, gx, spread,          \
+                       out_keys, out_stride)
     if (nbits == 2) {
         if (coop) PLAID_S4_LAUNCH(2, true);
         else PLAID_S4_LAUNCH(2, false);

@@ -21,15 +21,15 @@ KERNELS = {
     "stage1_tail_kernelILi2ELb1E": ("k_scq.hip", 128, 64 << 10),   # ... also with the re-evaluations in double
     "stage1_tail_kernelILi8ELb1E": ("k_scq.hip", 128, 64 << 10),
     "scq16_kernel": ("k_scq16.hip", 256, 40 << 10),                # two waves per SIMD, two to four workgroups per CU
-    "s2_invert_kernelILi11EjE": ("k_stage2.hip", 128, 53 << 10),   # 2048 passages per workgroup, three workgroups per CU
-    "s2_invert_kernelILi11EyE": ("k_stage2.hip", 128, 53 << 10),
+    "s2_invert_kernelILi11EjE": ("k_stage2.hip", 168, 53 << 10),   # 2048 passages per workgroup, three workgroups (of four waves) per CU
+    "s2_invert_kernelILi11EyE": ("k_stage2.hip", 168, 53 << 10),
     "s2_invert_kernelILi13EjE": ("k_stage2.hip", 128, 80 << 10),   # 8192 passages, 1024 threads, 32-bit sets: two per CU
     "s2_invert_kernelILi13EyE": ("k_stage2.hip", 128, 100 << 10),  # ... 64-bit sets: one per CU
     "s2_union_wide_kernel": ("k_stage2.hip", 128, 80 << 10),       # two workgroups of 1024 threads per CU
     "s2_stream_kernel": ("k_stage2.hip", 128, 40 << 10),
     "ci_list_kernelILb0E": ("k_ci.hip", 96, 8 << 10),              # five waves per SIMD; wave-private LDS areas
-    "decompress_maxsim_kernelILi2ELb0E": ("k_stage4.hip", 168, 16 << 10),   # three waves per SIMD
-    "decompress_maxsim_kernelILi1ELb0E": ("k_stage4.hip", 168, 16 << 10),
+    "decompress_maxsim_kernelILi2ELb0E": ("k_stage4.hip", 192, 16 << 10),   # two waves per SIMD
+    "decompress_maxsim_kernelILi1ELb0E": ("k_stage4.hip", 192, 16 << 10),
     "sel_sort_kernelILi512E": ("k_select.hip", 64, 0),             # dynamic LDS only
     "sel2_filter_kernel": ("k_select.hip", 64, 8 << 10),
     "encode_residuals_kernelILi2E": ("k_build.hip", 64, 0),

@@ -98,6 +98,9 @@ struct Stage1Out {          // per-query outputs of the tail (device pointers, l
     int32_t *kept_ids;      // [nq][S2_MAX_KEPT]
     float *T;               // [nq][S2_MAX_KEPT + 1][32]
     const int64_t *ivf_offsets;  // [C + 1] inverted-list offsets: slots are numbered by list length (null: by id)
+    int32_t *qcount;        // [3] / [3][qlist_stride]: the queries by number of surviving centroids (none, 1..31, more),
+    int32_t *qlist;         //   appended as their workgroups finish (null: not recorded).  Stage 2 runs one kernel per
+    int qlist_stride;       //   class and takes its queries from these lists.
 };
 
 // One entry of S_cq as the definition reads: the products of the 128 dimensions accumulated in double in index order
@@ -139,7 +142,8 @@ __device__ __forceinline__ void stage1_survivor_table(const float *__restrict__ 
                                       int32_t *ids /*[S2_MAX_KEPT + 1]*/, uint32_t *trial /*[S2_NHASH][S2_HASH / 32]*/,
                                       float *colmm /*[2][32]*/, int32_t *misc /*[2]*/, const float *__restrict__ Cm = nullptr,
                                       const float *Qq = nullptr /* the query's rows, in LDS */,
-                                      const int64_t *__restrict__ ivf_offsets = nullptr)
+                                      const int64_t *__restrict__ ivf_offsets = nullptr, int q = 0,
+                                      int32_t *qcount = nullptr, int32_t *qlist = nullptr, int qlist_stride = 0)
 {
     auto keep_word = [&](int64_t w) -> uint32_t {
         if (APPROX) return __hip_atomic_load(kb + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -268,6 +272,11 @@ __device__ __forceinline__ void stage1_survivor_table(const float *__restrict__ 
         m.bin_scale = (K > 0 && range > 0.f && range < INFINITY) ? (float)SEL_BINS / range : 0.f;
         m.hash_shift = hash_shift;
         *meta_q = m;
+        if (qlist) {
+            const int cls = K == 0 ? 0 : (K <= 31 ? 1 : 2);
+            const int at = atomicAdd(&qcount[cls], 1);
+            if (at < qlist_stride) qlist[(int64_t)cls * qlist_stride + at] = q;  // (always, when the counts start at zero)
+        }
     }
 }
 
@@ -287,7 +296,7 @@ __global__ __launch_bounds__(512) void stage1_survivor_kernel(const float *__res
     __syncthreads();
     stage1_survivor_table<false>(S + (int64_t)q * C * QLEN, C, keepbits + (int64_t)q * keep_words, keep_words, top1, o.meta + q,
                                  o.kept_ids + (int64_t)q * S2_MAX_KEPT, o.T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN, scan, ids,
-                                 trial, colmm, misc, nullptr, nullptr, o.ivf_offsets);
+                                 trial, colmm, misc, nullptr, nullptr, o.ivf_offsets, q, o.qcount, o.qlist, o.qlist_stride);
 }
 
 // tilemax: [q][tile][32] column maxima of each tile (null: scores and pruning bits only).
@@ -962,7 +971,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
     stage1_survivor_table<APPROX>(S + (int64_t)q * C * QLEN, C, keepbits + (int64_t)q * keep_words, keep_words, top1,
                                   o.meta + q, o.kept_ids + (int64_t)q * S2_MAX_KEPT,
                                   o.T + (int64_t)q * (S2_MAX_KEPT + 1) * QLEN, scan, ids, trial, colmm, misc, x.Cm, Qq,
-                                  o.ivf_offsets);
+                                  o.ivf_offsets, q, o.qcount, o.qlist, o.qlist_stride);
 }
 
 // np = capacity of the tail's lists (1, 2, 4 or 8 >= nprobe); np = 0: scores and pruning bits only (large nprobe).
@@ -1047,6 +1056,9 @@ void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int
     o.kept_ids = s2.kept_ids;
     o.T = s2.T;
     o.ivf_offsets = s2.ivf_offsets;
+    o.qcount = s2.qcount;
+    o.qlist = s2.qlist;
+    o.qlist_stride = s2.qlist_stride;
     const int np = nprobe == 1 ? 1 : (nprobe == 2 ? 2 : (nprobe <= 4 ? 4 : (nprobe <= PLAID_PROBE_FAST_MAX ? 8 : 0)));
     if (np > 0)
         launch_fused(st, phases, np, centroids, C, Q, Qd, form, A16, nq, t_cs, S, keepbits, ambbits, keep_words, tilemax, nprobe,

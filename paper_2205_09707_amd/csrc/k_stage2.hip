@@ -779,7 +779,7 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
     const int32_t *__restrict__ codes, const int64_t *__restrict__ doc_offsets, int64_t P, const S2Meta *__restrict__ meta,
     const int32_t *__restrict__ kept_ids, const float *__restrict__ T, uint32_t *__restrict__ candbits, int64_t cand_words,
     uint64_t *__restrict__ keys2, int64_t key_stride, int32_t *__restrict__ hist, uint32_t *__restrict__ emptybits,
-    int skip_k0)
+    int skip_k0, const int32_t *__restrict__ qcount, const int32_t *__restrict__ qlist, int qlist_stride)
 {
     constexpr int RANGE = 1 << SHIFT, THREADS = IVR_THREADS(SHIFT);
     __shared__ SetT lsets[RANGE];
@@ -790,14 +790,25 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
     __shared__ int32_t lhist[SEL_BINS];
     __shared__ IvrLists lists;
     __shared__ uint32_t slot_probed[2];  // bit s: surviving slot s is also a probed centroid
-    const int q = blockIdx.y;
     const int64_t r = blockIdx.x;
     const uint32_t r0 = (uint32_t)(r << SHIFT);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = s2_uniform(tid >> 6);
+    // This instance's queries: those with 1..31 (32-bit sets) or more (64-bit sets) surviving centroids, and with the
+    // 32-bit instance those without any unless s2_union_wide_kernel has produced their candidate and empty-bag words.
+    // Row y of the grid takes entries y, y + gridDim.y, ... of the lists the probe kernel made.
+    const int cls = sizeof(SetT) == 4 ? 1 : 2;
+    const int n_mine = qcount[cls], n_none = (cls == 1 && !skip_k0) ? qcount[0] : 0;
+    // Only the 2048-passage instance with 64-bit sets loops: its class is usually empty or nearly so, and a launch of
+    // nq rows of workgroups that all find nothing to do costs tens of microseconds.  The other instances are launched
+    // with one row per query and take one entry (a class that holds most of the chunk's queries runs faster that way).
+    constexpr bool LOOP = SHIFT == 11 && sizeof(SetT) == 8;
+    int qi = blockIdx.y;
+    if (qi >= n_mine + n_none) return;  // uniform
+    do {
+    const int q = qi < n_mine ? qlist[(int64_t)cls * qlist_stride + qi] : qlist[qi - n_mine];
     const int K = s2_uniform(meta[q].K);
-    if (K == 0 && skip_k0) return;  // uniform: s2_union_wide_kernel has produced this query's candidate and empty-bag words
-    if ((K <= 31) != (sizeof(SetT) == 4)) return;  // uniform: the other instance's query
+    if ((K <= 31) != (sizeof(SetT) == 4)) continue;  // (never: the lists are made from the same K)
     const bool slots = K > 0 && K <= S2_MAX_KEPT;  // bags are kept as slot sets
     const int hsh = s2_uniform(meta[q].hash_shift);
     for (int e = tid; e < RANGE; e += THREADS) lsets[e] = (SetT)0;
@@ -884,6 +895,8 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
                        doc_offsets, codes, bin_hi, bin_scale, keys_out, lhist, emptybits);
     }
     if (K > 0) s2_flush_hist(lhist, hist + (int64_t)q * SEL_BINS);
+    if (LOOP) __syncthreads();  // the LDS arrays are set up again for the next query
+    } while (LOOP && (qi += (int)gridDim.y) < n_mine + n_none);
 }
 
 void plaid_launch_stage2_inverted(hipStream_t st, const int32_t *uniq, const int32_t *n_uniq, int uniq_stride,
@@ -903,10 +916,13 @@ void plaid_launch_stage2_inverted(hipStream_t st, const int32_t *uniq, const int
         hipLaunchKernelGGL(s2_union_wide_kernel, dim3((unsigned)nwide, nq), dim3(UW_THREADS), 0, st, uniq, n_uniq, uniq_stride,
                            ivf_offsets, ivf_pids, table, nr, shift, P, b.meta, dense_id, dense_bits, candbits, cand_words,
                            b.emptybits);
+    // the looping instance (2048 passages, 64-bit sets): 128 rows of workgroups share its queries
 #define S2_INVERT(SH_, T_)                                                                                                  \
-    hipLaunchKernelGGL((s2_invert_kernel<SH_, T_>), dim3((unsigned)nr, nq), dim3(IVR_THREADS(SH_)), 0, st, uniq, n_uniq,       \
+    hipLaunchKernelGGL((s2_invert_kernel<SH_, T_>), dim3((unsigned)nr, (SH_ == 11 && sizeof(T_) == 8 && nq > 128) ? 128 : nq), \
+                       dim3(IVR_THREADS(SH_)), 0, st, uniq, n_uniq,                                                          \
                        uniq_stride, ivf_offsets, ivf_pids, table, nr, S, C, keepbits, keep_words, codes, doc_offsets, P,     \
-                       b.meta, b.kept_ids, b.T, candbits, cand_words, keys2, key_stride, b.hist, b.emptybits, wide)
+                       b.meta, b.kept_ids, b.T, candbits, cand_words, keys2, key_stride, b.hist, b.emptybits, wide,         \
+                       b.qcount, b.qlist, b.qlist_stride)
     if (shift == 11) {
         S2_INVERT(11, uint32_t);
         S2_INVERT(11, unsigned long long);

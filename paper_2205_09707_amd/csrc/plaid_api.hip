@@ -593,6 +593,7 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     w.s2.hist = (int32_t *)take((size_t)qc * SEL_BINS * 4);
     w.s2.hist1 = (int32_t *)take((size_t)qc * SEL_BINS * 4);
     w.s2.state = (Sel2State *)take((size_t)qc * sizeof(Sel2State));
+    w.s2.qcount = (int32_t *)take(4 * sizeof(int32_t));
     w.sel3_zero = take(plaid_select_zero_bytes(qc));
     w.sel4_zero = take(plaid_select_zero_bytes(qc));
     w.zero_bytes = off;
@@ -612,6 +613,8 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     w.s2.kept_ids = (int32_t *)take((size_t)qc * S2_MAX_KEPT * 4);
     w.s2.T = (float *)take((size_t)qc * (S2_MAX_KEPT + 1) * QLEN * 4);
     w.s2.emptybits = (uint32_t *)take((size_t)qc * w.cand_words * 4);
+    w.s2.qlist = (int32_t *)take((size_t)3 * qc * 4);
+    w.s2.qlist_stride = qc;
     w.s2.ivf_offsets = ix->ivf_offsets;
     w.sel2 = (uint64_t *)take((size_t)qc * pl.nd * 8);
     w.n2 = (int32_t *)take((size_t)qc * 4);

@@ -187,7 +187,10 @@ struct Stage2Buffers {   // all device pointers, leading dimension = query of th
     int32_t *hist;       // [nq][SEL_BINS]  bin histogram of the valid keys
     int32_t *hist1;      // [nq][SEL_BINS]  digit histogram of an over-long boundary list
     Sel2State *state;    // [nq]
+    int32_t *qcount;     // [3] queries of the chunk with no / 1..31 / more surviving centroids (null: not recorded)
     // no initialisation needed
+    int32_t *qlist;      // [3][qlist_stride] those queries, in the order their probe workgroups finished
+    int qlist_stride;
     S2Meta *meta;        // [nq]
     int32_t *kept_ids;   // [nq][S2_MAX_KEPT]
     float *T;            // [nq][S2_MAX_KEPT+1][32] rows of the surviving centroids (slot 0 unused)

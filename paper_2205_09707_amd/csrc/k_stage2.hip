@@ -768,6 +768,20 @@ __global__ __launch_bounds__(UW_THREADS) void s2_union_wide_kernel(
     }
 }
 
+// Counting sort of a round's bags by size (LDS).
+#define S2_ORDER_ROUND 2048  // passages per round
+struct S2Order {
+    int32_t count[64];                // bags of each size (2..63 members)
+    int32_t start[64];                // running positions, largest size first
+    int32_t total;
+    uint16_t list[S2_ORDER_ROUND];    // round-local passages in that order
+};
+// The list-application arrays and the sort are never live together.
+union S2InvertScratch {
+    IvrLists lists;
+    S2Order order;
+};
+
 // SetT: the per-passage set word.  Queries with at most 31 surviving centroids fit 32-bit words (bit 0 = candidate,
 // bits 1..31 = slots), which halves the kernel's largest LDS array and lets two of the 1024-thread workgroups share a
 // compute unit; the 64-bit instance serves the other queries.  Both are launched; each leaves the other's queries alone.
@@ -788,7 +802,7 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
     __shared__ __align__(16) float Tl[(S2_MAX_KEPT + 1) * S2_TSTRIDE];
     __shared__ float rowsum[S2_MAX_KEPT + 1];
     __shared__ int32_t lhist[SEL_BINS];
-    __shared__ IvrLists lists;
+    __shared__ S2InvertScratch scratch;
     __shared__ uint32_t slot_probed[2];  // bit s: surviving slot s is also a probed centroid
     const int64_t r = blockIdx.x;
     const uint32_t r0 = (uint32_t)(r << SHIFT);
@@ -833,7 +847,7 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
             first = ivf_offsets[c] + a;
             cnt = b > a ? (int)(b - a) : 0;
         }
-        ivr_apply_round(cnt, first, val, ivf_pids, r0, (uint32_t)RANGE, lsets, lists);
+        ivr_apply_round(cnt, first, val, ivf_pids, r0, (uint32_t)RANGE, lsets, scratch.lists);
     }
     // surviving centroids that were not probed: slot bit only
     if (slots) {
@@ -849,7 +863,7 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
                 cnt = b > a ? (int)(b - a) : 0;
             }
         }
-        ivr_apply_round(cnt, first, 1ull << ((tid & 63) + 1), ivf_pids, r0, (uint32_t)RANGE, lsets, lists);
+        ivr_apply_round(cnt, first, 1ull << ((tid & 63) + 1), ivf_pids, r0, (uint32_t)RANGE, lsets, scratch.lists);
     }
 
     const int64_t w_first = (int64_t)r0 >> 5;  // first bitmap word of the range
@@ -858,27 +872,73 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
     uint64_t *keys_out = keys2 + (int64_t)q * key_stride;
     uint32_t *cbq = candbits + (int64_t)q * cand_words;
     uint32_t *ebq = emptybits + (int64_t)q * cand_words;
-    for (int g = wave; g < RANGE / 64; g += THREADS / 64) {
-        const unsigned long long v = (unsigned long long)lsets[64 * g + lane];
-        const int64_t pid = (int64_t)r0 + 64 * g + lane;
-        const bool cand = (v & 1ull) && pid < P;
-        const unsigned long long members = v & ~1ull;
-        const unsigned long long cm = __ballot(cand);
-        bool empty = true;
+    // Pass 1, lane = passage in passage order: candidate and empty-bag words, the keys of empty bags and of bags with one
+    // member (a table look-up), and how many bags there are of each larger size.
+    // Pass 2, lane = bag with two members or more, in the order of their sizes (a counting sort of the passages of a
+    // round in LDS): the lanes of a wave then run about the same number of steps over their members, where in passage
+    // order each wave would run as long as its largest bag takes.
+    S2Order &ord = scratch.order;
+    for (int b0 = 0; b0 < RANGE; b0 += S2_ORDER_ROUND) {  // (the last list application ended with a barrier)
         if (slots) {
-            empty = members == 0;
-            if (cand) {
-                const float score = empty ? -INFINITY : s2_score_members_wide(members, Tl, rowsum);
-                keys_out[pid] = empty ? PLAID_KEY_MAX : plaid_make_key(score, (uint32_t)pid);
-                if (!empty) atomicAdd(&lhist[plaid_s2_bin(score, bin_hi, bin_scale)], 1);
+            for (int e = tid; e < 64; e += THREADS) ord.count[e] = 0;
+            __syncthreads();
+        }
+        for (int g = b0 / 64 + wave; g < (b0 + S2_ORDER_ROUND) / 64; g += THREADS / 64) {
+            const SetT vs = lsets[64 * g + lane];
+            const int64_t pid = (int64_t)r0 + 64 * g + lane;
+            const bool cand = (vs & (SetT)1) && pid < P;
+            const SetT members = vs & ~(SetT)1;
+            const unsigned long long cm = __ballot(cand);
+            bool empty = true;
+            if (slots) {
+                empty = members == 0;
+                const int size = sizeof(SetT) == 4 ? __popc((uint32_t)members) : __popcll((unsigned long long)members);
+                float score = -INFINITY;
+                if (cand && size == 1) score = rowsum[__ffsll((long long)(unsigned long long)members) - 1];
+                if (cand && size <= 1) keys_out[pid] = empty ? PLAID_KEY_MAX : plaid_make_key(score, (uint32_t)pid);
+                if (cand && size > 1) atomicAdd(&ord.count[size], 1);
+                if (cand && size == 1) atomicAdd(&lhist[plaid_s2_bin(score, bin_hi, bin_scale)], 1);
+            }
+            const unsigned long long em = __ballot(cand && empty);
+            if (lane == 0) {
+                lcand[2 * g] = (uint32_t)cm;
+                lcand[2 * g + 1] = (uint32_t)(cm >> 32);
+                lempty[2 * g] = (uint32_t)em;
+                lempty[2 * g + 1] = (uint32_t)(em >> 32);
             }
         }
-        const unsigned long long em = __ballot(cand && empty);
-        if (lane == 0) {
-            lcand[2 * g] = (uint32_t)cm;
-            lcand[2 * g + 1] = (uint32_t)(cm >> 32);
-            lempty[2 * g] = (uint32_t)em;
-            lempty[2 * g + 1] = (uint32_t)(em >> 32);
+        if (slots) {  // uniform
+            __syncthreads();
+            if (tid < 64) {  // exclusive prefix over the sizes, largest first: the long bags start the pass
+                const int c = ord.count[63 - lane];
+                int incl = c;
+#pragma unroll
+                for (int d = 1; d < 64; d <<= 1) {
+                    const int t = __shfl_up(incl, d);
+                    if (lane >= d) incl += t;
+                }
+                ord.start[63 - lane] = incl - c;
+                if (lane == 63) ord.total = incl;
+            }
+            __syncthreads();
+            for (int p = b0 + tid; p < b0 + S2_ORDER_ROUND; p += THREADS) {
+                const SetT vs = lsets[p];
+                const SetT members = vs & ~(SetT)1;
+                if ((vs & (SetT)1) && (int64_t)r0 + p < P && (members & (members - 1)) != 0) {
+                    const int size = sizeof(SetT) == 4 ? __popc((uint32_t)members) : __popcll((unsigned long long)members);
+                    ord.list[atomicAdd(&ord.start[size], 1)] = (uint16_t)(p - b0);
+                }
+            }
+            __syncthreads();
+            const int total = ord.total;
+            for (int e = tid; e < total; e += THREADS) {
+                const int p = b0 + ord.list[e];
+                const unsigned long long members = (unsigned long long)(lsets[p] & ~(SetT)1);
+                const float score = s2_score_members_wide(members, Tl, rowsum);
+                keys_out[(int64_t)r0 + p] = plaid_make_key(score, (uint32_t)(r0 + p));
+                atomicAdd(&lhist[plaid_s2_bin(score, bin_hi, bin_scale)], 1);
+            }
+            if (b0 + S2_ORDER_ROUND < RANGE) __syncthreads();  // the arrays are set up again for the next round
         }
     }
     __syncthreads();

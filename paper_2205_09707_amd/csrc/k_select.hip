@@ -671,14 +671,14 @@ __global__ __launch_bounds__(SEL_THREADS) void sel2_filter_kernel(const uint64_t
     const int32_t n_keys = scan[SEL_THREADS - 1];
     if (blockIdx.x == 0 && threadIdx.x == 0) s->m_rem = (m < n_keys ? m : n_keys) - before;
     if (n_keys == 0) return;
-    const uint64_t *k = keys + (int64_t)seg * key_stride;
+    const uint32_t *k = reinterpret_cast<const uint32_t *>(keys + (int64_t)seg * key_stride);  // score word of passage i
     const uint32_t *cb = candbits + (int64_t)seg * cand_words;
     uint64_t *my_out = out + (int64_t)seg * out_stride;
     uint64_t *my_bl = blist + (int64_t)seg * blist_stride;
     const int lane = threadIdx.x & 63;
     // A wave takes SEL2_GROUPS x 64 consecutive slots per step and reserves its output positions with one pair of
     // counter updates per step (the updates return a value, so their round trip is the step's latency).
-    constexpr int SEL2_GROUPS = 4;
+    constexpr int SEL2_GROUPS = 8;
     const int64_t wave_id = (int64_t)blockIdx.x * (SEL_THREADS / 64) + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int64_t n_waves = (int64_t)gridDim.x * (SEL_THREADS / 64);
     unsigned long long o = 0, no = 0;
@@ -687,12 +687,21 @@ __global__ __launch_bounds__(SEL_THREADS) void sel2_filter_kernel(const uint64_t
         int cls[SEL2_GROUPS];  // 0 = surely selected, 1 = boundary, 2 = dropped
         unsigned long long b0[SEL2_GROUPS], b1[SEL2_GROUPS];
         int n0 = 0, n1 = 0;
+        // word i is meaningful only when passage i is a candidate; it then holds its score word or "no score".  The
+        // candidate bits and the score words are requested together (a word that means nothing is read and dropped): one
+        // round trip to memory per step.
+        uint32_t cw[SEL2_GROUPS], sw[SEL2_GROUPS];
 #pragma unroll
         for (int u = 0; u < SEL2_GROUPS; ++u) {
-            // slot i is meaningful only when passage i is a candidate; it then holds its key or the invalid key
+            const int64_t i = i0 + 64 * u + lane;
+            cw[u] = i < P ? cb[i >> 5] : 0u;
+            sw[u] = i < P ? k[i] : PLAID_S2_NO_SCORE;
+        }
+#pragma unroll
+        for (int u = 0; u < SEL2_GROUPS; ++u) {
             const int64_t i = i0 + 64 * u + lane;
             key[u] = PLAID_KEY_MAX;
-            if (i < P && ((cb[i >> 5] >> (i & 31)) & 1u)) key[u] = k[i];
+            if (((cw[u] >> (i & 31)) & 1u) && sw[u] != PLAID_S2_NO_SCORE) key[u] = ((uint64_t)sw[u] << 32) | (uint32_t)i;
         }
 #pragma unroll
         for (int u = 0; u < SEL2_GROUPS; ++u) {

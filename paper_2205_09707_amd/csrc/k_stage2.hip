@@ -78,7 +78,7 @@ __device__ __forceinline__ void s2_gather_body(int q, const float *__restrict__ 
                                                int64_t cb_first, int64_t w_first, int64_t w_step, int64_t w_end,
                                                int64_t cand_words, int64_t P, const int64_t *__restrict__ doc_offsets,
                                                const int32_t *__restrict__ codes, float bin_hi, float bin_scale,
-                                               uint64_t *__restrict__ keys_out, int32_t *lhist,
+                                               uint32_t *__restrict__ keys_out, int32_t *lhist,
                                                uint32_t *__restrict__ emptybits)
 {
     const int lane = threadIdx.x & 63;
@@ -110,7 +110,7 @@ __device__ __forceinline__ void s2_gather_body(int q, const float *__restrict__ 
         }
         const bool cand = lane < 32 && ((word >> lane) & 1u);
         const bool live = cand && !my_empty;
-        if (cand) keys_out[p0 + lane] = live ? plaid_make_key(my, (uint32_t)(p0 + lane)) : PLAID_KEY_MAX;
+        if (cand) keys_out[p0 + lane] = live ? plaid_score_to_ord(my) : PLAID_S2_NO_SCORE;
         if (live) atomicAdd(&lhist[plaid_s2_bin(my, bin_hi, bin_scale)], 1);
         const unsigned long long e64 = __ballot(cand && my_empty);
         if (lane == 0) eb[w] = (uint32_t)e64;
@@ -262,7 +262,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
     const int q = blockIdx.y;
     const int K = s2_uniform(meta[q].K);
     const float bin_hi = meta[q].bin_hi, bin_scale = meta[q].bin_scale;
-    uint64_t *keys_out = keys2 + (int64_t)q * key_stride;
+    uint32_t *keys_out = reinterpret_cast<uint32_t *>(keys2 + (int64_t)q * key_stride);  // slot p: passage p's score word
     int32_t *hist_q = hist + (int64_t)q * SEL_BINS;
     const int tid = threadIdx.x, lane = tid & 63;
     if (K == 0) {
@@ -445,7 +445,7 @@ __global__ __launch_bounds__(S2_THREADS) void s2_stream_kernel(
         if (cand && !empty) score = s2_score_members(members, Tl, rowsum);
         // emit: slot p of the key array belongs to candidate p; no counters, no ordering between waves
         const bool live = cand && !empty;
-        if (cand) keys_out[p0 + lane] = live ? plaid_make_key(score, (uint32_t)(p0 + lane)) : PLAID_KEY_MAX;
+        if (cand) keys_out[p0 + lane] = live ? plaid_score_to_ord(score) : PLAID_S2_NO_SCORE;
         if (live) atomicAdd(&lhist[plaid_s2_bin(score, bin_hi, bin_scale)], 1);
         const unsigned long long eb64 = __ballot(cand && empty);
         if (lane == 0) {
@@ -869,7 +869,7 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
     const int64_t w_first = (int64_t)r0 >> 5;  // first bitmap word of the range
     // emit the range: lane = passage, 64 passages per step
     const float bin_hi = meta[q].bin_hi, bin_scale = meta[q].bin_scale;
-    uint64_t *keys_out = keys2 + (int64_t)q * key_stride;
+    uint32_t *keys_out = reinterpret_cast<uint32_t *>(keys2 + (int64_t)q * key_stride);  // slot p: passage p's score word
     uint32_t *cbq = candbits + (int64_t)q * cand_words;
     uint32_t *ebq = emptybits + (int64_t)q * cand_words;
     // Pass 1, lane = passage in passage order: candidate and empty-bag words, the keys of empty bags and of bags with one
@@ -895,7 +895,7 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
                 const int size = sizeof(SetT) == 4 ? __popc((uint32_t)members) : __popcll((unsigned long long)members);
                 float score = -INFINITY;
                 if (cand && size == 1) score = rowsum[__ffsll((long long)(unsigned long long)members) - 1];
-                if (cand && size <= 1) keys_out[pid] = empty ? PLAID_KEY_MAX : plaid_make_key(score, (uint32_t)pid);
+                if (cand && size <= 1) keys_out[pid] = empty ? PLAID_S2_NO_SCORE : plaid_score_to_ord(score);
                 if (cand && size > 1) atomicAdd(&ord.count[size], 1);
                 if (cand && size == 1) atomicAdd(&lhist[plaid_s2_bin(score, bin_hi, bin_scale)], 1);
             }
@@ -935,7 +935,7 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
                 const int p = b0 + ord.list[e];
                 const unsigned long long members = (unsigned long long)(lsets[p] & ~(SetT)1);
                 const float score = s2_score_members_wide(members, Tl, rowsum);
-                keys_out[(int64_t)r0 + p] = plaid_make_key(score, (uint32_t)(r0 + p));
+                keys_out[(int64_t)r0 + p] = plaid_score_to_ord(score);
                 atomicAdd(&lhist[plaid_s2_bin(score, bin_hi, bin_scale)], 1);
             }
             if (b0 + S2_ORDER_ROUND < RANGE) __syncthreads();  // the arrays are set up again for the next round

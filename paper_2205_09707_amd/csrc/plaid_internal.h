@@ -200,9 +200,11 @@ struct Stage2Buffers {   // all device pointers, leading dimension = query of th
     const int64_t *ivf_offsets;  // [C + 1]: the probe kernel numbers the surviving centroids by list length
 };
 
-// Eq. 3-5 over every candidate: keys2[q][p] = key of candidate p (invalid key when its bag is empty; slots of
-// 32-passage groups without candidates are left untouched), the bin histogram of the valid keys, and the bitmap
-// of empty candidates.
+// Eq. 3-5 over every candidate.  The passage id of a stage-2 key is its position, so only the score half is stored:
+// the 32-bit word p of query q's region of keys2 (region = key_stride 64-bit words) is the score word of candidate p
+// (plaid_score_to_ord), PLAID_S2_NO_SCORE when its bag is empty; words of 32-passage groups without candidates are left
+// untouched.  Also produced: the bin histogram of the scores and the bitmap of the candidates with an empty bag.
+#define PLAID_S2_NO_SCORE 0xFFFFFFFFu  // (the score word of one NaN bit pattern: scores are numbers)
 void plaid_launch_stage2(hipStream_t st, const float *S, int64_t C, const uint32_t *keepbits, int64_t keep_words,
                          const int32_t *probed, int nprobe, const uint32_t *candbits, int64_t cand_words, int64_t P,
                          int64_t N, const int64_t *doc_offsets, const int32_t *codes, int nq, const Stage2Buffers &b,

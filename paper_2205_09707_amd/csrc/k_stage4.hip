@@ -24,7 +24,7 @@
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef _Float16 s4_half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 s4_half4 __attribute__((ext_vector_type(4)));
-#define S4_RESIDENT_BLOCKS 768
+#define S4_RESIDENT_BLOCKS 1024
 #define S4_SCALE 2048.0f  // 2^11
 
 // The two fp16 terms of x: x1 = fp16(x) (0 below fp16's normal range), x2 = fp16(2^11 (x - x1)).
@@ -134,7 +134,7 @@ __device__ __forceinline__ int s4_token_of_lane(int lane)
 // consecutive workgroups go to the chip's eight partitions in turn, so a query's workgroups share one partition's
 // second-level cache and the rows of S_cq its passages have in common are fetched once.
 template <int NBITS, bool COOP>
-__global__ __launch_bounds__(256, 2) void decompress_maxsim_kernel(
+__global__ __launch_bounds__(256, 4) void decompress_maxsim_kernel(
     const float *__restrict__ Q, const float *__restrict__ S, int64_t C, const int64_t *__restrict__ doc_offsets,
     const int32_t *__restrict__ codes, const uint8_t *__restrict__ residuals, const float *__restrict__ weights,
     const uint64_t *__restrict__ in_keys, int64_t in_stride, const int32_t *__restrict__ in_counts, int nq, int gx,
@@ -143,6 +143,7 @@ __global__ __launch_bounds__(256, 2) void decompress_maxsim_kernel(
     constexpr int RB = 16 * NBITS;
     __shared__ s4_half8 hlut[256 * (NBITS == 2 ? 1 : 2)];
     __shared__ float wmax[4][QLEN];
+    __shared__ s4_half8 qs[2][8][64];  // [term][step of 16 dimensions][lane]
     int q, bx;
     if (spread) {
         q = blockIdx.x / gx;
@@ -161,20 +162,24 @@ __global__ __launch_bounds__(256, 2) void decompress_maxsim_kernel(
     build_half_tables<NBITS>(hlut, weights, threadIdx.x, 256);
     const float *Qq = Q + (int64_t)q * QLEN * DIM;
     const char *Sq = reinterpret_cast<const char *>(S + (int64_t)q * C * QLEN);
-    // A operands: the two fp16 terms of query token r32, dimensions 16 s + 8 h .. + 7
-    s4_half8 q1[8], q2[8];
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-        const float4 *p = reinterpret_cast<const float4 *>(Qq + r32 * DIM + 16 * s + 8 * h);
+    // A operands: the two fp16 terms of query token r32, dimensions 16 s + 8 h .. + 7.  They are the same for the four
+    // waves and stay in LDS (16 KB), from where each matrix step reads them: 64 registers less per lane, which buys a
+    // third wave per SIMD to cover the latency of the gathers.
+    for (int e = threadIdx.x; e < 8 * 64; e += 256) {
+        const int s = e >> 6, l = e & 63;
+        const float4 *p = reinterpret_cast<const float4 *>(Qq + (l & 31) * DIM + 16 * s + 8 * (l >> 5));
         const float4 u = p[0], w = p[1];
         const float x[8] = {u.x, u.y, u.z, u.w, w.x, w.y, w.z, w.w};
+        s4_half8 t1, t2;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             _Float16 x1, x2;
             s4_split(x[j], x1, x2);
-            q1[s][j] = x1;
-            q2[s][j] = x2;
+            t1[j] = x1;
+            t2[j] = x2;
         }
+        qs[0][s][l] = t1;
+        qs[1][s][l] = t2;
     }
     __syncthreads();
 
@@ -257,6 +262,10 @@ __global__ __launch_bounds__(256, 2) void decompress_maxsim_kernel(
             }
             floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
             floatx16 acx = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};  // cross terms, scaled by 2^11
+            // (the query operands are read anew in every step, through an index the compiler cannot tell from the last
+            // step's: kept across steps they would take the 64 registers again)
+            int ql = lane;
+            asm volatile("" : "+v"(ql));
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
                 // dimensions 16 s + 8 h .. + 7: bytes 4 s + 2 h and 4 s + 2 h + 1 of a 2-bit code, byte 2 s + h of a 1-bit one
@@ -271,9 +280,10 @@ __global__ __launch_bounds__(256, 2) void decompress_maxsim_kernel(
                     a1 = hlut[b];
                     a2 = hlut[256 + b];
                 }
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(q1[s], a1, acc, 0, 0, 0);
-                acx = __builtin_amdgcn_mfma_f32_32x32x16_f16(q2[s], a1, acx, 0, 0, 0);
-                acx = __builtin_amdgcn_mfma_f32_32x32x16_f16(q1[s], a2, acx, 0, 0, 0);
+                const s4_half8 q1 = qs[0][s][ql], q2 = qs[1][s][ql];
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(q1, a1, acc, 0, 0, 0);
+                acx = __builtin_amdgcn_mfma_f32_32x32x16_f16(q2, a1, acx, 0, 0, 0);
+                acx = __builtin_amdgcn_mfma_f32_32x32x16_f16(q1, a2, acx, 0, 0, 0);
             }
             const float svf[16] = {sv[0].x, sv[0].y, sv[0].z, sv[0].w, sv[1].x, sv[1].y, sv[1].z, sv[1].w,
                                    sv[2].x, sv[2].y, sv[2].z, sv[2].w, sv[3].x, sv[3].y, sv[3].z, sv[3].w};
@@ -465,7 +475,7 @@ void plaid_launch_decompress_maxsim(hipStream_t st, const float *Q, const float 
     // several passages each, so that the per-workgroup set-up (table, query operands) is paid rarely
     const bool coop = (int64_t)n_upper * nq <= 2048;
     int gx = coop ? n_upper : (n_upper + 3) / 4;
-    // (256 compute units x 3 resident workgroups: one full round of waves, each striding over several passages)
+    // (256 compute units x 4 resident workgroups: one full round of waves, each striding over several passages)
     const int cap = coop ? 2048 : (S4_RESIDENT_BLOCKS + nq - 1) / nq;
     if (gx > cap) gx = cap;
     const int spread = nq < 8 ? 1 : 0;

@@ -105,7 +105,8 @@ def algorithmic_work(pl, idx, w_dev, Q, params, cfg):
             c = b["cand"][j, :n].long()
             if survivors[j] > 0:
                 s2 += 8 * n + 4 * int(lens[c].sum())
-                inv += 8 * n if survivors[j] <= 63 else 8 * n + 4 * int(lens[c].sum())
+                # (inverted form: one 4-byte score word per candidate; more than 63 survivors: the candidates' codes too)
+                inv += 4 * n if survivors[j] <= 63 else 4 * n + 4 * int(lens[c].sum())
             else:
                 s2 += 8 * ((cfg.P + 31) // 32)
                 n_skipped += 1
@@ -247,9 +248,10 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
             work["stage4_bytes"], 1e9, HBM_PEAK_GBS, "GB/s",
             {"algorithmic_bytes_per_step": work["stage4_bytes"], "algorithmic_bytes_per_launch": work["stage4_bytes"] // launches,
              "tokens_per_step": work["stage4_tokens"],
-             "fp32_mfma_tflops": round(work["stage4_tokens"] * 8192 / (stage_ms["stage4_maxsim"] * 1e-3) / 1e12, 2),
-             "fp32_mfma_frac": round(work["stage4_tokens"] * 8192 / (stage_ms["stage4_maxsim"] * 1e-3) / 1e12
-                                     / FP32_MFMA_PEAK_TFLOPS, 4)})
+             # three fp16 matrix products per fp32 product (two-term operand splits): 3 x 2 x 32 x 128 flop per token
+             "fp16_mfma_tflops": round(3 * work["stage4_tokens"] * 8192 / (stage_ms["stage4_maxsim"] * 1e-3) / 1e12, 2),
+             "fp16_mfma_frac": round(3 * work["stage4_tokens"] * 8192 / (stage_ms["stage4_maxsim"] * 1e-3) / 1e12
+                                     / FP16_MFMA_PEAK_TFLOPS, 4)})
         dominant = max(rooflines, key=lambda s: stage_ms[s])
         roofline = dict(rooflines[dominant])
         roofline["stage"] = dominant

@@ -196,8 +196,9 @@ int plaid_get_score_kernel(const plaid_index *idx, int32_t *form);
  * and every pruned bag follow from the lists of the probed and the surviving centroids), 0 for the union of the probed
  * lists followed by a stream over the candidates' token codes.  Same results either way.  The inverted form needs a
  * table of num_centroids x (num_passages / R + 1) 32-bit positions, R = 2048 passages per workgroup (form 1) or 8192
- * (form 2), built at index creation with the smaller R whose table is at most 32 MiB or at most the size of the inverted
- * lists; PLAID_STAGE2_FORM=stream|inverted|inverted11|inverted13 (read at index creation) overrides. */
+ * (form 2), built at index creation with the smaller R whose table is at most 32 MiB or at most four times the size of
+ * the inverted lists (device memory of the library's own, beside the index);
+ * PLAID_STAGE2_FORM=stream|inverted|inverted11|inverted13 (read at index creation) overrides. */
 int plaid_get_stage2_kernel(const plaid_index *idx, int32_t *form);
 
 /* Per-stage GPU time of the most recent plaid_search on this index when stage timing is on

@@ -158,9 +158,10 @@ static int build_scq16_operands(plaid_index *ix)
 }
 
 // The inverted form of candidate generation + stage 2 needs a table of C x (P / 2^shift + 1) positions, shift = 11 or
-// 13 (2048 or 8192 passages per workgroup).  It is built at the finer granularity whose table is small next to the
-// inverted lists themselves (or tiny in absolute terms); PLAID_STAGE2_FORM=stream|inverted|inverted11|inverted13 (read
-// at index creation) overrides that.
+// 13 (2048 or 8192 passages per workgroup).  The finer one is faster at every index size measured (three or four
+// workgroups share a compute unit instead of one or two); it is built when its table is at most four times the size of
+// the inverted lists (or tiny in absolute terms), the coarser one under the same rule or when the finer table cannot
+// be allocated.  PLAID_STAGE2_FORM=stream|inverted|inverted11|inverted13 (read at index creation) overrides that.
 static int build_range_table(plaid_index *ix)
 {
     const char *env = getenv("PLAID_STAGE2_FORM");
@@ -169,7 +170,7 @@ static int build_range_table(plaid_index *ix)
     const size_t list_bytes = (size_t)ix->ivf_len * 4;
     auto fits = [&](int shift) {
         const size_t b = plaid_ivf_range_table_bytes(ix->C, ix->P, shift);
-        return b <= (size_t)32 << 20 || b <= list_bytes;
+        return b <= (size_t)32 << 20 || b <= 4 * list_bytes;
     };
     int shift = fits(11) ? 11 : (fits(13) ? 13 : 0);
     if (env && !strcmp(env, "stream")) shift = 0;
@@ -177,17 +178,22 @@ static int build_range_table(plaid_index *ix)
     if (env && !strcmp(env, "inverted11")) shift = 11;
     if (env && !strcmp(env, "inverted13")) shift = 13;
     if (!shift || ix->P == 0) return PLAID_OK;
-    if (env && !strcmp(env, "inverted")) env = nullptr;  // an allocation failure falls back to the streaming form
-    const bool forced = env != nullptr;
-    const size_t bytes = plaid_ivf_range_table_bytes(ix->C, ix->P, shift);
-    ix->ivr_shift = shift;
+    const bool forced = env != nullptr && strcmp(env, "inverted") != 0;  // else an allocation failure falls back
     void *d = nullptr;
+    size_t bytes = plaid_ivf_range_table_bytes(ix->C, ix->P, shift);
     hipError_t e = hipMalloc(&d, bytes ? bytes : 4);
+    if (e != hipSuccess && !forced && shift == 11) {  // the coarser table is a quarter of the size
+        (void)hipGetLastError();
+        shift = 13;
+        bytes = plaid_ivf_range_table_bytes(ix->C, ix->P, shift);
+        e = hipMalloc(&d, bytes ? bytes : 4);
+    }
     if (e != hipSuccess) {
         (void)hipGetLastError();
         if (forced) return fail(PLAID_ENOMEM, "hipMalloc(%zu) for the inverted-list range table failed", bytes);
         return PLAID_OK;  // not essential: the streaming form is used
     }
+    ix->ivr_shift = shift;
     ix->owned.push_back(d);
     plaid_launch_ivf_range_table(nullptr, ix->ivf_offsets, ix->ivf_pids, ix->C, ix->P, shift, (uint32_t *)d);
     HIP_TRY(hipGetLastError());

@@ -185,6 +185,39 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
         log(f"[bench] batch-1 latency over {nlat} queries (best of 3 trials): p50 {np.percentile(lat, 50):.4f} ms, "
             f"p99 {np.percentile(lat, 99):.4f} ms, mean {lat.mean():.4f} ms; host enqueue p50 {np.percentile(enq, 50):.4f} ms")
 
+    # ---- the same, replaying a HIP graph of the search (plaid_search_static records into a graph because it allocates
+    # nothing): the host enqueues one graph instead of a dozen kernels.  A reference figure: never fails the benchmark.
+    lat_graph = None
+    if nlat and not args.no_graph_latency:
+        try:
+            k_out = out_ids.shape[1]
+            Qb = Q[0:1].clone()
+            gi = torch.empty((1, k_out), dtype=torch.int32, device=Q.device)
+            gs = torch.empty((1, k_out), dtype=torch.float32, device=Q.device)
+            pl.plaid_search_static(idx, Qb, *params, gi, gs)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                pl.plaid_search_static(idx, Qb, *params, gi, gs)
+            torch.cuda.synchronize()
+            lg = np.empty(nlat)
+            same = True
+            for q in range(nlat):
+                Qb.copy_(Q[q:q + 1])
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                graph.replay()
+                torch.cuda.synchronize()
+                lg[q] = (time.perf_counter() - t1) * 1e3
+                same = same and bool(torch.equal(gi[0], out_ids[q]))
+            lat_graph = {"p50": round(float(np.percentile(lg, 50)), 4), "p99": round(float(np.percentile(lg, 99)), 4),
+                         "mean": round(float(lg.mean()), 4), "queries": int(nlat), "ids_equal_to_eager_search": same}
+            log(f"[bench] batch-1 latency, graph replay: p50 {lat_graph['p50']:.4f} ms, p99 {lat_graph['p99']:.4f} ms; "
+                f"ids equal to the eager search: {same}")
+            del graph
+        except Exception as e:
+            log(f"[bench] graph-replay latency not measured: {e}")
+
     # ---- rooflines of the three large kernels; the one with the largest share of the step is the headline
     roofline = None
     rooflines = {}
@@ -257,7 +290,8 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
         roofline["stage"] = dominant
 
     return {"w": w, "idx": idx, "Q": Q, "nq": nq, "params": params, "out_ids": out_ids, "qps": qps, "ms_per_step": ms_per_step,
-            "stage_ms": stage_ms, "lat": lat, "enq": enq, "nlat": nlat, "roofline": roofline, "rooflines": rooflines}
+            "stage_ms": stage_ms, "lat": lat, "enq": enq, "nlat": nlat, "lat_graph": lat_graph, "roofline": roofline,
+            "rooflines": rooflines}
 
 
 def memory_shortfall(torch, cfg):
@@ -426,6 +460,7 @@ def main():
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--single-noise", action="store_true", help="skip the run on the other reading of the noise scale")
     ap.add_argument("--no-index-build", action="store_true", help="skip the timing of the index-construction calls")
+    ap.add_argument("--no-graph-latency", action="store_true", help="skip the HIP-graph replay of the batch-1 search")
     ap.add_argument("--no-ablation", action="store_true", help="skip the vanilla-retrieval ablation ladder (Section 5.3)")
     ap.add_argument("--no-operating-points", action="store_true",
                     help="skip the k = 10 (cfg2), k = 1000 (cfg4) and 1-bit (cfg5) operating points reported beside the headline")
@@ -460,7 +495,7 @@ def main():
     r = measure(pl, torch, np, cfg, args.noise, args)
     w, idx, Q, nq, params, out_ids = r["w"], r["idx"], r["Q"], r["nq"], r["params"], r["out_ids"]
     qps, ms_per_step, stage_ms, lat, enq, nlat = r["qps"], r["ms_per_step"], r["stage_ms"], r["lat"], r["enq"], r["nlat"]
-    roofline, rooflines = r["roofline"], r["rooflines"]
+    roofline, rooflines, lat_graph = r["roofline"], r["rooflines"], r["lat_graph"]
 
     # ---- CPU oracle on a bounded sample of the same queries (rank 0, N = 1)
     cpu = None
@@ -531,7 +566,8 @@ def main():
                     "stage2_kernel": "inverted" if pl.plaid_get_stage2_kernel(r3["idx"]) else "stream",
                     "stage_ms_per_step": {s_: round(v, 4) for s_, v in r3["stage_ms"].items()},
                     "latency_batch1_ms": {"p50": round(float(np.percentile(l3, 50)), 4), "p99": round(float(np.percentile(l3, 99)), 4),
-                                          "mean": round(float(l3.mean()), 4), "queries": int(r3["nlat"]), "trials": 3}}
+                                          "mean": round(float(l3.mean()), 4), "queries": int(r3["nlat"]), "trials": 3,
+                                          "graph_replay": r3["lat_graph"]}}
                 pl.plaid_index_free(r3["idx"])
                 del r3
                 torch.cuda.empty_cache()
@@ -556,7 +592,7 @@ def main():
                                   "S_cq and the centroid-interaction sums accumulate in f64 (stored f32); MaxSim in f32")},
         "latency_batch1_ms": {"p50": round(float(np.percentile(lat, 50)), 4), "p99": round(float(np.percentile(lat, 99)), 4),
                               "mean": round(float(lat.mean()), 4), "queries": int(nlat), "trials": 3, "host_enqueue_p50": round(float(np.percentile(enq, 50)), 4),
-                              "qps": round(1e3 / float(lat.mean()), 1) if nlat else None},
+                              "qps": round(1e3 / float(lat.mean()), 1) if nlat else None, "graph_replay": lat_graph},
         "stage_ms_per_step": {s: round(v, 4) for s, v in stage_ms.items()},
         "roofline": roofline, "roofline_by_stage": rooflines or None, "cpu_baseline": cpu,
         "other_noise_reading": other, "operating_points": points, "ablation": ablation, "index_construction": build,

@@ -32,7 +32,7 @@ class _Index(ct.Structure):
     _fields_ = [("dim", ct.c_int32), ("nbits", ct.c_int32), ("C", ct.c_int64), ("P", ct.c_int64), ("N", ct.c_int64),
                 ("centroids", ct.c_void_p), ("doc_offsets", ct.c_void_p), ("codes", ct.c_void_p),
                 ("residuals", ct.c_void_p), ("bucket_weights", ct.c_void_p), ("ivf_offsets", ct.c_void_p),
-                ("ivf_pids", ct.c_void_p)]
+                ("ivf_pids", ct.c_void_p), ("renormalize", ct.c_int32)]
 
 
 class _Dumps(ct.Structure):
@@ -73,7 +73,10 @@ def _chk(a: np.ndarray, dtype) -> np.ndarray:
 class Index:
     """Borrowed view of host index buffers (keeps the numpy arrays alive)."""
 
-    def __init__(self, arrays: Dict[str, np.ndarray], nbits: int):
+    def __init__(self, arrays: Dict[str, np.ndarray], nbits: int, renormalize: bool = False):
+        """renormalize: the storage variant in which reconstructed vectors are scaled back to unit length
+        (orc_decompress); off by default."""
+        self.renormalize = bool(renormalize)
         self.centroids = _chk(arrays["centroids"], np.float32)
         self.doc_offsets = _chk(arrays["doc_offsets"], np.int64)
         self.codes = _chk(arrays["codes"], np.int32)
@@ -89,12 +92,21 @@ class Index:
         assert self.residuals.size == self.N * self.dim * nbits // 8
         self.c = _Index(self.dim, nbits, self.C, self.P, self.N, self.centroids.ctypes.data,
                         self.doc_offsets.ctypes.data, self.codes.ctypes.data, self.residuals.ctypes.data,
-                        self.bucket_weights.ctypes.data, self.ivf_offsets.ctypes.data, self.ivf_pids.ctypes.data)
+                        self.bucket_weights.ctypes.data, self.ivf_offsets.ctypes.data, self.ivf_pids.ctypes.data,
+                        1 if self.renormalize else 0)
+
+    def _arrays(self) -> Dict[str, np.ndarray]:
+        return dict(centroids=self.centroids, doc_offsets=self.doc_offsets, codes=self.codes, residuals=self.residuals,
+                    bucket_weights=self.bucket_weights, ivf_offsets=self.ivf_offsets, ivf_pids=self.ivf_pids)
 
     def with_weights(self, weights: np.ndarray) -> "Index":
-        d = dict(centroids=self.centroids, doc_offsets=self.doc_offsets, codes=self.codes, residuals=self.residuals,
-                 bucket_weights=np.asarray(weights, np.float32), ivf_offsets=self.ivf_offsets, ivf_pids=self.ivf_pids)
-        return Index(d, self.nbits)
+        d = self._arrays()
+        d["bucket_weights"] = np.asarray(weights, np.float32)
+        return Index(d, self.nbits, self.renormalize)
+
+    def renormalized(self, on: bool = True) -> "Index":
+        """The same arrays under the other reading of the reconstruction's length."""
+        return Index(self._arrays(), self.nbits, on)
 
 
 # ---- stage functions -----------------------------------------------------------------------

@@ -47,6 +47,8 @@ typedef struct {
     const float *bucket_weights; /* [2^nbits] */
     const int64_t *ivf_offsets;  /* [C+1] */
     const int32_t *ivf_pids;     /* ascending unique pids per centroid */
+    int32_t renormalize;         /* 0: reconstructed vectors as they come (the reading used by default);
+                                    1: scaled to unit length, see orc_decompress */
 } orc_index;
 
 /* ------------------------------------------------------------------ Eq. 2: S_cq = C . Q^T */
@@ -187,7 +189,13 @@ void orc_build_byte_table(int32_t nbits, uint8_t *table /* [256][8/nbits] */)
 }
 
 /* Decompress tokens [t0, t1): D[j][x] = fl32(centroid[code_j][x] + weight[index(j, x)]), the bucket index
- * read through the byte table.  idx_out (optional) receives the unpacked bucket indices. */
+ * read through the byte table.  idx_out (optional) receives the unpacked bucket indices.
+ *
+ * Section 4.5 says the reconstruction recovers the stored embedding and is silent on its length; the embeddings that
+ * were stored had unit length (Section 3.1 scores by cosine similarity), the reconstruction does not.  The storage
+ * variant ix->renormalize = 1 takes the other reading: the reconstructed vector is scaled back to unit length,
+ *     n2 = sum_x D[j][x]^2 (double, index order),  inv = fl32(1 / sqrt(n2))  (0 when n2 = 0),  D[j][x] <- fl32(D[j][x] * inv),
+ * and every score built on reconstructed vectors (Eq. 1, the vanilla pruning scores) uses the scaled ones. */
 void orc_decompress(const orc_index *ix, int64_t t0, int64_t t1, float *D /* [(t1-t0)][dim] */, uint8_t *idx_out)
 {
     int32_t per = 8 / ix->nbits, dim = ix->dim, rb = dim * ix->nbits / 8;
@@ -203,6 +211,13 @@ void orc_decompress(const orc_index *ix, int64_t t0, int64_t t1, float *D /* [(t
                 D[(j - t0) * dim + x] = cen[x] + ix->bucket_weights[b];
                 if (idx_out) idx_out[(j - t0) * dim + x] = b;
             }
+        if (ix->renormalize) {
+            float *v = D + (j - t0) * dim;
+            double n2 = 0.0;
+            for (int32_t x = 0; x < dim; ++x) n2 += (double)v[x] * (double)v[x];
+            float inv = n2 > 0.0 ? (float)(1.0 / sqrt(n2)) : 0.0f;
+            for (int32_t x = 0; x < dim; ++x) v[x] = v[x] * inv;
+        }
     }
 }
 

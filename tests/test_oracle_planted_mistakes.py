@@ -61,6 +61,11 @@ MISTAKES = [
     ("vanilla_misses_the_last_embedding_of_a_list", "for (int64_t e = eoff[c]; e < eoff[c + 1]; ++e) {",
      "for (int64_t e = eoff[c]; e < eoff[c + 1] - 1; ++e) {", 1),
     ("vanilla_embedding_lists_unsorted", "eids[fill[codes[j]]++] = j;", "eids[fill[codes[j]]++] = N - 1 - j;", 1),
+    # reconstructed vectors scaled to unit length (storage variant)
+    ("renormalize_divides_by_the_squared_norm", "(float)(1.0 / sqrt(n2))", "(float)(1.0 / n2)", 1),
+    ("renormalize_skips_the_last_dimension", "for (int32_t x = 0; x < dim; ++x) n2 +=", "for (int32_t x = 0; x < dim - 1; ++x) n2 +=", 1),
+    ("renormalize_scales_by_the_norm", "v[x] = v[x] * inv;", "v[x] = v[x] / inv;", 1),
+    ("renormalize_ignores_the_flag", "if (ix->renormalize) {", "if (0) {", 1),
 ]
 
 
@@ -75,7 +80,7 @@ def _pins_fail(name, old, new, count, tmp):
     env = dict(os.environ, PLAID_ORACLE_LIB=so, OMP_NUM_THREADS="2")
     r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
                         os.path.join(HERE, "test_oracle_pins.py"), os.path.join(HERE, "test_oracle_hand_example.py"),
-                        os.path.join(HERE, "test_oracle_vanilla.py")],
+                        os.path.join(HERE, "test_oracle_vanilla.py"), os.path.join(HERE, "test_oracle_renormalize.py")],
                        cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=600)
     tail = "\n".join(r.stdout.strip().splitlines()[-3:])
     return name, r.returncode, tail

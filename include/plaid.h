@@ -211,6 +211,17 @@ int plaid_get_stage2_kernel(const plaid_index *idx, int32_t *form);
 int plaid_set_stage_timing(plaid_index *idx, int32_t on);
 int plaid_get_stage_ms(const plaid_index *idx, float *out_ms);
 
+/* Storage variant (Section 4.5 reconstructs the stored embedding and is silent on its length; the embeddings that were
+ * stored have unit length, Section 3.1, the reconstruction centroid + residual does not): on != 0 makes every later
+ * plaid_search / plaid_search_debug / plaid_search_static on this index score, and plaid_decompress_passages return,
+ * reconstructed vectors scaled back to unit length: each token's vector is multiplied by
+ * fl32(1 / sqrt(sum of the squares of its fp32 components, added in double in index order)) (0 for a zero vector).
+ * The first call with on != 0 computes that factor for every token (num_embeddings floats of device memory owned by the
+ * index; the call synchronises the device's default stream); on = 0 switches back.  Stages 1-3 use centroids only and
+ * do not change.  Not to be called while a search on this index is in flight.  plaid_search_vanilla returns
+ * PLAID_EINVAL while the variant is on.  Errors: PLAID_EINVAL (null index), PLAID_ENOMEM, PLAID_EHIP. */
+int plaid_index_set_renormalize(plaid_index *idx, int32_t on);
+
 /* Limit on queries processed per internal chunk (0 = library default).  Affects workspace size only. */
 int plaid_set_max_chunk(plaid_index *idx, int32_t max_queries_per_chunk);
 

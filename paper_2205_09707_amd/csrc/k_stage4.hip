@@ -133,10 +133,13 @@ __device__ __forceinline__ int s4_token_of_lane(int lane)
 // The grid is one-dimensional; with eight queries or more (spread = 0) workgroup L serves query 8 (L / 8 / gx) + L % 8:
 // consecutive workgroups go to the chip's eight partitions in turn, so a query's workgroups share one partition's
 // second-level cache and the rows of S_cq its passages have in common are fetched once.
-template <int NBITS, bool COOP>
+// RN: the storage variant in which a reconstructed vector is scaled to unit length: its dot products are multiplied by
+// the token's factor inv_norm[token] = 1 / |centroid + residual| (plaid_launch_token_inv_norm).
+template <int NBITS, bool COOP, bool RN>
 __global__ __launch_bounds__(256, 4) void decompress_maxsim_kernel(
     const float *__restrict__ Q, const float *__restrict__ S, int64_t C, const int64_t *__restrict__ doc_offsets,
     const int32_t *__restrict__ codes, const uint8_t *__restrict__ residuals, const float *__restrict__ weights,
+    const float *__restrict__ inv_norm,
     const uint64_t *__restrict__ in_keys, int64_t in_stride, const int32_t *__restrict__ in_counts, int nq, int gx,
     int spread, uint64_t *__restrict__ out_keys, int64_t out_stride)
 {
@@ -202,10 +205,11 @@ __global__ __launch_bounds__(256, 4) void decompress_maxsim_kernel(
                (uint32_t)__builtin_amdgcn_readfirstlane((int)(v & 0xFFFFFFFFll));
     };
     constexpr int RW = RB / 4;
-    auto request = [&](int64_t t0, int len, int b, int32_t &c, uint32_t (&r)[RW]) {
+    auto request = [&](int64_t t0, int len, int b, int32_t &c, float &nf, uint32_t (&r)[RW]) {
         const int row = b + r32;  // this lane's passage token
         const int64_t tok = t0 + (row < len ? row : len - 1);
         c = codes[tok];
+        if (RN) nf = inv_norm[tok];
         // the token's packed residual: both halves of the wave read all of it, each uses half of the bytes
         const uint4 *rp = reinterpret_cast<const uint4 *>(residuals + tok * RB);
         const uint4 v0 = rp[0];
@@ -222,8 +226,9 @@ __global__ __launch_bounds__(256, 4) void decompress_maxsim_kernel(
     int64_t t0 = uniform64(doc_offsets[(int64_t)pid + vz]);
     int len = (int)(uniform64(doc_offsets[(int64_t)pid + 1 + vz]) - t0);
     int32_t code = 0;
+    float nf = 1.0f;  // this lane's token's scaling factor (RN)
     uint32_t rw[RW] = {0};
-    if (base0 < len) request(t0, len, base0, code, rw);
+    if (base0 < len) request(t0, len, base0, code, nf, rw);
     uint32_t pid1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)load_id(1));
     int64_t o1a = doc_offsets[(int64_t)pid1 + vz], o1b = doc_offsets[(int64_t)pid1 + 1 + vz];  // as loaded (same in every lane)
     uint32_t id2 = load_id(2);
@@ -238,6 +243,7 @@ __global__ __launch_bounds__(256, 4) void decompress_maxsim_kernel(
         const int64_t o2a = doc_offsets[(int64_t)pid2 + vz], o2b = doc_offsets[(int64_t)pid2 + 1 + vz];
         const uint32_t id3 = load_id(n + 3);
         int32_t code_next = 0;
+        float nf_next = 1.0f;
         uint32_t rw_next[RW] = {0};
         bool next_requested = false;
         float mx[16];  // running maxima of this lane's column class: query token 8 (v / 4) + 4 h + v % 4
@@ -255,9 +261,9 @@ __global__ __launch_bounds__(256, 4) void decompress_maxsim_kernel(
                 for (int g = 0; g < 4; ++g) sv[g] = *reinterpret_cast<const float4 *>(Sq + off + 32u * g);
             }
             if (base + STEP < len) {  // uniform
-                request(t0, len, base + STEP, code_next, rw_next);
+                request(t0, len, base + STEP, code_next, nf_next, rw_next);
             } else {  // last step: the first step of the next passage
-                if (base0 < len_next) request(t0_next, len_next, base0, code_next, rw_next);
+                if (base0 < len_next) request(t0_next, len_next, base0, code_next, nf_next, rw_next);
                 next_requested = true;
             }
             floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -290,16 +296,25 @@ __global__ __launch_bounds__(256, 4) void decompress_maxsim_kernel(
             // (med3(a, b, +inf) = max(a, b) for ordered operands, without the canonicalising copies of fmaxf)
             if (base + 32 <= len) {  // (uniform) a full step: every column counts
 #pragma unroll
-                for (int v = 0; v < 16; ++v) mx[v] = __builtin_amdgcn_fmed3f(mx[v], fmaf(acx[v], 1.0f / S4_SCALE, acc[v]) + svf[v], INFINITY);
+                for (int v = 0; v < 16; ++v) {
+                    float x = fmaf(acx[v], 1.0f / S4_SCALE, acc[v]) + svf[v];
+                    if (RN) x *= nf;
+                    mx[v] = __builtin_amdgcn_fmed3f(mx[v], x, INFINITY);
+                }
             } else if (base + r32 < len) {  // this lane's column is a token of the passage
 #pragma unroll
-                for (int v = 0; v < 16; ++v) mx[v] = __builtin_amdgcn_fmed3f(mx[v], fmaf(acx[v], 1.0f / S4_SCALE, acc[v]) + svf[v], INFINITY);
+                for (int v = 0; v < 16; ++v) {
+                    float x = fmaf(acx[v], 1.0f / S4_SCALE, acc[v]) + svf[v];
+                    if (RN) x *= nf;
+                    mx[v] = __builtin_amdgcn_fmed3f(mx[v], x, INFINITY);
+                }
             }
             code = code_next;
+            nf = nf_next;
 #pragma unroll
             for (int e = 0; e < RW; ++e) rw[e] = rw_next[e];
         }
-        if (!next_requested && base0 < len_next) request(t0_next, len_next, base0, code, rw);  // (uniform) no step was taken
+        if (!next_requested && base0 < len_next) request(t0_next, len_next, base0, code, nf, rw);  // (uniform) no step was taken
         const float cm = s4_column_maxima(mx, lane);  // query token s4_token_of_lane(lane), in even and odd lane alike
         float total;
         if (COOP) {  // j, len are the same in the four waves
@@ -468,7 +483,8 @@ void plaid_launch_vanilla_prune(hipStream_t st, const float *Q, const float *S, 
 void plaid_launch_decompress_maxsim(hipStream_t st, const float *Q, const float *S, int64_t C, const int64_t *doc_offsets,
                                     const int32_t *codes, const uint8_t *residuals, const float *bucket_weights,
                                     int nbits, int nq, const uint64_t *in_keys, int64_t in_stride,
-                                    const int32_t *in_counts, int n_upper, uint64_t *out_keys, int64_t out_stride)
+                                    const int32_t *in_counts, int n_upper, uint64_t *out_keys, int64_t out_stride,
+                                    const float *inv_norm)
 {
     if (n_upper <= 0 || nq <= 0) return;
     // few passages in all (short lists of few queries): a workgroup per passage; otherwise waves stride over the lists,
@@ -482,17 +498,23 @@ void plaid_launch_decompress_maxsim(hipStream_t st, const float *Q, const float 
     const int64_t slots = spread ? nq : 8 * (((int64_t)nq + 7) / 8);  // query slots of the one-dimensional grid
     if (slots * gx > (1ll << 23)) gx = (int)((1ll << 23) / slots);  // (the waves stride over longer lists)
     if (gx < 1) gx = 1;
-#define PLAID_S4_LAUNCH(NB, CO)                                                                                           \
-    hipLaunchKernelGGL((decompress_maxsim_kernel<NB, CO>), dim3((unsigned)(slots * gx)), dim3(256), 0, st, Q, S, C,          \
-                       doc_offsets, codes, residuals, bucket_weights, in_keys, in_stride, in_counts, nq, gx, spread,          \
-                       out_keys, out_stride)
+#define PLAID_S4_LAUNCH(NB, CO, RN)                                                                                       \
+    hipLaunchKernelGGL((decompress_maxsim_kernel<NB, CO, RN>), dim3((unsigned)(slots * gx)), dim3(256), 0, st, Q, S, C,      \
+                       doc_offsets, codes, residuals, bucket_weights, inv_norm, in_keys, in_stride, in_counts, nq, gx,       \
+                       spread, out_keys, out_stride)
+#define PLAID_S4_LAUNCH_RN(NB, CO)                                                                                        \
+    do {                                                                                                                  \
+        if (inv_norm) PLAID_S4_LAUNCH(NB, CO, true);                                                                      \
+        else PLAID_S4_LAUNCH(NB, CO, false);                                                                              \
+    } while (0)
     if (nbits == 2) {
-        if (coop) PLAID_S4_LAUNCH(2, true);
-        else PLAID_S4_LAUNCH(2, false);
+        if (coop) PLAID_S4_LAUNCH_RN(2, true);
+        else PLAID_S4_LAUNCH_RN(2, false);
     } else {
-        if (coop) PLAID_S4_LAUNCH(1, true);
-        else PLAID_S4_LAUNCH(1, false);
+        if (coop) PLAID_S4_LAUNCH_RN(1, true);
+        else PLAID_S4_LAUNCH_RN(1, false);
     }
+#undef PLAID_S4_LAUNCH_RN
 #undef PLAID_S4_LAUNCH
 }
 
@@ -543,7 +565,8 @@ __global__ __launch_bounds__(256) void decompress_dump_kernel(const float *__res
                                                               const int32_t *__restrict__ pids,
                                                               const int64_t *__restrict__ out_offsets,
                                                               float *__restrict__ out_vectors,
-                                                              uint8_t *__restrict__ out_indices)
+                                                              uint8_t *__restrict__ out_indices,
+                                                              const float *__restrict__ inv_norm)
 {
     constexpr int RB = 16 * NBITS;
     __shared__ float4 wlut[256 * (NBITS == 2 ? 1 : 2)];
@@ -562,22 +585,71 @@ __global__ __launch_bounds__(256) void decompress_dump_kernel(const float *__res
         const int slot = table_slot<NBITS>(residuals + tok * RB, quad);
         const float4 c = *reinterpret_cast<const float4 *>(crow + 4 * quad);
         const float4 w = wlut[slot];
-        if (out_vectors)
-            *reinterpret_cast<float4 *>(out_vectors + (o0 + row) * DIM + 4 * quad) =
-                make_float4(c.x + w.x, c.y + w.y, c.z + w.z, c.w + w.w);
+        if (out_vectors) {
+            float4 d = make_float4(c.x + w.x, c.y + w.y, c.z + w.z, c.w + w.w);
+            if (inv_norm) {  // scaled to unit length: one fp32 factor per token, one rounding per component
+                const float f = inv_norm[tok];
+                d = make_float4(d.x * f, d.y * f, d.z * f, d.w * f);
+            }
+            *reinterpret_cast<float4 *>(out_vectors + (o0 + row) * DIM + 4 * quad) = d;
+        }
         if (out_indices) *reinterpret_cast<uint32_t *>(out_indices + (o0 + row) * DIM + 4 * quad) = ilut[slot];
     }
 }
 void plaid_launch_decompress_dump(hipStream_t st, const float *centroids, const int64_t *doc_offsets,
                                   const int32_t *codes, const uint8_t *residuals, const float *bucket_weights,
                                   int nbits, const int32_t *pids, int n, const int64_t *out_offsets, float *out_vectors,
-                                  uint8_t *out_indices)
+                                  uint8_t *out_indices, const float *inv_norm)
 {
     if (n <= 0) return;
     if (nbits == 2)
         hipLaunchKernelGGL(decompress_dump_kernel<2>, dim3(n), dim3(256), 0, st, centroids, doc_offsets, codes, residuals,
-                           bucket_weights, pids, out_offsets, out_vectors, out_indices);
+                           bucket_weights, pids, out_offsets, out_vectors, out_indices, inv_norm);
     else
         hipLaunchKernelGGL(decompress_dump_kernel<1>, dim3(n), dim3(256), 0, st, centroids, doc_offsets, codes, residuals,
-                           bucket_weights, pids, out_offsets, out_vectors, out_indices);
+                           bucket_weights, pids, out_offsets, out_vectors, out_indices, inv_norm);
+}
+
+// Storage variant "reconstructed vectors scaled to unit length" (the other reading of Section 4.5's reconstruction):
+// inv_norm[t] = fl32(1 / sqrt(sum_x fl32(centroid[code_t][x] + weight[index(t, x)])^2)), the squares (exact in double)
+// added in double in index order; 0 for a zero vector.  One thread per token; run once, when the variant is switched on.
+template <int NBITS>
+__global__ __launch_bounds__(256) void token_inv_norm_kernel(const float *__restrict__ centroids,
+                                                             const int32_t *__restrict__ codes,
+                                                             const uint8_t *__restrict__ residuals,
+                                                             const float *__restrict__ weights, int64_t N,
+                                                             float *__restrict__ inv_norm)
+{
+    constexpr int RB = 16 * NBITS;
+    __shared__ float4 wlut[256 * (NBITS == 2 ? 1 : 2)];
+    build_tables<NBITS>(wlut, nullptr, weights, threadIdx.x, 256);
+    __syncthreads();
+    for (int64_t tok = (int64_t)blockIdx.x * 256 + threadIdx.x; tok < N; tok += (int64_t)gridDim.x * 256) {
+        const float *crow = centroids + (int64_t)codes[tok] * DIM;
+        const uint8_t *r = residuals + tok * RB;
+        double n2 = 0.0;
+        for (int quad = 0; quad < DIM / 4; ++quad) {
+            const float4 c = *reinterpret_cast<const float4 *>(crow + 4 * quad);
+            const float4 w = wlut[table_slot<NBITS>(r, quad)];
+            const float d0 = c.x + w.x, d1 = c.y + w.y, d2 = c.z + w.z, d3 = c.w + w.w;
+            n2 = fma((double)d0, (double)d0, n2);
+            n2 = fma((double)d1, (double)d1, n2);
+            n2 = fma((double)d2, (double)d2, n2);
+            n2 = fma((double)d3, (double)d3, n2);
+        }
+        inv_norm[tok] = n2 > 0.0 ? (float)(1.0 / sqrt(n2)) : 0.0f;
+    }
+}
+void plaid_launch_token_inv_norm(hipStream_t st, const float *centroids, const int32_t *codes, const uint8_t *residuals,
+                                 const float *bucket_weights, int nbits, int64_t N, float *inv_norm)
+{
+    if (N <= 0) return;
+    int64_t g = (N + 255) / 256;
+    if (g > 65536) g = 65536;
+    if (nbits == 2)
+        hipLaunchKernelGGL(token_inv_norm_kernel<2>, dim3((unsigned)g), dim3(256), 0, st, centroids, codes, residuals,
+                           bucket_weights, N, inv_norm);
+    else
+        hipLaunchKernelGGL(token_inv_norm_kernel<1>, dim3((unsigned)g), dim3(256), 0, st, centroids, codes, residuals,
+                           bucket_weights, N, inv_norm);
 }

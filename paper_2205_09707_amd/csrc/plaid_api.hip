@@ -64,6 +64,8 @@ struct plaid_index {
     int32_t scq_matrix_form = 0;  // double-precision score kernel: 1 = matrix instruction, 0 = vector FMA chain
     int32_t scq_form = 0;         // score kernel of a search: PLAID_SCQ_VECTOR / _MATRIX / _SPLIT16
     void *A16 = nullptr;          // split-fp16 operand form of the centroids (owned), when scq_form is PLAID_SCQ_SPLIT16
+    float *inv_norm = nullptr;    // [N] 1 / |reconstructed vector| (owned; built by plaid_index_set_renormalize)
+    bool renormalize = false;     // stage 4 and plaid_decompress_passages scale reconstructed vectors to unit length
     uint32_t *ivr_table = nullptr;  // range table of the inverted lists (owned); null: union + code stream are used
     int32_t ivr_shift = 11;         // log2 of the passages per table column (11 or 13)
     int32_t *dense_id = nullptr;    // with the range table: bitmap row of each centroid's list, -1 for all but the longest
@@ -523,6 +525,27 @@ extern "C" int plaid_get_stage_ms(const plaid_index *idx, float *out_ms)
     for (int i = 0; i < PLAID_NUM_STAGES; ++i) out_ms[i] = idx->stage_ms[i];
     return PLAID_OK;
 }
+extern "C" int plaid_index_set_renormalize(plaid_index *idx, int32_t on)
+{
+    if (!idx) return fail(PLAID_EINVAL, "null index");
+    if (on && !idx->inv_norm && idx->N > 0) {
+        DeviceGuard g(idx->device);
+        if (!g.ok) return fail(PLAID_EHIP, "hipSetDevice(%d) failed", idx->device);
+        void *d = nullptr;
+        if (hipMalloc(&d, (size_t)idx->N * sizeof(float)) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(PLAID_ENOMEM, "hipMalloc(%zu) for the tokens' scaling factors failed", (size_t)idx->N * sizeof(float));
+        }
+        idx->owned.push_back(d);
+        plaid_launch_token_inv_norm(nullptr, idx->centroids, idx->codes, idx->residuals, idx->weights, idx->nbits, idx->N,
+                                    (float *)d);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipStreamSynchronize(nullptr));
+        idx->inv_norm = (float *)d;
+    }
+    idx->renormalize = on != 0 && idx->N > 0;
+    return PLAID_OK;
+}
 extern "C" int plaid_set_max_chunk(plaid_index *idx, int32_t max_queries_per_chunk)
 {
     if (!idx || max_queries_per_chunk < 0) return fail(PLAID_EINVAL, "bad argument");
@@ -760,7 +783,8 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
         STAMP();
         // stage 4: decompression (Section 4.5) + exact MaxSim (Eq. 1), best k
         plaid_launch_decompress_maxsim(st, Qc, w.S, C, ix->doc_offsets, ix->codes, ix->residuals, ix->weights,
-                                       ix->nbits, n, w.sel3, pl.m3, w.n3, pl.m3, w.keys4, pl.m3);
+                                       ix->nbits, n, w.sel3, pl.m3, w.n3, pl.m3, w.keys4, pl.m3,
+                                       ix->renormalize ? ix->inv_norm : nullptr);
         STAMP();
         if (pl.m3 <= SEL_SORT_CAP) {
             plaid_launch_rank_output(st, w.keys4, pl.m3, w.n3, n, pl.m3, k, out_ids + (int64_t)q0 * k,
@@ -882,6 +906,9 @@ extern "C" int plaid_search_vanilla(plaid_index *ix, const float *Q, int32_t nq,
     if (nprobe < 1 || nprobe > ix->C) return fail(PLAID_EINVAL, "nprobe must be in [1, C] (got %d, C = %lld)", nprobe, (long long)ix->C);
     if (ncandidates < 1) return fail(PLAID_EINVAL, "ncandidates must be >= 1 (got %d)", ncandidates);
     if (k < 1) return fail(PLAID_EINVAL, "k must be >= 1 (got %d)", k);
+    if (ix->renormalize)
+        return fail(PLAID_EINVAL, "vanilla retrieval is not available while reconstructed vectors are scaled to unit length "
+                                  "(plaid_index_set_renormalize)");
     DeviceGuard g(ix->device);
     if (!g.ok) return fail(PLAID_EHIP, "hipSetDevice(%d) failed", ix->device);
     int rc = ensure_vanilla_structures(ix);
@@ -1164,7 +1191,7 @@ extern "C" int plaid_decompress_passages(plaid_index *ix, const int32_t *pids, i
         return fail(PLAID_EINVAL, "passages hold %lld tokens, capacity is %lld", (long long)total, (long long)capacity);
     if (out_vectors || out_indices)
         plaid_launch_decompress_dump(st, ix->centroids, ix->doc_offsets, ix->codes, ix->residuals, ix->weights, ix->nbits,
-                                     pids, n, offs, out_vectors, out_indices);
+                                     pids, n, offs, out_vectors, out_indices, ix->renormalize ? ix->inv_norm : nullptr);
     HIP_TRY(hipGetLastError());
     return PLAID_OK;
 }

@@ -260,13 +260,17 @@ void plaid_launch_ci_list(hipStream_t st, const float *S, int64_t C, const int64
 void plaid_launch_decompress_maxsim(hipStream_t st, const float *Q, const float *S, int64_t C, const int64_t *doc_offsets,
                                     const int32_t *codes, const uint8_t *residuals, const float *bucket_weights,
                                     int nbits, int nq, const uint64_t *in_keys, int64_t in_stride,
-                                    const int32_t *in_counts, int n_upper, uint64_t *out_keys, int64_t out_stride);
+                                    const int32_t *in_counts, int n_upper, uint64_t *out_keys, int64_t out_stride,
+                                    const float *inv_norm = nullptr /* [N]: reconstructed vectors scaled to unit length */);
 
 // Section 4.5 alone: reconstructed vectors / bucket indices of listed passages.
 void plaid_launch_decompress_dump(hipStream_t st, const float *centroids, const int64_t *doc_offsets,
                                   const int32_t *codes, const uint8_t *residuals, const float *bucket_weights,
                                   int nbits, const int32_t *pids, int n, const int64_t *out_offsets, float *out_vectors,
-                                  uint8_t *out_indices);
+                                  uint8_t *out_indices, const float *inv_norm = nullptr);
+// inv_norm[t] = 1 / |centroid[code_t] + residual_t| (fp32, from a double-precision sum of squares), 0 for a zero vector.
+void plaid_launch_token_inv_norm(hipStream_t st, const float *centroids, const int32_t *codes, const uint8_t *residuals,
+                                 const float *bucket_weights, int nbits, int64_t N, float *inv_norm);
 void plaid_launch_passage_offsets(hipStream_t st, const int64_t *doc_offsets, const int32_t *pids, int n,
                                   int64_t *out_offsets);
 

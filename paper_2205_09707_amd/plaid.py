@@ -50,7 +50,8 @@ class plaid_vanilla_debug(ct.Structure):
 EXPORTS = ("plaid_index_load", "plaid_index_from_view", "plaid_index_free", "plaid_search", "plaid_search_debug",
            "plaid_search_static", "plaid_search_vanilla", "plaid_decompress_passages", "plaid_index_info", "plaid_set_stage_timing", "plaid_get_stage_ms",
            "plaid_set_max_chunk", "plaid_get_score_kernel", "plaid_get_stage2_kernel", "plaid_assign_centroids",
-           "plaid_encode_residuals", "plaid_build_ivf", "plaid_workspace_bytes", "plaid_last_error")
+           "plaid_encode_residuals", "plaid_build_ivf", "plaid_workspace_bytes", "plaid_index_set_renormalize",
+           "plaid_last_error")
 
 _lib = None
 
@@ -301,6 +302,14 @@ def plaid_get_stage_ms(idx: Index) -> Dict[str, float]:
 
 def plaid_set_max_chunk(idx: Index, max_queries_per_chunk: int) -> None:
     _check(load_library().plaid_set_max_chunk(idx.handle, int(max_queries_per_chunk)))
+
+
+def plaid_index_set_renormalize(idx: Index, on: bool) -> None:
+    """Storage variant: score (stage 4) and return (plaid_decompress_passages) reconstructed vectors scaled back to unit
+    length.  The first call that switches it on computes one factor per token on the device."""
+    lib = load_library()
+    lib.plaid_index_set_renormalize.argtypes = [ct.c_void_p, ct.c_int32]
+    _check(lib.plaid_index_set_renormalize(idx.handle, 1 if on else 0))
 
 
 def plaid_get_score_kernel(idx: Index) -> int:

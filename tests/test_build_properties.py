@@ -28,8 +28,9 @@ KERNELS = {
     "s2_union_wide_kernel": ("k_stage2.hip", 128, 80 << 10),       # two workgroups of 1024 threads per CU
     "s2_stream_kernel": ("k_stage2.hip", 128, 40 << 10),
     "ci_list_kernelILb0E": ("k_ci.hip", 96, 8 << 10),              # five waves per SIMD; wave-private LDS areas
-    "decompress_maxsim_kernelILi2ELb0E": ("k_stage4.hip", 128, 32 << 10),   # four waves per SIMD (query operands in LDS)
-    "decompress_maxsim_kernelILi1ELb0E": ("k_stage4.hip", 128, 32 << 10),
+    "decompress_maxsim_kernelILi2ELb0ELb0E": ("k_stage4.hip", 128, 32 << 10),   # four waves per SIMD (query operands in LDS)
+    "decompress_maxsim_kernelILi1ELb0ELb0E": ("k_stage4.hip", 128, 32 << 10),
+    "decompress_maxsim_kernelILi2ELb0ELb1E": ("k_stage4.hip", 128, 32 << 10),   # ... with unit-length reconstruction
     "sel_sort_kernelILi512E": ("k_select.hip", 64, 0),             # dynamic LDS only
     "sel2_filter_kernel": ("k_select.hip", 64, 8 << 10),
     "encode_residuals_kernelILi2E": ("k_build.hip", 64, 0),

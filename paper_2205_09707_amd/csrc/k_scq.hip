@@ -842,7 +842,9 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
                     if (!listed && ok[u]) ok[u] = tmq[(int64_t)t * QLEN + i] >= T;
                     cc[u] = (int64_t)t * tile_rows + r;
                     ok[u] = ok[u] && r < tile_rows && cc[u] < C;
-                    sv[u] = ok[u] ? Sq[cc[u] * QLEN + i] : 0.f;
+                    // (no stored scores: nearest-centroid assignment keeps only the tile maxima, and every row of a listed
+                    // tile counts as a row that may be among the best)
+                    sv[u] = ok[u] ? (S ? Sq[cc[u] * QLEN + i] : INFINITY) : 0.f;
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
@@ -959,7 +961,7 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
             for (int p = tid; p < n_amb * QLEN; p += TAIL_THREADS) {
                 const int64_t c = amb_rows[p >> 5];
                 const int tok = p & 31;
-                if (Sq[c * QLEN + tok] >= x.t_lo && scq_exact_entry(x.Cm + c * DIM, Qq + tok * DIM) >= x.t_cs)
+                if ((!S || Sq[c * QLEN + tok] >= x.t_lo) && scq_exact_entry(x.Cm + c * DIM, Qq + tok * DIM) >= x.t_cs)
                     atomicOr(&kbq[c >> 5], 1u << (c & 31));
             }
         }

@@ -159,17 +159,18 @@ __global__ __launch_bounds__(H16_THREADS, NT == 2 ? 2 : 4) void scq16_kernel(
             float cmax = -INFINITY;
             if (nvalid == 32) {  // (uniform) a whole tile: sixteen unconditional stores of two 128-byte rows each, marked
                                  // as streaming (4 GB per launch pass through: nothing of it is worth a cache line)
+                if (S) {         // (uniform; null: only the tile maxima are wanted -- nearest-centroid assignment)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    __builtin_nontemporal_store(val[v], &srow[(8 * (v >> 2) + (v & 3)) * QLEN]);
-                    cmax = fmaxf(cmax, val[v]);
+                    for (int v = 0; v < 16; ++v) __builtin_nontemporal_store(val[v], &srow[(8 * (v >> 2) + (v & 3)) * QLEN]);
                 }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) cmax = fmaxf(cmax, val[v]);
             } else {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int r = 8 * (v >> 2) + (v & 3);
                     if (r + 4 * h < nvalid) {
-                        srow[r * QLEN] = val[v];
+                        if (S) srow[r * QLEN] = val[v];
                         cmax = fmaxf(cmax, val[v]);
                     }
                 }

@@ -66,6 +66,7 @@ struct plaid_index {
     void *A16 = nullptr;          // split-fp16 operand form of the centroids (owned), when scq_form is PLAID_SCQ_SPLIT16
     float *inv_norm = nullptr;    // [N] 1 / |reconstructed vector| (owned; built by plaid_index_set_renormalize)
     bool renormalize = false;     // stage 4 and plaid_decompress_passages scale reconstructed vectors to unit length
+    bool no_scores = false;       // nearest-centroid assignment with the split-fp16 kernel: S_cq itself is not stored
     uint32_t *ivr_table = nullptr;  // range table of the inverted lists (owned); null: union + code stream are used
     int32_t ivr_shift = 11;         // log2 of the passages per table column (11 or 13)
     int32_t *dense_id = nullptr;    // with the range table: bitmap row of each centroid's list, -1 for all but the longest
@@ -627,7 +628,7 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     w.sel4_zero = take(plaid_select_zero_bytes(qc));
     w.zero_bytes = off;
     w.Qd = (double *)take((size_t)qc * QLEN * DIM * 8);
-    w.S = (float *)take((size_t)qc * C * QLEN * 4);
+    w.S = ix->no_scores ? nullptr : (float *)take((size_t)qc * C * QLEN * 4);
     w.keepbits = (uint32_t *)take((size_t)qc * w.keep_words * 4);
     w.ambbits = (uint32_t *)take((size_t)qc * w.keep_words * 4);
     w.probed = (int32_t *)take((size_t)qc * QLEN * pl.nprobe * 4);
@@ -1034,6 +1035,9 @@ extern "C" int plaid_assign_centroids(const float *centroids, int64_t C, const f
             return fail(PLAID_ENOMEM, "hipMalloc(%zu) for the centroids' matrix operands failed", ab);
         }
         plaid_launch_scq16_split_centroids(st, centroids, C, a16.p);
+        // The probe kernel ranks by scores it re-evaluates in double and needs the tile maxima only to find the rows worth
+        // re-evaluating: the scores themselves (4 C bytes per vector, the kernel's whole memory traffic) are not stored.
+        fake.no_scores = true;
     }
     Plan pl;
     pl.nprobe = 1;

@@ -811,18 +811,27 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
     // This instance's queries: those with 1..31 (32-bit sets) or more (64-bit sets) surviving centroids, and with the
     // 32-bit instance those without any unless s2_union_wide_kernel has produced their candidate and empty-bag words.
     // Row y of the grid takes entries y, y + gridDim.y, ... of the lists the probe kernel made.
+    // skip_k0 bit 1 (64-bit instance only): this instance is the only one launched and takes every query (a launch of a
+    // few queries: one kernel less on the way of each).
     const int cls = sizeof(SetT) == 4 ? 1 : 2;
-    const int n_mine = qcount[cls], n_none = (cls == 1 && !skip_k0) ? qcount[0] : 0;
+    const bool take_all = sizeof(SetT) == 8 && (skip_k0 & 2);
+    const bool skip_none = skip_k0 & 1;
+    const int n_first = take_all ? qcount[1] : qcount[cls];                      // entries of list 1 (or of this class)
+    const int n_second = take_all ? qcount[2] : 0;                               // then of list 2
+    const int n_none = ((cls == 1 || take_all) && !skip_none) ? qcount[0] : 0;   // then of list 0
+    const int n_all = n_first + n_second + n_none;
     // Only the 2048-passage instance with 64-bit sets loops: its class is usually empty or nearly so, and a launch of
     // nq rows of workgroups that all find nothing to do costs tens of microseconds.  The other instances are launched
     // with one row per query and take one entry (a class that holds most of the chunk's queries runs faster that way).
     constexpr bool LOOP = SHIFT == 11 && sizeof(SetT) == 8;
     int qi = blockIdx.y;
-    if (qi >= n_mine + n_none) return;  // uniform
+    if (qi >= n_all) return;  // uniform
     do {
-    const int q = qi < n_mine ? qlist[(int64_t)cls * qlist_stride + qi] : qlist[qi - n_mine];
+    const int q = qi < n_first ? qlist[(int64_t)(take_all ? 1 : cls) * qlist_stride + qi]
+                               : (qi < n_first + n_second ? qlist[2ll * qlist_stride + qi - n_first]
+                                                          : qlist[qi - n_first - n_second]);
     const int K = s2_uniform(meta[q].K);
-    if ((K <= 31) != (sizeof(SetT) == 4)) continue;  // (never: the lists are made from the same K)
+    if (!take_all && (K <= 31) != (sizeof(SetT) == 4)) continue;  // (never: the lists are made from the same K)
     const bool slots = K > 0 && K <= S2_MAX_KEPT;  // bags are kept as slot sets
     const int hsh = s2_uniform(meta[q].hash_shift);
     for (int e = tid; e < RANGE; e += THREADS) lsets[e] = (SetT)0;
@@ -956,7 +965,7 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
     }
     if (K > 0) s2_flush_hist(lhist, hist + (int64_t)q * SEL_BINS);
     if (LOOP) __syncthreads();  // the LDS arrays are set up again for the next query
-    } while (LOOP && (qi += (int)gridDim.y) < n_mine + n_none);
+    } while (LOOP && (qi += (int)gridDim.y) < n_all);
 }
 
 void plaid_launch_stage2_inverted(hipStream_t st, const int32_t *uniq, const int32_t *n_uniq, int uniq_stride,
@@ -983,7 +992,13 @@ void plaid_launch_stage2_inverted(hipStream_t st, const int32_t *uniq, const int
                        uniq_stride, ivf_offsets, ivf_pids, table, nr, S, C, keepbits, keep_words, codes, doc_offsets, P,     \
                        b.meta, b.kept_ids, b.T, candbits, cand_words, keys2, key_stride, b.hist, b.emptybits, wide,         \
                        b.qcount, b.qlist, b.qlist_stride)
-    if (shift == 11) {
+    if (shift == 11 && nq < 8) {
+        // a few queries: the 64-bit instance alone, taking every query (same sets, same scores, one launch less)
+        hipLaunchKernelGGL((s2_invert_kernel<11, unsigned long long>), dim3((unsigned)nr, nq), dim3(IVR_THREADS(11)), 0, st, uniq,
+                           n_uniq, uniq_stride, ivf_offsets, ivf_pids, table, nr, S, C, keepbits, keep_words, codes, doc_offsets,
+                           P, b.meta, b.kept_ids, b.T, candbits, cand_words, keys2, key_stride, b.hist, b.emptybits, wide | 2,
+                           b.qcount, b.qlist, b.qlist_stride);
+    } else if (shift == 11) {
         S2_INVERT(11, uint32_t);
         S2_INVERT(11, unsigned long long);
     } else {

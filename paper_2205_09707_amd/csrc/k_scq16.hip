@@ -80,7 +80,9 @@ __device__ __forceinline__ void scq16_lds_barrier()
 // The loop over the group's queries is software-pipelined so that no wait covers a score store: the operands of query
 // q + 1 are requested before the matrix instructions of query q, moved into the other LDS buffer right after them (by
 // then they have arrived), the operands of q + 2 are requested, and only then are the scores of q stored.
-template <int NT>
+// STORE = false: the scores themselves are not written, only the tile maxima and the pruning words (nearest-centroid
+// assignment, which re-evaluates the rows of the best tile).
+template <int NT, bool STORE>
 __global__ __launch_bounds__(H16_THREADS, NT == 2 ? 2 : 4) void scq16_kernel(
     const scq16_half8 *__restrict__ A16, int64_t C, const scq16_half8 *__restrict__ B16, int nq, int qg, float t_lo, float t_hi,
     float *__restrict__ S, uint32_t *__restrict__ keepbits, uint32_t *__restrict__ ambbits, int64_t keep_words,
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(H16_THREADS, NT == 2 ? 2 : 4) void scq16_kernel(
             float cmax = -INFINITY;
             if (nvalid == 32) {  // (uniform) a whole tile: sixteen unconditional stores of two 128-byte rows each, marked
                                  // as streaming (4 GB per launch pass through: nothing of it is worth a cache line)
-                if (S) {         // (uniform; null: only the tile maxima are wanted -- nearest-centroid assignment)
+                if (STORE) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) __builtin_nontemporal_store(val[v], &srow[(8 * (v >> 2) + (v & 3)) * QLEN]);
                 }
@@ -170,7 +172,7 @@ __global__ __launch_bounds__(H16_THREADS, NT == 2 ? 2 : 4) void scq16_kernel(
                 for (int v = 0; v < 16; ++v) {
                     const int r = 8 * (v >> 2) + (v & 3);
                     if (r + 4 * h < nvalid) {
-                        if (S) srow[r * QLEN] = val[v];
+                        if (STORE) srow[r * QLEN] = val[v];
                         cmax = fmaxf(cmax, val[v]);
                     }
                 }
@@ -249,6 +251,10 @@ void plaid_launch_scq16(hipStream_t st, const void *A16, int64_t C, const void *
     if (qg > 64) qg = 64;
     if (qg > nq) qg = nq;
     const unsigned gy = (unsigned)((nq + qg - 1) / qg);
-    hipLaunchKernelGGL(scq16_kernel<H16_NT>, dim3(gx, gy), dim3(H16_THREADS), 0, st, (const scq16_half8 *)A16, C,
-                       (const scq16_half8 *)B16, nq, qg, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax);
+    if (S)
+        hipLaunchKernelGGL((scq16_kernel<H16_NT, true>), dim3(gx, gy), dim3(H16_THREADS), 0, st, (const scq16_half8 *)A16, C,
+                           (const scq16_half8 *)B16, nq, qg, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax);
+    else
+        hipLaunchKernelGGL((scq16_kernel<H16_NT, false>), dim3(gx, gy), dim3(H16_THREADS), 0, st, (const scq16_half8 *)A16, C,
+                           (const scq16_half8 *)B16, nq, qg, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax);
 }

@@ -20,7 +20,7 @@ KERNELS = {
     "stage1_tail_kernelILi8ELb0E": ("k_scq.hip", 128, 64 << 10),
     "stage1_tail_kernelILi2ELb1E": ("k_scq.hip", 128, 64 << 10),   # ... also with the re-evaluations in double
     "stage1_tail_kernelILi8ELb1E": ("k_scq.hip", 128, 64 << 10),
-    "scq16_kernel": ("k_scq16.hip", 256, 40 << 10),                # two waves per SIMD, two to four workgroups per CU
+    "scq16_kernelILi2ELb1E": ("k_scq16.hip", 256, 40 << 10),       # two waves per SIMD, two to four workgroups per CU
     "s2_invert_kernelILi11EjE": ("k_stage2.hip", 168, 53 << 10),   # 2048 passages per workgroup, three workgroups (of four waves) per CU
     "s2_invert_kernelILi11EyE": ("k_stage2.hip", 168, 53 << 10),
     "s2_invert_kernelILi13EjE": ("k_stage2.hip", 128, 80 << 10),   # 8192 passages, 1024 threads, 32-bit sets: two per CU

@@ -177,7 +177,7 @@ int plaid_index_info(const plaid_index *idx, int64_t *num_centroids, int64_t *nu
 
 /* Which kernel computes S_cq (Eq. 2) for this index: HOST *form =
  *   2  the half-precision matrix instruction on operands split into two fp16 terms each (the default).  Scores are
- *      within 2^-16 of the exact dot products for vectors of norm <= 1 whose components lie in fp16's range (observed:
+ *      within 2^-15 of the exact dot products for vectors of norm <= 1 whose components lie in fp16's range (observed:
  *      a few 1e-7); every decision taken on them -- probed centroids (Section 4.1), the pruning map (Eq. 5) -- is
  *      completed in double wherever that bound leaves it open, and the rows of the surviving centroids that stage 2
  *      scores with are re-evaluated in double, so probes, candidates, the pruning map and the stage-2 scores of

@@ -2,19 +2,22 @@
 //
 // An fp32 value a is written a = a1 + 2^-11 a2 + d, with a1 = fp16(a), a2 = fp16(2^11 (a - a1)) and |d| <= 2^-22 |a|
 // (each rounding keeps 11 significant bits; a1 is taken as 0 below fp16's normal range, so no operand is subnormal but
-// for values under 2^-25).  Then a b = a1 b1 + 2^-11 (a1 b2 + a2 b1) + r with |r| <= 3 * 2^-22 |a b|: three products
-// of fp16 values, each exact in fp32, accumulated in fp32 by v_mfma_f32_32x32x16_f16 -- a1 b1 in one accumulator, the
-// two cross terms in a second one that is scaled by 2^-11 when the two are added.  For vectors of norm at most one the
-// result differs from the exact dot product by at most 3 * 2^-22 (dropped terms) plus the fp32 accumulation error of
-// the 128 products, 128 * 2^-24 in the worst case: PLAID_SCQ16_EPS = 2^-16 covers both with room to spare.  Discrete
-// decisions never rest on these values alone: the probe kernel re-evaluates in double, as the definition reads, every
-// entry that lies within the bound of a decision (k_scq.hip).
+// for values under 2^-25).  Then 2^11 a b = (2^11 a1) b1 + a1 b2 + a2 b1 + r with |r| <= 3 * 2^-11 |a b|: three
+// products of fp16 values, each exact in fp32, accumulated in fp32 by v_mfma_f32_32x32x16_f16 into ONE accumulator,
+// which is scaled by 2^-11 on its way out.  (2^11 a1 is formed from a1 next to its use, an exact packed multiplication;
+// it needs |a| < 32 on the centroid side.)  Scaling the first product up, rather than the other two down, is what lets
+// the three share an accumulator: the cross terms are 2^-11 of the sum, and a rounding of the sum at 2^-24 of its size
+// costs them no more than it costs the first product.  For vectors of norm at most one the result differs from the exact
+// dot product by at most 3 * 2^-22 (dropped terms) plus the fp32 accumulation error of the 384 products, 384 * 2^-24 in
+// the worst case: PLAID_SCQ16_EPS = 2^-15 covers both.  Discrete decisions never rest on these values alone: the probe
+// kernel re-evaluates in double, as the definition reads, every entry that lies within the bound of a decision
+// (k_scq.hip).
 //
 // Work split: a workgroup of four waves owns 256 consecutive centroids; a wave keeps the operands of its 64 centroid
 // rows (two 32-row tiles) in registers for the whole kernel and walks a group of queries, whose operands (16 KB per
 // query, already split and laid out in operand order by scq16_split_kernel) pass through LDS, double-buffered, shared
-// by the four waves.  Per query and tile: 24 matrix instructions, then the epilogue straight from the accumulators:
-// S (a store instruction writes two whole 128-byte rows), the tile's column maxima, and the pruning bits of Eq. 5 in
+// by the four waves.  Per query and tile: 24 matrix instructions, then straight from the accumulator: S (a store
+// instruction writes two whole 128-byte rows), the tile's column maxima, and the pruning bits of Eq. 5 in
 // two flavours -- "passes even if every entry were PLAID_SCQ16_EPS lower" (kept for sure) and "would pass if some
 // entry were PLAID_SCQ16_EPS higher" (ambiguous: decided later in double).
 #include "plaid_internal.h"
@@ -74,27 +77,105 @@ __device__ __forceinline__ void scq16_lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// Grid: x = block of 32 * H16_WAVES * NT centroids, y = group of qg queries.  A16: a whole number of workgroups' tiles
-// (rows past C are zero).  keepbits / ambbits: [q][keep_words], bit c = row c passes Eq. 5 for sure / is ambiguous;
-// tilemax: [q][ceil(C/32)][32].
-// The loop over the group's queries is software-pipelined so that no wait covers a score store: the operands of query
-// q + 1 are requested before the matrix instructions of query q, moved into the other LDS buffer right after them (by
-// then they have arrived), the operands of q + 2 are requested, and only then are the scores of q stored.
-// STORE = false: the scores themselves are not written, only the tile maxima and the pruning words (nearest-centroid
-// assignment, which re-evaluates the rows of the best tile).
-template <int NT, bool STORE>
-__global__ __launch_bounds__(H16_THREADS, NT == 2 ? 2 : 4) void scq16_kernel(
-    const scq16_half8 *__restrict__ A16, int64_t C, const scq16_half8 *__restrict__ B16, int nq, int qg, float t_lo, float t_hi,
-    float *__restrict__ S, uint32_t *__restrict__ keepbits, uint32_t *__restrict__ ambbits, int64_t keep_words,
-    float *__restrict__ tilemax)
+// One step of the matrix work: dimensions 16 s .. 16 s + 15 of every tile of the wave, all three products into the one
+// accumulator of the tile.  k2048: 2^11 in every half (handed in so that the scaled operands are formed here, next to
+// their use, instead of being kept in registers for the whole kernel).
+template <int NT>
+__device__ __forceinline__ void scq16_step(const scq16_half8 (&a)[NT][2][H16_STEPS], const scq16_half8 *buf, int lane, int s,
+                                           scq16_half8 k2048, scq16_floatx16 (&acc)[NT])
 {
-    __shared__ scq16_half8 Bs[2][H16_TILE_VEC];
+    const scq16_half8 b1 = buf[s * 64 + lane], b2 = buf[(H16_STEPS + s) * 64 + lane];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[t][0][s] * k2048, b1, acc[t], 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[t][0][s], b2, acc[t], 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[t][1][s], b1, acc[t], 0, 0, 0);
+}
+
+// The score stores of one query, cut into H16_STEPS parts of 2 NT store instructions each (a store instruction writes
+// two whole 128-byte rows).  val[t][v] of lane 32 h + n is row 8 (v / 4) + 4 h + v % 4 of tile t, column (query token) n;
+// s0: the address of row 4 h, column n of the wave's first tile.  WHOLE: every tile of the wave has its 32 rows; otherwise
+// lim[t] = rows of tile t that exist, less 4 h.
+template <int NT, bool WHOLE>
+__device__ __forceinline__ void scq16_store_part(float *__restrict__ s0, const float (&val)[NT][16], int part, const int (&lim)[NT])
+{
+#pragma unroll
+    for (int j = 0; j < 2 * NT; ++j) {
+        const int i = part * 2 * NT + j, t = i >> 4, v = i & 15, r = 8 * (v >> 2) + (v & 3);
+        float *dst = s0 + (int64_t)(32 * t + r) * QLEN;
+        if (WHOLE)  // marked as streaming: 4 GB per launch pass through, nothing of it is worth a cache line
+            __builtin_nontemporal_store(val[t][v], dst);
+        else if (r < lim[t])
+            *dst = val[t][v];
+    }
+}
+
+// Out of the accumulators of one query: the scores (val, scaled back), the tiles' column maxima and the pruning words.
+template <int NT>
+__device__ __forceinline__ void scq16_reduce(const scq16_floatx16 (&acc)[NT], float (&val)[NT][16], const int (&nvalid)[NT],
+                                             int64_t tile0, int64_t n_blk, int q, int lane, float t_lo, float t_hi,
+                                             uint32_t *__restrict__ keepbits, uint32_t *__restrict__ ambbits, int64_t keep_words,
+                                             float *__restrict__ tilemax)
+{
+    const int n = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) val[t][v] = acc[t][v] * (1.0f / H16_SCALE);
+        if (nvalid[t] == 0) continue;  // (uniform) a tile past the end of the table
+        const int64_t tile = tile0 + t;
+        float cmax = -INFINITY;
+        if (nvalid[t] == 32) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) cmax = fmaxf(cmax, val[t][v]);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (8 * (v >> 2) + (v & 3) + 4 * h < nvalid[t]) cmax = fmaxf(cmax, val[t][v]);
+        }
+        // Eq. 5.  A row can only pass when some lane's maximum reaches t_lo, which no lane's does for all but a few
+        // tiles: one comparison settles those.  (Rows past the end hold zeros and are masked below.)
+        float lmax = val[t][0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) lmax = fmaxf(lmax, val[t][v]);
+        uint32_t maybe = 0u, sure = 0u;  // uniform: bit = row of the tile with an entry >= t_lo / >= t_hi
+        if (__ballot(lmax >= t_lo) != 0ull) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = 8 * (v >> 2) + (v & 3);
+                const unsigned long long m = __ballot(val[t][v] >= t_lo), ms = __ballot(val[t][v] >= t_hi);
+                maybe |= (((uint32_t)m) ? 1u : 0u) << r;
+                maybe |= (((uint32_t)(m >> 32)) ? 1u : 0u) << (r + 4);
+                sure |= (((uint32_t)ms) ? 1u : 0u) << r;
+                sure |= (((uint32_t)(ms >> 32)) ? 1u : 0u) << (r + 4);
+            }
+        }
+        const uint32_t valid = nvalid[t] == 32 ? 0xFFFFFFFFu : (1u << nvalid[t]) - 1u;  // rows past the end never pass
+        cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
+        if (tilemax && h == 0) tilemax[((int64_t)q * n_blk + tile) * QLEN + n] = cmax;
+        if (lane == 0) {
+            keepbits[(int64_t)q * keep_words + tile] = sure & valid;
+            ambbits[(int64_t)q * keep_words + tile] = maybe & ~sure & valid;
+        }
+    }
+}
+
+// The kernel's body.  WHOLE (uniform over the wave): each of its tiles has all 32 rows, so every score store is
+// unconditional.  The two cases are separate instances, and the first query is taken out of the loop, so that the number
+// of stores between a request for operands and the wait for them is the same on every path: the memory counter retires
+// in order, and a wait sized for the path with the fewest stores would sit out the score stores of the others.
+template <int NT, bool STORE, bool WHOLE>
+__device__ __forceinline__ void scq16_body(scq16_half8 (&Bs)[2][H16_TILE_VEC], const int (&nvalid)[NT], const scq16_half8 *__restrict__ A16,
+                                           int64_t C, const scq16_half8 *__restrict__ B16, int q_begin, int q_end, float t_lo,
+                                           float t_hi, float *__restrict__ S, uint32_t *__restrict__ keepbits,
+                                           uint32_t *__restrict__ ambbits, int64_t keep_words, float *__restrict__ tilemax)
+{
     constexpr int NPRE = H16_TILE_VEC / H16_THREADS;  // operand vectors a thread moves per query
     const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t tile0 = ((int64_t)blockIdx.x * H16_WAVES + wave) * NT;
     const int64_t n_blk = (C + 31) >> 5;
-    const int q_begin = blockIdx.y * qg, q_end = q_begin + qg < nq ? q_begin + qg : nq;
 
     scq16_half8 pre[NPRE];
     const scq16_half8 *bsrc = B16 + (int64_t)q_begin * H16_TILE_VEC + tid;
@@ -119,25 +200,41 @@ __global__ __launch_bounds__(H16_THREADS, NT == 2 ? 2 : 4) void scq16_kernel(
     }
     scq16_lds_barrier();
 
-    for (int q = q_begin; q < q_end; ++q) {
+    scq16_floatx16 acc[NT];
+    float val[NT][16];
+    typedef _Float16 scq16_half2 __attribute__((ext_vector_type(2)));
+    // matrix work of query q (operands in Bs[(q - q_begin) & 1]); with_stores: the scores in val go out between the steps
+    auto products = [&](int q, float *sdst, auto with_stores) {
         const scq16_half8 *buf = Bs[(q - q_begin) & 1];
-        scq16_half8 *nxt = Bs[(q - q_begin + 1) & 1];
-        scq16_floatx16 hi[NT], lo[NT];
+        uint32_t kbits;  // 2^11 twice over in fp16, produced here so that the scaled operands are not hoisted out of the loop
+        asm volatile("s_mov_b32 %0, 0x68006800" : "=s"(kbits));
+        const scq16_half2 k2 = __builtin_bit_cast(scq16_half2, kbits);
+        const scq16_half8 k2048 = {k2.x, k2.y, k2.x, k2.y, k2.x, k2.y, k2.x, k2.y};
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) hi[t][v] = 0.f, lo[t][v] = 0.f;
+            for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+        int lim[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            lim[t] = nvalid[t] - 4 * h;
+            if (!WHOLE) asm volatile("" : "+v"(lim[t]));  // or 32 lane masks would be formed ahead of the loop and kept
+        }
 #pragma unroll
         for (int s = 0; s < H16_STEPS; ++s) {
-            const scq16_half8 b1 = buf[s * 64 + lane], b2 = buf[(H16_STEPS + s) * 64 + lane];
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                hi[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[t][0][s], b1, hi[t], 0, 0, 0);
-                lo[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[t][0][s], b2, lo[t], 0, 0, 0);
-                lo[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[t][1][s], b1, lo[t], 0, 0, 0);
+            scq16_step<NT>(a, buf, lane, s, k2048, acc);
+            if (decltype(with_stores)::value) {
+                scq16_store_part<NT, WHOLE>(sdst, val, s, lim);
+                // keeps the stores and matrix instructions of a step in that step (the compiler would gather the stores
+                // at the end); LDS reads and scalar / vector arithmetic may still move across
+                __builtin_amdgcn_sched_barrier(0x0106);
             }
         }
-        // the next query's operands: into the buffer that every wave finished reading before the last barrier
+    };
+    // after the matrix work of query q: the next query's operands go into the buffer that every wave finished reading
+    // before the last barrier, those of the query after it are requested, and the accumulators are reduced into val
+    auto finish = [&](int q) {
+        scq16_half8 *nxt = Bs[(q - q_begin + 1) & 1];
         if (q + 1 < q_end) {
 #pragma unroll
             for (int k = 0; k < NPRE; ++k) nxt[tid + k * H16_THREADS] = pre[k];
@@ -147,63 +244,65 @@ __global__ __launch_bounds__(H16_THREADS, NT == 2 ? 2 : 4) void scq16_kernel(
 #pragma unroll
             for (int k = 0; k < NPRE; ++k) pre[k] = bsrc[k * H16_THREADS];
         }
-        // Epilogue.  Accumulator v of lane 32 h + n is row 8 (v / 4) + 4 h + v % 4 of the tile, column (query token) n.
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const int64_t tile = tile0 + t;
-            if (tile >= n_blk) break;  // (uniform) a tile past the end of the table
-            const int64_t row0 = tile << 5;
-            const int nvalid = C - row0 < 32 ? (int)(C - row0) : 32;
-            float *srow = S + ((int64_t)q * C + row0 + 4 * h) * QLEN + n;
-            float val[16];
-#pragma unroll
-            for (int v = 0; v < 16; ++v) val[v] = fmaf(lo[t][v], 1.0f / H16_SCALE, hi[t][v]);
-            float cmax = -INFINITY;
-            if (nvalid == 32) {  // (uniform) a whole tile: sixteen unconditional stores of two 128-byte rows each, marked
-                                 // as streaming (4 GB per launch pass through: nothing of it is worth a cache line)
-                if (STORE) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) __builtin_nontemporal_store(val[v], &srow[(8 * (v >> 2) + (v & 3)) * QLEN]);
-                }
-#pragma unroll
-                for (int v = 0; v < 16; ++v) cmax = fmaxf(cmax, val[v]);
-            } else {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int r = 8 * (v >> 2) + (v & 3);
-                    if (r + 4 * h < nvalid) {
-                        if (STORE) srow[r * QLEN] = val[v];
-                        cmax = fmaxf(cmax, val[v]);
-                    }
-                }
-            }
-            // Eq. 5.  A row can only pass when some lane's maximum reaches t_lo, which no lane's does for all but a few
-            // tiles: one comparison settles those.  (Rows past the end hold zeros and are masked below.)
-            float lmax = val[0];
-#pragma unroll
-            for (int v = 1; v < 16; ++v) lmax = fmaxf(lmax, val[v]);
-            uint32_t maybe = 0u, sure = 0u;  // uniform: bit = row of the tile with an entry >= t_lo / >= t_hi
-            if (__ballot(lmax >= t_lo) != 0ull) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int r = 8 * (v >> 2) + (v & 3);
-                    const unsigned long long m = __ballot(val[v] >= t_lo), ms = __ballot(val[v] >= t_hi);
-                    maybe |= (((uint32_t)m) ? 1u : 0u) << r;
-                    maybe |= (((uint32_t)(m >> 32)) ? 1u : 0u) << (r + 4);
-                    sure |= (((uint32_t)ms) ? 1u : 0u) << r;
-                    sure |= (((uint32_t)(ms >> 32)) ? 1u : 0u) << (r + 4);
-                }
-            }
-            const uint32_t valid = nvalid == 32 ? 0xFFFFFFFFu : (1u << nvalid) - 1u;  // rows past the end never pass
-            cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
-            if (tilemax && h == 0) tilemax[((int64_t)q * n_blk + tile) * QLEN + n] = cmax;
-            if (lane == 0) {
-                keepbits[(int64_t)q * keep_words + tile] = sure & valid;
-                ambbits[(int64_t)q * keep_words + tile] = maybe & ~sure & valid;
-            }
-        }
+        scq16_reduce<NT>(acc, val, nvalid, tile0, n_blk, q, lane, t_lo, t_hi, keepbits, ambbits, keep_words, tilemax);
         scq16_lds_barrier();  // publishes nxt; every wave is done reading buf
+    };
+    struct no_t { enum { value = 0 }; };
+    struct yes_t { enum { value = 1 }; };
+    float *s0 = STORE ? S + ((int64_t)q_begin * C + (tile0 << 5) + 4 * h) * QLEN + n : nullptr;  // of the query whose stores are due
+    products(q_begin, s0, no_t());
+    finish(q_begin);
+    for (int q = q_begin + 1; q < q_end; ++q) {
+        if (STORE) {
+            products(q, s0, yes_t());
+            s0 += C * QLEN;
+        } else {
+            products(q, s0, no_t());
+        }
+        finish(q);
     }
+    if (STORE) {  // the last query's scores
+        int lim[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) lim[t] = nvalid[t] - 4 * h;
+#pragma unroll
+        for (int s = 0; s < H16_STEPS; ++s) scq16_store_part<NT, WHOLE>(s0, val, s, lim);
+    }
+}
+
+// Grid: x = block of 32 * H16_WAVES * NT centroids, y = group of qg queries.  A16: a whole number of workgroups' tiles
+// (rows past C are zero).  keepbits / ambbits: [q][keep_words], bit c = row c passes Eq. 5 for sure / is ambiguous;
+// tilemax: [q][ceil(C/32)][32].
+// The loop over the group's queries is software-pipelined twice over.  Operands: those of query q + 1 are requested
+// before the matrix instructions of query q, moved into the other LDS buffer right after them (by then they have
+// arrived), and those of q + 2 are requested.  Scores: the results of query q leave the accumulators (scaled, reduced
+// for the tile maxima and the pruning words) into registers of their own, and their stores are issued between the
+// matrix instructions of query q + 1, a few per step, so that the store stream and the matrix pipe run side by side.
+// STORE = false: the scores themselves are not written, only the tile maxima and the pruning words (nearest-centroid
+// assignment, which re-evaluates the rows of the best tile).
+template <int NT, bool STORE>
+__global__ __launch_bounds__(H16_THREADS, NT == 2 ? 2 : 4) void scq16_kernel(
+    const scq16_half8 *__restrict__ A16, int64_t C, const scq16_half8 *__restrict__ B16, int nq, int qg, float t_lo, float t_hi,
+    float *__restrict__ S, uint32_t *__restrict__ keepbits, uint32_t *__restrict__ ambbits, int64_t keep_words,
+    float *__restrict__ tilemax)
+{
+    __shared__ scq16_half8 Bs[2][H16_TILE_VEC];
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int64_t tile0 = ((int64_t)blockIdx.x * H16_WAVES + wave) * NT;
+    const int q_begin = blockIdx.y * qg, q_end = q_begin + qg < nq ? q_begin + qg : nq;
+    int nvalid[NT];  // (uniform) rows of each tile that exist: 0 for a tile past the end of the table
+    bool whole = true;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int64_t left = C - ((tile0 + t) << 5);
+        nvalid[t] = left >= 32 ? 32 : left > 0 ? (int)left : 0;
+        whole = whole && nvalid[t] == 32;
+    }
+    // (the barriers inside are reached by all four waves in either instance: both run the same loop over the queries)
+    if (whole)
+        scq16_body<NT, STORE, true>(Bs, nvalid, A16, C, B16, q_begin, q_end, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax);
+    else
+        scq16_body<NT, STORE, false>(Bs, nvalid, A16, C, B16, q_begin, q_end, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax);
 }
 
 // ------------------------------------------------------------------ host side

@@ -127,7 +127,7 @@ size_t plaid_stage1_tilemax_bytes(int64_t C, int nq, int nprobe);
 // Split-fp16 form of Eq. 2 (k_scq16.hip).  S differs from the exact dot products by at most PLAID_SCQ16_EPS for
 // vectors of norm <= 1 (components within fp16's range); keepbits holds the rows that pass Eq. 5 even if every entry
 // were that much lower, ambbits the rows whose test the bound leaves open (decided in double by the probe kernel).
-#define PLAID_SCQ16_EPS 1.52587890625e-05f  // 2^-16
+#define PLAID_SCQ16_EPS 3.0517578125e-05f  // 2^-15
 size_t plaid_scq16_centroid_bytes(int64_t C);  // operand form of the centroid table, built once per index
 size_t plaid_scq16_query_bytes(int nq);        // operand form of nq queries
 void plaid_launch_scq16_split_centroids(hipStream_t st, const float *centroids, int64_t C, void *A16);

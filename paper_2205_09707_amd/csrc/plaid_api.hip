@@ -865,7 +865,7 @@ static int ensure_vanilla_structures(plaid_index *ix)
     if (ix->N >= (1ll << 31)) return fail(PLAID_EINVAL, "vanilla retrieval needs fewer than 2^31 embeddings (index has %lld)", (long long)ix->N);
     HIP_TRY(hipDeviceSynchronize());
     void *off = nullptr, *ids = nullptr, *t2p = nullptr, *scratch = nullptr;
-    const size_t sb = plaid_ivf_build_scratch_bytes(ix->N, ix->C) + 256;
+    const size_t sb = plaid_embedding_lists_scratch_bytes(ix->N, ix->C) + 256;
     const size_t nb = (size_t)(ix->N > 0 ? ix->N : 1) * 4;
     if (hipMalloc(&off, (size_t)(ix->C + 1) * 8) != hipSuccess || hipMalloc(&ids, nb) != hipSuccess ||
         hipMalloc(&t2p, nb) != hipSuccess || hipMalloc(&scratch, sb) != hipSuccess) {
@@ -1132,14 +1132,16 @@ extern "C" int plaid_build_ivf(const int32_t *codes, const int64_t *doc_offsets,
     HIP_TRY(hipMemcpyAsync(&ends[1], doc_offsets + P, 8, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     if (ends[0] != 0 || ends[1] != N) return fail(PLAID_EINVAL, "doc_offsets must run from 0 to num_embeddings (%lld)", (long long)N);
-    const size_t sb = plaid_ivf_build_scratch_bytes(P, C);
+    // scratch: the list builder's area (counters first, they start at zero), then 256 bytes for the error flag
+    const size_t sb = plaid_ivf_lists_scratch_bytes(N, C), zb = plaid_ivf_lists_scratch_zero_bytes(N, C);
     TempAlloc scratch;
     if (hipMalloc(&scratch.p, sb + 256) != hipSuccess) {
         (void)hipGetLastError();
-        return fail(PLAID_ENOMEM, "hipMalloc(%zu) for the inverted-list counts failed", sb);
+        return fail(PLAID_ENOMEM, "hipMalloc(%zu) for the inverted-list scratch failed", sb);
     }
-    HIP_TRY(hipMemsetAsync(scratch.p, 0, sb + 256, st));
-    int32_t *bad_d = (int32_t *)((char *)scratch.p + sb);  // the last 256 bytes: the error flag
+    HIP_TRY(hipMemsetAsync(scratch.p, 0, zb, st));
+    int32_t *bad_d = (int32_t *)((char *)scratch.p + sb);
+    HIP_TRY(hipMemsetAsync(bad_d, 0, 256, st));
     plaid_launch_ivf_build_offsets(st, codes, doc_offsets, P, N, C, scratch.p, ivf_offsets, bad_d);
     HIP_TRY(hipGetLastError());
     int32_t bad = 0;

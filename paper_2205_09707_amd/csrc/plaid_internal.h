@@ -238,8 +238,11 @@ void plaid_launch_ivf_dense_fill(hipStream_t st, const int64_t *ivf_offsets, con
 // residuals[j] = packed bucket indices of x[j] - centroids[codes[j]]; bad[0] is set when a code is out of range.
 void plaid_launch_encode_residuals(hipStream_t st, const float *centroids, int64_t C, const float *x, const int32_t *codes,
                                    int64_t n, const float *cutoffs, int nbits, uint8_t *residuals, int32_t *bad);
-// Inverted lists in two steps sharing a scratch area (zero on entry): offsets first, then the passage ids.
-size_t plaid_ivf_build_scratch_bytes(int64_t P, int64_t C);
+// Inverted lists in two steps sharing a scratch area of plaid_ivf_lists_scratch_bytes(N, C) bytes, whose first
+// plaid_ivf_lists_scratch_zero_bytes(N, C) bytes are zero on entry: offsets first (bad[0] is set when a code or an
+// offset is out of range), then -- only if nothing was bad -- the passage ids.
+size_t plaid_ivf_lists_scratch_bytes(int64_t N, int64_t C);
+size_t plaid_ivf_lists_scratch_zero_bytes(int64_t N, int64_t C);
 void plaid_launch_ivf_build_offsets(hipStream_t st, const int32_t *codes, const int64_t *doc_offsets, int64_t P, int64_t N,
                                     int64_t C, void *scratch, int64_t *ivf_offsets, int32_t *bad);
 void plaid_launch_ivf_build_fill(hipStream_t st, const int32_t *codes, const int64_t *doc_offsets, int64_t P, int64_t N,
@@ -283,7 +286,8 @@ void plaid_launch_index_validate(hipStream_t st, const int64_t *doc_offsets, int
 // Vanilla ColBERTv2 retrieval, the paper's baseline (k_build.hip, k_vanilla.hip, k_stage4.hip)
 // ---------------------------------------------------------------------------------------------
 // Embedding-level inverted lists: offsets [C+1], eids [N] = ascending token indices per centroid (N < 2^31);
-// scratch: plaid_ivf_build_scratch_bytes(N, C) bytes, zero on entry; bad[0] is set when a code is out of range.
+// scratch: plaid_embedding_lists_scratch_bytes(N, C) bytes, zero on entry; bad[0] is set when a code is out of range.
+size_t plaid_embedding_lists_scratch_bytes(int64_t N, int64_t C);
 void plaid_launch_embedding_lists(hipStream_t st, const int32_t *codes, int64_t N, int64_t C, void *scratch, int64_t *offsets,
                                   int32_t *eids, int32_t *bad);
 void plaid_launch_tok2pid(hipStream_t st, const int64_t *doc_offsets, int64_t P, int64_t N, int32_t *tok2pid);

@@ -34,7 +34,9 @@ KERNELS = {
     "sel_sort_kernelILi512E": ("k_select.hip", 64, 0),             # dynamic LDS only
     "sel2_filter_kernel": ("k_select.hip", 64, 8 << 10),
     "encode_residuals_kernelILi2E": ("k_build.hip", 64, 0),
-    "ivb_fill_kernel": ("k_build.hip", 64, 0),
+    "ivb_rank_kernel": ("k_build.hip", 64, 0),
+    "ivb_sort_short_kernel": ("k_build.hip", 64, 32 << 10),      # a 2048-entry LDS area per wave
+    "ivb_sort_long_kernel": ("k_build.hip", 128, 130 << 10),     # a bitmap of 2^20 passage ids: one workgroup (16 waves) per CU
 }
 
 

@@ -125,6 +125,43 @@ def test_build_ivf_equals_oracle(pl, kw):
     assert torch.equal(goff, goff2) and torch.equal(gpids, gpids2)
 
 
+def test_build_ivf_long_lists_over_several_id_ranges(pl):
+    """More than 2^20 passages, two lists that hold a third of them each (sorted through the bitmap, one range of 2^20
+    ids at a time), the rest short (sorted by a wave), some of them empty."""
+    rng = np.random.default_rng(62)
+    P, C = 1_300_000, 5000
+    lengths = rng.integers(0, 3, size=P)
+    doc_offsets = np.zeros(P + 1, dtype=np.int64)
+    np.cumsum(lengths, out=doc_offsets[1:])
+    N = int(doc_offsets[-1])
+    codes = np.where(rng.random(N) < 0.5, rng.integers(0, 2, size=N), rng.integers(2, C - 100, size=N)).astype(np.int32)
+    off, pids = orc.build_ivf(codes, doc_offsets, C)
+    assert off[1] - off[0] > (1 << 18) and np.all(off[C - 100:] == off[C])
+    goff, gpids = pl.plaid_build_ivf(torch.from_numpy(codes).to(DEV), torch.from_numpy(doc_offsets).to(DEV), C)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(goff.cpu().numpy(), off)
+    np.testing.assert_array_equal(gpids.cpu().numpy(), pids)
+
+
+def test_build_ivf_with_two_million_centroids(pl):
+    """So many centroids that the counter tables get fewer stripes than the usual 64; one list is long."""
+    rng = np.random.default_rng(63)
+    P, C = 3000, (1 << 21) + 7
+    lengths = rng.integers(1, 7, size=P)
+    doc_offsets = np.zeros(P + 1, dtype=np.int64)
+    np.cumsum(lengths, out=doc_offsets[1:])
+    N = int(doc_offsets[-1])
+    codes = rng.integers(0, C, size=N).astype(np.int32)
+    codes[doc_offsets[:2500]] = 5                     # the first token of 2500 passages
+    codes[doc_offsets[:2500:2] + lengths[:2500:2] - 1] = 5   # and, in every other one, the last token too (counted once)
+    off, pids = orc.build_ivf(codes, doc_offsets, C)
+    assert off[6] - off[5] == 2500
+    goff, gpids = pl.plaid_build_ivf(torch.from_numpy(codes).to(DEV), torch.from_numpy(doc_offsets).to(DEV), C)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(goff.cpu().numpy(), off)
+    np.testing.assert_array_equal(gpids.cpu().numpy(), pids)
+
+
 def test_index_built_on_the_gpu_searches_like_the_oracle(pl):
     """Assignment, encoding and inverted lists on the GPU; the oracle searches an index made of those very arrays."""
     w = _workload(C=128, P=400, lo=1, hi=40, seed=59)
@@ -159,6 +196,11 @@ def test_index_build_argument_errors(pl):
         pl.plaid_build_ivf(bad, w.doc_offsets.to(DEV), 16)
     with pytest.raises(pl.PlaidError):
         pl.plaid_build_ivf(codes, w.doc_offsets.to(DEV)[:-1].contiguous(), 16)     # offsets do not end at N
+    back = w.doc_offsets.clone()
+    back[5] = back[3]                                   # passage 4 would end before it starts, passage 5 overlaps 3 and 4
+    if int(back[5]) < int(back[4]):
+        with pytest.raises(pl.PlaidError):
+            pl.plaid_build_ivf(codes, back.to(DEV), 16)
     with pytest.raises(pl.PlaidError):
         pl.plaid_encode_residuals(cen, x, codes, torch.zeros(7, device=DEV), 3)      # nbits must be 1 or 2
     with pytest.raises(ValueError):

@@ -745,19 +745,31 @@ __global__ __launch_bounds__(SEL_THREADS) void sel2_filter_kernel(const uint64_t
     }
 }
 
-// A boundary list longer than this goes through one digit pass (all workgroups of the query) before the finishing
+// A boundary list longer than this goes through a digit pass (all workgroups of the query) before the finishing
 // workgroup sorts what is left: far below what that workgroup could sort (SEL_SORT_CAP), because its sort is the one
-// serial step of the selection.
+// serial step of the selection.  Two such passes can be chained (LEVEL 1 reads the bin filter's list, LEVEL 2 the list
+// LEVEL 1 leaves): when a few distinct scores are shared by very many passages, the first digit falls into the score
+// bits and leaves one whole tie group, the second falls into the passage-id bits and leaves 2^-11 of it.
 #define SEL2_DIGIT_MIN 1024
+#define SEL2_SECOND_MIN_PASSAGES (1 << 19)  // indexes with more passages than this get the second digit pass
+template <int LEVEL>
+__device__ __forceinline__ int sel2_level_input(const Sel2State *s, int &m_rem)
+{
+    m_rem = LEVEL == 1 ? s->m_rem : s->m_rem1;
+    // (LEVEL 2 has work only when LEVEL 1 had: n_b1 is zero otherwise)
+    return LEVEL == 1 ? s->n_b : s->n_b1;
+}
+template <int LEVEL>
 __device__ __forceinline__ void sel2_digit_plan(const Sel2State *s, int &shift, int &width)
 {
-    const unsigned long long diff = s->b_or & s->b_nor;
+    const unsigned long long diff = LEVEL == 1 ? s->b_or & s->b_nor : s->b_or1 & s->b_nor1;
     const int hi = diff ? 63 - __clzll((long long)diff) : -1;
     width = hi + 1 < SEL_RADIX_BITS ? hi + 1 : SEL_RADIX_BITS;
     shift = hi + 1 - width;
 }
 
 // Digit histogram of an over-long boundary list (no-op otherwise).
+template <int LEVEL>
 __global__ __launch_bounds__(SEL_THREADS) void sel2_digit_hist_kernel(const uint64_t *__restrict__ blist,
                                                                       int64_t blist_stride, Sel2State *state,
                                                                       int32_t *__restrict__ hist1)
@@ -765,10 +777,11 @@ __global__ __launch_bounds__(SEL_THREADS) void sel2_digit_hist_kernel(const uint
     __shared__ int32_t lh[SEL_BINS];
     const int seg = blockIdx.y;
     Sel2State *s = state + seg;
-    const int n = s->n_b;
+    int m_rem;
+    const int n = sel2_level_input<LEVEL>(s, m_rem);
     if (n <= SEL2_DIGIT_MIN) return;
     int shift, width;
-    sel2_digit_plan(s, shift, width);
+    sel2_digit_plan<LEVEL>(s, shift, width);
     for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS) lh[b] = 0;
     __syncthreads();
     const uint64_t *k = blist + (int64_t)seg * blist_stride;
@@ -779,13 +792,14 @@ __global__ __launch_bounds__(SEL_THREADS) void sel2_digit_hist_kernel(const uint
     for (int b = threadIdx.x; b < SEL_BINS; b += SEL_THREADS)
         if (lh[b]) atomicAdd(&gh[b], lh[b]);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        s->shift1 = shift;
-        s->width1 = width;
+        if (LEVEL == 1) s->shift1 = shift, s->width1 = width;
+        else s->shift2 = shift, s->width2 = width;
     }
 }
 
 // Digit filter of an over-long boundary list (no-op otherwise): smaller digits are selected, the boundary digit
-// goes to blist1.
+// goes to blist1 (LEVEL 1 also records in which bits the keys it leaves differ, for LEVEL 2's plan).
+template <int LEVEL>
 __global__ __launch_bounds__(SEL_THREADS) void sel2_digit_filter_kernel(const uint64_t *__restrict__ blist,
                                                                         int64_t blist_stride, Sel2State *state,
                                                                         const int32_t *__restrict__ hist1,
@@ -797,19 +811,24 @@ __global__ __launch_bounds__(SEL_THREADS) void sel2_digit_filter_kernel(const ui
     __shared__ int32_t res[2];
     const int seg = blockIdx.y;
     Sel2State *s = state + seg;
-    const int n = s->n_b;
+    int32_t m_rem;
+    const int n = sel2_level_input<LEVEL>(s, m_rem);
     if (n <= SEL2_DIGIT_MIN) return;
     int shift, width;
-    sel2_digit_plan(s, shift, width);
-    const int32_t m_rem = s->m_rem;
+    sel2_digit_plan<LEVEL>(s, shift, width);
     int bstar, before;
     find_boundary(hist1 + (int64_t)seg * SEL_BINS, m_rem, scan, res, bstar, before);
-    if (blockIdx.x == 0 && threadIdx.x == 0) s->m_rem1 = m_rem - before;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (LEVEL == 1) s->m_rem1 = m_rem - before;
+        else s->m_rem2 = m_rem - before;
+    }
+    int32_t *n_left = LEVEL == 1 ? &s->n_b1 : &s->n_b2;
     const uint64_t *k = blist + (int64_t)seg * blist_stride;
     uint64_t *my_out = out + (int64_t)seg * out_stride;
     uint64_t *my_bl = blist1 + (int64_t)seg * blist1_stride;
     const int lane = threadIdx.x & 63;
     const int64_t n_round = ((int64_t)n + 63) & ~63ll;
+    unsigned long long o = 0, no = 0;
     for (int64_t i = (int64_t)blockIdx.x * SEL_THREADS + threadIdx.x; i < n_round; i += (int64_t)gridDim.x * SEL_THREADS) {
         uint64_t key = 0;
         int cls = 2;
@@ -823,12 +842,26 @@ __global__ __launch_bounds__(SEL_THREADS) void sel2_digit_filter_kernel(const ui
         int base0 = 0, base1 = 0;
         if (lane == 0) {
             if (b0) base0 = atomicAdd(&s->n_sure, __popcll(b0));
-            if (b1) base1 = atomicAdd(&s->n_b1, __popcll(b1));
+            if (b1) base1 = atomicAdd(n_left, __popcll(b1));
         }
         base0 = __shfl(base0, 0);
         base1 = __shfl(base1, 0);
         if (cls == 0) my_out[base0 + __popcll(b0 & below)] = key;
-        if (cls == 1) my_bl[base1 + __popcll(b1 & below)] = key;
+        if (cls == 1) {
+            my_bl[base1 + __popcll(b1 & below)] = key;
+            o |= key;
+            no |= ~key;
+        }
+    }
+    if (LEVEL == 1) {
+        for (int d = 1; d < 64; d <<= 1) {
+            o |= __shfl_xor(o, d);
+            no |= __shfl_xor(no, d);
+        }
+        if (lane == 0 && (o | no)) {
+            atomicOr(&s->b_or1, o);
+            atomicOr(&s->b_nor1, no);
+        }
     }
 }
 
@@ -837,7 +870,7 @@ __global__ __launch_bounds__(FIN_THREADS) void sel2_finish_kernel(const uint64_t
                                                                   const uint64_t *__restrict__ blist1,
                                                                   int64_t blist1_stride, const Sel2State *state,
                                                                   const uint32_t *__restrict__ emptybits,
-                                                                  int64_t cand_words, int64_t P, int32_t m,
+                                                                  int64_t cand_words, int64_t P, int32_t m, int levels,
                                                                   uint64_t *__restrict__ out, int64_t out_stride,
                                                                   int32_t *__restrict__ out_counts)
 {
@@ -846,12 +879,15 @@ __global__ __launch_bounds__(FIN_THREADS) void sel2_finish_kernel(const uint64_t
     __shared__ int32_t sh[4];
     const int seg = blockIdx.x;
     const Sel2State *s = state + seg;
-    const bool two = s->n_b > SEL2_DIGIT_MIN;
-    const uint64_t *bl = two ? blist1 + (int64_t)seg * blist1_stride : blist + (int64_t)seg * blist_stride;
-    const int nb = two ? s->n_b1 : s->n_b;
-    const int m_rem = two ? s->m_rem1 : s->m_rem;
+    // how many digit filters this query's boundary list went through (levels: how many were launched); the second one
+    // writes where the first one read
+    const int done = (levels >= 1 && s->n_b > SEL2_DIGIT_MIN) ? ((levels >= 2 && s->n_b1 > SEL2_DIGIT_MIN) ? 2 : 1) : 0;
+    const uint64_t *bl = done == 1 ? blist1 + (int64_t)seg * blist1_stride : blist + (int64_t)seg * blist_stride;
+    const int nb = done == 2 ? s->n_b2 : (done == 1 ? s->n_b1 : s->n_b);
+    const int m_rem = done == 2 ? s->m_rem2 : (done == 1 ? s->m_rem1 : s->m_rem);
     const int n_sure = s->n_sure;
-    const int top_bit = two ? s->shift1 : 64;  // boundary keys agree on every bit at or above this position
+    // boundary keys agree on every bit at or above this position
+    const int top_bit = done == 2 ? s->shift2 : (done == 1 ? s->shift1 : 64);
     uint64_t *o = out + (int64_t)seg * out_stride;
     int total = n_sure + m_rem;
 
@@ -978,12 +1014,21 @@ void plaid_launch_select2(hipStream_t st, uint64_t *keys2, int64_t key_stride, c
     const int gx = blocks_for(P, nq);
     hipLaunchKernelGGL(sel2_filter_kernel, dim3(gx, nq), dim3(SEL_THREADS), 0, st, keys2, key_stride, candbits, cand_words, P,
                        m, b.meta, b.hist, b.state, out, out_stride, b.blist, P);
-    if (P > SEL2_DIGIT_MIN) {
-        // only a boundary bin longer than SEL2_DIGIT_MIN makes these two do anything; keys2 serves as blist1
-        hipLaunchKernelGGL(sel2_digit_hist_kernel, dim3(gx, nq), dim3(SEL_THREADS), 0, st, b.blist, P, b.state, b.hist1);
-        hipLaunchKernelGGL(sel2_digit_filter_kernel, dim3(gx, nq), dim3(SEL_THREADS), 0, st, b.blist, P, b.state, b.hist1,
+    // Digit filters: only a boundary list longer than SEL2_DIGIT_MIN makes them do anything.  The second pair is worth its
+    // two launches for large indexes (a tie group can be as long as the index) in launches of several queries; otherwise
+    // the query's finishing workgroup handles a long remainder alone (same result).  keys2 serves as the first
+    // filter's output list, b.blist (its input) as the second one's.
+    const int levels = P > SEL2_DIGIT_MIN ? ((nq >= 8 && P > SEL2_SECOND_MIN_PASSAGES) ? 2 : 1) : 0;
+    if (levels >= 1) {
+        hipLaunchKernelGGL(sel2_digit_hist_kernel<1>, dim3(gx, nq), dim3(SEL_THREADS), 0, st, b.blist, P, b.state, b.hist1);
+        hipLaunchKernelGGL(sel2_digit_filter_kernel<1>, dim3(gx, nq), dim3(SEL_THREADS), 0, st, b.blist, P, b.state, b.hist1,
                            out, out_stride, keys2, key_stride);
     }
+    if (levels >= 2) {
+        hipLaunchKernelGGL(sel2_digit_hist_kernel<2>, dim3(gx, nq), dim3(SEL_THREADS), 0, st, keys2, key_stride, b.state, b.hist2);
+        hipLaunchKernelGGL(sel2_digit_filter_kernel<2>, dim3(gx, nq), dim3(SEL_THREADS), 0, st, keys2, key_stride, b.state,
+                           b.hist2, out, out_stride, b.blist, P);
+    }
     hipLaunchKernelGGL(sel2_finish_kernel, dim3(nq), dim3(FIN_THREADS), 0, st, b.blist, P, keys2, key_stride, b.state,
-                       b.emptybits, cand_words, P, m, out, out_stride, out_counts);
+                       b.emptybits, cand_words, P, m, levels, out, out_stride, out_counts);
 }

@@ -560,7 +560,7 @@ struct Workspace {
     char *zero_base;
     size_t zero_bytes;
     uint32_t *candbits;  // [qc][cand_words]
-    Stage2Buffers s2;    // n_ne, hist, hist1, state live in the zeroed region
+    Stage2Buffers s2;    // n_ne, hist, hist1, hist2, state live in the zeroed region
     void *sel3_zero, *sel4_zero;
     // everything else
     double *Qd;          // [qc][128][32]
@@ -622,6 +622,7 @@ static Workspace carve(char *base, const plaid_index *ix, int qc, const Plan &pl
     w.candbits = (uint32_t *)take((size_t)qc * w.cand_words * 4);
     w.s2.hist = (int32_t *)take((size_t)qc * SEL_BINS * 4);
     w.s2.hist1 = (int32_t *)take((size_t)qc * SEL_BINS * 4);
+    w.s2.hist2 = (int32_t *)take((size_t)qc * SEL_BINS * 4);
     w.s2.state = (Sel2State *)take((size_t)qc * sizeof(Sel2State));
     w.s2.qcount = (int32_t *)take(4 * sizeof(int32_t));
     w.sel3_zero = take(plaid_select_zero_bytes(qc));

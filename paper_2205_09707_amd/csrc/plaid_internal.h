@@ -162,16 +162,20 @@ struct S2Meta {        // per query
 
 // Per-query state of the stage-2 selection (device memory, 64 bytes, zeroed before each use).
 struct Sel2State {
-    unsigned long long b_or, b_nor;  // OR over the boundary keys / over their complements
-    int32_t n_sure;                  // keys already written to the output
-    int32_t n_b;                     // boundary list after the bin filter
-    int32_t m_rem;                   // keys still to take from it
-    int32_t n_b1;                    // boundary list after the digit filter (only when n_b > SEL_SORT_CAP)
+    unsigned long long b_or, b_nor;    // OR over the boundary keys / over their complements
+    unsigned long long b_or1, b_nor1;  // the same over the list the first digit filter leaves
+    int32_t n_sure;                    // keys already written to the output
+    int32_t n_b;                       // boundary list after the bin filter
+    int32_t m_rem;                     // keys still to take from it
+    int32_t n_b1;                      // boundary list after the first digit filter (only when n_b > SEL2_DIGIT_MIN)
     int32_t m_rem1;
-    int32_t shift1, width1;          // digit examined by the digit filter
-    int32_t pad[5];
+    int32_t shift1, width1;            // digit examined by the first digit filter
+    int32_t n_b2;                      // ... after the second one (only when it is launched and n_b1 > SEL2_DIGIT_MIN)
+    int32_t m_rem2;
+    int32_t shift2, width2;
+    int32_t pad[13];
 };
-static_assert(sizeof(Sel2State) == 64, "Sel2State is a 64-byte record");
+static_assert(sizeof(Sel2State) == 128, "Sel2State is a 128-byte record");
 
 // Bin of a finite pruned score: 0 for the best scores, SEL_BINS-1 for the worst.  Monotone in the score, so bins
 // never contradict the ranking; producer and selection call this same function on the same inputs.
@@ -186,6 +190,7 @@ struct Stage2Buffers {   // all device pointers, leading dimension = query of th
     // zeroed before each chunk
     int32_t *hist;       // [nq][SEL_BINS]  bin histogram of the valid keys
     int32_t *hist1;      // [nq][SEL_BINS]  digit histogram of an over-long boundary list
+    int32_t *hist2;      // [nq][SEL_BINS]  ... of the list the first digit filter leaves, when that is over-long too
     Sel2State *state;    // [nq]
     int32_t *qcount;     // [3] queries of the chunk with no / 1..31 / more surviving centroids (null: not recorded)
     // no initialisation needed

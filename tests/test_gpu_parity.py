@@ -220,6 +220,50 @@ def test_rare_paths(pl, name, cfgkw, params, forms):
         _check_workload(pl, w, params, stage2=stage2)
 
 
+def test_two_long_tie_groups_in_one_score_bin(pl):
+    """Two nearly equal centroids, each the only one of some 240 000 passages: two pruned scores that differ in their
+    last bits, so both tie groups land in one bin of the stage-2 histogram and the ndocs cut falls inside the second.
+    In a launch of nine queries on an index of more than 2^19 passages the boundary list then passes two digit filters
+    (score bits, then passage-id bits)."""
+    rng = np.random.default_rng(71)
+    P, nq = 600000, 9
+    c0 = rng.standard_normal(128)
+    c0 /= np.linalg.norm(c0)
+    c1 = c0 + 5e-5 * rng.standard_normal(128)
+    c1 /= np.linalg.norm(c1)
+    c2 = rng.standard_normal(128)
+    c2 /= np.linalg.norm(c2)
+    centroids = np.stack([c0, c1, c2]).astype(np.float32)
+    kind = rng.integers(0, 10, size=P)               # 4 in 10 hold centroid 0 only, 4 in 10 centroid 1 only, the rest more
+    lengths = np.where(kind < 8, 1, 2)
+    doc_offsets = np.zeros(P + 1, dtype=np.int64)
+    np.cumsum(lengths, out=doc_offsets[1:])
+    N = int(doc_offsets[-1])
+    codes = np.zeros(N, dtype=np.int32)
+    first = doc_offsets[:-1]
+    codes[first] = np.where(kind < 4, 0, np.where(kind < 8, 1, 2))
+    two = np.nonzero(lengths == 2)[0]
+    codes[first[two] + 1] = rng.integers(0, 2, size=len(two))
+    residuals = rng.integers(0, 256, size=(N, 32), dtype=np.uint8)
+    weights = np.array([-0.03, -0.01, 0.01, 0.03], dtype=np.float32)
+    ivf_offsets, ivf_pids = orc.build_ivf(codes, doc_offsets, 3)
+    arrays = dict(centroids=centroids, doc_offsets=doc_offsets, codes=codes, residuals=residuals, bucket_weights=weights,
+                  ivf_offsets=ivf_offsets, ivf_pids=ivf_pids)
+    Q = c0[None, None, :] + 0.3 * rng.standard_normal((nq, 32, 128))
+    Q = (Q / np.linalg.norm(Q, axis=2, keepdims=True)).astype(np.float32)
+    ix = orc.Index(arrays, 2)
+    gidx = pl.plaid_index_from_view({k: torch.from_numpy(v).to("cuda:0") for k, v in arrays.items()}, 2, device=0, copy=True)
+    try:
+        Qdev = torch.from_numpy(Q).to("cuda:0")
+        for params in [(1, -np.inf, 300000, 10), (3, 0.3, 400000, 5)]:
+            out = pu.run_gpu_debug(pl, gidx, Qdev, params)
+            for q in (0, 4, 8):
+                pu.compare_query(ix, Q[q], params, pu.slice_query(out, q), ctx=f"tie bins {params} q{q}",
+                                 approx=pu.is_approx(pl, gidx, params))
+    finally:
+        pl.plaid_index_free(gidx)
+
+
 @pytest.mark.parametrize("form", ["split16", "matrix", "vector"])
 def test_all_zero_query_token(pl, form):
     """A query token of zeros scores 0 against every centroid: all tiles of the score kernel tie on their column

@@ -840,39 +840,37 @@ __global__ __launch_bounds__(IVR_THREADS(SHIFT)) void s2_invert_kernel(
     if (slots) s2_stage_tables(q, K, hsh, kept_ids, T, htab, Tl, rowsum);
     else __syncthreads();
 
-    // probed lists: candidate bit, plus the slot bit when the centroid also survives
-    const int nu = n_uniq[q];
-    for (int u0 = 0; u0 < nu; u0 += IVR_LISTS) {
-        const int nb = nu - u0 < IVR_LISTS ? nu - u0 : IVR_LISTS;
-        int cnt = 0;
-        int64_t first = 0;
+    // The lists to apply, in one index space: the probed centroids' (candidate bit, plus the slot bit when the centroid
+    // also survives), then the surviving centroids' that were not probed (slot bit only).  A round takes IVR_LISTS of
+    // them: the centroid ids are fetched first, the slots of the probed ones marked in LDS, and only then -- one
+    // barrier later, which by then costs no memory round trip -- do all lists of the round look up their stretch of
+    // the range together.  (A surviving centroid's round comes after every probed centroid's mark.)
+    const int nu = n_uniq[q], ntot = nu + (slots ? K : 0);
+    for (int u0 = 0; u0 < ntot; u0 += IVR_LISTS) {
+        const int e = u0 + tid;
+        const bool mine = tid < IVR_LISTS && e < ntot, survivor = mine && e >= nu;
+        int32_t c = -1;
+        if (mine) c = survivor ? kept_ids[(int64_t)q * S2_MAX_KEPT + e - nu] : uniq[(int64_t)q * uniq_stride + e];
         unsigned long long val = 0;
-        if (tid < nb) {
-            const int32_t c = uniq[(int64_t)q * uniq_stride + u0 + tid];
+        if (mine && !survivor) {
             const uint32_t sl = slots ? s2_lookup(htab, (uint32_t)c, hsh) : 0u;
             val = 1ull | (sl ? 1ull << sl : 0ull);
             if (sl) atomicOr(&slot_probed[sl >> 5], 1u << (sl & 31));
+        }
+        __syncthreads();
+        if (survivor) {
+            const int sl = e - nu + 1;
+            val = 1ull << sl;
+            if ((slot_probed[sl >> 5] >> (sl & 31)) & 1u) c = -1;  // already applied with its probed list
+        }
+        int cnt = 0;
+        int64_t first = 0;
+        if (c >= 0) {
             const uint32_t a = table[(int64_t)c * (nr + 1) + r], b = table[(int64_t)c * (nr + 1) + r + 1];
             first = ivf_offsets[c] + a;
             cnt = b > a ? (int)(b - a) : 0;
         }
         ivr_apply_round(cnt, first, val, ivf_pids, r0, (uint32_t)RANGE, lsets, scratch.lists);
-    }
-    // surviving centroids that were not probed: slot bit only
-    if (slots) {
-        int cnt = 0;
-        int64_t first = 0;
-        if (tid < K) {
-            const int sl = tid + 1;
-            const bool seen = (slot_probed[sl >> 5] >> (sl & 31)) & 1u;
-            if (!seen) {
-                const int32_t c = kept_ids[(int64_t)q * S2_MAX_KEPT + tid];
-                const uint32_t a = table[(int64_t)c * (nr + 1) + r], b = table[(int64_t)c * (nr + 1) + r + 1];
-                first = ivf_offsets[c] + a;
-                cnt = b > a ? (int)(b - a) : 0;
-            }
-        }
-        ivr_apply_round(cnt, first, 1ull << ((tid & 63) + 1), ivf_pids, r0, (uint32_t)RANGE, lsets, scratch.lists);
     }
 
     const int64_t w_first = (int64_t)r0 >> 5;  // first bitmap word of the range

@@ -182,7 +182,8 @@ int plaid_index_info(const plaid_index *idx, int64_t *num_centroids, int64_t *nu
  *      completed in double wherever that bound leaves it open, and the rows of the surviving centroids that stage 2
  *      scores with are re-evaluated in double, so probes, candidates, the pruning map and the stage-2 scores of
  *      queries with at most 63 surviving centroids are those of forms 0 and 1; stage-3 and final scores inherit the
- *      bound (32 entries per score).  Serves nprobe <= 8; a search with a larger nprobe runs form 1 (or 0).
+ *      bound (32 entries per score).  Serves nprobe <= 8; a search with a larger nprobe runs form 1 (or 0).  Needs
+ *      centroid components below 32 in magnitude: an index whose table exceeds that is given form 1 (or 0) instead.
  *   1  the double-precision matrix instruction, 0  a vector fused-multiply-add chain: both accumulate each score in
  *      double over the dimensions in index order and round once, the definition's bits.  Form 1 is used only when a
  *      check run on the device at the first index creation of the process confirms that the instruction adds its

@@ -305,7 +305,28 @@ __global__ __launch_bounds__(H16_THREADS, NT == 2 ? 2 : 4) void scq16_kernel(
         scq16_body<NT, STORE, false>(Bs, nvalid, A16, C, B16, q_begin, q_end, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax);
 }
 
+// max_bits[0] = bit pattern of the largest |value| among n values (a value that is not a number counts as infinite;
+// bit patterns of non-negative floats order like the floats).  Zero on entry.
+__global__ __launch_bounds__(256) void scq16_max_abs_kernel(const float *__restrict__ x, int64_t n, uint32_t *__restrict__ max_bits)
+{
+    float m = 0.f;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const float a = fabsf(x[i]);
+        m = a == a ? fmaxf(m, a) : INFINITY;
+    }
+    for (int d = 1; d < 64; d <<= 1) m = fmaxf(m, __shfl_xor(m, d));
+    if ((threadIdx.x & 63) == 0 && m > 0.f) atomicMax(max_bits, __float_as_uint(m));
+}
+
 // ------------------------------------------------------------------ host side
+void plaid_launch_scq16_max_abs(hipStream_t st, const float *x, int64_t n, uint32_t *max_bits)
+{
+    int64_t g = (n + 255) / 256;
+    if (g > 2048) g = 2048;
+    if (g < 1) g = 1;
+    hipLaunchKernelGGL(scq16_max_abs_kernel, dim3((unsigned)g), dim3(256), 0, st, x, n, max_bits);
+}
+
 size_t plaid_scq16_centroid_bytes(int64_t C)
 {
     const int64_t tiles = ((C + 32 * H16_WG_TILES - 1) / (32 * H16_WG_TILES)) * H16_WG_TILES;

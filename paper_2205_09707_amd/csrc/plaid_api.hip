@@ -142,10 +142,45 @@ static int choose_scq_form(plaid_index *ix)
     return PLAID_OK;
 }
 
+struct TempAlloc {  // device memory released when the call returns
+    void *p = nullptr;
+    ~TempAlloc()
+    {
+        if (p) (void)hipFree(p);
+    }
+};
+
+// The split kernel scales the centroids' leading fp16 terms by 2^11: a table with a component of 32 or more (or one that
+// is not a number) cannot use it.  Such an index (ix->scq_form is PLAID_SCQ_SPLIT16 on entry) gets a double-precision
+// form instead, unless the caller insisted on the split form, which is then an error.  Synchronises the stream.
+static int scq16_check_centroids(plaid_index *ix, const float *centroids, int64_t C, hipStream_t st)
+{
+    TempAlloc mb;
+    if (hipMalloc(&mb.p, 256) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(PLAID_ENOMEM, "hipMalloc(256) failed");
+    }
+    HIP_TRY(hipMemsetAsync(mb.p, 0, 256, st));
+    plaid_launch_scq16_max_abs(st, centroids, C * DIM, (uint32_t *)mb.p);
+    HIP_TRY(hipGetLastError());
+    float largest = 0.f;
+    HIP_TRY(hipMemcpyAsync(&largest, mb.p, 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (largest <= PLAID_SCQ16_CENTROID_MAX) return PLAID_OK;
+    const char *env = getenv("PLAID_SCQ_FORM");
+    if (env && !strcmp(env, "split16"))
+        return fail(PLAID_EINVAL, "PLAID_SCQ_FORM=split16 needs centroid components within %g (largest: %g)",
+                    (double)PLAID_SCQ16_CENTROID_MAX, (double)largest);
+    ix->scq_form = ix->scq_matrix_form ? PLAID_SCQ_MATRIX : PLAID_SCQ_VECTOR;
+    return PLAID_OK;
+}
+
 // Operand form of the centroid table for the split-fp16 score kernel (512 bytes per centroid, built once).
 static int build_scq16_operands(plaid_index *ix)
 {
     if (ix->scq_form != PLAID_SCQ_SPLIT16) return PLAID_OK;
+    int rc = scq16_check_centroids(ix, ix->centroids, ix->C, nullptr);
+    if (rc || ix->scq_form != PLAID_SCQ_SPLIT16) return rc;
     const size_t bytes = plaid_scq16_centroid_bytes(ix->C);
     void *d = nullptr;
     if (hipMalloc(&d, bytes) != hipSuccess) {
@@ -1002,14 +1037,6 @@ extern "C" int plaid_workspace_bytes(int64_t C, int64_t P, int32_t nq, int32_t n
 }
 
 // ------------------------------------------------------------------ index construction
-struct TempAlloc {  // device memory released when the call returns
-    void *p = nullptr;
-    ~TempAlloc()
-    {
-        if (p) (void)hipFree(p);
-    }
-};
-
 extern "C" int plaid_assign_centroids(const float *centroids, int64_t C, const float *x, int64_t n, int32_t *codes, int device,
                                       void *hip_stream)
 {
@@ -1028,6 +1055,10 @@ extern "C" int plaid_assign_centroids(const float *centroids, int64_t C, const f
     fake.P = 1;
     int rc = choose_scq_form(&fake);
     if (rc) return rc;
+    if (fake.scq_form == PLAID_SCQ_SPLIT16) {
+        rc = scq16_check_centroids(&fake, centroids, C, st);
+        if (rc) return rc;
+    }
     TempAlloc a16;
     if (fake.scq_form == PLAID_SCQ_SPLIT16) {
         const size_t ab = plaid_scq16_centroid_bytes(C);

@@ -128,6 +128,10 @@ size_t plaid_stage1_tilemax_bytes(int64_t C, int nq, int nprobe);
 // vectors of norm <= 1 (components within fp16's range); keepbits holds the rows that pass Eq. 5 even if every entry
 // were that much lower, ambbits the rows whose test the bound leaves open (decided in double by the probe kernel).
 #define PLAID_SCQ16_EPS 3.0517578125e-05f  // 2^-15
+// The kernel forms 2^11 a1 in fp16 on the centroid side: components must stay below this magnitude.
+#define PLAID_SCQ16_CENTROID_MAX 31.0f
+// max_bits[0] (zero on entry) = bit pattern of the largest |x[i]|, infinity's when a value is not a number.
+void plaid_launch_scq16_max_abs(hipStream_t st, const float *x, int64_t n, uint32_t *max_bits);
 size_t plaid_scq16_centroid_bytes(int64_t C);  // operand form of the centroid table, built once per index
 size_t plaid_scq16_query_bytes(int nq);        // operand form of nq queries
 void plaid_launch_scq16_split_centroids(hipStream_t st, const float *centroids, int64_t C, void *A16);

@@ -128,6 +128,33 @@ def test_default_kernel_forms(pl):
         pl.plaid_index_free(gidx)
 
 
+def test_large_centroid_components_get_a_double_precision_score_kernel(pl):
+    """The split-fp16 kernel scales the centroids' leading terms by 2^11 in fp16: a table with a component of 32 or more
+    is given the double-precision matrix kernel instead (and searches like the oracle); insisting on the split form
+    for such a table is an error."""
+    w = make_workload(tiny_config(C=64, P=300, lo=2, hi=20, nbits=2, nq=3, seed=72), device="cpu", noise="calibrated")
+    arrays = pu.device_arrays(w)
+    # one more centroid, in no passage (so the final scores keep their usual size): a unit vector times 400
+    big = 400.0 * arrays["centroids"][5:6]
+    arrays["centroids"] = torch.cat([arrays["centroids"], big]).contiguous()
+    arrays["ivf_offsets"] = torch.cat([arrays["ivf_offsets"], arrays["ivf_offsets"][-1:]]).contiguous()
+    assert float(arrays["centroids"].abs().max()) > 32.0
+    with _kernel_forms(None, None):
+        gidx = pl.plaid_index_from_view(arrays, w.cfg.nbits, device=0, copy=True)
+    try:
+        assert pl.plaid_get_score_kernel(gidx) == 1
+        ix = orc.Index({k: v.cpu().numpy() for k, v in arrays.items()}, w.cfg.nbits)
+        params = (2, 0.45, 64, 10)
+        out = pu.run_gpu_debug(pl, gidx, w.queries.to("cuda:0"), params)
+        for q in range(3):
+            pu.compare_query(ix, w.queries[q].numpy(), params, pu.slice_query(out, q), ctx=f"large centroid q{q}", approx=False)
+    finally:
+        pl.plaid_index_free(gidx)
+    with _kernel_forms("split16", None):
+        with pytest.raises(pl.PlaidError):
+            pl.plaid_index_from_view(arrays, w.cfg.nbits, device=0, copy=True)
+
+
 def test_pipeline_equals_exhaustive_when_nothing_is_filtered(pl):
     """nprobe = C, t_cs = -inf, ndocs >= 4P: every passage reaches stage 4, so the library's result must be the
     exhaustive MaxSim ranking (ndocs = 4P because stage 3 keeps ndocs/4)."""

@@ -158,6 +158,10 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
     qps = nq * args.steps / dt
     stage_ms = {s: v / args.steps for s, v in stage_acc.items()}
     log(f"[bench] batch of {nq}: {ms_per_step:.3f} ms/step, {qps:.0f} queries/s; stage ms/step {stage_ms}")
+    # shader-clock and 100 MHz timer ticks of the score kernel's workgroups in the last timed step (read outside the timed
+    # region: the call copies from the device)
+    clock_ticks = pl.plaid_get_score_kernel_clocks(idx)
+    scq_clock_mhz = round(100.0 * clock_ticks[0] / clock_ticks[1], 0) if clock_ticks[1] else None
     pl.plaid_set_stage_timing(idx, False)
 
     # ---- batch-1 latency: one query per call, host clock around call + stream sync
@@ -256,7 +260,10 @@ def measure(pl, torch, np, cfg, noise, args, latency=True):
                 {"algorithmic_bytes_per_step": scq_bytes, "algorithmic_bytes_per_launch": scq_bytes // launches, "dtype": "f16x2/f32",
                  "matrix_flop_per_step": 3 * scq_flop,
                  "fp16_mfma_tflops": round(3 * scq_flop / t_scq / 1e12, 1) if t_scq > 0 else None,
-                 "fp16_mfma_frac": round(3 * scq_flop / t_scq / 1e12 / FP16_MFMA_PEAK_TFLOPS, 4) if t_scq > 0 else None})
+                 "fp16_mfma_frac": round(3 * scq_flop / t_scq / 1e12 / FP16_MFMA_PEAK_TFLOPS, 4) if t_scq > 0 else None,
+                 # the clock the chip held while this kernel ran (shader-clock counter over the 100 MHz timer, read inside
+                 # the kernel by every workgroup): the published peaks are quoted at the top clock
+                 "shader_clock_mhz_during_kernel": scq_clock_mhz})
         else:
             rooflines["scq"] = entry(
                 "scq", "S_cq = C.Q^T (Eq. 2) in double through the fp64 matrix instruction" if form == 1

@@ -212,6 +212,13 @@ int plaid_get_stage2_kernel(const plaid_index *idx, int32_t *form);
 int plaid_set_stage_timing(plaid_index *idx, int32_t on);
 int plaid_get_stage_ms(const plaid_index *idx, float *out_ms);
 
+/* The clock the chip held while the S_cq kernel (Eq. 2; score kernel 2 of plaid_get_score_kernel only) of the most
+ * recent plaid_search with stage timing on was running: HOST out_ticks[2] = how far the shader-clock counter
+ * (out_ticks[0]) and the fixed-rate 100 MHz timer (out_ticks[1]) moved, each summed over the kernel's workgroups;
+ * 100 * out_ticks[0] / out_ticks[1] is the shader clock in MHz.  Both are 0 when nothing was measured.  Synchronises
+ * the device.  A diagnostic, like the stage times: the published peak rates assume the chip's top clock. */
+int plaid_get_score_kernel_clocks(const plaid_index *idx, uint64_t *out_ticks);
+
 /* Storage variant (Section 4.5 reconstructs the stored embedding and is silent on its length; the embeddings that were
  * stored have unit length, Section 3.1, the reconstruction centroid + residual does not): on != 0 makes every later
  * plaid_search / plaid_search_debug / plaid_search_static on this index score, and plaid_decompress_passages return,

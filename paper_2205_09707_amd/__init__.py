@@ -13,6 +13,7 @@ from .plaid import (  # noqa: F401
     plaid_decompress_passages,
     plaid_encode_residuals,
     plaid_get_score_kernel,
+    plaid_get_score_kernel_clocks,
     plaid_index_set_renormalize,
     plaid_get_stage2_kernel,
     plaid_get_stage_ms,

@@ -979,7 +979,8 @@ __global__ __launch_bounds__(TAIL_THREADS) void stage1_tail_kernel(const float *
 // np = capacity of the tail's lists (1, 2, 4 or 8 >= nprobe); np = 0: scores and pruning bits only (large nprobe).
 static void launch_fused(hipStream_t st, int phases, int np, const float *centroids, int64_t C, const float *Q, const void *Qx,
                          int form, const void *A16, int nq, float t_cs, float *S, uint32_t *keepbits, uint32_t *ambbits,
-                         int64_t keep_words, float *tilemax, int nprobe, const Stage1Out &o, uint32_t *zero, int64_t zero_words)
+                         int64_t keep_words, float *tilemax, int nprobe, const Stage1Out &o, uint32_t *zero, int64_t zero_words,
+                         unsigned long long *score_clocks)
 {
     const bool matrix_form = form == PLAID_SCQ_MATRIX;
     const int tile_rows = form == PLAID_SCQ_VECTOR ? SCQ_ROWS : SM_WROWS;  // rows per tile of column maxima
@@ -990,7 +991,7 @@ static void launch_fused(hipStream_t st, int phases, int np, const float *centro
     static_assert(SM_WROWS == 32, "the split-fp16 kernel emits column maxima per 32 rows, like the matrix form");
     if (!(phases & PLAID_STAGE1_SCORES)) {
     } else if (form == PLAID_SCQ_SPLIT16) {
-        plaid_launch_scq16(st, A16, C, Qx, nq, t_cs, S, keepbits, ambbits, keep_words, tmx);
+        plaid_launch_scq16(st, A16, C, Qx, nq, t_cs, S, keepbits, ambbits, keep_words, tmx, score_clocks);
     } else if (matrix_form) {
         if (nq == 1)
             hipLaunchKernelGGL(scq_mfma_kernel<1>, dim3(1, nblk), dim3(SM_THREADS), 0, st, centroids, C, Q, nq, t_cs, S, keepbits,
@@ -1039,7 +1040,7 @@ void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int
                          const void *A16, int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, uint32_t *ambbits,
                          int64_t keep_words, float *tilemax, uint32_t *zero, int64_t zero_words, int32_t *probed,
                          int32_t *uniq, int uniq_stride, int32_t *n_uniq, const Stage2Buffers &s2, void *probe_scratch,
-                         size_t probe_scratch_bytes)
+                         size_t probe_scratch_bytes, unsigned long long *score_clocks)
 {
     if ((phases & PLAID_STAGE1_PREP) && form == PLAID_SCQ_SPLIT16) plaid_launch_scq16_split_queries(st, Q, nq, Qd, zero, zero_words);
     if ((phases & PLAID_STAGE1_PREP) && form == PLAID_SCQ_VECTOR) {
@@ -1064,11 +1065,11 @@ void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int
     const int np = nprobe == 1 ? 1 : (nprobe == 2 ? 2 : (nprobe <= 4 ? 4 : (nprobe <= PLAID_PROBE_FAST_MAX ? 8 : 0)));
     if (np > 0)
         launch_fused(st, phases, np, centroids, C, Q, Qd, form, A16, nq, t_cs, S, keepbits, ambbits, keep_words, tilemax, nprobe,
-                     o, zero, zero_words);
+                     o, zero, zero_words, score_clocks);
     else {
         // large nprobe: scores and pruning bits here, probes through the generic selection, survivor table after it
         launch_fused(st, phases, 0, centroids, C, Q, Qd, form, A16, nq, t_cs, S, keepbits, ambbits, keep_words, tilemax, nprobe,
-                     o, zero, zero_words);
+                     o, zero, zero_words, score_clocks);
         if (phases & PLAID_STAGE1_PROBES) {
             plaid_launch_top_nprobe_general(st, S, C, nq, nprobe, probed, uniq, uniq_stride, n_uniq, probe_scratch,
                                             probe_scratch_bytes);

@@ -284,9 +284,12 @@ template <int NT, bool STORE>
 __global__ __launch_bounds__(H16_THREADS, NT == 2 ? 2 : 4) void scq16_kernel(
     const scq16_half8 *__restrict__ A16, int64_t C, const scq16_half8 *__restrict__ B16, int nq, int qg, float t_lo, float t_hi,
     float *__restrict__ S, uint32_t *__restrict__ keepbits, uint32_t *__restrict__ ambbits, int64_t keep_words,
-    float *__restrict__ tilemax)
+    float *__restrict__ tilemax, unsigned long long *__restrict__ clocks)
 {
     __shared__ scq16_half8 Bs[2][H16_TILE_VEC];
+    // clocks (may be null): every workgroup adds how far the shader-clock counter and the fixed-rate (100 MHz) timer moved
+    // while it ran -- the ratio of the two sums is the clock the chip held during this kernel
+    const long long sc0 = clocks ? clock64() : 0, rt0 = clocks ? wall_clock64() : 0;
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
     const int64_t tile0 = ((int64_t)blockIdx.x * H16_WAVES + wave) * NT;
     const int q_begin = blockIdx.y * qg, q_end = q_begin + qg < nq ? q_begin + qg : nq;
@@ -303,6 +306,10 @@ __global__ __launch_bounds__(H16_THREADS, NT == 2 ? 2 : 4) void scq16_kernel(
         scq16_body<NT, STORE, true>(Bs, nvalid, A16, C, B16, q_begin, q_end, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax);
     else
         scq16_body<NT, STORE, false>(Bs, nvalid, A16, C, B16, q_begin, q_end, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax);
+    if (clocks && threadIdx.x == 0) {
+        atomicAdd(&clocks[0], (unsigned long long)(clock64() - sc0));
+        atomicAdd(&clocks[1], (unsigned long long)(wall_clock64() - rt0));
+    }
 }
 
 // max_bits[0] = bit pattern of the largest |value| among n values (a value that is not a number counts as infinite;
@@ -355,7 +362,7 @@ void plaid_launch_scq16_split_queries(hipStream_t st, const float *Q, int nq, vo
 }
 
 void plaid_launch_scq16(hipStream_t st, const void *A16, int64_t C, const void *B16, int nq, float t_cs, float *S,
-                        uint32_t *keepbits, uint32_t *ambbits, int64_t keep_words, float *tilemax)
+                        uint32_t *keepbits, uint32_t *ambbits, int64_t keep_words, float *tilemax, unsigned long long *clocks)
 {
     // the two thresholds of the pruning test, rounded away from t_cs (infinite t_cs: both equal it, nothing is ambiguous)
     float t_lo = t_cs, t_hi = t_cs;
@@ -373,8 +380,8 @@ void plaid_launch_scq16(hipStream_t st, const void *A16, int64_t C, const void *
     const unsigned gy = (unsigned)((nq + qg - 1) / qg);
     if (S)
         hipLaunchKernelGGL((scq16_kernel<H16_NT, true>), dim3(gx, gy), dim3(H16_THREADS), 0, st, (const scq16_half8 *)A16, C,
-                           (const scq16_half8 *)B16, nq, qg, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax);
+                           (const scq16_half8 *)B16, nq, qg, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax, clocks);
     else
         hipLaunchKernelGGL((scq16_kernel<H16_NT, false>), dim3(gx, gy), dim3(H16_THREADS), 0, st, (const scq16_half8 *)A16, C,
-                           (const scq16_half8 *)B16, nq, qg, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax);
+                           (const scq16_half8 *)B16, nq, qg, t_lo, t_hi, S, keepbits, ambbits, keep_words, tilemax, clocks);
 }

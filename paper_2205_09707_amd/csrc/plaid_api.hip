@@ -61,6 +61,7 @@ struct plaid_index {
     size_t ws_bytes = 0;
     int32_t max_chunk = 0;
     int32_t timing = 0;
+    unsigned long long *score_clocks = nullptr;  // device [2] (owned): tick sums of the score kernel while timing is on
     int32_t scq_matrix_form = 0;  // double-precision score kernel: 1 = matrix instruction, 0 = vector FMA chain
     int32_t scq_form = 0;         // score kernel of a search: PLAID_SCQ_VECTOR / _MATRIX / _SPLIT16
     void *A16 = nullptr;          // split-fp16 operand form of the centroids (owned), when scq_form is PLAID_SCQ_SPLIT16
@@ -552,7 +553,31 @@ extern "C" int plaid_set_stage_timing(plaid_index *idx, int32_t on)
         DeviceGuard g(idx->device);
         for (int i = 0; i < N_EVENTS; ++i) HIP_TRY(hipEventCreate(&idx->ev[i]));
     }
+    if (on && !idx->score_clocks) {
+        DeviceGuard g(idx->device);
+        void *d = nullptr;
+        if (hipMalloc(&d, 256) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(PLAID_ENOMEM, "hipMalloc(256) failed");
+        }
+        idx->owned.push_back(d);
+        HIP_TRY(hipMemset(d, 0, 256));
+        idx->score_clocks = (unsigned long long *)d;
+    }
     idx->timing = on ? 1 : 0;
+    return PLAID_OK;
+}
+extern "C" int plaid_get_score_kernel_clocks(const plaid_index *idx, uint64_t *out_ticks)
+{
+    if (!idx || !out_ticks) return fail(PLAID_EINVAL, "null argument");
+    out_ticks[0] = out_ticks[1] = 0;
+    if (!idx->score_clocks) return PLAID_OK;
+    DeviceGuard g(idx->device);
+    if (!g.ok) return fail(PLAID_EHIP, "hipSetDevice(%d) failed", idx->device);
+    unsigned long long h[2] = {0, 0};
+    HIP_TRY(hipMemcpy(h, idx->score_clocks, sizeof(h), hipMemcpyDeviceToHost));
+    out_ticks[0] = h[0];
+    out_ticks[1] = h[1];
     return PLAID_OK;
 }
 extern "C" int plaid_get_stage_ms(const plaid_index *idx, float *out_ms)
@@ -775,8 +800,10 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
                          ? (ix->scq_matrix_form ? PLAID_SCQ_MATRIX : PLAID_SCQ_VECTOR)
                          : ix->scq_form;
     const bool timing = ix->timing != 0;
-    if (timing)
+    if (timing) {
         for (int s = 0; s < PLAID_NUM_STAGES; ++s) ix->stage_ms[s] = 0.f;
+        if (ix->score_clocks) HIP_TRY(hipMemsetAsync(ix->score_clocks, 0, 16, st));
+    }
 
     for (int32_t q0 = 0; q0 < nq; q0 += qc) {
         const int n = nq - q0 < qc ? nq - q0 : qc;
@@ -795,7 +822,8 @@ static int search_impl(plaid_index *ix, const float *Q, int32_t nq, int32_t npro
         for (int phase = PLAID_STAGE1_PREP; phase <= PLAID_STAGE1_PROBES; phase <<= 1) {
             plaid_launch_stage1(st, phase, ix->centroids, C, Qc, w.Qd, form, ix->A16, n, t_cs, nprobe, w.S, w.keepbits, w.ambbits,
                                 w.keep_words, w.tilemax, (uint32_t *)w.zero_base, (int64_t)(w.zero_bytes / 4), w.probed,
-                                w.uniq, w.uniq_stride, w.n_uniq, w.s2, w.probe_scratch, w.probe_scratch_bytes);
+                                w.uniq, w.uniq_stride, w.n_uniq, w.s2, w.probe_scratch, w.probe_scratch_bytes,
+                                timing ? ix->score_clocks : nullptr);
             STAMP();
         }
         if (!ix->ivr_table)

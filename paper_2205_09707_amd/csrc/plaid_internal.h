@@ -121,7 +121,7 @@ void plaid_launch_stage1(hipStream_t st, int phases, const float *centroids, int
                          const void *A16, int nq, float t_cs, int nprobe, float *S, uint32_t *keepbits, uint32_t *ambbits,
                          int64_t keep_words, float *tilemax, uint32_t *zero, int64_t zero_words, int32_t *probed,
                          int32_t *uniq, int uniq_stride, int32_t *n_uniq, const struct Stage2Buffers &s2, void *probe_scratch,
-                         size_t probe_scratch_bytes);
+                         size_t probe_scratch_bytes, unsigned long long *score_clocks = nullptr);
 size_t plaid_stage1_tilemax_bytes(int64_t C, int nq, int nprobe);
 
 // Split-fp16 form of Eq. 2 (k_scq16.hip).  S differs from the exact dot products by at most PLAID_SCQ16_EPS for
@@ -136,8 +136,10 @@ size_t plaid_scq16_centroid_bytes(int64_t C);  // operand form of the centroid t
 size_t plaid_scq16_query_bytes(int nq);        // operand form of nq queries
 void plaid_launch_scq16_split_centroids(hipStream_t st, const float *centroids, int64_t C, void *A16);
 void plaid_launch_scq16_split_queries(hipStream_t st, const float *Q, int nq, void *B16, uint32_t *zero, int64_t zero_words);
+// clocks (may be null): [0] += shader-clock ticks, [1] += 100 MHz timer ticks, both summed over the workgroups.
 void plaid_launch_scq16(hipStream_t st, const void *A16, int64_t C, const void *B16, int nq, float t_cs, float *S,
-                        uint32_t *keepbits, uint32_t *ambbits, int64_t keep_words, float *tilemax);
+                        uint32_t *keepbits, uint32_t *ambbits, int64_t keep_words, float *tilemax,
+                        unsigned long long *clocks = nullptr);
 
 // General top-nprobe (nprobe > PLAID_PROBE_FAST_MAX): ranking keys of every S column through the generic selection.
 void plaid_launch_top_nprobe_general(hipStream_t st, const float *S, int64_t C, int nq, int nprobe, int32_t *probed,

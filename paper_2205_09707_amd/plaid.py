@@ -49,6 +49,7 @@ class plaid_vanilla_debug(ct.Structure):
 
 EXPORTS = ("plaid_index_load", "plaid_index_from_view", "plaid_index_free", "plaid_search", "plaid_search_debug",
            "plaid_search_static", "plaid_search_vanilla", "plaid_decompress_passages", "plaid_index_info", "plaid_set_stage_timing", "plaid_get_stage_ms",
+           "plaid_get_score_kernel_clocks",
            "plaid_set_max_chunk", "plaid_get_score_kernel", "plaid_get_stage2_kernel", "plaid_assign_centroids",
            "plaid_encode_residuals", "plaid_build_ivf", "plaid_workspace_bytes", "plaid_index_set_renormalize",
            "plaid_last_error")
@@ -82,6 +83,7 @@ def load_library() -> ct.CDLL:
         lib.plaid_index_info.argtypes = [ct.c_void_p] + [ct.c_void_p] * 5
         lib.plaid_set_stage_timing.argtypes = [ct.c_void_p, ct.c_int32]
         lib.plaid_get_stage_ms.argtypes = [ct.c_void_p, ct.c_void_p]
+        lib.plaid_get_score_kernel_clocks.argtypes = [ct.c_void_p, ct.c_void_p]
         lib.plaid_set_max_chunk.argtypes = [ct.c_void_p, ct.c_int32]
         lib.plaid_get_score_kernel.argtypes = [ct.c_void_p, ct.c_void_p]
         lib.plaid_get_stage2_kernel.argtypes = [ct.c_void_p, ct.c_void_p]
@@ -298,6 +300,13 @@ def plaid_get_stage_ms(idx: Index) -> Dict[str, float]:
     arr = (ct.c_float * PLAID_NUM_STAGES)()
     _check(load_library().plaid_get_stage_ms(idx.handle, arr))
     return {STAGE_NAMES[i]: float(arr[i]) for i in range(PLAID_NUM_STAGES)}
+
+
+def plaid_get_score_kernel_clocks(idx: Index):
+    """(shader-clock ticks, 100 MHz timer ticks) summed over the workgroups of the S_cq kernel of the last timed search."""
+    arr = (ct.c_uint64 * 2)()
+    _check(load_library().plaid_get_score_kernel_clocks(idx.handle, arr))
+    return int(arr[0]), int(arr[1])
 
 
 def plaid_set_max_chunk(idx: Index, max_queries_per_chunk: int) -> None:

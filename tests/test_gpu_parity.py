@@ -128,6 +128,32 @@ def test_default_kernel_forms(pl):
         pl.plaid_index_free(gidx)
 
 
+def test_score_kernel_clock_diagnostic(pl):
+    """With stage timing on, the split-fp16 score kernel's workgroups add up how far the shader-clock counter and the
+    100 MHz timer moved while they ran: the ratio is a clock between a few hundred MHz and the chip's 2.4 GHz.  Nothing
+    is recorded with timing off, nor by the double-precision kernels."""
+    w = make_workload(tiny_config(C=700, P=300, lo=2, hi=20, nbits=2, nq=6, seed=73), device="cpu", noise="calibrated")
+    Qdev = w.queries.to("cuda:0")
+    for form, measured in (("split16", True), ("matrix", False)):
+        with _kernel_forms(form, None):
+            gidx = pl.plaid_index_from_view(pu.device_arrays(w), w.cfg.nbits, device=0, copy=True)
+        try:
+            assert pl.plaid_get_score_kernel_clocks(gidx) == (0, 0)
+            ids0, sc0 = pl.plaid_search(gidx, Qdev, 2, 0.45, 64, 10)
+            assert pl.plaid_get_score_kernel_clocks(gidx) == (0, 0)
+            pl.plaid_set_stage_timing(gidx, True)
+            ids1, sc1 = pl.plaid_search(gidx, Qdev, 2, 0.45, 64, 10)
+            core, fixed = pl.plaid_get_score_kernel_clocks(gidx)
+            pl.plaid_set_stage_timing(gidx, False)
+            assert torch.equal(ids0, ids1) and torch.equal(sc0, sc1)
+            if measured:
+                assert fixed > 0 and 200.0 < 100.0 * core / fixed < 2600.0, (core, fixed)
+            else:
+                assert (core, fixed) == (0, 0)
+        finally:
+            pl.plaid_index_free(gidx)
+
+
 def test_large_centroid_components_get_a_double_precision_score_kernel(pl):
     """The split-fp16 kernel scales the centroids' leading terms by 2^11 in fp16: a table with a component of 32 or more
     is given the double-precision matrix kernel instead (and searches like the oracle); insisting on the split form
